@@ -1,0 +1,256 @@
+/*
+ * CPU oracle for the Slim-DP communication-set path (Sun et al., AAAI-18,
+ * "Slim-DP: A Light Communication Data Parallelism for DNN").
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow,
+ * single-threaded statement of what each step computes, written so that it
+ * can be checked against the paper by eye.  It shares no code, header,
+ * table or helper with the HIP library and neither includes the other.
+ * Only the tests, the smoke check and the benchmark's cpu_baseline leg may
+ * call it.
+ *
+ * Every function is pinned by tests that do not go through this file:
+ * published Philox known-answer vectors, closed forms, brute-force stable
+ * argsort on tiny inputs, the dense (Plump-DP) special case, conservation
+ * and hand-built collision cases.  No function here is "parity unpinned".
+ *
+ * Conventions: indices are 0-based uint32 (the paper counts from 1), values
+ * are IEEE binary32, all arithmetic is round-to-nearest-even with no
+ * contraction other than the explicit fmaf calls below.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------ */
+/* Counter-based random numbers: Philox4x32 with 10 rounds            */
+/* (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as  */
+/* 1, 2, 3", SC'11, section 3.3 and table 2 constants).               */
+/* The paper's Exploration operator (section 3.1 item 2, section 3.3  */
+/* step 2) only says "randomly"; this generator is the reading taken  */
+/* so that the draw is reproducible and independent of any schedule.  */
+/* ------------------------------------------------------------------ */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The random word attached to parameter index i for (seed, iteration,
+ * worker): word (i mod 4) of the block whose counter is
+ * (i div 4, worker, iteration low, iteration high) under the key
+ * (seed low, seed high). */
+uint32_t oracle_explore_word(uint64_t seed, uint64_t iteration, uint32_t worker, uint32_t i)
+{
+    uint32_t ctr[4] = { i >> 2, worker, (uint32_t)iteration, (uint32_t)(iteration >> 32) };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    oracle_philox4x32_10(ctr, key, out);
+    return out[i & 3u];
+}
+
+void oracle_explore_words(uint64_t seed, uint64_t iteration, uint32_t worker,
+                          uint32_t i0, uint64_t count, uint32_t* out)
+{
+    for (uint64_t j = 0; j < count; ++j)
+        out[j] = oracle_explore_word(seed, iteration, worker, (uint32_t)(i0 + j));
+}
+
+/* ------------------------------------------------------------------ */
+/* Significance, equation (1) of section 3.2:  S_i = |w_i| + c |g_i|. */
+/* g is the sum of the W workers' updates in worker order (what the   */
+/* server holds after a full push, section 3.3 steps 3 and 6).        */
+/* Rounding: one fused multiply-add.  A NaN result is replaced by the */
+/* one canonical quiet NaN so that its bit pattern is defined.        */
+/* ------------------------------------------------------------------ */
+void oracle_score(uint64_t n, uint32_t W, const float* w, const float* const* g,
+                  float c, float* S)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        float gi = g[0][i];
+        for (uint32_t k = 1; k < W; ++k)
+            gi = gi + g[k][i];
+        float s = fmaf(c, fabsf(gi), fabsf(w[i]));
+        if (s != s) {
+            uint32_t qnan = 0x7FC00000u;
+            memcpy(&s, &qnan, 4);
+        }
+        S[i] = s;
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* Ranking helpers: (key, index) pairs and a full comparison sort.    */
+/* ------------------------------------------------------------------ */
+typedef struct { uint32_t key; uint32_t idx; } pair_t;
+
+static int cmp_key_desc_idx_asc(const void* a, const void* b)
+{
+    const pair_t* x = (const pair_t*)a; const pair_t* y = (const pair_t*)b;
+    if (x->key != y->key) return (x->key > y->key) ? -1 : 1;
+    if (x->idx != y->idx) return (x->idx < y->idx) ? -1 : 1;
+    return 0;
+}
+static int cmp_key_asc_idx_asc(const void* a, const void* b)
+{
+    const pair_t* x = (const pair_t*)a; const pair_t* y = (const pair_t*)b;
+    if (x->key != y->key) return (x->key < y->key) ? -1 : 1;
+    if (x->idx != y->idx) return (x->idx < y->idx) ? -1 : 1;
+    return 0;
+}
+static int cmp_u32_asc(const void* a, const void* b)
+{
+    uint32_t x = *(const uint32_t*)a, y = *(const uint32_t*)b;
+    return (x > y) - (x < y);
+}
+
+/* ------------------------------------------------------------------ */
+/* Core-Selection (section 3.1 item 1, section 3.2 last sentence,     */
+/* section 3.3 step 6): rank the parameters of one segment            */
+/* [base, base+len) by significance and keep the top k.  The rank     */
+/* order is (score bit pattern as uint32, descending; index           */
+/* ascending), which for non-negative scores is the numeric order.    */
+/* Output: the k chosen GLOBAL indices in ascending order.            */
+/* Returns 0, or -1 on bad arguments / allocation failure.            */
+/* ------------------------------------------------------------------ */
+int oracle_select_core(const float* S, uint32_t base, uint32_t len, uint32_t k, uint32_t* core_idx)
+{
+    if (k > len) return -1;
+    if (len == 0) return 0;
+    pair_t* p = (pair_t*)malloc((size_t)len * sizeof(pair_t));
+    if (!p) return -1;
+    for (uint32_t j = 0; j < len; ++j) {
+        uint32_t bits;
+        memcpy(&bits, &S[base + j], 4);
+        p[j].key = bits;
+        p[j].idx = base + j;
+    }
+    qsort(p, len, sizeof(pair_t), cmp_key_desc_idx_asc);
+    for (uint32_t j = 0; j < k; ++j) core_idx[j] = p[j].idx;
+    qsort(core_idx, k, sizeof(uint32_t), cmp_u32_asc);
+    free(p);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Exploration (section 3.1 item 2, section 3.3 step 2): worker k     */
+/* draws m parameters uniformly without replacement from those of the */
+/* segment [base, base+len) that are NOT in the core.  Realised as    */
+/* random-key selection: every non-core index gets its random word,   */
+/* and the m indices with the smallest (word, index) are taken.       */
+/* in_core: one byte per GLOBAL index, non-zero = in the core.        */
+/* Output: the m chosen GLOBAL indices in ascending order.            */
+/* ------------------------------------------------------------------ */
+int oracle_sample_explore(const uint8_t* in_core, uint32_t base, uint32_t len,
+                          uint64_t seed, uint64_t iteration, uint32_t worker,
+                          uint32_t m, uint32_t* expl_idx)
+{
+    if (len == 0) return (m == 0) ? 0 : -1;
+    pair_t* p = (pair_t*)malloc((size_t)len * sizeof(pair_t));
+    if (!p) return -1;
+    uint32_t cnt = 0;
+    for (uint32_t j = 0; j < len; ++j) {
+        uint32_t i = base + j;
+        if (in_core[i]) continue;
+        p[cnt].key = oracle_explore_word(seed, iteration, worker, i);
+        p[cnt].idx = i;
+        ++cnt;
+    }
+    if (m > cnt) { free(p); return -1; }
+    qsort(p, cnt, sizeof(pair_t), cmp_key_asc_idx_asc);
+    for (uint32_t j = 0; j < m; ++j) expl_idx[j] = p[j].idx;
+    qsort(expl_idx, m, sizeof(uint32_t), cmp_u32_asc);
+    free(p);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Push, worker side (section 3.3 step 3; wire format of section 3.5):*/
+/* extract the worker's updates at the core (values only, the keys    */
+/* are cached on both ends) and at its explorer (<key, value> pairs;  */
+/* the keys are expl_idx itself).  Bit copies.                        */
+/* ------------------------------------------------------------------ */
+void oracle_pack(const float* g_k, const uint32_t* core_idx, uint64_t k,
+                 const uint32_t* expl_idx, uint64_t m, float* core_val, float* expl_val)
+{
+    for (uint64_t j = 0; j < k; ++j) core_val[j] = g_k[core_idx[j]];
+    for (uint64_t j = 0; j < m; ++j) expl_val[j] = g_k[expl_idx[j]];
+}
+
+/* ------------------------------------------------------------------ */
+/* Update, server side (section 3.3 step 3):                          */
+/*   w_i <- w_i - lr * sum_k T_C(delta_k)_i                           */
+/* The sum runs over the workers whose communication set contains i,  */
+/* in ascending worker order, starting from +0; one fused             */
+/* multiply-add applies it.  Indices no worker sent are not written.  */
+/* scratch_acc (n floats) and scratch_hit (n bytes) are caller-owned  */
+/* work arrays; their contents on entry do not matter.                */
+/* ------------------------------------------------------------------ */
+void oracle_merge(uint64_t n, float* w, float lr, uint32_t W,
+                  const uint32_t* core_idx, uint64_t k, const float* const* core_val,
+                  const uint32_t* const* expl_idx, const float* const* expl_val,
+                  const uint64_t* m_w, float* scratch_acc, uint8_t* scratch_hit)
+{
+    for (uint64_t i = 0; i < n; ++i) { scratch_acc[i] = 0.0f; scratch_hit[i] = 0; }
+    for (uint32_t wk = 0; wk < W; ++wk) {
+        for (uint64_t j = 0; j < k; ++j) {
+            uint32_t i = core_idx[j];
+            scratch_acc[i] = scratch_acc[i] + core_val[wk][j];
+            scratch_hit[i] = 1;
+        }
+        for (uint64_t j = 0; j < m_w[wk]; ++j) {
+            uint32_t i = expl_idx[wk][j];
+            scratch_acc[i] = scratch_acc[i] + expl_val[wk][j];
+            scratch_hit[i] = 1;
+        }
+    }
+    for (uint64_t i = 0; i < n; ++i)
+        if (scratch_hit[i]) w[i] = fmaf(-lr, scratch_acc[i], w[i]);
+}
+
+/* The same update in binary64 with no intermediate rounding to binary32:
+ * the reference against which the binary32 tolerance is stated. */
+void oracle_merge_f64(uint64_t n, const float* w_in, double* w_out, double lr, uint32_t W,
+                      const uint32_t* core_idx, uint64_t k, const float* const* core_val,
+                      const uint32_t* const* expl_idx, const float* const* expl_val,
+                      const uint64_t* m_w)
+{
+    for (uint64_t i = 0; i < n; ++i) w_out[i] = 0.0;
+    for (uint32_t wk = 0; wk < W; ++wk) {
+        for (uint64_t j = 0; j < k; ++j) w_out[core_idx[j]] += (double)core_val[wk][j];
+        for (uint64_t j = 0; j < m_w[wk]; ++j) w_out[expl_idx[wk][j]] += (double)expl_val[wk][j];
+    }
+    for (uint64_t i = 0; i < n; ++i) w_out[i] = (double)w_in[i] - lr * w_out[i];
+}
+
+/* ------------------------------------------------------------------ */
+/* Pull and local Merge (section 3.3 steps 4 and 5): read the global  */
+/* model at the worker's communication set; if w_local is given,      */
+/* overwrite the local model at those indices and leave the rest.     */
+/* ------------------------------------------------------------------ */
+void oracle_pull(const float* w, const uint32_t* core_idx, uint64_t k,
+                 const uint32_t* expl_idx, uint64_t m,
+                 float* core_out, float* expl_out, float* w_local)
+{
+    for (uint64_t j = 0; j < k; ++j) {
+        core_out[j] = w[core_idx[j]];
+        if (w_local) w_local[core_idx[j]] = core_out[j];
+    }
+    for (uint64_t j = 0; j < m; ++j) {
+        expl_out[j] = w[expl_idx[j]];
+        if (w_local) w_local[expl_idx[j]] = expl_out[j];
+    }
+}
