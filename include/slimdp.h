@@ -1,0 +1,202 @@
+/*
+ * libslimdp -- the per-iteration communication-set path of Slim-DP
+ * (Sun, Chen, Bian, Liu, Liu: "Slim-DP: A Light Communication Data Parallelism
+ * for DNN", AAAI-18) as hand-written HIP kernels for gfx950 behind a C ABI.
+ *
+ * One context serves one global model of n binary32 parameters and up to
+ * max_workers logical workers whose buffers all live on ONE GPU.
+ *
+ * General rules
+ *  - Every pointer marked [dev] is device memory owned by the caller; every pointer
+ *    marked [host] is host memory that is read (or written) during the call and not
+ *    retained.  "table" = a host array of device pointers, one per worker.
+ *  - Every call returns SLIMDP_OK or a negative SLIMDP_ERR_* code; on error nothing has
+ *    been launched and slimdp_last_error() describes the cause.  Nothing aborts, throws
+ *    or prints.
+ *  - Calls are asynchronous on the HIP stream given to slimdp_create and never
+ *    synchronise the host; every output size is known from the arguments.  Conditions
+ *    only the device can detect (see slimdp_synchronize) are reported there.
+ *  - The library allocates device memory only in slimdp_create.
+ *  - Same inputs give the same output bits, whatever the launch geometry.
+ *  - Indices are 0-based uint32 (the paper counts from 1); n < 2^32.
+ *
+ * Tiles.  The index range is cut into tiles of at most SLIMDP_TILE consecutive
+ * parameters that never cross a segment boundary (flat model: tile t is
+ * [t*SLIMDP_TILE, (t+1)*SLIMDP_TILE)).  Every ascending index list the library writes
+ * comes with its "tile offsets": off[t] = number of list entries below the start of tile
+ * t, off[T] = list length (T = slimdp_num_tiles).  pack / merge / pull take those
+ * offsets back so that no kernel has to search the lists.
+ */
+#ifndef SLIMDP_H
+#define SLIMDP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SLIMDP_TILE 4096u
+#define SLIMDP_MAX_WORKERS 32u
+#define SLIMDP_MAX_SEGMENTS 65536u
+
+enum {
+    SLIMDP_OK = 0,
+    SLIMDP_ERR_INVALID_ARG = -1,   /* null pointer, zero size, unsorted segment offsets, W out of range */
+    SLIMDP_ERR_OUT_OF_RANGE = -2,  /* k_s > n_s, m_s > n_s - k_s, counts that do not add up */
+    SLIMDP_ERR_STALE_CORE = -3,    /* core_epoch is not the epoch of the context's current core */
+    SLIMDP_ERR_WORKSPACE = -4,     /* device allocation failed in slimdp_create */
+    SLIMDP_ERR_HIP = -5,           /* a HIP runtime call failed */
+    SLIMDP_ERR_DEVICE_STATUS = -6  /* slimdp_synchronize: a kernel flagged an impossible request */
+};
+
+/* slimdp_select_core flags */
+#define SLIMDP_SELECT_REUSE_HISTOGRAM 1u
+
+typedef struct slimdp_ctx slimdp_ctx;
+
+/* ---------------------------------------------------------------------------------- */
+/* Context                                                                             */
+/* ---------------------------------------------------------------------------------- */
+
+/* Creates a context for n parameters in n_seg segments.
+ *   seg_off [host, n_seg+1]: seg_off[0]=0 < ... < seg_off[n_seg]=n (strictly increasing).
+ *                            n_seg=1 is the flat model (global ranking, section 3.2 of the paper).
+ *   seed: key of the counter-based generator used by slimdp_sample_explore.
+ *   hip_stream: a hipStream_t (NULL = the default stream); all work is enqueued there.
+ * Allocates slimdp_workspace_bytes(...) of device memory on the current device. */
+int slimdp_create(slimdp_ctx** out, uint64_t n, uint32_t max_workers, uint32_t n_seg,
+                  const uint64_t* seg_off, uint64_t seed, void* hip_stream);
+int slimdp_destroy(slimdp_ctx* ctx);
+
+/* Device bytes slimdp_create allocates; 0 if the arguments are invalid.  Pure host function. */
+uint64_t slimdp_workspace_bytes(uint64_t n, uint32_t max_workers, uint32_t n_seg,
+                                const uint64_t* seg_off);
+/* Number of tiles T; 0 if the arguments are invalid.  Pure host function. */
+uint64_t slimdp_num_tiles(uint64_t n, uint32_t n_seg, const uint64_t* seg_off);
+/* tile_start [host, T+1]: start index of every tile, tile_start[T] = n. */
+int slimdp_tile_starts(const slimdp_ctx* ctx, uint32_t* tile_start);
+
+/* Message for the last error returned on this context ("" if none).  ctx may be NULL:
+ * then the message of the last failed slimdp_create on this thread. */
+const char* slimdp_last_error(const slimdp_ctx* ctx);
+
+/* Waits for the context's stream and returns SLIMDP_ERR_DEVICE_STATUS if a kernel since
+ * the previous slimdp_synchronize met a request it could not satisfy (an explorer larger
+ * than the number of non-core parameters of its segment, index lists whose length does
+ * not match).  The only call that blocks the host. */
+int slimdp_synchronize(slimdp_ctx* ctx);
+
+/* Tuning / test switches.  Known names:
+ *   "explore_force_fallback" (0/1): make the first candidate bound of slimdp_sample_explore
+ *                                   too small, so that the exact wide-bound path runs. */
+int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value);
+
+/* ---------------------------------------------------------------------------------- */
+/* The path                                                                            */
+/* ---------------------------------------------------------------------------------- */
+
+/* Significance, equation (1) of section 3.2:  score_i = |w_i| + c * |g_i|, with
+ * g_i = ((g_0[i] + g_1[i]) + ...) + g_{W-1}[i] in binary32 in worker order (the summed
+ * update the server holds, section 3.3 steps 3 and 6) and ONE fused multiply-add
+ * fma(c, |g_i|, |w_i|).  A NaN result is stored as the quiet NaN 0x7FC00000.
+ *   w [dev, n], g [host table of W dev pointers, n each], c >= 0 finite,
+ *   score [dev, n] fully overwritten.  1 <= W <= SLIMDP_MAX_WORKERS.
+ * Also accumulates, per segment, the histogram of the leading bits of every score, which
+ * the next slimdp_select_core may reuse (SLIMDP_SELECT_REUSE_HISTOGRAM). */
+int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_t W, float c,
+                 float* score);
+
+/* Core-Selection operator T_S (section 3.1 item 1; section 3.2 "rank ... select the top";
+ * section 3.3 step 6): per segment s the k_seg[s] parameters that come first when ranked
+ * by (score bit pattern as uint32, descending; index, ascending).  For scores >= +0 that
+ * is the numeric order with ties going to the lower index; NaN ranks above +infinity.
+ *   score    [dev, n]
+ *   k_seg    [host, n_seg], k_seg[s] <= size of segment s
+ *   flags    SLIMDP_SELECT_REUSE_HISTOGRAM: score is the buffer the last slimdp_score on
+ *            this context wrote and has not been modified since (otherwise the library
+ *            spends one more pass over score to count); error if no such histogram is pending.
+ *   core_idx [dev, sum k_seg]  chosen global indices, ascending
+ *   core_bits[dev, ceil(n/32)] bit (i mod 32) of word (i div 32) set iff i is in the core
+ *   core_off [dev, T+1]        tile offsets of core_idx
+ *   core_epoch [host, 1]       identifier of this core: the "signature of the keys" both
+ *            ends of the key-caching filter hold (section 3.5); pack/merge/pull made for
+ *            another core are refused with SLIMDP_ERR_STALE_CORE. */
+int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_seg, uint32_t flags,
+                       uint32_t* core_idx, uint32_t* core_bits, uint32_t* core_off,
+                       uint64_t* core_epoch);
+
+/* Exploration operator T_R^k (section 3.1 item 2; section 3.3 step 2) for the workers
+ * worker0 .. worker0+n_workers-1: each draws, per segment s, m_seg[s] parameters uniformly
+ * without replacement from those outside the core, afresh for every (worker, iteration).
+ * Realisation: parameter i gets the random word r = word (i mod 4) of Philox4x32-10 with
+ * counter (i div 4, worker, iteration low 32, iteration high 32) and key (seed low, seed
+ * high); the m_seg[s] non-core parameters with the smallest (r, i) are taken.
+ *   core_bits [dev, ceil(n/32)] as written by slimdp_select_core
+ *   k_seg     [host, n_seg]  number of core parameters per segment in core_bits (bounds m_seg
+ *             and sizes the candidate search; a wrong value costs time, not correctness)
+ *   m_seg     [host, n_seg], m_seg[s] <= n_s - k_seg[s]
+ *   expl_idx  [host table, n_workers] of [dev, sum m_seg]: chosen global indices, ascending
+ *   expl_off  [host table, n_workers] of [dev, T+1]: their tile offsets
+ * If core_bits holds more core parameters than k_seg says and m_seg cannot be met, the
+ * affected list is left partly unwritten and slimdp_synchronize reports it. */
+int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint64_t* k_seg,
+                          uint32_t worker0, uint32_t n_workers, uint64_t iteration,
+                          const uint64_t* m_seg, uint32_t* const* expl_idx,
+                          uint32_t* const* expl_off);
+
+/* Tile offsets of any ascending index list (for lists that did not come from the two
+ * calls above).  idx [dev, count] ascending, all < n; off [dev, T+1]. */
+int slimdp_tile_offsets(slimdp_ctx* ctx, const uint32_t* idx, uint64_t count, uint32_t* off);
+
+/* Push, worker side (section 3.3 step 3; wire format of section 3.5): for each of the
+ * n_workers workers extract its update at the communication set T_C = core U explorer.
+ * Core: values only (the keys are cached under core_epoch); explorer: <key, value> with
+ * the keys being expl_idx itself.  Bit copies:
+ *   core_val[q][j] = g[q][core_idx[j]],  expl_val[q][j] = g[q][expl_idx[q][j]].
+ *   g [host table, n_workers] of [dev, n]; core_idx [dev, k]; core_off [dev, T+1];
+ *   expl_idx / expl_off [host tables]; m_w [host, n_workers] explorer sizes;
+ *   core_val [host table] of [dev, k]; expl_val [host table] of [dev, m_w[q]].
+ * Words on the wire per worker: k + 2*m_w[q], the (2*alpha - beta)*n of section 3.5. */
+int slimdp_pack(slimdp_ctx* ctx, uint32_t n_workers, const float* const* g,
+                const uint32_t* core_idx, const uint32_t* core_off, uint64_t k,
+                const uint32_t* const* expl_idx, const uint32_t* const* expl_off,
+                const uint64_t* m_w, float* const* core_val, float* const* expl_val,
+                uint64_t core_epoch);
+
+/* Update, server side (section 3.3 step 3):  w_i <- w_i - lr * sum_q T_C(delta_q)_i.
+ * For every index i some worker sent: acc = +0; for q ascending over the workers whose
+ * communication set holds i: acc += value; then w_i = fma(-lr, acc, w_i).  Indices nobody
+ * sent keep their bits.  No atomics; the result does not depend on scheduling.
+ * Requires each explorer list to be disjoint from the core (as slimdp_sample_explore
+ * guarantees); otherwise the core contributions to an index are added before the
+ * explorer ones.
+ *   w [dev, n] in place; the other arguments as in slimdp_pack (values are inputs). */
+int slimdp_merge(slimdp_ctx* ctx, float* w, float lr, uint64_t core_epoch, uint32_t n_workers,
+                 const uint32_t* core_idx, const uint32_t* core_off, uint64_t k,
+                 const float* const* core_val, const uint32_t* const* expl_idx,
+                 const uint32_t* const* expl_off, const float* const* expl_val,
+                 const uint64_t* m_w);
+
+/* Pull and local Merge (section 3.3 steps 4 and 5): each worker reads the global model
+ * at its communication set, core_out[q][j] = w[core_idx[j]], expl_out[q][j] =
+ * w[expl_idx[q][j]]; if w_local is not NULL and w_local[q] is not NULL the worker's local
+ * model is overwritten at those indices and left alone elsewhere.
+ *   w [dev, n]; core_out [host table] of [dev, k]; expl_out [host table] of [dev, m_w[q]];
+ *   w_local NULL or [host table] of (NULL or [dev, n]). */
+int slimdp_pull(slimdp_ctx* ctx, const float* w, uint64_t core_epoch, uint32_t n_workers,
+                const uint32_t* core_idx, const uint32_t* core_off, uint64_t k,
+                const uint32_t* const* expl_idx, const uint32_t* const* expl_off,
+                const uint64_t* m_w, float* const* core_out, float* const* expl_out,
+                float* const* w_local);
+
+/* The raw random words slimdp_sample_explore attaches to the indices i0 .. i0+count-1 for
+ * (worker, iteration) under the context's seed.  out [dev, count]. */
+int slimdp_debug_philox(slimdp_ctx* ctx, uint64_t iteration, uint32_t worker, uint32_t i0,
+                        uint64_t count, uint32_t* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLIMDP_H */

@@ -1,0 +1,645 @@
+// libslimdp host side: the C ABI of include/slimdp.h.  Argument checks, workspace carving
+// and kernel launches only; every step of the path runs in the kernels of slimdp_kernels.h.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "slimdp.h"
+#include "slimdp_kernels.h"
+
+using namespace slimdp;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+struct Tiling {
+    std::vector<uint32_t> tile_start;      // T+1
+    std::vector<uint32_t> tile_seg;        // T
+    std::vector<uint32_t> seg_first_tile;  // n_seg+1
+    bool word_aligned = true;              // every tile starts on a bitmap word
+};
+
+bool valid_shape(uint64_t n, uint32_t n_seg, const uint64_t* seg_off)
+{
+    if (n == 0 || n >= (1ull << 32) || n_seg == 0 || n_seg > SLIMDP_MAX_SEGMENTS || !seg_off) return false;
+    if (seg_off[0] != 0 || seg_off[n_seg] != n) return false;
+    for (uint32_t s = 0; s < n_seg; ++s)
+        if (seg_off[s + 1] <= seg_off[s]) return false;
+    return true;
+}
+
+Tiling make_tiling(uint64_t n, uint32_t n_seg, const uint64_t* seg_off)
+{
+    Tiling tl;
+    tl.seg_first_tile.resize(n_seg + 1);
+    for (uint32_t s = 0; s < n_seg; ++s) {
+        tl.seg_first_tile[s] = (uint32_t)tl.tile_seg.size();
+        for (uint64_t a = seg_off[s]; a < seg_off[s + 1]; a += TILE) {
+            tl.tile_start.push_back((uint32_t)a);
+            tl.tile_seg.push_back(s);
+            if (a & 31u) tl.word_aligned = false;
+        }
+    }
+    tl.seg_first_tile[n_seg] = (uint32_t)tl.tile_seg.size();
+    tl.tile_start.push_back((uint32_t)n);   // n < 2^32
+    return tl;
+}
+
+uint64_t count_tiles(uint64_t n, uint32_t n_seg, const uint64_t* seg_off)
+{
+    (void)n;
+    uint64_t T = 0;
+    for (uint32_t s = 0; s < n_seg; ++s) T += (seg_off[s + 1] - seg_off[s] + TILE - 1) / TILE;
+    return T;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// One linear pass hands out the workspace; run once with base == nullptr to size it.
+struct Carver {
+    char* base;
+    size_t pos = 0;
+    explicit Carver(char* b) : base(b) {}
+    template <class Tp> Tp* take(size_t count)
+    {
+        pos = align_up(pos, 256);
+        Tp* p = base ? reinterpret_cast<Tp*>(base + pos) : nullptr;
+        pos += count * sizeof(Tp);
+        return p;
+    }
+};
+
+}  // namespace
+
+struct slimdp_ctx {
+    uint64_t n = 0;
+    uint32_t maxW = 0, n_seg = 0, T = 0;
+    uint64_t seed = 0;
+    hipStream_t stream = nullptr;
+    int device = 0, cus = 256;
+    std::vector<uint64_t> seg_off;
+    Tiling tl;
+    char* ws = nullptr;
+    size_t ws_bytes = 0;
+    uint64_t keys_stride = 0;
+    // device tables
+    uint32_t *d_tile_start = nullptr, *d_tile_seg = nullptr, *d_seg_first_tile = nullptr, *d_flags = nullptr;
+    // core selection
+    SegState* c_state = nullptr;
+    uint32_t *c_hist = nullptr, *c_gt_bits = nullptr, *c_cand_bits = nullptr, *c_cand_keys = nullptr;
+    uint32_t *c_cnt_gt = nullptr, *c_cnt_cand = nullptr, *c_cnt_sel = nullptr, *c_cnt_tie = nullptr, *c_tie_pre = nullptr;
+    // explorer selection (batch = worker)
+    SegState* e_state = nullptr;
+    uint32_t *e_hist = nullptr, *e_cand_bits = nullptr, *e_cand_keys = nullptr;
+    uint32_t *e_cnt_cand = nullptr, *e_cnt_sel = nullptr, *e_cnt_tie = nullptr, *e_tie_pre = nullptr;
+    // host state
+    uint64_t epoch = 0;
+    bool hist_pending = false;
+    const float* hist_score = nullptr;
+    int64_t opt_force_fallback = 0;
+    std::string err;
+};
+
+namespace {
+
+void carve(slimdp_ctx* c, Carver& cv)
+{
+    const size_t T = c->T, S = c->n_seg, B = c->maxW;
+    c->d_tile_start = cv.take<uint32_t>(T + 1);
+    c->d_tile_seg = cv.take<uint32_t>(T);
+    c->d_seg_first_tile = cv.take<uint32_t>(S + 1);
+    c->d_flags = cv.take<uint32_t>(64);
+    c->c_state = cv.take<SegState>(S);
+    c->c_hist = cv.take<uint32_t>(S * H_STRIDE);
+    c->c_gt_bits = cv.take<uint32_t>(T * TILE_WORDS);
+    c->c_cand_bits = cv.take<uint32_t>(T * TILE_WORDS);
+    c->c_cand_keys = cv.take<uint32_t>(c->keys_stride);
+    c->c_cnt_gt = cv.take<uint32_t>(T);
+    c->c_cnt_cand = cv.take<uint32_t>(T);
+    c->c_cnt_sel = cv.take<uint32_t>(T);
+    c->c_cnt_tie = cv.take<uint32_t>(T);
+    c->c_tie_pre = cv.take<uint32_t>(T + 1);
+    c->e_state = cv.take<SegState>(B * S);
+    c->e_hist = cv.take<uint32_t>(B * S * H_STRIDE);
+    c->e_cand_bits = cv.take<uint32_t>(B * T * TILE_WORDS);
+    c->e_cand_keys = cv.take<uint32_t>(B * c->keys_stride);
+    c->e_cnt_cand = cv.take<uint32_t>(B * T);
+    c->e_cnt_sel = cv.take<uint32_t>(B * T);
+    c->e_cnt_tie = cv.take<uint32_t>(B * T);
+    c->e_tie_pre = cv.take<uint32_t>(B * (T + 1));
+}
+
+int fail(slimdp_ctx* c, int code, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (c) c->err = buf; else g_create_error = buf;
+    return code;
+}
+
+int hip_fail(slimdp_ctx* c, hipError_t e, const char* what)
+{
+    return fail(c, SLIMDP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define SLIMDP_HIP(c, call)                                        \
+    do {                                                           \
+        hipError_t e__ = (call);                                   \
+        if (e__ != hipSuccess) return hip_fail((c), e__, #call);   \
+    } while (0)
+
+#define SLIMDP_LAUNCHED(c, name)                                   \
+    do {                                                           \
+        hipError_t e__ = hipGetLastError();                        \
+        if (e__ != hipSuccess) return hip_fail((c), e__, name);    \
+    } while (0)
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+uint32_t fill_grid(uint64_t count) { uint64_t g = (count + 255) / 256; return (uint32_t)(g < 1 ? 1 : (g > 4096 ? 4096 : g)); }
+
+int fill(slimdp_ctx* c, uint32_t* p, uint64_t count, uint32_t v)
+{
+    if (count == 0) return SLIMDP_OK;
+    hipLaunchKernelGGL(k_fill_u32, dim3(fill_grid(count)), dim3(256), 0, c->stream, p, count, v);
+    SLIMDP_LAUNCHED(c, "k_fill_u32");
+    return SLIMDP_OK;
+}
+
+int init_states(slimdp_ctx* c, SegState* st, const std::vector<SegInit>& init, uint32_t nbatch, int core)
+{
+    for (uint32_t s0 = 0; s0 < c->n_seg; s0 += INIT_CHUNK) {
+        SegInitChunk chunk;
+        const uint32_t cnt = (c->n_seg - s0 < (uint32_t)INIT_CHUNK) ? c->n_seg - s0 : (uint32_t)INIT_CHUNK;
+        memset(&chunk, 0, sizeof chunk);
+        for (uint32_t j = 0; j < cnt; ++j) chunk.s[j] = init[s0 + j];
+        const uint32_t threads = cnt * nbatch;
+        hipLaunchKernelGGL(k_init_state, dim3((threads + 255) / 256), dim3(256), 0, c->stream, st, chunk, s0, cnt,
+                           c->n_seg, nbatch, core);
+        SLIMDP_LAUNCHED(c, "k_init_state");
+    }
+    return SLIMDP_OK;
+}
+
+uint32_t persistent_blocks(const slimdp_ctx* c, uint32_t per_cu, uint32_t nbatch)
+{
+    uint64_t p = (uint64_t)c->cus * per_cu / (nbatch ? nbatch : 1);
+    if (p < 32) p = 32;
+    if (p > c->T) p = c->T;
+    return (uint32_t)p;
+}
+
+// Levels 1, 2, per-tile counts, scan over tiles and ordered emission, shared by the core
+// (after k_core_build, which already filled the level-1 histogram) and the explorer.
+int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* hist, const uint32_t* gt_bits,
+                     const uint32_t* cand_bits, const uint32_t* cand_keys, const uint32_t* cnt_gt,
+                     const uint32_t* cnt_cand, uint32_t* cnt_sel, uint32_t* cnt_tie, uint32_t* tie_pre,
+                     uint64_t keys_stride, bool level1_done, const MutPtrTab& out_off, const MutPtrTab& out_idx,
+                     uint32_t expected, uint32_t* pub_bits)
+{
+    const uint32_t T = c->T, S = c->n_seg;
+    const dim3 wave_grid((T + 3) / 4, nbatch);
+    if (!level1_done) {
+        hipLaunchKernelGGL(k_list_hist, wave_grid, dim3(BLOCK), 0, c->stream, c->d_tile_start, c->d_tile_seg, T, S, st,
+                           hist, (uint32_t)H_L1, 1, cand_keys, cnt_cand, keys_stride);
+        SLIMDP_LAUNCHED(c, "k_list_hist(1)");
+    }
+    hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 1, (uint32_t)H_L1, S, 0, c->d_flags);
+    SLIMDP_LAUNCHED(c, "k_threshold(1)");
+    hipLaunchKernelGGL(k_list_hist, wave_grid, dim3(BLOCK), 0, c->stream, c->d_tile_start, c->d_tile_seg, T, S, st, hist,
+                       (uint32_t)H_L2, 2, cand_keys, cnt_cand, keys_stride);
+    SLIMDP_LAUNCHED(c, "k_list_hist(2)");
+    hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 2, (uint32_t)H_L2, S, 0, c->d_flags);
+    SLIMDP_LAUNCHED(c, "k_threshold(2)");
+    hipLaunchKernelGGL(k_count, wave_grid, dim3(BLOCK), 0, c->stream, c->d_tile_start, c->d_tile_seg, T, S, st, cand_keys,
+                       cnt_cand, cnt_gt, keys_stride, cnt_sel, cnt_tie);
+    SLIMDP_LAUNCHED(c, "k_count");
+    hipLaunchKernelGGL(k_scan, dim3(1, nbatch), dim3(1024), 0, c->stream, c->d_tile_seg, c->d_seg_first_tile, T, S, st,
+                       cnt_sel, cnt_tie, tie_pre, out_off, expected, c->d_flags);
+    SLIMDP_LAUNCHED(c, "k_scan");
+    PtrTab off_ro;
+    for (int q = 0; q < MAXW; ++q) off_ro.p[q] = out_off.p[q];
+    hipLaunchKernelGGL(k_emit, dim3(T, nbatch), dim3(128), 0, c->stream, c->d_tile_start, c->d_tile_seg,
+                       c->d_seg_first_tile, T, S, st, gt_bits, cand_bits, cand_keys, keys_stride, tie_pre, off_ro, out_idx,
+                       expected, pub_bits);
+    SLIMDP_LAUNCHED(c, "k_emit");
+    return SLIMDP_OK;
+}
+
+template <class P> bool table_ok(P const* tab, uint32_t nw, bool allow_null_entries = false)
+{
+    if (!tab) return false;
+    if (!allow_null_entries)
+        for (uint32_t q = 0; q < nw; ++q)
+            if (!tab[q]) return false;
+    return true;
+}
+
+template <class Tab, class P> Tab make_tab(P const* tab, uint32_t nw)
+{
+    Tab t;
+    for (int q = 0; q < MAXW; ++q) t.p[q] = nullptr;
+    if (tab)
+        for (uint32_t q = 0; q < nw; ++q) t.p[q] = (decltype(t.p[0]))tab[q];
+    return t;
+}
+
+int check_epoch(slimdp_ctx* c, uint64_t core_epoch)
+{
+    if (c->epoch == 0 || core_epoch != c->epoch)
+        return fail(c, SLIMDP_ERR_STALE_CORE, "core_epoch %llu is not the context's current core epoch %llu",
+                    (unsigned long long)core_epoch, (unsigned long long)c->epoch);
+    return SLIMDP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint64_t slimdp_num_tiles(uint64_t n, uint32_t n_seg, const uint64_t* seg_off)
+{
+    if (!valid_shape(n, n_seg, seg_off)) return 0;
+    return count_tiles(n, n_seg, seg_off);
+}
+
+uint64_t slimdp_workspace_bytes(uint64_t n, uint32_t max_workers, uint32_t n_seg, const uint64_t* seg_off)
+{
+    if (!valid_shape(n, n_seg, seg_off) || max_workers == 0 || max_workers > SLIMDP_MAX_WORKERS) return 0;
+    slimdp_ctx tmp;
+    tmp.n = n; tmp.maxW = max_workers; tmp.n_seg = n_seg;
+    tmp.T = (uint32_t)count_tiles(n, n_seg, seg_off);
+    tmp.keys_stride = align_up(n, 64);
+    Carver cv(nullptr);
+    carve(&tmp, cv);
+    return align_up(cv.pos, 256);
+}
+
+const char* slimdp_last_error(const slimdp_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+int slimdp_create(slimdp_ctx** out, uint64_t n, uint32_t max_workers, uint32_t n_seg, const uint64_t* seg_off,
+                  uint64_t seed, void* hip_stream)
+{
+    if (!out) return fail(nullptr, SLIMDP_ERR_INVALID_ARG, "slimdp_create: out is NULL");
+    *out = nullptr;
+    if (n == 0 || n >= (1ull << 32)) return fail(nullptr, SLIMDP_ERR_INVALID_ARG, "slimdp_create: n must be in [1, 2^32)");
+    if (max_workers == 0 || max_workers > SLIMDP_MAX_WORKERS)
+        return fail(nullptr, SLIMDP_ERR_INVALID_ARG, "slimdp_create: max_workers must be in [1, %u]", SLIMDP_MAX_WORKERS);
+    if (!valid_shape(n, n_seg, seg_off))
+        return fail(nullptr, SLIMDP_ERR_INVALID_ARG,
+                    "slimdp_create: seg_off must be %u+1 strictly increasing offsets from 0 to n", n_seg);
+    slimdp_ctx* c = new (std::nothrow) slimdp_ctx;
+    if (!c) return fail(nullptr, SLIMDP_ERR_WORKSPACE, "slimdp_create: out of host memory");
+    c->n = n; c->maxW = max_workers; c->n_seg = n_seg; c->seed = seed;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->seg_off.assign(seg_off, seg_off + n_seg + 1);
+    c->tl = make_tiling(n, n_seg, seg_off);
+    c->T = (uint32_t)c->tl.tile_seg.size();
+    c->keys_stride = align_up(n, 64);
+    hipError_t e = hipGetDevice(&c->device);
+    if (e != hipSuccess) { int rc = hip_fail(nullptr, e, "hipGetDevice (no usable GPU?)"); delete c; return rc; }
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, c->device);
+    if (e != hipSuccess) { int rc = hip_fail(nullptr, e, "hipGetDeviceProperties"); delete c; return rc; }
+    c->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    Carver sizing(nullptr);
+    carve(c, sizing);
+    c->ws_bytes = align_up(sizing.pos, 256);
+    e = hipMalloc(reinterpret_cast<void**>(&c->ws), c->ws_bytes);
+    if (e != hipSuccess) {
+        int rc = fail(nullptr, SLIMDP_ERR_WORKSPACE, "slimdp_create: hipMalloc(%zu bytes): %s", c->ws_bytes, hipGetErrorString(e));
+        delete c;
+        return rc;
+    }
+    Carver cv(c->ws);
+    carve(c, cv);
+    // tables are uploaded once; the copies are synchronous with respect to the host
+    e = hipMemcpy(c->d_tile_start, c->tl.tile_start.data(), (c->T + 1) * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->d_tile_seg, c->tl.tile_seg.data(), c->T * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->d_seg_first_tile, c->tl.seg_first_tile.data(), (n_seg + 1) * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemset(c->d_flags, 0, 64 * 4);
+    if (e != hipSuccess) {
+        int rc = hip_fail(nullptr, e, "slimdp_create: table upload");
+        (void)hipFree(c->ws);
+        delete c;
+        return rc;
+    }
+    *out = c;
+    return SLIMDP_OK;
+}
+
+int slimdp_destroy(slimdp_ctx* ctx)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    (void)hipStreamSynchronize(ctx->stream);
+    hipError_t e = hipFree(ctx->ws);
+    delete ctx;
+    return e == hipSuccess ? SLIMDP_OK : SLIMDP_ERR_HIP;
+}
+
+int slimdp_tile_starts(const slimdp_ctx* ctx, uint32_t* tile_start)
+{
+    if (!ctx || !tile_start) return SLIMDP_ERR_INVALID_ARG;
+    memcpy(tile_start, ctx->tl.tile_start.data(), (ctx->T + 1) * sizeof(uint32_t));
+    return SLIMDP_OK;
+}
+
+int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value)
+{
+    if (!ctx || !name) return SLIMDP_ERR_INVALID_ARG;
+    if (strcmp(name, "explore_force_fallback") == 0) { ctx->opt_force_fallback = value; return SLIMDP_OK; }
+    return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_set_option: unknown option '%s'", name);
+}
+
+int slimdp_synchronize(slimdp_ctx* ctx)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    SLIMDP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    uint32_t flags[2] = {0, 0};
+    SLIMDP_HIP(ctx, hipMemcpy(flags, ctx->d_flags, sizeof flags, hipMemcpyDeviceToHost));
+    if (flags[1]) {
+        SLIMDP_HIP(ctx, hipMemset(ctx->d_flags + 1, 0, 4));
+        return fail(ctx, SLIMDP_ERR_DEVICE_STATUS, "device status 0x%x:%s%s", flags[1],
+                    (flags[1] & 1u) ? " an emitted index list does not have the requested length;" : "",
+                    (flags[1] & 2u) ? " a segment holds fewer eligible parameters than requested;" : "");
+    }
+    return SLIMDP_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_t W, float c, float* score)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    if (!w || !score) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_score: NULL array");
+    if (W == 0 || W > ctx->maxW) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_score: W=%u outside [1, %u]", W, ctx->maxW);
+    if (!table_ok(g, W)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_score: NULL update pointer");
+    if (!(c >= 0.0f) || std::isinf(c)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_score: c must be finite and >= 0");
+    ctx->hist_pending = false;
+    int rc = fill(ctx, ctx->c_hist, (uint64_t)ctx->n_seg * H_STRIDE, 0u);
+    if (rc) return rc;
+    PtrTab gt = make_tab<PtrTab>(g, W);
+    int vec_ok = aligned16(w) && aligned16(score);
+    for (uint32_t q = 0; q < W; ++q) vec_ok = vec_ok && aligned16(g[q]);
+    const uint32_t P = persistent_blocks(ctx, 4, 1);
+    const dim3 grid(P), block(BLOCK);
+#define LAUNCH_SCORE(WT)                                                                                              \
+    hipLaunchKernelGGL(k_score<WT>, grid, block, 0, ctx->stream, w, gt, (int)W, c, score, ctx->d_tile_start,           \
+                       ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok)
+    switch (W) {
+        case 1: LAUNCH_SCORE(1); break;
+        case 2: LAUNCH_SCORE(2); break;
+        case 4: LAUNCH_SCORE(4); break;
+        case 8: LAUNCH_SCORE(8); break;
+        case 16: LAUNCH_SCORE(16); break;
+        default: LAUNCH_SCORE(0); break;
+    }
+#undef LAUNCH_SCORE
+    SLIMDP_LAUNCHED(ctx, "k_score");
+    ctx->hist_pending = true;
+    ctx->hist_score = score;
+    return SLIMDP_OK;
+}
+
+int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_seg, uint32_t flags, uint32_t* core_idx,
+                       uint32_t* core_bits, uint32_t* core_off, uint64_t* core_epoch)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    if (!score || !k_seg || !core_bits || !core_off || !core_epoch)
+        return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_select_core: NULL argument");
+    uint64_t K = 0;
+    std::vector<SegInit> init(ctx->n_seg);
+    for (uint32_t s = 0; s < ctx->n_seg; ++s) {
+        const uint64_t ns = ctx->seg_off[s + 1] - ctx->seg_off[s];
+        if (k_seg[s] > ns)
+            return fail(ctx, SLIMDP_ERR_OUT_OF_RANGE, "slimdp_select_core: k_seg[%u]=%llu exceeds the segment size %llu", s,
+                        (unsigned long long)k_seg[s], (unsigned long long)ns);
+        init[s] = SegInit{(uint32_t)k_seg[s], 0u, 0u};
+        K += k_seg[s];
+    }
+    if (K > 0 && !core_idx) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_select_core: core_idx is NULL");
+    const bool reuse = (flags & SLIMDP_SELECT_REUSE_HISTOGRAM) != 0;
+    if (reuse && !(ctx->hist_pending && ctx->hist_score == score))
+        return fail(ctx, SLIMDP_ERR_INVALID_ARG,
+                    "slimdp_select_core: no histogram pending for this score buffer (call slimdp_score first)");
+    ctx->hist_pending = false;
+    const uint32_t T = ctx->T, S = ctx->n_seg;
+    int rc = init_states(ctx, ctx->c_state, init, 1, 1);
+    if (rc) return rc;
+    const uint32_t P = persistent_blocks(ctx, 4, 1);
+    if (!reuse) {
+        rc = fill(ctx, ctx->c_hist, (uint64_t)S * H_STRIDE, 0u);
+        if (rc) return rc;
+        hipLaunchKernelGGL(k_core_hist0, dim3(P), dim3(BLOCK), 0, ctx->stream, score, ctx->d_tile_start, ctx->d_tile_seg, T,
+                           ctx->c_hist);
+        SLIMDP_LAUNCHED(ctx, "k_core_hist0");
+    }
+    hipLaunchKernelGGL(k_threshold, dim3(S, 1), dim3(256), 0, ctx->stream, ctx->c_state, ctx->c_hist, 0, (uint32_t)H_L0, S, 0,
+                       ctx->d_flags);
+    SLIMDP_LAUNCHED(ctx, "k_threshold(0)");
+    hipLaunchKernelGGL(k_core_build, dim3(P), dim3(BLOCK), 0, ctx->stream, score, ctx->d_tile_start, ctx->d_tile_seg, T,
+                       ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys, ctx->c_cnt_gt,
+                       ctx->c_cnt_cand, (int)aligned16(score));
+    SLIMDP_LAUNCHED(ctx, "k_core_build");
+    MutPtrTab off_tab = make_tab<MutPtrTab, uint32_t*>(&core_off, 1);
+    MutPtrTab idx_tab = make_tab<MutPtrTab, uint32_t*>(&core_idx, 1);
+    uint32_t* pub = ctx->tl.word_aligned ? core_bits : nullptr;
+    rc = finish_selection(ctx, 1, ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys,
+                          ctx->c_cnt_gt, ctx->c_cnt_cand, ctx->c_cnt_sel, ctx->c_cnt_tie, ctx->c_tie_pre, ctx->keys_stride,
+                          true, off_tab, idx_tab, (uint32_t)K, pub);
+    if (rc) return rc;
+    if (!pub) {
+        rc = fill(ctx, core_bits, (ctx->n + 31) / 32, 0u);
+        if (rc) return rc;
+        if (K) {
+            hipLaunchKernelGGL(k_bits_from_idx, dim3(fill_grid(K)), dim3(256), 0, ctx->stream, core_idx, K, ctx->n, core_bits);
+            SLIMDP_LAUNCHED(ctx, "k_bits_from_idx");
+        }
+    }
+    *core_epoch = ++ctx->epoch;
+    return SLIMDP_OK;
+}
+
+int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint64_t* k_seg, uint32_t worker0,
+                          uint32_t n_workers, uint64_t iteration, const uint64_t* m_seg, uint32_t* const* expl_idx,
+                          uint32_t* const* expl_off)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    if (!core_bits || !k_seg || !m_seg) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_sample_explore: NULL argument");
+    if (n_workers == 0 || n_workers > ctx->maxW)
+        return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_sample_explore: n_workers=%u outside [1, %u]", n_workers, ctx->maxW);
+    if (!table_ok(expl_off, n_workers)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_sample_explore: NULL expl_off entry");
+    uint64_t M = 0;
+    std::vector<SegInit> init(ctx->n_seg);
+    for (uint32_t s = 0; s < ctx->n_seg; ++s) {
+        const uint64_t ns = ctx->seg_off[s + 1] - ctx->seg_off[s];
+        if (k_seg[s] > ns || m_seg[s] > ns - k_seg[s])
+            return fail(ctx, SLIMDP_ERR_OUT_OF_RANGE,
+                        "slimdp_sample_explore: segment %u: m=%llu exceeds the %llu parameters outside the core", s,
+                        (unsigned long long)m_seg[s], (unsigned long long)(k_seg[s] > ns ? 0 : ns - k_seg[s]));
+        const uint64_t m = m_seg[s];
+        M += m;
+        SegInit in{(uint32_t)m, 0u, 0u};
+        if (m > 0) {
+            // Narrow bound: expect m + 6 sqrt(m) + 32 candidate words below it; the exact
+            // rerun with the full range catches the (astronomically rare) shortfall.
+            const double avail = (double)(ns - k_seg[s]);
+            double frac = ((double)m + 6.0 * std::sqrt((double)m) + 32.0) / avail;
+            if (ctx->opt_force_fallback) frac = 0.25 * (double)m / avail;
+            if (frac >= 0.95) {
+                in.bound_m1 = 0xFFFFFFFFu; in.shift0 = 20;
+            } else {
+                uint64_t B0 = (uint64_t)std::ceil(frac * 4294967296.0);
+                if (B0 < 1) B0 = 1;
+                uint32_t bitlen = 0;
+                while (bitlen < 33 && ((B0 - 1) >> bitlen) != 0) ++bitlen;
+                const uint32_t sh = bitlen > 12 ? bitlen - 12 : 0;
+                B0 = (B0 + ((1ull << sh) - 1)) >> sh << sh;
+                if (B0 > (1ull << 32)) B0 = 1ull << 32;
+                in.bound_m1 = (uint32_t)(B0 - 1);
+                in.shift0 = sh;
+            }
+        }
+        init[s] = in;
+    }
+    if (M > 0 && !table_ok(expl_idx, n_workers)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_sample_explore: NULL expl_idx entry");
+    const uint32_t T = ctx->T, S = ctx->n_seg, B = n_workers;
+    int rc = init_states(ctx, ctx->e_state, init, B, 0);
+    if (rc) return rc;
+    rc = fill(ctx, ctx->e_hist, (uint64_t)B * S * H_STRIDE, 0u);
+    if (rc) return rc;
+    rc = fill(ctx, ctx->d_flags, 1, 0u);
+    if (rc) return rc;
+    const uint32_t P = persistent_blocks(ctx, 8, B);
+    const uint32_t seed_lo = (uint32_t)ctx->seed, seed_hi = (uint32_t)(ctx->seed >> 32);
+    const uint32_t it_lo = (uint32_t)iteration, it_hi = (uint32_t)(iteration >> 32);
+    for (int fb = 0; fb < 2; ++fb) {
+        hipLaunchKernelGGL(k_explore_keys, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->n, ctx->d_tile_start,
+                           ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_cand_bits, ctx->e_cand_keys,
+                           ctx->e_cnt_cand, ctx->keys_stride, worker0, seed_lo, seed_hi, it_lo, it_hi, fb, ctx->d_flags);
+        SLIMDP_LAUNCHED(ctx, "k_explore_keys");
+        hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, ctx->stream, ctx->e_state, ctx->e_hist, 0,
+                           (uint32_t)(fb ? H_L0FB : H_L0), S, fb ? 2 : 1, ctx->d_flags);
+        SLIMDP_LAUNCHED(ctx, "k_threshold(0)");
+    }
+    MutPtrTab off_tab = make_tab<MutPtrTab>(expl_off, B);
+    MutPtrTab idx_tab = make_tab<MutPtrTab>(expl_idx, B);
+    return finish_selection(ctx, B, ctx->e_state, ctx->e_hist, nullptr, ctx->e_cand_bits, ctx->e_cand_keys, nullptr,
+                            ctx->e_cnt_cand, ctx->e_cnt_sel, ctx->e_cnt_tie, ctx->e_tie_pre, ctx->keys_stride, false,
+                            off_tab, idx_tab, (uint32_t)M, nullptr);
+}
+
+int slimdp_tile_offsets(slimdp_ctx* ctx, const uint32_t* idx, uint64_t count, uint32_t* off)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    if (!off || (count && !idx)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_tile_offsets: NULL argument");
+    if (count > ctx->n) return fail(ctx, SLIMDP_ERR_OUT_OF_RANGE, "slimdp_tile_offsets: count exceeds n");
+    hipLaunchKernelGGL(k_tile_offsets, dim3((ctx->T + 1 + 255) / 256), dim3(256), 0, ctx->stream, idx, count,
+                       ctx->d_tile_start, ctx->T, ctx->n, off);
+    SLIMDP_LAUNCHED(ctx, "k_tile_offsets");
+    return SLIMDP_OK;
+}
+
+static int check_lists(slimdp_ctx* ctx, const char* who, uint32_t n_workers, const uint32_t* core_idx,
+                       const uint32_t* core_off, uint64_t k, const uint32_t* const* expl_idx,
+                       const uint32_t* const* expl_off, const uint64_t* m_w)
+{
+    if (n_workers == 0 || n_workers > ctx->maxW)
+        return fail(ctx, SLIMDP_ERR_INVALID_ARG, "%s: n_workers=%u outside [1, %u]", who, n_workers, ctx->maxW);
+    if (!core_off || (k && !core_idx) || !m_w) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "%s: NULL argument", who);
+    if (k > ctx->n) return fail(ctx, SLIMDP_ERR_OUT_OF_RANGE, "%s: k exceeds n", who);
+    if (!table_ok(expl_off, n_workers)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "%s: NULL expl_off entry", who);
+    for (uint32_t q = 0; q < n_workers; ++q) {
+        if (m_w[q] > ctx->n - k) return fail(ctx, SLIMDP_ERR_OUT_OF_RANGE, "%s: m_w[%u] exceeds n - k", who, q);
+        if (m_w[q] && (!expl_idx || !expl_idx[q])) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "%s: NULL expl_idx entry", who);
+    }
+    return SLIMDP_OK;
+}
+
+int slimdp_pack(slimdp_ctx* ctx, uint32_t n_workers, const float* const* g, const uint32_t* core_idx,
+                const uint32_t* core_off, uint64_t k, const uint32_t* const* expl_idx, const uint32_t* const* expl_off,
+                const uint64_t* m_w, float* const* core_val, float* const* expl_val, uint64_t core_epoch)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    int rc = check_lists(ctx, "slimdp_pack", n_workers, core_idx, core_off, k, expl_idx, expl_off, m_w);
+    if (rc) return rc;
+    if (!table_ok(g, n_workers)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_pack: NULL update pointer");
+    for (uint32_t q = 0; q < n_workers; ++q) {
+        if (k && (!core_val || !core_val[q])) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_pack: NULL core_val entry");
+        if (m_w[q] && (!expl_val || !expl_val[q])) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_pack: NULL expl_val entry");
+    }
+    rc = check_epoch(ctx, core_epoch);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_gather, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, make_tab<PtrTab>(g, n_workers), 0, n_workers,
+                       ctx->n, core_idx, core_off, make_tab<PtrTab>(expl_idx, n_workers),
+                       make_tab<PtrTab>(expl_off, n_workers), make_tab<MutPtrTab>(core_val, n_workers),
+                       make_tab<MutPtrTab>(expl_val, n_workers), make_tab<MutPtrTab, float*>(nullptr, 0));
+    SLIMDP_LAUNCHED(ctx, "k_gather(pack)");
+    return SLIMDP_OK;
+}
+
+int slimdp_merge(slimdp_ctx* ctx, float* w, float lr, uint64_t core_epoch, uint32_t n_workers, const uint32_t* core_idx,
+                 const uint32_t* core_off, uint64_t k, const float* const* core_val, const uint32_t* const* expl_idx,
+                 const uint32_t* const* expl_off, const float* const* expl_val, const uint64_t* m_w)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    if (!w) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_merge: w is NULL");
+    int rc = check_lists(ctx, "slimdp_merge", n_workers, core_idx, core_off, k, expl_idx, expl_off, m_w);
+    if (rc) return rc;
+    for (uint32_t q = 0; q < n_workers; ++q) {
+        if (k && (!core_val || !core_val[q])) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_merge: NULL core_val entry");
+        if (m_w[q] && (!expl_val || !expl_val[q])) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_merge: NULL expl_val entry");
+    }
+    rc = check_epoch(ctx, core_epoch);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_merge, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, w, lr, n_workers, ctx->d_tile_start, core_idx,
+                       core_off, make_tab<PtrTab>(core_val, n_workers), make_tab<PtrTab>(expl_idx, n_workers),
+                       make_tab<PtrTab>(expl_off, n_workers), make_tab<PtrTab>(expl_val, n_workers), (int)aligned16(w));
+    SLIMDP_LAUNCHED(ctx, "k_merge");
+    return SLIMDP_OK;
+}
+
+int slimdp_pull(slimdp_ctx* ctx, const float* w, uint64_t core_epoch, uint32_t n_workers, const uint32_t* core_idx,
+                const uint32_t* core_off, uint64_t k, const uint32_t* const* expl_idx, const uint32_t* const* expl_off,
+                const uint64_t* m_w, float* const* core_out, float* const* expl_out, float* const* w_local)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    if (!w) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_pull: w is NULL");
+    int rc = check_lists(ctx, "slimdp_pull", n_workers, core_idx, core_off, k, expl_idx, expl_off, m_w);
+    if (rc) return rc;
+    for (uint32_t q = 0; q < n_workers; ++q) {
+        if (k && (!core_out || !core_out[q])) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_pull: NULL core_out entry");
+        if (m_w[q] && (!expl_out || !expl_out[q])) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_pull: NULL expl_out entry");
+        if (w_local && w_local[q] == w) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_pull: w_local aliases w");
+    }
+    rc = check_epoch(ctx, core_epoch);
+    if (rc) return rc;
+    const float* src = w;
+    hipLaunchKernelGGL(k_gather, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, make_tab<PtrTab, const float*>(&src, 1), 1,
+                       n_workers, ctx->n, core_idx, core_off, make_tab<PtrTab>(expl_idx, n_workers),
+                       make_tab<PtrTab>(expl_off, n_workers), make_tab<MutPtrTab>(core_out, n_workers),
+                       make_tab<MutPtrTab>(expl_out, n_workers), make_tab<MutPtrTab>(w_local, w_local ? n_workers : 0));
+    SLIMDP_LAUNCHED(ctx, "k_gather(pull)");
+    return SLIMDP_OK;
+}
+
+int slimdp_debug_philox(slimdp_ctx* ctx, uint64_t iteration, uint32_t worker, uint32_t i0, uint64_t count, uint32_t* out)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    if (count && !out) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_debug_philox: out is NULL");
+    if (count == 0) return SLIMDP_OK;
+    hipLaunchKernelGGL(k_debug_philox, dim3(fill_grid(count)), dim3(256), 0, ctx->stream, (uint32_t)ctx->seed,
+                       (uint32_t)(ctx->seed >> 32), (uint32_t)iteration, (uint32_t)(iteration >> 32), worker, i0, count, out);
+    SLIMDP_LAUNCHED(ctx, "k_debug_philox");
+    return SLIMDP_OK;
+}
+
+}  // extern "C"

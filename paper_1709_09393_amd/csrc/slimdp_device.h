@@ -1,0 +1,129 @@
+// Device-side building blocks of libslimdp (gfx950, wave64).  Included only by slimdp.hip.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "slimdp.h"
+
+namespace slimdp {
+
+constexpr uint32_t TILE = SLIMDP_TILE;            // parameters per tile
+constexpr uint32_t TILE_WORDS = TILE / 32;        // bitmap words per tile
+constexpr uint32_t NONE = 0xFFFFFFFFu;
+constexpr int MAXW = SLIMDP_MAX_WORKERS;
+constexpr int BLOCK = 256;                        // threads per block in the tile kernels
+constexpr int EPT = TILE / BLOCK;                 // elements per thread per tile (16)
+
+// Histogram storage per (batch, segment): level 0, level 0 of the wide-bound rerun,
+// level 1, level 2.
+constexpr uint32_t H_L0 = 0, H_L0FB = 8192, H_L1 = 16384, H_L2 = 20480, H_STRIDE = 24576;
+
+// Core ranking key = raw bits of the score: 13 + 12 + 7 bits.
+constexpr uint32_t CORE_SHIFT0 = 19, CORE_NB0 = 8192, CORE_SHIFT1 = 7, CORE_NB1 = 4096, CORE_NB2 = 128;
+
+struct PtrTab { const void* p[MAXW]; };           // host pointer tables travel as kernel arguments
+struct MutPtrTab { void* p[MAXW]; };
+
+// Selection state of one (batch, segment): the radix descent towards the threshold key.
+struct SegState {
+    uint32_t need0;     // number of elements to select
+    uint32_t need;      // of those, how many still come from the keys matching `prefix`
+    uint32_t prefix;    // keys still in play satisfy (key >> shift[level-1]) == prefix
+    uint32_t none;      // 1: nothing is selected here
+    uint32_t tau;       // threshold key once all levels are done
+    uint32_t quota;     // how many keys == tau are taken, lowest index first
+    uint32_t bound_m1;  // explorer only: candidates are words r <= bound_m1, key = bound_m1 - r
+    uint32_t pad0;
+    uint32_t shift[3];  // digit of level l = (key >> shift[l]) & (nbins[l] - 1); level 0 unmasked
+    uint32_t nbins[3];
+    uint32_t pad1[2];
+};
+static_assert(sizeof(SegState) == 64, "SegState layout");
+
+struct SegInit { uint32_t need; uint32_t bound_m1; uint32_t shift0; };
+constexpr int INIT_CHUNK = 256;
+struct SegInitChunk { SegInit s[INIT_CHUNK]; };
+
+// ---------------------------------------------------------------------------------------
+// wave / block primitives
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
+{
+    const uint32_t lane = lane_id();
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t t = __shfl_up(v, d, 64);
+        if (lane >= (uint32_t)d) v += t;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+// Exclusive prefix sum over the block (NWAVES*64 threads, all must call).  wtot: NWAVES words
+// of shared memory, free for reuse on return.
+template <int NWAVES>
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wtot, uint32_t& total)
+{
+    const uint32_t lane = lane_id(), wid = threadIdx.x >> 6;
+    const uint32_t incl = wave_incl_scan(v);
+    if (lane == 63) wtot[wid] = incl;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < NWAVES; ++w) {
+        const uint32_t t = wtot[w];
+        if ((uint32_t)w < wid) base += t;
+        tot += t;
+    }
+    __syncthreads();
+    total = tot;
+    return base + incl - v;
+}
+
+// Local element handled by (thread, slot j) of a tile.  Vector layout: four consecutive
+// elements per thread and round (16-byte loads); scalar layout: one element per thread and round.
+__device__ __forceinline__ uint32_t elem_vec(int j) { return (uint32_t)(j >> 2) * 1024u + threadIdx.x * 4u + (uint32_t)(j & 3); }
+__device__ __forceinline__ uint32_t elem_scl(int j) { return (uint32_t)j * BLOCK + threadIdx.x; }
+
+__device__ __forceinline__ uint32_t mask_below(uint32_t bit) { return (1u << bit) - 1u; }   // bit in 0..31
+
+// ---------------------------------------------------------------------------------------
+// Philox4x32 with 10 rounds (Salmon et al., SC'11): the explorer's random words.
+// Counter (c0, c1, c2, c3), key (k0, k1).
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t out[4])
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// Equation (1) with the rounding the interface promises: one fused multiply-add, canonical NaN.
+__device__ __forceinline__ float significance(float w, float gsum, float c)
+{
+    float s = __builtin_fmaf(c, __builtin_fabsf(gsum), __builtin_fabsf(w));
+    if (s != s) s = __uint_as_float(0x7FC00000u);
+    return s;
+}
+
+}  // namespace slimdp

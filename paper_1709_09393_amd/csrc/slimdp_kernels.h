@@ -1,0 +1,773 @@
+// Kernels of libslimdp (gfx950).  Included only by slimdp.hip.
+//
+// Shared structure: the index range is cut into tiles of <= 4096 parameters (never across
+// a segment).  Exact "top-need by (key desc, index asc)" selection, used both for the core
+// (keys = score bits) and for the explorer (keys = bound - Philox word over the non-core
+// parameters), is a three-level radix descent:
+//   level 0 histogram over every key (fused into the kernel that produces the keys),
+//   -> keys in the threshold bin become "candidates": a per-tile bitmap plus the tile's
+//      candidate keys compacted in index order at cand_keys[tile_start ...],
+//   levels 1 and 2 histogram only candidates, giving the threshold key tau and the number
+//   of keys == tau to take (quota, lowest index first),
+//   count per tile -> scan over tiles -> ordered emission of the ascending index list.
+#pragma once
+#include "slimdp_device.h"
+
+namespace slimdp {
+
+// ---------------------------------------------------------------------------------------
+// small utilities
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_fill_u32(uint32_t* __restrict__ p, uint64_t count, uint32_t v)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (uint64_t)gridDim.x * 256)
+        p[i] = v;
+}
+
+// Writes the selection state of segments [seg0, seg0+count) for every batch.
+// core != 0: fixed score-bit levels; else explorer levels derived from (bound_m1, shift0).
+__global__ __launch_bounds__(256) void k_init_state(SegState* __restrict__ st, SegInitChunk chunk, uint32_t seg0,
+                                                    uint32_t count, uint32_t n_seg, uint32_t nbatch, int core)
+{
+    const uint32_t x = blockIdx.x * 256 + threadIdx.x;
+    if (x >= count * nbatch) return;
+    const uint32_t b = x / count, j = x % count;
+    const SegInit in = chunk.s[j];
+    SegState s;
+    s.need0 = in.need; s.need = in.need; s.prefix = 0; s.none = (in.need == 0) ? 1u : 0u;
+    s.tau = NONE; s.quota = 0; s.bound_m1 = in.bound_m1; s.pad0 = 0; s.pad1[0] = s.pad1[1] = 0;
+    if (core) {
+        s.shift[0] = CORE_SHIFT0; s.nbins[0] = CORE_NB0;
+        s.shift[1] = CORE_SHIFT1; s.nbins[1] = CORE_NB1;
+        s.shift[2] = 0;           s.nbins[2] = CORE_NB2;
+    } else {
+        const uint32_t sh0 = in.shift0;
+        const uint32_t bits1 = sh0 < 12u ? sh0 : 12u;
+        const uint32_t sh1 = sh0 - bits1;
+        s.shift[0] = sh0; s.nbins[0] = (in.bound_m1 >> sh0) + 1u;
+        s.shift[1] = sh1; s.nbins[1] = 1u << bits1;
+        s.shift[2] = 0;   s.nbins[2] = 1u << sh1;
+    }
+    st[(size_t)b * n_seg + seg0 + j] = s;
+}
+
+// ---------------------------------------------------------------------------------------
+// K1: significance of every parameter + level-0 histogram of its bits (per segment).
+// Reads w and the W updates once, writes the score once: 4n(W+2) bytes.
+// Persistent blocks over contiguous tile ranges keep the 8192-bin histogram in LDS.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void flush_hist(uint32_t* lds, uint32_t nb, uint32_t* __restrict__ g)
+{
+    for (uint32_t b = threadIdx.x; b < nb; b += BLOCK) {
+        const uint32_t v = lds[b];
+        if (v) { atomicAdd(&g[b], v); lds[b] = 0; }
+    }
+}
+
+template <int WT>
+__global__ __launch_bounds__(BLOCK) void k_score(const float* __restrict__ w, PtrTab g, int Wrt, float c,
+                                                 float* __restrict__ S, const uint32_t* __restrict__ tile_start,
+                                                 const uint32_t* __restrict__ tile_seg, uint32_t T,
+                                                 uint32_t* __restrict__ hist, int vec_ok)
+{
+    __shared__ uint32_t h[CORE_NB0];
+    const int W = WT ? WT : Wrt;
+    for (uint32_t b = threadIdx.x; b < CORE_NB0; b += BLOCK) h[b] = 0;
+    __syncthreads();
+    const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
+    const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
+    if (t0 >= t1) return;
+    uint32_t cur_seg = tile_seg[t0];
+    for (uint32_t t = t0; t < t1; ++t) {
+        const uint32_t seg = tile_seg[t];
+        if (seg != cur_seg) {
+            __syncthreads();
+            flush_hist(h, CORE_NB0, hist + (size_t)cur_seg * H_STRIDE + H_L0);
+            __syncthreads();
+            cur_seg = seg;
+        }
+        const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
+        if (vec_ok && len == TILE && (start & 3u) == 0) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const size_t e = (size_t)start + (size_t)r * 1024 + threadIdx.x * 4;
+                const float4 wv = *reinterpret_cast<const float4*>(w + e);
+                float4 a = *reinterpret_cast<const float4*>(static_cast<const float*>(g.p[0]) + e);
+#pragma unroll
+                for (int k = 1; k < (WT ? WT : MAXW); ++k) {
+                    if (k >= W) break;
+                    const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(g.p[k]) + e);
+                    a.x = a.x + x.x; a.y = a.y + x.y; a.z = a.z + x.z; a.w = a.w + x.w;
+                }
+                float4 s;
+                s.x = significance(wv.x, a.x, c); s.y = significance(wv.y, a.y, c);
+                s.z = significance(wv.z, a.z, c); s.w = significance(wv.w, a.w, c);
+                *reinterpret_cast<float4*>(S + e) = s;
+                atomicAdd(&h[__float_as_uint(s.x) >> CORE_SHIFT0], 1u);
+                atomicAdd(&h[__float_as_uint(s.y) >> CORE_SHIFT0], 1u);
+                atomicAdd(&h[__float_as_uint(s.z) >> CORE_SHIFT0], 1u);
+                atomicAdd(&h[__float_as_uint(s.w) >> CORE_SHIFT0], 1u);
+            }
+        } else {
+            for (uint32_t l = threadIdx.x; l < len; l += BLOCK) {
+                const size_t e = (size_t)start + l;
+                float a = static_cast<const float*>(g.p[0])[e];
+                for (int k = 1; k < W; ++k) a = a + static_cast<const float*>(g.p[k])[e];
+                const float s = significance(w[e], a, c);
+                S[e] = s;
+                atomicAdd(&h[__float_as_uint(s) >> CORE_SHIFT0], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    flush_hist(h, CORE_NB0, hist + (size_t)cur_seg * H_STRIDE + H_L0);
+}
+
+// Level-0 histogram of a score array that did not come from k_score.
+__global__ __launch_bounds__(BLOCK) void k_core_hist0(const float* __restrict__ S, const uint32_t* __restrict__ tile_start,
+                                                      const uint32_t* __restrict__ tile_seg, uint32_t T,
+                                                      uint32_t* __restrict__ hist)
+{
+    __shared__ uint32_t h[CORE_NB0];
+    for (uint32_t b = threadIdx.x; b < CORE_NB0; b += BLOCK) h[b] = 0;
+    __syncthreads();
+    const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
+    const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
+    if (t0 >= t1) return;
+    uint32_t cur_seg = tile_seg[t0];
+    for (uint32_t t = t0; t < t1; ++t) {
+        const uint32_t seg = tile_seg[t];
+        if (seg != cur_seg) {
+            __syncthreads();
+            flush_hist(h, CORE_NB0, hist + (size_t)cur_seg * H_STRIDE + H_L0);
+            __syncthreads();
+            cur_seg = seg;
+        }
+        const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
+        for (uint32_t l = threadIdx.x; l < len; l += BLOCK)
+            atomicAdd(&h[__float_as_uint(S[(size_t)start + l]) >> CORE_SHIFT0], 1u);
+    }
+    __syncthreads();
+    flush_hist(h, CORE_NB0, hist + (size_t)cur_seg * H_STRIDE + H_L0);
+}
+
+// ---------------------------------------------------------------------------------------
+// Threshold step of one radix level: walk the bins from the largest digit down until
+// `need` keys are covered.  grid (n_seg, nbatch), 256 threads.
+// mode 0: plain.  mode 1: explorer level 0 with the narrow bound; too few candidates raise
+// the rerun flag.  mode 2: explorer level 0 after the wide-bound rerun (only if flagged).
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states, const uint32_t* __restrict__ hist,
+                                                   int level, uint32_t hist_off, uint32_t n_seg, int mode,
+                                                   uint32_t* __restrict__ flags)
+{
+    __shared__ uint32_t wtot[4];
+    __shared__ uint32_t sh_bcast[2];
+    const uint32_t seg = blockIdx.x, b = blockIdx.y;
+    SegState* st = &states[(size_t)b * n_seg + seg];
+    const uint32_t* hp = hist + ((size_t)b * n_seg + seg) * H_STRIDE + hist_off;
+    if (mode == 2) {
+        if (flags[0] == 0) return;
+        if (threadIdx.x == 0) {          // wide bound: every non-core parameter is a candidate
+            st->bound_m1 = 0xFFFFFFFFu;
+            st->shift[0] = 20; st->nbins[0] = 4096;
+            st->shift[1] = 8;  st->nbins[1] = 4096;
+            st->shift[2] = 0;  st->nbins[2] = 256;
+            st->need = st->need0; st->prefix = 0; st->none = (st->need0 == 0) ? 1u : 0u;
+        }
+        __syncthreads();
+    }
+    const uint32_t need = st->need, none = st->none, nb = st->nbins[level];
+    const uint32_t prefix = st->prefix;
+    const uint32_t bits = (level == 0) ? 0u : (st->shift[level - 1] - st->shift[level]);
+    __syncthreads();
+    if (none || need == 0) {
+        if (threadIdx.x == 0) { st->none = 1; st->need = 0; st->tau = NONE; st->quota = 0; }
+        return;
+    }
+    const uint32_t C = (nb + 255u) / 256u;
+    const uint32_t p0 = threadIdx.x * C;
+    uint32_t sum = 0;
+    for (uint32_t p = p0; p < p0 + C && p < nb; ++p) sum += hp[nb - 1u - p];
+    uint32_t total;
+    const uint32_t excl = block_excl_scan<4>(sum, wtot, total);
+    if (total < need) {
+        if (threadIdx.x == 0) {
+            if (mode == 1) atomicOr(&flags[0], 1u);                    // rerun with the wide bound
+            else { atomicOr(&flags[1], 2u); st->none = 1; st->need = 0; st->tau = NONE; st->quota = 0; }
+        }
+        return;
+    }
+    if (excl < need && need <= excl + sum) {
+        uint32_t run = excl;
+        for (uint32_t p = p0; p < p0 + C && p < nb; ++p) {
+            const uint32_t bin = nb - 1u - p;
+            const uint32_t cnt = hp[bin];
+            if (run + cnt >= need) {
+                const uint32_t np = (level == 0) ? bin : ((prefix << bits) | bin);
+                st->prefix = np;
+                st->need = need - run;
+                if (level == 2) { st->tau = np; st->quota = need - run; }
+                break;
+            }
+            run += cnt;
+        }
+    }
+    (void)sh_bcast;
+}
+
+// ---------------------------------------------------------------------------------------
+// K2: core candidates.  One pass over the score: parameters whose level-0 digit is above
+// the threshold bin are certainly in the core (gt bitmap), those in the bin are candidates
+// (bitmap + keys compacted per tile) and feed the level-1 histogram.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ S, const uint32_t* __restrict__ tile_start,
+                                                      const uint32_t* __restrict__ tile_seg, uint32_t T,
+                                                      const SegState* __restrict__ states, uint32_t* __restrict__ hist,
+                                                      uint32_t* __restrict__ gt_bits, uint32_t* __restrict__ cand_bits,
+                                                      uint32_t* __restrict__ cand_keys, uint32_t* __restrict__ cnt_gt,
+                                                      uint32_t* __restrict__ cnt_cand, int vec_ok)
+{
+    __shared__ uint32_t h[CORE_NB1];
+    __shared__ uint32_t gt[TILE_WORDS], cd[TILE_WORDS], cpre[TILE_WORDS];
+    __shared__ uint32_t wtot[4];
+    for (uint32_t b = threadIdx.x; b < CORE_NB1; b += BLOCK) h[b] = 0;
+    const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
+    const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
+    if (t0 >= t1) return;
+    uint32_t cur_seg = tile_seg[t0];
+    for (uint32_t t = t0; t < t1; ++t) {
+        const uint32_t seg = tile_seg[t];
+        if (seg != cur_seg) {
+            __syncthreads();
+            flush_hist(h, CORE_NB1, hist + (size_t)cur_seg * H_STRIDE + H_L1);
+            cur_seg = seg;
+        }
+        const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
+        const uint32_t b1 = states[seg].prefix, none = states[seg].none;
+        if (threadIdx.x < TILE_WORDS) { gt[threadIdx.x] = 0; cd[threadIdx.x] = 0; }
+        __syncthreads();
+        const bool vec = vec_ok && len == TILE && (start & 3u) == 0;
+        uint32_t key[EPT];
+        if (vec) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint4 v = *reinterpret_cast<const uint4*>(S + (size_t)start + r * 1024 + threadIdx.x * 4);
+                key[4 * r + 0] = v.x; key[4 * r + 1] = v.y; key[4 * r + 2] = v.z; key[4 * r + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < EPT; ++j) {
+                const uint32_t e = elem_scl(j);
+                key[j] = (e < len) ? __float_as_uint(S[(size_t)start + e]) : 0u;
+            }
+        }
+        uint32_t is_cand = 0;   // bit j: slot j is a candidate
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            const uint32_t e = vec ? elem_vec(j) : elem_scl(j);
+            if (e < len && !none) {
+                const uint32_t d = key[j] >> CORE_SHIFT0;
+                if (d > b1) atomicOr(&gt[e >> 5], 1u << (e & 31));
+                else if (d == b1) {
+                    atomicOr(&cd[e >> 5], 1u << (e & 31));
+                    atomicAdd(&h[(key[j] >> CORE_SHIFT1) & (CORE_NB1 - 1u)], 1u);
+                    is_cand |= 1u << j;
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t cw = (threadIdx.x < TILE_WORDS) ? cd[threadIdx.x] : 0u;
+        const uint32_t gw = (threadIdx.x < TILE_WORDS) ? gt[threadIdx.x] : 0u;
+        uint32_t tot_c, tot_g;
+        const uint32_t ex = block_excl_scan<4>(__popc(cw), wtot, tot_c);
+        (void)block_excl_scan<4>(__popc(gw), wtot, tot_g);
+        if (threadIdx.x < TILE_WORDS) {
+            cpre[threadIdx.x] = ex;
+            gt_bits[(size_t)t * TILE_WORDS + threadIdx.x] = gw;
+            cand_bits[(size_t)t * TILE_WORDS + threadIdx.x] = cw;
+        }
+        if (threadIdx.x == 0) { cnt_cand[t] = tot_c; cnt_gt[t] = tot_g; }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            if (is_cand & (1u << j)) {
+                const uint32_t e = vec ? elem_vec(j) : elem_scl(j);
+                const uint32_t rank = cpre[e >> 5] + __popc(cd[e >> 5] & mask_below(e & 31));
+                cand_keys[(size_t)start + rank] = key[j];
+            }
+        }
+        __syncthreads();
+    }
+    __syncthreads();
+    flush_hist(h, CORE_NB1, hist + (size_t)cur_seg * H_STRIDE + H_L1);
+}
+
+// ---------------------------------------------------------------------------------------
+// K4: explorer candidates for every (worker, tile): the Philox word of each non-core
+// parameter; words r <= bound_m1 become candidates with key = bound_m1 - r (so that the
+// smallest words are the largest keys), plus the level-0 histogram of those keys.
+// grid (blocks, n_workers); fallback != 0: the wide-bound rerun, a no-op unless flagged.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_explore_keys(const uint32_t* __restrict__ core_bits, uint64_t n,
+                                                        const uint32_t* __restrict__ tile_start,
+                                                        const uint32_t* __restrict__ tile_seg, uint32_t T,
+                                                        uint32_t n_seg, const SegState* __restrict__ states,
+                                                        uint32_t* __restrict__ hist, uint32_t* __restrict__ cand_bits,
+                                                        uint32_t* __restrict__ cand_keys, uint32_t* __restrict__ cnt_cand,
+                                                        uint64_t keys_stride, uint32_t worker0, uint32_t seed_lo,
+                                                        uint32_t seed_hi, uint32_t it_lo, uint32_t it_hi, int fallback,
+                                                        const uint32_t* __restrict__ flags)
+{
+    __shared__ uint32_t h[4096];
+    __shared__ uint32_t cd[TILE_WORDS], cpre[TILE_WORDS];
+    __shared__ uint32_t wtot[4];
+    if (fallback && flags[0] == 0) return;
+    const uint32_t b = blockIdx.y, worker = worker0 + b;
+    const uint32_t hoff = fallback ? H_L0FB : H_L0;
+    for (uint32_t x = threadIdx.x; x < 4096; x += BLOCK) h[x] = 0;
+    const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
+    const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
+    if (t0 >= t1) return;
+    uint32_t* cbits = cand_bits + (size_t)b * T * TILE_WORDS;
+    uint32_t* ckeys = cand_keys + (size_t)b * keys_stride;
+    uint32_t* ccnt = cnt_cand + (size_t)b * T;
+    uint32_t cur_seg = tile_seg[t0];
+    for (uint32_t t = t0; t < t1; ++t) {
+        const uint32_t seg = tile_seg[t];
+        if (seg != cur_seg) {
+            __syncthreads();
+            flush_hist(h, 4096, hist + ((size_t)b * n_seg + cur_seg) * H_STRIDE + hoff);
+            cur_seg = seg;
+        }
+        const SegState* st = &states[(size_t)b * n_seg + seg];
+        const uint32_t bound_m1 = fallback ? 0xFFFFFFFFu : st->bound_m1;
+        const uint32_t shift0 = fallback ? 20u : st->shift[0];
+        const uint32_t skip = st->need0 == 0;
+        const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
+        if (threadIdx.x < TILE_WORDS) cd[threadIdx.x] = 0;
+        __syncthreads();
+        const uint32_t g0 = start >> 2, g1 = (start + len - 1u) >> 2;   // Philox blocks touched by the tile
+        uint32_t key[5][4];
+        uint32_t is_cand = 0;
+#pragma unroll
+        for (int it = 0; it < 5; ++it) {
+            const uint32_t gi = g0 + (uint32_t)it * BLOCK + threadIdx.x;
+            if (gi <= g1 && !skip) {
+                uint32_t r[4];
+                philox4x32_10(gi, worker, it_lo, it_hi, seed_lo, seed_hi, r);
+                const uint32_t i0 = gi << 2;
+                const uint32_t nib = (core_bits[i0 >> 5] >> (i0 & 31u)) & 0xFu;
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    const uint32_t e = i0 + cc - start;          // wraps below the tile start
+                    key[it][cc] = bound_m1 - r[cc];
+                    if (e < len && !((nib >> cc) & 1u) && r[cc] <= bound_m1) {
+                        atomicOr(&cd[e >> 5], 1u << (e & 31));
+                        atomicAdd(&h[key[it][cc] >> shift0], 1u);
+                        is_cand |= 1u << (it * 4 + cc);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t cw = (threadIdx.x < TILE_WORDS) ? cd[threadIdx.x] : 0u;
+        uint32_t tot_c;
+        const uint32_t ex = block_excl_scan<4>(__popc(cw), wtot, tot_c);
+        if (threadIdx.x < TILE_WORDS) {
+            cpre[threadIdx.x] = ex;
+            cbits[(size_t)t * TILE_WORDS + threadIdx.x] = cw;
+        }
+        if (threadIdx.x == 0) ccnt[t] = tot_c;
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < 5; ++it) {
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                if (is_cand & (1u << (it * 4 + cc))) {
+                    const uint32_t gi = g0 + (uint32_t)it * BLOCK + threadIdx.x;
+                    const uint32_t e = (gi << 2) + cc - start;
+                    const uint32_t rank = cpre[e >> 5] + __popc(cd[e >> 5] & mask_below(e & 31));
+                    ckeys[(size_t)start + rank] = key[it][cc];
+                }
+            }
+        }
+        __syncthreads();
+    }
+    __syncthreads();
+    flush_hist(h, 4096, hist + ((size_t)b * n_seg + cur_seg) * H_STRIDE + hoff);
+    (void)n;
+}
+
+// ---------------------------------------------------------------------------------------
+// Levels 1 and 2: histogram of the candidates that still match the prefix.  One wave per
+// tile list; equal digits inside a wave are merged before the global atomic.
+// grid (ceil(T/4), nbatch).
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_list_hist(const uint32_t* __restrict__ tile_start, const uint32_t* __restrict__ tile_seg,
+                                                     uint32_t T, uint32_t n_seg, const SegState* __restrict__ states,
+                                                     uint32_t* __restrict__ hist, uint32_t hist_off, int level,
+                                                     const uint32_t* __restrict__ cand_keys, const uint32_t* __restrict__ cnt_cand,
+                                                     uint64_t keys_stride)
+{
+    const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b = blockIdx.y, lane = lane_id();
+    if (t >= T) return;
+    const uint32_t seg = tile_seg[t];
+    const SegState* st = &states[(size_t)b * n_seg + seg];
+    if (st->none) return;
+    const uint32_t pshift = st->shift[level - 1], shift = st->shift[level], mask = st->nbins[level] - 1u;
+    const uint32_t prefix = st->prefix;
+    const uint32_t cnt = cnt_cand[(size_t)b * T + t];
+    const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tile_start[t];
+    uint32_t* hp = hist + ((size_t)b * n_seg + seg) * H_STRIDE + hist_off;
+    for (uint32_t j0 = 0; j0 < cnt; j0 += 64) {
+        const uint32_t j = j0 + lane;
+        bool part = false;
+        uint32_t digit = 0;
+        if (j < cnt) {
+            const uint32_t k = keys[j];
+            part = (k >> pshift) == prefix;
+            digit = (k >> shift) & mask;
+        }
+        unsigned long long active = __ballot(part);
+        while (active) {
+            const int leader = __ffsll((long long)active) - 1;
+            const uint32_t d = __shfl(digit, leader, 64);
+            const unsigned long long same = __ballot(part && digit == d);
+            if ((int)lane == leader) atomicAdd(&hp[d], (uint32_t)__popcll(same));
+            if (digit == d) part = false;
+            active &= ~same;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Per-tile counts once tau is known: selected-for-sure (gt + keys > tau) and ties (== tau).
+// One wave per tile.  grid (ceil(T/4), nbatch).
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_count(const uint32_t* __restrict__ tile_start, const uint32_t* __restrict__ tile_seg,
+                                                 uint32_t T, uint32_t n_seg, const SegState* __restrict__ states,
+                                                 const uint32_t* __restrict__ cand_keys, const uint32_t* __restrict__ cnt_cand,
+                                                 const uint32_t* __restrict__ cnt_gt, uint64_t keys_stride,
+                                                 uint32_t* __restrict__ cnt_sel, uint32_t* __restrict__ cnt_tie)
+{
+    const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b = blockIdx.y, lane = lane_id();
+    if (t >= T) return;
+    const SegState* st = &states[(size_t)b * n_seg + tile_seg[t]];
+    uint32_t sel = 0, tie = 0;
+    if (!st->none) {
+        const uint32_t tau = st->tau;
+        const uint32_t cnt = cnt_cand[(size_t)b * T + t];
+        const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tile_start[t];
+        for (uint32_t j = lane; j < cnt; j += 64) {
+            const uint32_t k = keys[j];
+            sel += (k > tau) ? 1u : 0u;
+            tie += (k == tau) ? 1u : 0u;
+        }
+        sel = wave_sum(sel);
+        tie = wave_sum(tie);
+        if (cnt_gt) sel += cnt_gt[t];
+    }
+    if (lane == 0) { cnt_sel[(size_t)b * T + t] = sel; cnt_tie[(size_t)b * T + t] = tie; }
+}
+
+// ---------------------------------------------------------------------------------------
+// Scan over tiles: global tie prefix, then how many ties each tile takes under its
+// segment's quota, then the output offset of every tile.  grid (1, nbatch), 1024 threads.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void k_scan(const uint32_t* __restrict__ tile_seg, const uint32_t* __restrict__ seg_first_tile,
+                                               uint32_t T, uint32_t n_seg, const SegState* __restrict__ states,
+                                               const uint32_t* __restrict__ cnt_sel, const uint32_t* __restrict__ cnt_tie,
+                                               uint32_t* __restrict__ tie_pre, MutPtrTab out_off, uint32_t expected,
+                                               uint32_t* __restrict__ flags)
+{
+    __shared__ uint32_t wtot[16];
+    const uint32_t b = blockIdx.y;
+    const uint32_t* cs = cnt_sel + (size_t)b * T;
+    const uint32_t* ct = cnt_tie + (size_t)b * T;
+    uint32_t* tp = tie_pre + (size_t)b * (T + 1);
+    uint32_t* off = static_cast<uint32_t*>(out_off.p[b]);
+    const uint32_t C = (T + 1023u) / 1024u;
+    const uint32_t a0 = threadIdx.x * C, a1 = (a0 + C < T) ? a0 + C : T;
+    uint32_t sum = 0;
+    for (uint32_t t = a0; t < a1; ++t) sum += ct[t];
+    uint32_t total;
+    uint32_t run = block_excl_scan<16>(sum, wtot, total);
+    for (uint32_t t = a0; t < a1; ++t) { tp[t] = run; run += ct[t]; }
+    if (threadIdx.x == 0) tp[T] = total;
+    __syncthreads();
+    sum = 0;
+    for (uint32_t t = a0; t < a1; ++t) {
+        const uint32_t seg = tile_seg[t];
+        const uint32_t base = tp[t] - tp[seg_first_tile[seg]];
+        const uint32_t q = states[(size_t)b * n_seg + seg].quota;
+        const uint32_t room = (q > base) ? q - base : 0u;
+        sum += cs[t] + (room < ct[t] ? room : ct[t]);
+    }
+    run = block_excl_scan<16>(sum, wtot, total);
+    for (uint32_t t = a0; t < a1; ++t) {
+        const uint32_t seg = tile_seg[t];
+        const uint32_t base = tp[t] - tp[seg_first_tile[seg]];
+        const uint32_t q = states[(size_t)b * n_seg + seg].quota;
+        const uint32_t room = (q > base) ? q - base : 0u;
+        off[t] = run;
+        run += cs[t] + (room < ct[t] ? room : ct[t]);
+    }
+    if (threadIdx.x == 0) {
+        off[T] = total;
+        if (total != expected) atomicOr(&flags[1], 1u);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// K3: ordered emission.  One thread per bitmap word of the tile: decide every candidate
+// against tau, hand out the tie quota in index order, and write the tile's chosen indices
+// at its offset.  grid (T, nbatch), 128 threads.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(128) void k_emit(const uint32_t* __restrict__ tile_start, const uint32_t* __restrict__ tile_seg,
+                                              const uint32_t* __restrict__ seg_first_tile, uint32_t T, uint32_t n_seg,
+                                              const SegState* __restrict__ states, const uint32_t* __restrict__ gt_bits,
+                                              const uint32_t* __restrict__ cand_bits, const uint32_t* __restrict__ cand_keys,
+                                              uint64_t keys_stride, const uint32_t* __restrict__ tie_pre, PtrTab out_off,
+                                              MutPtrTab out_idx, uint32_t expected, uint32_t* __restrict__ pub_bits)
+{
+    __shared__ uint32_t wtot[2];
+    const uint32_t t = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const uint32_t seg = tile_seg[t];
+    const SegState* st = &states[(size_t)b * n_seg + seg];
+    const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
+    const uint32_t none = st->none, tau = st->tau, quota = st->quota;
+    const uint32_t cw = none ? 0u : cand_bits[((size_t)b * T + t) * TILE_WORDS + tid];
+    const uint32_t gw = (gt_bits && !none) ? gt_bits[(size_t)t * TILE_WORDS + tid] : 0u;
+    uint32_t dummy;
+    const uint32_t cpre = block_excl_scan<2>(__popc(cw), wtot, dummy);
+    const uint32_t* keys = cand_keys + (size_t)b * keys_stride + start;
+    uint32_t selmask = 0, tiemask = 0;
+    {
+        uint32_t m = cw, j = cpre;
+        while (m) {
+            const uint32_t p = __ffs(m) - 1;
+            m &= m - 1;
+            const uint32_t k = keys[j++];
+            if (k > tau) selmask |= 1u << p;
+            else if (k == tau) tiemask |= 1u << p;
+        }
+    }
+    const uint32_t* tp = tie_pre + (size_t)b * (T + 1);
+    const uint32_t tpre = block_excl_scan<2>(__popc(tiemask), wtot, dummy);
+    const uint32_t tbase = tp[t] - tp[seg_first_tile[seg]] + tpre;
+    uint32_t take = (quota > tbase) ? quota - tbase : 0u;
+    uint32_t taken = 0;
+    {
+        uint32_t m = tiemask;
+        while (m && take) { const uint32_t low = m & (0u - m); taken |= low; m ^= low; --take; }
+    }
+    const uint32_t fm = gw | selmask | taken;
+    const uint32_t opre = block_excl_scan<2>(__popc(fm), wtot, dummy);
+    const uint32_t* off = static_cast<const uint32_t*>(out_off.p[b]);
+    uint32_t* out = static_cast<uint32_t*>(out_idx.p[b]);
+    uint32_t o = off[t] + opre;
+    {
+        uint32_t m = fm;
+        while (m) {
+            const uint32_t p = __ffs(m) - 1;
+            m &= m - 1;
+            if (o < expected) out[o] = start + tid * 32u + p;   // never beyond the caller's list
+            ++o;
+        }
+    }
+    if (pub_bits && tid * 32u < len) pub_bits[(start >> 5) + tid] = fm;
+}
+
+// Segmented models: the public bitmap is built from the index list (tiles may start inside a word).
+__global__ __launch_bounds__(256) void k_bits_from_idx(const uint32_t* __restrict__ idx, uint64_t count, uint64_t n,
+                                                       uint32_t* __restrict__ bits)
+{
+    for (uint64_t j = (uint64_t)blockIdx.x * 256 + threadIdx.x; j < count; j += (uint64_t)gridDim.x * 256) {
+        const uint32_t i = idx[j];
+        if (i < n) atomicOr(&bits[i >> 5], 1u << (i & 31u));
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Tile offsets of an ascending index list by binary search.  One thread per tile boundary.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_tile_offsets(const uint32_t* __restrict__ idx, uint64_t count,
+                                                      const uint32_t* __restrict__ tile_start, uint32_t T, uint64_t n,
+                                                      uint32_t* __restrict__ off)
+{
+    const uint32_t t = blockIdx.x * 256 + threadIdx.x;
+    if (t > T) return;
+    const uint64_t target = (t == T) ? n : tile_start[t];
+    uint64_t lo = 0, hi = count;                 // first position with idx >= target
+    while (lo < hi) {
+        const uint64_t mid = (lo + hi) >> 1;
+        if ((uint64_t)idx[mid] < target) lo = mid + 1; else hi = mid;
+    }
+    off[t] = (uint32_t)lo;
+}
+
+// ---------------------------------------------------------------------------------------
+// K5: pack (src_is_w == 0: the workers' updates) and the read half of pull (one shared
+// source).  One block per tile; the tile's slice of every list is a short contiguous run,
+// and the gathered lines of the source are shared by the core and explorer reads.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_gather(PtrTab src, int shared_src, uint32_t nw, uint64_t n,
+                                                  const uint32_t* __restrict__ core_idx, const uint32_t* __restrict__ core_off,
+                                                  PtrTab expl_idx, PtrTab expl_off, MutPtrTab core_val, MutPtrTab expl_val,
+                                                  MutPtrTab scatter_dst)
+{
+    const uint32_t t = blockIdx.x;
+    const uint32_t c0 = core_off[t], c1 = core_off[t + 1];
+    for (uint32_t j = c0 + threadIdx.x; j < c1; j += BLOCK) {
+        const uint32_t i = core_idx[j];
+        if (i >= n) continue;
+        if (shared_src) {
+            const float v = static_cast<const float*>(src.p[0])[i];
+            for (uint32_t q = 0; q < nw; ++q) {
+                static_cast<float*>(core_val.p[q])[j] = v;
+                if (scatter_dst.p[q]) static_cast<float*>(scatter_dst.p[q])[i] = v;
+            }
+        } else {
+            for (uint32_t q = 0; q < nw; ++q)
+                static_cast<float*>(core_val.p[q])[j] = static_cast<const float*>(src.p[q])[i];
+        }
+    }
+    for (uint32_t q = 0; q < nw; ++q) {
+        const uint32_t* eo = static_cast<const uint32_t*>(expl_off.p[q]);
+        const uint32_t* ei = static_cast<const uint32_t*>(expl_idx.p[q]);
+        const float* s = static_cast<const float*>(src.p[shared_src ? 0 : q]);
+        float* ev = static_cast<float*>(expl_val.p[q]);
+        float* sd = static_cast<float*>(scatter_dst.p[q]);
+        const uint32_t e0 = eo[t], e1 = eo[t + 1];
+        for (uint32_t j = e0 + threadIdx.x; j < e1; j += BLOCK) {
+            const uint32_t i = ei[j];
+            if (i >= n) continue;
+            const float v = s[i];
+            ev[j] = v;
+            if (sd) sd[i] = v;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// K6: merge.  One block per tile of the global model.  Contributions are summed in LDS in
+// worker order (core first: every worker holds it; then each worker's explorer slice),
+// one fused multiply-add applies the sum, and the tile is streamed back.  No atomics.
+// ---------------------------------------------------------------------------------------
+constexpr int MERGE_STAGE = 2048;
+
+__global__ __launch_bounds__(BLOCK) void k_merge(float* __restrict__ w, float lr, uint32_t nw,
+                                                 const uint32_t* __restrict__ tile_start,
+                                                 const uint32_t* __restrict__ core_idx, const uint32_t* __restrict__ core_off,
+                                                 PtrTab core_val, PtrTab expl_idx, PtrTab expl_off, PtrTab expl_val,
+                                                 int vec_ok)
+{
+    __shared__ float acc[TILE];
+    __shared__ uint8_t hit[TILE];
+    __shared__ uint16_t spos[MERGE_STAGE];
+    __shared__ float sval[MERGE_STAGE];
+    __shared__ uint32_t elo[MAXW], epre[MAXW + 1];
+    const uint32_t t = blockIdx.x;
+    const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
+    const bool vec = vec_ok && len == TILE && (start & 3u) == 0;
+    // the tile of w is requested first so that its latency overlaps everything below
+    float wv[EPT];
+    if (vec) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float4 v = *reinterpret_cast<const float4*>(w + (size_t)start + r * 1024 + threadIdx.x * 4);
+            wv[4 * r + 0] = v.x; wv[4 * r + 1] = v.y; wv[4 * r + 2] = v.z; wv[4 * r + 3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            const uint32_t e = elem_scl(j);
+            wv[j] = (e < len) ? w[(size_t)start + e] : 0.0f;
+        }
+    }
+    for (uint32_t e = threadIdx.x; e < TILE; e += BLOCK) { acc[e] = 0.0f; hit[e] = 0; }
+    if (threadIdx.x < nw) {
+        const uint32_t* eo = static_cast<const uint32_t*>(expl_off.p[threadIdx.x]);
+        elo[threadIdx.x] = eo[t];
+        epre[threadIdx.x] = eo[t + 1] - eo[t];      // counts; turned into a prefix below
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (uint32_t q = 0; q < nw; ++q) { const uint32_t c = epre[q]; epre[q] = run; run += c; }
+        epre[nw] = run;
+    }
+    // core: every worker contributes, in worker order
+    {
+        const uint32_t c0 = core_off[t], c1 = core_off[t + 1];
+        for (uint32_t j = c0 + threadIdx.x; j < c1; j += BLOCK) {
+            const uint32_t pos = core_idx[j] - start;
+            float a = 0.0f;
+            for (uint32_t q = 0; q < nw; ++q) a = a + static_cast<const float*>(core_val.p[q])[j];
+            if (pos < len) { acc[pos] = a; hit[pos] = 1; }
+        }
+    }
+    __syncthreads();
+    // explorers: staged through LDS in chunks, applied one worker at a time
+    const uint32_t E = epre[nw];
+    for (uint32_t cb = 0; cb < E; cb += MERGE_STAGE) {
+        const uint32_t cn = (E - cb < (uint32_t)MERGE_STAGE) ? E - cb : (uint32_t)MERGE_STAGE;
+        for (uint32_t x = threadIdx.x; x < cn; x += BLOCK) {
+            const uint32_t v = cb + x;
+            uint32_t q = 0;
+            while (q + 1 < nw && epre[q + 1] <= v) ++q;
+            const uint32_t j = elo[q] + (v - epre[q]);
+            const uint32_t pos = static_cast<const uint32_t*>(expl_idx.p[q])[j] - start;
+            spos[x] = (pos < len) ? (uint16_t)pos : (uint16_t)0xFFFF;
+            sval[x] = static_cast<const float*>(expl_val.p[q])[j];
+        }
+        __syncthreads();
+        for (uint32_t q = 0; q < nw; ++q) {
+            const uint32_t lo = (epre[q] > cb) ? epre[q] - cb : 0u;
+            const uint32_t hi_abs = epre[q + 1];
+            if (hi_abs <= cb) continue;
+            const uint32_t hi = (hi_abs - cb < cn) ? hi_abs - cb : cn;
+            if (lo >= hi) continue;
+            for (uint32_t x = lo + threadIdx.x; x < hi; x += BLOCK) {
+                const uint32_t pos = spos[x];
+                if (pos != 0xFFFFu) { acc[pos] = acc[pos] + sval[x]; hit[pos] = 1; }
+            }
+            __syncthreads();
+        }
+        __syncthreads();
+    }
+    // apply and stream the tile back
+    if (vec) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float o[4];
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                const uint32_t e = elem_vec(4 * r + cc);
+                o[cc] = hit[e] ? __builtin_fmaf(-lr, acc[e], wv[4 * r + cc]) : wv[4 * r + cc];
+            }
+            *reinterpret_cast<float4*>(w + (size_t)start + r * 1024 + threadIdx.x * 4) = make_float4(o[0], o[1], o[2], o[3]);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            const uint32_t e = elem_scl(j);
+            if (e < len && hit[e]) w[(size_t)start + e] = __builtin_fmaf(-lr, acc[e], wv[j]);
+        }
+    }
+}
+
+// Raw random words of the explorer for indices i0 .. i0+count-1.
+__global__ __launch_bounds__(256) void k_debug_philox(uint32_t seed_lo, uint32_t seed_hi, uint32_t it_lo, uint32_t it_hi,
+                                                      uint32_t worker, uint32_t i0, uint64_t count, uint32_t* __restrict__ out)
+{
+    for (uint64_t j = (uint64_t)blockIdx.x * 256 + threadIdx.x; j < count; j += (uint64_t)gridDim.x * 256) {
+        const uint32_t i = i0 + (uint32_t)j;
+        uint32_t r[4];
+        philox4x32_10(i >> 2, worker, it_lo, it_hi, seed_lo, seed_hi, r);
+        out[j] = r[i & 3u];
+    }
+}
+
+}  // namespace slimdp

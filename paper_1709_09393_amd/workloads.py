@@ -119,7 +119,9 @@ class Workload:
 
     def scaled(self, n: int, **kw) -> "Workload":
         """Same recipe at another length (parity-test sizes the oracle finishes in seconds)."""
-        return replace(self, n=int(n), name=f"{self.name}@{n}", seg_off=None, **kw)
+        params = dict(n=int(n), name=f"{self.name}@{n}", seg_off=None)
+        params.update(kw)
+        return replace(self, **params)
 
 
 TINY = Workload("tiny", 1_000_000, 4, "normal", 0.05, 1e-3)

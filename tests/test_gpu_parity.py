@@ -1,0 +1,337 @@
+"""GPU parity: every call of the C ABI against the CPU oracle on the same seeded inputs.
+
+Bar: bit-exact scores, index sets, tile offsets, packs, pulls and random words; merged
+binary32 parameters within 1e-6 relative (+1e-12) of the oracle and of the binary64 truth
+(they are in fact expected to be bit-identical, and the test reports if they are not).
+Sizes span several 4096-parameter tiles and a ragged tail.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1709_09393_amd import binding, workloads
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def dev():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU test selected but torch.cuda.is_available() is False")
+    return torch.device("cuda:0")
+
+
+def to_dev(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(a).to(dev())
+
+
+def u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def f32bits(a):
+    return np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+
+
+def host_tile_offsets(idx, tile_start):
+    return np.searchsorted(idx.astype(np.int64), tile_start.astype(np.int64), side="left").astype(np.uint32)
+
+
+def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, check=True):
+    """One reselect iteration on the GPU and in the oracle; returns both results."""
+    seg_off = [int(x) for x in wl.segment_offsets()]
+    ks, ms = [int(x) for x in wl.k_seg()], [int(x) for x in wl.m_seg()]
+    w_h = wl.weights() if w_h is None else w_h
+    g_h = wl.gradients(iteration)
+    own = sd is None
+    if own:
+        sd = binding.SlimDP(wl.n, wl.W, seg_off=seg_off, seed=workloads.EXPLORE_SEED)
+    sd.set_option("explore_force_fallback", 1 if force_fallback else 0)
+    w = to_dev(w_h)
+    g = [to_dev(x) for x in g_h]
+    S = sd.score(w, g, wl.c)
+    core_idx, core_bits, core_off, epoch = sd.select_core(S, ks, reuse_histogram=True)
+    expl_idx, expl_off = sd.sample_explore(core_bits, ks, iteration, ms, 0, wl.W)
+    core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)
+    sd.merge(w, wl.lr, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
+    core_out, expl_out = sd.pull(w, epoch, core_idx, core_off, expl_idx, expl_off)
+    sd.synchronize()
+    got = dict(S=S.cpu().numpy(), core_idx=u32(core_idx), core_bits=u32(core_bits), core_off=u32(core_off),
+               expl_idx=[u32(x) for x in expl_idx], expl_off=[u32(x) for x in expl_off],
+               core_val=[x.cpu().numpy() for x in core_val], expl_val=[x.cpu().numpy() for x in expl_val],
+               w=w.cpu().numpy(), core_out=[x.cpu().numpy() for x in core_out],
+               expl_out=[x.cpu().numpy() for x in expl_out], tile_start=sd.tile_starts())
+    if own:
+        sd.close()
+    if not check:
+        return got, None
+    so = None if wl.n_seg == 1 and wl.seg_off is None else seg_off
+    S_o = oracle.score(w_h, g_h, wl.c)
+    core_o = oracle.select_core(S_o, ks, so)
+    ei_o = [oracle.sample_explore(wl.n, core_o, workloads.EXPLORE_SEED, iteration, q, ms, so) for q in range(wl.W)]
+    packs = [oracle.pack(g_h[q], core_o, ei_o[q]) for q in range(wl.W)]
+    w_o = oracle.merge(w_h, wl.lr, core_o, [p[0] for p in packs], ei_o, [p[1] for p in packs])
+    w_t = oracle.merge_f64(w_h, wl.lr, core_o, [p[0] for p in packs], ei_o, [p[1] for p in packs])
+    want = dict(S=S_o, core_idx=core_o, expl_idx=ei_o, packs=packs, w=w_o, w_truth=w_t)
+    return got, want
+
+
+def assert_iteration_matches(wl, got, want):
+    ts = got["tile_start"]
+    assert np.array_equal(f32bits(got["S"]), f32bits(want["S"])), "score bits"
+    assert np.array_equal(got["core_idx"], want["core_idx"]), "core index set"
+    assert np.array_equal(got["core_bits"], oracle.core_bits(wl.n, want["core_idx"])), "core bitmap"
+    assert np.array_equal(got["core_off"], host_tile_offsets(want["core_idx"], ts)), "core tile offsets"
+    for q in range(wl.W):
+        assert np.array_equal(got["expl_idx"][q], want["expl_idx"][q]), "explorer %d" % q
+        assert np.array_equal(got["expl_off"][q], host_tile_offsets(want["expl_idx"][q], ts))
+        assert np.array_equal(f32bits(got["core_val"][q]), f32bits(want["packs"][q][0])), "core_val %d" % q
+        assert np.array_equal(f32bits(got["expl_val"][q]), f32bits(want["packs"][q][1])), "expl_val %d" % q
+    w_g, w_o, w_t = got["w"], want["w"], want["w_truth"]
+    assert np.all(np.abs(w_g - w_o) <= 1e-6 * np.abs(w_o) + 1e-12), "merge vs oracle"
+    assert np.all(np.abs(w_g.astype(np.float64) - w_t) <= 1e-6 * np.abs(w_t) + 1e-12), "merge vs binary64"
+    nbad = int((f32bits(w_g) != f32bits(w_o)).sum())
+    assert nbad == 0, "merged parameters differ from the oracle in %d places (within tolerance)" % nbad
+    for q in range(wl.W):
+        assert np.array_equal(f32bits(got["core_out"][q]), f32bits(w_o[want["core_idx"]])), "pull core"
+        assert np.array_equal(f32bits(got["expl_out"][q]), f32bits(w_o[want["expl_idx"][q]])), "pull explorer"
+
+
+# ----------------------------------------------------------------------------------------
+def test_philox_words_match_oracle():
+    sd = binding.SlimDP(100_000, 2, seed=0x299F31D0A4093822)
+    for it, worker, i0, cnt in [(0, 0, 0, 10_000), (2 ** 33 + 7, 5, 3, 4099), (1, 31, 99_000, 1000)]:
+        got = u32(sd.debug_philox(it, worker, i0, cnt))
+        assert np.array_equal(got, oracle.explore_words(0x299F31D0A4093822, it, worker, i0, cnt))
+    sd.close()
+
+
+@pytest.mark.parametrize("n", [1, 5, 4096, 4097, 50_001, 200_003])
+def test_flat_iteration_sizes(n):
+    wl = workloads.TINY.scaled(n)
+    got, want = run_iteration(wl)
+    assert_iteration_matches(wl, got, want)
+
+
+@pytest.mark.parametrize("W", [1, 2, 3, 8, 16])
+def test_worker_counts(W):
+    wl = workloads.TINY.scaled(30_011, W=W)
+    got, want = run_iteration(wl)
+    assert_iteration_matches(wl, got, want)
+
+
+def test_tiny_config_full_size():
+    wl = workloads.TINY
+    got, want = run_iteration(wl)
+    assert_iteration_matches(wl, got, want)
+
+
+def test_segmented_googlenet_recipe_scaled():
+    wl = workloads.GOOGLENET.scaled(700_001)
+    got, want = run_iteration(wl)
+    assert_iteration_matches(wl, got, want)
+
+
+def test_segments_with_awkward_boundaries():
+    n = 30_000
+    wl = workloads.TINY.scaled(n, seg_off=(0, 1, 18, 4114, 4115, 12_307, 29_999, n), n_seg=7)
+    got, want = run_iteration(wl)
+    assert_iteration_matches(wl, got, want)
+
+
+def test_tie_heavy_stress_recipe_scaled():
+    wl = workloads.STRESS.scaled(300_007)
+    got, want = run_iteration(wl)
+    assert_iteration_matches(wl, got, want)
+
+
+def test_explore_wide_bound_rerun_gives_the_same_sets():
+    wl = workloads.TINY.scaled(100_003)
+    got, want = run_iteration(wl, force_fallback=True)
+    assert_iteration_matches(wl, got, want)
+
+
+@pytest.mark.parametrize("core_pct,explore_pct", [(0, 2), (10, 0), (100, 0), (0, 100), (50, 100), (0, 0)])
+def test_degenerate_fractions(core_pct, explore_pct):
+    # beta = 0 (pure random sampling), beta = alpha (no exploration), k = n (dense update),
+    # explorer = everything outside the core
+    wl = workloads.TINY.scaled(20_005, core_pct=core_pct, explore_pct=explore_pct)
+    got, want = run_iteration(wl)
+    assert_iteration_matches(wl, got, want)
+
+
+def test_select_core_on_constructed_scores():
+    n = 70_001
+    sd = binding.SlimDP(n, 1)
+    rng = np.random.default_rng(0)
+    cases = {
+        "all_equal": np.full(n, 0.125, np.float32),
+        "two_values": rng.integers(0, 2, n).astype(np.float32),
+        "few_levels": (rng.integers(0, 37, n) / 8.0).astype(np.float32),
+        "zeros_and_denormals": (rng.integers(0, 3, n) * np.float32(1e-45)).astype(np.float32),
+        "with_inf_nan": np.abs(rng.standard_normal(n)).astype(np.float32),
+        "same_top_bits": (np.float32(1.0) + rng.integers(0, 64, n).astype(np.float32) * np.float32(2.0 ** -23)),
+    }
+    cases["with_inf_nan"][::1000] = np.inf
+    cases["with_inf_nan"][5::1000] = np.array([0x7FC00000], np.uint32).view(np.float32)[0]
+    for name, S_h in cases.items():
+        S = to_dev(S_h)
+        for k in [0, 1, n // 10, n // 2, n - 1, n]:
+            core_idx, core_bits, core_off, _ = sd.select_core(S, [k])
+            sd.synchronize()
+            want = oracle.select_core(S_h, k)
+            assert np.array_equal(u32(core_idx), want), (name, k)
+            assert np.array_equal(u32(core_bits), oracle.core_bits(n, want)), (name, k)
+    sd.close()
+
+
+def test_merge_hand_built_collisions_and_tile_offsets():
+    n = 10_000
+    sd = binding.SlimDP(n, 3)
+    rng = np.random.default_rng(1)
+    w_h = rng.standard_normal(n).astype(np.float32)
+    w_h[7] = -0.0
+    S = to_dev(np.abs(w_h))
+    core_idx, core_bits, core_off, epoch = sd.select_core(S, [50])
+    core_h = u32(core_idx)
+    rest = np.setdiff1d(np.arange(n, dtype=np.uint32), core_h)
+    # three workers, overlapping explorer lists: index rest[10] is sent by all, with values
+    # whose sum depends on the order
+    ei = [np.sort(np.concatenate([rest[[10, 500, 4100]], rest[6000:6100]])).astype(np.uint32),
+          np.sort(np.concatenate([rest[[10, 4100]], rest[6050:6200]])).astype(np.uint32),
+          np.sort(rest[[10, 11, 9000]]).astype(np.uint32)]
+    ev = [rng.standard_normal(x.size).astype(np.float32) for x in ei]
+    ev[0][np.searchsorted(ei[0], rest[10])] = 1e8
+    ev[1][np.searchsorted(ei[1], rest[10])] = -1e8
+    ev[2][np.searchsorted(ei[2], rest[10])] = 1.0
+    cv = [rng.standard_normal(50).astype(np.float32) for _ in range(3)]
+    d_ei = [to_dev(x) for x in ei]
+    d_eo = [sd.tile_offsets(x) for x in d_ei]
+    ts = sd.tile_starts()
+    for q in range(3):
+        assert np.array_equal(u32(d_eo[q]), host_tile_offsets(ei[q], ts))
+    w = to_dev(w_h)
+    sd.merge(w, 0.5, epoch, core_idx, core_off, [to_dev(x) for x in cv], d_ei, d_eo, [to_dev(x) for x in ev])
+    sd.synchronize()
+    want = oracle.merge(w_h, 0.5, core_h, cv, ei, ev)
+    assert np.array_equal(f32bits(w.cpu().numpy()), f32bits(want))
+    assert want[rest[10]] == np.float32(w_h[rest[10]] - 0.5)       # (1e8 + -1e8) + 1
+    sd.close()
+
+
+def test_pull_overwrites_local_models_only_at_the_communication_set():
+    wl = workloads.TINY.scaled(25_003, W=2)
+    seg_off = [0, wl.n]
+    sd = binding.SlimDP(wl.n, wl.W)
+    w_h = wl.weights()
+    g_h = wl.gradients(0)
+    w = to_dev(w_h)
+    g = [to_dev(x) for x in g_h]
+    S = sd.score(w, g, 1.0)
+    core_idx, core_bits, core_off, epoch = sd.select_core(S, [wl.k], reuse_histogram=True)
+    expl_idx, expl_off = sd.sample_explore(core_bits, [wl.k], 3, [wl.m], 0, 2)
+    rng = np.random.default_rng(2)
+    wl_h = [rng.standard_normal(wl.n).astype(np.float32) for _ in range(2)]
+    w_local = [to_dev(wl_h[0]), None]
+    core_out, expl_out = sd.pull(w, epoch, core_idx, core_off, expl_idx, expl_off, w_local=w_local)
+    sd.synchronize()
+    ci = u32(core_idx)
+    for q in range(2):
+        eq = u32(expl_idx[q])
+        co, eo, new_local = oracle.pull(w_h, ci, eq, wl_h[q] if q == 0 else None)
+        assert np.array_equal(f32bits(core_out[q].cpu().numpy()), f32bits(co))
+        assert np.array_equal(f32bits(expl_out[q].cpu().numpy()), f32bits(eo))
+        if q == 0:
+            assert np.array_equal(f32bits(w_local[0].cpu().numpy()), f32bits(new_local))
+    sd.close()
+    assert seg_off[-1] == wl.n
+
+
+def test_same_call_twice_gives_identical_bits_and_workers_differ():
+    wl = workloads.TINY.scaled(60_001)
+    a, _ = run_iteration(wl, check=False)
+    b, _ = run_iteration(wl, check=False)
+    for key in ["core_idx", "core_bits", "core_off"]:
+        assert np.array_equal(a[key], b[key])
+    for q in range(wl.W):
+        assert np.array_equal(a["expl_idx"][q], b["expl_idx"][q])
+    assert np.array_equal(f32bits(a["w"]), f32bits(b["w"]))
+    assert not np.array_equal(a["expl_idx"][0], a["expl_idx"][1])
+    c, _ = run_iteration(wl, iteration=1, check=False)
+    assert not np.array_equal(a["expl_idx"][0], c["expl_idx"][0])
+
+
+def test_multi_iteration_loop_scaled():
+    # 20 iterations, core every 5, explorer every iteration, model carried along
+    wl = workloads.LOOP.scaled(40_009, W=4)
+    sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
+    w_h = wl.weights()
+    w = to_dev(w_h)
+    k, m = wl.k, wl.m
+    core_o = None
+    for t in range(wl.iterations):
+        g_h = wl.gradients(t)
+        g = [to_dev(x) for x in g_h]
+        if t % wl.reselect_every == 0:
+            S = sd.score(w, g, wl.c)
+            core_idx, core_bits, core_off, epoch = sd.select_core(S, [k], reuse_histogram=True)
+            core_o = oracle.select_core(oracle.score(w_h, g_h, wl.c), k)
+            assert np.array_equal(u32(core_idx), core_o), t
+        expl_idx, expl_off = sd.sample_explore(core_bits, [k], t, [m], 0, wl.W)
+        core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)
+        sd.merge(w, wl.lr, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
+        ei_o = [oracle.sample_explore(wl.n, core_o, workloads.EXPLORE_SEED, t, q, m) for q in range(wl.W)]
+        for q in range(wl.W):
+            assert np.array_equal(u32(expl_idx[q]), ei_o[q]), (t, q)
+        packs = [oracle.pack(g_h[q], core_o, ei_o[q]) for q in range(wl.W)]
+        w_h = oracle.merge(w_h, wl.lr, core_o, [p[0] for p in packs], ei_o, [p[1] for p in packs])
+    sd.synchronize()
+    w_g = w.cpu().numpy()
+    assert np.all(np.abs(w_g - w_h) <= 1e-6 * np.abs(w_h) + 1e-12)
+    assert np.array_equal(f32bits(w_g), f32bits(w_h))
+    sd.close()
+
+
+def test_error_paths_launch_nothing():
+    n = 10_000
+    sd = binding.SlimDP(n, 2)
+    S = to_dev(np.abs(np.random.default_rng(0).standard_normal(n)).astype(np.float32))
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.select_core(S, [n + 1])
+    assert e.value.code == binding.ERR_OUT_OF_RANGE
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.select_core(S, [10], reuse_histogram=True)          # no slimdp_score before it
+    assert e.value.code == binding.ERR_INVALID_ARG
+    core_idx, core_bits, core_off, epoch = sd.select_core(S, [100])
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.sample_explore(core_bits, [100], 0, [n - 99])
+    assert e.value.code == binding.ERR_OUT_OF_RANGE
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.sample_explore(core_bits, [100], 0, [5], 0, 3)       # more workers than the context holds
+    assert e.value.code == binding.ERR_INVALID_ARG
+    expl_idx, expl_off = sd.sample_explore(core_bits, [100], 0, [5])
+    g = [S]
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch + 1)
+    assert e.value.code == binding.ERR_STALE_CORE
+    core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)
+    sd.select_core(S, [100])                                    # new core: old packs are stale
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.merge(S, 0.1, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
+    assert e.value.code == binding.ERR_STALE_CORE
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.score(S, [S], -1.0)
+    assert e.value.code == binding.ERR_INVALID_ARG
+    sd.synchronize()
+    # a bitmap with more core bits than k_seg claims: the device reports the shortfall
+    full = to_dev(np.full((n + 31) // 32, 0xFFFFFFFF, np.uint32))
+    sd.sample_explore(full, [0], 0, [10])
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.synchronize()
+    assert e.value.code == binding.ERR_DEVICE_STATUS
+    sd.synchronize()                                            # status is cleared once reported
+    sd.close()
