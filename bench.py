@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Benchmark of the Slim-DP communication-set path on one MI355X.
+
+A step is one full reselect iteration of the hot path on the VGG-16-sized flat model
+(138,357,544 binary32 parameters, W = 8 logical workers, core 10 %, explorer 2 % of the
+rest): score -> select core -> sample W explorers -> pack W workers -> merge.  Inputs are
+seeded synthetic vectors already resident in HBM when the timed region starts.
+
+Prints ONE JSON line: whole-job throughput in Gparam/s (n / step time), the roofline of the
+dominant kernel measured with events on the library's stream, per-stage times, and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
+STAGES = ["score", "select_core", "sample_explore", "pack", "merge"]
+
+
+def stage_bytes(n: int, W: int, k: int, m: int) -> dict:
+    """Algorithmic bytes of every stage (stream model: a sorted gather at >= 10 % density
+    touches nearly every line, so extracting from an update vector costs reading it)."""
+    return {
+        "score": 4 * n * (1 + W) + 4 * n,
+        "select_core": 2 * 4 * n + 4 * k + n // 8,
+        "sample_explore": W * (n // 8 + 4 * m),
+        "pack": W * (4 * n + n // 8 + 4 * m + 4 * (k + m)),
+        "merge": 4 * n + 4 * n + 4 * W * (k + m) + 4 * k + 4 * W * m,
+    }
+
+
+def cpu_baseline(sample_n: int) -> dict:
+    """The oracle as it stands, single thread, one iteration on a bounded sample."""
+    import oracle
+    from paper_1709_09393_amd import workloads
+    wl = workloads.VGG16.scaled(sample_n)
+    w = wl.weights()
+    g = wl.gradients(0)
+    k, m = wl.k, wl.m
+    oracle.lib()
+    t0 = time.perf_counter()
+    S = oracle.score(w, g, wl.c)
+    core = oracle.select_core(S, k)
+    ei = [oracle.sample_explore(wl.n, core, workloads.EXPLORE_SEED, 0, q, m) for q in range(wl.W)]
+    packs = [oracle.pack(g[q], core, ei[q]) for q in range(wl.W)]
+    oracle.merge(w, wl.lr, core, [p[0] for p in packs], ei, [p[1] for p in packs])
+    dt = time.perf_counter() - t0
+    return {"value": wl.n / dt / 1e9, "unit": "Gparam/s", "cores": 1, "kind": "oracle",
+            "sample": "one full iteration of the same recipe at n=%d, W=%d (k=%d, m=%d), %.2f s" % (wl.n, wl.W, k, m, dt)}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--n", type=int, default=0, help="override the parameter count (profiling runs)")
+    ap.add_argument("--cpu-sample", type=int, default=8_000_000, help="oracle sample size; 0 skips the CPU leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (W logical workers share it); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_1709_09393_amd import binding, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = workloads.VGG16 if not args.n else workloads.VGG16.scaled(args.n)
+    n, W, k, m = wl.n, wl.W, wl.k, wl.m
+    sd = binding.SlimDP(n, W, seed=workloads.EXPLORE_SEED)
+
+    w = torch.from_numpy(wl.weights()).to(dev)
+    g = [torch.from_numpy(wl.gradient(0, q)).to(dev) for q in range(W)]
+    i32, f32 = torch.int32, torch.float32
+    S = torch.empty(n, dtype=f32, device=dev)
+    core_idx = torch.empty(k, dtype=i32, device=dev)
+    core_bits = torch.empty((n + 31) // 32, dtype=i32, device=dev)
+    core_off = torch.empty(sd.T + 1, dtype=i32, device=dev)
+    expl_idx = [torch.empty(m, dtype=i32, device=dev) for _ in range(W)]
+    expl_off = [torch.empty(sd.T + 1, dtype=i32, device=dev) for _ in range(W)]
+    core_val = [torch.empty(k, dtype=f32, device=dev) for _ in range(W)]
+    expl_val = [torch.empty(m, dtype=f32, device=dev) for _ in range(W)]
+
+    def step(t: int, ev=None) -> None:
+        def mark(j):
+            if ev is not None:
+                ev[j].record()
+        mark(0)
+        sd.score(w, g, wl.c, out=S)
+        mark(1)
+        _, _, _, epoch = sd.select_core(S, [k], reuse_histogram=True, core_idx=core_idx, core_bits=core_bits,
+                                        core_off=core_off)
+        mark(2)
+        sd.sample_explore(core_bits, [k], t, [m], 0, W, expl_idx=expl_idx, expl_off=expl_off)
+        mark(3)
+        sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch, core_val=core_val, expl_val=expl_val)
+        mark(4)
+        sd.merge(w, wl.lr, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
+        mark(5)
+
+    for t in range(args.warmup):
+        step(t)
+    sd.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.steps):
+        step(args.warmup + t, events[t])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sd.synchronize()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    stage_ms = {s: float(np.mean([events[t][j].elapsed_time(events[t][j + 1]) for t in range(args.steps)]))
+                for j, s in enumerate(STAGES)}
+    sb = stage_bytes(n, W, k, m)
+    total_bytes = sum(sb.values())
+    value = n / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel: k_score (one launch per step: reads w and the W updates, writes the score)
+    score_gbs = sb["score"] / (stage_ms["score"] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "k_score", "achieved": score_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": score_gbs / HBM_PEAK_GBS, "traffic": None,
+                "algorithmic_bytes_per_launch": sb["score"], "avg_launch_ms": stage_ms["score"]}
+
+    out = {
+        "metric": "Gparam/s score+select+pack+merge, % of HBM peak GB/s, 138M params, W=8",
+        "value": value, "unit": "Gparam/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "n": n, "W": W, "k": k, "m": m, "core_pct": wl.core_pct,
+                   "explore_pct": wl.explore_pct, "c": wl.c, "lr": wl.lr, "tile": binding.TILE},
+        "hbm_frac_whole_step": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "algorithmic_bytes_per_step": total_bytes,
+        "stage_ms": stage_ms,
+        "stage_hbm_frac": {s: sb[s] / (stage_ms[s] * 1e-3) / 1e9 / HBM_PEAK_GBS for s in STAGES},
+        "roofline": roofline,
+    }
+    sd.close()
+    del w, g, S
+    if args.cpu_sample > 0:
+        out["cpu_baseline"] = cpu_baseline(args.cpu_sample)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
