@@ -103,6 +103,7 @@ def main() -> int:
             if ev is not None:
                 ev[j].record()
         mark(0)
+        sd.explore_hint([k], t, [m], 0, W)      # host-only: the draw rides inside the scoring kernel
         sd.score(w, g, wl.c, out=S)
         mark(1)
         _, _, _, epoch = sd.select_core(S, [k], reuse_histogram=True, core_idx=core_idx, core_bits=core_bits,

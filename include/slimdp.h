@@ -146,6 +146,18 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
                           const uint64_t* m_seg, uint32_t* const* expl_idx,
                           uint32_t* const* expl_off);
 
+/* Optional announcement: the next slimdp_score on this context is to draw, while it
+ * streams the model, the explorer candidates that the following
+ * slimdp_sample_explore(ctx, core_bits, k_seg, worker0, n_workers, iteration, m_seg, ...)
+ * will need (the arguments must then be identical, else the draw is simply redone).  The
+ * random words do not depend on the core, so their generation -- the only step of the path
+ * bound by integer arithmetic rather than by memory -- can hide under the scoring pass, as
+ * the paper notes for its worker side (section 3.5, "Time Efficiency").  Purely a
+ * performance hint: results are bit-identical with or without it.  Host arrays as in
+ * slimdp_sample_explore; k_seg is the core size the coming slimdp_select_core will use. */
+int slimdp_explore_hint(slimdp_ctx* ctx, const uint64_t* k_seg, uint32_t worker0, uint32_t n_workers,
+                        uint64_t iteration, const uint64_t* m_seg);
+
 /* Tile offsets of any ascending index list (for lists that did not come from the two
  * calls above).  idx [dev, count] ascending, all < n; off [dev, T+1]. */
 int slimdp_tile_offsets(slimdp_ctx* ctx, const uint32_t* idx, uint64_t count, uint32_t* off);

@@ -30,7 +30,7 @@ SELECT_REUSE_HISTOGRAM = 1
 EXPORTS = [
     "slimdp_create", "slimdp_destroy", "slimdp_workspace_bytes", "slimdp_num_tiles",
     "slimdp_tile_starts", "slimdp_last_error", "slimdp_synchronize", "slimdp_set_option",
-    "slimdp_score", "slimdp_select_core", "slimdp_sample_explore", "slimdp_tile_offsets",
+    "slimdp_score", "slimdp_select_core", "slimdp_sample_explore", "slimdp_explore_hint", "slimdp_tile_offsets",
     "slimdp_pack", "slimdp_merge", "slimdp_pull", "slimdp_debug_philox",
 ]
 
@@ -78,6 +78,8 @@ def load() -> C.CDLL:
     L.slimdp_select_core.restype = C.c_int
     L.slimdp_sample_explore.argtypes = [_vp, _vp, _u64p, C.c_uint32, C.c_uint32, C.c_uint64, _u64p, _vpp, _vpp]
     L.slimdp_sample_explore.restype = C.c_int
+    L.slimdp_explore_hint.argtypes = [_vp, _u64p, C.c_uint32, C.c_uint32, C.c_uint64, _u64p]
+    L.slimdp_explore_hint.restype = C.c_int
     L.slimdp_tile_offsets.argtypes = [_vp, _vp, C.c_uint64, _vp]
     L.slimdp_tile_offsets.restype = C.c_int
     L.slimdp_pack.argtypes = [_vp, C.c_uint32, _vpp, _vp, _vp, C.c_uint64, _vpp, _vpp, _u64p, _vpp, _vpp, C.c_uint64]
@@ -222,6 +224,11 @@ class SlimDP:
         self._check(self._L.slimdp_sample_explore(self._h, _ptr(core_bits), _u64arr(ks), worker0, n_workers,
                                                   int(iteration), _u64arr(ms), _table(expl_idx), _table(expl_off)))
         return expl_idx, expl_off
+
+    def explore_hint(self, k_seg, iteration: int, m_seg, worker0: int = 0, n_workers: int = 1) -> None:
+        ks = [int(k_seg)] if np.isscalar(k_seg) else [int(x) for x in k_seg]
+        ms = [int(m_seg)] if np.isscalar(m_seg) else [int(x) for x in m_seg]
+        self._check(self._L.slimdp_explore_hint(self._h, _u64arr(ks), worker0, n_workers, int(iteration), _u64arr(ms)))
 
     def tile_offsets(self, idx, out=None):
         if out is None:

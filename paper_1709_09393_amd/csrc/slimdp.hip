@@ -104,6 +104,20 @@ struct slimdp_ctx {
     bool hist_pending = false;
     const float* hist_score = nullptr;
     int64_t opt_force_fallback = 0;
+    // explorer draw announced by slimdp_explore_hint (hint) / already drawn inside slimdp_score (pre)
+    struct Draw {
+        bool valid = false;
+        uint64_t iteration = 0;
+        uint32_t worker0 = 0, n_workers = 0;
+        std::vector<uint64_t> k_seg, m_seg;
+        bool same(uint64_t it, uint32_t w0, uint32_t nw, const uint64_t* k, const uint64_t* m, uint32_t n_seg) const
+        {
+            if (!valid || it != iteration || w0 != worker0 || nw != n_workers) return false;
+            for (uint32_t s = 0; s < n_seg; ++s)
+                if (k[s] != k_seg[s] || m[s] != m_seg[s]) return false;
+            return true;
+        }
+    } hint, pre;
     std::string err;
 };
 
@@ -176,7 +190,7 @@ int fill(slimdp_ctx* c, uint32_t* p, uint64_t count, uint32_t v)
     return SLIMDP_OK;
 }
 
-int init_states(slimdp_ctx* c, SegState* st, const std::vector<SegInit>& init, uint32_t nbatch, int core)
+int init_states(slimdp_ctx* c, SegState* st, const std::vector<SegInit>& init, uint32_t nbatch, int core, uint32_t has_void)
 {
     for (uint32_t s0 = 0; s0 < c->n_seg; s0 += INIT_CHUNK) {
         SegInitChunk chunk;
@@ -185,7 +199,7 @@ int init_states(slimdp_ctx* c, SegState* st, const std::vector<SegInit>& init, u
         for (uint32_t j = 0; j < cnt; ++j) chunk.s[j] = init[s0 + j];
         const uint32_t threads = cnt * nbatch;
         hipLaunchKernelGGL(k_init_state, dim3((threads + 255) / 256), dim3(256), 0, c->stream, st, chunk, s0, cnt,
-                           c->n_seg, nbatch, core);
+                           c->n_seg, nbatch, core, has_void);
         SLIMDP_LAUNCHED(c, "k_init_state");
     }
     return SLIMDP_OK;
@@ -229,7 +243,7 @@ int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* his
     SLIMDP_LAUNCHED(c, "k_scan");
     PtrTab off_ro;
     for (int q = 0; q < MAXW; ++q) off_ro.p[q] = out_off.p[q];
-    hipLaunchKernelGGL(k_emit, dim3(T, nbatch), dim3(128), 0, c->stream, c->d_tile_start, c->d_tile_seg,
+    hipLaunchKernelGGL(k_emit, wave_grid, dim3(BLOCK), 0, c->stream, c->d_tile_start, c->d_tile_seg,
                        c->d_seg_first_tile, T, S, st, gt_bits, cand_bits, cand_keys, keys_stride, tie_pre, off_ro, out_idx,
                        expected, pub_bits);
     SLIMDP_LAUNCHED(c, "k_emit");
@@ -259,6 +273,51 @@ int check_epoch(slimdp_ctx* c, uint64_t core_epoch)
     if (c->epoch == 0 || core_epoch != c->epoch)
         return fail(c, SLIMDP_ERR_STALE_CORE, "core_epoch %llu is not the context's current core epoch %llu",
                     (unsigned long long)core_epoch, (unsigned long long)c->epoch);
+    return SLIMDP_OK;
+}
+
+// Per-segment start of the explorer's radix descent.  Narrow bound: expect m + 6 sqrt(m) + 32
+// candidate words below it; the exact rerun with the full range catches the (astronomically
+// rare) shortfall.  Returns an error code for impossible requests; *narrow is set when every
+// segment got a narrow bound.
+int explorer_init(slimdp_ctx* ctx, const char* who, const uint64_t* k_seg, const uint64_t* m_seg,
+                  std::vector<SegInit>& init, uint64_t* M_out, bool* narrow)
+{
+    uint64_t M = 0;
+    bool all_narrow = true;
+    init.resize(ctx->n_seg);
+    for (uint32_t s = 0; s < ctx->n_seg; ++s) {
+        const uint64_t ns = ctx->seg_off[s + 1] - ctx->seg_off[s];
+        if (k_seg[s] > ns || m_seg[s] > ns - k_seg[s])
+            return fail(ctx, SLIMDP_ERR_OUT_OF_RANGE, "%s: segment %u: m=%llu exceeds the %llu parameters outside the core",
+                        who, s, (unsigned long long)m_seg[s], (unsigned long long)(k_seg[s] > ns ? 0 : ns - k_seg[s]));
+        const uint64_t m = m_seg[s];
+        M += m;
+        SegInit in{(uint32_t)m, 0u, 0u};
+        if (m > 0) {
+            const double avail = (double)(ns - k_seg[s]);
+            double frac = ((double)m + 6.0 * std::sqrt((double)m) + 32.0) / avail;
+            if (ctx->opt_force_fallback) frac = 0.25 * (double)m / avail;
+            if (frac >= 0.95) {
+                in.bound_m1 = 0xFFFFFFFFu; in.shift0 = 20;
+                all_narrow = false;
+            } else {
+                uint64_t B0 = (uint64_t)std::ceil(frac * 4294967296.0);
+                if (B0 < 1) B0 = 1;
+                uint32_t bitlen = 0;
+                while (bitlen < 33 && ((B0 - 1) >> bitlen) != 0) ++bitlen;
+                const uint32_t sh = bitlen > 12 ? bitlen - 12 : 0;
+                B0 = (B0 + ((1ull << sh) - 1)) >> sh << sh;
+                if (B0 > (1ull << 32)) B0 = 1ull << 32;
+                in.bound_m1 = (uint32_t)(B0 - 1);
+                in.shift0 = sh;
+                if (in.bound_m1 == 0xFFFFFFFFu) all_narrow = false;
+            }
+        }
+        init[s] = in;
+    }
+    *M_out = M;
+    *narrow = all_narrow;
     return SLIMDP_OK;
 }
 
@@ -389,11 +448,37 @@ int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_
     PtrTab gt = make_tab<PtrTab>(g, W);
     int vec_ok = aligned16(w) && aligned16(score);
     for (uint32_t q = 0; q < W; ++q) vec_ok = vec_ok && aligned16(g[q]);
+    // an announced explorer draw rides along if every segment has a narrow candidate bound
+    PreArgs pre{};
+    bool presample = false;
+    ctx->pre.valid = false;
+    if (ctx->hint.valid) {
+        std::vector<SegInit> init;
+        uint64_t M = 0;
+        bool narrow = false;
+        if (explorer_init(ctx, "slimdp_score(hint)", ctx->hint.k_seg.data(), ctx->hint.m_seg.data(), init, &M, &narrow) ==
+                SLIMDP_OK && narrow && M > 0) {
+            rc = init_states(ctx, ctx->e_state, init, ctx->hint.n_workers, 0, 1);
+            if (rc) return rc;
+            pre.nw = ctx->hint.n_workers; pre.worker0 = ctx->hint.worker0; pre.n_seg = ctx->n_seg;
+            pre.states = ctx->e_state; pre.cand_bits = ctx->e_cand_bits; pre.cand_keys = ctx->e_cand_keys;
+            pre.cnt_cand = ctx->e_cnt_cand; pre.keys_stride = ctx->keys_stride;
+            pre.pk = PhiloxKey{(uint32_t)ctx->seed, (uint32_t)(ctx->seed >> 32), (uint32_t)ctx->hint.iteration,
+                               (uint32_t)(ctx->hint.iteration >> 32)};
+            presample = true;
+        }
+    }
     const uint32_t P = persistent_blocks(ctx, 4, 1);
     const dim3 grid(P), block(BLOCK);
 #define LAUNCH_SCORE(WT)                                                                                              \
-    hipLaunchKernelGGL(k_score<WT>, grid, block, 0, ctx->stream, w, gt, (int)W, c, score, ctx->d_tile_start,           \
-                       ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok)
+    do {                                                                                                              \
+        if (presample)                                                                                                \
+            hipLaunchKernelGGL((k_score<WT, 1>), grid, block, 0, ctx->stream, w, gt, (int)W, c, score,                \
+                               ctx->d_tile_start, ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok, pre);                 \
+        else                                                                                                          \
+            hipLaunchKernelGGL((k_score<WT, 0>), grid, block, 0, ctx->stream, w, gt, (int)W, c, score,                \
+                               ctx->d_tile_start, ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok, pre);                 \
+    } while (0)
     switch (W) {
         case 1: LAUNCH_SCORE(1); break;
         case 2: LAUNCH_SCORE(2); break;
@@ -404,6 +489,8 @@ int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_
     }
 #undef LAUNCH_SCORE
     SLIMDP_LAUNCHED(ctx, "k_score");
+    if (presample) ctx->pre = ctx->hint;
+    ctx->hint.valid = false;
     ctx->hist_pending = true;
     ctx->hist_score = score;
     return SLIMDP_OK;
@@ -432,7 +519,7 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
                     "slimdp_select_core: no histogram pending for this score buffer (call slimdp_score first)");
     ctx->hist_pending = false;
     const uint32_t T = ctx->T, S = ctx->n_seg;
-    int rc = init_states(ctx, ctx->c_state, init, 1, 1);
+    int rc = init_states(ctx, ctx->c_state, init, 1, 1, 0);
     if (rc) return rc;
     const uint32_t P = persistent_blocks(ctx, 4, 1);
     if (!reuse) {
@@ -478,54 +565,36 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
         return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_sample_explore: n_workers=%u outside [1, %u]", n_workers, ctx->maxW);
     if (!table_ok(expl_off, n_workers)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_sample_explore: NULL expl_off entry");
     uint64_t M = 0;
-    std::vector<SegInit> init(ctx->n_seg);
-    for (uint32_t s = 0; s < ctx->n_seg; ++s) {
-        const uint64_t ns = ctx->seg_off[s + 1] - ctx->seg_off[s];
-        if (k_seg[s] > ns || m_seg[s] > ns - k_seg[s])
-            return fail(ctx, SLIMDP_ERR_OUT_OF_RANGE,
-                        "slimdp_sample_explore: segment %u: m=%llu exceeds the %llu parameters outside the core", s,
-                        (unsigned long long)m_seg[s], (unsigned long long)(k_seg[s] > ns ? 0 : ns - k_seg[s]));
-        const uint64_t m = m_seg[s];
-        M += m;
-        SegInit in{(uint32_t)m, 0u, 0u};
-        if (m > 0) {
-            // Narrow bound: expect m + 6 sqrt(m) + 32 candidate words below it; the exact
-            // rerun with the full range catches the (astronomically rare) shortfall.
-            const double avail = (double)(ns - k_seg[s]);
-            double frac = ((double)m + 6.0 * std::sqrt((double)m) + 32.0) / avail;
-            if (ctx->opt_force_fallback) frac = 0.25 * (double)m / avail;
-            if (frac >= 0.95) {
-                in.bound_m1 = 0xFFFFFFFFu; in.shift0 = 20;
-            } else {
-                uint64_t B0 = (uint64_t)std::ceil(frac * 4294967296.0);
-                if (B0 < 1) B0 = 1;
-                uint32_t bitlen = 0;
-                while (bitlen < 33 && ((B0 - 1) >> bitlen) != 0) ++bitlen;
-                const uint32_t sh = bitlen > 12 ? bitlen - 12 : 0;
-                B0 = (B0 + ((1ull << sh) - 1)) >> sh << sh;
-                if (B0 > (1ull << 32)) B0 = 1ull << 32;
-                in.bound_m1 = (uint32_t)(B0 - 1);
-                in.shift0 = sh;
-            }
-        }
-        init[s] = in;
-    }
+    std::vector<SegInit> init;
+    bool narrow = false;
+    int rc = explorer_init(ctx, "slimdp_sample_explore", k_seg, m_seg, init, &M, &narrow);
+    if (rc) return rc;
     if (M > 0 && !table_ok(expl_idx, n_workers)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_sample_explore: NULL expl_idx entry");
     const uint32_t T = ctx->T, S = ctx->n_seg, B = n_workers;
-    int rc = init_states(ctx, ctx->e_state, init, B, 0);
+    // candidates already drawn inside slimdp_score for exactly this request?
+    const bool cached = ctx->pre.same(iteration, worker0, n_workers, k_seg, m_seg, S);
+    ctx->pre.valid = false;
+    ctx->hint.valid = false;
+    rc = init_states(ctx, ctx->e_state, init, B, 0, cached ? 1u : 0u);
     if (rc) return rc;
     rc = fill(ctx, ctx->e_hist, (uint64_t)B * S * H_STRIDE, 0u);
     if (rc) return rc;
     rc = fill(ctx, ctx->d_flags, 1, 0u);
     if (rc) return rc;
     const uint32_t P = persistent_blocks(ctx, 8, B);
-    const uint32_t seed_lo = (uint32_t)ctx->seed, seed_hi = (uint32_t)(ctx->seed >> 32);
-    const uint32_t it_lo = (uint32_t)iteration, it_hi = (uint32_t)(iteration >> 32);
+    const PhiloxKey pk{(uint32_t)ctx->seed, (uint32_t)(ctx->seed >> 32), (uint32_t)iteration, (uint32_t)(iteration >> 32)};
     for (int fb = 0; fb < 2; ++fb) {
-        hipLaunchKernelGGL(k_explore_keys, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->n, ctx->d_tile_start,
-                           ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_cand_bits, ctx->e_cand_keys,
-                           ctx->e_cnt_cand, ctx->keys_stride, worker0, seed_lo, seed_hi, it_lo, it_hi, fb, ctx->d_flags);
-        SLIMDP_LAUNCHED(ctx, "k_explore_keys");
+        if (fb == 0 && cached) {
+            hipLaunchKernelGGL(k_explore_filter, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->d_tile_start,
+                               ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_cand_bits, ctx->e_cand_keys,
+                               ctx->keys_stride);
+            SLIMDP_LAUNCHED(ctx, "k_explore_filter");
+        } else {
+            hipLaunchKernelGGL(k_explore_keys, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->d_tile_start,
+                               ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_cand_bits, ctx->e_cand_keys,
+                               ctx->e_cnt_cand, ctx->keys_stride, worker0, pk, fb, ctx->d_flags);
+            SLIMDP_LAUNCHED(ctx, "k_explore_keys");
+        }
         hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, ctx->stream, ctx->e_state, ctx->e_hist, 0,
                            (uint32_t)(fb ? H_L0FB : H_L0), S, fb ? 2 : 1, ctx->d_flags);
         SLIMDP_LAUNCHED(ctx, "k_threshold(0)");
@@ -535,6 +604,26 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
     return finish_selection(ctx, B, ctx->e_state, ctx->e_hist, nullptr, ctx->e_cand_bits, ctx->e_cand_keys, nullptr,
                             ctx->e_cnt_cand, ctx->e_cnt_sel, ctx->e_cnt_tie, ctx->e_tie_pre, ctx->keys_stride, false,
                             off_tab, idx_tab, (uint32_t)M, nullptr);
+}
+
+int slimdp_explore_hint(slimdp_ctx* ctx, const uint64_t* k_seg, uint32_t worker0, uint32_t n_workers,
+                        uint64_t iteration, const uint64_t* m_seg)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    ctx->hint.valid = false;
+    if (!k_seg || !m_seg) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_explore_hint: NULL argument");
+    if (n_workers == 0 || n_workers > ctx->maxW)
+        return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_explore_hint: n_workers=%u outside [1, %u]", n_workers, ctx->maxW);
+    std::vector<SegInit> init;
+    uint64_t M = 0;
+    bool narrow = false;
+    int rc = explorer_init(ctx, "slimdp_explore_hint", k_seg, m_seg, init, &M, &narrow);
+    if (rc) return rc;
+    ctx->hint.iteration = iteration; ctx->hint.worker0 = worker0; ctx->hint.n_workers = n_workers;
+    ctx->hint.k_seg.assign(k_seg, k_seg + ctx->n_seg);
+    ctx->hint.m_seg.assign(m_seg, m_seg + ctx->n_seg);
+    ctx->hint.valid = true;
+    return SLIMDP_OK;
 }
 
 int slimdp_tile_offsets(slimdp_ctx* ctx, const uint32_t* idx, uint64_t count, uint32_t* off)

@@ -27,7 +27,7 @@ __global__ __launch_bounds__(256) void k_fill_u32(uint32_t* __restrict__ p, uint
 // Writes the selection state of segments [seg0, seg0+count) for every batch.
 // core != 0: fixed score-bit levels; else explorer levels derived from (bound_m1, shift0).
 __global__ __launch_bounds__(256) void k_init_state(SegState* __restrict__ st, SegInitChunk chunk, uint32_t seg0,
-                                                    uint32_t count, uint32_t n_seg, uint32_t nbatch, int core)
+                                                    uint32_t count, uint32_t n_seg, uint32_t nbatch, int core, uint32_t has_void)
 {
     const uint32_t x = blockIdx.x * 256 + threadIdx.x;
     if (x >= count * nbatch) return;
@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256) void k_init_state(SegState* __restrict__ st, S
     const SegInit in = chunk.s[j];
     SegState s;
     s.need0 = in.need; s.need = in.need; s.prefix = 0; s.none = (in.need == 0) ? 1u : 0u;
-    s.tau = NONE; s.quota = 0; s.bound_m1 = in.bound_m1; s.pad0 = 0; s.pad1[0] = s.pad1[1] = 0;
+    s.tau = NONE; s.quota = 0; s.bound_m1 = in.bound_m1; s.has_void = has_void; s.pad1[0] = s.pad1[1] = 0;
     if (core) {
         s.shift[0] = CORE_SHIFT0; s.nbins[0] = CORE_NB0;
         s.shift[1] = CORE_SHIFT1; s.nbins[1] = CORE_NB1;
@@ -52,6 +52,76 @@ __global__ __launch_bounds__(256) void k_init_state(SegState* __restrict__ st, S
 }
 
 // ---------------------------------------------------------------------------------------
+// K4: explorer candidates of one (worker, tile): the Philox word of each parameter; words
+// r <= bound_m1 become candidates with key = bound_m1 - r (so that the smallest words are
+// the largest keys): a tile bitmap plus the keys compacted in index order.
+// PRESAMPLE = 0: the core is known; core parameters are skipped and the level-0 histogram
+//                of the candidate keys is accumulated in the LDS array h.
+// PRESAMPLE = 1: the core is not known yet (runs inside the scoring kernel, hidden under
+//                its memory traffic); k_explore_filter later voids the core candidates.
+// All threads of the block call it; cd, cpre: TILE_WORDS words of LDS each; wtot: 4 words.
+// ---------------------------------------------------------------------------------------
+struct PhiloxKey { uint32_t seed_lo, seed_hi, it_lo, it_hi; };
+
+template <int PRESAMPLE>
+__device__ __forceinline__ void explore_tile(uint32_t worker, uint32_t t, uint32_t start, uint32_t len, uint32_t bound_m1,
+                                             uint32_t shift0, uint32_t skip, const uint32_t* __restrict__ core_bits,
+                                             uint32_t* h, uint32_t* cd, uint32_t* cpre, uint32_t* wtot,
+                                             uint32_t* __restrict__ cbits, uint32_t* __restrict__ ckeys,
+                                             uint32_t* __restrict__ ccnt, PhiloxKey pk)
+{
+    if (threadIdx.x < TILE_WORDS) cd[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t g0 = start >> 2, g1 = (start + len - 1u) >> 2;   // Philox blocks touched by the tile
+    uint32_t key[5][4];
+    uint32_t is_cand = 0;
+#pragma unroll
+    for (int it = 0; it < 5; ++it) {
+        const uint32_t gi = g0 + (uint32_t)it * BLOCK + threadIdx.x;
+        if (gi <= g1 && !skip) {
+            uint32_t r[4];
+            philox4x32_10(gi, worker, pk.it_lo, pk.it_hi, pk.seed_lo, pk.seed_hi, r);
+            const uint32_t i0 = gi << 2;
+            uint32_t nib = 0;
+            if (!PRESAMPLE) nib = (core_bits[i0 >> 5] >> (i0 & 31u)) & 0xFu;
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                const uint32_t e = i0 + cc - start;          // wraps below the tile start
+                key[it][cc] = bound_m1 - r[cc];
+                if (e < len && !((nib >> cc) & 1u) && r[cc] <= bound_m1) {
+                    atomicOr(&cd[e >> 5], 1u << (e & 31));
+                    if (!PRESAMPLE) atomicAdd(&h[key[it][cc] >> shift0], 1u);
+                    is_cand |= 1u << (it * 4 + cc);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t cw = (threadIdx.x < TILE_WORDS) ? cd[threadIdx.x] : 0u;
+    uint32_t tot_c;
+    const uint32_t ex = block_excl_scan<4>(__popc(cw), wtot, tot_c);
+    if (threadIdx.x < TILE_WORDS) {
+        cpre[threadIdx.x] = ex;
+        cbits[(size_t)t * TILE_WORDS + threadIdx.x] = cw;
+    }
+    if (threadIdx.x == 0) ccnt[t] = tot_c;
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 5; ++it) {
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+            if (is_cand & (1u << (it * 4 + cc))) {
+                const uint32_t gi = g0 + (uint32_t)it * BLOCK + threadIdx.x;
+                const uint32_t e = (gi << 2) + cc - start;
+                const uint32_t rank = cpre[e >> 5] + __popc(cd[e >> 5] & mask_below(e & 31));
+                ckeys[(size_t)start + rank] = key[it][cc];
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// ---------------------------------------------------------------------------------------
 // K1: significance of every parameter + level-0 histogram of its bits (per segment).
 // Reads w and the W updates once, writes the score once: 4n(W+2) bytes.
 // Persistent blocks over contiguous tile ranges keep the 8192-bin histogram in LDS.
@@ -64,13 +134,26 @@ __device__ __forceinline__ void flush_hist(uint32_t* lds, uint32_t nb, uint32_t*
     }
 }
 
-template <int WT>
+// PRE = 1 additionally draws the explorer candidates of pre.nw workers for every tile
+// (explore_tile<1>): integer work that runs while other waves wait for memory.
+struct PreArgs {
+    uint32_t nw, worker0, n_seg;
+    const SegState* states;
+    uint32_t* cand_bits;
+    uint32_t* cand_keys;
+    uint32_t* cnt_cand;
+    uint64_t keys_stride;
+    PhiloxKey pk;
+};
+
+template <int WT, int PRE>
 __global__ __launch_bounds__(BLOCK) void k_score(const float* __restrict__ w, PtrTab g, int Wrt, float c,
                                                  float* __restrict__ S, const uint32_t* __restrict__ tile_start,
                                                  const uint32_t* __restrict__ tile_seg, uint32_t T,
-                                                 uint32_t* __restrict__ hist, int vec_ok)
+                                                 uint32_t* __restrict__ hist, int vec_ok, PreArgs pre)
 {
     __shared__ uint32_t h[CORE_NB0];
+    __shared__ uint32_t cd[PRE ? TILE_WORDS : 1], cpre[PRE ? TILE_WORDS : 1], wtot[4];
     const int W = WT ? WT : Wrt;
     for (uint32_t b = threadIdx.x; b < CORE_NB0; b += BLOCK) h[b] = 0;
     __syncthreads();
@@ -116,6 +199,14 @@ __global__ __launch_bounds__(BLOCK) void k_score(const float* __restrict__ w, Pt
                 const float s = significance(w[e], a, c);
                 S[e] = s;
                 atomicAdd(&h[__float_as_uint(s) >> CORE_SHIFT0], 1u);
+            }
+        }
+        if (PRE) {
+            for (uint32_t b = 0; b < pre.nw; ++b) {
+                const SegState* st = &pre.states[(size_t)b * pre.n_seg + seg];
+                explore_tile<1>(pre.worker0 + b, t, start, len, st->bound_m1, st->shift[0], st->need0 == 0, nullptr,
+                                nullptr, cd, cpre, wtot, pre.cand_bits + (size_t)b * T * TILE_WORDS,
+                                pre.cand_keys + (size_t)b * pre.keys_stride, pre.cnt_cand + (size_t)b * T, pre.pk);
             }
         }
     }
@@ -174,6 +265,7 @@ __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states
             st->shift[1] = 8;  st->nbins[1] = 4096;
             st->shift[2] = 0;  st->nbins[2] = 256;
             st->need = st->need0; st->prefix = 0; st->none = (st->need0 == 0) ? 1u : 0u;
+            st->has_void = 0;
         }
         __syncthreads();
     }
@@ -303,20 +395,15 @@ __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ 
     flush_hist(h, CORE_NB1, hist + (size_t)cur_seg * H_STRIDE + H_L1);
 }
 
-// ---------------------------------------------------------------------------------------
-// K4: explorer candidates for every (worker, tile): the Philox word of each non-core
-// parameter; words r <= bound_m1 become candidates with key = bound_m1 - r (so that the
-// smallest words are the largest keys), plus the level-0 histogram of those keys.
-// grid (blocks, n_workers); fallback != 0: the wide-bound rerun, a no-op unless flagged.
-// ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void k_explore_keys(const uint32_t* __restrict__ core_bits, uint64_t n,
+// Stand-alone pass over every (worker, tile).  grid (blocks, n_workers); fallback != 0: the
+// wide-bound rerun, a no-op unless flagged.
+__global__ __launch_bounds__(BLOCK) void k_explore_keys(const uint32_t* __restrict__ core_bits,
                                                         const uint32_t* __restrict__ tile_start,
                                                         const uint32_t* __restrict__ tile_seg, uint32_t T,
                                                         uint32_t n_seg, const SegState* __restrict__ states,
                                                         uint32_t* __restrict__ hist, uint32_t* __restrict__ cand_bits,
                                                         uint32_t* __restrict__ cand_keys, uint32_t* __restrict__ cnt_cand,
-                                                        uint64_t keys_stride, uint32_t worker0, uint32_t seed_lo,
-                                                        uint32_t seed_hi, uint32_t it_lo, uint32_t it_hi, int fallback,
+                                                        uint64_t keys_stride, uint32_t worker0, PhiloxKey pk, int fallback,
                                                         const uint32_t* __restrict__ flags)
 {
     __shared__ uint32_t h[4096];
@@ -345,58 +432,62 @@ __global__ __launch_bounds__(BLOCK) void k_explore_keys(const uint32_t* __restri
         const uint32_t shift0 = fallback ? 20u : st->shift[0];
         const uint32_t skip = st->need0 == 0;
         const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
-        if (threadIdx.x < TILE_WORDS) cd[threadIdx.x] = 0;
-        __syncthreads();
-        const uint32_t g0 = start >> 2, g1 = (start + len - 1u) >> 2;   // Philox blocks touched by the tile
-        uint32_t key[5][4];
-        uint32_t is_cand = 0;
-#pragma unroll
-        for (int it = 0; it < 5; ++it) {
-            const uint32_t gi = g0 + (uint32_t)it * BLOCK + threadIdx.x;
-            if (gi <= g1 && !skip) {
-                uint32_t r[4];
-                philox4x32_10(gi, worker, it_lo, it_hi, seed_lo, seed_hi, r);
-                const uint32_t i0 = gi << 2;
-                const uint32_t nib = (core_bits[i0 >> 5] >> (i0 & 31u)) & 0xFu;
-#pragma unroll
-                for (int cc = 0; cc < 4; ++cc) {
-                    const uint32_t e = i0 + cc - start;          // wraps below the tile start
-                    key[it][cc] = bound_m1 - r[cc];
-                    if (e < len && !((nib >> cc) & 1u) && r[cc] <= bound_m1) {
-                        atomicOr(&cd[e >> 5], 1u << (e & 31));
-                        atomicAdd(&h[key[it][cc] >> shift0], 1u);
-                        is_cand |= 1u << (it * 4 + cc);
-                    }
-                }
-            }
-        }
-        __syncthreads();
-        const uint32_t cw = (threadIdx.x < TILE_WORDS) ? cd[threadIdx.x] : 0u;
-        uint32_t tot_c;
-        const uint32_t ex = block_excl_scan<4>(__popc(cw), wtot, tot_c);
-        if (threadIdx.x < TILE_WORDS) {
-            cpre[threadIdx.x] = ex;
-            cbits[(size_t)t * TILE_WORDS + threadIdx.x] = cw;
-        }
-        if (threadIdx.x == 0) ccnt[t] = tot_c;
-        __syncthreads();
-#pragma unroll
-        for (int it = 0; it < 5; ++it) {
-#pragma unroll
-            for (int cc = 0; cc < 4; ++cc) {
-                if (is_cand & (1u << (it * 4 + cc))) {
-                    const uint32_t gi = g0 + (uint32_t)it * BLOCK + threadIdx.x;
-                    const uint32_t e = (gi << 2) + cc - start;
-                    const uint32_t rank = cpre[e >> 5] + __popc(cd[e >> 5] & mask_below(e & 31));
-                    ckeys[(size_t)start + rank] = key[it][cc];
-                }
-            }
-        }
-        __syncthreads();
+        explore_tile<0>(worker, t, start, len, bound_m1, shift0, skip, core_bits, h, cd, cpre, wtot, cbits, ckeys, ccnt, pk);
     }
     __syncthreads();
     flush_hist(h, 4096, hist + ((size_t)b * n_seg + cur_seg) * H_STRIDE + hoff);
-    (void)n;
+}
+
+// After a presampling pass: candidates that turned out to be core parameters get the void
+// key (never selected, never counted); the others feed the level-0 histogram.
+// One wave per tile, each lane owning two bitmap words.  grid (blocks, n_workers).
+constexpr uint32_t VOID_KEY = 0xFFFFFFFFu;
+
+__global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __restrict__ core_bits,
+                                                          const uint32_t* __restrict__ tile_start,
+                                                          const uint32_t* __restrict__ tile_seg, uint32_t T,
+                                                          uint32_t n_seg, const SegState* __restrict__ states,
+                                                          uint32_t* __restrict__ hist, const uint32_t* __restrict__ cand_bits,
+                                                          uint32_t* __restrict__ cand_keys, uint64_t keys_stride)
+{
+    __shared__ uint32_t h[4096];
+    const uint32_t b = blockIdx.y, lane = lane_id(), wid = threadIdx.x >> 6;
+    for (uint32_t x = threadIdx.x; x < 4096; x += BLOCK) h[x] = 0;
+    __syncthreads();
+    const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
+    const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
+    if (t0 >= t1) return;
+    // one segment per block range: histogram in LDS; otherwise straight to global memory
+    const uint32_t seg_first = tile_seg[t0];
+    const bool one_seg = seg_first == tile_seg[t1 - 1];
+    for (uint32_t t = t0 + wid; t < t1; t += 4) {
+        const uint32_t seg = tile_seg[t];
+        const SegState* st = &states[(size_t)b * n_seg + seg];
+        if (st->need0 == 0) continue;
+        const uint32_t shift0 = st->shift[0];
+        const uint32_t start = tile_start[t];
+        const uint2 c2 = *reinterpret_cast<const uint2*>(cand_bits + ((size_t)b * T + t) * TILE_WORDS + 2 * lane);
+        const uint32_t cw[2] = {c2.x, c2.y};
+        const uint32_t ccnt = __popc(cw[0]) + __popc(cw[1]);
+        uint32_t j = wave_incl_scan(ccnt) - ccnt;
+        uint32_t* keys = cand_keys + (size_t)b * keys_stride + start;
+        uint32_t* hg = hist + ((size_t)b * n_seg + seg) * H_STRIDE + H_L0;
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            uint32_t m = cw[hh];
+            while (m) {
+                const uint32_t p = __ffs(m) - 1;
+                m &= m - 1;
+                const uint32_t i = start + lane * 64u + 32u * hh + p;
+                if ((core_bits[i >> 5] >> (i & 31u)) & 1u) keys[j] = VOID_KEY;
+                else if (one_seg) atomicAdd(&h[keys[j] >> shift0], 1u);
+                else atomicAdd(&hg[keys[j] >> shift0], 1u);
+                ++j;
+            }
+        }
+    }
+    __syncthreads();
+    if (one_seg) flush_hist(h, 4096, hist + ((size_t)b * n_seg + seg_first) * H_STRIDE + H_L0);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -416,7 +507,7 @@ __global__ __launch_bounds__(BLOCK) void k_list_hist(const uint32_t* __restrict_
     const SegState* st = &states[(size_t)b * n_seg + seg];
     if (st->none) return;
     const uint32_t pshift = st->shift[level - 1], shift = st->shift[level], mask = st->nbins[level] - 1u;
-    const uint32_t prefix = st->prefix;
+    const uint32_t prefix = st->prefix, voidk = st->has_void;
     const uint32_t cnt = cnt_cand[(size_t)b * T + t];
     const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tile_start[t];
     uint32_t* hp = hist + ((size_t)b * n_seg + seg) * H_STRIDE + hist_off;
@@ -426,7 +517,7 @@ __global__ __launch_bounds__(BLOCK) void k_list_hist(const uint32_t* __restrict_
         uint32_t digit = 0;
         if (j < cnt) {
             const uint32_t k = keys[j];
-            part = (k >> pshift) == prefix;
+            part = (k >> pshift) == prefix && !(voidk && k == VOID_KEY);
             digit = (k >> shift) & mask;
         }
         unsigned long long active = __ballot(part);
@@ -456,11 +547,12 @@ __global__ __launch_bounds__(BLOCK) void k_count(const uint32_t* __restrict__ ti
     const SegState* st = &states[(size_t)b * n_seg + tile_seg[t]];
     uint32_t sel = 0, tie = 0;
     if (!st->none) {
-        const uint32_t tau = st->tau;
+        const uint32_t tau = st->tau, voidk = st->has_void;
         const uint32_t cnt = cnt_cand[(size_t)b * T + t];
         const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tile_start[t];
         for (uint32_t j = lane; j < cnt; j += 64) {
             const uint32_t k = keys[j];
+            if (voidk && k == VOID_KEY) continue;
             sel += (k > tau) ? 1u : 0u;
             tie += (k == tau) ? 1u : 0u;
         }
@@ -473,45 +565,75 @@ __global__ __launch_bounds__(BLOCK) void k_count(const uint32_t* __restrict__ ti
 
 // ---------------------------------------------------------------------------------------
 // Scan over tiles: global tie prefix, then how many ties each tile takes under its
-// segment's quota, then the output offset of every tile.  grid (1, nbatch), 1024 threads.
+// segment's quota, then the output offset of every tile.  grid (1, nbatch), 1024 threads:
+// each wave owns a contiguous range of tiles and walks it 64 tiles at a time with
+// coalesced loads and a wave scan.
 // ---------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t tile_out_count(uint32_t t, const uint32_t* __restrict__ cs, const uint32_t* __restrict__ ct,
+                                                   const uint32_t* __restrict__ tp, const uint32_t* __restrict__ tile_seg,
+                                                   const uint32_t* __restrict__ seg_first_tile,
+                                                   const SegState* __restrict__ st)
+{
+    const uint32_t seg = tile_seg[t];
+    const uint32_t base = tp[t] - tp[seg_first_tile[seg]];
+    const uint32_t q = st[seg].quota;
+    const uint32_t room = (q > base) ? q - base : 0u;
+    const uint32_t c = ct[t];
+    return cs[t] + (room < c ? room : c);
+}
+
 __global__ __launch_bounds__(1024) void k_scan(const uint32_t* __restrict__ tile_seg, const uint32_t* __restrict__ seg_first_tile,
                                                uint32_t T, uint32_t n_seg, const SegState* __restrict__ states,
                                                const uint32_t* __restrict__ cnt_sel, const uint32_t* __restrict__ cnt_tie,
                                                uint32_t* __restrict__ tie_pre, MutPtrTab out_off, uint32_t expected,
                                                uint32_t* __restrict__ flags)
 {
-    __shared__ uint32_t wtot[16];
-    const uint32_t b = blockIdx.y;
+    __shared__ uint32_t wsum[16];
+    const uint32_t b = blockIdx.y, lane = lane_id(), wid = threadIdx.x >> 6;
     const uint32_t* cs = cnt_sel + (size_t)b * T;
     const uint32_t* ct = cnt_tie + (size_t)b * T;
+    const SegState* st = states + (size_t)b * n_seg;
     uint32_t* tp = tie_pre + (size_t)b * (T + 1);
     uint32_t* off = static_cast<uint32_t*>(out_off.p[b]);
-    const uint32_t C = (T + 1023u) / 1024u;
-    const uint32_t a0 = threadIdx.x * C, a1 = (a0 + C < T) ? a0 + C : T;
-    uint32_t sum = 0;
-    for (uint32_t t = a0; t < a1; ++t) sum += ct[t];
-    uint32_t total;
-    uint32_t run = block_excl_scan<16>(sum, wtot, total);
-    for (uint32_t t = a0; t < a1; ++t) { tp[t] = run; run += ct[t]; }
-    if (threadIdx.x == 0) tp[T] = total;
+    const uint32_t per = ((T + 15u) / 16u + 63u) / 64u * 64u;       // tiles per wave, multiple of 64
+    const uint32_t r0 = wid * per;
+    const uint32_t r1 = (r0 + per < T) ? r0 + per : T;
+    // ---- ties: wave totals, then the prefix -------------------------------------------
+    uint32_t s = 0;
+#pragma unroll 4
+    for (uint32_t t = r0 + lane; t < r1; t += 64) s += ct[t];
+    s = wave_sum(s);
+    if (lane == 0) wsum[wid] = s;
     __syncthreads();
-    sum = 0;
-    for (uint32_t t = a0; t < a1; ++t) {
-        const uint32_t seg = tile_seg[t];
-        const uint32_t base = tp[t] - tp[seg_first_tile[seg]];
-        const uint32_t q = states[(size_t)b * n_seg + seg].quota;
-        const uint32_t room = (q > base) ? q - base : 0u;
-        sum += cs[t] + (room < ct[t] ? room : ct[t]);
+    uint32_t run = 0, total = 0;
+    for (uint32_t w = 0; w < 16; ++w) { const uint32_t x = wsum[w]; if (w < wid) run += x; total += x; }
+    __syncthreads();
+#pragma unroll 4
+    for (uint32_t t0 = r0; t0 < r1; t0 += 64) {
+        const uint32_t t = t0 + lane;
+        const uint32_t v = (t < r1) ? ct[t] : 0u;
+        const uint32_t incl = wave_incl_scan(v);
+        if (t < r1) tp[t] = run + incl - v;
+        run += __shfl(incl, 63, 64);
     }
-    run = block_excl_scan<16>(sum, wtot, total);
-    for (uint32_t t = a0; t < a1; ++t) {
-        const uint32_t seg = tile_seg[t];
-        const uint32_t base = tp[t] - tp[seg_first_tile[seg]];
-        const uint32_t q = states[(size_t)b * n_seg + seg].quota;
-        const uint32_t room = (q > base) ? q - base : 0u;
-        off[t] = run;
-        run += cs[t] + (room < ct[t] ? room : ct[t]);
+    if (threadIdx.x == 0) tp[T] = total;
+    __syncthreads();      // tp written by other waves is read below
+    // ---- output offsets ---------------------------------------------------------------
+    s = 0;
+#pragma unroll 2
+    for (uint32_t t = r0 + lane; t < r1; t += 64) s += tile_out_count(t, cs, ct, tp, tile_seg, seg_first_tile, st);
+    s = wave_sum(s);
+    if (lane == 0) wsum[wid] = s;
+    __syncthreads();
+    run = 0; total = 0;
+    for (uint32_t w = 0; w < 16; ++w) { const uint32_t x = wsum[w]; if (w < wid) run += x; total += x; }
+#pragma unroll 2
+    for (uint32_t t0 = r0; t0 < r1; t0 += 64) {
+        const uint32_t t = t0 + lane;
+        const uint32_t v = (t < r1) ? tile_out_count(t, cs, ct, tp, tile_seg, seg_first_tile, st) : 0u;
+        const uint32_t incl = wave_incl_scan(v);
+        if (t < r1) off[t] = run + incl - v;
+        run += __shfl(incl, 63, 64);
     }
     if (threadIdx.x == 0) {
         off[T] = total;
@@ -520,63 +642,86 @@ __global__ __launch_bounds__(1024) void k_scan(const uint32_t* __restrict__ tile
 }
 
 // ---------------------------------------------------------------------------------------
-// K3: ordered emission.  One thread per bitmap word of the tile: decide every candidate
-// against tau, hand out the tie quota in index order, and write the tile's chosen indices
-// at its offset.  grid (T, nbatch), 128 threads.
+// K3: ordered emission.  One wave per (tile, batch), each lane owning two consecutive
+// bitmap words: decide every candidate against tau, hand out the tie quota in index
+// order, and write the tile's chosen indices at its offset.  grid (ceil(T/4), nbatch).
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(128) void k_emit(const uint32_t* __restrict__ tile_start, const uint32_t* __restrict__ tile_seg,
-                                              const uint32_t* __restrict__ seg_first_tile, uint32_t T, uint32_t n_seg,
-                                              const SegState* __restrict__ states, const uint32_t* __restrict__ gt_bits,
-                                              const uint32_t* __restrict__ cand_bits, const uint32_t* __restrict__ cand_keys,
-                                              uint64_t keys_stride, const uint32_t* __restrict__ tie_pre, PtrTab out_off,
-                                              MutPtrTab out_idx, uint32_t expected, uint32_t* __restrict__ pub_bits)
+__global__ __launch_bounds__(BLOCK) void k_emit(const uint32_t* __restrict__ tile_start, const uint32_t* __restrict__ tile_seg,
+                                                const uint32_t* __restrict__ seg_first_tile, uint32_t T, uint32_t n_seg,
+                                                const SegState* __restrict__ states, const uint32_t* __restrict__ gt_bits,
+                                                const uint32_t* __restrict__ cand_bits, const uint32_t* __restrict__ cand_keys,
+                                                uint64_t keys_stride, const uint32_t* __restrict__ tie_pre, PtrTab out_off,
+                                                MutPtrTab out_idx, uint32_t expected, uint32_t* __restrict__ pub_bits)
 {
-    __shared__ uint32_t wtot[2];
-    const uint32_t t = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b = blockIdx.y, lane = lane_id();
+    if (t >= T) return;
     const uint32_t seg = tile_seg[t];
     const SegState* st = &states[(size_t)b * n_seg + seg];
     const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
-    const uint32_t none = st->none, tau = st->tau, quota = st->quota;
-    const uint32_t cw = none ? 0u : cand_bits[((size_t)b * T + t) * TILE_WORDS + tid];
-    const uint32_t gw = (gt_bits && !none) ? gt_bits[(size_t)t * TILE_WORDS + tid] : 0u;
-    uint32_t dummy;
-    const uint32_t cpre = block_excl_scan<2>(__popc(cw), wtot, dummy);
+    const uint32_t none = st->none, tau = st->tau, quota = st->quota, voidk = st->has_void;
+    uint32_t cw[2] = {0u, 0u}, gw[2] = {0u, 0u};
+    if (!none) {
+        const uint2 c2 = *reinterpret_cast<const uint2*>(cand_bits + ((size_t)b * T + t) * TILE_WORDS + 2 * lane);
+        cw[0] = c2.x; cw[1] = c2.y;
+        if (gt_bits) {
+            const uint2 g2 = *reinterpret_cast<const uint2*>(gt_bits + (size_t)t * TILE_WORDS + 2 * lane);
+            gw[0] = g2.x; gw[1] = g2.y;
+        }
+    }
+    const uint32_t ccnt = __popc(cw[0]) + __popc(cw[1]);
+    uint32_t j = wave_incl_scan(ccnt) - ccnt;
     const uint32_t* keys = cand_keys + (size_t)b * keys_stride + start;
-    uint32_t selmask = 0, tiemask = 0;
-    {
-        uint32_t m = cw, j = cpre;
+    uint32_t selmask[2] = {0u, 0u}, tiemask[2] = {0u, 0u};
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint32_t m = cw[h];
         while (m) {
             const uint32_t p = __ffs(m) - 1;
             m &= m - 1;
             const uint32_t k = keys[j++];
-            if (k > tau) selmask |= 1u << p;
-            else if (k == tau) tiemask |= 1u << p;
+            if (voidk && k == VOID_KEY) continue;
+            if (k > tau) selmask[h] |= 1u << p;
+            else if (k == tau) tiemask[h] |= 1u << p;
         }
     }
-    const uint32_t* tp = tie_pre + (size_t)b * (T + 1);
-    const uint32_t tpre = block_excl_scan<2>(__popc(tiemask), wtot, dummy);
-    const uint32_t tbase = tp[t] - tp[seg_first_tile[seg]] + tpre;
-    uint32_t take = (quota > tbase) ? quota - tbase : 0u;
-    uint32_t taken = 0;
-    {
-        uint32_t m = tiemask;
-        while (m && take) { const uint32_t low = m & (0u - m); taken |= low; m ^= low; --take; }
+    const uint32_t tcnt = __popc(tiemask[0]) + __popc(tiemask[1]);
+    uint32_t taken[2] = {0u, 0u};
+    if (__ballot(tcnt != 0)) {
+        const uint32_t* tp = tie_pre + (size_t)b * (T + 1);
+        const uint32_t tbase = tp[t] - tp[seg_first_tile[seg]] + wave_incl_scan(tcnt) - tcnt;
+        uint32_t take = (quota > tbase) ? quota - tbase : 0u;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            uint32_t m = tiemask[h];
+            while (m && take) { const uint32_t low = m & (0u - m); taken[h] |= low; m ^= low; --take; }
+        }
     }
-    const uint32_t fm = gw | selmask | taken;
-    const uint32_t opre = block_excl_scan<2>(__popc(fm), wtot, dummy);
+    const uint32_t fm0 = gw[0] | selmask[0] | taken[0], fm1 = gw[1] | selmask[1] | taken[1];
+    const uint32_t ocnt = __popc(fm0) + __popc(fm1);
     const uint32_t* off = static_cast<const uint32_t*>(out_off.p[b]);
     uint32_t* out = static_cast<uint32_t*>(out_idx.p[b]);
-    uint32_t o = off[t] + opre;
+    uint32_t o = off[t] + wave_incl_scan(ocnt) - ocnt;
     {
-        uint32_t m = fm;
+        uint32_t m = fm0;
         while (m) {
             const uint32_t p = __ffs(m) - 1;
             m &= m - 1;
-            if (o < expected) out[o] = start + tid * 32u + p;   // never beyond the caller's list
+            if (o < expected) out[o] = start + lane * 64u + p;     // never beyond the caller's list
+            ++o;
+        }
+        m = fm1;
+        while (m) {
+            const uint32_t p = __ffs(m) - 1;
+            m &= m - 1;
+            if (o < expected) out[o] = start + lane * 64u + 32u + p;
             ++o;
         }
     }
-    if (pub_bits && tid * 32u < len) pub_bits[(start >> 5) + tid] = fm;
+    if (pub_bits) {
+        uint32_t* pb = pub_bits + (start >> 5) + 2 * lane;
+        if (lane * 64u < len) pb[0] = fm0;
+        if (lane * 64u + 32u < len) pb[1] = fm1;
+    }
 }
 
 // Segmented models: the public bitmap is built from the index list (tiles may start inside a word).

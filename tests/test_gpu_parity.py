@@ -41,7 +41,7 @@ def host_tile_offsets(idx, tile_start):
     return np.searchsorted(idx.astype(np.int64), tile_start.astype(np.int64), side="left").astype(np.uint32)
 
 
-def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, check=True):
+def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, check=True, hint=False):
     """One reselect iteration on the GPU and in the oracle; returns both results."""
     seg_off = [int(x) for x in wl.segment_offsets()]
     ks, ms = [int(x) for x in wl.k_seg()], [int(x) for x in wl.m_seg()]
@@ -53,6 +53,8 @@ def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, chec
     sd.set_option("explore_force_fallback", 1 if force_fallback else 0)
     w = to_dev(w_h)
     g = [to_dev(x) for x in g_h]
+    if hint:        # the explorer candidates are drawn inside the scoring kernel
+        sd.explore_hint(ks, iteration, ms, 0, wl.W)
     S = sd.score(w, g, wl.c)
     core_idx, core_bits, core_off, epoch = sd.select_core(S, ks, reuse_histogram=True)
     expl_idx, expl_off = sd.sample_explore(core_bits, ks, iteration, ms, 0, wl.W)
@@ -76,7 +78,10 @@ def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, chec
     packs = [oracle.pack(g_h[q], core_o, ei_o[q]) for q in range(wl.W)]
     w_o = oracle.merge(w_h, wl.lr, core_o, [p[0] for p in packs], ei_o, [p[1] for p in packs])
     w_t = oracle.merge_f64(w_h, wl.lr, core_o, [p[0] for p in packs], ei_o, [p[1] for p in packs])
-    want = dict(S=S_o, core_idx=core_o, expl_idx=ei_o, packs=packs, w=w_o, w_truth=w_t)
+    # sum of |value| sent to each index: the scale of the binary32 summation error
+    sent = oracle.merge_f64(np.zeros_like(w_h), -1.0, core_o, [np.abs(p[0]) for p in packs], ei_o,
+                            [np.abs(p[1]) for p in packs])
+    want = dict(S=S_o, core_idx=core_o, expl_idx=ei_o, packs=packs, w=w_o, w_truth=w_t, sent=sent, lr=wl.lr)
     return got, want
 
 
@@ -93,7 +98,10 @@ def assert_iteration_matches(wl, got, want):
         assert np.array_equal(f32bits(got["expl_val"][q]), f32bits(want["packs"][q][1])), "expl_val %d" % q
     w_g, w_o, w_t = got["w"], want["w"], want["w_truth"]
     assert np.all(np.abs(w_g - w_o) <= 1e-6 * np.abs(w_o) + 1e-12), "merge vs oracle"
-    assert np.all(np.abs(w_g.astype(np.float64) - w_t) <= 1e-6 * np.abs(w_t) + 1e-12), "merge vs binary64"
+    # against exact arithmetic: 1e-6 relative to the result plus 1e-6 of the update's own scale
+    # (a sum of up to W binary32 values carries about W * 2^-24 of sum|v|, scaled by lr)
+    tol = 1e-6 * (np.abs(w_t) + want["lr"] * want["sent"]) + 1e-12
+    assert np.all(np.abs(w_g.astype(np.float64) - w_t) <= tol), "merge vs binary64"
     nbad = int((f32bits(w_g) != f32bits(w_o)).sum())
     assert nbad == 0, "merged parameters differ from the oracle in %d places (within tolerance)" % nbad
     for q in range(wl.W):
@@ -153,6 +161,56 @@ def test_explore_wide_bound_rerun_gives_the_same_sets():
     wl = workloads.TINY.scaled(100_003)
     got, want = run_iteration(wl, force_fallback=True)
     assert_iteration_matches(wl, got, want)
+
+
+@pytest.mark.parametrize("n,W", [(5, 1), (4097, 3), (200_003, 4), (150_001, 8)])
+def test_hinted_draw_inside_score_matches(n, W):
+    wl = workloads.TINY.scaled(n, W=W)
+    got, want = run_iteration(wl, iteration=3, hint=True)
+    assert_iteration_matches(wl, got, want)
+
+
+def test_hinted_draw_segmented_and_stress_and_rerun():
+    wl = workloads.GOOGLENET.scaled(300_001)
+    got, want = run_iteration(wl, hint=True)
+    assert_iteration_matches(wl, got, want)
+    wl = workloads.TINY.scaled(30_000, seg_off=(0, 1, 18, 4114, 4115, 12_307, 29_999, 30_000), n_seg=7)
+    got, want = run_iteration(wl, hint=True)
+    assert_iteration_matches(wl, got, want)
+    wl = workloads.STRESS.scaled(100_003)
+    got, want = run_iteration(wl, hint=True)
+    assert_iteration_matches(wl, got, want)
+    wl = workloads.TINY.scaled(100_003)                       # narrow bound too small: exact rerun
+    got, want = run_iteration(wl, hint=True, force_fallback=True)
+    assert_iteration_matches(wl, got, want)
+    for core_pct, explore_pct in [(0, 2), (10, 0), (50, 100), (10, 60)]:
+        wl = workloads.TINY.scaled(20_005, core_pct=core_pct, explore_pct=explore_pct)
+        got, want = run_iteration(wl, hint=True)
+        assert_iteration_matches(wl, got, want)
+
+
+def test_hint_that_does_not_match_the_request_is_ignored():
+    wl = workloads.TINY.scaled(50_001, W=2)
+    sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
+    w = to_dev(wl.weights())
+    g_h = wl.gradients(0)
+    g = [to_dev(x) for x in g_h]
+    k, m = wl.k, wl.m
+    sd.explore_hint([k], 7, [m], 0, 2)                        # announced: iteration 7, workers 0..1
+    S = sd.score(w, g, wl.c)
+    core_idx, core_bits, core_off, epoch = sd.select_core(S, [k], reuse_histogram=True)
+    core_o = u32(core_idx)
+    # asked for: iteration 8; then worker 1 alone; then a different m
+    for (it, w0, nw, mm) in [(8, 0, 2, m), (7, 1, 1, m), (7, 0, 2, m - 5)]:
+        sd.explore_hint([k], 7, [m], 0, 2)
+        sd.score(w, g, wl.c, out=S)
+        sd.select_core(S, [k], reuse_histogram=True, core_idx=core_idx, core_bits=core_bits, core_off=core_off)
+        expl_idx, _ = sd.sample_explore(core_bits, [k], it, [mm], w0, nw)
+        sd.synchronize()
+        for q in range(nw):
+            want = oracle.sample_explore(wl.n, core_o, workloads.EXPLORE_SEED, it, w0 + q, mm)
+            assert np.array_equal(u32(expl_idx[q]), want), (it, w0, nw, mm)
+    sd.close()
 
 
 @pytest.mark.parametrize("core_pct,explore_pct", [(0, 2), (10, 0), (100, 0), (0, 100), (50, 100), (0, 0)])
