@@ -24,6 +24,7 @@ struct Tiling {
     std::vector<uint32_t> tile_seg;        // T
     std::vector<uint32_t> seg_first_tile;  // n_seg+1
     bool word_aligned = true;              // every tile starts on a bitmap word
+    bool quad_aligned = true;              // every tile starts on a Philox block (index divisible by 4)
 };
 
 bool valid_shape(uint64_t n, uint32_t n_seg, const uint64_t* seg_off)
@@ -45,6 +46,7 @@ Tiling make_tiling(uint64_t n, uint32_t n_seg, const uint64_t* seg_off)
             tl.tile_start.push_back((uint32_t)a);
             tl.tile_seg.push_back(s);
             if (a & 31u) tl.word_aligned = false;
+            if (a & 3u) tl.quad_aligned = false;
         }
     }
     tl.seg_first_tile[n_seg] = (uint32_t)tl.tile_seg.size();
@@ -136,7 +138,7 @@ void carve(slimdp_ctx* c, Carver& cv)
     c->c_cand_bits = cv.take<uint32_t>(T * TILE_WORDS);
     c->c_cand_keys = cv.take<uint32_t>(c->keys_stride);
     c->c_cnt_gt = cv.take<uint32_t>(T);
-    c->c_cnt_cand = cv.take<uint32_t>(T);
+    c->c_cnt_cand = cv.take<uint32_t>(T * SUBS);
     c->c_cnt_sel = cv.take<uint32_t>(T);
     c->c_cnt_tie = cv.take<uint32_t>(T);
     c->c_tie_pre = cv.take<uint32_t>(T + 1);
@@ -144,7 +146,7 @@ void carve(slimdp_ctx* c, Carver& cv)
     c->e_hist = cv.take<uint32_t>(B * S * H_STRIDE);
     c->e_cand_bits = cv.take<uint32_t>(B * T * TILE_WORDS);
     c->e_cand_keys = cv.take<uint32_t>(B * c->keys_stride);
-    c->e_cnt_cand = cv.take<uint32_t>(B * T);
+    c->e_cnt_cand = cv.take<uint32_t>(B * T * SUBS);
     c->e_cnt_sel = cv.take<uint32_t>(B * T);
     c->e_cnt_tie = cv.take<uint32_t>(B * T);
     c->e_tie_pre = cv.take<uint32_t>(B * (T + 1));
@@ -452,7 +454,7 @@ int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_
     PreArgs pre{};
     bool presample = false;
     ctx->pre.valid = false;
-    if (ctx->hint.valid) {
+    if (ctx->hint.valid && ctx->tl.quad_aligned) {
         std::vector<SegInit> init;
         uint64_t M = 0;
         bool narrow = false;
@@ -587,12 +589,17 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
         if (fb == 0 && cached) {
             hipLaunchKernelGGL(k_explore_filter, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->d_tile_start,
                                ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_cand_bits, ctx->e_cand_keys,
-                               ctx->keys_stride);
+                               ctx->keys_stride, (uint32_t)((ctx->n + 31) / 32));
             SLIMDP_LAUNCHED(ctx, "k_explore_filter");
         } else {
-            hipLaunchKernelGGL(k_explore_keys, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->d_tile_start,
-                               ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_cand_bits, ctx->e_cand_keys,
-                               ctx->e_cnt_cand, ctx->keys_stride, worker0, pk, fb, ctx->d_flags);
+            if (ctx->tl.quad_aligned)
+                hipLaunchKernelGGL(k_explore_keys<1>, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->d_tile_start,
+                                   ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_cand_bits, ctx->e_cand_keys,
+                                   ctx->e_cnt_cand, ctx->keys_stride, worker0, pk, fb, ctx->d_flags);
+            else
+                hipLaunchKernelGGL(k_explore_keys<0>, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->d_tile_start,
+                                   ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_cand_bits, ctx->e_cand_keys,
+                                   ctx->e_cnt_cand, ctx->keys_stride, worker0, pk, fb, ctx->d_flags);
             SLIMDP_LAUNCHED(ctx, "k_explore_keys");
         }
         hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, ctx->stream, ctx->e_state, ctx->e_hist, 0,

@@ -9,6 +9,7 @@ namespace slimdp {
 
 constexpr uint32_t TILE = SLIMDP_TILE;            // parameters per tile
 constexpr uint32_t TILE_WORDS = TILE / 32;        // bitmap words per tile
+constexpr uint32_t SUB = 1024, SUB_WORDS = SUB / 32, SUBS = TILE / SUB;   // sub-tile: one wave's share of a tile
 constexpr uint32_t NONE = 0xFFFFFFFFu;
 constexpr int MAXW = SLIMDP_MAX_WORKERS;
 constexpr int BLOCK = 256;                        // threads per block in the tile kernels

@@ -5,8 +5,10 @@
 // (keys = score bits) and for the explorer (keys = bound - Philox word over the non-core
 // parameters), is a three-level radix descent:
 //   level 0 histogram over every key (fused into the kernel that produces the keys),
-//   -> keys in the threshold bin become "candidates": a per-tile bitmap plus the tile's
-//      candidate keys compacted in index order at cand_keys[tile_start ...],
+//   -> keys in the threshold bin become "candidates": a per-tile bitmap plus the candidate
+//      keys of each 1024-parameter sub-tile compacted in index order at
+//      cand_keys[tile_start + 1024*s ...] with their number in cnt_cand[4*tile + s]
+//      (a sub-tile is what one wave handles on its own, without block barriers),
 //   levels 1 and 2 histogram only candidates, giving the threshold key tau and the number
 //   of keys == tau to take (quota, lowest index first),
 //   count per tile -> scan over tiles -> ordered emission of the ascending index list.
@@ -52,33 +54,51 @@ __global__ __launch_bounds__(256) void k_init_state(SegState* __restrict__ st, S
 }
 
 // ---------------------------------------------------------------------------------------
-// K4: explorer candidates of one (worker, tile): the Philox word of each parameter; words
-// r <= bound_m1 become candidates with key = bound_m1 - r (so that the smallest words are
-// the largest keys): a tile bitmap plus the keys compacted in index order.
+// K4: explorer candidates of one (worker, sub-tile), by ONE wave with no block barrier:
+// the Philox word of each parameter; words r <= bound_m1 become candidates with
+// key = bound_m1 - r (so that the smallest words are the largest keys): 32 bitmap words
+// plus the keys compacted in index order.
 // PRESAMPLE = 0: the core is known; core parameters are skipped and the level-0 histogram
 //                of the candidate keys is accumulated in the LDS array h.
 // PRESAMPLE = 1: the core is not known yet (runs inside the scoring kernel, hidden under
 //                its memory traffic); k_explore_filter later voids the core candidates.
-// All threads of the block call it; cd, cpre: TILE_WORDS words of LDS each; wtot: 4 words.
+// wb, wp: 32 words of LDS each, private to the calling wave.
 // ---------------------------------------------------------------------------------------
 struct PhiloxKey { uint32_t seed_lo, seed_hi, it_lo, it_hi; };
 
-template <int PRESAMPLE>
-__device__ __forceinline__ void explore_tile(uint32_t worker, uint32_t t, uint32_t start, uint32_t len, uint32_t bound_m1,
-                                             uint32_t shift0, uint32_t skip, const uint32_t* __restrict__ core_bits,
-                                             uint32_t* h, uint32_t* cd, uint32_t* cpre, uint32_t* wtot,
-                                             uint32_t* __restrict__ cbits, uint32_t* __restrict__ ckeys,
-                                             uint32_t* __restrict__ ccnt, PhiloxKey pk)
+// LDS traffic between the lanes of one wave: the hardware keeps a wave's LDS operations in
+// order, this keeps the compiler from moving them across the hand-over point.
+__device__ __forceinline__ void wave_sync()
 {
-    if (threadIdx.x < TILE_WORDS) cd[threadIdx.x] = 0;
-    __syncthreads();
-    const uint32_t g0 = start >> 2, g1 = (start + len - 1u) >> 2;   // Philox blocks touched by the tile
+    __builtin_amdgcn_wave_barrier();
+}
+
+template <int PRESAMPLE>
+__device__ __forceinline__ void explore_subtile(uint32_t worker, uint32_t t, uint32_t sub, uint32_t start, uint32_t len,
+                                                uint32_t bound_m1, uint32_t shift0, uint32_t skip,
+                                                const uint32_t* __restrict__ core_bits, uint32_t* h, uint32_t* wb,
+                                                uint32_t* wp, uint32_t* __restrict__ cbits, uint32_t* __restrict__ ckeys,
+                                                uint32_t* __restrict__ ccnt, PhiloxKey pk)
+{
+    const uint32_t lane = lane_id();
+    const uint32_t off = sub * SUB;
+    const uint32_t sub_len = (len > off) ? ((len - off < SUB) ? len - off : SUB) : 0u;
+    if (sub_len == 0 || skip) {                                   // uniform over the wave
+        if (lane < SUB_WORDS) cbits[(size_t)t * TILE_WORDS + sub * SUB_WORDS + lane] = 0;
+        if (lane == 0) ccnt[(size_t)t * SUBS + sub] = 0;
+        return;
+    }
+    if (lane < SUB_WORDS) wb[lane] = 0;
+    wave_sync();
+    const uint32_t base = start + off;
+    const uint32_t g0 = base >> 2, g1 = (base + sub_len - 1u) >> 2;     // Philox blocks touched: at most 257
     uint32_t key[5][4];
     uint32_t is_cand = 0;
 #pragma unroll
     for (int it = 0; it < 5; ++it) {
-        const uint32_t gi = g0 + (uint32_t)it * BLOCK + threadIdx.x;
-        if (gi <= g1 && !skip) {
+        if (g1 - g0 < (uint32_t)it * 64u) break;                   // uniform: the 5th round only for unaligned starts
+        const uint32_t gi = g0 + (uint32_t)it * 64u + lane;
+        if (gi <= g1) {
             uint32_t r[4];
             philox4x32_10(gi, worker, pk.it_lo, pk.it_hi, pk.seed_lo, pk.seed_hi, r);
             const uint32_t i0 = gi << 2;
@@ -86,39 +106,107 @@ __device__ __forceinline__ void explore_tile(uint32_t worker, uint32_t t, uint32
             if (!PRESAMPLE) nib = (core_bits[i0 >> 5] >> (i0 & 31u)) & 0xFu;
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) {
-                const uint32_t e = i0 + cc - start;          // wraps below the tile start
+                const uint32_t e = i0 + cc - base;                  // wraps below the sub-tile start
                 key[it][cc] = bound_m1 - r[cc];
-                if (e < len && !((nib >> cc) & 1u) && r[cc] <= bound_m1) {
-                    atomicOr(&cd[e >> 5], 1u << (e & 31));
+                if (e < sub_len && !((nib >> cc) & 1u) && r[cc] <= bound_m1) {
+                    atomicOr(&wb[e >> 5], 1u << (e & 31));
                     if (!PRESAMPLE) atomicAdd(&h[key[it][cc] >> shift0], 1u);
                     is_cand |= 1u << (it * 4 + cc);
                 }
             }
         }
     }
-    __syncthreads();
-    const uint32_t cw = (threadIdx.x < TILE_WORDS) ? cd[threadIdx.x] : 0u;
-    uint32_t tot_c;
-    const uint32_t ex = block_excl_scan<4>(__popc(cw), wtot, tot_c);
-    if (threadIdx.x < TILE_WORDS) {
-        cpre[threadIdx.x] = ex;
-        cbits[(size_t)t * TILE_WORDS + threadIdx.x] = cw;
+    wave_sync();
+    const uint32_t cw = (lane < SUB_WORDS) ? wb[lane] : 0u;
+    const uint32_t pc = __popc(cw);
+    const uint32_t incl = wave_incl_scan(pc);
+    if (lane < SUB_WORDS) {
+        wp[lane] = incl - pc;
+        cbits[(size_t)t * TILE_WORDS + sub * SUB_WORDS + lane] = cw;
     }
-    if (threadIdx.x == 0) ccnt[t] = tot_c;
-    __syncthreads();
+    if (lane == SUB_WORDS - 1) ccnt[(size_t)t * SUBS + sub] = incl;
+    wave_sync();
+    if (is_cand) {
 #pragma unroll
-    for (int it = 0; it < 5; ++it) {
+        for (int it = 0; it < 5; ++it) {
 #pragma unroll
-        for (int cc = 0; cc < 4; ++cc) {
-            if (is_cand & (1u << (it * 4 + cc))) {
-                const uint32_t gi = g0 + (uint32_t)it * BLOCK + threadIdx.x;
-                const uint32_t e = (gi << 2) + cc - start;
-                const uint32_t rank = cpre[e >> 5] + __popc(cd[e >> 5] & mask_below(e & 31));
-                ckeys[(size_t)start + rank] = key[it][cc];
+            for (int cc = 0; cc < 4; ++cc) {
+                if (is_cand & (1u << (it * 4 + cc))) {
+                    const uint32_t gi = g0 + (uint32_t)it * 64u + lane;
+                    const uint32_t e = (gi << 2) + cc - base;
+                    const uint32_t rank = wp[e >> 5] + __popc(wb[e >> 5] & mask_below(e & 31));
+                    ckeys[(size_t)base + rank] = key[it][cc];
+                }
             }
         }
     }
-    __syncthreads();
+    wave_sync();
+}
+
+// The same for a sub-tile that starts on a Philox block (start + 1024*sub divisible by 4):
+// no LDS at all.  Round `it` covers the 256 parameters [256*it, 256*it+256) of the sub-tile
+// in index order (lane L owns parameters 4L..4L+3 of the round), so a candidate's place in
+// the key list is the number of candidates in earlier rounds plus a wave ballot count, and
+// the eight bitmap words of the round are OR-reductions over groups of eight lanes.
+template <int PRESAMPLE>
+__device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t, uint32_t sub, uint32_t start, uint32_t len,
+                                                     uint32_t bound_m1, uint32_t shift0, uint32_t skip,
+                                                     const uint32_t* __restrict__ core_bits, uint32_t* h,
+                                                     uint32_t* __restrict__ cbits, uint32_t* __restrict__ ckeys,
+                                                     uint32_t* __restrict__ ccnt, PhiloxKey pk)
+{
+    const uint32_t lane = lane_id();
+    const uint32_t off = sub * SUB;
+    const uint32_t sub_len = (len > off) ? ((len - off < SUB) ? len - off : SUB) : 0u;
+    uint32_t* words = cbits + (size_t)t * TILE_WORDS + sub * SUB_WORDS;
+    if (sub_len == 0 || skip) {                                   // uniform over the wave
+        if (lane < SUB_WORDS) words[lane] = 0;
+        if (lane == 0) ccnt[(size_t)t * SUBS + sub] = 0;
+        return;
+    }
+    const uint32_t base = start + off;
+    uint32_t run = 0;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const uint32_t e0 = (uint32_t)it * 256u + lane * 4u;      // first of this lane's four parameters
+        const uint32_t i0 = base + e0;
+        uint32_t nib = 0;
+        if (!PRESAMPLE) nib = (e0 < sub_len) ? (core_bits[i0 >> 5] >> (i0 & 31u)) & 0xFu : 0xFu;
+        uint32_t r[4];
+        philox4x32_10(i0 >> 2, worker, pk.it_lo, pk.it_hi, pk.seed_lo, pk.seed_hi, r);
+        uint32_t flags = 0;
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc)
+            if (e0 + cc < sub_len && !((nib >> cc) & 1u) && r[cc] <= bound_m1) flags |= 1u << cc;
+        // bitmap words: lanes 8j..8j+7 make word j of this round
+        uint32_t v = flags << (4u * (lane & 7u));
+        v |= __shfl_xor(v, 1, 64);
+        v |= __shfl_xor(v, 2, 64);
+        v |= __shfl_xor(v, 4, 64);
+        if ((lane & 7u) == 0) words[it * 8 + (lane >> 3)] = v;
+        // place in the list: candidates of lower lanes in this round, all four components
+        uint32_t below = 0, total = 0;
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+            const unsigned long long bal = __ballot((flags >> cc) & 1u);
+            below += __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+            total += (uint32_t)__popcll(bal);
+        }
+        if (flags) {
+            uint32_t pos = run + below;
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                if ((flags >> cc) & 1u) {
+                    const uint32_t key = bound_m1 - r[cc];
+                    ckeys[(size_t)base + pos] = key;
+                    if (!PRESAMPLE) atomicAdd(&h[key >> shift0], 1u);
+                    ++pos;
+                }
+            }
+        }
+        run += total;
+    }
+    if (lane == 0) ccnt[(size_t)t * SUBS + sub] = run;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -147,20 +235,22 @@ struct PreArgs {
 };
 
 template <int WT, int PRE>
-__global__ __launch_bounds__(BLOCK) void k_score(const float* __restrict__ w, PtrTab g, int Wrt, float c,
+__global__ __launch_bounds__(BLOCK, 4) void k_score(const float* __restrict__ w, PtrTab g, int Wrt, float c,
                                                  float* __restrict__ S, const uint32_t* __restrict__ tile_start,
                                                  const uint32_t* __restrict__ tile_seg, uint32_t T,
                                                  uint32_t* __restrict__ hist, int vec_ok, PreArgs pre)
 {
     __shared__ uint32_t h[CORE_NB0];
-    __shared__ uint32_t cd[PRE ? TILE_WORDS : 1], cpre[PRE ? TILE_WORDS : 1], wtot[4];
     const int W = WT ? WT : Wrt;
+    const uint32_t lane = lane_id(), wid = threadIdx.x >> 6;
     for (uint32_t b = threadIdx.x; b < CORE_NB0; b += BLOCK) h[b] = 0;
     __syncthreads();
     const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
     const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
     if (t0 >= t1) return;
     uint32_t cur_seg = tile_seg[t0];
+    // Every wave owns sub-tile `wid` of each tile and runs through the block's tiles on its
+    // own; the block only meets at a segment change and at the end (histogram flush).
     for (uint32_t t = t0; t < t1; ++t) {
         const uint32_t seg = tile_seg[t];
         if (seg != cur_seg) {
@@ -170,43 +260,66 @@ __global__ __launch_bounds__(BLOCK) void k_score(const float* __restrict__ w, Pt
             cur_seg = seg;
         }
         const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
-        if (vec_ok && len == TILE && (start & 3u) == 0) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const size_t e = (size_t)start + (size_t)r * 1024 + threadIdx.x * 4;
-                const float4 wv = *reinterpret_cast<const float4*>(w + e);
-                float4 a = *reinterpret_cast<const float4*>(static_cast<const float*>(g.p[0]) + e);
-#pragma unroll
-                for (int k = 1; k < (WT ? WT : MAXW); ++k) {
-                    if (k >= W) break;
-                    const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(g.p[k]) + e);
-                    a.x = a.x + x.x; a.y = a.y + x.y; a.z = a.z + x.z; a.w = a.w + x.w;
-                }
-                float4 s;
-                s.x = significance(wv.x, a.x, c); s.y = significance(wv.y, a.y, c);
-                s.z = significance(wv.z, a.z, c); s.w = significance(wv.w, a.w, c);
-                *reinterpret_cast<float4*>(S + e) = s;
-                atomicAdd(&h[__float_as_uint(s.x) >> CORE_SHIFT0], 1u);
-                atomicAdd(&h[__float_as_uint(s.y) >> CORE_SHIFT0], 1u);
-                atomicAdd(&h[__float_as_uint(s.z) >> CORE_SHIFT0], 1u);
-                atomicAdd(&h[__float_as_uint(s.w) >> CORE_SHIFT0], 1u);
-            }
-        } else {
-            for (uint32_t l = threadIdx.x; l < len; l += BLOCK) {
+        // the candidate bound depends on the segment only (every worker draws the same number)
+        uint32_t pre_bound = 0, pre_skip = 1;
+        if (PRE) {
+            const SegState* st = &pre.states[seg];
+            pre_bound = st->bound_m1; pre_skip = st->need0 == 0;
+        }
+        const bool vec = vec_ok && len == TILE && (start & 3u) == 0;
+        if (!vec) {
+            const uint32_t lo = wid * SUB, hi = (lo + SUB < len) ? lo + SUB : len;
+            for (uint32_t l = lo + lane; l < hi; l += 64) {
                 const size_t e = (size_t)start + l;
                 float a = static_cast<const float*>(g.p[0])[e];
                 for (int k = 1; k < W; ++k) a = a + static_cast<const float*>(g.p[k])[e];
-                const float s = significance(w[e], a, c);
-                S[e] = s;
-                atomicAdd(&h[__float_as_uint(s) >> CORE_SHIFT0], 1u);
+                const float sc = significance(w[e], a, c);
+                S[e] = sc;
+                atomicAdd(&h[__float_as_uint(sc) >> CORE_SHIFT0], 1u);
             }
         }
-        if (PRE) {
-            for (uint32_t b = 0; b < pre.nw; ++b) {
-                const SegState* st = &pre.states[(size_t)b * pre.n_seg + seg];
-                explore_tile<1>(pre.worker0 + b, t, start, len, st->bound_m1, st->shift[0], st->need0 == 0, nullptr,
-                                nullptr, cd, cpre, wtot, pre.cand_bits + (size_t)b * T * TILE_WORDS,
-                                pre.cand_keys + (size_t)b * pre.keys_stride, pre.cnt_cand + (size_t)b * T, pre.pk);
+        if (!vec && !PRE) continue;
+#pragma unroll 1
+        for (int r = 0; r < 4; ++r) {
+            const size_t e = (size_t)start + (size_t)wid * SUB + (size_t)r * 256 + lane * 4;
+            float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
+            float4 x[WT ? WT : 1];
+            if (vec) {          // request this round's lines first ...
+                wv = *reinterpret_cast<const float4*>(w + e);
+                if (WT) {
+#pragma unroll
+                    for (int k = 0; k < WT; ++k) x[k] = *reinterpret_cast<const float4*>(static_cast<const float*>(g.p[k]) + e);
+                }
+            }
+            if (PRE) {          // ... do this round's share of the integer work while they fly ...
+#pragma unroll 1
+                for (uint32_t b = (uint32_t)r; b < pre.nw; b += 4)
+                    explore_subtile_fast<1>(pre.worker0 + b, t, wid, start, len, pre_bound, 0u, pre_skip, nullptr, nullptr,
+                                            pre.cand_bits + (size_t)b * T * TILE_WORDS,
+                                            pre.cand_keys + (size_t)b * pre.keys_stride, pre.cnt_cand + (size_t)b * T * SUBS,
+                                            pre.pk);
+            }
+            if (vec) {          // ... then score them
+                float4 a;
+                if (WT) {
+                    a = x[0];
+#pragma unroll
+                    for (int k = 1; k < WT; ++k) { a.x = a.x + x[k].x; a.y = a.y + x[k].y; a.z = a.z + x[k].z; a.w = a.w + x[k].w; }
+                } else {
+                    a = *reinterpret_cast<const float4*>(static_cast<const float*>(g.p[0]) + e);
+                    for (int k = 1; k < W; ++k) {
+                        const float4 y = *reinterpret_cast<const float4*>(static_cast<const float*>(g.p[k]) + e);
+                        a.x = a.x + y.x; a.y = a.y + y.y; a.z = a.z + y.z; a.w = a.w + y.w;
+                    }
+                }
+                float4 sc;
+                sc.x = significance(wv.x, a.x, c); sc.y = significance(wv.y, a.y, c);
+                sc.z = significance(wv.z, a.z, c); sc.w = significance(wv.w, a.w, c);
+                *reinterpret_cast<float4*>(S + e) = sc;
+                atomicAdd(&h[__float_as_uint(sc.x) >> CORE_SHIFT0], 1u);
+                atomicAdd(&h[__float_as_uint(sc.y) >> CORE_SHIFT0], 1u);
+                atomicAdd(&h[__float_as_uint(sc.z) >> CORE_SHIFT0], 1u);
+                atomicAdd(&h[__float_as_uint(sc.w) >> CORE_SHIFT0], 1u);
             }
         }
     }
@@ -379,14 +492,20 @@ __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ 
             gt_bits[(size_t)t * TILE_WORDS + threadIdx.x] = gw;
             cand_bits[(size_t)t * TILE_WORDS + threadIdx.x] = cw;
         }
-        if (threadIdx.x == 0) { cnt_cand[t] = tot_c; cnt_gt[t] = tot_g; }
+        if (threadIdx.x == 0) cnt_gt[t] = tot_g;
         __syncthreads();
+        if (threadIdx.x < SUBS) {       // candidates per sub-tile
+            const uint32_t s0 = cpre[threadIdx.x * SUB_WORDS];
+            const uint32_t s1 = (threadIdx.x + 1 < SUBS) ? cpre[(threadIdx.x + 1) * SUB_WORDS] : tot_c;
+            cnt_cand[(size_t)t * SUBS + threadIdx.x] = s1 - s0;
+        }
 #pragma unroll
         for (int j = 0; j < EPT; ++j) {
             if (is_cand & (1u << j)) {
                 const uint32_t e = vec ? elem_vec(j) : elem_scl(j);
-                const uint32_t rank = cpre[e >> 5] + __popc(cd[e >> 5] & mask_below(e & 31));
-                cand_keys[(size_t)start + rank] = key[j];
+                const uint32_t wd = e >> 5;
+                const uint32_t rank = cpre[wd] - cpre[wd & ~(SUB_WORDS - 1u)] + __popc(cd[wd] & mask_below(e & 31));
+                cand_keys[(size_t)start + (e & ~(SUB - 1u)) + rank] = key[j];
             }
         }
         __syncthreads();
@@ -395,8 +514,9 @@ __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ 
     flush_hist(h, CORE_NB1, hist + (size_t)cur_seg * H_STRIDE + H_L1);
 }
 
-// Stand-alone pass over every (worker, tile).  grid (blocks, n_workers); fallback != 0: the
-// wide-bound rerun, a no-op unless flagged.
+// Stand-alone pass over every (worker, tile); each wave owns one sub-tile of the block's
+// tiles.  grid (blocks, n_workers); fallback != 0: the wide-bound rerun, a no-op unless flagged.
+template <int FAST>
 __global__ __launch_bounds__(BLOCK) void k_explore_keys(const uint32_t* __restrict__ core_bits,
                                                         const uint32_t* __restrict__ tile_start,
                                                         const uint32_t* __restrict__ tile_seg, uint32_t T,
@@ -407,24 +527,25 @@ __global__ __launch_bounds__(BLOCK) void k_explore_keys(const uint32_t* __restri
                                                         const uint32_t* __restrict__ flags)
 {
     __shared__ uint32_t h[4096];
-    __shared__ uint32_t cd[TILE_WORDS], cpre[TILE_WORDS];
-    __shared__ uint32_t wtot[4];
+    __shared__ uint32_t wbits[FAST ? 1 : 4][SUB_WORDS], wpre[FAST ? 1 : 4][SUB_WORDS];
     if (fallback && flags[0] == 0) return;
-    const uint32_t b = blockIdx.y, worker = worker0 + b;
+    const uint32_t b = blockIdx.y, worker = worker0 + b, wid = threadIdx.x >> 6;
     const uint32_t hoff = fallback ? H_L0FB : H_L0;
     for (uint32_t x = threadIdx.x; x < 4096; x += BLOCK) h[x] = 0;
+    __syncthreads();
     const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
     const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
     if (t0 >= t1) return;
     uint32_t* cbits = cand_bits + (size_t)b * T * TILE_WORDS;
     uint32_t* ckeys = cand_keys + (size_t)b * keys_stride;
-    uint32_t* ccnt = cnt_cand + (size_t)b * T;
+    uint32_t* ccnt = cnt_cand + (size_t)b * T * SUBS;
     uint32_t cur_seg = tile_seg[t0];
     for (uint32_t t = t0; t < t1; ++t) {
         const uint32_t seg = tile_seg[t];
         if (seg != cur_seg) {
             __syncthreads();
             flush_hist(h, 4096, hist + ((size_t)b * n_seg + cur_seg) * H_STRIDE + hoff);
+            __syncthreads();
             cur_seg = seg;
         }
         const SegState* st = &states[(size_t)b * n_seg + seg];
@@ -432,15 +553,28 @@ __global__ __launch_bounds__(BLOCK) void k_explore_keys(const uint32_t* __restri
         const uint32_t shift0 = fallback ? 20u : st->shift[0];
         const uint32_t skip = st->need0 == 0;
         const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
-        explore_tile<0>(worker, t, start, len, bound_m1, shift0, skip, core_bits, h, cd, cpre, wtot, cbits, ckeys, ccnt, pk);
+        if (FAST)
+            explore_subtile_fast<0>(worker, t, wid, start, len, bound_m1, shift0, skip, core_bits, h, cbits, ckeys, ccnt, pk);
+        else
+            explore_subtile<0>(worker, t, wid, start, len, bound_m1, shift0, skip, core_bits, h, wbits[FAST ? 0 : wid],
+                               wpre[FAST ? 0 : wid], cbits, ckeys, ccnt, pk);
     }
     __syncthreads();
     flush_hist(h, 4096, hist + ((size_t)b * n_seg + cur_seg) * H_STRIDE + hoff);
 }
 
+// A wave walks one tile's candidates with every lane owning two bitmap words; the 16 lanes
+// of a sub-tile find their place in that sub-tile's key list by a prefix inside the group.
+__device__ __forceinline__ uint32_t sublist_pos(uint32_t lane, uint32_t my_count)
+{
+    const uint32_t excl = wave_incl_scan(my_count) - my_count;
+    const uint32_t group0 = __shfl(excl, (int)(lane & ~15u), 64);
+    return (lane >> 4) * SUB + (excl - group0);
+}
+
 // After a presampling pass: candidates that turned out to be core parameters get the void
 // key (never selected, never counted); the others feed the level-0 histogram.
-// One wave per tile, each lane owning two bitmap words.  grid (blocks, n_workers).
+// One wave per tile.  grid (blocks, n_workers), persistent so that the histogram stays in LDS.
 constexpr uint32_t VOID_KEY = 0xFFFFFFFFu;
 
 __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __restrict__ core_bits,
@@ -448,7 +582,8 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
                                                           const uint32_t* __restrict__ tile_seg, uint32_t T,
                                                           uint32_t n_seg, const SegState* __restrict__ states,
                                                           uint32_t* __restrict__ hist, const uint32_t* __restrict__ cand_bits,
-                                                          uint32_t* __restrict__ cand_keys, uint64_t keys_stride)
+                                                          uint32_t* __restrict__ cand_keys, uint64_t keys_stride,
+                                                          uint32_t n_words)
 {
     __shared__ uint32_t h[4096];
     const uint32_t b = blockIdx.y, lane = lane_id(), wid = threadIdx.x >> 6;
@@ -468,8 +603,19 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
         const uint32_t start = tile_start[t];
         const uint2 c2 = *reinterpret_cast<const uint2*>(cand_bits + ((size_t)b * T + t) * TILE_WORDS + 2 * lane);
         const uint32_t cw[2] = {c2.x, c2.y};
-        const uint32_t ccnt = __popc(cw[0]) + __popc(cw[1]);
-        uint32_t j = wave_incl_scan(ccnt) - ccnt;
+        // core bits of this lane's 64 parameters (a tile may start inside a bitmap word)
+        const uint32_t i0 = start + lane * 64u;
+        const uint32_t sh = i0 & 31u;
+        const uint32_t wi = i0 >> 5;
+        uint32_t kw[2] = {0u, 0u};
+        if (cw[0] | cw[1]) {                       // then i0 < n, so word wi exists
+            const uint32_t a0 = core_bits[wi];
+            const uint32_t a1 = (wi + 1 < n_words) ? core_bits[wi + 1] : 0u;
+            const uint32_t a2 = (sh && wi + 2 < n_words) ? core_bits[wi + 2] : 0u;
+            kw[0] = sh ? ((a0 >> sh) | (a1 << (32u - sh))) : a0;
+            kw[1] = sh ? ((a1 >> sh) | (a2 << (32u - sh))) : a1;
+        }
+        uint32_t j = sublist_pos(lane, __popc(cw[0]) + __popc(cw[1]));
         uint32_t* keys = cand_keys + (size_t)b * keys_stride + start;
         uint32_t* hg = hist + ((size_t)b * n_seg + seg) * H_STRIDE + H_L0;
 #pragma unroll
@@ -478,8 +624,7 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
             while (m) {
                 const uint32_t p = __ffs(m) - 1;
                 m &= m - 1;
-                const uint32_t i = start + lane * 64u + 32u * hh + p;
-                if ((core_bits[i >> 5] >> (i & 31u)) & 1u) keys[j] = VOID_KEY;
+                if ((kw[hh] >> p) & 1u) keys[j] = VOID_KEY;
                 else if (one_seg) atomicAdd(&h[keys[j] >> shift0], 1u);
                 else atomicAdd(&hg[keys[j] >> shift0], 1u);
                 ++j;
@@ -492,8 +637,8 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
 
 // ---------------------------------------------------------------------------------------
 // Levels 1 and 2: histogram of the candidates that still match the prefix.  One wave per
-// tile list; equal digits inside a wave are merged before the global atomic.
-// grid (ceil(T/4), nbatch).
+// tile, 16 lanes per sub-tile list; equal digits inside a wave are merged before the
+// global atomic.  grid (ceil(T/4), nbatch).
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(BLOCK) void k_list_hist(const uint32_t* __restrict__ tile_start, const uint32_t* __restrict__ tile_seg,
                                                      uint32_t T, uint32_t n_seg, const SegState* __restrict__ states,
@@ -508,11 +653,12 @@ __global__ __launch_bounds__(BLOCK) void k_list_hist(const uint32_t* __restrict_
     if (st->none) return;
     const uint32_t pshift = st->shift[level - 1], shift = st->shift[level], mask = st->nbins[level] - 1u;
     const uint32_t prefix = st->prefix, voidk = st->has_void;
-    const uint32_t cnt = cnt_cand[(size_t)b * T + t];
-    const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tile_start[t];
+    const uint32_t cnt = cnt_cand[((size_t)b * T + t) * SUBS + (lane >> 4)];
+    const uint32_t maxcnt = max(max(__shfl(cnt, 0, 64), __shfl(cnt, 16, 64)), max(__shfl(cnt, 32, 64), __shfl(cnt, 48, 64)));
+    const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tile_start[t] + (lane >> 4) * SUB;
     uint32_t* hp = hist + ((size_t)b * n_seg + seg) * H_STRIDE + hist_off;
-    for (uint32_t j0 = 0; j0 < cnt; j0 += 64) {
-        const uint32_t j = j0 + lane;
+    for (uint32_t j0 = 0; j0 < maxcnt; j0 += 16) {
+        const uint32_t j = j0 + (lane & 15u);
         bool part = false;
         uint32_t digit = 0;
         if (j < cnt) {
@@ -548,9 +694,9 @@ __global__ __launch_bounds__(BLOCK) void k_count(const uint32_t* __restrict__ ti
     uint32_t sel = 0, tie = 0;
     if (!st->none) {
         const uint32_t tau = st->tau, voidk = st->has_void;
-        const uint32_t cnt = cnt_cand[(size_t)b * T + t];
-        const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tile_start[t];
-        for (uint32_t j = lane; j < cnt; j += 64) {
+        const uint32_t cnt = cnt_cand[((size_t)b * T + t) * SUBS + (lane >> 4)];
+        const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tile_start[t] + (lane >> 4) * SUB;
+        for (uint32_t j = lane & 15u; j < cnt; j += 16) {
             const uint32_t k = keys[j];
             if (voidk && k == VOID_KEY) continue;
             sel += (k > tau) ? 1u : 0u;
@@ -668,8 +814,7 @@ __global__ __launch_bounds__(BLOCK) void k_emit(const uint32_t* __restrict__ til
             gw[0] = g2.x; gw[1] = g2.y;
         }
     }
-    const uint32_t ccnt = __popc(cw[0]) + __popc(cw[1]);
-    uint32_t j = wave_incl_scan(ccnt) - ccnt;
+    uint32_t j = sublist_pos(lane, __popc(cw[0]) + __popc(cw[1]));
     const uint32_t* keys = cand_keys + (size_t)b * keys_stride + start;
     uint32_t selmask[2] = {0u, 0u}, tiemask[2] = {0u, 0u};
 #pragma unroll
