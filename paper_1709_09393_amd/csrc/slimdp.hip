@@ -106,6 +106,7 @@ struct slimdp_ctx {
     bool hist_pending = false;
     const float* hist_score = nullptr;
     int64_t opt_force_fallback = 0;
+    int64_t opt_pack_nbuf = 2;
     // explorer draw announced by slimdp_explore_hint (hint) / already drawn inside slimdp_score (pre)
     struct Draw {
         bool valid = false;
@@ -418,6 +419,7 @@ int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value)
 {
     if (!ctx || !name) return SLIMDP_ERR_INVALID_ARG;
     if (strcmp(name, "explore_force_fallback") == 0) { ctx->opt_force_fallback = value; return SLIMDP_OK; }
+    if (strcmp(name, "pack_nbuf") == 0 && (value == 1 || value == 2)) { ctx->opt_pack_nbuf = value; return SLIMDP_OK; }
     return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_set_option: unknown option '%s'", name);
 }
 
@@ -674,11 +676,19 @@ int slimdp_pack(slimdp_ctx* ctx, uint32_t n_workers, const float* const* g, cons
     }
     rc = check_epoch(ctx, core_epoch);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_gather, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, make_tab<PtrTab>(g, n_workers), 0, n_workers,
-                       ctx->n, core_idx, core_off, make_tab<PtrTab>(expl_idx, n_workers),
-                       make_tab<PtrTab>(expl_off, n_workers), make_tab<MutPtrTab>(core_val, n_workers),
-                       make_tab<MutPtrTab>(expl_val, n_workers), make_tab<MutPtrTab, float*>(nullptr, 0));
-    SLIMDP_LAUNCHED(ctx, "k_gather(pack)");
+    int vec_ok = 1;
+    for (uint32_t q = 0; q < n_workers; ++q) vec_ok = vec_ok && aligned16(g[q]);
+    if (ctx->opt_pack_nbuf == 2)
+        hipLaunchKernelGGL(k_pack_stream<2>, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, make_tab<PtrTab>(g, n_workers),
+                           n_workers, ctx->d_tile_start, core_idx, core_off, make_tab<PtrTab>(expl_idx, n_workers),
+                           make_tab<PtrTab>(expl_off, n_workers), make_tab<MutPtrTab>(core_val, n_workers),
+                           make_tab<MutPtrTab>(expl_val, n_workers), vec_ok);
+    else
+        hipLaunchKernelGGL(k_pack_stream<1>, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, make_tab<PtrTab>(g, n_workers),
+                           n_workers, ctx->d_tile_start, core_idx, core_off, make_tab<PtrTab>(expl_idx, n_workers),
+                           make_tab<PtrTab>(expl_off, n_workers), make_tab<MutPtrTab>(core_val, n_workers),
+                           make_tab<MutPtrTab>(expl_val, n_workers), vec_ok);
+    SLIMDP_LAUNCHED(ctx, "k_pack_stream");
     return SLIMDP_OK;
 }
 

@@ -96,6 +96,14 @@ __device__ __forceinline__ uint32_t elem_scl(int j) { return (uint32_t)j * BLOCK
 
 __device__ __forceinline__ uint32_t mask_below(uint32_t bit) { return (1u << bit) - 1u; }   // bit in 0..31
 
+// 16-byte load of data that is read once (streamed): bypasses cache-line retention.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream4(const float* p)
+{
+    const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
 // ---------------------------------------------------------------------------------------
 // Philox4x32 with 10 rounds (Salmon et al., SC'11): the explorer's random words.
 // Counter (c0, c1, c2, c3), key (k0, k1).

@@ -941,11 +941,97 @@ __global__ __launch_bounds__(BLOCK) void k_gather(PtrTab src, int shared_src, ui
 }
 
 // ---------------------------------------------------------------------------------------
-// K6: merge.  One block per tile of the global model.  Contributions are summed in LDS in
-// worker order (core first: every worker holds it; then each worker's explorer slice),
-// one fused multiply-add applies the sum, and the tile is streamed back.  No atomics.
+// K5 (pack): extraction by streaming, the way the paper puts it ("scanning the whole set").
+// One block per tile.  Each worker's tile of updates is read with full-width coalesced
+// loads into LDS (the next worker's tile is already in flight in registers), and the
+// tile's slice of the core list and of the worker's explorer list is then picked out of
+// LDS and written out contiguously.  (Storing the core values straight from registers at
+// their prefix-sum positions was tried and is slower: many narrow partial-line stores.)
+// NBUF = 2: one barrier per worker; NBUF = 1: two barriers, half the LDS, more blocks per CU.
 // ---------------------------------------------------------------------------------------
-constexpr int MERGE_STAGE = 2048;
+template <int NBUF>
+__global__ __launch_bounds__(BLOCK) void k_pack_stream(PtrTab g, uint32_t nw, const uint32_t* __restrict__ tile_start,
+                                                       const uint32_t* __restrict__ core_idx,
+                                                       const uint32_t* __restrict__ core_off, PtrTab expl_idx,
+                                                       PtrTab expl_off, MutPtrTab core_val, MutPtrTab expl_val, int vec_ok)
+{
+    __shared__ float buf[NBUF][TILE];
+    __shared__ uint32_t elo[MAXW], ehi[MAXW];
+    const uint32_t t = blockIdx.x;
+    const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
+    const bool vec = vec_ok && len == TILE && (start & 3u) == 0;
+    const uint32_t c0 = core_off[t], c1 = core_off[t + 1];
+    if (threadIdx.x < nw) {
+        const uint32_t* eo = static_cast<const uint32_t*>(expl_off.p[threadIdx.x]);
+        elo[threadIdx.x] = eo[t];
+        ehi[threadIdx.x] = eo[t + 1];
+    }
+    float r[EPT];
+    auto fetch = [&](uint32_t q) {
+        const float* src = static_cast<const float*>(g.p[q]) + start;
+        if (vec) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float4 v = *reinterpret_cast<const float4*>(src + k * 1024 + threadIdx.x * 4);
+                r[4 * k + 0] = v.x; r[4 * k + 1] = v.y; r[4 * k + 2] = v.z; r[4 * k + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < EPT; ++j) {
+                const uint32_t e = elem_scl(j);
+                r[j] = (e < len) ? src[e] : 0.0f;
+            }
+        }
+    };
+    fetch(0);
+    for (uint32_t q = 0; q < nw; ++q) {
+        float* b = buf[NBUF == 2 ? (q & 1u) : 0];
+        if (NBUF == 1 && q) __syncthreads();     // the previous worker's readers are done with the buffer
+        if (vec) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                *reinterpret_cast<float4*>(b + k * 1024 + threadIdx.x * 4) = make_float4(r[4 * k], r[4 * k + 1], r[4 * k + 2], r[4 * k + 3]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < EPT; ++j) b[elem_scl(j)] = r[j];
+        }
+        __syncthreads();     // with two buffers this also orders a buffer's readers (two workers ago) before its writers
+        if (q + 1 < nw) fetch(q + 1);
+        float* cv = static_cast<float*>(core_val.p[q]);
+        for (uint32_t j = c0 + threadIdx.x; j < c1; j += BLOCK) {
+            const uint32_t pos = core_idx[j] - start;
+            if (pos < len) cv[j] = b[pos];
+        }
+        const uint32_t* ei = static_cast<const uint32_t*>(expl_idx.p[q]);
+        float* ev = static_cast<float*>(expl_val.p[q]);
+        const uint32_t e1 = ehi[q];
+        for (uint32_t j = elo[q] + threadIdx.x; j < e1; j += BLOCK) {
+            const uint32_t pos = ei[j] - start;
+            if (pos < len) ev[j] = b[pos];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// K6: merge.  One block per tile of the global model; no atomics on global memory and a
+// result that does not depend on scheduling.
+//
+// Core: every worker sends a value for each core index, so the thread that owns entry j of
+// the tile's slice of the core list sums the W values in worker order in registers.
+//
+// Explorers: each entry of the tile takes a ticket at its position (LDS byte counter).  A
+// position with one or two entries is summed in ticket order -- with at most two addends
+// the binary32 sum does not depend on their order.  Positions with three or more entries
+// (rare) go to a short list that one thread replays in worker order.  Tiles with more
+// explorer entries than the fast path holds in registers, or with too many such positions,
+// take the generic path: entries staged through LDS and applied one worker at a time.
+//
+// All loads of a tile (its w, its core slice, its explorer entries) are requested in one
+// go right after the tile's offsets are known.
+// ---------------------------------------------------------------------------------------
+constexpr int MERGE_R = 4;                 // explorer entries per thread kept in registers
+constexpr uint32_t MERGE_HOT_CAP = 256;
+constexpr uint32_t MERGE_STAGE = 512;
 
 __global__ __launch_bounds__(BLOCK) void k_merge(float* __restrict__ w, float lr, uint32_t nw,
                                                  const uint32_t* __restrict__ tile_start,
@@ -954,14 +1040,18 @@ __global__ __launch_bounds__(BLOCK) void k_merge(float* __restrict__ w, float lr
                                                  int vec_ok)
 {
     __shared__ float acc[TILE];
-    __shared__ uint8_t hit[TILE];
+    __shared__ uint32_t cnt[TILE / 4];     // one byte per position: bit 7 = core, low bits = explorer entries
+    __shared__ uint32_t elo[MAXW], ecn[MAXW];
+    __shared__ uint16_t hpos[MERGE_HOT_CAP];
+    __shared__ uint8_t hq[MERGE_HOT_CAP];
+    __shared__ float hval[MERGE_HOT_CAP];
+    __shared__ uint32_t hcount;
     __shared__ uint16_t spos[MERGE_STAGE];
     __shared__ float sval[MERGE_STAGE];
-    __shared__ uint32_t elo[MAXW], epre[MAXW + 1];
     const uint32_t t = blockIdx.x;
     const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
     const bool vec = vec_ok && len == TILE && (start & 3u) == 0;
-    // the tile of w is requested first so that its latency overlaps everything below
+    const uint32_t c0 = core_off[t], c1 = core_off[t + 1];
     float wv[EPT];
     if (vec) {
 #pragma unroll
@@ -976,75 +1066,148 @@ __global__ __launch_bounds__(BLOCK) void k_merge(float* __restrict__ w, float lr
             wv[j] = (e < len) ? w[(size_t)start + e] : 0.0f;
         }
     }
-    for (uint32_t e = threadIdx.x; e < TILE; e += BLOCK) { acc[e] = 0.0f; hit[e] = 0; }
+    for (uint32_t x = threadIdx.x; x < TILE / 4; x += BLOCK) cnt[x] = 0;
+    if (threadIdx.x == 0) hcount = 0;
     if (threadIdx.x < nw) {
         const uint32_t* eo = static_cast<const uint32_t*>(expl_off.p[threadIdx.x]);
-        elo[threadIdx.x] = eo[t];
-        epre[threadIdx.x] = eo[t + 1] - eo[t];      // counts; turned into a prefix below
+        const uint32_t lo = eo[t];
+        elo[threadIdx.x] = lo;
+        ecn[threadIdx.x] = eo[t + 1] - lo;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t run = 0;
-        for (uint32_t q = 0; q < nw; ++q) { const uint32_t c = epre[q]; epre[q] = run; run += c; }
-        epre[nw] = run;
+    uint32_t E = 0;
+    for (uint32_t q = 0; q < nw; ++q) E += ecn[q];
+    const bool fast = E <= (uint32_t)(BLOCK * MERGE_R);
+    // explorer entries of the fast path: requested now, held in registers
+    uint32_t epos[MERGE_R], eq[MERGE_R], etk[MERGE_R];
+    float eval[MERGE_R];
+    if (fast) {
+#pragma unroll
+        for (int i = 0; i < MERGE_R; ++i) {
+            const uint32_t x = threadIdx.x + (uint32_t)i * BLOCK;
+            epos[i] = 0xFFFFFFFFu; eq[i] = 0; etk[i] = 0; eval[i] = 0.0f;
+            if (x < E) {
+                uint32_t q = 0, run = 0;
+                while (q + 1 < nw && run + ecn[q] <= x) { run += ecn[q]; ++q; }
+                const uint32_t j = elo[q] + (x - run);
+                const uint32_t pos = static_cast<const uint32_t*>(expl_idx.p[q])[j] - start;
+                eval[i] = static_cast<const float*>(expl_val.p[q])[j];
+                eq[i] = q;
+                if (pos < len) epos[i] = pos;
+            }
+        }
     }
     // core: every worker contributes, in worker order
-    {
-        const uint32_t c0 = core_off[t], c1 = core_off[t + 1];
-        for (uint32_t j = c0 + threadIdx.x; j < c1; j += BLOCK) {
-            const uint32_t pos = core_idx[j] - start;
-            float a = 0.0f;
-            for (uint32_t q = 0; q < nw; ++q) a = a + static_cast<const float*>(core_val.p[q])[j];
-            if (pos < len) { acc[pos] = a; hit[pos] = 1; }
+    for (uint32_t j = c0 + threadIdx.x; j < c1; j += BLOCK) {
+        const uint32_t pos = core_idx[j] - start;
+        float a = 0.0f;
+        for (uint32_t q = 0; q < nw; ++q) a = a + static_cast<const float*>(core_val.p[q])[j];
+        if (pos < len) { acc[pos] = a; atomicOr(&cnt[pos >> 2], 0x80u << (8u * (pos & 3u))); }
+    }
+    if (fast) {
+#pragma unroll
+        for (int i = 0; i < MERGE_R; ++i) {
+            if (epos[i] != 0xFFFFFFFFu) {
+                const uint32_t sh = 8u * (epos[i] & 3u);
+                etk[i] = (atomicAdd(&cnt[epos[i] >> 2], 1u << sh) >> sh) & 0x7Fu;
+            }
         }
     }
     __syncthreads();
-    // explorers: staged through LDS in chunks, applied one worker at a time
-    const uint32_t E = epre[nw];
-    for (uint32_t cb = 0; cb < E; cb += MERGE_STAGE) {
-        const uint32_t cn = (E - cb < (uint32_t)MERGE_STAGE) ? E - cb : (uint32_t)MERGE_STAGE;
-        for (uint32_t x = threadIdx.x; x < cn; x += BLOCK) {
-            const uint32_t v = cb + x;
-            uint32_t q = 0;
-            while (q + 1 < nw && epre[q + 1] <= v) ++q;
-            const uint32_t j = elo[q] + (v - epre[q]);
-            const uint32_t pos = static_cast<const uint32_t*>(expl_idx.p[q])[j] - start;
-            spos[x] = (pos < len) ? (uint16_t)pos : (uint16_t)0xFFFF;
-            sval[x] = static_cast<const float*>(expl_val.p[q])[j];
+    uint32_t nhot = 0;
+    if (fast) {
+        // first and second entry of a position, in ticket order; the rest is replayed in worker order
+        uint32_t tot[MERGE_R];
+#pragma unroll
+        for (int i = 0; i < MERGE_R; ++i) {
+            tot[i] = 0;
+            if (epos[i] != 0xFFFFFFFFu) {
+                const uint32_t byte = (cnt[epos[i] >> 2] >> (8u * (epos[i] & 3u))) & 0xFFu;
+                tot[i] = byte & 0x7Fu;
+                if (tot[i] <= 2u) {
+                    if (etk[i] == 0) acc[epos[i]] = ((byte & 0x80u) ? acc[epos[i]] : 0.0f) + eval[i];
+                } else {
+                    const uint32_t slot = atomicAdd(&hcount, 1u);
+                    if (slot < MERGE_HOT_CAP) { hpos[slot] = (uint16_t)epos[i]; hq[slot] = (uint8_t)eq[i]; hval[slot] = eval[i]; }
+                }
+            }
         }
         __syncthreads();
-        for (uint32_t q = 0; q < nw; ++q) {
-            const uint32_t lo = (epre[q] > cb) ? epre[q] - cb : 0u;
-            const uint32_t hi_abs = epre[q + 1];
-            if (hi_abs <= cb) continue;
-            const uint32_t hi = (hi_abs - cb < cn) ? hi_abs - cb : cn;
-            if (lo >= hi) continue;
-            for (uint32_t x = lo + threadIdx.x; x < hi; x += BLOCK) {
-                const uint32_t pos = spos[x];
-                if (pos != 0xFFFFu) { acc[pos] = acc[pos] + sval[x]; hit[pos] = 1; }
+#pragma unroll
+        for (int i = 0; i < MERGE_R; ++i)
+            if (epos[i] != 0xFFFFFFFFu && tot[i] == 2u && etk[i] == 1u) acc[epos[i]] = acc[epos[i]] + eval[i];
+        nhot = hcount;
+        if (nhot && nhot <= MERGE_HOT_CAP && threadIdx.x == 0) {
+            for (uint32_t i = 0; i < nhot; ++i) {
+                const uint32_t pos = hpos[i];
+                if (!((cnt[pos >> 2] >> (8u * (pos & 3u))) & 0x80u)) acc[pos] = 0.0f;
+            }
+            for (uint32_t q = 0; q < nw; ++q)
+                for (uint32_t i = 0; i < nhot; ++i)
+                    if (hq[i] == q) acc[hpos[i]] = acc[hpos[i]] + hval[i];
+        }
+    }
+    __syncthreads();
+    if (!fast || nhot > MERGE_HOT_CAP) {
+        // generic path: every explorer entry staged through LDS, applied one worker at a time.
+        // The counters keep their core bits; a set low bit now means "an explorer sum is in acc".
+        for (uint32_t x = threadIdx.x; x < TILE / 4; x += BLOCK) cnt[x] &= 0x80808080u;
+        if (nhot > MERGE_HOT_CAP) {       // the fast path wrote partial sums over core sums: redo the core
+            __syncthreads();
+            for (uint32_t j = c0 + threadIdx.x; j < c1; j += BLOCK) {
+                const uint32_t pos = core_idx[j] - start;
+                float a = 0.0f;
+                for (uint32_t q = 0; q < nw; ++q) a = a + static_cast<const float*>(core_val.p[q])[j];
+                if (pos < len) acc[pos] = a;
+            }
+        }
+        __syncthreads();
+        uint8_t* hit = reinterpret_cast<uint8_t*>(cnt);
+        for (uint32_t cb = 0; cb < E; cb += MERGE_STAGE) {
+            const uint32_t cn = (E - cb < MERGE_STAGE) ? E - cb : MERGE_STAGE;
+            for (uint32_t x = threadIdx.x; x < cn; x += BLOCK) {
+                const uint32_t v = cb + x;
+                uint32_t q = 0, run = 0;
+                while (q + 1 < nw && run + ecn[q] <= v) { run += ecn[q]; ++q; }
+                const uint32_t j = elo[q] + (v - run);
+                const uint32_t pos = static_cast<const uint32_t*>(expl_idx.p[q])[j] - start;
+                spos[x] = (pos < len) ? (uint16_t)pos : (uint16_t)0xFFFF;
+                sval[x] = static_cast<const float*>(expl_val.p[q])[j];
+            }
+            __syncthreads();
+            uint32_t run = 0;
+            for (uint32_t q = 0; q < nw; ++q) {
+                const uint32_t qlo = run, qhi = run + ecn[q];
+                run = qhi;
+                if (qhi <= cb || qlo >= cb + cn) continue;
+                const uint32_t lo = (qlo > cb) ? qlo - cb : 0u;
+                const uint32_t hi = (qhi - cb < cn) ? qhi - cb : cn;
+                for (uint32_t x = lo + threadIdx.x; x < hi; x += BLOCK) {
+                    const uint32_t pos = spos[x];
+                    if (pos != 0xFFFFu) {
+                        acc[pos] = (hit[pos] ? acc[pos] : 0.0f) + sval[x];
+                        hit[pos] |= 1;
+                    }
+                }
+                __syncthreads();
             }
             __syncthreads();
         }
-        __syncthreads();
     }
     // apply and stream the tile back
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const uint32_t e = vec ? elem_vec(j) : elem_scl(j);
+        if (e < len && ((cnt[e >> 2] >> (8u * (e & 3u))) & 0xFFu)) {
+            wv[j] = __builtin_fmaf(-lr, acc[e], wv[j]);
+            if (!vec) w[(size_t)start + e] = wv[j];
+        }
+    }
     if (vec) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            float o[4];
-#pragma unroll
-            for (int cc = 0; cc < 4; ++cc) {
-                const uint32_t e = elem_vec(4 * r + cc);
-                o[cc] = hit[e] ? __builtin_fmaf(-lr, acc[e], wv[4 * r + cc]) : wv[4 * r + cc];
-            }
-            *reinterpret_cast<float4*>(w + (size_t)start + r * 1024 + threadIdx.x * 4) = make_float4(o[0], o[1], o[2], o[3]);
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < EPT; ++j) {
-            const uint32_t e = elem_scl(j);
-            if (e < len && hit[e]) w[(size_t)start + e] = __builtin_fmaf(-lr, acc[e], wv[j]);
-        }
+        for (int r = 0; r < 4; ++r)
+            *reinterpret_cast<float4*>(w + (size_t)start + r * 1024 + threadIdx.x * 4) =
+                make_float4(wv[4 * r], wv[4 * r + 1], wv[4 * r + 2], wv[4 * r + 3]);
     }
 }
 
