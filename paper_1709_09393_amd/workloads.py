@@ -24,6 +24,16 @@ def gradient_seed(iteration: int, worker: int) -> int:
     return 1000 * iteration + worker + 1
 
 
+def round_through_fp16(a: np.ndarray) -> np.ndarray:
+    """binary32 -> binary16 (round to nearest even) -> binary32.  torch's cast is the same IEEE
+    conversion as NumPy's and many times faster on 1e8 elements; either gives the same bits."""
+    try:
+        import torch
+        return torch.from_numpy(np.ascontiguousarray(a)).to(torch.float16).to(torch.float32).numpy()
+    except ImportError:
+        return a.astype(np.float16).astype(np.float32)
+
+
 @dataclass(frozen=True)
 class Workload:
     name: str
@@ -95,7 +105,7 @@ class Workload:
             return w
         if self.weight_dist == "laplace_fp16":
             w = rng.laplace(0.0, self.weight_scale, size=self.n).astype(np.float32)
-            return w.astype(np.float16).astype(np.float32)
+            return round_through_fp16(w)
         if self.weight_dist == "fan_in":
             # per segment: variance 2 / fan_in with fan_in = segment size / 64
             off = self.segment_offsets().astype(np.int64)
@@ -111,7 +121,7 @@ class Workload:
         g = rng.standard_normal(self.n, dtype=np.float32)
         g *= np.float32(self.grad_sigma)
         if self.grad_fp16:
-            g = g.astype(np.float16).astype(np.float32)
+            g = round_through_fp16(g)
         return g
 
     def gradients(self, iteration: int = 0) -> List[np.ndarray]:
