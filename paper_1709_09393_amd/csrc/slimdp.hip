@@ -218,6 +218,7 @@ uint32_t persistent_blocks(const slimdp_ctx* c, uint32_t per_cu, uint32_t nbatch
 
 // Levels 1, 2, per-tile counts, scan over tiles and ordered emission, shared by the core
 // (after k_core_build, which already filled the level-1 histogram) and the explorer.
+template <int KPL>
 int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* hist, const uint32_t* gt_bits,
                      const uint32_t* cand_bits, const uint32_t* cand_keys, const uint32_t* cnt_gt,
                      const uint32_t* cnt_cand, uint32_t* cnt_sel, uint32_t* cnt_tie, uint32_t* tie_pre,
@@ -227,26 +228,26 @@ int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* his
     const uint32_t T = c->T, S = c->n_seg;
     const dim3 wave_grid((T + 3) / 4, nbatch);
     if (!level1_done) {
-        hipLaunchKernelGGL(k_list_hist, wave_grid, dim3(BLOCK), 0, c->stream, c->d_tile_start, c->d_tile_seg, T, S, st,
-                           hist, (uint32_t)H_L1, 1, cand_keys, cnt_cand, keys_stride);
+        hipLaunchKernelGGL(k_list_hist<KPL>, wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg, T, S,
+                           st, hist, (uint32_t)H_L1, 1, cand_keys, cnt_cand, keys_stride);
         SLIMDP_LAUNCHED(c, "k_list_hist(1)");
     }
     hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 1, (uint32_t)H_L1, S, 0, c->d_flags);
     SLIMDP_LAUNCHED(c, "k_threshold(1)");
-    hipLaunchKernelGGL(k_list_hist, wave_grid, dim3(BLOCK), 0, c->stream, c->d_tile_start, c->d_tile_seg, T, S, st, hist,
-                       (uint32_t)H_L2, 2, cand_keys, cnt_cand, keys_stride);
+    hipLaunchKernelGGL(k_list_hist<KPL>, wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg, T, S, st,
+                       hist, (uint32_t)H_L2, 2, cand_keys, cnt_cand, keys_stride);
     SLIMDP_LAUNCHED(c, "k_list_hist(2)");
     hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 2, (uint32_t)H_L2, S, 0, c->d_flags);
     SLIMDP_LAUNCHED(c, "k_threshold(2)");
-    hipLaunchKernelGGL(k_count, wave_grid, dim3(BLOCK), 0, c->stream, c->d_tile_start, c->d_tile_seg, T, S, st, cand_keys,
-                       cnt_cand, cnt_gt, keys_stride, cnt_sel, cnt_tie);
+    hipLaunchKernelGGL(k_count<KPL>, wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg, T, S, st,
+                       cand_keys, cnt_cand, cnt_gt, keys_stride, cnt_sel, cnt_tie);
     SLIMDP_LAUNCHED(c, "k_count");
     hipLaunchKernelGGL(k_scan, dim3(1, nbatch), dim3(1024), 0, c->stream, c->d_tile_seg, c->d_seg_first_tile, T, S, st,
                        cnt_sel, cnt_tie, tie_pre, out_off, expected, c->d_flags);
     SLIMDP_LAUNCHED(c, "k_scan");
     PtrTab off_ro;
     for (int q = 0; q < MAXW; ++q) off_ro.p[q] = out_off.p[q];
-    hipLaunchKernelGGL(k_emit, wave_grid, dim3(BLOCK), 0, c->stream, c->d_tile_start, c->d_tile_seg,
+    hipLaunchKernelGGL(k_emit<KPL>, wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg,
                        c->d_seg_first_tile, T, S, st, gt_bits, cand_bits, cand_keys, keys_stride, tie_pre, off_ro, out_idx,
                        expected, pub_bits);
     SLIMDP_LAUNCHED(c, "k_emit");
@@ -340,7 +341,7 @@ uint64_t slimdp_workspace_bytes(uint64_t n, uint32_t max_workers, uint32_t n_seg
     slimdp_ctx tmp;
     tmp.n = n; tmp.maxW = max_workers; tmp.n_seg = n_seg;
     tmp.T = (uint32_t)count_tiles(n, n_seg, seg_off);
-    tmp.keys_stride = align_up(n, 64);
+    tmp.keys_stride = align_up(n, TILE) + TILE;
     Carver cv(nullptr);
     carve(&tmp, cv);
     return align_up(cv.pos, 256);
@@ -366,7 +367,7 @@ int slimdp_create(slimdp_ctx** out, uint64_t n, uint32_t max_workers, uint32_t n
     c->seg_off.assign(seg_off, seg_off + n_seg + 1);
     c->tl = make_tiling(n, n_seg, seg_off);
     c->T = (uint32_t)c->tl.tile_seg.size();
-    c->keys_stride = align_up(n, 64);
+    c->keys_stride = align_up(n, TILE) + TILE;
     hipError_t e = hipGetDevice(&c->device);
     if (e != hipSuccess) { int rc = hip_fail(nullptr, e, "hipGetDevice (no usable GPU?)"); delete c; return rc; }
     hipDeviceProp_t prop;
@@ -543,7 +544,7 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
     MutPtrTab off_tab = make_tab<MutPtrTab, uint32_t*>(&core_off, 1);
     MutPtrTab idx_tab = make_tab<MutPtrTab, uint32_t*>(&core_idx, 1);
     uint32_t* pub = ctx->tl.word_aligned ? core_bits : nullptr;
-    rc = finish_selection(ctx, 1, ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys,
+    rc = finish_selection<CORE_KPL>(ctx, 1, ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys,
                           ctx->c_cnt_gt, ctx->c_cnt_cand, ctx->c_cnt_sel, ctx->c_cnt_tie, ctx->c_tie_pre, ctx->keys_stride,
                           true, off_tab, idx_tab, (uint32_t)K, pub);
     if (rc) return rc;
@@ -589,7 +590,7 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
     const PhiloxKey pk{(uint32_t)ctx->seed, (uint32_t)(ctx->seed >> 32), (uint32_t)iteration, (uint32_t)(iteration >> 32)};
     for (int fb = 0; fb < 2; ++fb) {
         if (fb == 0 && cached) {
-            hipLaunchKernelGGL(k_explore_filter, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->d_tile_start,
+            hipLaunchKernelGGL(k_explore_filter, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->n, ctx->d_tile_start,
                                ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_cand_bits, ctx->e_cand_keys,
                                ctx->keys_stride, (uint32_t)((ctx->n + 31) / 32));
             SLIMDP_LAUNCHED(ctx, "k_explore_filter");
@@ -610,7 +611,7 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
     }
     MutPtrTab off_tab = make_tab<MutPtrTab>(expl_off, B);
     MutPtrTab idx_tab = make_tab<MutPtrTab>(expl_idx, B);
-    return finish_selection(ctx, B, ctx->e_state, ctx->e_hist, nullptr, ctx->e_cand_bits, ctx->e_cand_keys, nullptr,
+    return finish_selection<EXPL_KPL>(ctx, B, ctx->e_state, ctx->e_hist, nullptr, ctx->e_cand_bits, ctx->e_cand_keys, nullptr,
                             ctx->e_cnt_cand, ctx->e_cnt_sel, ctx->e_cnt_tie, ctx->e_tie_pre, ctx->keys_stride, false,
                             off_tab, idx_tab, (uint32_t)M, nullptr);
 }

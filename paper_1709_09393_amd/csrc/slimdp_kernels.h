@@ -572,12 +572,41 @@ __device__ __forceinline__ uint32_t sublist_pos(uint32_t lane, uint32_t my_count
     return (lane >> 4) * SUB + (excl - group0);
 }
 
+// Where a tile is.  Flat model: no table look-ups, so that every load a tail kernel needs
+// can be requested at once.
+struct TileRef { uint32_t seg, start, len; };
+__device__ __forceinline__ TileRef tile_ref(uint32_t t, uint32_t n_seg, uint64_t n, const uint32_t* __restrict__ tile_start,
+                                            const uint32_t* __restrict__ tile_seg)
+{
+    TileRef r;
+    if (n_seg == 1) {
+        r.seg = 0; r.start = t * TILE;
+        const uint64_t rest = n - (uint64_t)r.start;
+        r.len = rest < TILE ? (uint32_t)rest : TILE;
+    } else {
+        r.seg = tile_seg[t]; r.start = tile_start[t]; r.len = tile_start[t + 1] - r.start;
+    }
+    return r;
+}
+
+// The first 16*KPL keys of each of a tile's four sub-lists, requested without waiting for
+// the lists' lengths (the slots exist whatever the length; the unused ones are ignored):
+// lane (s = lane/16, r = lane%16) holds entries r, r+16, ... of sub-list s.
+template <int KPL>
+__device__ __forceinline__ void load_sublists(const uint32_t* __restrict__ keys_tile, uint32_t lane, uint32_t kv[KPL])
+{
+    const uint32_t* p = keys_tile + (lane >> 4) * SUB + (lane & 15u);
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) kv[i] = p[16 * i];
+}
+
 // After a presampling pass: candidates that turned out to be core parameters get the void
 // key (never selected, never counted); the others feed the level-0 histogram.
 // One wave per tile.  grid (blocks, n_workers), persistent so that the histogram stays in LDS.
 constexpr uint32_t VOID_KEY = 0xFFFFFFFFu;
+constexpr int EXPL_KPL = 2, CORE_KPL = 4;
 
-__global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __restrict__ core_bits,
+__global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __restrict__ core_bits, uint64_t n,
                                                           const uint32_t* __restrict__ tile_start,
                                                           const uint32_t* __restrict__ tile_seg, uint32_t T,
                                                           uint32_t n_seg, const SegState* __restrict__ states,
@@ -586,6 +615,7 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
                                                           uint32_t n_words)
 {
     __shared__ uint32_t h[4096];
+    __shared__ uint32_t kb[4][SUBS * 16 * EXPL_KPL];
     const uint32_t b = blockIdx.y, lane = lane_id(), wid = threadIdx.x >> 6;
     for (uint32_t x = threadIdx.x; x < 4096; x += BLOCK) h[x] = 0;
     __syncthreads();
@@ -593,43 +623,49 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
     const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
     if (t0 >= t1) return;
     // one segment per block range: histogram in LDS; otherwise straight to global memory
-    const uint32_t seg_first = tile_seg[t0];
-    const bool one_seg = seg_first == tile_seg[t1 - 1];
+    const uint32_t seg_first = (n_seg == 1) ? 0u : tile_seg[t0];
+    const bool one_seg = (n_seg == 1) || seg_first == tile_seg[t1 - 1];
     for (uint32_t t = t0 + wid; t < t1; t += 4) {
-        const uint32_t seg = tile_seg[t];
-        const SegState* st = &states[(size_t)b * n_seg + seg];
-        if (st->need0 == 0) continue;
-        const uint32_t shift0 = st->shift[0];
-        const uint32_t start = tile_start[t];
+        const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
+        const SegState* st = &states[(size_t)b * n_seg + tr.seg];
+        uint32_t* keys = cand_keys + (size_t)b * keys_stride + tr.start;
+        // everything this tile needs is requested here, before any of it is used
         const uint2 c2 = *reinterpret_cast<const uint2*>(cand_bits + ((size_t)b * T + t) * TILE_WORDS + 2 * lane);
+        uint32_t kv[EXPL_KPL];
+        load_sublists<EXPL_KPL>(keys, lane, kv);
+        const uint32_t i0 = tr.start + lane * 64u;      // core bits of this lane's 64 parameters
+        const uint32_t sh = i0 & 31u, wi = i0 >> 5;
+        const uint32_t a0 = (wi < n_words) ? core_bits[wi] : 0u;
+        const uint32_t a1 = (wi + 1 < n_words) ? core_bits[wi + 1] : 0u;
+        const uint32_t a2 = (sh && wi + 2 < n_words) ? core_bits[wi + 2] : 0u;
+        const uint32_t need0 = st->need0, shift0 = st->shift[0];
+        if (need0 == 0) continue;
         const uint32_t cw[2] = {c2.x, c2.y};
-        // core bits of this lane's 64 parameters (a tile may start inside a bitmap word)
-        const uint32_t i0 = start + lane * 64u;
-        const uint32_t sh = i0 & 31u;
-        const uint32_t wi = i0 >> 5;
-        uint32_t kw[2] = {0u, 0u};
-        if (cw[0] | cw[1]) {                       // then i0 < n, so word wi exists
-            const uint32_t a0 = core_bits[wi];
-            const uint32_t a1 = (wi + 1 < n_words) ? core_bits[wi + 1] : 0u;
-            const uint32_t a2 = (sh && wi + 2 < n_words) ? core_bits[wi + 2] : 0u;
-            kw[0] = sh ? ((a0 >> sh) | (a1 << (32u - sh))) : a0;
-            kw[1] = sh ? ((a1 >> sh) | (a2 << (32u - sh))) : a1;
-        }
-        uint32_t j = sublist_pos(lane, __popc(cw[0]) + __popc(cw[1]));
-        uint32_t* keys = cand_keys + (size_t)b * keys_stride + start;
-        uint32_t* hg = hist + ((size_t)b * n_seg + seg) * H_STRIDE + H_L0;
+        const uint32_t kw[2] = {sh ? ((a0 >> sh) | (a1 << (32u - sh))) : a0, sh ? ((a1 >> sh) | (a2 << (32u - sh))) : a1};
+        uint32_t* kbw = kb[wid];
+#pragma unroll
+        for (int i = 0; i < EXPL_KPL; ++i) kbw[(lane >> 4) * (16 * EXPL_KPL) + (lane & 15u) + 16 * i] = kv[i];
+        wave_sync();
+        const uint32_t pos = sublist_pos(lane, __popc(cw[0]) + __popc(cw[1]));
+        const uint32_t sub = pos >> 10;
+        uint32_t j = pos & (SUB - 1u);
+        uint32_t* hg = hist + ((size_t)b * n_seg + tr.seg) * H_STRIDE + H_L0;
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
             uint32_t m = cw[hh];
             while (m) {
                 const uint32_t p = __ffs(m) - 1;
                 m &= m - 1;
-                if ((kw[hh] >> p) & 1u) keys[j] = VOID_KEY;
-                else if (one_seg) atomicAdd(&h[keys[j] >> shift0], 1u);
-                else atomicAdd(&hg[keys[j] >> shift0], 1u);
+                if ((kw[hh] >> p) & 1u) keys[sub * SUB + j] = VOID_KEY;
+                else {
+                    const uint32_t key = (j < 16u * EXPL_KPL) ? kbw[sub * (16 * EXPL_KPL) + j] : keys[sub * SUB + j];
+                    if (one_seg) atomicAdd(&h[key >> shift0], 1u);
+                    else atomicAdd(&hg[key >> shift0], 1u);
+                }
                 ++j;
             }
         }
+        wave_sync();
     }
     __syncthreads();
     if (one_seg) flush_hist(h, 4096, hist + ((size_t)b * n_seg + seg_first) * H_STRIDE + H_L0);
@@ -640,32 +676,37 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
 // tile, 16 lanes per sub-tile list; equal digits inside a wave are merged before the
 // global atomic.  grid (ceil(T/4), nbatch).
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void k_list_hist(const uint32_t* __restrict__ tile_start, const uint32_t* __restrict__ tile_seg,
-                                                     uint32_t T, uint32_t n_seg, const SegState* __restrict__ states,
-                                                     uint32_t* __restrict__ hist, uint32_t hist_off, int level,
-                                                     const uint32_t* __restrict__ cand_keys, const uint32_t* __restrict__ cnt_cand,
-                                                     uint64_t keys_stride)
+template <int KPL>
+__global__ __launch_bounds__(BLOCK) void k_list_hist(uint64_t n, const uint32_t* __restrict__ tile_start,
+                                                     const uint32_t* __restrict__ tile_seg, uint32_t T, uint32_t n_seg,
+                                                     const SegState* __restrict__ states, uint32_t* __restrict__ hist,
+                                                     uint32_t hist_off, int level, const uint32_t* __restrict__ cand_keys,
+                                                     const uint32_t* __restrict__ cnt_cand, uint64_t keys_stride)
 {
     const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b = blockIdx.y, lane = lane_id();
     if (t >= T) return;
-    const uint32_t seg = tile_seg[t];
-    const SegState* st = &states[(size_t)b * n_seg + seg];
+    const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
+    const SegState* st = &states[(size_t)b * n_seg + tr.seg];
+    const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tr.start + (lane >> 4) * SUB;
+    uint32_t kv[KPL];
+    load_sublists<KPL>(cand_keys + (size_t)b * keys_stride + tr.start, lane, kv);
+    const uint32_t cnt = cnt_cand[((size_t)b * T + t) * SUBS + (lane >> 4)];
     if (st->none) return;
     const uint32_t pshift = st->shift[level - 1], shift = st->shift[level], mask = st->nbins[level] - 1u;
     const uint32_t prefix = st->prefix, voidk = st->has_void;
-    const uint32_t cnt = cnt_cand[((size_t)b * T + t) * SUBS + (lane >> 4)];
     const uint32_t maxcnt = max(max(__shfl(cnt, 0, 64), __shfl(cnt, 16, 64)), max(__shfl(cnt, 32, 64), __shfl(cnt, 48, 64)));
-    const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tile_start[t] + (lane >> 4) * SUB;
-    uint32_t* hp = hist + ((size_t)b * n_seg + seg) * H_STRIDE + hist_off;
+    uint32_t* hp = hist + ((size_t)b * n_seg + tr.seg) * H_STRIDE + hist_off;
     for (uint32_t j0 = 0; j0 < maxcnt; j0 += 16) {
         const uint32_t j = j0 + (lane & 15u);
-        bool part = false;
-        uint32_t digit = 0;
-        if (j < cnt) {
-            const uint32_t k = keys[j];
-            part = (k >> pshift) == prefix && !(voidk && k == VOID_KEY);
-            digit = (k >> shift) & mask;
+        uint32_t k = 0;
+        if (j0 < 16u * KPL) {
+#pragma unroll
+            for (int i = 0; i < KPL; ++i) if (j0 == 16u * i) k = kv[i];
+        } else if (j < cnt) {
+            k = keys[j];
         }
+        bool part = (j < cnt) && (k >> pshift) == prefix && !(voidk && k == VOID_KEY);
+        const uint32_t digit = (k >> shift) & mask;
         unsigned long long active = __ballot(part);
         while (active) {
             const int leader = __ffsll((long long)active) - 1;
@@ -682,50 +723,69 @@ __global__ __launch_bounds__(BLOCK) void k_list_hist(const uint32_t* __restrict_
 // Per-tile counts once tau is known: selected-for-sure (gt + keys > tau) and ties (== tau).
 // One wave per tile.  grid (ceil(T/4), nbatch).
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void k_count(const uint32_t* __restrict__ tile_start, const uint32_t* __restrict__ tile_seg,
-                                                 uint32_t T, uint32_t n_seg, const SegState* __restrict__ states,
-                                                 const uint32_t* __restrict__ cand_keys, const uint32_t* __restrict__ cnt_cand,
-                                                 const uint32_t* __restrict__ cnt_gt, uint64_t keys_stride,
-                                                 uint32_t* __restrict__ cnt_sel, uint32_t* __restrict__ cnt_tie)
+template <int KPL>
+__global__ __launch_bounds__(BLOCK) void k_count(uint64_t n, const uint32_t* __restrict__ tile_start,
+                                                 const uint32_t* __restrict__ tile_seg, uint32_t T, uint32_t n_seg,
+                                                 const SegState* __restrict__ states, const uint32_t* __restrict__ cand_keys,
+                                                 const uint32_t* __restrict__ cnt_cand, const uint32_t* __restrict__ cnt_gt,
+                                                 uint64_t keys_stride, uint32_t* __restrict__ cnt_sel,
+                                                 uint32_t* __restrict__ cnt_tie)
 {
     const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b = blockIdx.y, lane = lane_id();
     if (t >= T) return;
-    const SegState* st = &states[(size_t)b * n_seg + tile_seg[t]];
+    const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
+    const SegState* st = &states[(size_t)b * n_seg + tr.seg];
+    const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tr.start + (lane >> 4) * SUB;
+    uint32_t kv[KPL];
+    load_sublists<KPL>(cand_keys + (size_t)b * keys_stride + tr.start, lane, kv);
+    const uint32_t cnt = cnt_cand[((size_t)b * T + t) * SUBS + (lane >> 4)];
+    const uint32_t gtc = cnt_gt ? cnt_gt[t] : 0u;
     uint32_t sel = 0, tie = 0;
     if (!st->none) {
         const uint32_t tau = st->tau, voidk = st->has_void;
-        const uint32_t cnt = cnt_cand[((size_t)b * T + t) * SUBS + (lane >> 4)];
-        const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tile_start[t] + (lane >> 4) * SUB;
-        for (uint32_t j = lane & 15u; j < cnt; j += 16) {
+#pragma unroll
+        for (int i = 0; i < KPL; ++i) {
+            const uint32_t k = kv[i];
+            if ((lane & 15u) + 16u * i < cnt && !(voidk && k == VOID_KEY)) {
+                sel += (k > tau) ? 1u : 0u;
+                tie += (k == tau) ? 1u : 0u;
+            }
+        }
+        for (uint32_t j = (lane & 15u) + 16u * KPL; j < cnt; j += 16) {
             const uint32_t k = keys[j];
             if (voidk && k == VOID_KEY) continue;
             sel += (k > tau) ? 1u : 0u;
             tie += (k == tau) ? 1u : 0u;
         }
-        sel = wave_sum(sel);
+        sel = wave_sum(sel) + gtc;
         tie = wave_sum(tie);
-        if (cnt_gt) sel += cnt_gt[t];
     }
     if (lane == 0) { cnt_sel[(size_t)b * T + t] = sel; cnt_tie[(size_t)b * T + t] = tie; }
 }
 
 // ---------------------------------------------------------------------------------------
 // Scan over tiles: global tie prefix, then how many ties each tile takes under its
-// segment's quota, then the output offset of every tile.  grid (1, nbatch), 1024 threads:
-// each wave owns a contiguous range of tiles and walks it 64 tiles at a time with
-// coalesced loads and a wave scan.
+// segment's quota, then the output offset of every tile.  grid (1, nbatch), 1024 threads.
+// The tiles go through LDS in chunks of 8192: coalesced loads, each thread scans eight
+// consecutive values (padded rows, no bank conflicts), one block scan per chunk.
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t tile_out_count(uint32_t t, const uint32_t* __restrict__ cs, const uint32_t* __restrict__ ct,
-                                                   const uint32_t* __restrict__ tp, const uint32_t* __restrict__ tile_seg,
-                                                   const uint32_t* __restrict__ seg_first_tile,
-                                                   const SegState* __restrict__ st)
+constexpr uint32_t SCAN_CHUNK = 8192, SCAN_PER = SCAN_CHUNK / 1024;
+__device__ __forceinline__ uint32_t scan_phys(uint32_t x) { return x + (x >> 3); }     // one pad word per thread row
+
+// vals: SCAN_CHUNK*9/8 words; tb: 1024 words; wtot: 16 words.  Values of the chunk are already in
+// vals (physical layout).  On return vals holds each value's exclusive prefix inside the chunk.
+__device__ __forceinline__ uint32_t scan_chunk(uint32_t* vals, uint32_t* wtot)
 {
-    const uint32_t seg = tile_seg[t];
-    const uint32_t base = tp[t] - tp[seg_first_tile[seg]];
-    const uint32_t q = st[seg].quota;
-    const uint32_t room = (q > base) ? q - base : 0u;
-    const uint32_t c = ct[t];
-    return cs[t] + (room < c ? room : c);
+    uint32_t s = 0;
+    const uint32_t row = threadIdx.x * (SCAN_PER + 1);
+#pragma unroll
+    for (uint32_t e = 0; e < SCAN_PER; ++e) { const uint32_t v = vals[row + e]; vals[row + e] = s; s += v; }
+    uint32_t total;
+    const uint32_t base = block_excl_scan<16>(s, wtot, total);
+#pragma unroll
+    for (uint32_t e = 0; e < SCAN_PER; ++e) vals[row + e] += base;
+    __syncthreads();
+    return total;
 }
 
 __global__ __launch_bounds__(1024) void k_scan(const uint32_t* __restrict__ tile_seg, const uint32_t* __restrict__ seg_first_tile,
@@ -734,56 +794,51 @@ __global__ __launch_bounds__(1024) void k_scan(const uint32_t* __restrict__ tile
                                                uint32_t* __restrict__ tie_pre, MutPtrTab out_off, uint32_t expected,
                                                uint32_t* __restrict__ flags)
 {
-    __shared__ uint32_t wsum[16];
-    const uint32_t b = blockIdx.y, lane = lane_id(), wid = threadIdx.x >> 6;
+    __shared__ uint32_t vals[SCAN_CHUNK + SCAN_CHUNK / 8];
+    __shared__ uint32_t wtot[16];
+    const uint32_t b = blockIdx.y;
     const uint32_t* cs = cnt_sel + (size_t)b * T;
     const uint32_t* ct = cnt_tie + (size_t)b * T;
     const SegState* st = states + (size_t)b * n_seg;
     uint32_t* tp = tie_pre + (size_t)b * (T + 1);
     uint32_t* off = static_cast<uint32_t*>(out_off.p[b]);
-    const uint32_t per = ((T + 15u) / 16u + 63u) / 64u * 64u;       // tiles per wave, multiple of 64
-    const uint32_t r0 = wid * per;
-    const uint32_t r1 = (r0 + per < T) ? r0 + per : T;
-    // ---- ties: wave totals, then the prefix -------------------------------------------
-    uint32_t s = 0;
-#pragma unroll 4
-    for (uint32_t t = r0 + lane; t < r1; t += 64) s += ct[t];
-    s = wave_sum(s);
-    if (lane == 0) wsum[wid] = s;
-    __syncthreads();
-    uint32_t run = 0, total = 0;
-    for (uint32_t w = 0; w < 16; ++w) { const uint32_t x = wsum[w]; if (w < wid) run += x; total += x; }
-    __syncthreads();
-#pragma unroll 4
-    for (uint32_t t0 = r0; t0 < r1; t0 += 64) {
-        const uint32_t t = t0 + lane;
-        const uint32_t v = (t < r1) ? ct[t] : 0u;
-        const uint32_t incl = wave_incl_scan(v);
-        if (t < r1) tp[t] = run + incl - v;
-        run += __shfl(incl, 63, 64);
+    // ---- ties ---------------------------------------------------------------------------
+    uint32_t carry = 0;
+    for (uint32_t c0 = 0; c0 < T; c0 += SCAN_CHUNK) {
+        for (uint32_t x = threadIdx.x; x < SCAN_CHUNK; x += 1024) vals[scan_phys(x)] = (c0 + x < T) ? ct[c0 + x] : 0u;
+        __syncthreads();
+        const uint32_t total = scan_chunk(vals, wtot);
+        for (uint32_t x = threadIdx.x; x < SCAN_CHUNK && c0 + x < T; x += 1024) tp[c0 + x] = carry + vals[scan_phys(x)];
+        carry += total;
+        __syncthreads();
     }
-    if (threadIdx.x == 0) tp[T] = total;
-    __syncthreads();      // tp written by other waves is read below
-    // ---- output offsets ---------------------------------------------------------------
-    s = 0;
-#pragma unroll 2
-    for (uint32_t t = r0 + lane; t < r1; t += 64) s += tile_out_count(t, cs, ct, tp, tile_seg, seg_first_tile, st);
-    s = wave_sum(s);
-    if (lane == 0) wsum[wid] = s;
-    __syncthreads();
-    run = 0; total = 0;
-    for (uint32_t w = 0; w < 16; ++w) { const uint32_t x = wsum[w]; if (w < wid) run += x; total += x; }
-#pragma unroll 2
-    for (uint32_t t0 = r0; t0 < r1; t0 += 64) {
-        const uint32_t t = t0 + lane;
-        const uint32_t v = (t < r1) ? tile_out_count(t, cs, ct, tp, tile_seg, seg_first_tile, st) : 0u;
-        const uint32_t incl = wave_incl_scan(v);
-        if (t < r1) off[t] = run + incl - v;
-        run += __shfl(incl, 63, 64);
+    if (threadIdx.x == 0) tp[T] = carry;
+    __syncthreads();      // tp written by other threads of this block is read below
+    // ---- output offsets -------------------------------------------------------------------
+    carry = 0;
+    for (uint32_t c0 = 0; c0 < T; c0 += SCAN_CHUNK) {
+        for (uint32_t x = threadIdx.x; x < SCAN_CHUNK; x += 1024) {
+            const uint32_t t = c0 + x;
+            uint32_t v = 0;
+            if (t < T) {
+                const uint32_t seg = (n_seg == 1) ? 0u : tile_seg[t];
+                const uint32_t base = tp[t] - ((n_seg == 1) ? 0u : tp[seg_first_tile[seg]]);
+                const uint32_t q = st[seg].quota;
+                const uint32_t room = (q > base) ? q - base : 0u;
+                const uint32_t c = ct[t];
+                v = cs[t] + (room < c ? room : c);
+            }
+            vals[scan_phys(x)] = v;
+        }
+        __syncthreads();
+        const uint32_t total = scan_chunk(vals, wtot);
+        for (uint32_t x = threadIdx.x; x < SCAN_CHUNK && c0 + x < T; x += 1024) off[c0 + x] = carry + vals[scan_phys(x)];
+        carry += total;
+        __syncthreads();
     }
     if (threadIdx.x == 0) {
-        off[T] = total;
-        if (total != expected) atomicOr(&flags[1], 1u);
+        off[T] = carry;
+        if (carry != expected) atomicOr(&flags[1], 1u);
     }
 }
 
@@ -792,30 +847,42 @@ __global__ __launch_bounds__(1024) void k_scan(const uint32_t* __restrict__ tile
 // bitmap words: decide every candidate against tau, hand out the tie quota in index
 // order, and write the tile's chosen indices at its offset.  grid (ceil(T/4), nbatch).
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void k_emit(const uint32_t* __restrict__ tile_start, const uint32_t* __restrict__ tile_seg,
+template <int KPL>
+__global__ __launch_bounds__(BLOCK) void k_emit(uint64_t n, const uint32_t* __restrict__ tile_start,
+                                                const uint32_t* __restrict__ tile_seg,
                                                 const uint32_t* __restrict__ seg_first_tile, uint32_t T, uint32_t n_seg,
                                                 const SegState* __restrict__ states, const uint32_t* __restrict__ gt_bits,
                                                 const uint32_t* __restrict__ cand_bits, const uint32_t* __restrict__ cand_keys,
                                                 uint64_t keys_stride, const uint32_t* __restrict__ tie_pre, PtrTab out_off,
                                                 MutPtrTab out_idx, uint32_t expected, uint32_t* __restrict__ pub_bits)
 {
-    const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b = blockIdx.y, lane = lane_id();
+    __shared__ uint32_t kb[4][SUBS * 16 * KPL];
+    const uint32_t wid = threadIdx.x >> 6;
+    const uint32_t t = blockIdx.x * 4 + wid, b = blockIdx.y, lane = lane_id();
     if (t >= T) return;
-    const uint32_t seg = tile_seg[t];
+    const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
+    const uint32_t start = tr.start, len = tr.len, seg = tr.seg;
     const SegState* st = &states[(size_t)b * n_seg + seg];
-    const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
+    const uint32_t* keys = cand_keys + (size_t)b * keys_stride + start;
+    const uint32_t* tp = tie_pre + (size_t)b * (T + 1);
+    // everything the tile needs is requested here, before any of it is used
+    const uint2 c2 = *reinterpret_cast<const uint2*>(cand_bits + ((size_t)b * T + t) * TILE_WORDS + 2 * lane);
+    uint2 g2 = make_uint2(0u, 0u);
+    if (gt_bits) g2 = *reinterpret_cast<const uint2*>(gt_bits + (size_t)t * TILE_WORDS + 2 * lane);
+    uint32_t kv[KPL];
+    load_sublists<KPL>(keys, lane, kv);
+    const uint32_t off_t = static_cast<const uint32_t*>(out_off.p[b])[t];
+    const uint32_t tp_t = tp[t];
     const uint32_t none = st->none, tau = st->tau, quota = st->quota, voidk = st->has_void;
     uint32_t cw[2] = {0u, 0u}, gw[2] = {0u, 0u};
-    if (!none) {
-        const uint2 c2 = *reinterpret_cast<const uint2*>(cand_bits + ((size_t)b * T + t) * TILE_WORDS + 2 * lane);
-        cw[0] = c2.x; cw[1] = c2.y;
-        if (gt_bits) {
-            const uint2 g2 = *reinterpret_cast<const uint2*>(gt_bits + (size_t)t * TILE_WORDS + 2 * lane);
-            gw[0] = g2.x; gw[1] = g2.y;
-        }
-    }
-    uint32_t j = sublist_pos(lane, __popc(cw[0]) + __popc(cw[1]));
-    const uint32_t* keys = cand_keys + (size_t)b * keys_stride + start;
+    if (!none) { cw[0] = c2.x; cw[1] = c2.y; gw[0] = g2.x; gw[1] = g2.y; }
+    uint32_t* kbw = kb[wid];
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) kbw[(lane >> 4) * (16 * KPL) + (lane & 15u) + 16 * i] = kv[i];
+    wave_sync();
+    const uint32_t pos = sublist_pos(lane, __popc(cw[0]) + __popc(cw[1]));
+    const uint32_t sub = pos >> 10;
+    uint32_t j = pos & (SUB - 1u);
     uint32_t selmask[2] = {0u, 0u}, tiemask[2] = {0u, 0u};
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -823,7 +890,8 @@ __global__ __launch_bounds__(BLOCK) void k_emit(const uint32_t* __restrict__ til
         while (m) {
             const uint32_t p = __ffs(m) - 1;
             m &= m - 1;
-            const uint32_t k = keys[j++];
+            const uint32_t k = (j < 16u * KPL) ? kbw[sub * (16 * KPL) + j] : keys[sub * SUB + j];
+            ++j;
             if (voidk && k == VOID_KEY) continue;
             if (k > tau) selmask[h] |= 1u << p;
             else if (k == tau) tiemask[h] |= 1u << p;
@@ -832,8 +900,8 @@ __global__ __launch_bounds__(BLOCK) void k_emit(const uint32_t* __restrict__ til
     const uint32_t tcnt = __popc(tiemask[0]) + __popc(tiemask[1]);
     uint32_t taken[2] = {0u, 0u};
     if (__ballot(tcnt != 0)) {
-        const uint32_t* tp = tie_pre + (size_t)b * (T + 1);
-        const uint32_t tbase = tp[t] - tp[seg_first_tile[seg]] + wave_incl_scan(tcnt) - tcnt;
+        const uint32_t tp_seg = (n_seg == 1) ? 0u : tp[seg_first_tile[seg]];
+        const uint32_t tbase = tp_t - tp_seg + wave_incl_scan(tcnt) - tcnt;
         uint32_t take = (quota > tbase) ? quota - tbase : 0u;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -843,9 +911,8 @@ __global__ __launch_bounds__(BLOCK) void k_emit(const uint32_t* __restrict__ til
     }
     const uint32_t fm0 = gw[0] | selmask[0] | taken[0], fm1 = gw[1] | selmask[1] | taken[1];
     const uint32_t ocnt = __popc(fm0) + __popc(fm1);
-    const uint32_t* off = static_cast<const uint32_t*>(out_off.p[b]);
     uint32_t* out = static_cast<uint32_t*>(out_idx.p[b]);
-    uint32_t o = off[t] + wave_incl_scan(ocnt) - ocnt;
+    uint32_t o = off_t + wave_incl_scan(ocnt) - ocnt;
     {
         uint32_t m = fm0;
         while (m) {
