@@ -138,7 +138,7 @@ void carve(slimdp_ctx* c, Carver& cv)
     c->c_gt_bits = cv.take<uint32_t>(T * TILE_WORDS);
     c->c_cand_bits = cv.take<uint32_t>(T * TILE_WORDS);
     c->c_cand_keys = cv.take<uint32_t>(c->keys_stride);
-    c->c_cnt_gt = cv.take<uint32_t>(T);
+    c->c_cnt_gt = cv.take<uint32_t>(T * SUBS);
     c->c_cnt_cand = cv.take<uint32_t>(T * SUBS);
     c->c_cnt_sel = cv.take<uint32_t>(T);
     c->c_cnt_tie = cv.take<uint32_t>(T);
@@ -218,7 +218,7 @@ uint32_t persistent_blocks(const slimdp_ctx* c, uint32_t per_cu, uint32_t nbatch
 
 // Levels 1, 2, per-tile counts, scan over tiles and ordered emission, shared by the core
 // (after k_core_build, which already filled the level-1 histogram) and the explorer.
-template <int KPL>
+template <int KPL, int BPW>
 int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* hist, const uint32_t* gt_bits,
                      const uint32_t* cand_bits, const uint32_t* cand_keys, const uint32_t* cnt_gt,
                      const uint32_t* cnt_cand, uint32_t* cnt_sel, uint32_t* cnt_tie, uint32_t* tie_pre,
@@ -226,30 +226,30 @@ int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* his
                      uint32_t expected, uint32_t* pub_bits)
 {
     const uint32_t T = c->T, S = c->n_seg;
-    const dim3 wave_grid((T + 3) / 4, nbatch);
+    const dim3 wave_grid((T + 3) / 4, (nbatch + BPW - 1) / BPW);     // a wave serves its tile for BPW batches
     if (!level1_done) {
-        hipLaunchKernelGGL(k_list_hist<KPL>, wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg, T, S,
-                           st, hist, (uint32_t)H_L1, 1, cand_keys, cnt_cand, keys_stride);
+        hipLaunchKernelGGL((k_list_hist<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start,
+                           c->d_tile_seg, T, S, nbatch, st, hist, (uint32_t)H_L1, 1, cand_keys, cnt_cand, keys_stride);
         SLIMDP_LAUNCHED(c, "k_list_hist(1)");
     }
     hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 1, (uint32_t)H_L1, S, 0, c->d_flags);
     SLIMDP_LAUNCHED(c, "k_threshold(1)");
-    hipLaunchKernelGGL(k_list_hist<KPL>, wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg, T, S, st,
-                       hist, (uint32_t)H_L2, 2, cand_keys, cnt_cand, keys_stride);
+    hipLaunchKernelGGL((k_list_hist<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg,
+                       T, S, nbatch, st, hist, (uint32_t)H_L2, 2, cand_keys, cnt_cand, keys_stride);
     SLIMDP_LAUNCHED(c, "k_list_hist(2)");
     hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 2, (uint32_t)H_L2, S, 0, c->d_flags);
     SLIMDP_LAUNCHED(c, "k_threshold(2)");
-    hipLaunchKernelGGL(k_count<KPL>, wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg, T, S, st,
-                       cand_keys, cnt_cand, cnt_gt, keys_stride, cnt_sel, cnt_tie);
+    hipLaunchKernelGGL((k_count<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg, T, S,
+                       nbatch, st, cand_keys, cnt_cand, cnt_gt, keys_stride, cnt_sel, cnt_tie);
     SLIMDP_LAUNCHED(c, "k_count");
     hipLaunchKernelGGL(k_scan, dim3(1, nbatch), dim3(1024), 0, c->stream, c->d_tile_seg, c->d_seg_first_tile, T, S, st,
                        cnt_sel, cnt_tie, tie_pre, out_off, expected, c->d_flags);
     SLIMDP_LAUNCHED(c, "k_scan");
     PtrTab off_ro;
     for (int q = 0; q < MAXW; ++q) off_ro.p[q] = out_off.p[q];
-    hipLaunchKernelGGL(k_emit<KPL>, wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg,
-                       c->d_seg_first_tile, T, S, st, gt_bits, cand_bits, cand_keys, keys_stride, tie_pre, off_ro, out_idx,
-                       expected, pub_bits);
+    hipLaunchKernelGGL((k_emit<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg,
+                       c->d_seg_first_tile, T, S, nbatch, st, gt_bits, cand_bits, cand_keys, keys_stride, tie_pre, off_ro,
+                       out_idx, expected, pub_bits);
     SLIMDP_LAUNCHED(c, "k_emit");
     return SLIMDP_OK;
 }
@@ -544,7 +544,7 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
     MutPtrTab off_tab = make_tab<MutPtrTab, uint32_t*>(&core_off, 1);
     MutPtrTab idx_tab = make_tab<MutPtrTab, uint32_t*>(&core_idx, 1);
     uint32_t* pub = ctx->tl.word_aligned ? core_bits : nullptr;
-    rc = finish_selection<CORE_KPL>(ctx, 1, ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys,
+    rc = finish_selection<CORE_KPL, 1>(ctx, 1, ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys,
                           ctx->c_cnt_gt, ctx->c_cnt_cand, ctx->c_cnt_sel, ctx->c_cnt_tie, ctx->c_tie_pre, ctx->keys_stride,
                           true, off_tab, idx_tab, (uint32_t)K, pub);
     if (rc) return rc;
@@ -611,7 +611,7 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
     }
     MutPtrTab off_tab = make_tab<MutPtrTab>(expl_off, B);
     MutPtrTab idx_tab = make_tab<MutPtrTab>(expl_idx, B);
-    return finish_selection<EXPL_KPL>(ctx, B, ctx->e_state, ctx->e_hist, nullptr, ctx->e_cand_bits, ctx->e_cand_keys, nullptr,
+    return finish_selection<EXPL_KPL, 4>(ctx, B, ctx->e_state, ctx->e_hist, nullptr, ctx->e_cand_bits, ctx->e_cand_keys, nullptr,
                             ctx->e_cnt_cand, ctx->e_cnt_sel, ctx->e_cnt_tie, ctx->e_tie_pre, ctx->keys_stride, false,
                             off_tab, idx_tab, (uint32_t)M, nullptr);
 }

@@ -424,7 +424,11 @@ __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states
 // ---------------------------------------------------------------------------------------
 // K2: core candidates.  One pass over the score: parameters whose level-0 digit is above
 // the threshold bin are certainly in the core (gt bitmap), those in the bin are candidates
-// (bitmap + keys compacted per tile) and feed the level-1 histogram.
+// (bitmap + keys compacted per sub-tile) and feed the level-1 histogram.
+// Every wave owns sub-tile `wid` of each of the block's tiles and needs no block barrier:
+// round `it` covers parameters [256*it, 256*it+256) of the sub-tile in index order (lane L
+// owns 4L..4L+3), the eight bitmap words of a round are OR-reductions over groups of
+// eight lanes, a candidate's place in the key list comes from wave ballots.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ S, const uint32_t* __restrict__ tile_start,
                                                       const uint32_t* __restrict__ tile_seg, uint32_t T,
@@ -434,9 +438,9 @@ __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ 
                                                       uint32_t* __restrict__ cnt_cand, int vec_ok)
 {
     __shared__ uint32_t h[CORE_NB1];
-    __shared__ uint32_t gt[TILE_WORDS], cd[TILE_WORDS], cpre[TILE_WORDS];
-    __shared__ uint32_t wtot[4];
+    const uint32_t lane = lane_id(), wid = threadIdx.x >> 6;
     for (uint32_t b = threadIdx.x; b < CORE_NB1; b += BLOCK) h[b] = 0;
+    __syncthreads();
     const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
     const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
     if (t0 >= t1) return;
@@ -446,69 +450,73 @@ __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ 
         if (seg != cur_seg) {
             __syncthreads();
             flush_hist(h, CORE_NB1, hist + (size_t)cur_seg * H_STRIDE + H_L1);
+            __syncthreads();
             cur_seg = seg;
         }
         const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
         const uint32_t b1 = states[seg].prefix, none = states[seg].none;
-        if (threadIdx.x < TILE_WORDS) { gt[threadIdx.x] = 0; cd[threadIdx.x] = 0; }
-        __syncthreads();
-        const bool vec = vec_ok && len == TILE && (start & 3u) == 0;
-        uint32_t key[EPT];
-        if (vec) {
+        const uint32_t off = wid * SUB;
+        const uint32_t sub_len = (len > off) ? ((len - off < SUB) ? len - off : SUB) : 0u;
+        const float* src = S + (size_t)start + off;
+        uint32_t* gwords = gt_bits + (size_t)t * TILE_WORDS + wid * SUB_WORDS;
+        uint32_t* cwords = cand_bits + (size_t)t * TILE_WORDS + wid * SUB_WORDS;
+        uint32_t* ckeys = cand_keys + (size_t)start + off;
+        uint32_t key[4][4];
+        if (vec_ok && sub_len == SUB && (start & 3u) == 0) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const uint4 v = *reinterpret_cast<const uint4*>(S + (size_t)start + r * 1024 + threadIdx.x * 4);
-                key[4 * r + 0] = v.x; key[4 * r + 1] = v.y; key[4 * r + 2] = v.z; key[4 * r + 3] = v.w;
+            for (int it = 0; it < 4; ++it) {
+                const uint4 v = *reinterpret_cast<const uint4*>(src + it * 256 + lane * 4);
+                key[it][0] = v.x; key[it][1] = v.y; key[it][2] = v.z; key[it][3] = v.w;
             }
         } else {
 #pragma unroll
-            for (int j = 0; j < EPT; ++j) {
-                const uint32_t e = elem_scl(j);
-                key[j] = (e < len) ? __float_as_uint(S[(size_t)start + e]) : 0u;
-            }
-        }
-        uint32_t is_cand = 0;   // bit j: slot j is a candidate
+            for (int it = 0; it < 4; ++it)
 #pragma unroll
-        for (int j = 0; j < EPT; ++j) {
-            const uint32_t e = vec ? elem_vec(j) : elem_scl(j);
-            if (e < len && !none) {
-                const uint32_t d = key[j] >> CORE_SHIFT0;
-                if (d > b1) atomicOr(&gt[e >> 5], 1u << (e & 31));
-                else if (d == b1) {
-                    atomicOr(&cd[e >> 5], 1u << (e & 31));
-                    atomicAdd(&h[(key[j] >> CORE_SHIFT1) & (CORE_NB1 - 1u)], 1u);
-                    is_cand |= 1u << j;
+                for (int cc = 0; cc < 4; ++cc) {
+                    const uint32_t e = (uint32_t)it * 256u + lane * 4u + cc;
+                    key[it][cc] = (e < sub_len) ? __float_as_uint(src[e]) : 0u;
+                }
+        }
+        uint32_t run = 0, ngt = 0;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            uint32_t fg = 0, fc = 0;
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                const uint32_t e = (uint32_t)it * 256u + lane * 4u + cc;
+                if (e < sub_len && !none) {
+                    const uint32_t d = key[it][cc] >> CORE_SHIFT0;
+                    if (d > b1) fg |= 1u << cc;
+                    else if (d == b1) fc |= 1u << cc;
                 }
             }
-        }
-        __syncthreads();
-        const uint32_t cw = (threadIdx.x < TILE_WORDS) ? cd[threadIdx.x] : 0u;
-        const uint32_t gw = (threadIdx.x < TILE_WORDS) ? gt[threadIdx.x] : 0u;
-        uint32_t tot_c, tot_g;
-        const uint32_t ex = block_excl_scan<4>(__popc(cw), wtot, tot_c);
-        (void)block_excl_scan<4>(__popc(gw), wtot, tot_g);
-        if (threadIdx.x < TILE_WORDS) {
-            cpre[threadIdx.x] = ex;
-            gt_bits[(size_t)t * TILE_WORDS + threadIdx.x] = gw;
-            cand_bits[(size_t)t * TILE_WORDS + threadIdx.x] = cw;
-        }
-        if (threadIdx.x == 0) cnt_gt[t] = tot_g;
-        __syncthreads();
-        if (threadIdx.x < SUBS) {       // candidates per sub-tile
-            const uint32_t s0 = cpre[threadIdx.x * SUB_WORDS];
-            const uint32_t s1 = (threadIdx.x + 1 < SUBS) ? cpre[(threadIdx.x + 1) * SUB_WORDS] : tot_c;
-            cnt_cand[(size_t)t * SUBS + threadIdx.x] = s1 - s0;
-        }
+            uint32_t vg = fg << (4u * (lane & 7u)), vc = fc << (4u * (lane & 7u));
+            vg |= __shfl_xor(vg, 1, 64); vc |= __shfl_xor(vc, 1, 64);
+            vg |= __shfl_xor(vg, 2, 64); vc |= __shfl_xor(vc, 2, 64);
+            vg |= __shfl_xor(vg, 4, 64); vc |= __shfl_xor(vc, 4, 64);
+            if ((lane & 7u) == 0) { gwords[it * 8 + (lane >> 3)] = vg; cwords[it * 8 + (lane >> 3)] = vc; }
+            ngt += __popc(fg);
+            uint32_t below = 0, total = 0;
 #pragma unroll
-        for (int j = 0; j < EPT; ++j) {
-            if (is_cand & (1u << j)) {
-                const uint32_t e = vec ? elem_vec(j) : elem_scl(j);
-                const uint32_t wd = e >> 5;
-                const uint32_t rank = cpre[wd] - cpre[wd & ~(SUB_WORDS - 1u)] + __popc(cd[wd] & mask_below(e & 31));
-                cand_keys[(size_t)start + (e & ~(SUB - 1u)) + rank] = key[j];
+            for (int cc = 0; cc < 4; ++cc) {
+                const unsigned long long bal = __ballot((fc >> cc) & 1u);
+                below += __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+                total += (uint32_t)__popcll(bal);
             }
+            if (fc) {
+                uint32_t pos = run + below;
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    if ((fc >> cc) & 1u) {
+                        ckeys[pos++] = key[it][cc];
+                        atomicAdd(&h[(key[it][cc] >> CORE_SHIFT1) & (CORE_NB1 - 1u)], 1u);
+                    }
+                }
+            }
+            run += total;
         }
-        __syncthreads();
+        ngt = wave_sum(ngt);
+        if (lane == 0) { cnt_cand[(size_t)t * SUBS + wid] = run; cnt_gt[(size_t)t * SUBS + wid] = ngt; }
     }
     __syncthreads();
     flush_hist(h, CORE_NB1, hist + (size_t)cur_seg * H_STRIDE + H_L1);
@@ -676,91 +684,119 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
 // tile, 16 lanes per sub-tile list; equal digits inside a wave are merged before the
 // global atomic.  grid (ceil(T/4), nbatch).
 // ---------------------------------------------------------------------------------------
-template <int KPL>
+template <int KPL, int BPW>
 __global__ __launch_bounds__(BLOCK) void k_list_hist(uint64_t n, const uint32_t* __restrict__ tile_start,
                                                      const uint32_t* __restrict__ tile_seg, uint32_t T, uint32_t n_seg,
-                                                     const SegState* __restrict__ states, uint32_t* __restrict__ hist,
-                                                     uint32_t hist_off, int level, const uint32_t* __restrict__ cand_keys,
+                                                     uint32_t nbatch, const SegState* __restrict__ states,
+                                                     uint32_t* __restrict__ hist, uint32_t hist_off, int level,
+                                                     const uint32_t* __restrict__ cand_keys,
                                                      const uint32_t* __restrict__ cnt_cand, uint64_t keys_stride)
 {
-    const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b = blockIdx.y, lane = lane_id();
+    const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b0 = blockIdx.y * BPW, lane = lane_id();
     if (t >= T) return;
     const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
-    const SegState* st = &states[(size_t)b * n_seg + tr.seg];
-    const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tr.start + (lane >> 4) * SUB;
-    uint32_t kv[KPL];
-    load_sublists<KPL>(cand_keys + (size_t)b * keys_stride + tr.start, lane, kv);
-    const uint32_t cnt = cnt_cand[((size_t)b * T + t) * SUBS + (lane >> 4)];
-    if (st->none) return;
-    const uint32_t pshift = st->shift[level - 1], shift = st->shift[level], mask = st->nbins[level] - 1u;
-    const uint32_t prefix = st->prefix, voidk = st->has_void;
-    const uint32_t maxcnt = max(max(__shfl(cnt, 0, 64), __shfl(cnt, 16, 64)), max(__shfl(cnt, 32, 64), __shfl(cnt, 48, 64)));
-    uint32_t* hp = hist + ((size_t)b * n_seg + tr.seg) * H_STRIDE + hist_off;
-    for (uint32_t j0 = 0; j0 < maxcnt; j0 += 16) {
-        const uint32_t j = j0 + (lane & 15u);
-        uint32_t k = 0;
-        if (j0 < 16u * KPL) {
+    // one wave serves the tile for BPW batches: all their loads are requested before any is used
+    uint32_t kv[BPW][KPL], cnt[BPW];
 #pragma unroll
-            for (int i = 0; i < KPL; ++i) if (j0 == 16u * i) k = kv[i];
-        } else if (j < cnt) {
-            k = keys[j];
+    for (int bb = 0; bb < BPW; ++bb) {
+        const uint32_t b = b0 + bb;
+        cnt[bb] = 0;
+        if (b < nbatch) {
+            load_sublists<KPL>(cand_keys + (size_t)b * keys_stride + tr.start, lane, kv[bb]);
+            cnt[bb] = cnt_cand[((size_t)b * T + t) * SUBS + (lane >> 4)];
         }
-        bool part = (j < cnt) && (k >> pshift) == prefix && !(voidk && k == VOID_KEY);
-        const uint32_t digit = (k >> shift) & mask;
-        unsigned long long active = __ballot(part);
-        while (active) {
-            const int leader = __ffsll((long long)active) - 1;
-            const uint32_t d = __shfl(digit, leader, 64);
-            const unsigned long long same = __ballot(part && digit == d);
-            if ((int)lane == leader) atomicAdd(&hp[d], (uint32_t)__popcll(same));
-            if (digit == d) part = false;
-            active &= ~same;
+    }
+#pragma unroll
+    for (int bb = 0; bb < BPW; ++bb) {
+        const uint32_t b = b0 + bb;
+        if (b >= nbatch) break;
+        const SegState* st = &states[(size_t)b * n_seg + tr.seg];
+        if (st->none) continue;
+        const uint32_t pshift = st->shift[level - 1], shift = st->shift[level], mask = st->nbins[level] - 1u;
+        const uint32_t prefix = st->prefix, voidk = st->has_void;
+        const uint32_t c = cnt[bb];
+        const uint32_t maxcnt = max(max(__shfl(c, 0, 64), __shfl(c, 16, 64)), max(__shfl(c, 32, 64), __shfl(c, 48, 64)));
+        const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tr.start + (lane >> 4) * SUB;
+        uint32_t* hp = hist + ((size_t)b * n_seg + tr.seg) * H_STRIDE + hist_off;
+        for (uint32_t j0 = 0; j0 < maxcnt; j0 += 16) {
+            const uint32_t j = j0 + (lane & 15u);
+            uint32_t k = 0;
+            if (j0 < 16u * KPL) {
+#pragma unroll
+                for (int i = 0; i < KPL; ++i) if (j0 == 16u * i) k = kv[bb][i];
+            } else if (j < c) {
+                k = keys[j];
+            }
+            bool part = (j < c) && (k >> pshift) == prefix && !(voidk && k == VOID_KEY);
+            const uint32_t digit = (k >> shift) & mask;
+            unsigned long long active = __ballot(part);
+            while (active) {
+                const int leader = __ffsll((long long)active) - 1;
+                const uint32_t d = __shfl(digit, leader, 64);
+                const unsigned long long same = __ballot(part && digit == d);
+                if ((int)lane == leader) atomicAdd(&hp[d], (uint32_t)__popcll(same));
+                if (digit == d) part = false;
+                active &= ~same;
+            }
         }
     }
 }
 
 // ---------------------------------------------------------------------------------------
 // Per-tile counts once tau is known: selected-for-sure (gt + keys > tau) and ties (== tau).
-// One wave per tile.  grid (ceil(T/4), nbatch).
+// One wave per tile and BPW batches.  grid (ceil(T/4), ceil(nbatch/BPW)).
 // ---------------------------------------------------------------------------------------
-template <int KPL>
+template <int KPL, int BPW>
 __global__ __launch_bounds__(BLOCK) void k_count(uint64_t n, const uint32_t* __restrict__ tile_start,
                                                  const uint32_t* __restrict__ tile_seg, uint32_t T, uint32_t n_seg,
-                                                 const SegState* __restrict__ states, const uint32_t* __restrict__ cand_keys,
-                                                 const uint32_t* __restrict__ cnt_cand, const uint32_t* __restrict__ cnt_gt,
-                                                 uint64_t keys_stride, uint32_t* __restrict__ cnt_sel,
-                                                 uint32_t* __restrict__ cnt_tie)
+                                                 uint32_t nbatch, const SegState* __restrict__ states,
+                                                 const uint32_t* __restrict__ cand_keys, const uint32_t* __restrict__ cnt_cand,
+                                                 const uint32_t* __restrict__ cnt_gt, uint64_t keys_stride,
+                                                 uint32_t* __restrict__ cnt_sel, uint32_t* __restrict__ cnt_tie)
 {
-    const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b = blockIdx.y, lane = lane_id();
+    const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b0 = blockIdx.y * BPW, lane = lane_id();
     if (t >= T) return;
     const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
-    const SegState* st = &states[(size_t)b * n_seg + tr.seg];
-    const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tr.start + (lane >> 4) * SUB;
-    uint32_t kv[KPL];
-    load_sublists<KPL>(cand_keys + (size_t)b * keys_stride + tr.start, lane, kv);
-    const uint32_t cnt = cnt_cand[((size_t)b * T + t) * SUBS + (lane >> 4)];
-    const uint32_t gtc = cnt_gt ? cnt_gt[t] : 0u;
-    uint32_t sel = 0, tie = 0;
-    if (!st->none) {
-        const uint32_t tau = st->tau, voidk = st->has_void;
+    uint32_t kv[BPW][KPL], cnt[BPW];
 #pragma unroll
-        for (int i = 0; i < KPL; ++i) {
-            const uint32_t k = kv[i];
-            if ((lane & 15u) + 16u * i < cnt && !(voidk && k == VOID_KEY)) {
+    for (int bb = 0; bb < BPW; ++bb) {
+        const uint32_t b = b0 + bb;
+        cnt[bb] = 0;
+        if (b < nbatch) {
+            load_sublists<KPL>(cand_keys + (size_t)b * keys_stride + tr.start, lane, kv[bb]);
+            cnt[bb] = cnt_cand[((size_t)b * T + t) * SUBS + (lane >> 4)];
+        }
+    }
+    uint32_t gtc = 0;
+    if (cnt_gt) { const uint4 g4 = *reinterpret_cast<const uint4*>(cnt_gt + (size_t)t * SUBS); gtc = g4.x + g4.y + g4.z + g4.w; }
+#pragma unroll
+    for (int bb = 0; bb < BPW; ++bb) {
+        const uint32_t b = b0 + bb;
+        if (b >= nbatch) break;
+        const SegState* st = &states[(size_t)b * n_seg + tr.seg];
+        uint32_t sel = 0, tie = 0;
+        if (!st->none) {
+            const uint32_t tau = st->tau, voidk = st->has_void, c = cnt[bb];
+            const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tr.start + (lane >> 4) * SUB;
+#pragma unroll
+            for (int i = 0; i < KPL; ++i) {
+                const uint32_t k = kv[bb][i];
+                if ((lane & 15u) + 16u * i < c && !(voidk && k == VOID_KEY)) {
+                    sel += (k > tau) ? 1u : 0u;
+                    tie += (k == tau) ? 1u : 0u;
+                }
+            }
+            for (uint32_t j = (lane & 15u) + 16u * KPL; j < c; j += 16) {
+                const uint32_t k = keys[j];
+                if (voidk && k == VOID_KEY) continue;
                 sel += (k > tau) ? 1u : 0u;
                 tie += (k == tau) ? 1u : 0u;
             }
+            sel = wave_sum(sel) + gtc;
+            tie = wave_sum(tie);
         }
-        for (uint32_t j = (lane & 15u) + 16u * KPL; j < cnt; j += 16) {
-            const uint32_t k = keys[j];
-            if (voidk && k == VOID_KEY) continue;
-            sel += (k > tau) ? 1u : 0u;
-            tie += (k == tau) ? 1u : 0u;
-        }
-        sel = wave_sum(sel) + gtc;
-        tie = wave_sum(tie);
+        if (lane == 0) { cnt_sel[(size_t)b * T + t] = sel; cnt_tie[(size_t)b * T + t] = tie; }
     }
-    if (lane == 0) { cnt_sel[(size_t)b * T + t] = sel; cnt_tie[(size_t)b * T + t] = tie; }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -847,92 +883,107 @@ __global__ __launch_bounds__(1024) void k_scan(const uint32_t* __restrict__ tile
 // bitmap words: decide every candidate against tau, hand out the tie quota in index
 // order, and write the tile's chosen indices at its offset.  grid (ceil(T/4), nbatch).
 // ---------------------------------------------------------------------------------------
-template <int KPL>
+template <int KPL, int BPW>
 __global__ __launch_bounds__(BLOCK) void k_emit(uint64_t n, const uint32_t* __restrict__ tile_start,
                                                 const uint32_t* __restrict__ tile_seg,
                                                 const uint32_t* __restrict__ seg_first_tile, uint32_t T, uint32_t n_seg,
-                                                const SegState* __restrict__ states, const uint32_t* __restrict__ gt_bits,
-                                                const uint32_t* __restrict__ cand_bits, const uint32_t* __restrict__ cand_keys,
-                                                uint64_t keys_stride, const uint32_t* __restrict__ tie_pre, PtrTab out_off,
-                                                MutPtrTab out_idx, uint32_t expected, uint32_t* __restrict__ pub_bits)
+                                                uint32_t nbatch, const SegState* __restrict__ states,
+                                                const uint32_t* __restrict__ gt_bits, const uint32_t* __restrict__ cand_bits,
+                                                const uint32_t* __restrict__ cand_keys, uint64_t keys_stride,
+                                                const uint32_t* __restrict__ tie_pre, PtrTab out_off, MutPtrTab out_idx,
+                                                uint32_t expected, uint32_t* __restrict__ pub_bits)
 {
     __shared__ uint32_t kb[4][SUBS * 16 * KPL];
     const uint32_t wid = threadIdx.x >> 6;
-    const uint32_t t = blockIdx.x * 4 + wid, b = blockIdx.y, lane = lane_id();
+    const uint32_t t = blockIdx.x * 4 + wid, b0 = blockIdx.y * BPW, lane = lane_id();
     if (t >= T) return;
     const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
     const uint32_t start = tr.start, len = tr.len, seg = tr.seg;
-    const SegState* st = &states[(size_t)b * n_seg + seg];
-    const uint32_t* keys = cand_keys + (size_t)b * keys_stride + start;
-    const uint32_t* tp = tie_pre + (size_t)b * (T + 1);
-    // everything the tile needs is requested here, before any of it is used
-    const uint2 c2 = *reinterpret_cast<const uint2*>(cand_bits + ((size_t)b * T + t) * TILE_WORDS + 2 * lane);
+    // one wave serves the tile for BPW batches: all their loads are requested before any is used
+    uint2 c2[BPW];
+    uint32_t kv[BPW][KPL], off_t[BPW], tp_t[BPW];
     uint2 g2 = make_uint2(0u, 0u);
     if (gt_bits) g2 = *reinterpret_cast<const uint2*>(gt_bits + (size_t)t * TILE_WORDS + 2 * lane);
-    uint32_t kv[KPL];
-    load_sublists<KPL>(keys, lane, kv);
-    const uint32_t off_t = static_cast<const uint32_t*>(out_off.p[b])[t];
-    const uint32_t tp_t = tp[t];
-    const uint32_t none = st->none, tau = st->tau, quota = st->quota, voidk = st->has_void;
-    uint32_t cw[2] = {0u, 0u}, gw[2] = {0u, 0u};
-    if (!none) { cw[0] = c2.x; cw[1] = c2.y; gw[0] = g2.x; gw[1] = g2.y; }
+#pragma unroll
+    for (int bb = 0; bb < BPW; ++bb) {
+        const uint32_t b = b0 + bb;
+        c2[bb] = make_uint2(0u, 0u); off_t[bb] = 0; tp_t[bb] = 0;
+        if (b < nbatch) {
+            c2[bb] = *reinterpret_cast<const uint2*>(cand_bits + ((size_t)b * T + t) * TILE_WORDS + 2 * lane);
+            load_sublists<KPL>(cand_keys + (size_t)b * keys_stride + start, lane, kv[bb]);
+            off_t[bb] = static_cast<const uint32_t*>(out_off.p[b])[t];
+            tp_t[bb] = tie_pre[(size_t)b * (T + 1) + t];
+        }
+    }
     uint32_t* kbw = kb[wid];
 #pragma unroll
-    for (int i = 0; i < KPL; ++i) kbw[(lane >> 4) * (16 * KPL) + (lane & 15u) + 16 * i] = kv[i];
-    wave_sync();
-    const uint32_t pos = sublist_pos(lane, __popc(cw[0]) + __popc(cw[1]));
-    const uint32_t sub = pos >> 10;
-    uint32_t j = pos & (SUB - 1u);
-    uint32_t selmask[2] = {0u, 0u}, tiemask[2] = {0u, 0u};
+    for (int bb = 0; bb < BPW; ++bb) {
+        const uint32_t b = b0 + bb;
+        if (b >= nbatch) break;
+        const SegState* st = &states[(size_t)b * n_seg + seg];
+        const uint32_t* keys = cand_keys + (size_t)b * keys_stride + start;
+        const uint32_t* tp = tie_pre + (size_t)b * (T + 1);
+        const uint32_t none = st->none, tau = st->tau, quota = st->quota, voidk = st->has_void;
+        uint32_t cw[2] = {0u, 0u}, gw[2] = {0u, 0u};
+        if (!none) { cw[0] = c2[bb].x; cw[1] = c2[bb].y; gw[0] = g2.x; gw[1] = g2.y; }
+        wave_sync();
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        uint32_t m = cw[h];
-        while (m) {
-            const uint32_t p = __ffs(m) - 1;
-            m &= m - 1;
-            const uint32_t k = (j < 16u * KPL) ? kbw[sub * (16 * KPL) + j] : keys[sub * SUB + j];
-            ++j;
-            if (voidk && k == VOID_KEY) continue;
-            if (k > tau) selmask[h] |= 1u << p;
-            else if (k == tau) tiemask[h] |= 1u << p;
-        }
-    }
-    const uint32_t tcnt = __popc(tiemask[0]) + __popc(tiemask[1]);
-    uint32_t taken[2] = {0u, 0u};
-    if (__ballot(tcnt != 0)) {
-        const uint32_t tp_seg = (n_seg == 1) ? 0u : tp[seg_first_tile[seg]];
-        const uint32_t tbase = tp_t - tp_seg + wave_incl_scan(tcnt) - tcnt;
-        uint32_t take = (quota > tbase) ? quota - tbase : 0u;
+        for (int i = 0; i < KPL; ++i) kbw[(lane >> 4) * (16 * KPL) + (lane & 15u) + 16 * i] = kv[bb][i];
+        wave_sync();
+        const uint32_t pos = sublist_pos(lane, __popc(cw[0]) + __popc(cw[1]));
+        const uint32_t sub = pos >> 10;
+        uint32_t j = pos & (SUB - 1u);
+        uint32_t selmask[2] = {0u, 0u}, tiemask[2] = {0u, 0u};
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            uint32_t m = tiemask[h];
-            while (m && take) { const uint32_t low = m & (0u - m); taken[h] |= low; m ^= low; --take; }
+            uint32_t m = cw[h];
+            while (m) {
+                const uint32_t p = __ffs(m) - 1;
+                m &= m - 1;
+                const uint32_t k = (j < 16u * KPL) ? kbw[sub * (16 * KPL) + j] : keys[sub * SUB + j];
+                ++j;
+                if (voidk && k == VOID_KEY) continue;
+                if (k > tau) selmask[h] |= 1u << p;
+                else if (k == tau) tiemask[h] |= 1u << p;
+            }
         }
-    }
-    const uint32_t fm0 = gw[0] | selmask[0] | taken[0], fm1 = gw[1] | selmask[1] | taken[1];
-    const uint32_t ocnt = __popc(fm0) + __popc(fm1);
-    uint32_t* out = static_cast<uint32_t*>(out_idx.p[b]);
-    uint32_t o = off_t + wave_incl_scan(ocnt) - ocnt;
-    {
-        uint32_t m = fm0;
-        while (m) {
-            const uint32_t p = __ffs(m) - 1;
-            m &= m - 1;
-            if (o < expected) out[o] = start + lane * 64u + p;     // never beyond the caller's list
-            ++o;
+        const uint32_t tcnt = __popc(tiemask[0]) + __popc(tiemask[1]);
+        uint32_t taken[2] = {0u, 0u};
+        if (__ballot(tcnt != 0)) {
+            const uint32_t tp_seg = (n_seg == 1) ? 0u : tp[seg_first_tile[seg]];
+            const uint32_t tbase = tp_t[bb] - tp_seg + wave_incl_scan(tcnt) - tcnt;
+            uint32_t take = (quota > tbase) ? quota - tbase : 0u;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                uint32_t m = tiemask[h];
+                while (m && take) { const uint32_t low = m & (0u - m); taken[h] |= low; m ^= low; --take; }
+            }
         }
-        m = fm1;
-        while (m) {
-            const uint32_t p = __ffs(m) - 1;
-            m &= m - 1;
-            if (o < expected) out[o] = start + lane * 64u + 32u + p;
-            ++o;
+        const uint32_t fm0 = gw[0] | selmask[0] | taken[0], fm1 = gw[1] | selmask[1] | taken[1];
+        const uint32_t ocnt = __popc(fm0) + __popc(fm1);
+        uint32_t* out = static_cast<uint32_t*>(out_idx.p[b]);
+        uint32_t o = off_t[bb] + wave_incl_scan(ocnt) - ocnt;
+        {
+            uint32_t m = fm0;
+            while (m) {
+                const uint32_t p = __ffs(m) - 1;
+                m &= m - 1;
+                if (o < expected) out[o] = start + lane * 64u + p;     // never beyond the caller's list
+                ++o;
+            }
+            m = fm1;
+            while (m) {
+                const uint32_t p = __ffs(m) - 1;
+                m &= m - 1;
+                if (o < expected) out[o] = start + lane * 64u + 32u + p;
+                ++o;
+            }
         }
-    }
-    if (pub_bits) {
-        uint32_t* pb = pub_bits + (start >> 5) + 2 * lane;
-        if (lane * 64u < len) pb[0] = fm0;
-        if (lane * 64u + 32u < len) pb[1] = fm1;
+        if (pub_bits) {
+            uint32_t* pb = pub_bits + (start >> 5) + 2 * lane;
+            if (lane * 64u < len) pb[0] = fm0;
+            if (lane * 64u + 32u < len) pb[1] = fm1;
+        }
     }
 }
 
@@ -1023,17 +1074,28 @@ __global__ __launch_bounds__(BLOCK) void k_pack_stream(PtrTab g, uint32_t nw, co
                                                        PtrTab expl_off, MutPtrTab core_val, MutPtrTab expl_val, int vec_ok)
 {
     __shared__ float buf[NBUF][TILE];
+    __shared__ uint16_t cpos[TILE];          // the tile's core positions: the same for every worker
     __shared__ uint32_t elo[MAXW], ehi[MAXW];
     const uint32_t t = blockIdx.x;
     const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
     const bool vec = vec_ok && len == TILE && (start & 3u) == 0;
     const uint32_t c0 = core_off[t], c1 = core_off[t + 1];
+    const uint32_t ccnt = (c1 - c0 < TILE) ? c1 - c0 : TILE;
     if (threadIdx.x < nw) {
         const uint32_t* eo = static_cast<const uint32_t*>(expl_off.p[threadIdx.x]);
         elo[threadIdx.x] = eo[t];
         ehi[threadIdx.x] = eo[t + 1];
     }
+    for (uint32_t x = threadIdx.x; x < ccnt; x += BLOCK) {
+        const uint32_t pos = core_idx[c0 + x] - start;
+        cpos[x] = (pos < len) ? (uint16_t)pos : (uint16_t)0xFFFF;
+    }
+    __syncthreads();
+    // Loads are requested one worker ahead and nothing inside the loop waits for a load that
+    // was requested in the same iteration: the tile of updates and this thread's explorer
+    // index of the next worker travel while the current worker's values are picked from LDS.
     float r[EPT];
+    uint32_t epos = 0xFFFFFFFFu;             // explorer entry elo[q] + threadIdx.x of the coming worker, if any
     auto fetch = [&](uint32_t q) {
         const float* src = static_cast<const float*>(g.p[q]) + start;
         if (vec) {
@@ -1049,6 +1111,8 @@ __global__ __launch_bounds__(BLOCK) void k_pack_stream(PtrTab g, uint32_t nw, co
                 r[j] = (e < len) ? src[e] : 0.0f;
             }
         }
+        const uint32_t j = elo[q] + threadIdx.x;
+        epos = (j < ehi[q]) ? static_cast<const uint32_t*>(expl_idx.p[q])[j] - start : 0xFFFFFFFFu;
     };
     fetch(0);
     for (uint32_t q = 0; q < nw; ++q) {
@@ -1062,19 +1126,23 @@ __global__ __launch_bounds__(BLOCK) void k_pack_stream(PtrTab g, uint32_t nw, co
 #pragma unroll
             for (int j = 0; j < EPT; ++j) b[elem_scl(j)] = r[j];
         }
+        const uint32_t my_epos = epos;
         __syncthreads();     // with two buffers this also orders a buffer's readers (two workers ago) before its writers
         if (q + 1 < nw) fetch(q + 1);
         float* cv = static_cast<float*>(core_val.p[q]);
-        for (uint32_t j = c0 + threadIdx.x; j < c1; j += BLOCK) {
-            const uint32_t pos = core_idx[j] - start;
-            if (pos < len) cv[j] = b[pos];
+        for (uint32_t x = threadIdx.x; x < ccnt; x += BLOCK) {
+            const uint32_t pos = cpos[x];
+            if (pos != 0xFFFFu) cv[c0 + x] = b[pos];
         }
-        const uint32_t* ei = static_cast<const uint32_t*>(expl_idx.p[q]);
         float* ev = static_cast<float*>(expl_val.p[q]);
-        const uint32_t e1 = ehi[q];
-        for (uint32_t j = elo[q] + threadIdx.x; j < e1; j += BLOCK) {
-            const uint32_t pos = ei[j] - start;
-            if (pos < len) ev[j] = b[pos];
+        const uint32_t e0 = elo[q], e1 = ehi[q];
+        if (my_epos < len) ev[e0 + threadIdx.x] = b[my_epos];
+        if (e1 - e0 > BLOCK) {               // dense explorers: the rest of the slice, loaded here
+            const uint32_t* ei = static_cast<const uint32_t*>(expl_idx.p[q]);
+            for (uint32_t j = e0 + BLOCK + threadIdx.x; j < e1; j += BLOCK) {
+                const uint32_t pos = ei[j] - start;
+                if (pos < len) ev[j] = b[pos];
+            }
         }
     }
 }
