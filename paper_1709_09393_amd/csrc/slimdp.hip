@@ -99,7 +99,8 @@ struct slimdp_ctx {
     uint32_t *c_cnt_gt = nullptr, *c_cnt_cand = nullptr, *c_cnt_sel = nullptr, *c_cnt_tie = nullptr, *c_tie_pre = nullptr;
     // explorer selection (batch = worker)
     SegState* e_state = nullptr;
-    uint32_t *e_hist = nullptr, *e_cand_bits = nullptr, *e_cand_keys = nullptr;
+    uint32_t *e_hist = nullptr, *e_sure_bits = nullptr, *e_cand_bits = nullptr, *e_cand_keys = nullptr;
+    uint32_t *e_cnt_gt = nullptr, *e_nsure = nullptr;
     uint32_t *e_cnt_cand = nullptr, *e_cnt_sel = nullptr, *e_cnt_tie = nullptr, *e_tie_pre = nullptr;
     // host state
     uint64_t epoch = 0;
@@ -145,7 +146,10 @@ void carve(slimdp_ctx* c, Carver& cv)
     c->c_tie_pre = cv.take<uint32_t>(T + 1);
     c->e_state = cv.take<SegState>(B * S);
     c->e_hist = cv.take<uint32_t>(B * S * H_STRIDE);
+    c->e_sure_bits = cv.take<uint32_t>(B * T * TILE_WORDS);
     c->e_cand_bits = cv.take<uint32_t>(B * T * TILE_WORDS);
+    c->e_cnt_gt = cv.take<uint32_t>(B * T * SUBS);
+    c->e_nsure = cv.take<uint32_t>(B * S);
     c->e_cand_keys = cv.take<uint32_t>(B * c->keys_stride);
     c->e_cnt_cand = cv.take<uint32_t>(B * T * SUBS);
     c->e_cnt_sel = cv.take<uint32_t>(B * T);
@@ -193,7 +197,7 @@ int fill(slimdp_ctx* c, uint32_t* p, uint64_t count, uint32_t v)
     return SLIMDP_OK;
 }
 
-int init_states(slimdp_ctx* c, SegState* st, const std::vector<SegInit>& init, uint32_t nbatch, int core, uint32_t has_void)
+int init_states(slimdp_ctx* c, SegState* st, const std::vector<SegInit>& init, uint32_t nbatch, int core)
 {
     for (uint32_t s0 = 0; s0 < c->n_seg; s0 += INIT_CHUNK) {
         SegInitChunk chunk;
@@ -202,7 +206,7 @@ int init_states(slimdp_ctx* c, SegState* st, const std::vector<SegInit>& init, u
         for (uint32_t j = 0; j < cnt; ++j) chunk.s[j] = init[s0 + j];
         const uint32_t threads = cnt * nbatch;
         hipLaunchKernelGGL(k_init_state, dim3((threads + 255) / 256), dim3(256), 0, c->stream, st, chunk, s0, cnt,
-                           c->n_seg, nbatch, core, has_void);
+                           c->n_seg, nbatch, core);
         SLIMDP_LAUNCHED(c, "k_init_state");
     }
     return SLIMDP_OK;
@@ -223,7 +227,7 @@ int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* his
                      const uint32_t* cand_bits, const uint32_t* cand_keys, const uint32_t* cnt_gt,
                      const uint32_t* cnt_cand, uint32_t* cnt_sel, uint32_t* cnt_tie, uint32_t* tie_pre,
                      uint64_t keys_stride, bool level1_done, const MutPtrTab& out_off, const MutPtrTab& out_idx,
-                     uint32_t expected, uint32_t* pub_bits)
+                     uint32_t expected, uint32_t* pub_bits, const uint32_t* excl_bits)
 {
     const uint32_t T = c->T, S = c->n_seg;
     const dim3 wave_grid((T + 3) / 4, (nbatch + BPW - 1) / BPW);     // a wave serves its tile for BPW batches
@@ -232,12 +236,14 @@ int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* his
                            c->d_tile_seg, T, S, nbatch, st, hist, (uint32_t)H_L1, 1, cand_keys, cnt_cand, keys_stride);
         SLIMDP_LAUNCHED(c, "k_list_hist(1)");
     }
-    hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 1, (uint32_t)H_L1, S, 0, c->d_flags);
+    hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 1, (uint32_t)H_L1, S, 0, c->d_flags,
+                       nullptr);
     SLIMDP_LAUNCHED(c, "k_threshold(1)");
     hipLaunchKernelGGL((k_list_hist<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg,
                        T, S, nbatch, st, hist, (uint32_t)H_L2, 2, cand_keys, cnt_cand, keys_stride);
     SLIMDP_LAUNCHED(c, "k_list_hist(2)");
-    hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 2, (uint32_t)H_L2, S, 0, c->d_flags);
+    hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 2, (uint32_t)H_L2, S, 0, c->d_flags,
+                       nullptr);
     SLIMDP_LAUNCHED(c, "k_threshold(2)");
     hipLaunchKernelGGL((k_count<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg, T, S,
                        nbatch, st, cand_keys, cnt_cand, cnt_gt, keys_stride, cnt_sel, cnt_tie);
@@ -249,7 +255,7 @@ int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* his
     for (int q = 0; q < MAXW; ++q) off_ro.p[q] = out_off.p[q];
     hipLaunchKernelGGL((k_emit<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg,
                        c->d_seg_first_tile, T, S, nbatch, st, gt_bits, cand_bits, cand_keys, keys_stride, tie_pre, off_ro,
-                       out_idx, expected, pub_bits);
+                       out_idx, expected, pub_bits, excl_bits, (uint32_t)((c->n + 31) / 32));
     SLIMDP_LAUNCHED(c, "k_emit");
     return SLIMDP_OK;
 }
@@ -280,10 +286,13 @@ int check_epoch(slimdp_ctx* c, uint64_t core_epoch)
     return SLIMDP_OK;
 }
 
-// Per-segment start of the explorer's radix descent.  Narrow bound: expect m + 6 sqrt(m) + 32
-// candidate words below it; the exact rerun with the full range catches the (astronomically
-// rare) shortfall.  Returns an error code for impossible requests; *narrow is set when every
-// segment got a narrow bound.
+// Per-segment start of the explorer's radix descent.  The m-th smallest Philox word of the
+// avail = n_s - k_s parameters outside the core lies, with overwhelming probability, between
+// the words that m - 6 sqrt(m) - 32 and m + 6 sqrt(m) + 32 of them are expected to stay below:
+// words up to the first are taken without ranking (sure zone), only the words between the two
+// become candidates.  The exact rerun with every word a candidate catches a miss on either
+// side.  Returns an error code for impossible requests; *narrow is set when every segment
+// got a narrow candidate zone.
 int explorer_init(slimdp_ctx* ctx, const char* who, const uint64_t* k_seg, const uint64_t* m_seg,
                   std::vector<SegInit>& init, uint64_t* M_out, bool* narrow)
 {
@@ -297,26 +306,33 @@ int explorer_init(slimdp_ctx* ctx, const char* who, const uint64_t* k_seg, const
                         who, s, (unsigned long long)m_seg[s], (unsigned long long)(k_seg[s] > ns ? 0 : ns - k_seg[s]));
         const uint64_t m = m_seg[s];
         M += m;
-        SegInit in{(uint32_t)m, 0u, 0u};
+        SegInit in{(uint32_t)m, 0u, 0u, 0u, 0u};
         if (m > 0) {
             const double avail = (double)(ns - k_seg[s]);
-            double frac = ((double)m + 6.0 * std::sqrt((double)m) + 32.0) / avail;
-            if (ctx->opt_force_fallback) frac = 0.25 * (double)m / avail;
-            if (frac >= 0.95) {
-                in.bound_m1 = 0xFFFFFFFFu; in.shift0 = 20;
+            const double slack = 6.0 * std::sqrt((double)m) + 32.0;
+            double hi = ((double)m + slack) / avail, lo = ((double)m - slack) / avail;
+            if (ctx->opt_force_fallback == 1) { hi = 0.25 * (double)m / avail; lo = 0.5 * hi; }     // too few candidates
+            if (ctx->opt_force_fallback == 2) { hi = 2.0 * (double)m / avail; lo = 0.75 * hi; }     // sure zone too large
+            uint64_t width = 1ull << 32;                     // number of distinct candidate words
+            if (hi >= 0.95) {
+                in.bound_m1 = 0xFFFFFFFFu;
                 all_narrow = false;
             } else {
-                uint64_t B0 = (uint64_t)std::ceil(frac * 4294967296.0);
-                if (B0 < 1) B0 = 1;
-                uint32_t bitlen = 0;
-                while (bitlen < 33 && ((B0 - 1) >> bitlen) != 0) ++bitlen;
-                const uint32_t sh = bitlen > 12 ? bitlen - 12 : 0;
-                B0 = (B0 + ((1ull << sh) - 1)) >> sh << sh;
-                if (B0 > (1ull << 32)) B0 = 1ull << 32;
-                in.bound_m1 = (uint32_t)(B0 - 1);
-                in.shift0 = sh;
-                if (in.bound_m1 == 0xFFFFFFFFu) all_narrow = false;
+                uint64_t B1 = (uint64_t)std::ceil(hi * 4294967296.0);
+                if (B1 < 1) B1 = 1;
+                if (B1 > (1ull << 32)) B1 = 1ull << 32;
+                in.bound_m1 = (uint32_t)(B1 - 1);
+                width = B1;
+                const uint64_t B0 = lo > 0.0 ? (uint64_t)std::floor(lo * 4294967296.0) : 0;
+                if (B0 >= 1 && B0 < B1) {                    // words 0 .. B0-1 are sure, B0 .. B1-1 candidates
+                    in.sure_m1 = (uint32_t)(B0 - 1);
+                    in.has_gt = 1;
+                    width = B1 - B0;
+                }
             }
+            uint32_t bitlen = 0;
+            while (bitlen < 33 && ((width - 1) >> bitlen) != 0) ++bitlen;
+            in.shift0 = bitlen > 12 ? bitlen - 12 : 0;
         }
         init[s] = in;
     }
@@ -463,10 +479,10 @@ int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_
         bool narrow = false;
         if (explorer_init(ctx, "slimdp_score(hint)", ctx->hint.k_seg.data(), ctx->hint.m_seg.data(), init, &M, &narrow) ==
                 SLIMDP_OK && narrow && M > 0) {
-            rc = init_states(ctx, ctx->e_state, init, ctx->hint.n_workers, 0, 1);
+            rc = init_states(ctx, ctx->e_state, init, ctx->hint.n_workers, 0);
             if (rc) return rc;
             pre.nw = ctx->hint.n_workers; pre.worker0 = ctx->hint.worker0; pre.n_seg = ctx->n_seg;
-            pre.states = ctx->e_state; pre.cand_bits = ctx->e_cand_bits; pre.cand_keys = ctx->e_cand_keys;
+            pre.states = ctx->e_state; pre.sure_bits = ctx->e_sure_bits; pre.cand_bits = ctx->e_cand_bits; pre.cand_keys = ctx->e_cand_keys;
             pre.cnt_cand = ctx->e_cnt_cand; pre.keys_stride = ctx->keys_stride;
             pre.pk = PhiloxKey{(uint32_t)ctx->seed, (uint32_t)(ctx->seed >> 32), (uint32_t)ctx->hint.iteration,
                                (uint32_t)(ctx->hint.iteration >> 32)};
@@ -514,7 +530,7 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
         if (k_seg[s] > ns)
             return fail(ctx, SLIMDP_ERR_OUT_OF_RANGE, "slimdp_select_core: k_seg[%u]=%llu exceeds the segment size %llu", s,
                         (unsigned long long)k_seg[s], (unsigned long long)ns);
-        init[s] = SegInit{(uint32_t)k_seg[s], 0u, 0u};
+        init[s] = SegInit{(uint32_t)k_seg[s], 0u, 0u, 0u, 1u};
         K += k_seg[s];
     }
     if (K > 0 && !core_idx) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_select_core: core_idx is NULL");
@@ -524,7 +540,7 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
                     "slimdp_select_core: no histogram pending for this score buffer (call slimdp_score first)");
     ctx->hist_pending = false;
     const uint32_t T = ctx->T, S = ctx->n_seg;
-    int rc = init_states(ctx, ctx->c_state, init, 1, 1, 0);
+    int rc = init_states(ctx, ctx->c_state, init, 1, 1);
     if (rc) return rc;
     const uint32_t P = persistent_blocks(ctx, 4, 1);
     if (!reuse) {
@@ -535,7 +551,7 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
         SLIMDP_LAUNCHED(ctx, "k_core_hist0");
     }
     hipLaunchKernelGGL(k_threshold, dim3(S, 1), dim3(256), 0, ctx->stream, ctx->c_state, ctx->c_hist, 0, (uint32_t)H_L0, S, 0,
-                       ctx->d_flags);
+                       ctx->d_flags, nullptr);
     SLIMDP_LAUNCHED(ctx, "k_threshold(0)");
     hipLaunchKernelGGL(k_core_build, dim3(P), dim3(BLOCK), 0, ctx->stream, score, ctx->d_tile_start, ctx->d_tile_seg, T,
                        ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys, ctx->c_cnt_gt,
@@ -546,7 +562,7 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
     uint32_t* pub = ctx->tl.word_aligned ? core_bits : nullptr;
     rc = finish_selection<CORE_KPL, 1>(ctx, 1, ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys,
                           ctx->c_cnt_gt, ctx->c_cnt_cand, ctx->c_cnt_sel, ctx->c_cnt_tie, ctx->c_tie_pre, ctx->keys_stride,
-                          true, off_tab, idx_tab, (uint32_t)K, pub);
+                          true, off_tab, idx_tab, (uint32_t)K, pub, nullptr);
     if (rc) return rc;
     if (!pub) {
         rc = fill(ctx, core_bits, (ctx->n + 31) / 32, 0u);
@@ -576,44 +592,47 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
     if (rc) return rc;
     if (M > 0 && !table_ok(expl_idx, n_workers)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_sample_explore: NULL expl_idx entry");
     const uint32_t T = ctx->T, S = ctx->n_seg, B = n_workers;
-    // candidates already drawn inside slimdp_score for exactly this request?
+    // zones already drawn inside slimdp_score for exactly this request?
     const bool cached = ctx->pre.same(iteration, worker0, n_workers, k_seg, m_seg, S);
     ctx->pre.valid = false;
     ctx->hint.valid = false;
-    rc = init_states(ctx, ctx->e_state, init, B, 0, cached ? 1u : 0u);
+    rc = init_states(ctx, ctx->e_state, init, B, 0);
     if (rc) return rc;
     rc = fill(ctx, ctx->e_hist, (uint64_t)B * S * H_STRIDE, 0u);
+    if (rc) return rc;
+    rc = fill(ctx, ctx->e_nsure, (uint64_t)B * S, 0u);
     if (rc) return rc;
     rc = fill(ctx, ctx->d_flags, 1, 0u);
     if (rc) return rc;
     const uint32_t P = persistent_blocks(ctx, 8, B);
+    const uint32_t n_words = (uint32_t)((ctx->n + 31) / 32);
     const PhiloxKey pk{(uint32_t)ctx->seed, (uint32_t)(ctx->seed >> 32), (uint32_t)iteration, (uint32_t)(iteration >> 32)};
+    // pass 0: the zones of explorer_init; pass 1: every word a candidate, runs only if pass 0 raised the flag
     for (int fb = 0; fb < 2; ++fb) {
-        if (fb == 0 && cached) {
-            hipLaunchKernelGGL(k_explore_filter, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->n, ctx->d_tile_start,
-                               ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_cand_bits, ctx->e_cand_keys,
-                               ctx->keys_stride, (uint32_t)((ctx->n + 31) / 32));
-            SLIMDP_LAUNCHED(ctx, "k_explore_filter");
-        } else {
+        if (fb == 1 || !cached) {
             if (ctx->tl.quad_aligned)
-                hipLaunchKernelGGL(k_explore_keys<1>, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->d_tile_start,
-                                   ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_cand_bits, ctx->e_cand_keys,
+                hipLaunchKernelGGL(k_explore_keys<1>, dim3(P, B), dim3(BLOCK), 0, ctx->stream, ctx->d_tile_start,
+                                   ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_sure_bits, ctx->e_cand_bits, ctx->e_cand_keys,
                                    ctx->e_cnt_cand, ctx->keys_stride, worker0, pk, fb, ctx->d_flags);
             else
-                hipLaunchKernelGGL(k_explore_keys<0>, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->d_tile_start,
-                                   ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_cand_bits, ctx->e_cand_keys,
+                hipLaunchKernelGGL(k_explore_keys<0>, dim3(P, B), dim3(BLOCK), 0, ctx->stream, ctx->d_tile_start,
+                                   ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_sure_bits, ctx->e_cand_bits, ctx->e_cand_keys,
                                    ctx->e_cnt_cand, ctx->keys_stride, worker0, pk, fb, ctx->d_flags);
             SLIMDP_LAUNCHED(ctx, "k_explore_keys");
         }
+        hipLaunchKernelGGL(k_explore_filter, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->n, ctx->d_tile_start,
+                           ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_sure_bits, ctx->e_cnt_gt, ctx->e_nsure,
+                           ctx->e_cand_bits, ctx->e_cand_keys, ctx->e_cnt_cand, ctx->keys_stride, n_words, fb, ctx->d_flags);
+        SLIMDP_LAUNCHED(ctx, "k_explore_filter");
         hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, ctx->stream, ctx->e_state, ctx->e_hist, 0,
-                           (uint32_t)(fb ? H_L0FB : H_L0), S, fb ? 2 : 1, ctx->d_flags);
+                           (uint32_t)(fb ? H_L0FB : H_L0), S, fb ? 2 : 1, ctx->d_flags, ctx->e_nsure);
         SLIMDP_LAUNCHED(ctx, "k_threshold(0)");
     }
     MutPtrTab off_tab = make_tab<MutPtrTab>(expl_off, B);
     MutPtrTab idx_tab = make_tab<MutPtrTab>(expl_idx, B);
-    return finish_selection<EXPL_KPL, 4>(ctx, B, ctx->e_state, ctx->e_hist, nullptr, ctx->e_cand_bits, ctx->e_cand_keys, nullptr,
-                            ctx->e_cnt_cand, ctx->e_cnt_sel, ctx->e_cnt_tie, ctx->e_tie_pre, ctx->keys_stride, false,
-                            off_tab, idx_tab, (uint32_t)M, nullptr);
+    return finish_selection<EXPL_KPL, 4>(ctx, B, ctx->e_state, ctx->e_hist, ctx->e_sure_bits, ctx->e_cand_bits, ctx->e_cand_keys,
+                            ctx->e_cnt_gt, ctx->e_cnt_cand, ctx->e_cnt_sel, ctx->e_cnt_tie, ctx->e_tie_pre, ctx->keys_stride,
+                            false, off_tab, idx_tab, (uint32_t)M, nullptr, core_bits);
 }
 
 int slimdp_explore_hint(slimdp_ctx* ctx, const uint64_t* k_seg, uint32_t worker0, uint32_t n_workers,

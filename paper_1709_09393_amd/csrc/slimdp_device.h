@@ -34,15 +34,16 @@ struct SegState {
     uint32_t tau;       // threshold key once all levels are done
     uint32_t quota;     // how many keys == tau are taken, lowest index first
     uint32_t bound_m1;  // explorer only: candidates are words r <= bound_m1, key = bound_m1 - r
-    uint32_t has_void;  // explorer after presampling: keys equal to the void key are not candidates
+    uint32_t pad0;
     uint32_t shift[3];  // digit of level l = (key >> shift[l]) & (nbins[l] - 1); level 0 unmasked
     uint32_t nbins[3];
-    uint32_t pad1[2];
+    uint32_t sure_m1;   // explorer: words r <= sure_m1 are taken without looking at their rank (if has_gt)
+    uint32_t has_gt;    // a bitmap of certainly selected parameters exists (core: always; explorer: narrow zone)
 };
 static_assert(sizeof(SegState) == 64, "SegState layout");
 
-struct SegInit { uint32_t need; uint32_t bound_m1; uint32_t shift0; };
-constexpr int INIT_CHUNK = 256;
+struct SegInit { uint32_t need; uint32_t bound_m1; uint32_t shift0; uint32_t sure_m1; uint32_t has_gt; };
+constexpr int INIT_CHUNK = 128;
 struct SegInitChunk { SegInit s[INIT_CHUNK]; };
 
 // ---------------------------------------------------------------------------------------

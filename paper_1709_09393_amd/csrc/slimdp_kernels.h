@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256) void k_fill_u32(uint32_t* __restrict__ p, uint
 // Writes the selection state of segments [seg0, seg0+count) for every batch.
 // core != 0: fixed score-bit levels; else explorer levels derived from (bound_m1, shift0).
 __global__ __launch_bounds__(256) void k_init_state(SegState* __restrict__ st, SegInitChunk chunk, uint32_t seg0,
-                                                    uint32_t count, uint32_t n_seg, uint32_t nbatch, int core, uint32_t has_void)
+                                                    uint32_t count, uint32_t n_seg, uint32_t nbatch, int core)
 {
     const uint32_t x = blockIdx.x * 256 + threadIdx.x;
     if (x >= count * nbatch) return;
@@ -37,16 +37,19 @@ __global__ __launch_bounds__(256) void k_init_state(SegState* __restrict__ st, S
     const SegInit in = chunk.s[j];
     SegState s;
     s.need0 = in.need; s.need = in.need; s.prefix = 0; s.none = (in.need == 0) ? 1u : 0u;
-    s.tau = NONE; s.quota = 0; s.bound_m1 = in.bound_m1; s.has_void = has_void; s.pad1[0] = s.pad1[1] = 0;
+    s.tau = NONE; s.quota = 0; s.bound_m1 = in.bound_m1; s.pad0 = 0;
+    s.sure_m1 = in.sure_m1; s.has_gt = core ? 1u : in.has_gt;
     if (core) {
         s.shift[0] = CORE_SHIFT0; s.nbins[0] = CORE_NB0;
         s.shift[1] = CORE_SHIFT1; s.nbins[1] = CORE_NB1;
         s.shift[2] = 0;           s.nbins[2] = CORE_NB2;
     } else {
+        // explorer keys are bound_m1 - r for the words sure_m1 < r <= bound_m1 (all r <= bound_m1 without a sure zone)
+        const uint32_t width_m1 = in.has_gt ? in.bound_m1 - in.sure_m1 - 1u : in.bound_m1;
         const uint32_t sh0 = in.shift0;
         const uint32_t bits1 = sh0 < 12u ? sh0 : 12u;
         const uint32_t sh1 = sh0 - bits1;
-        s.shift[0] = sh0; s.nbins[0] = (in.bound_m1 >> sh0) + 1u;
+        s.shift[0] = sh0; s.nbins[0] = (width_m1 >> sh0) + 1u;
         s.shift[1] = sh1; s.nbins[1] = 1u << bits1;
         s.shift[2] = 0;   s.nbins[2] = 1u << sh1;
     }
@@ -54,17 +57,25 @@ __global__ __launch_bounds__(256) void k_init_state(SegState* __restrict__ st, S
 }
 
 // ---------------------------------------------------------------------------------------
-// K4: explorer candidates of one (worker, sub-tile), by ONE wave with no block barrier:
-// the Philox word of each parameter; words r <= bound_m1 become candidates with
-// key = bound_m1 - r (so that the smallest words are the largest keys): 32 bitmap words
-// plus the keys compacted in index order.
-// PRESAMPLE = 0: the core is known; core parameters are skipped and the level-0 histogram
-//                of the candidate keys is accumulated in the LDS array h.
-// PRESAMPLE = 1: the core is not known yet (runs inside the scoring kernel, hidden under
-//                its memory traffic); k_explore_filter later voids the core candidates.
-// wb, wp: 32 words of LDS each, private to the calling wave.
+// K4: the explorer draw of one (worker, sub-tile), by ONE wave with no block barrier: the
+// Philox word r of each parameter, sorted into two zones chosen on the host so that the
+// m-th smallest word of the segment falls into the second one:
+//   sure zone       r <= sure_m1 (if has_sure): one bit in the "sure" bitmap; such a
+//                   parameter is taken unless it turns out to be in the core;
+//   candidate zone  sure_m1 < r <= bound_m1: one bit in the candidate bitmap plus the key
+//                   bound_m1 - r (the smallest words are the largest keys), the keys of a
+//                   sub-tile compacted in index order.
+// The draw does not look at the core; k_explore_filter applies it afterwards, so the same
+// routine serves inside the scoring kernel (core not known yet) and stand-alone.
+// wa, wb, wp: 32 words of LDS each, private to the calling wave (generic variant only).
 // ---------------------------------------------------------------------------------------
 struct PhiloxKey { uint32_t seed_lo, seed_hi, it_lo, it_hi; };
+struct DrawOut {                 // per batch (worker) base pointers
+    uint32_t* sure_bits;         // [T * TILE_WORDS]
+    uint32_t* cand_bits;         // [T * TILE_WORDS]
+    uint32_t* cand_keys;         // [keys_stride]
+    uint32_t* cnt_cand;          // [T * SUBS]
+};
 
 // LDS traffic between the lanes of one wave: the hardware keeps a wave's LDS operations in
 // order, this keeps the compiler from moving them across the hand-over point.
@@ -73,22 +84,21 @@ __device__ __forceinline__ void wave_sync()
     __builtin_amdgcn_wave_barrier();
 }
 
-template <int PRESAMPLE>
+// Any tile start (tiles of a segmented model may begin inside a Philox block).
 __device__ __forceinline__ void explore_subtile(uint32_t worker, uint32_t t, uint32_t sub, uint32_t start, uint32_t len,
-                                                uint32_t bound_m1, uint32_t shift0, uint32_t skip,
-                                                const uint32_t* __restrict__ core_bits, uint32_t* h, uint32_t* wb,
-                                                uint32_t* wp, uint32_t* __restrict__ cbits, uint32_t* __restrict__ ckeys,
-                                                uint32_t* __restrict__ ccnt, PhiloxKey pk)
+                                                uint32_t bound_m1, uint32_t sure_m1, uint32_t has_sure, uint32_t skip,
+                                                uint32_t* wa, uint32_t* wb, uint32_t* wp, DrawOut out, PhiloxKey pk)
 {
     const uint32_t lane = lane_id();
     const uint32_t off = sub * SUB;
     const uint32_t sub_len = (len > off) ? ((len - off < SUB) ? len - off : SUB) : 0u;
+    const size_t wbase = (size_t)t * TILE_WORDS + sub * SUB_WORDS;
     if (sub_len == 0 || skip) {                                   // uniform over the wave
-        if (lane < SUB_WORDS) cbits[(size_t)t * TILE_WORDS + sub * SUB_WORDS + lane] = 0;
-        if (lane == 0) ccnt[(size_t)t * SUBS + sub] = 0;
+        if (lane < SUB_WORDS) { out.cand_bits[wbase + lane] = 0; out.sure_bits[wbase + lane] = 0; }
+        if (lane == 0) out.cnt_cand[(size_t)t * SUBS + sub] = 0;
         return;
     }
-    if (lane < SUB_WORDS) wb[lane] = 0;
+    if (lane < SUB_WORDS) { wa[lane] = 0; wb[lane] = 0; }
     wave_sync();
     const uint32_t base = start + off;
     const uint32_t g0 = base >> 2, g1 = (base + sub_len - 1u) >> 2;     // Philox blocks touched: at most 257
@@ -102,16 +112,16 @@ __device__ __forceinline__ void explore_subtile(uint32_t worker, uint32_t t, uin
             uint32_t r[4];
             philox4x32_10(gi, worker, pk.it_lo, pk.it_hi, pk.seed_lo, pk.seed_hi, r);
             const uint32_t i0 = gi << 2;
-            uint32_t nib = 0;
-            if (!PRESAMPLE) nib = (core_bits[i0 >> 5] >> (i0 & 31u)) & 0xFu;
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) {
                 const uint32_t e = i0 + cc - base;                  // wraps below the sub-tile start
                 key[it][cc] = bound_m1 - r[cc];
-                if (e < sub_len && !((nib >> cc) & 1u) && r[cc] <= bound_m1) {
-                    atomicOr(&wb[e >> 5], 1u << (e & 31));
-                    if (!PRESAMPLE) atomicAdd(&h[key[it][cc] >> shift0], 1u);
-                    is_cand |= 1u << (it * 4 + cc);
+                if (e < sub_len) {
+                    if (has_sure && r[cc] <= sure_m1) atomicOr(&wa[e >> 5], 1u << (e & 31));
+                    else if (r[cc] <= bound_m1) {
+                        atomicOr(&wb[e >> 5], 1u << (e & 31));
+                        is_cand |= 1u << (it * 4 + cc);
+                    }
                 }
             }
         }
@@ -122,9 +132,10 @@ __device__ __forceinline__ void explore_subtile(uint32_t worker, uint32_t t, uin
     const uint32_t incl = wave_incl_scan(pc);
     if (lane < SUB_WORDS) {
         wp[lane] = incl - pc;
-        cbits[(size_t)t * TILE_WORDS + sub * SUB_WORDS + lane] = cw;
+        out.cand_bits[wbase + lane] = cw;
+        out.sure_bits[wbase + lane] = wa[lane];
     }
-    if (lane == SUB_WORDS - 1) ccnt[(size_t)t * SUBS + sub] = incl;
+    if (lane == SUB_WORDS - 1) out.cnt_cand[(size_t)t * SUBS + sub] = incl;
     wave_sync();
     if (is_cand) {
 #pragma unroll
@@ -135,7 +146,7 @@ __device__ __forceinline__ void explore_subtile(uint32_t worker, uint32_t t, uin
                     const uint32_t gi = g0 + (uint32_t)it * 64u + lane;
                     const uint32_t e = (gi << 2) + cc - base;
                     const uint32_t rank = wp[e >> 5] + __popc(wb[e >> 5] & mask_below(e & 31));
-                    ckeys[(size_t)base + rank] = key[it][cc];
+                    out.cand_keys[(size_t)base + rank] = key[it][cc];
                 }
             }
         }
@@ -148,65 +159,59 @@ __device__ __forceinline__ void explore_subtile(uint32_t worker, uint32_t t, uin
 // in index order (lane L owns parameters 4L..4L+3 of the round), so a candidate's place in
 // the key list is the number of candidates in earlier rounds plus a wave ballot count, and
 // the eight bitmap words of the round are OR-reductions over groups of eight lanes.
-template <int PRESAMPLE>
 __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t, uint32_t sub, uint32_t start, uint32_t len,
-                                                     uint32_t bound_m1, uint32_t shift0, uint32_t skip,
-                                                     const uint32_t* __restrict__ core_bits, uint32_t* h,
-                                                     uint32_t* __restrict__ cbits, uint32_t* __restrict__ ckeys,
-                                                     uint32_t* __restrict__ ccnt, PhiloxKey pk)
+                                                     uint32_t bound_m1, uint32_t sure_m1, uint32_t has_sure, uint32_t skip,
+                                                     DrawOut out, PhiloxKey pk)
 {
     const uint32_t lane = lane_id();
     const uint32_t off = sub * SUB;
     const uint32_t sub_len = (len > off) ? ((len - off < SUB) ? len - off : SUB) : 0u;
-    uint32_t* words = cbits + (size_t)t * TILE_WORDS + sub * SUB_WORDS;
+    uint32_t* cwords = out.cand_bits + (size_t)t * TILE_WORDS + sub * SUB_WORDS;
+    uint32_t* swords = out.sure_bits + (size_t)t * TILE_WORDS + sub * SUB_WORDS;
     if (sub_len == 0 || skip) {                                   // uniform over the wave
-        if (lane < SUB_WORDS) words[lane] = 0;
-        if (lane == 0) ccnt[(size_t)t * SUBS + sub] = 0;
+        if (lane < SUB_WORDS) { cwords[lane] = 0; swords[lane] = 0; }
+        if (lane == 0) out.cnt_cand[(size_t)t * SUBS + sub] = 0;
         return;
     }
     const uint32_t base = start + off;
+    uint32_t* ckeys = out.cand_keys + (size_t)base;
     uint32_t run = 0;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
         const uint32_t e0 = (uint32_t)it * 256u + lane * 4u;      // first of this lane's four parameters
-        const uint32_t i0 = base + e0;
-        uint32_t nib = 0;
-        if (!PRESAMPLE) nib = (e0 < sub_len) ? (core_bits[i0 >> 5] >> (i0 & 31u)) & 0xFu : 0xFu;
         uint32_t r[4];
-        philox4x32_10(i0 >> 2, worker, pk.it_lo, pk.it_hi, pk.seed_lo, pk.seed_hi, r);
-        uint32_t flags = 0;
+        philox4x32_10((base + e0) >> 2, worker, pk.it_lo, pk.it_hi, pk.seed_lo, pk.seed_hi, r);
+        uint32_t fs = 0, fc = 0;
 #pragma unroll
-        for (int cc = 0; cc < 4; ++cc)
-            if (e0 + cc < sub_len && !((nib >> cc) & 1u) && r[cc] <= bound_m1) flags |= 1u << cc;
+        for (int cc = 0; cc < 4; ++cc) {
+            if (e0 + cc < sub_len) {
+                if (has_sure && r[cc] <= sure_m1) fs |= 1u << cc;
+                else if (r[cc] <= bound_m1) fc |= 1u << cc;
+            }
+        }
         // bitmap words: lanes 8j..8j+7 make word j of this round
-        uint32_t v = flags << (4u * (lane & 7u));
-        v |= __shfl_xor(v, 1, 64);
-        v |= __shfl_xor(v, 2, 64);
-        v |= __shfl_xor(v, 4, 64);
-        if ((lane & 7u) == 0) words[it * 8 + (lane >> 3)] = v;
+        uint32_t vs = fs << (4u * (lane & 7u)), vc = fc << (4u * (lane & 7u));
+        vs |= __shfl_xor(vs, 1, 64); vc |= __shfl_xor(vc, 1, 64);
+        vs |= __shfl_xor(vs, 2, 64); vc |= __shfl_xor(vc, 2, 64);
+        vs |= __shfl_xor(vs, 4, 64); vc |= __shfl_xor(vc, 4, 64);
+        if ((lane & 7u) == 0) { swords[it * 8 + (lane >> 3)] = vs; cwords[it * 8 + (lane >> 3)] = vc; }
         // place in the list: candidates of lower lanes in this round, all four components
         uint32_t below = 0, total = 0;
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc) {
-            const unsigned long long bal = __ballot((flags >> cc) & 1u);
+            const unsigned long long bal = __ballot((fc >> cc) & 1u);
             below += __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
             total += (uint32_t)__popcll(bal);
         }
-        if (flags) {
+        if (fc) {
             uint32_t pos = run + below;
 #pragma unroll
-            for (int cc = 0; cc < 4; ++cc) {
-                if ((flags >> cc) & 1u) {
-                    const uint32_t key = bound_m1 - r[cc];
-                    ckeys[(size_t)base + pos] = key;
-                    if (!PRESAMPLE) atomicAdd(&h[key >> shift0], 1u);
-                    ++pos;
-                }
-            }
+            for (int cc = 0; cc < 4; ++cc)
+                if ((fc >> cc) & 1u) ckeys[pos++] = bound_m1 - r[cc];
         }
         run += total;
     }
-    if (lane == 0) ccnt[(size_t)t * SUBS + sub] = run;
+    if (lane == 0) out.cnt_cand[(size_t)t * SUBS + sub] = run;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -222,11 +227,12 @@ __device__ __forceinline__ void flush_hist(uint32_t* lds, uint32_t nb, uint32_t*
     }
 }
 
-// PRE = 1 additionally draws the explorer candidates of pre.nw workers for every tile
-// (explore_tile<1>): integer work that runs while other waves wait for memory.
+// PRE = 1 additionally draws the explorer zones of pre.nw workers for every tile
+// (explore_subtile_fast): integer work that runs while other waves wait for memory.
 struct PreArgs {
     uint32_t nw, worker0, n_seg;
     const SegState* states;
+    uint32_t* sure_bits;
     uint32_t* cand_bits;
     uint32_t* cand_keys;
     uint32_t* cnt_cand;
@@ -261,10 +267,10 @@ __global__ __launch_bounds__(BLOCK, 4) void k_score(const float* __restrict__ w,
         }
         const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
         // the candidate bound depends on the segment only (every worker draws the same number)
-        uint32_t pre_bound = 0, pre_skip = 1;
+        uint32_t pre_bound = 0, pre_sure = 0, pre_has_sure = 0, pre_skip = 1;
         if (PRE) {
             const SegState* st = &pre.states[seg];
-            pre_bound = st->bound_m1; pre_skip = st->need0 == 0;
+            pre_bound = st->bound_m1; pre_sure = st->sure_m1; pre_has_sure = st->has_gt; pre_skip = st->need0 == 0;
         }
         const bool vec = vec_ok && len == TILE && (start & 3u) == 0;
         if (!vec) {
@@ -293,11 +299,15 @@ __global__ __launch_bounds__(BLOCK, 4) void k_score(const float* __restrict__ w,
             }
             if (PRE) {          // ... do this round's share of the integer work while they fly ...
 #pragma unroll 1
-                for (uint32_t b = (uint32_t)r; b < pre.nw; b += 4)
-                    explore_subtile_fast<1>(pre.worker0 + b, t, wid, start, len, pre_bound, 0u, pre_skip, nullptr, nullptr,
-                                            pre.cand_bits + (size_t)b * T * TILE_WORDS,
-                                            pre.cand_keys + (size_t)b * pre.keys_stride, pre.cnt_cand + (size_t)b * T * SUBS,
-                                            pre.pk);
+                for (uint32_t b = (uint32_t)r; b < pre.nw; b += 4) {
+                    DrawOut out;
+                    out.sure_bits = pre.sure_bits + (size_t)b * T * TILE_WORDS;
+                    out.cand_bits = pre.cand_bits + (size_t)b * T * TILE_WORDS;
+                    out.cand_keys = pre.cand_keys + (size_t)b * pre.keys_stride;
+                    out.cnt_cand = pre.cnt_cand + (size_t)b * T * SUBS;
+                    explore_subtile_fast(pre.worker0 + b, t, wid, start, len, pre_bound, pre_sure, pre_has_sure, pre_skip,
+                                         out, pre.pk);
+                }
             }
             if (vec) {          // ... then score them
                 float4 a;
@@ -363,7 +373,7 @@ __global__ __launch_bounds__(BLOCK) void k_core_hist0(const float* __restrict__ 
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states, const uint32_t* __restrict__ hist,
                                                    int level, uint32_t hist_off, uint32_t n_seg, int mode,
-                                                   uint32_t* __restrict__ flags)
+                                                   uint32_t* __restrict__ flags, const uint32_t* __restrict__ nsure)
 {
     __shared__ uint32_t wtot[4];
     __shared__ uint32_t sh_bcast[2];
@@ -378,8 +388,20 @@ __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states
             st->shift[1] = 8;  st->nbins[1] = 4096;
             st->shift[2] = 0;  st->nbins[2] = 256;
             st->need = st->need0; st->prefix = 0; st->none = (st->need0 == 0) ? 1u : 0u;
-            st->has_void = 0;
+            st->has_gt = 0;
         }
+        __syncthreads();
+    }
+    if (mode == 1 && st->has_gt) {
+        // the certainly taken ones (word below the sure bound, outside the core) come off the demand
+        const uint32_t ns = nsure[(size_t)b * n_seg + seg];
+        const uint32_t n0 = st->need0;
+        __syncthreads();
+        if (ns > n0) {                        // the sure zone alone is already too large: rerun with the wide bound
+            if (threadIdx.x == 0) atomicOr(&flags[0], 1u);
+            return;
+        }
+        if (threadIdx.x == 0) st->need = n0 - ns;
         __syncthreads();
     }
     const uint32_t need = st->need, none = st->none, nb = st->nbins[level];
@@ -522,53 +544,41 @@ __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ 
     flush_hist(h, CORE_NB1, hist + (size_t)cur_seg * H_STRIDE + H_L1);
 }
 
-// Stand-alone pass over every (worker, tile); each wave owns one sub-tile of the block's
-// tiles.  grid (blocks, n_workers); fallback != 0: the wide-bound rerun, a no-op unless flagged.
+// Stand-alone draw over every (worker, tile); each wave owns one sub-tile of the block's
+// tiles.  grid (blocks, n_workers); wide != 0: the rerun with every word a candidate and no
+// sure zone, a no-op unless flagged.
 template <int FAST>
-__global__ __launch_bounds__(BLOCK) void k_explore_keys(const uint32_t* __restrict__ core_bits,
-                                                        const uint32_t* __restrict__ tile_start,
+__global__ __launch_bounds__(BLOCK) void k_explore_keys(const uint32_t* __restrict__ tile_start,
                                                         const uint32_t* __restrict__ tile_seg, uint32_t T,
                                                         uint32_t n_seg, const SegState* __restrict__ states,
-                                                        uint32_t* __restrict__ hist, uint32_t* __restrict__ cand_bits,
+                                                        uint32_t* __restrict__ sure_bits, uint32_t* __restrict__ cand_bits,
                                                         uint32_t* __restrict__ cand_keys, uint32_t* __restrict__ cnt_cand,
-                                                        uint64_t keys_stride, uint32_t worker0, PhiloxKey pk, int fallback,
+                                                        uint64_t keys_stride, uint32_t worker0, PhiloxKey pk, int wide,
                                                         const uint32_t* __restrict__ flags)
 {
-    __shared__ uint32_t h[4096];
-    __shared__ uint32_t wbits[FAST ? 1 : 4][SUB_WORDS], wpre[FAST ? 1 : 4][SUB_WORDS];
-    if (fallback && flags[0] == 0) return;
+    __shared__ uint32_t wa[FAST ? 1 : 4][SUB_WORDS], wb[FAST ? 1 : 4][SUB_WORDS], wp[FAST ? 1 : 4][SUB_WORDS];
+    if (wide && flags[0] == 0) return;
     const uint32_t b = blockIdx.y, worker = worker0 + b, wid = threadIdx.x >> 6;
-    const uint32_t hoff = fallback ? H_L0FB : H_L0;
-    for (uint32_t x = threadIdx.x; x < 4096; x += BLOCK) h[x] = 0;
-    __syncthreads();
     const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
     const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
-    if (t0 >= t1) return;
-    uint32_t* cbits = cand_bits + (size_t)b * T * TILE_WORDS;
-    uint32_t* ckeys = cand_keys + (size_t)b * keys_stride;
-    uint32_t* ccnt = cnt_cand + (size_t)b * T * SUBS;
-    uint32_t cur_seg = tile_seg[t0];
+    DrawOut out;
+    out.sure_bits = sure_bits + (size_t)b * T * TILE_WORDS;
+    out.cand_bits = cand_bits + (size_t)b * T * TILE_WORDS;
+    out.cand_keys = cand_keys + (size_t)b * keys_stride;
+    out.cnt_cand = cnt_cand + (size_t)b * T * SUBS;
     for (uint32_t t = t0; t < t1; ++t) {
-        const uint32_t seg = tile_seg[t];
-        if (seg != cur_seg) {
-            __syncthreads();
-            flush_hist(h, 4096, hist + ((size_t)b * n_seg + cur_seg) * H_STRIDE + hoff);
-            __syncthreads();
-            cur_seg = seg;
-        }
+        const uint32_t seg = (n_seg == 1) ? 0u : tile_seg[t];
         const SegState* st = &states[(size_t)b * n_seg + seg];
-        const uint32_t bound_m1 = fallback ? 0xFFFFFFFFu : st->bound_m1;
-        const uint32_t shift0 = fallback ? 20u : st->shift[0];
+        const uint32_t bound_m1 = wide ? 0xFFFFFFFFu : st->bound_m1;
+        const uint32_t sure_m1 = st->sure_m1, has_sure = wide ? 0u : st->has_gt;
         const uint32_t skip = st->need0 == 0;
         const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
         if (FAST)
-            explore_subtile_fast<0>(worker, t, wid, start, len, bound_m1, shift0, skip, core_bits, h, cbits, ckeys, ccnt, pk);
+            explore_subtile_fast(worker, t, wid, start, len, bound_m1, sure_m1, has_sure, skip, out, pk);
         else
-            explore_subtile<0>(worker, t, wid, start, len, bound_m1, shift0, skip, core_bits, h, wbits[FAST ? 0 : wid],
-                               wpre[FAST ? 0 : wid], cbits, ckeys, ccnt, pk);
+            explore_subtile(worker, t, wid, start, len, bound_m1, sure_m1, has_sure, skip, wa[FAST ? 0 : wid],
+                            wb[FAST ? 0 : wid], wp[FAST ? 0 : wid], out, pk);
     }
-    __syncthreads();
-    flush_hist(h, 4096, hist + ((size_t)b * n_seg + cur_seg) * H_STRIDE + hoff);
 }
 
 // A wave walks one tile's candidates with every lane owning two bitmap words; the 16 lanes
@@ -608,75 +618,121 @@ __device__ __forceinline__ void load_sublists(const uint32_t* __restrict__ keys_
     for (int i = 0; i < KPL; ++i) kv[i] = p[16 * i];
 }
 
-// After a presampling pass: candidates that turned out to be core parameters get the void
-// key (never selected, never counted); the others feed the level-0 histogram.
-// One wave per tile.  grid (blocks, n_workers), persistent so that the histogram stays in LDS.
-constexpr uint32_t VOID_KEY = 0xFFFFFFFFu;
 constexpr int EXPL_KPL = 2, CORE_KPL = 4;
 
+// Bits [i0, i0 + 64) of a bitmap over all n parameters (i0 need not be word aligned).
+__device__ __forceinline__ void bitmap_window(const uint32_t* __restrict__ bits, uint32_t n_words, uint32_t i0, uint32_t out[2])
+{
+    const uint32_t sh = i0 & 31u, wi = i0 >> 5;
+    const uint32_t a0 = (wi < n_words) ? bits[wi] : 0u;
+    const uint32_t a1 = (wi + 1 < n_words) ? bits[wi + 1] : 0u;
+    const uint32_t a2 = (sh && wi + 2 < n_words) ? bits[wi + 2] : 0u;
+    out[0] = sh ? ((a0 >> sh) | (a1 << (32u - sh))) : a0;
+    out[1] = sh ? ((a1 >> sh) | (a2 << (32u - sh))) : a1;
+}
+
+// The draw does not know the core; this pass applies it.  Per (worker, tile), one wave:
+//   sure zone: counts the sure parameters outside the core per sub-tile (cnt_gt) and per
+//     segment (nsure); the bitmap itself stays as drawn, the emission masks it again;
+//   candidate zone: candidates inside the core are dropped (bitmap bit cleared, the sub-tile's
+//     key list closed up in place, its count lowered); the remaining keys feed the level-0
+//     histogram.
+// grid (blocks, n_workers), persistent so that the histogram stays in LDS.  wide != 0: after
+// the wide-bound rerun (no sure zone, 20-bit shift), a no-op unless flagged.
 __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __restrict__ core_bits, uint64_t n,
                                                           const uint32_t* __restrict__ tile_start,
                                                           const uint32_t* __restrict__ tile_seg, uint32_t T,
                                                           uint32_t n_seg, const SegState* __restrict__ states,
-                                                          uint32_t* __restrict__ hist, const uint32_t* __restrict__ cand_bits,
-                                                          uint32_t* __restrict__ cand_keys, uint64_t keys_stride,
-                                                          uint32_t n_words)
+                                                          uint32_t* __restrict__ hist, const uint32_t* __restrict__ sure_bits,
+                                                          uint32_t* __restrict__ cnt_gt, uint32_t* __restrict__ nsure,
+                                                          uint32_t* __restrict__ cand_bits, uint32_t* __restrict__ cand_keys,
+                                                          uint32_t* __restrict__ cnt_cand, uint64_t keys_stride,
+                                                          uint32_t n_words, int wide, const uint32_t* __restrict__ flags)
 {
     __shared__ uint32_t h[4096];
-    __shared__ uint32_t kb[4][SUBS * 16 * EXPL_KPL];
+    __shared__ uint32_t kl[4][SUB];
+    if (wide && flags[0] == 0) return;
     const uint32_t b = blockIdx.y, lane = lane_id(), wid = threadIdx.x >> 6;
     for (uint32_t x = threadIdx.x; x < 4096; x += BLOCK) h[x] = 0;
     __syncthreads();
     const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
     const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
     if (t0 >= t1) return;
-    // one segment per block range: histogram in LDS; otherwise straight to global memory
+    // one segment per block range: histogram and sure count stay on chip; otherwise straight to global memory
     const uint32_t seg_first = (n_seg == 1) ? 0u : tile_seg[t0];
     const bool one_seg = (n_seg == 1) || seg_first == tile_seg[t1 - 1];
+    const uint32_t hist_off = wide ? H_L0FB : H_L0;
+    uint32_t ns_acc = 0;
+    uint32_t* klw = kl[wid];
     for (uint32_t t = t0 + wid; t < t1; t += 4) {
         const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
         const SegState* st = &states[(size_t)b * n_seg + tr.seg];
-        uint32_t* keys = cand_keys + (size_t)b * keys_stride + tr.start;
+        const size_t bt = (size_t)b * T + t;
         // everything this tile needs is requested here, before any of it is used
-        const uint2 c2 = *reinterpret_cast<const uint2*>(cand_bits + ((size_t)b * T + t) * TILE_WORDS + 2 * lane);
-        uint32_t kv[EXPL_KPL];
-        load_sublists<EXPL_KPL>(keys, lane, kv);
-        const uint32_t i0 = tr.start + lane * 64u;      // core bits of this lane's 64 parameters
-        const uint32_t sh = i0 & 31u, wi = i0 >> 5;
-        const uint32_t a0 = (wi < n_words) ? core_bits[wi] : 0u;
-        const uint32_t a1 = (wi + 1 < n_words) ? core_bits[wi + 1] : 0u;
-        const uint32_t a2 = (sh && wi + 2 < n_words) ? core_bits[wi + 2] : 0u;
-        const uint32_t need0 = st->need0, shift0 = st->shift[0];
+        const uint2 s2 = *reinterpret_cast<const uint2*>(sure_bits + bt * TILE_WORDS + 2 * lane);
+        const uint2 c2 = *reinterpret_cast<const uint2*>(cand_bits + bt * TILE_WORDS + 2 * lane);
+        const uint32_t cnt = cnt_cand[bt * SUBS + (lane >> 4)];
+        uint32_t kw[2];
+        bitmap_window(core_bits, n_words, tr.start + lane * 64u, kw);
+        const uint32_t need0 = st->need0, shift0 = wide ? 20u : st->shift[0], has_sure = wide ? 0u : st->has_gt;
         if (need0 == 0) continue;
-        const uint32_t cw[2] = {c2.x, c2.y};
-        const uint32_t kw[2] = {sh ? ((a0 >> sh) | (a1 << (32u - sh))) : a0, sh ? ((a1 >> sh) | (a2 << (32u - sh))) : a1};
-        uint32_t* kbw = kb[wid];
-#pragma unroll
-        for (int i = 0; i < EXPL_KPL; ++i) kbw[(lane >> 4) * (16 * EXPL_KPL) + (lane & 15u) + 16 * i] = kv[i];
-        wave_sync();
-        const uint32_t pos = sublist_pos(lane, __popc(cw[0]) + __popc(cw[1]));
-        const uint32_t sub = pos >> 10;
-        uint32_t j = pos & (SUB - 1u);
-        uint32_t* hg = hist + ((size_t)b * n_seg + tr.seg) * H_STRIDE + H_L0;
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-            uint32_t m = cw[hh];
-            while (m) {
-                const uint32_t p = __ffs(m) - 1;
-                m &= m - 1;
-                if ((kw[hh] >> p) & 1u) keys[sub * SUB + j] = VOID_KEY;
-                else {
-                    const uint32_t key = (j < 16u * EXPL_KPL) ? kbw[sub * (16 * EXPL_KPL) + j] : keys[sub * SUB + j];
-                    if (one_seg) atomicAdd(&h[key >> shift0], 1u);
-                    else atomicAdd(&hg[key >> shift0], 1u);
-                }
-                ++j;
+        if (has_sure) {
+            const uint32_t sc = __popc(s2.x & ~kw[0]) + __popc(s2.y & ~kw[1]);
+            uint32_t g = sc;
+            g += __shfl_xor(g, 1, 64); g += __shfl_xor(g, 2, 64); g += __shfl_xor(g, 4, 64); g += __shfl_xor(g, 8, 64);
+            if ((lane & 15u) == 0) cnt_gt[bt * SUBS + (lane >> 4)] = g;
+            if (one_seg) ns_acc += sc;
+            else {
+                const uint32_t tot = wave_sum(sc);
+                if (lane == 0 && tot) atomicAdd(&nsure[(size_t)b * n_seg + tr.seg], tot);
             }
         }
-        wave_sync();
+        const uint32_t cw[2] = {c2.x, c2.y};
+        if (__ballot((cw[0] | cw[1]) != 0u) == 0ull) continue;
+        const uint32_t nw[2] = {cw[0] & ~kw[0], cw[1] & ~kw[1]};
+        const uint32_t oldc = __popc(cw[0]) + __popc(cw[1]), newc = __popc(nw[0]) + __popc(nw[1]);
+        const uint32_t oi = wave_incl_scan(oldc), ni = wave_incl_scan(newc);
+        const uint32_t og0 = __shfl(oi - oldc, (int)(lane & ~15u), 64), ng0 = __shfl(ni - newc, (int)(lane & ~15u), 64);
+        uint32_t jo = oi - oldc - og0, jn = ni - newc - ng0;        // places in the sub-tile's old and new key list
+        uint32_t* keys = cand_keys + (size_t)b * keys_stride + tr.start;
+        uint32_t* hg = hist + ((size_t)b * n_seg + tr.seg) * H_STRIDE + hist_off;
+#pragma unroll 1
+        for (uint32_t s = 0; s < (uint32_t)SUBS; ++s) {
+            const uint32_t c_s = __shfl(cnt, (int)(16u * s), 64);
+            if (c_s == 0) continue;
+            const bool mine = (lane >> 4) == s;
+            const bool close_up = __ballot(mine && oldc != newc) != 0ull;
+            uint32_t* ks = keys + s * SUB;
+            for (uint32_t j = lane; j < c_s; j += 64) klw[j] = ks[j];   // the whole old list, before any of it is overwritten
+            wave_sync();
+            if (mine) {
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    uint32_t m = cw[hh];
+                    while (m) {
+                        const uint32_t p = __ffs(m) - 1;
+                        m &= m - 1;
+                        const uint32_t key = klw[jo++];
+                        if ((kw[hh] >> p) & 1u) continue;
+                        if (close_up) ks[jn] = key;
+                        ++jn;
+                        if (one_seg) atomicAdd(&h[key >> shift0], 1u);
+                        else atomicAdd(&hg[key >> shift0], 1u);
+                    }
+                }
+            }
+            wave_sync();
+            if (close_up && lane == 16u * s + 15u) cnt_cand[bt * SUBS + s] = ni - ng0;
+        }
+        if (__ballot(oldc != newc) != 0ull)
+            *reinterpret_cast<uint2*>(cand_bits + bt * TILE_WORDS + 2 * lane) = make_uint2(nw[0], nw[1]);
+    }
+    if (one_seg) {
+        ns_acc = wave_sum(ns_acc);
+        if (lane == 0 && ns_acc) atomicAdd(&nsure[(size_t)b * n_seg + seg_first], ns_acc);
     }
     __syncthreads();
-    if (one_seg) flush_hist(h, 4096, hist + ((size_t)b * n_seg + seg_first) * H_STRIDE + H_L0);
+    if (one_seg) flush_hist(h, 4096, hist + ((size_t)b * n_seg + seg_first) * H_STRIDE + hist_off);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -713,7 +769,7 @@ __global__ __launch_bounds__(BLOCK) void k_list_hist(uint64_t n, const uint32_t*
         const SegState* st = &states[(size_t)b * n_seg + tr.seg];
         if (st->none) continue;
         const uint32_t pshift = st->shift[level - 1], shift = st->shift[level], mask = st->nbins[level] - 1u;
-        const uint32_t prefix = st->prefix, voidk = st->has_void;
+        const uint32_t prefix = st->prefix;
         const uint32_t c = cnt[bb];
         const uint32_t maxcnt = max(max(__shfl(c, 0, 64), __shfl(c, 16, 64)), max(__shfl(c, 32, 64), __shfl(c, 48, 64)));
         const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tr.start + (lane >> 4) * SUB;
@@ -727,7 +783,7 @@ __global__ __launch_bounds__(BLOCK) void k_list_hist(uint64_t n, const uint32_t*
             } else if (j < c) {
                 k = keys[j];
             }
-            bool part = (j < c) && (k >> pshift) == prefix && !(voidk && k == VOID_KEY);
+            bool part = (j < c) && (k >> pshift) == prefix;
             const uint32_t digit = (k >> shift) & mask;
             unsigned long long active = __ballot(part);
             while (active) {
@@ -767,8 +823,15 @@ __global__ __launch_bounds__(BLOCK) void k_count(uint64_t n, const uint32_t* __r
             cnt[bb] = cnt_cand[((size_t)b * T + t) * SUBS + (lane >> 4)];
         }
     }
-    uint32_t gtc = 0;
-    if (cnt_gt) { const uint4 g4 = *reinterpret_cast<const uint4*>(cnt_gt + (size_t)t * SUBS); gtc = g4.x + g4.y + g4.z + g4.w; }
+    uint32_t gtc[BPW];
+#pragma unroll
+    for (int bb = 0; bb < BPW; ++bb) {
+        gtc[bb] = 0;
+        if (cnt_gt && b0 + bb < nbatch) {
+            const uint4 g4 = *reinterpret_cast<const uint4*>(cnt_gt + ((size_t)(b0 + bb) * T + t) * SUBS);
+            gtc[bb] = g4.x + g4.y + g4.z + g4.w;
+        }
+    }
 #pragma unroll
     for (int bb = 0; bb < BPW; ++bb) {
         const uint32_t b = b0 + bb;
@@ -776,25 +839,25 @@ __global__ __launch_bounds__(BLOCK) void k_count(uint64_t n, const uint32_t* __r
         const SegState* st = &states[(size_t)b * n_seg + tr.seg];
         uint32_t sel = 0, tie = 0;
         if (!st->none) {
-            const uint32_t tau = st->tau, voidk = st->has_void, c = cnt[bb];
+            const uint32_t tau = st->tau, c = cnt[bb];
             const uint32_t* keys = cand_keys + (size_t)b * keys_stride + tr.start + (lane >> 4) * SUB;
 #pragma unroll
             for (int i = 0; i < KPL; ++i) {
                 const uint32_t k = kv[bb][i];
-                if ((lane & 15u) + 16u * i < c && !(voidk && k == VOID_KEY)) {
+                if ((lane & 15u) + 16u * i < c) {
                     sel += (k > tau) ? 1u : 0u;
                     tie += (k == tau) ? 1u : 0u;
                 }
             }
             for (uint32_t j = (lane & 15u) + 16u * KPL; j < c; j += 16) {
                 const uint32_t k = keys[j];
-                if (voidk && k == VOID_KEY) continue;
                 sel += (k > tau) ? 1u : 0u;
                 tie += (k == tau) ? 1u : 0u;
             }
-            sel = wave_sum(sel) + gtc;
+            sel = wave_sum(sel);
             tie = wave_sum(tie);
         }
+        if (st->has_gt && st->need0) sel += gtc[bb];
         if (lane == 0) { cnt_sel[(size_t)b * T + t] = sel; cnt_tie[(size_t)b * T + t] = tie; }
     }
 }
@@ -891,7 +954,8 @@ __global__ __launch_bounds__(BLOCK) void k_emit(uint64_t n, const uint32_t* __re
                                                 const uint32_t* __restrict__ gt_bits, const uint32_t* __restrict__ cand_bits,
                                                 const uint32_t* __restrict__ cand_keys, uint64_t keys_stride,
                                                 const uint32_t* __restrict__ tie_pre, PtrTab out_off, MutPtrTab out_idx,
-                                                uint32_t expected, uint32_t* __restrict__ pub_bits)
+                                                uint32_t expected, uint32_t* __restrict__ pub_bits,
+                                                const uint32_t* __restrict__ excl_bits, uint32_t n_words)
 {
     __shared__ uint32_t kb[4][SUBS * 16 * KPL];
     const uint32_t wid = threadIdx.x >> 6;
@@ -902,19 +966,21 @@ __global__ __launch_bounds__(BLOCK) void k_emit(uint64_t n, const uint32_t* __re
     // one wave serves the tile for BPW batches: all their loads are requested before any is used
     uint2 c2[BPW];
     uint32_t kv[BPW][KPL], off_t[BPW], tp_t[BPW];
-    uint2 g2 = make_uint2(0u, 0u);
-    if (gt_bits) g2 = *reinterpret_cast<const uint2*>(gt_bits + (size_t)t * TILE_WORDS + 2 * lane);
+    uint2 g2[BPW];
 #pragma unroll
     for (int bb = 0; bb < BPW; ++bb) {
         const uint32_t b = b0 + bb;
-        c2[bb] = make_uint2(0u, 0u); off_t[bb] = 0; tp_t[bb] = 0;
+        c2[bb] = make_uint2(0u, 0u); g2[bb] = make_uint2(0u, 0u); off_t[bb] = 0; tp_t[bb] = 0;
         if (b < nbatch) {
+            if (gt_bits) g2[bb] = *reinterpret_cast<const uint2*>(gt_bits + ((size_t)b * T + t) * TILE_WORDS + 2 * lane);
             c2[bb] = *reinterpret_cast<const uint2*>(cand_bits + ((size_t)b * T + t) * TILE_WORDS + 2 * lane);
             load_sublists<KPL>(cand_keys + (size_t)b * keys_stride + start, lane, kv[bb]);
             off_t[bb] = static_cast<const uint32_t*>(out_off.p[b])[t];
             tp_t[bb] = tie_pre[(size_t)b * (T + 1) + t];
         }
     }
+    uint32_t xw[2] = {0u, 0u};      // parameters that the certainly-selected bitmap must not contribute (explorer: the core)
+    if (excl_bits) bitmap_window(excl_bits, n_words, start + lane * 64u, xw);
     uint32_t* kbw = kb[wid];
 #pragma unroll
     for (int bb = 0; bb < BPW; ++bb) {
@@ -923,9 +989,10 @@ __global__ __launch_bounds__(BLOCK) void k_emit(uint64_t n, const uint32_t* __re
         const SegState* st = &states[(size_t)b * n_seg + seg];
         const uint32_t* keys = cand_keys + (size_t)b * keys_stride + start;
         const uint32_t* tp = tie_pre + (size_t)b * (T + 1);
-        const uint32_t none = st->none, tau = st->tau, quota = st->quota, voidk = st->has_void;
+        const uint32_t none = st->none, tau = st->tau, quota = st->quota;
         uint32_t cw[2] = {0u, 0u}, gw[2] = {0u, 0u};
-        if (!none) { cw[0] = c2[bb].x; cw[1] = c2[bb].y; gw[0] = g2.x; gw[1] = g2.y; }
+        if (!none) { cw[0] = c2[bb].x; cw[1] = c2[bb].y; }
+        if (st->has_gt && st->need0) { gw[0] = g2[bb].x & ~xw[0]; gw[1] = g2[bb].y & ~xw[1]; }
         wave_sync();
 #pragma unroll
         for (int i = 0; i < KPL; ++i) kbw[(lane >> 4) * (16 * KPL) + (lane & 15u) + 16 * i] = kv[bb][i];
@@ -942,7 +1009,6 @@ __global__ __launch_bounds__(BLOCK) void k_emit(uint64_t n, const uint32_t* __re
                 m &= m - 1;
                 const uint32_t k = (j < 16u * KPL) ? kbw[sub * (16 * KPL) + j] : keys[sub * SUB + j];
                 ++j;
-                if (voidk && k == VOID_KEY) continue;
                 if (k > tau) selmask[h] |= 1u << p;
                 else if (k == tau) tiemask[h] |= 1u << p;
             }

@@ -50,7 +50,7 @@ def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, chec
     own = sd is None
     if own:
         sd = binding.SlimDP(wl.n, wl.W, seg_off=seg_off, seed=workloads.EXPLORE_SEED)
-    sd.set_option("explore_force_fallback", 1 if force_fallback else 0)
+    sd.set_option("explore_force_fallback", int(force_fallback))
     w = to_dev(w_h)
     g = [to_dev(x) for x in g_h]
     if hint:        # the explorer candidates are drawn inside the scoring kernel
@@ -157,9 +157,14 @@ def test_tie_heavy_stress_recipe_scaled():
     assert_iteration_matches(wl, got, want)
 
 
-def test_explore_wide_bound_rerun_gives_the_same_sets():
+@pytest.mark.parametrize("mode", [1, 2])          # 1: too few candidates; 2: the sure zone alone exceeds the demand
+@pytest.mark.parametrize("hint", [False, True])
+def test_explore_wide_bound_rerun_gives_the_same_sets(mode, hint):
     wl = workloads.TINY.scaled(100_003)
-    got, want = run_iteration(wl, force_fallback=True)
+    got, want = run_iteration(wl, force_fallback=mode, hint=hint)
+    assert_iteration_matches(wl, got, want)
+    wl = workloads.GOOGLENET.scaled(300_001)
+    got, want = run_iteration(wl, force_fallback=mode, hint=hint)
     assert_iteration_matches(wl, got, want)
 
 
