@@ -100,13 +100,17 @@ struct slimdp_ctx {
     // explorer selection (batch = worker)
     SegState* e_state = nullptr;
     uint32_t *e_hist = nullptr, *e_sure_bits = nullptr, *e_cand_bits = nullptr, *e_cand_keys = nullptr;
-    uint32_t *e_cnt_gt = nullptr, *e_nsure = nullptr;
+    uint32_t *e_cnt_gt = nullptr, *e_nsure = nullptr, *e_list_count = nullptr, *e_chunk_sum = nullptr, *e_tie_list = nullptr;
+    uint4* e_list = nullptr;
+    uint64_t list_cap = 0;
+    uint32_t n_chunks = 0;
     uint32_t *e_cnt_cand = nullptr, *e_cnt_sel = nullptr, *e_cnt_tie = nullptr, *e_tie_pre = nullptr;
     // host state
     uint64_t epoch = 0;
     bool hist_pending = false;
     const float* hist_score = nullptr;
     int64_t opt_force_fallback = 0;
+    int64_t opt_per_tile_tail = 0;
     int64_t opt_pack_nbuf = 2;
     // explorer draw announced by slimdp_explore_hint (hint) / already drawn inside slimdp_score (pre)
     struct Draw {
@@ -114,6 +118,7 @@ struct slimdp_ctx {
         uint64_t iteration = 0;
         uint32_t worker0 = 0, n_workers = 0;
         std::vector<uint64_t> k_seg, m_seg;
+        bool pairs = false;          // drawn in the short-list format
         bool same(uint64_t it, uint32_t w0, uint32_t nw, const uint64_t* k, const uint64_t* m, uint32_t n_seg) const
         {
             if (!valid || it != iteration || w0 != worker0 || nw != n_workers) return false;
@@ -150,6 +155,10 @@ void carve(slimdp_ctx* c, Carver& cv)
     c->e_cand_bits = cv.take<uint32_t>(B * T * TILE_WORDS);
     c->e_cnt_gt = cv.take<uint32_t>(B * T * SUBS);
     c->e_nsure = cv.take<uint32_t>(B * S);
+    c->e_list_count = cv.take<uint32_t>(64);          // [0] candidates listed, [1] ties listed
+    c->e_tie_list = cv.take<uint32_t>(TIE_CAP);
+    c->e_chunk_sum = cv.take<uint32_t>(B * c->n_chunks);
+    c->e_list = cv.take<uint4>(c->list_cap);
     c->e_cand_keys = cv.take<uint32_t>(B * c->keys_stride);
     c->e_cnt_cand = cv.take<uint32_t>(B * T * SUBS);
     c->e_cnt_sel = cv.take<uint32_t>(B * T);
@@ -227,35 +236,35 @@ int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* his
                      const uint32_t* cand_bits, const uint32_t* cand_keys, const uint32_t* cnt_gt,
                      const uint32_t* cnt_cand, uint32_t* cnt_sel, uint32_t* cnt_tie, uint32_t* tie_pre,
                      uint64_t keys_stride, bool level1_done, const MutPtrTab& out_off, const MutPtrTab& out_idx,
-                     uint32_t expected, uint32_t* pub_bits, const uint32_t* excl_bits)
+                     uint32_t expected, uint32_t* pub_bits, const uint32_t* excl_bits, const uint32_t* gate)
 {
     const uint32_t T = c->T, S = c->n_seg;
     const dim3 wave_grid((T + 3) / 4, (nbatch + BPW - 1) / BPW);     // a wave serves its tile for BPW batches
     if (!level1_done) {
         hipLaunchKernelGGL((k_list_hist<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start,
-                           c->d_tile_seg, T, S, nbatch, st, hist, (uint32_t)H_L1, 1, cand_keys, cnt_cand, keys_stride);
+                           c->d_tile_seg, T, S, nbatch, st, hist, (uint32_t)H_L1, 1, cand_keys, cnt_cand, keys_stride, gate);
         SLIMDP_LAUNCHED(c, "k_list_hist(1)");
     }
     hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 1, (uint32_t)H_L1, S, 0, c->d_flags,
-                       nullptr);
+                       nullptr, gate ? 2 : 0);
     SLIMDP_LAUNCHED(c, "k_threshold(1)");
     hipLaunchKernelGGL((k_list_hist<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg,
-                       T, S, nbatch, st, hist, (uint32_t)H_L2, 2, cand_keys, cnt_cand, keys_stride);
+                       T, S, nbatch, st, hist, (uint32_t)H_L2, 2, cand_keys, cnt_cand, keys_stride, gate);
     SLIMDP_LAUNCHED(c, "k_list_hist(2)");
     hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 2, (uint32_t)H_L2, S, 0, c->d_flags,
-                       nullptr);
+                       nullptr, gate ? 2 : 0);
     SLIMDP_LAUNCHED(c, "k_threshold(2)");
     hipLaunchKernelGGL((k_count<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg, T, S,
-                       nbatch, st, cand_keys, cnt_cand, cnt_gt, keys_stride, cnt_sel, cnt_tie);
+                       nbatch, st, cand_keys, cnt_cand, cnt_gt, keys_stride, cnt_sel, cnt_tie, gate);
     SLIMDP_LAUNCHED(c, "k_count");
     hipLaunchKernelGGL(k_scan, dim3(1, nbatch), dim3(1024), 0, c->stream, c->d_tile_seg, c->d_seg_first_tile, T, S, st,
-                       cnt_sel, cnt_tie, tie_pre, out_off, expected, c->d_flags);
+                       cnt_sel, cnt_tie, tie_pre, out_off, expected, c->d_flags, gate);
     SLIMDP_LAUNCHED(c, "k_scan");
     PtrTab off_ro;
     for (int q = 0; q < MAXW; ++q) off_ro.p[q] = out_off.p[q];
     hipLaunchKernelGGL((k_emit<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg,
                        c->d_seg_first_tile, T, S, nbatch, st, gt_bits, cand_bits, cand_keys, keys_stride, tie_pre, off_ro,
-                       out_idx, expected, pub_bits, excl_bits, (uint32_t)((c->n + 31) / 32));
+                       out_idx, expected, pub_bits, excl_bits, (uint32_t)((c->n + 31) / 32), gate);
     SLIMDP_LAUNCHED(c, "k_emit");
     return SLIMDP_OK;
 }
@@ -292,12 +301,14 @@ int check_epoch(slimdp_ctx* c, uint64_t core_epoch)
 // words up to the first are taken without ranking (sure zone), only the words between the two
 // become candidates.  The exact rerun with every word a candidate catches a miss on either
 // side.  Returns an error code for impossible requests; *narrow is set when every segment
-// got a narrow candidate zone.
-int explorer_init(slimdp_ctx* ctx, const char* who, const uint64_t* k_seg, const uint64_t* m_seg,
-                  std::vector<SegInit>& init, uint64_t* M_out, bool* narrow)
+// got a narrow candidate zone; *short_list when the zones are so narrow that the candidates
+// of n_workers draws fit the unordered list of the short-list path with room to spare.
+int explorer_init(slimdp_ctx* ctx, const char* who, const uint64_t* k_seg, const uint64_t* m_seg, uint32_t n_workers,
+                  std::vector<SegInit>& init, uint64_t* M_out, bool* narrow, bool* short_list)
 {
     uint64_t M = 0;
-    bool all_narrow = true;
+    bool all_narrow = true, all_short = true;
+    double expect = 0.0;           // candidates of one draw
     init.resize(ctx->n_seg);
     for (uint32_t s = 0; s < ctx->n_seg; ++s) {
         const uint64_t ns = ctx->seg_off[s + 1] - ctx->seg_off[s];
@@ -314,6 +325,8 @@ int explorer_init(slimdp_ctx* ctx, const char* who, const uint64_t* k_seg, const
             if (ctx->opt_force_fallback == 1) { hi = 0.25 * (double)m / avail; lo = 0.5 * hi; }     // too few candidates
             if (ctx->opt_force_fallback == 2) { hi = 2.0 * (double)m / avail; lo = 0.75 * hi; }     // sure zone too large
             uint64_t width = 1ull << 32;                     // number of distinct candidate words
+            if (hi >= 0.25) all_short = false;
+            expect += (hi - (lo > 0.0 ? lo : 0.0)) * avail;
             if (hi >= 0.95) {
                 in.bound_m1 = 0xFFFFFFFFu;
                 all_narrow = false;
@@ -338,6 +351,8 @@ int explorer_init(slimdp_ctx* ctx, const char* who, const uint64_t* k_seg, const
     }
     *M_out = M;
     *narrow = all_narrow;
+    *short_list = all_narrow && all_short && !ctx->opt_per_tile_tail && (uint64_t)ctx->T * TILE <= 0xFFFFFFFFull &&
+                  1.25 * expect * (double)n_workers + 4096.0 <= (double)ctx->list_cap;
     return SLIMDP_OK;
 }
 
@@ -358,6 +373,9 @@ uint64_t slimdp_workspace_bytes(uint64_t n, uint32_t max_workers, uint32_t n_seg
     tmp.n = n; tmp.maxW = max_workers; tmp.n_seg = n_seg;
     tmp.T = (uint32_t)count_tiles(n, n_seg, seg_off);
     tmp.keys_stride = align_up(n, TILE) + TILE;
+    tmp.n_chunks = (tmp.T + SCAN_CHUNK - 1) / SCAN_CHUNK;
+    tmp.list_cap = (uint64_t)tmp.maxW * (64ull * tmp.T + 8192ull);
+    if (tmp.list_cap > 0x40000000ull) tmp.list_cap = 0x40000000ull;
     Carver cv(nullptr);
     carve(&tmp, cv);
     return align_up(cv.pos, 256);
@@ -384,6 +402,9 @@ int slimdp_create(slimdp_ctx** out, uint64_t n, uint32_t max_workers, uint32_t n
     c->tl = make_tiling(n, n_seg, seg_off);
     c->T = (uint32_t)c->tl.tile_seg.size();
     c->keys_stride = align_up(n, TILE) + TILE;
+    c->n_chunks = (c->T + SCAN_CHUNK - 1) / SCAN_CHUNK;
+    c->list_cap = (uint64_t)c->maxW * (64ull * c->T + 8192ull);
+    if (c->list_cap > 0x40000000ull) c->list_cap = 0x40000000ull;
     hipError_t e = hipGetDevice(&c->device);
     if (e != hipSuccess) { int rc = hip_fail(nullptr, e, "hipGetDevice (no usable GPU?)"); delete c; return rc; }
     hipDeviceProp_t prop;
@@ -436,6 +457,7 @@ int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value)
 {
     if (!ctx || !name) return SLIMDP_ERR_INVALID_ARG;
     if (strcmp(name, "explore_force_fallback") == 0) { ctx->opt_force_fallback = value; return SLIMDP_OK; }
+    if (strcmp(name, "explore_per_tile_tail") == 0) { ctx->opt_per_tile_tail = value; return SLIMDP_OK; }
     if (strcmp(name, "pack_nbuf") == 0 && (value == 1 || value == 2)) { ctx->opt_pack_nbuf = value; return SLIMDP_OK; }
     return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_set_option: unknown option '%s'", name);
 }
@@ -471,19 +493,19 @@ int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_
     for (uint32_t q = 0; q < W; ++q) vec_ok = vec_ok && aligned16(g[q]);
     // an announced explorer draw rides along if every segment has a narrow candidate bound
     PreArgs pre{};
-    bool presample = false;
+    bool presample = false, pairs = false;
     ctx->pre.valid = false;
     if (ctx->hint.valid && ctx->tl.quad_aligned) {
         std::vector<SegInit> init;
         uint64_t M = 0;
         bool narrow = false;
-        if (explorer_init(ctx, "slimdp_score(hint)", ctx->hint.k_seg.data(), ctx->hint.m_seg.data(), init, &M, &narrow) ==
-                SLIMDP_OK && narrow && M > 0) {
+        if (explorer_init(ctx, "slimdp_score(hint)", ctx->hint.k_seg.data(), ctx->hint.m_seg.data(), ctx->hint.n_workers, init,
+                          &M, &narrow, &pairs) == SLIMDP_OK && narrow && M > 0) {
             rc = init_states(ctx, ctx->e_state, init, ctx->hint.n_workers, 0);
             if (rc) return rc;
             pre.nw = ctx->hint.n_workers; pre.worker0 = ctx->hint.worker0; pre.n_seg = ctx->n_seg;
-            pre.states = ctx->e_state; pre.sure_bits = ctx->e_sure_bits; pre.cand_bits = ctx->e_cand_bits; pre.cand_keys = ctx->e_cand_keys;
-            pre.cnt_cand = ctx->e_cnt_cand; pre.keys_stride = ctx->keys_stride;
+            pre.states = ctx->e_state; pre.sure_bits = ctx->e_sure_bits; pre.cand_bits = ctx->e_cand_bits;
+            pre.cand_keys = ctx->e_cand_keys; pre.cnt_cand = ctx->e_cnt_cand; pre.keys_stride = ctx->keys_stride;
             pre.pk = PhiloxKey{(uint32_t)ctx->seed, (uint32_t)(ctx->seed >> 32), (uint32_t)ctx->hint.iteration,
                                (uint32_t)(ctx->hint.iteration >> 32)};
             presample = true;
@@ -493,7 +515,10 @@ int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_
     const dim3 grid(P), block(BLOCK);
 #define LAUNCH_SCORE(WT)                                                                                              \
     do {                                                                                                              \
-        if (presample)                                                                                                \
+        if (presample && pairs)                                                                                       \
+            hipLaunchKernelGGL((k_score<WT, 2>), grid, block, 0, ctx->stream, w, gt, (int)W, c, score,                \
+                               ctx->d_tile_start, ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok, pre);                 \
+        else if (presample)                                                                                           \
             hipLaunchKernelGGL((k_score<WT, 1>), grid, block, 0, ctx->stream, w, gt, (int)W, c, score,                \
                                ctx->d_tile_start, ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok, pre);                 \
         else                                                                                                          \
@@ -510,7 +535,7 @@ int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_
     }
 #undef LAUNCH_SCORE
     SLIMDP_LAUNCHED(ctx, "k_score");
-    if (presample) ctx->pre = ctx->hint;
+    if (presample) { ctx->pre = ctx->hint; ctx->pre.pairs = pairs; }
     ctx->hint.valid = false;
     ctx->hist_pending = true;
     ctx->hist_score = score;
@@ -551,7 +576,7 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
         SLIMDP_LAUNCHED(ctx, "k_core_hist0");
     }
     hipLaunchKernelGGL(k_threshold, dim3(S, 1), dim3(256), 0, ctx->stream, ctx->c_state, ctx->c_hist, 0, (uint32_t)H_L0, S, 0,
-                       ctx->d_flags, nullptr);
+                       ctx->d_flags, nullptr, 0);
     SLIMDP_LAUNCHED(ctx, "k_threshold(0)");
     hipLaunchKernelGGL(k_core_build, dim3(P), dim3(BLOCK), 0, ctx->stream, score, ctx->d_tile_start, ctx->d_tile_seg, T,
                        ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys, ctx->c_cnt_gt,
@@ -562,7 +587,7 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
     uint32_t* pub = ctx->tl.word_aligned ? core_bits : nullptr;
     rc = finish_selection<CORE_KPL, 1>(ctx, 1, ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys,
                           ctx->c_cnt_gt, ctx->c_cnt_cand, ctx->c_cnt_sel, ctx->c_cnt_tie, ctx->c_tie_pre, ctx->keys_stride,
-                          true, off_tab, idx_tab, (uint32_t)K, pub, nullptr);
+                          true, off_tab, idx_tab, (uint32_t)K, pub, nullptr, nullptr);
     if (rc) return rc;
     if (!pub) {
         rc = fill(ctx, core_bits, (ctx->n + 31) / 32, 0u);
@@ -587,52 +612,114 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
     if (!table_ok(expl_off, n_workers)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_sample_explore: NULL expl_off entry");
     uint64_t M = 0;
     std::vector<SegInit> init;
-    bool narrow = false;
-    int rc = explorer_init(ctx, "slimdp_sample_explore", k_seg, m_seg, init, &M, &narrow);
+    bool narrow = false, short_list = false;
+    int rc = explorer_init(ctx, "slimdp_sample_explore", k_seg, m_seg, n_workers, init, &M, &narrow, &short_list);
     if (rc) return rc;
     if (M > 0 && !table_ok(expl_idx, n_workers)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_sample_explore: NULL expl_idx entry");
     const uint32_t T = ctx->T, S = ctx->n_seg, B = n_workers;
-    // zones already drawn inside slimdp_score for exactly this request?
-    const bool cached = ctx->pre.same(iteration, worker0, n_workers, k_seg, m_seg, S);
+    // zones already drawn inside slimdp_score for exactly this request, in the format this call wants?
+    const bool cached = ctx->pre.same(iteration, worker0, n_workers, k_seg, m_seg, S) && ctx->pre.pairs == short_list;
     ctx->pre.valid = false;
     ctx->hint.valid = false;
     rc = init_states(ctx, ctx->e_state, init, B, 0);
     if (rc) return rc;
     rc = fill(ctx, ctx->e_hist, (uint64_t)B * S * H_STRIDE, 0u);
     if (rc) return rc;
-    rc = fill(ctx, ctx->e_nsure, (uint64_t)B * S, 0u);
-    if (rc) return rc;
     rc = fill(ctx, ctx->d_flags, 1, 0u);
     if (rc) return rc;
     const uint32_t P = persistent_blocks(ctx, 8, B);
     const uint32_t n_words = (uint32_t)((ctx->n + 31) / 32);
     const PhiloxKey pk{(uint32_t)ctx->seed, (uint32_t)(ctx->seed >> 32), (uint32_t)iteration, (uint32_t)(iteration >> 32)};
-    // pass 0: the zones of explorer_init; pass 1: every word a candidate, runs only if pass 0 raised the flag
-    for (int fb = 0; fb < 2; ++fb) {
-        if (fb == 1 || !cached) {
-            if (ctx->tl.quad_aligned)
-                hipLaunchKernelGGL(k_explore_keys<1>, dim3(P, B), dim3(BLOCK), 0, ctx->stream, ctx->d_tile_start,
-                                   ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_sure_bits, ctx->e_cand_bits, ctx->e_cand_keys,
-                                   ctx->e_cnt_cand, ctx->keys_stride, worker0, pk, fb, ctx->d_flags);
-            else
-                hipLaunchKernelGGL(k_explore_keys<0>, dim3(P, B), dim3(BLOCK), 0, ctx->stream, ctx->d_tile_start,
-                                   ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_sure_bits, ctx->e_cand_bits, ctx->e_cand_keys,
-                                   ctx->e_cnt_cand, ctx->keys_stride, worker0, pk, fb, ctx->d_flags);
-            SLIMDP_LAUNCHED(ctx, "k_explore_keys");
-        }
-        hipLaunchKernelGGL(k_explore_filter, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->n, ctx->d_tile_start,
-                           ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_sure_bits, ctx->e_cnt_gt, ctx->e_nsure,
-                           ctx->e_cand_bits, ctx->e_cand_keys, ctx->e_cnt_cand, ctx->keys_stride, n_words, fb, ctx->d_flags);
-        SLIMDP_LAUNCHED(ctx, "k_explore_filter");
-        hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, ctx->stream, ctx->e_state, ctx->e_hist, 0,
-                           (uint32_t)(fb ? H_L0FB : H_L0), S, fb ? 2 : 1, ctx->d_flags, ctx->e_nsure);
-        SLIMDP_LAUNCHED(ctx, "k_threshold(0)");
-    }
     MutPtrTab off_tab = make_tab<MutPtrTab>(expl_off, B);
     MutPtrTab idx_tab = make_tab<MutPtrTab>(expl_idx, B);
+#define LAUNCH_DRAW(PAIRS, WIDE)                                                                                         \
+    do {                                                                                                                 \
+        if (ctx->tl.quad_aligned)                                                                                        \
+            hipLaunchKernelGGL((k_explore_keys<1, PAIRS>), dim3(P, B), dim3(BLOCK), 0, ctx->stream, ctx->d_tile_start,   \
+                               ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_sure_bits, ctx->e_cand_bits,                  \
+                               ctx->e_cand_keys, ctx->e_cnt_cand, ctx->keys_stride, worker0, pk, WIDE, ctx->d_flags);    \
+        else                                                                                                             \
+            hipLaunchKernelGGL((k_explore_keys<0, PAIRS>), dim3(P, B), dim3(BLOCK), 0, ctx->stream, ctx->d_tile_start,   \
+                               ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_sure_bits, ctx->e_cand_bits,                  \
+                               ctx->e_cand_keys, ctx->e_cnt_cand, ctx->keys_stride, worker0, pk, WIDE, ctx->d_flags);    \
+        SLIMDP_LAUNCHED(ctx, "k_explore_keys");                                                                          \
+    } while (0)
+#define LAUNCH_FILTER(WIDE)                                                                                              \
+    do {                                                                                                                 \
+        hipLaunchKernelGGL(k_explore_filter, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->n,                 \
+                           ctx->d_tile_start, ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_sure_bits,        \
+                           ctx->e_cnt_gt, ctx->e_cand_bits, ctx->e_cand_keys, ctx->e_cnt_cand, ctx->keys_stride,         \
+                           n_words, WIDE, ctx->d_flags);                                                                 \
+        SLIMDP_LAUNCHED(ctx, "k_explore_filter");                                                                        \
+        if (!(WIDE)) {                                                                                                   \
+            hipLaunchKernelGGL(k_seg_sum, dim3(S, B), dim3(1024), 0, ctx->stream, ctx->e_cnt_gt, (uint32_t)SUBS,         \
+                               ctx->d_seg_first_tile, T, S, ctx->e_nsure, ctx->d_flags, 0);                              \
+            SLIMDP_LAUNCHED(ctx, "k_seg_sum");                                                                           \
+        }                                                                                                                \
+    } while (0)
+#define LAUNCH_T0(MODE, GATE)                                                                                            \
+    do {                                                                                                                 \
+        hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, ctx->stream, ctx->e_state, ctx->e_hist, 0,             \
+                           (uint32_t)((MODE) == 2 ? H_L0FB : H_L0), S, MODE, ctx->d_flags, ctx->e_nsure, GATE);          \
+        SLIMDP_LAUNCHED(ctx, "k_threshold(0)");                                                                          \
+    } while (0)
+    if (short_list) {
+        // the few candidates go through one unordered list; any irregularity raises the flag that
+        // switches these kernels off and the wide-bound per-tile rerun below on
+        constexpr int SBPW = 8;
+        rc = fill(ctx, ctx->e_list_count, 2, 0u);
+        if (rc) return rc;
+        if (!cached) LAUNCH_DRAW(1, 0);
+        hipLaunchKernelGGL(k_sure_count<SBPW>, dim3((T + 3) / 4, (B + SBPW - 1) / SBPW), dim3(BLOCK), 0, ctx->stream, core_bits,
+                           n_words, ctx->n, ctx->d_tile_start, ctx->d_tile_seg, T, S, B, ctx->e_sure_bits, ctx->e_cnt_sel);
+        SLIMDP_LAUNCHED(ctx, "k_sure_count");
+        hipLaunchKernelGGL(k_seg_sum, dim3(S, B), dim3(1024), 0, ctx->stream, ctx->e_cnt_sel, 1u, ctx->d_seg_first_tile, T, S,
+                           ctx->e_nsure, ctx->d_flags, 0);
+        SLIMDP_LAUNCHED(ctx, "k_seg_sum");
+        hipLaunchKernelGGL(k_cand_gather, dim3((uint32_t)(((uint64_t)B * T + 1023) / 1024)), dim3(1024), 0, ctx->stream,
+                           core_bits, ctx->n, ctx->d_tile_start, ctx->d_tile_seg, T, S, B, ctx->e_cand_keys, ctx->keys_stride,
+                           ctx->e_cnt_cand, ctx->e_list, ctx->e_list_count, (uint32_t)ctx->list_cap, ctx->d_flags);
+        SLIMDP_LAUNCHED(ctx, "k_cand_gather");
+        const uint32_t hoff[3] = {H_L0, H_L1, H_L2};
+        for (int level = 0; level < 3; ++level) {
+            hipLaunchKernelGGL(k_short_hist, dim3(512), dim3(256), 0, ctx->stream, ctx->e_list, ctx->e_list_count,
+                               (uint32_t)ctx->list_cap, ctx->e_state, ctx->e_hist, hoff[level], level, ctx->d_flags);
+            SLIMDP_LAUNCHED(ctx, "k_short_hist");
+            hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, ctx->stream, ctx->e_state, ctx->e_hist, level, hoff[level],
+                               S, level == 0 ? 1 : 0, ctx->d_flags, ctx->e_nsure, 1);
+            SLIMDP_LAUNCHED(ctx, "k_threshold");
+        }
+        hipLaunchKernelGGL(k_short_mark, dim3(512), dim3(256), 0, ctx->stream, ctx->e_list, ctx->e_list_count,
+                           (uint32_t)ctx->list_cap, ctx->e_state, T, ctx->e_sure_bits, ctx->e_cnt_sel, ctx->e_tie_list,
+                           ctx->e_list_count + 1, ctx->d_flags);
+        SLIMDP_LAUNCHED(ctx, "k_short_mark");
+        hipLaunchKernelGGL(k_short_ties, dim3(1), dim3(1024), 0, ctx->stream, ctx->e_list, ctx->e_list_count,
+                           (uint32_t)ctx->list_cap, ctx->e_state, T, ctx->e_sure_bits, ctx->e_cnt_sel, ctx->e_tie_list,
+                           ctx->e_list_count + 1, ctx->d_flags);
+        SLIMDP_LAUNCHED(ctx, "k_short_ties");
+        hipLaunchKernelGGL(k_chunk_scan, dim3(ctx->n_chunks, B), dim3(1024), 0, ctx->stream, T, ctx->e_cnt_sel, off_tab,
+                           ctx->e_chunk_sum, ctx->d_flags);
+        SLIMDP_LAUNCHED(ctx, "k_chunk_scan");
+        constexpr int EBPW = 4;
+        hipLaunchKernelGGL(k_emit_bits<EBPW>, dim3((T + 3) / 4, (B + EBPW - 1) / EBPW), dim3(BLOCK), 0, ctx->stream, core_bits,
+                           n_words, ctx->n, ctx->d_tile_start, ctx->d_tile_seg, T, S, B, ctx->e_sure_bits, ctx->e_chunk_sum,
+                           ctx->n_chunks, off_tab, idx_tab, (uint32_t)M, ctx->d_flags);
+        SLIMDP_LAUNCHED(ctx, "k_emit_bits");
+    } else {
+        if (!cached) LAUNCH_DRAW(0, 0);
+        LAUNCH_FILTER(0);
+        LAUNCH_T0(1, 0);
+    }
+    // every word a candidate, no sure zone: runs only if the flag went up
+    LAUNCH_DRAW(0, 1);
+    LAUNCH_FILTER(1);
+    LAUNCH_T0(2, 2);
+#undef LAUNCH_DRAW
+#undef LAUNCH_FILTER
+#undef LAUNCH_T0
     return finish_selection<EXPL_KPL, 4>(ctx, B, ctx->e_state, ctx->e_hist, ctx->e_sure_bits, ctx->e_cand_bits, ctx->e_cand_keys,
                             ctx->e_cnt_gt, ctx->e_cnt_cand, ctx->e_cnt_sel, ctx->e_cnt_tie, ctx->e_tie_pre, ctx->keys_stride,
-                            false, off_tab, idx_tab, (uint32_t)M, nullptr, core_bits);
+                            false, off_tab, idx_tab, (uint32_t)M, nullptr, core_bits, short_list ? ctx->d_flags : nullptr);
 }
 
 int slimdp_explore_hint(slimdp_ctx* ctx, const uint64_t* k_seg, uint32_t worker0, uint32_t n_workers,
@@ -645,8 +732,8 @@ int slimdp_explore_hint(slimdp_ctx* ctx, const uint64_t* k_seg, uint32_t worker0
         return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_explore_hint: n_workers=%u outside [1, %u]", n_workers, ctx->maxW);
     std::vector<SegInit> init;
     uint64_t M = 0;
-    bool narrow = false;
-    int rc = explorer_init(ctx, "slimdp_explore_hint", k_seg, m_seg, init, &M, &narrow);
+    bool narrow = false, short_list = false;
+    int rc = explorer_init(ctx, "slimdp_explore_hint", k_seg, m_seg, n_workers, init, &M, &narrow, &short_list);
     if (rc) return rc;
     ctx->hint.iteration = iteration; ctx->hint.worker0 = worker0; ctx->hint.n_workers = n_workers;
     ctx->hint.k_seg.assign(k_seg, k_seg + ctx->n_seg);

@@ -34,7 +34,7 @@ struct SegState {
     uint32_t tau;       // threshold key once all levels are done
     uint32_t quota;     // how many keys == tau are taken, lowest index first
     uint32_t bound_m1;  // explorer only: candidates are words r <= bound_m1, key = bound_m1 - r
-    uint32_t pad0;
+    uint32_t tie_all;   // 1: the quota covers every key equal to tau
     uint32_t shift[3];  // digit of level l = (key >> shift[l]) & (nbins[l] - 1); level 0 unmasked
     uint32_t nbins[3];
     uint32_t sure_m1;   // explorer: words r <= sure_m1 are taken without looking at their rank (if has_gt)

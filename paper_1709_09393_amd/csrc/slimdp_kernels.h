@@ -37,7 +37,7 @@ __global__ __launch_bounds__(256) void k_init_state(SegState* __restrict__ st, S
     const SegInit in = chunk.s[j];
     SegState s;
     s.need0 = in.need; s.need = in.need; s.prefix = 0; s.none = (in.need == 0) ? 1u : 0u;
-    s.tau = NONE; s.quota = 0; s.bound_m1 = in.bound_m1; s.pad0 = 0;
+    s.tau = NONE; s.quota = 0; s.bound_m1 = in.bound_m1; s.tie_all = 0;
     s.sure_m1 = in.sure_m1; s.has_gt = core ? 1u : in.has_gt;
     if (core) {
         s.shift[0] = CORE_SHIFT0; s.nbins[0] = CORE_NB0;
@@ -65,8 +65,11 @@ __global__ __launch_bounds__(256) void k_init_state(SegState* __restrict__ st, S
 //   candidate zone  sure_m1 < r <= bound_m1: one bit in the candidate bitmap plus the key
 //                   bound_m1 - r (the smallest words are the largest keys), the keys of a
 //                   sub-tile compacted in index order.
-// The draw does not look at the core; k_explore_filter applies it afterwards, so the same
-// routine serves inside the scoring kernel (core not known yet) and stand-alone.
+// The draw does not look at the core; a later pass applies it, so the same routine serves
+// inside the scoring kernel (core not known yet) and stand-alone.
+// PAIRS = 1 (every segment's candidate zone is narrow): no candidate bitmap; the sub-tile's
+// list holds (key, offset inside the sub-tile) pairs, at most SUB/2 of them: the count still
+// reports any beyond, which the gathering pass turns into the exact rerun.
 // wa, wb, wp: 32 words of LDS each, private to the calling wave (generic variant only).
 // ---------------------------------------------------------------------------------------
 struct PhiloxKey { uint32_t seed_lo, seed_hi, it_lo, it_hi; };
@@ -85,6 +88,7 @@ __device__ __forceinline__ void wave_sync()
 }
 
 // Any tile start (tiles of a segmented model may begin inside a Philox block).
+template <int PAIRS>
 __device__ __forceinline__ void explore_subtile(uint32_t worker, uint32_t t, uint32_t sub, uint32_t start, uint32_t len,
                                                 uint32_t bound_m1, uint32_t sure_m1, uint32_t has_sure, uint32_t skip,
                                                 uint32_t* wa, uint32_t* wb, uint32_t* wp, DrawOut out, PhiloxKey pk)
@@ -94,7 +98,10 @@ __device__ __forceinline__ void explore_subtile(uint32_t worker, uint32_t t, uin
     const uint32_t sub_len = (len > off) ? ((len - off < SUB) ? len - off : SUB) : 0u;
     const size_t wbase = (size_t)t * TILE_WORDS + sub * SUB_WORDS;
     if (sub_len == 0 || skip) {                                   // uniform over the wave
-        if (lane < SUB_WORDS) { out.cand_bits[wbase + lane] = 0; out.sure_bits[wbase + lane] = 0; }
+        if (lane < SUB_WORDS) {
+            if (!PAIRS) out.cand_bits[wbase + lane] = 0;
+            out.sure_bits[wbase + lane] = 0;
+        }
         if (lane == 0) out.cnt_cand[(size_t)t * SUBS + sub] = 0;
         return;
     }
@@ -132,7 +139,7 @@ __device__ __forceinline__ void explore_subtile(uint32_t worker, uint32_t t, uin
     const uint32_t incl = wave_incl_scan(pc);
     if (lane < SUB_WORDS) {
         wp[lane] = incl - pc;
-        out.cand_bits[wbase + lane] = cw;
+        if (!PAIRS) out.cand_bits[wbase + lane] = cw;
         out.sure_bits[wbase + lane] = wa[lane];
     }
     if (lane == SUB_WORDS - 1) out.cnt_cand[(size_t)t * SUBS + sub] = incl;
@@ -146,7 +153,11 @@ __device__ __forceinline__ void explore_subtile(uint32_t worker, uint32_t t, uin
                     const uint32_t gi = g0 + (uint32_t)it * 64u + lane;
                     const uint32_t e = (gi << 2) + cc - base;
                     const uint32_t rank = wp[e >> 5] + __popc(wb[e >> 5] & mask_below(e & 31));
-                    out.cand_keys[(size_t)base + rank] = key[it][cc];
+                    if (!PAIRS) out.cand_keys[(size_t)base + rank] = key[it][cc];
+                    else if (rank < SUB / 2) {
+                        out.cand_keys[(size_t)base + 2u * rank] = key[it][cc];
+                        out.cand_keys[(size_t)base + 2u * rank + 1u] = e;
+                    }
                 }
             }
         }
@@ -159,6 +170,7 @@ __device__ __forceinline__ void explore_subtile(uint32_t worker, uint32_t t, uin
 // in index order (lane L owns parameters 4L..4L+3 of the round), so a candidate's place in
 // the key list is the number of candidates in earlier rounds plus a wave ballot count, and
 // the eight bitmap words of the round are OR-reductions over groups of eight lanes.
+template <int PAIRS>
 __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t, uint32_t sub, uint32_t start, uint32_t len,
                                                      uint32_t bound_m1, uint32_t sure_m1, uint32_t has_sure, uint32_t skip,
                                                      DrawOut out, PhiloxKey pk)
@@ -169,7 +181,10 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
     uint32_t* cwords = out.cand_bits + (size_t)t * TILE_WORDS + sub * SUB_WORDS;
     uint32_t* swords = out.sure_bits + (size_t)t * TILE_WORDS + sub * SUB_WORDS;
     if (sub_len == 0 || skip) {                                   // uniform over the wave
-        if (lane < SUB_WORDS) { cwords[lane] = 0; swords[lane] = 0; }
+        if (lane < SUB_WORDS) {
+            if (!PAIRS) cwords[lane] = 0;
+            swords[lane] = 0;
+        }
         if (lane == 0) out.cnt_cand[(size_t)t * SUBS + sub] = 0;
         return;
     }
@@ -190,11 +205,18 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
             }
         }
         // bitmap words: lanes 8j..8j+7 make word j of this round
-        uint32_t vs = fs << (4u * (lane & 7u)), vc = fc << (4u * (lane & 7u));
-        vs |= __shfl_xor(vs, 1, 64); vc |= __shfl_xor(vc, 1, 64);
-        vs |= __shfl_xor(vs, 2, 64); vc |= __shfl_xor(vc, 2, 64);
-        vs |= __shfl_xor(vs, 4, 64); vc |= __shfl_xor(vc, 4, 64);
-        if ((lane & 7u) == 0) { swords[it * 8 + (lane >> 3)] = vs; cwords[it * 8 + (lane >> 3)] = vc; }
+        uint32_t vs = fs << (4u * (lane & 7u));
+        vs |= __shfl_xor(vs, 1, 64);
+        vs |= __shfl_xor(vs, 2, 64);
+        vs |= __shfl_xor(vs, 4, 64);
+        if ((lane & 7u) == 0) swords[it * 8 + (lane >> 3)] = vs;
+        if (!PAIRS) {
+            uint32_t vc = fc << (4u * (lane & 7u));
+            vc |= __shfl_xor(vc, 1, 64);
+            vc |= __shfl_xor(vc, 2, 64);
+            vc |= __shfl_xor(vc, 4, 64);
+            if ((lane & 7u) == 0) cwords[it * 8 + (lane >> 3)] = vc;
+        }
         // place in the list: candidates of lower lanes in this round, all four components
         uint32_t below = 0, total = 0;
 #pragma unroll
@@ -206,8 +228,13 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
         if (fc) {
             uint32_t pos = run + below;
 #pragma unroll
-            for (int cc = 0; cc < 4; ++cc)
-                if ((fc >> cc) & 1u) ckeys[pos++] = bound_m1 - r[cc];
+            for (int cc = 0; cc < 4; ++cc) {
+                if ((fc >> cc) & 1u) {
+                    if (!PAIRS) ckeys[pos] = bound_m1 - r[cc];
+                    else if (pos < SUB / 2) { ckeys[2u * pos] = bound_m1 - r[cc]; ckeys[2u * pos + 1u] = e0 + cc; }
+                    ++pos;
+                }
+            }
         }
         run += total;
     }
@@ -227,8 +254,8 @@ __device__ __forceinline__ void flush_hist(uint32_t* lds, uint32_t nb, uint32_t*
     }
 }
 
-// PRE = 1 additionally draws the explorer zones of pre.nw workers for every tile
-// (explore_subtile_fast): integer work that runs while other waves wait for memory.
+// PRE != 0 additionally draws the explorer zones of pre.nw workers for every tile
+// (explore_subtile_fast<PRE - 1>): integer work that runs while other waves wait for memory.
 struct PreArgs {
     uint32_t nw, worker0, n_seg;
     const SegState* states;
@@ -305,8 +332,8 @@ __global__ __launch_bounds__(BLOCK, 4) void k_score(const float* __restrict__ w,
                     out.cand_bits = pre.cand_bits + (size_t)b * T * TILE_WORDS;
                     out.cand_keys = pre.cand_keys + (size_t)b * pre.keys_stride;
                     out.cnt_cand = pre.cnt_cand + (size_t)b * T * SUBS;
-                    explore_subtile_fast(pre.worker0 + b, t, wid, start, len, pre_bound, pre_sure, pre_has_sure, pre_skip,
-                                         out, pre.pk);
+                    explore_subtile_fast<(PRE == 2) ? 1 : 0>(pre.worker0 + b, t, wid, start, len, pre_bound, pre_sure,
+                                                             pre_has_sure, pre_skip, out, pre.pk);
                 }
             }
             if (vec) {          // ... then score them
@@ -370,13 +397,21 @@ __global__ __launch_bounds__(BLOCK) void k_core_hist0(const float* __restrict__ 
 // `need` keys are covered.  grid (n_seg, nbatch), 256 threads.
 // mode 0: plain.  mode 1: explorer level 0 with the narrow bound; too few candidates raise
 // the rerun flag.  mode 2: explorer level 0 after the wide-bound rerun (only if flagged).
+// gate 1: only while the rerun flag is down; gate 2: only once it is up; 0: always.
+// The kernels of the per-tile tail take the flag word as `gate` (nullptr: always run) and
+// return at once while it is down: they then serve the rerun after the short-list path.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states, const uint32_t* __restrict__ hist,
                                                    int level, uint32_t hist_off, uint32_t n_seg, int mode,
-                                                   uint32_t* __restrict__ flags, const uint32_t* __restrict__ nsure)
+                                                   uint32_t* __restrict__ flags, const uint32_t* __restrict__ nsure, int gate)
 {
     __shared__ uint32_t wtot[4];
     __shared__ uint32_t sh_bcast[2];
+    if (gate) {          // other blocks of this launch may raise the flag: one read per block
+        if (threadIdx.x == 0) sh_bcast[0] = flags[0];
+        __syncthreads();
+        if ((sh_bcast[0] != 0) != (gate == 2)) return;
+    }
     const uint32_t seg = blockIdx.x, b = blockIdx.y;
     SegState* st = &states[(size_t)b * n_seg + seg];
     const uint32_t* hp = hist + ((size_t)b * n_seg + seg) * H_STRIDE + hist_off;
@@ -434,13 +469,12 @@ __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states
                 const uint32_t np = (level == 0) ? bin : ((prefix << bits) | bin);
                 st->prefix = np;
                 st->need = need - run;
-                if (level == 2) { st->tau = np; st->quota = need - run; }
+                if (level == 2) { st->tau = np; st->quota = need - run; st->tie_all = (need - run == cnt) ? 1u : 0u; }
                 break;
             }
             run += cnt;
         }
     }
-    (void)sh_bcast;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -547,7 +581,7 @@ __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ 
 // Stand-alone draw over every (worker, tile); each wave owns one sub-tile of the block's
 // tiles.  grid (blocks, n_workers); wide != 0: the rerun with every word a candidate and no
 // sure zone, a no-op unless flagged.
-template <int FAST>
+template <int FAST, int PAIRS>
 __global__ __launch_bounds__(BLOCK) void k_explore_keys(const uint32_t* __restrict__ tile_start,
                                                         const uint32_t* __restrict__ tile_seg, uint32_t T,
                                                         uint32_t n_seg, const SegState* __restrict__ states,
@@ -574,9 +608,9 @@ __global__ __launch_bounds__(BLOCK) void k_explore_keys(const uint32_t* __restri
         const uint32_t skip = st->need0 == 0;
         const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
         if (FAST)
-            explore_subtile_fast(worker, t, wid, start, len, bound_m1, sure_m1, has_sure, skip, out, pk);
+            explore_subtile_fast<PAIRS>(worker, t, wid, start, len, bound_m1, sure_m1, has_sure, skip, out, pk);
         else
-            explore_subtile(worker, t, wid, start, len, bound_m1, sure_m1, has_sure, skip, wa[FAST ? 0 : wid],
+            explore_subtile<PAIRS>(worker, t, wid, start, len, bound_m1, sure_m1, has_sure, skip, wa[FAST ? 0 : wid],
                             wb[FAST ? 0 : wid], wp[FAST ? 0 : wid], out, pk);
     }
 }
@@ -632,8 +666,8 @@ __device__ __forceinline__ void bitmap_window(const uint32_t* __restrict__ bits,
 }
 
 // The draw does not know the core; this pass applies it.  Per (worker, tile), one wave:
-//   sure zone: counts the sure parameters outside the core per sub-tile (cnt_gt) and per
-//     segment (nsure); the bitmap itself stays as drawn, the emission masks it again;
+//   sure zone: counts the sure parameters outside the core per sub-tile (cnt_gt; k_seg_sum
+//     adds them up per segment); the bitmap itself stays as drawn, the emission masks it again;
 //   candidate zone: candidates inside the core are dropped (bitmap bit cleared, the sub-tile's
 //     key list closed up in place, its count lowered); the remaining keys feed the level-0
 //     histogram.
@@ -644,7 +678,7 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
                                                           const uint32_t* __restrict__ tile_seg, uint32_t T,
                                                           uint32_t n_seg, const SegState* __restrict__ states,
                                                           uint32_t* __restrict__ hist, const uint32_t* __restrict__ sure_bits,
-                                                          uint32_t* __restrict__ cnt_gt, uint32_t* __restrict__ nsure,
+                                                          uint32_t* __restrict__ cnt_gt,
                                                           uint32_t* __restrict__ cand_bits, uint32_t* __restrict__ cand_keys,
                                                           uint32_t* __restrict__ cnt_cand, uint64_t keys_stride,
                                                           uint32_t n_words, int wide, const uint32_t* __restrict__ flags)
@@ -658,11 +692,10 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
     const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
     const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
     if (t0 >= t1) return;
-    // one segment per block range: histogram and sure count stay on chip; otherwise straight to global memory
+    // one segment per block range: histogram in LDS; otherwise straight to global memory
     const uint32_t seg_first = (n_seg == 1) ? 0u : tile_seg[t0];
     const bool one_seg = (n_seg == 1) || seg_first == tile_seg[t1 - 1];
     const uint32_t hist_off = wide ? H_L0FB : H_L0;
-    uint32_t ns_acc = 0;
     uint32_t* klw = kl[wid];
     for (uint32_t t = t0 + wid; t < t1; t += 4) {
         const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
@@ -675,18 +708,12 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
         uint32_t kw[2];
         bitmap_window(core_bits, n_words, tr.start + lane * 64u, kw);
         const uint32_t need0 = st->need0, shift0 = wide ? 20u : st->shift[0], has_sure = wide ? 0u : st->has_gt;
-        if (need0 == 0) continue;
-        if (has_sure) {
-            const uint32_t sc = __popc(s2.x & ~kw[0]) + __popc(s2.y & ~kw[1]);
-            uint32_t g = sc;
+        {
+            uint32_t g = (has_sure && need0) ? __popc(s2.x & ~kw[0]) + __popc(s2.y & ~kw[1]) : 0u;
             g += __shfl_xor(g, 1, 64); g += __shfl_xor(g, 2, 64); g += __shfl_xor(g, 4, 64); g += __shfl_xor(g, 8, 64);
             if ((lane & 15u) == 0) cnt_gt[bt * SUBS + (lane >> 4)] = g;
-            if (one_seg) ns_acc += sc;
-            else {
-                const uint32_t tot = wave_sum(sc);
-                if (lane == 0 && tot) atomicAdd(&nsure[(size_t)b * n_seg + tr.seg], tot);
-            }
         }
+        if (need0 == 0) continue;
         const uint32_t cw[2] = {c2.x, c2.y};
         if (__ballot((cw[0] | cw[1]) != 0u) == 0ull) continue;
         const uint32_t nw[2] = {cw[0] & ~kw[0], cw[1] & ~kw[1]};
@@ -727,12 +754,311 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
         if (__ballot(oldc != newc) != 0ull)
             *reinterpret_cast<uint2*>(cand_bits + bt * TILE_WORDS + 2 * lane) = make_uint2(nw[0], nw[1]);
     }
-    if (one_seg) {
-        ns_acc = wave_sum(ns_acc);
-        if (lane == 0 && ns_acc) atomicAdd(&nsure[(size_t)b * n_seg + seg_first], ns_acc);
-    }
     __syncthreads();
     if (one_seg) flush_hist(h, 4096, hist + ((size_t)b * n_seg + seg_first) * H_STRIDE + hist_off);
+}
+
+// =======================================================================================
+// Explorer, short-list path (every segment's candidate zone is narrow, draw with PAIRS = 1).
+// The few candidates outside the core are collected into one unordered list; the radix
+// descent, the decision against tau and the tie ranks run over that list; the chosen
+// candidates are then set in the sure bitmap, which alone drives the ordered emission.
+// Every kernel of the path returns at once when flags[0] is raised (the exact rerun with
+// the per-tile path follows), except where noted.
+// =======================================================================================
+// list entry: x = key, y = t * TILE + offset inside the tile, z = b * n_seg + seg, w = b
+constexpr uint32_t FLAG_RERUN = 1u;
+
+// Sure parameters outside the core, counted per tile (cnt_sel).  One wave per tile, serving
+// BPW batches.  grid (ceil(T/4), ceil(nbatch / BPW)).  Runs whatever the flag.
+template <int BPW>
+__global__ __launch_bounds__(BLOCK) void k_sure_count(const uint32_t* __restrict__ core_bits, uint32_t n_words, uint64_t n,
+                                                      const uint32_t* __restrict__ tile_start,
+                                                      const uint32_t* __restrict__ tile_seg, uint32_t T, uint32_t n_seg,
+                                                      uint32_t nbatch, const uint32_t* __restrict__ sure_bits,
+                                                      uint32_t* __restrict__ cnt_sel)
+{
+    const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b0 = blockIdx.y * BPW, lane = lane_id();
+    if (t >= T) return;
+    const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
+    uint2 s2[BPW];
+#pragma unroll
+    for (int bb = 0; bb < BPW; ++bb) {
+        s2[bb] = make_uint2(0u, 0u);
+        if (b0 + bb < nbatch)
+            s2[bb] = *reinterpret_cast<const uint2*>(sure_bits + ((size_t)(b0 + bb) * T + t) * TILE_WORDS + 2 * lane);
+    }
+    uint32_t kw[2];
+    bitmap_window(core_bits, n_words, tr.start + lane * 64u, kw);
+#pragma unroll
+    for (int bb = 0; bb < BPW; ++bb) {
+        if (b0 + bb >= nbatch) break;
+        const uint32_t tot = wave_sum(__popc(s2[bb].x & ~kw[0]) + __popc(s2[bb].y & ~kw[1]));
+        if (lane == 0) cnt_sel[(size_t)(b0 + bb) * T + t] = tot;
+    }
+}
+
+// nsure[b][seg] = sum of `per` consecutive counts for every tile of the segment.  No atomics:
+// thousands of them on one cache line take longer than this whole kernel.
+// grid (n_seg, nbatch), 1024 threads.
+__global__ __launch_bounds__(1024) void k_seg_sum(const uint32_t* __restrict__ counts, uint32_t per,
+                                                  const uint32_t* __restrict__ seg_first_tile, uint32_t T, uint32_t n_seg,
+                                                  uint32_t* __restrict__ nsure, const uint32_t* __restrict__ flags, int wide)
+{
+    __shared__ uint32_t wtot[16];
+    if (wide && flags[0] == 0) return;
+    const uint32_t seg = blockIdx.x, b = blockIdx.y;
+    const size_t x0 = ((size_t)b * T + seg_first_tile[seg]) * per, x1 = ((size_t)b * T + seg_first_tile[seg + 1]) * per;
+    uint32_t sum = 0;
+    for (size_t x = x0 + threadIdx.x; x < x1; x += 1024) sum += counts[x];
+    uint32_t total;
+    (void)block_excl_scan<16>(sum, wtot, total);
+    if (threadIdx.x == 0) nsure[(size_t)b * n_seg + seg] = total;
+}
+
+// Candidates outside the core -> list.  One thread per (batch, tile); a block reserves its
+// share of the list with one atomic.  A sub-tile with more pairs than its slots hold, or a
+// full list, raises the rerun flag.  grid ceil(nbatch * T / 1024), 1024 threads.
+__global__ __launch_bounds__(1024) void k_cand_gather(const uint32_t* __restrict__ core_bits, uint64_t n,
+                                                      const uint32_t* __restrict__ tile_start,
+                                                      const uint32_t* __restrict__ tile_seg, uint32_t T, uint32_t n_seg,
+                                                      uint32_t nbatch, const uint32_t* __restrict__ cand_keys,
+                                                      uint64_t keys_stride, const uint32_t* __restrict__ cnt_cand,
+                                                      uint4* __restrict__ list, uint32_t* __restrict__ list_count,
+                                                      uint32_t list_cap, uint32_t* __restrict__ flags)
+{
+    __shared__ uint32_t wtot[16];
+    __shared__ uint32_t sh_base;
+    if (threadIdx.x == 0) sh_base = flags[0];      // other blocks may raise the flag: one read per block
+    __syncthreads();
+    if (sh_base != 0) return;
+    const uint32_t x = blockIdx.x * 1024 + threadIdx.x;
+    const bool live = x < nbatch * T;
+    const uint32_t b = live ? x / T : 0u, t = live ? x % T : 0u;
+    uint4 c4 = make_uint4(0u, 0u, 0u, 0u);
+    if (live) c4 = *reinterpret_cast<const uint4*>(cnt_cand + (size_t)x * SUBS);
+    uint32_t cs[SUBS] = {c4.x, c4.y, c4.z, c4.w};
+    bool over = false;
+#pragma unroll
+    for (int sub = 0; sub < SUBS; ++sub)
+        if (cs[sub] > SUB / 2) { over = true; cs[sub] = 0; }
+    if (over) atomicOr(&flags[0], FLAG_RERUN);
+    uint32_t mine = 0;
+    TileRef tr{0u, 0u, 0u};
+    const uint32_t* keys = cand_keys;
+    if (cs[0] | cs[1] | cs[2] | cs[3]) {
+        tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
+        keys = cand_keys + (size_t)b * keys_stride + tr.start;
+#pragma unroll 1
+        for (int sub = 0; sub < SUBS; ++sub)
+            for (uint32_t j = 0; j < cs[sub]; ++j) {
+                const uint32_t i = tr.start + sub * SUB + keys[sub * SUB + 2 * j + 1];
+                mine += ((core_bits[i >> 5] >> (i & 31u)) & 1u) ^ 1u;
+            }
+    }
+    uint32_t total;
+    const uint32_t excl = block_excl_scan<16>(mine, wtot, total);
+    if (total == 0) return;
+    if (threadIdx.x == 0) sh_base = atomicAdd(list_count, total);
+    __syncthreads();
+    const uint32_t base = sh_base;
+    if (base + total > list_cap || base + total < base) {
+        if (threadIdx.x == 0) atomicOr(&flags[0], FLAG_RERUN);
+        return;
+    }
+    if (mine == 0) return;
+    uint32_t o = base + excl;
+#pragma unroll 1
+    for (int sub = 0; sub < SUBS; ++sub)
+        for (uint32_t j = 0; j < cs[sub]; ++j) {
+            const uint32_t key = keys[sub * SUB + 2 * j], e = keys[sub * SUB + 2 * j + 1];
+            const uint32_t i = tr.start + sub * SUB + e;
+            if ((core_bits[i >> 5] >> (i & 31u)) & 1u) continue;
+            list[o++] = make_uint4(key, t * TILE + sub * SUB + e, b * n_seg + tr.seg, b);
+        }
+}
+
+// Histogram of one radix level over the list.  grid: any, grid-stride.
+__global__ __launch_bounds__(256) void k_short_hist(const uint4* __restrict__ list, const uint32_t* __restrict__ list_count,
+                                                    uint32_t list_cap, const SegState* __restrict__ states,
+                                                    uint32_t* __restrict__ hist, uint32_t hist_off, int level,
+                                                    const uint32_t* __restrict__ flags)
+{
+    if (flags[0] != 0) return;
+    const uint32_t cnt = min(list_count[0], list_cap);
+    for (uint32_t j = blockIdx.x * 256 + threadIdx.x; j < cnt; j += gridDim.x * 256) {
+        const uint4 e = list[j];
+        const SegState* st = &states[e.z];
+        if (st->none) continue;
+        uint32_t digit;
+        if (level == 0) digit = e.x >> st->shift[0];
+        else {
+            if ((e.x >> st->shift[level - 1]) != st->prefix) continue;
+            digit = (e.x >> st->shift[level]) & (st->nbins[level] - 1u);
+        }
+        atomicAdd(&hist[(size_t)e.z * H_STRIDE + hist_off + digit], 1u);
+    }
+}
+
+// Decision of every list entry against its segment's tau.  A chosen candidate is added to
+// the sure bitmap and to its tile's count.  Entries equal to tau: all taken if the quota
+// covers them all, otherwise they go to the tie list for k_short_ties (a full tie list raises
+// the rerun flag).
+constexpr uint32_t TIE_CAP = 4096;
+__device__ __forceinline__ void short_take(const uint4 e, uint32_t T, uint32_t* __restrict__ sure_bits,
+                                           uint32_t* __restrict__ cnt_sel)
+{
+    const uint32_t t = e.y / TILE, o = e.y % TILE;
+    atomicOr(&sure_bits[((size_t)e.w * T + t) * TILE_WORDS + (o >> 5)], 1u << (o & 31u));
+    atomicAdd(&cnt_sel[(size_t)e.w * T + t], 1u);
+}
+
+__global__ __launch_bounds__(256) void k_short_mark(const uint4* __restrict__ list, const uint32_t* __restrict__ list_count,
+                                                    uint32_t list_cap, const SegState* __restrict__ states, uint32_t T,
+                                                    uint32_t* __restrict__ sure_bits, uint32_t* __restrict__ cnt_sel,
+                                                    uint32_t* __restrict__ tie_list, uint32_t* __restrict__ tie_count,
+                                                    uint32_t* __restrict__ flags)
+{
+    if (flags[0] != 0) return;
+    const uint32_t cnt = min(list_count[0], list_cap);
+    for (uint32_t j = blockIdx.x * 256 + threadIdx.x; j < cnt; j += gridDim.x * 256) {
+        const uint4 e = list[j];
+        const SegState* st = &states[e.z];
+        if (st->none) continue;
+        const uint32_t tau = st->tau;
+        if (e.x > tau || (e.x == tau && st->tie_all)) short_take(e, T, sure_bits, cnt_sel);
+        else if (e.x == tau && st->quota != 0) {
+            const uint32_t slot = atomicAdd(tie_count, 1u);
+            if (slot < TIE_CAP) tie_list[slot] = j;
+            else atomicOr(&flags[0], FLAG_RERUN);
+        }
+    }
+}
+
+// Ties that the quota covers only in part: the quota goes to the lowest positions.  The rank
+// of a tied entry is the number of tied entries of its segment below it, counted by the
+// whole block over the candidate list.  One block of 1024 threads; nothing to do as a rule.
+__global__ __launch_bounds__(1024) void k_short_ties(const uint4* __restrict__ list, const uint32_t* __restrict__ list_count,
+                                                     uint32_t list_cap, const SegState* __restrict__ states, uint32_t T,
+                                                     uint32_t* __restrict__ sure_bits, uint32_t* __restrict__ cnt_sel,
+                                                     const uint32_t* __restrict__ tie_list,
+                                                     const uint32_t* __restrict__ tie_count, const uint32_t* __restrict__ flags)
+{
+    __shared__ uint32_t wtot[16];
+    if (flags[0] != 0) return;                       // nobody raises the flag while this kernel runs
+    const uint32_t nt = min(tie_count[0], TIE_CAP);
+    const uint32_t cnt = min(list_count[0], list_cap);
+    for (uint32_t q = 0; q < nt; ++q) {
+        const uint4 e = list[tie_list[q]];
+        uint32_t below = 0;
+        for (uint32_t j = threadIdx.x; j < cnt; j += 1024) {
+            const uint4 o = list[j];
+            below += (o.z == e.z && o.x == e.x && o.y < e.y) ? 1u : 0u;
+        }
+        uint32_t rank;
+        (void)block_excl_scan<16>(below, wtot, rank);
+        if (threadIdx.x == 0 && rank < states[e.z].quota) short_take(e, T, sure_bits, cnt_sel);
+    }
+}
+
+// Exclusive prefix of the tile counts inside chunks of SCAN_CHUNK tiles, and the chunk sums.
+// grid (ceil(T / SCAN_CHUNK), nbatch), 1024 threads.
+constexpr uint32_t SCAN_CHUNK = 8192, SCAN_PER = SCAN_CHUNK / 1024;
+__device__ __forceinline__ uint32_t scan_phys(uint32_t x) { return x + (x >> 3); }     // one pad word per thread row
+
+// vals: SCAN_CHUNK*9/8 words; wtot: 16 words.  Values of the chunk are already in vals
+// (physical layout).  On return vals holds each value's exclusive prefix inside the chunk.
+__device__ __forceinline__ uint32_t scan_chunk(uint32_t* vals, uint32_t* wtot)
+{
+    uint32_t s = 0;
+    const uint32_t row = threadIdx.x * (SCAN_PER + 1);
+#pragma unroll
+    for (uint32_t e = 0; e < SCAN_PER; ++e) { const uint32_t v = vals[row + e]; vals[row + e] = s; s += v; }
+    uint32_t total;
+    const uint32_t base = block_excl_scan<16>(s, wtot, total);
+#pragma unroll
+    for (uint32_t e = 0; e < SCAN_PER; ++e) vals[row + e] += base;
+    __syncthreads();
+    return total;
+}
+
+__global__ __launch_bounds__(1024) void k_chunk_scan(uint32_t T, const uint32_t* __restrict__ cnt_sel, MutPtrTab out_off,
+                                                     uint32_t* __restrict__ chunk_sum, const uint32_t* __restrict__ flags)
+{
+    __shared__ uint32_t vals[SCAN_CHUNK + SCAN_CHUNK / 8];
+    __shared__ uint32_t wtot[16];
+    if (flags[0] != 0) return;
+    const uint32_t b = blockIdx.y, c0 = blockIdx.x * SCAN_CHUNK;
+    const uint32_t* cs = cnt_sel + (size_t)b * T;
+    uint32_t* off = static_cast<uint32_t*>(out_off.p[b]);
+    for (uint32_t x = threadIdx.x; x < SCAN_CHUNK; x += 1024) vals[scan_phys(x)] = (c0 + x < T) ? cs[c0 + x] : 0u;
+    __syncthreads();
+    const uint32_t total = scan_chunk(vals, wtot);
+    for (uint32_t x = threadIdx.x; x < SCAN_CHUNK && c0 + x < T; x += 1024) off[c0 + x] = vals[scan_phys(x)];
+    if (threadIdx.x == 0) chunk_sum[(size_t)b * gridDim.x + blockIdx.x] = total;
+}
+
+// Ordered emission from the sure bitmap (chosen candidates included) minus the core.  One
+// wave per tile and BPW batches; the wave also turns its tile's chunk-relative offset into
+// the final one.  grid (ceil(T/4), ceil(nbatch/BPW)).
+template <int BPW>
+__global__ __launch_bounds__(BLOCK) void k_emit_bits(const uint32_t* __restrict__ core_bits, uint32_t n_words, uint64_t n,
+                                                     const uint32_t* __restrict__ tile_start,
+                                                     const uint32_t* __restrict__ tile_seg, uint32_t T, uint32_t n_seg,
+                                                     uint32_t nbatch, const uint32_t* __restrict__ sure_bits,
+                                                     const uint32_t* __restrict__ chunk_sum, uint32_t n_chunks,
+                                                     MutPtrTab out_off, MutPtrTab out_idx, uint32_t expected,
+                                                     uint32_t* __restrict__ flags)
+{
+    if (flags[0] != 0) return;
+    const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b0 = blockIdx.y * BPW, lane = lane_id();
+    if (t >= T) return;
+    const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
+    const uint32_t chunk = t / SCAN_CHUNK;
+    uint2 s2[BPW];
+    uint32_t off_t[BPW];
+#pragma unroll
+    for (int bb = 0; bb < BPW; ++bb) {
+        s2[bb] = make_uint2(0u, 0u); off_t[bb] = 0;
+        if (b0 + bb < nbatch) {
+            s2[bb] = *reinterpret_cast<const uint2*>(sure_bits + ((size_t)(b0 + bb) * T + t) * TILE_WORDS + 2 * lane);
+            off_t[bb] = static_cast<const uint32_t*>(out_off.p[b0 + bb])[t];
+        }
+    }
+    uint32_t kw[2];
+    bitmap_window(core_bits, n_words, tr.start + lane * 64u, kw);
+#pragma unroll
+    for (int bb = 0; bb < BPW; ++bb) {
+        const uint32_t b = b0 + bb;
+        if (b >= nbatch) break;
+        uint32_t first = off_t[bb];
+        for (uint32_t c = 0; c < chunk; ++c) first += chunk_sum[(size_t)b * n_chunks + c];
+        const uint32_t fm0 = s2[bb].x & ~kw[0], fm1 = s2[bb].y & ~kw[1];
+        const uint32_t ocnt = __popc(fm0) + __popc(fm1);
+        const uint32_t incl = wave_incl_scan(ocnt);
+        uint32_t* out = static_cast<uint32_t*>(out_idx.p[b]);
+        uint32_t* off = static_cast<uint32_t*>(out_off.p[b]);
+        if (lane == 0) off[t] = first;
+        if (t == T - 1 && lane == 63) {
+            off[T] = first + incl;
+            if (first + incl != expected) atomicOr(&flags[1], 1u);
+        }
+        uint32_t o = first + incl - ocnt;
+        uint32_t m = fm0;
+        while (m) {
+            const uint32_t p = __ffs(m) - 1;
+            m &= m - 1;
+            if (o < expected) out[o] = tr.start + lane * 64u + p;     // never beyond the caller's list
+            ++o;
+        }
+        m = fm1;
+        while (m) {
+            const uint32_t p = __ffs(m) - 1;
+            m &= m - 1;
+            if (o < expected) out[o] = tr.start + lane * 64u + 32u + p;
+            ++o;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -746,10 +1072,11 @@ __global__ __launch_bounds__(BLOCK) void k_list_hist(uint64_t n, const uint32_t*
                                                      uint32_t nbatch, const SegState* __restrict__ states,
                                                      uint32_t* __restrict__ hist, uint32_t hist_off, int level,
                                                      const uint32_t* __restrict__ cand_keys,
-                                                     const uint32_t* __restrict__ cnt_cand, uint64_t keys_stride)
+                                                     const uint32_t* __restrict__ cnt_cand, uint64_t keys_stride,
+                                                     const uint32_t* __restrict__ gate)
 {
     const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b0 = blockIdx.y * BPW, lane = lane_id();
-    if (t >= T) return;
+    if (t >= T || (gate && gate[0] == 0)) return;
     const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
     // one wave serves the tile for BPW batches: all their loads are requested before any is used
     uint32_t kv[BPW][KPL], cnt[BPW];
@@ -808,10 +1135,11 @@ __global__ __launch_bounds__(BLOCK) void k_count(uint64_t n, const uint32_t* __r
                                                  uint32_t nbatch, const SegState* __restrict__ states,
                                                  const uint32_t* __restrict__ cand_keys, const uint32_t* __restrict__ cnt_cand,
                                                  const uint32_t* __restrict__ cnt_gt, uint64_t keys_stride,
-                                                 uint32_t* __restrict__ cnt_sel, uint32_t* __restrict__ cnt_tie)
+                                                 uint32_t* __restrict__ cnt_sel, uint32_t* __restrict__ cnt_tie,
+                                                 const uint32_t* __restrict__ gate)
 {
     const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b0 = blockIdx.y * BPW, lane = lane_id();
-    if (t >= T) return;
+    if (t >= T || (gate && gate[0] == 0)) return;
     const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
     uint32_t kv[BPW][KPL], cnt[BPW];
 #pragma unroll
@@ -868,33 +1196,15 @@ __global__ __launch_bounds__(BLOCK) void k_count(uint64_t n, const uint32_t* __r
 // The tiles go through LDS in chunks of 8192: coalesced loads, each thread scans eight
 // consecutive values (padded rows, no bank conflicts), one block scan per chunk.
 // ---------------------------------------------------------------------------------------
-constexpr uint32_t SCAN_CHUNK = 8192, SCAN_PER = SCAN_CHUNK / 1024;
-__device__ __forceinline__ uint32_t scan_phys(uint32_t x) { return x + (x >> 3); }     // one pad word per thread row
-
-// vals: SCAN_CHUNK*9/8 words; tb: 1024 words; wtot: 16 words.  Values of the chunk are already in
-// vals (physical layout).  On return vals holds each value's exclusive prefix inside the chunk.
-__device__ __forceinline__ uint32_t scan_chunk(uint32_t* vals, uint32_t* wtot)
-{
-    uint32_t s = 0;
-    const uint32_t row = threadIdx.x * (SCAN_PER + 1);
-#pragma unroll
-    for (uint32_t e = 0; e < SCAN_PER; ++e) { const uint32_t v = vals[row + e]; vals[row + e] = s; s += v; }
-    uint32_t total;
-    const uint32_t base = block_excl_scan<16>(s, wtot, total);
-#pragma unroll
-    for (uint32_t e = 0; e < SCAN_PER; ++e) vals[row + e] += base;
-    __syncthreads();
-    return total;
-}
-
 __global__ __launch_bounds__(1024) void k_scan(const uint32_t* __restrict__ tile_seg, const uint32_t* __restrict__ seg_first_tile,
                                                uint32_t T, uint32_t n_seg, const SegState* __restrict__ states,
                                                const uint32_t* __restrict__ cnt_sel, const uint32_t* __restrict__ cnt_tie,
                                                uint32_t* __restrict__ tie_pre, MutPtrTab out_off, uint32_t expected,
-                                               uint32_t* __restrict__ flags)
+                                               uint32_t* __restrict__ flags, const uint32_t* __restrict__ gate)
 {
     __shared__ uint32_t vals[SCAN_CHUNK + SCAN_CHUNK / 8];
     __shared__ uint32_t wtot[16];
+    if (gate && gate[0] == 0) return;
     const uint32_t b = blockIdx.y;
     const uint32_t* cs = cnt_sel + (size_t)b * T;
     const uint32_t* ct = cnt_tie + (size_t)b * T;
@@ -955,12 +1265,13 @@ __global__ __launch_bounds__(BLOCK) void k_emit(uint64_t n, const uint32_t* __re
                                                 const uint32_t* __restrict__ cand_keys, uint64_t keys_stride,
                                                 const uint32_t* __restrict__ tie_pre, PtrTab out_off, MutPtrTab out_idx,
                                                 uint32_t expected, uint32_t* __restrict__ pub_bits,
-                                                const uint32_t* __restrict__ excl_bits, uint32_t n_words)
+                                                const uint32_t* __restrict__ excl_bits, uint32_t n_words,
+                                                const uint32_t* __restrict__ gate)
 {
     __shared__ uint32_t kb[4][SUBS * 16 * KPL];
     const uint32_t wid = threadIdx.x >> 6;
     const uint32_t t = blockIdx.x * 4 + wid, b0 = blockIdx.y * BPW, lane = lane_id();
-    if (t >= T) return;
+    if (t >= T || (gate && gate[0] == 0)) return;
     const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
     const uint32_t start = tr.start, len = tr.len, seg = tr.seg;
     // one wave serves the tile for BPW batches: all their loads are requested before any is used

@@ -41,7 +41,7 @@ def host_tile_offsets(idx, tile_start):
     return np.searchsorted(idx.astype(np.int64), tile_start.astype(np.int64), side="left").astype(np.uint32)
 
 
-def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, check=True, hint=False):
+def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, check=True, hint=False, per_tile_tail=False):
     """One reselect iteration on the GPU and in the oracle; returns both results."""
     seg_off = [int(x) for x in wl.segment_offsets()]
     ks, ms = [int(x) for x in wl.k_seg()], [int(x) for x in wl.m_seg()]
@@ -51,6 +51,7 @@ def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, chec
     if own:
         sd = binding.SlimDP(wl.n, wl.W, seg_off=seg_off, seed=workloads.EXPLORE_SEED)
     sd.set_option("explore_force_fallback", int(force_fallback))
+    sd.set_option("explore_per_tile_tail", int(per_tile_tail))      # 1: never the short-list explorer path
     w = to_dev(w_h)
     g = [to_dev(x) for x in g_h]
     if hint:        # the explorer candidates are drawn inside the scoring kernel
@@ -159,13 +160,23 @@ def test_tie_heavy_stress_recipe_scaled():
 
 @pytest.mark.parametrize("mode", [1, 2])          # 1: too few candidates; 2: the sure zone alone exceeds the demand
 @pytest.mark.parametrize("hint", [False, True])
-def test_explore_wide_bound_rerun_gives_the_same_sets(mode, hint):
+@pytest.mark.parametrize("per_tile_tail", [False, True])
+def test_explore_wide_bound_rerun_gives_the_same_sets(mode, hint, per_tile_tail):
     wl = workloads.TINY.scaled(100_003)
-    got, want = run_iteration(wl, force_fallback=mode, hint=hint)
+    got, want = run_iteration(wl, force_fallback=mode, hint=hint, per_tile_tail=per_tile_tail)
     assert_iteration_matches(wl, got, want)
     wl = workloads.GOOGLENET.scaled(300_001)
-    got, want = run_iteration(wl, force_fallback=mode, hint=hint)
+    got, want = run_iteration(wl, force_fallback=mode, hint=hint, per_tile_tail=per_tile_tail)
     assert_iteration_matches(wl, got, want)
+
+
+@pytest.mark.parametrize("hint", [False, True])
+def test_explore_per_tile_tail_with_narrow_zones(hint):
+    """The general explorer tail (the one that also serves wide zones) on workloads that would take the short list."""
+    for wl in (workloads.TINY.scaled(200_003), workloads.GOOGLENET.scaled(300_001),
+               workloads.STRESS.scaled(150_001, W=5), workloads.TINY.scaled(20_005, core_pct=10, explore_pct=60)):
+        got, want = run_iteration(wl, hint=hint, per_tile_tail=True)
+        assert_iteration_matches(wl, got, want)
 
 
 @pytest.mark.parametrize("n,W", [(5, 1), (4097, 3), (200_003, 4), (150_001, 8)])
@@ -192,6 +203,33 @@ def test_hinted_draw_segmented_and_stress_and_rerun():
         wl = workloads.TINY.scaled(20_005, core_pct=core_pct, explore_pct=explore_pct)
         got, want = run_iteration(wl, hint=True)
         assert_iteration_matches(wl, got, want)
+
+
+@pytest.mark.parametrize("per_tile_tail", [False, True])
+def test_explorer_ties_at_the_threshold_take_the_lower_index(per_tile_tail):
+    """Two equal Philox words exactly at the threshold, the demand covering one of them: both explorer tails
+    must hand it to the lower index.  Pairs early in the ranking go through the short list, late ones through
+    the per-tile tail with a wide zone."""
+    n, seed = 1 << 20, 9
+    r = oracle.explore_words(seed, 0, 0, 0, n)
+    order = np.argsort(r, kind="stable")
+    rs = r[order]
+    dup = np.flatnonzero(rs[1:] == rs[:-1])
+    early, late = dup[dup < n // 8], dup[dup > n // 2]
+    assert early.size and late.size
+    sd = binding.SlimDP(n, 1, seed=seed)
+    sd.set_option("explore_per_tile_tail", int(per_tile_tail))
+    core_bits = torch.zeros((n + 31) // 32, dtype=torch.int32, device=dev())
+    core = np.zeros(0, np.uint32)
+    for d in (early[0], early[-1], late[0]):
+        m = int(d) + 1                      # the words below the pair, plus one
+        want = oracle.sample_explore(n, core, seed, 0, 0, m)
+        tied = np.sort(order[rs == rs[d]])
+        assert tied[0] in want and tied[1] not in want
+        expl_idx, expl_off = sd.sample_explore(core_bits, [0], 0, [m], 0, 1)
+        sd.synchronize()
+        assert np.array_equal(u32(expl_idx[0]), want)
+    sd.close()
 
 
 def test_hint_that_does_not_match_the_request_is_ignored():
