@@ -88,6 +88,7 @@ def main() -> int:
     wl = workloads.VGG16 if not args.n else workloads.VGG16.scaled(args.n)
     n, W, k, m = wl.n, wl.W, wl.k, wl.m
     sd = binding.SlimDP(n, W, seed=workloads.EXPLORE_SEED)
+    sd.set_option("speculative_pack", 1)   # the scoring pass keeps the likely core's update values for the pack
 
     w = torch.from_numpy(wl.weights()).to(dev)
     g = [torch.from_numpy(wl.gradient(0, q)).to(dev) for q in range(W)]

@@ -111,6 +111,24 @@ struct slimdp_ctx {
     const float* hist_score = nullptr;
     int64_t opt_force_fallback = 0;
     int64_t opt_per_tile_tail = 0;
+    // speculative packing: its own allocation, made when the option is switched on
+    struct Spec {
+        bool on = false;
+        char* mem = nullptr;
+        uint32_t* lo[2] = {nullptr, nullptr};   // capture bound per segment: [cur] read by the scoring pass, the other written by the selection
+        uint32_t* fail = nullptr;               // per segment: the selection's threshold fell below the capture bound
+        uint32_t* bits = nullptr;
+        float* vals = nullptr;
+        int cur = 0;
+        bool next_written = false;              // a selection has refreshed lo[cur ^ 1] since the last capture
+        // the capture made by the last slimdp_score, and the selection that used that score
+        bool captured = false;
+        const float* score = nullptr;
+        const float* g[MAXW] = {};
+        uint32_t W = 0;
+        int vec_ok = 0;
+        uint64_t core_epoch = 0;                // 0: no selection on the captured score yet
+    } spec;
     int64_t opt_pack_nbuf = 2;
     // explorer draw announced by slimdp_explore_hint (hint) / already drawn inside slimdp_score (pre)
     struct Draw {
@@ -236,7 +254,8 @@ int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* his
                      const uint32_t* cand_bits, const uint32_t* cand_keys, const uint32_t* cnt_gt,
                      const uint32_t* cnt_cand, uint32_t* cnt_sel, uint32_t* cnt_tie, uint32_t* tie_pre,
                      uint64_t keys_stride, bool level1_done, const MutPtrTab& out_off, const MutPtrTab& out_idx,
-                     uint32_t expected, uint32_t* pub_bits, const uint32_t* excl_bits, const uint32_t* gate)
+                     uint32_t expected, uint32_t* pub_bits, const uint32_t* excl_bits, const uint32_t* gate,
+                     SpecTau sp = SpecTau{nullptr, nullptr, nullptr})
 {
     const uint32_t T = c->T, S = c->n_seg;
     const dim3 wave_grid((T + 3) / 4, (nbatch + BPW - 1) / BPW);     // a wave serves its tile for BPW batches
@@ -246,13 +265,13 @@ int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* his
         SLIMDP_LAUNCHED(c, "k_list_hist(1)");
     }
     hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 1, (uint32_t)H_L1, S, 0, c->d_flags,
-                       nullptr, gate ? 2 : 0);
+                       nullptr, gate ? 2 : 0, SpecTau{nullptr, nullptr, nullptr});
     SLIMDP_LAUNCHED(c, "k_threshold(1)");
     hipLaunchKernelGGL((k_list_hist<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg,
                        T, S, nbatch, st, hist, (uint32_t)H_L2, 2, cand_keys, cnt_cand, keys_stride, gate);
     SLIMDP_LAUNCHED(c, "k_list_hist(2)");
     hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 2, (uint32_t)H_L2, S, 0, c->d_flags,
-                       nullptr, gate ? 2 : 0);
+                       nullptr, gate ? 2 : 0, sp);
     SLIMDP_LAUNCHED(c, "k_threshold(2)");
     hipLaunchKernelGGL((k_count<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg, T, S,
                        nbatch, st, cand_keys, cnt_cand, cnt_gt, keys_stride, cnt_sel, cnt_tie, gate);
@@ -442,6 +461,7 @@ int slimdp_destroy(slimdp_ctx* ctx)
     if (!ctx) return SLIMDP_ERR_INVALID_ARG;
     (void)hipStreamSynchronize(ctx->stream);
     hipError_t e = hipFree(ctx->ws);
+    if (ctx->spec.mem) (void)hipFree(ctx->spec.mem);
     delete ctx;
     return e == hipSuccess ? SLIMDP_OK : SLIMDP_ERR_HIP;
 }
@@ -459,6 +479,38 @@ int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value)
     if (strcmp(name, "explore_force_fallback") == 0) { ctx->opt_force_fallback = value; return SLIMDP_OK; }
     if (strcmp(name, "explore_per_tile_tail") == 0) { ctx->opt_per_tile_tail = value; return SLIMDP_OK; }
     if (strcmp(name, "pack_nbuf") == 0 && (value == 1 || value == 2)) { ctx->opt_pack_nbuf = value; return SLIMDP_OK; }
+    if (strcmp(name, "speculative_pack") == 0) {
+        ctx->spec.captured = false;
+        if (value && !ctx->spec.mem) {
+            const size_t S = ctx->n_seg;
+            Carver sizing(nullptr);
+            auto carve_spec = [&](Carver& cv) {
+                ctx->spec.lo[0] = cv.take<uint32_t>(S);
+                ctx->spec.lo[1] = cv.take<uint32_t>(S);
+                ctx->spec.fail = cv.take<uint32_t>(S);
+                ctx->spec.bits = cv.take<uint32_t>((size_t)ctx->T * TILE_WORDS);
+                ctx->spec.vals = cv.take<float>((size_t)ctx->maxW * ctx->keys_stride);
+            };
+            carve_spec(sizing);
+            hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->spec.mem), align_up(sizing.pos, 256));
+            if (e != hipSuccess) {
+                ctx->spec.mem = nullptr;
+                return fail(ctx, SLIMDP_ERR_WORKSPACE, "slimdp_set_option(speculative_pack): hipMalloc(%zu bytes): %s",
+                            align_up(sizing.pos, 256), hipGetErrorString(e));
+            }
+            Carver cv(ctx->spec.mem);
+            carve_spec(cv);
+            // nothing captured, nothing trusted until a selection has set a bound
+            int rc = fill(ctx, ctx->spec.lo[0], S, NONE);
+            if (!rc) rc = fill(ctx, ctx->spec.lo[1], S, NONE);
+            if (!rc) rc = fill(ctx, ctx->spec.fail, S, 1u);
+            if (rc) return rc;
+            ctx->spec.cur = 0;
+            ctx->spec.next_written = false;
+        }
+        ctx->spec.on = value != 0;
+        return SLIMDP_OK;
+    }
     return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_set_option: unknown option '%s'", name);
 }
 
@@ -511,19 +563,29 @@ int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_
             presample = true;
         }
     }
-    const uint32_t P = persistent_blocks(ctx, 4, 1);
+    // speculative packing: keep the update values of the parameters at or above the previous threshold
+    SpecArgs sa{};
+    const bool capture = ctx->spec.on && (W == 1 || W == 2 || W == 4 || W == 8 || W == 16);
+    ctx->spec.captured = false;
+    if (capture) {
+        if (ctx->spec.next_written) { ctx->spec.cur ^= 1; ctx->spec.next_written = false; }
+        sa.lo = ctx->spec.lo[ctx->spec.cur]; sa.bits = ctx->spec.bits; sa.vals = ctx->spec.vals; sa.stride = ctx->keys_stride;
+    }
+    const uint32_t P = persistent_blocks(ctx, SCORE_MINB, 1);
     const dim3 grid(P), block(BLOCK);
+#define LAUNCH_SCORE_P(WT, PRE, SPEC)                                                                                 \
+    hipLaunchKernelGGL((k_score<WT, PRE, SPEC>), grid, block, 0, ctx->stream, w, gt, (int)W, c, score,                \
+                       ctx->d_tile_start, ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok, pre, sa)
+#define LAUNCH_SCORE_S(WT, SPEC)                                                                                      \
+    do {                                                                                                              \
+        if (presample && pairs) LAUNCH_SCORE_P(WT, 2, SPEC);                                                          \
+        else if (presample) LAUNCH_SCORE_P(WT, 1, SPEC);                                                              \
+        else LAUNCH_SCORE_P(WT, 0, SPEC);                                                                             \
+    } while (0)
 #define LAUNCH_SCORE(WT)                                                                                              \
     do {                                                                                                              \
-        if (presample && pairs)                                                                                       \
-            hipLaunchKernelGGL((k_score<WT, 2>), grid, block, 0, ctx->stream, w, gt, (int)W, c, score,                \
-                               ctx->d_tile_start, ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok, pre);                 \
-        else if (presample)                                                                                           \
-            hipLaunchKernelGGL((k_score<WT, 1>), grid, block, 0, ctx->stream, w, gt, (int)W, c, score,                \
-                               ctx->d_tile_start, ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok, pre);                 \
-        else                                                                                                          \
-            hipLaunchKernelGGL((k_score<WT, 0>), grid, block, 0, ctx->stream, w, gt, (int)W, c, score,                \
-                               ctx->d_tile_start, ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok, pre);                 \
+        if (capture) LAUNCH_SCORE_S(WT, 1);                                                                           \
+        else LAUNCH_SCORE_S(WT, 0);                                                                                   \
     } while (0)
     switch (W) {
         case 1: LAUNCH_SCORE(1); break;
@@ -531,11 +593,17 @@ int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_
         case 4: LAUNCH_SCORE(4); break;
         case 8: LAUNCH_SCORE(8); break;
         case 16: LAUNCH_SCORE(16); break;
-        default: LAUNCH_SCORE(0); break;
+        default: LAUNCH_SCORE_S(0, 0); break;
     }
+#undef LAUNCH_SCORE_P
+#undef LAUNCH_SCORE_S
 #undef LAUNCH_SCORE
     SLIMDP_LAUNCHED(ctx, "k_score");
     if (presample) { ctx->pre = ctx->hint; ctx->pre.pairs = pairs; }
+    if (capture) {
+        ctx->spec.captured = true; ctx->spec.score = score; ctx->spec.W = W; ctx->spec.vec_ok = vec_ok; ctx->spec.core_epoch = 0;
+        for (uint32_t q = 0; q < W; ++q) ctx->spec.g[q] = g[q];
+    }
     ctx->hint.valid = false;
     ctx->hist_pending = true;
     ctx->hist_score = score;
@@ -576,7 +644,7 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
         SLIMDP_LAUNCHED(ctx, "k_core_hist0");
     }
     hipLaunchKernelGGL(k_threshold, dim3(S, 1), dim3(256), 0, ctx->stream, ctx->c_state, ctx->c_hist, 0, (uint32_t)H_L0, S, 0,
-                       ctx->d_flags, nullptr, 0);
+                       ctx->d_flags, nullptr, 0, SpecTau{nullptr, nullptr, nullptr});
     SLIMDP_LAUNCHED(ctx, "k_threshold(0)");
     hipLaunchKernelGGL(k_core_build, dim3(P), dim3(BLOCK), 0, ctx->stream, score, ctx->d_tile_start, ctx->d_tile_seg, T,
                        ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys, ctx->c_cnt_gt,
@@ -584,10 +652,14 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
     SLIMDP_LAUNCHED(ctx, "k_core_build");
     MutPtrTab off_tab = make_tab<MutPtrTab, uint32_t*>(&core_off, 1);
     MutPtrTab idx_tab = make_tab<MutPtrTab, uint32_t*>(&core_idx, 1);
+    // speculative packing: this selection rates the capture of the scoring pass it reuses and sets the next bound
+    const bool spec_sel = ctx->spec.on && ctx->spec.mem && ctx->spec.captured && reuse && ctx->spec.score == score;
+    SpecTau sp{nullptr, nullptr, nullptr};
+    if (spec_sel) sp = SpecTau{ctx->spec.lo[ctx->spec.cur], ctx->spec.lo[ctx->spec.cur ^ 1], ctx->spec.fail};
     uint32_t* pub = ctx->tl.word_aligned ? core_bits : nullptr;
     rc = finish_selection<CORE_KPL, 1>(ctx, 1, ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys,
                           ctx->c_cnt_gt, ctx->c_cnt_cand, ctx->c_cnt_sel, ctx->c_cnt_tie, ctx->c_tie_pre, ctx->keys_stride,
-                          true, off_tab, idx_tab, (uint32_t)K, pub, nullptr, nullptr);
+                          true, off_tab, idx_tab, (uint32_t)K, pub, nullptr, nullptr, sp);
     if (rc) return rc;
     if (!pub) {
         rc = fill(ctx, core_bits, (ctx->n + 31) / 32, 0u);
@@ -598,6 +670,8 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
         }
     }
     *core_epoch = ++ctx->epoch;
+    if (spec_sel) { ctx->spec.core_epoch = ctx->epoch; ctx->spec.next_written = true; }
+    else ctx->spec.core_epoch = 0;
     return SLIMDP_OK;
 }
 
@@ -660,7 +734,8 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
 #define LAUNCH_T0(MODE, GATE)                                                                                            \
     do {                                                                                                                 \
         hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, ctx->stream, ctx->e_state, ctx->e_hist, 0,             \
-                           (uint32_t)((MODE) == 2 ? H_L0FB : H_L0), S, MODE, ctx->d_flags, ctx->e_nsure, GATE);          \
+                           (uint32_t)((MODE) == 2 ? H_L0FB : H_L0), S, MODE, ctx->d_flags, ctx->e_nsure, GATE,           \
+                           SpecTau{nullptr, nullptr, nullptr});                                                          \
         SLIMDP_LAUNCHED(ctx, "k_threshold(0)");                                                                          \
     } while (0)
     if (short_list) {
@@ -686,7 +761,7 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
                                (uint32_t)ctx->list_cap, ctx->e_state, ctx->e_hist, hoff[level], level, ctx->d_flags);
             SLIMDP_LAUNCHED(ctx, "k_short_hist");
             hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, ctx->stream, ctx->e_state, ctx->e_hist, level, hoff[level],
-                               S, level == 0 ? 1 : 0, ctx->d_flags, ctx->e_nsure, 1);
+                               S, level == 0 ? 1 : 0, ctx->d_flags, ctx->e_nsure, 1, SpecTau{nullptr, nullptr, nullptr});
             SLIMDP_LAUNCHED(ctx, "k_threshold");
         }
         hipLaunchKernelGGL(k_short_mark, dim3(512), dim3(256), 0, ctx->stream, ctx->e_list, ctx->e_list_count,
@@ -783,6 +858,31 @@ int slimdp_pack(slimdp_ctx* ctx, uint32_t n_workers, const float* const* g, cons
     }
     rc = check_epoch(ctx, core_epoch);
     if (rc) return rc;
+    // the scoring pass of this very selection kept the core's update values: no second pass over the updates
+    bool spec = ctx->spec.on && ctx->spec.captured && ctx->spec.core_epoch == core_epoch && ctx->spec.W == n_workers;
+    for (uint32_t q = 0; spec && q < n_workers; ++q) spec = ctx->spec.g[q] == g[q];
+    if (spec) {
+        ctx->spec.captured = false;      // one capture serves one pack
+        if (k) {
+            hipLaunchKernelGGL(k_pack_core_spec, dim3((ctx->T + 3) / 4), dim3(BLOCK), 0, ctx->stream, make_tab<PtrTab>(g, n_workers),
+                               n_workers, ctx->n, ctx->d_tile_start, ctx->d_tile_seg, ctx->T, core_idx, core_off, ctx->spec.bits,
+                               ctx->spec.vals, ctx->keys_stride, ctx->spec.fail, ctx->spec.vec_ok,
+                               make_tab<MutPtrTab>(core_val, n_workers));
+            SLIMDP_LAUNCHED(ctx, "k_pack_core_spec");
+        }
+        CountTab mt{};
+        uint64_t mmax = 0;
+        for (uint32_t q = 0; q < n_workers; ++q) { mt.c[q] = (uint32_t)m_w[q]; if (m_w[q] > mmax) mmax = m_w[q]; }
+        if (mmax) {
+            uint64_t blocks = (mmax + 1023) / 1024;
+            if (blocks > 2048) blocks = 2048;
+            hipLaunchKernelGGL(k_pack_expl_gather, dim3((uint32_t)blocks, n_workers), dim3(256), 0, ctx->stream,
+                               make_tab<PtrTab>(g, n_workers), ctx->n, make_tab<PtrTab>(expl_idx, n_workers), mt,
+                               make_tab<MutPtrTab>(expl_val, n_workers));
+            SLIMDP_LAUNCHED(ctx, "k_pack_expl_gather");
+        }
+        return SLIMDP_OK;
+    }
     int vec_ok = 1;
     for (uint32_t q = 0; q < n_workers; ++q) vec_ok = vec_ok && aligned16(g[q]);
     if (ctx->opt_pack_nbuf == 2)

@@ -267,15 +267,33 @@ struct PreArgs {
     PhiloxKey pk;
 };
 
-template <int WT, int PRE>
-__global__ __launch_bounds__(BLOCK, 4) void k_score(const float* __restrict__ w, PtrTab g, int Wrt, float c,
+// SPEC = 1 (speculative packing, WT != 0 only) keeps, for every parameter of a full aligned
+// tile whose significance reaches spec.lo[segment] - a little below the core threshold of
+// the previous selection -, the W update values while they are in registers: one bit in
+// spec.bits, the values compacted per sub-tile in index order at spec.vals[q * stride +
+// tile start + 1024 * sub-tile + rank].  If the coming selection's threshold is not below
+// spec.lo, every core parameter is among them and the pack need not read the updates again.
+struct SpecArgs {
+    const uint32_t* lo;      // [n_seg] lowest captured significance (as bits)
+    uint32_t* bits;          // [T * TILE_WORDS]
+    float* vals;             // [W][stride]
+    uint64_t stride;
+};
+
+#ifndef SCORE_MINB
+#define SCORE_MINB 4
+#endif
+template <int WT, int PRE, int SPEC>
+__global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __restrict__ w, PtrTab g, int Wrt, float c,
                                                  float* __restrict__ S, const uint32_t* __restrict__ tile_start,
                                                  const uint32_t* __restrict__ tile_seg, uint32_t T,
-                                                 uint32_t* __restrict__ hist, int vec_ok, PreArgs pre)
+                                                 uint32_t* __restrict__ hist, int vec_ok, PreArgs pre, SpecArgs spec)
 {
+    static_assert(!SPEC || WT != 0, "capture needs the update values in registers");
     __shared__ uint32_t h[CORE_NB0];
     const int W = WT ? WT : Wrt;
-    const uint32_t lane = lane_id(), wid = threadIdx.x >> 6;
+    // the wave's number as a scalar: addresses below are then a scalar base plus a small per-lane offset
+    const uint32_t lane = lane_id(), wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     for (uint32_t b = threadIdx.x; b < CORE_NB0; b += BLOCK) h[b] = 0;
     __syncthreads();
     const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
@@ -300,6 +318,8 @@ __global__ __launch_bounds__(BLOCK, 4) void k_score(const float* __restrict__ w,
             pre_bound = st->bound_m1; pre_sure = st->sure_m1; pre_has_sure = st->has_gt; pre_skip = st->need0 == 0;
         }
         const bool vec = vec_ok && len == TILE && (start & 3u) == 0;
+        uint32_t spec_lo = 0xFFFFFFFFu, spec_run = 0;
+        if (SPEC) spec_lo = spec.lo[seg];
         if (!vec) {
             const uint32_t lo = wid * SUB, hi = (lo + SUB < len) ? lo + SUB : len;
             for (uint32_t l = lo + lane; l < hi; l += 64) {
@@ -314,14 +334,14 @@ __global__ __launch_bounds__(BLOCK, 4) void k_score(const float* __restrict__ w,
         if (!vec && !PRE) continue;
 #pragma unroll 1
         for (int r = 0; r < 4; ++r) {
-            const size_t e = (size_t)start + (size_t)wid * SUB + (size_t)r * 256 + lane * 4;
+            const size_t e0 = (size_t)start + (size_t)wid * SUB + (size_t)r * 256;      // uniform over the wave
             float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
             float4 x[WT ? WT : 1];
             if (vec) {          // request this round's lines first ...
-                wv = *reinterpret_cast<const float4*>(w + e);
+                wv = reinterpret_cast<const float4*>(w + e0)[lane];
                 if (WT) {
 #pragma unroll
-                    for (int k = 0; k < WT; ++k) x[k] = *reinterpret_cast<const float4*>(static_cast<const float*>(g.p[k]) + e);
+                    for (int k = 0; k < WT; ++k) x[k] = reinterpret_cast<const float4*>(static_cast<const float*>(g.p[k]) + e0)[lane];
                 }
             }
             if (PRE) {          // ... do this round's share of the integer work while they fly ...
@@ -343,20 +363,52 @@ __global__ __launch_bounds__(BLOCK, 4) void k_score(const float* __restrict__ w,
 #pragma unroll
                     for (int k = 1; k < WT; ++k) { a.x = a.x + x[k].x; a.y = a.y + x[k].y; a.z = a.z + x[k].z; a.w = a.w + x[k].w; }
                 } else {
-                    a = *reinterpret_cast<const float4*>(static_cast<const float*>(g.p[0]) + e);
+                    a = reinterpret_cast<const float4*>(static_cast<const float*>(g.p[0]) + e0)[lane];
                     for (int k = 1; k < W; ++k) {
-                        const float4 y = *reinterpret_cast<const float4*>(static_cast<const float*>(g.p[k]) + e);
+                        const float4 y = reinterpret_cast<const float4*>(static_cast<const float*>(g.p[k]) + e0)[lane];
                         a.x = a.x + y.x; a.y = a.y + y.y; a.z = a.z + y.z; a.w = a.w + y.w;
                     }
                 }
                 float4 sc;
                 sc.x = significance(wv.x, a.x, c); sc.y = significance(wv.y, a.y, c);
                 sc.z = significance(wv.z, a.z, c); sc.w = significance(wv.w, a.w, c);
-                *reinterpret_cast<float4*>(S + e) = sc;
+                reinterpret_cast<float4*>(S + e0)[lane] = sc;
                 atomicAdd(&h[__float_as_uint(sc.x) >> CORE_SHIFT0], 1u);
                 atomicAdd(&h[__float_as_uint(sc.y) >> CORE_SHIFT0], 1u);
                 atomicAdd(&h[__float_as_uint(sc.z) >> CORE_SHIFT0], 1u);
                 atomicAdd(&h[__float_as_uint(sc.w) >> CORE_SHIFT0], 1u);
+                if (SPEC) {
+                    const uint32_t f = (__float_as_uint(sc.x) >= spec_lo ? 1u : 0u) | (__float_as_uint(sc.y) >= spec_lo ? 2u : 0u) |
+                                       (__float_as_uint(sc.z) >= spec_lo ? 4u : 0u) | (__float_as_uint(sc.w) >= spec_lo ? 8u : 0u);
+                    uint32_t v = f << (4u * (lane & 7u));      // lanes 8j..8j+7 make bitmap word j of this round
+                    v |= __shfl_xor(v, 1, 64);
+                    v |= __shfl_xor(v, 2, 64);
+                    v |= __shfl_xor(v, 4, 64);
+                    if ((lane & 7u) == 0) spec.bits[(size_t)t * TILE_WORDS + wid * SUB_WORDS + r * 8 + (lane >> 3)] = v;
+                    uint32_t below = 0, total = 0;
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc) {
+                        const unsigned long long bal = __ballot((f >> cc) & 1u);
+                        below += __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+                        total += (uint32_t)__popcll(bal);
+                    }
+                    if (f) {
+                        float* sub_base = spec.vals + (size_t)start + wid * SUB;     // uniform; the rank is the lane's part
+                        uint32_t pos = spec_run + below;
+#pragma unroll
+                        for (int cc = 0; cc < 4; ++cc) {
+                            if ((f >> cc) & 1u) {
+#pragma unroll
+                                for (int k = 0; k < WT; ++k) {
+                                    const float val = cc == 0 ? x[k].x : cc == 1 ? x[k].y : cc == 2 ? x[k].z : x[k].w;
+                                    (sub_base + (size_t)k * spec.stride)[pos] = val;
+                                }
+                                ++pos;
+                            }
+                        }
+                    }
+                    spec_run += total;
+                }
             }
         }
     }
@@ -401,9 +453,17 @@ __global__ __launch_bounds__(BLOCK) void k_core_hist0(const float* __restrict__ 
 // The kernels of the per-tile tail take the flag word as `gate` (nullptr: always run) and
 // return at once while it is down: they then serve the rerun after the short-list path.
 // ---------------------------------------------------------------------------------------
+// At the last level of a core selection with speculative packing on (st.next != nullptr):
+// fail[seg] tells whether the threshold fell below what the scoring pass captured (cur), and
+// next[seg] becomes the capture bound of the next scoring pass: the new threshold less
+// 2^17 units in the last place (0.8 % to 1.6 %).
+struct SpecTau { const uint32_t* cur; uint32_t* next; uint32_t* fail; };
+constexpr uint32_t SPEC_MARGIN = 1u << 17;
+
 __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states, const uint32_t* __restrict__ hist,
                                                    int level, uint32_t hist_off, uint32_t n_seg, int mode,
-                                                   uint32_t* __restrict__ flags, const uint32_t* __restrict__ nsure, int gate)
+                                                   uint32_t* __restrict__ flags, const uint32_t* __restrict__ nsure, int gate,
+                                                   SpecTau sp)
 {
     __shared__ uint32_t wtot[4];
     __shared__ uint32_t sh_bcast[2];
@@ -444,7 +504,10 @@ __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states
     const uint32_t bits = (level == 0) ? 0u : (st->shift[level - 1] - st->shift[level]);
     __syncthreads();
     if (none || need == 0) {
-        if (threadIdx.x == 0) { st->none = 1; st->need = 0; st->tau = NONE; st->quota = 0; }
+        if (threadIdx.x == 0) {
+            st->none = 1; st->need = 0; st->tau = NONE; st->quota = 0;
+            if (level == 2 && sp.next) { sp.fail[seg] = 0; sp.next[seg] = NONE; }      // nothing selected, nothing to capture
+        }
         return;
     }
     const uint32_t C = (nb + 255u) / 256u;
@@ -469,7 +532,13 @@ __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states
                 const uint32_t np = (level == 0) ? bin : ((prefix << bits) | bin);
                 st->prefix = np;
                 st->need = need - run;
-                if (level == 2) { st->tau = np; st->quota = need - run; st->tie_all = (need - run == cnt) ? 1u : 0u; }
+                if (level == 2) {
+                    st->tau = np; st->quota = need - run; st->tie_all = (need - run == cnt) ? 1u : 0u;
+                    if (sp.next) {
+                        sp.fail[seg] = (np < sp.cur[seg]) ? 1u : 0u;
+                        sp.next[seg] = np > SPEC_MARGIN ? np - SPEC_MARGIN : 0u;
+                    }
+                }
                 break;
             }
             run += cnt;
@@ -1444,6 +1513,76 @@ __global__ __launch_bounds__(BLOCK) void k_gather(PtrTab src, int shared_src, ui
 // their prefix-sum positions was tried and is slower: many narrow partial-line stores.)
 // NBUF = 2: one barrier per worker; NBUF = 1: two barriers, half the LDS, more blocks per CU.
 // ---------------------------------------------------------------------------------------
+// ---------------------------------------------------------------------------------------
+// Pack after a scoring pass that captured the update values of every parameter at or above
+// spec_lo (k_score<.., SPEC = 1>): the core values of a captured tile come from the compact
+// capture (rank of the parameter among the captured ones of its sub-tile), not from the
+// update vectors.  Tiles that were not captured (ragged, unaligned, or a segment whose
+// threshold fell below the capture bound) gather from the update vectors.
+// One wave per tile, all workers (the rank is the same for all).  grid ceil(T/4).
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_pack_core_spec(PtrTab g, uint32_t nw, uint64_t n,
+                                                          const uint32_t* __restrict__ tile_start,
+                                                          const uint32_t* __restrict__ tile_seg, uint32_t T,
+                                                          const uint32_t* __restrict__ core_idx,
+                                                          const uint32_t* __restrict__ core_off,
+                                                          const uint32_t* __restrict__ spec_bits,
+                                                          const float* __restrict__ spec_vals, uint64_t stride,
+                                                          const uint32_t* __restrict__ spec_fail, int vec_ok, MutPtrTab core_val)
+{
+    __shared__ uint32_t wd[4][TILE_WORDS], pre[4][TILE_WORDS];
+    const uint32_t wid = threadIdx.x >> 6, t = blockIdx.x * 4 + wid, lane = lane_id();
+    if (t >= T) return;
+    const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
+    const uint32_t j0 = core_off[t], j1 = core_off[t + 1];
+    if (j0 >= j1) return;
+    const bool captured = vec_ok && len == TILE && (start & 3u) == 0 && spec_fail[tile_seg[t]] == 0;
+    if (captured) {
+        const uint2 w2 = *reinterpret_cast<const uint2*>(spec_bits + (size_t)t * TILE_WORDS + 2 * lane);
+        const uint32_t pc = __popc(w2.x) + __popc(w2.y);
+        const uint32_t excl = wave_incl_scan(pc) - pc;
+        const uint32_t group0 = __shfl(excl, (int)(lane & ~15u), 64);       // ranks restart at every sub-tile
+        wd[wid][2 * lane] = w2.x; wd[wid][2 * lane + 1] = w2.y;
+        pre[wid][2 * lane] = excl - group0; pre[wid][2 * lane + 1] = excl - group0 + __popc(w2.x);
+        wave_sync();
+        for (uint32_t j = j0 + lane; j < j1; j += 64) {
+            const uint32_t e = core_idx[j] - start;
+            if (e >= TILE) continue;                                        // not this tile's: the caller's lists are inconsistent
+            const uint32_t rank = pre[wid][e >> 5] + __popc(wd[wid][e >> 5] & mask_below(e & 31u));
+            const float* src = spec_vals + (size_t)start + (e & ~(SUB - 1u)) + rank;
+            for (uint32_t q = 0; q < nw; ++q) static_cast<float*>(core_val.p[q])[j] = src[(size_t)q * stride];
+        }
+    } else {
+        for (uint32_t j = j0 + lane; j < j1; j += 64) {
+            const uint32_t i = core_idx[j];
+            if (i >= n) continue;
+            for (uint32_t q = 0; q < nw; ++q) static_cast<float*>(core_val.p[q])[j] = static_cast<const float*>(g.p[q])[i];
+        }
+    }
+}
+
+// Explorer values by gathering from the update vectors.  grid (blocks, n_workers).
+struct CountTab { uint32_t c[MAXW]; };
+__global__ __launch_bounds__(256) void k_pack_expl_gather(PtrTab g, uint64_t n, PtrTab expl_idx, CountTab m_w,
+                                                          MutPtrTab expl_val)
+{
+    const uint32_t q = blockIdx.y, cnt = m_w.c[q];
+    const float* src = static_cast<const float*>(g.p[q]);
+    const uint32_t* idx = static_cast<const uint32_t*>(expl_idx.p[q]);
+    float* out = static_cast<float*>(expl_val.p[q]);
+    const uint32_t stride = gridDim.x * 256u;
+    for (uint32_t j = blockIdx.x * 256u + threadIdx.x; j < cnt; j += 4u * stride) {
+        uint32_t i[4];
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) i[u] = (j + u * stride < cnt) ? idx[j + u * stride] : 0u;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = (j + u * stride < cnt && i[u] < n) ? src[i[u]] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) if (j + u * stride < cnt) out[j + u * stride] = v[u];
+    }
+}
+
 template <int NBUF>
 __global__ __launch_bounds__(BLOCK) void k_pack_stream(PtrTab g, uint32_t nw, const uint32_t* __restrict__ tile_start,
                                                        const uint32_t* __restrict__ core_idx,

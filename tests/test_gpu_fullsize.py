@@ -1,5 +1,6 @@
 """Full-size parity: the VGG-16-sized workload in the launch configuration bench.py times
-(flat model, n = 138,357,544, W = 8, hinted explorer draw inside the scoring kernel), and
+(flat model, n = 138,357,544, W = 8, hinted explorer draw inside the scoring kernel,
+speculative packing with the capture bound of an earlier selection), and
 the tie-heavy stress workload of the same length (W = 16, values rounded through binary16).
 
 What the oracle can do at this size it does in full (score, random words, pack, merge:
@@ -56,6 +57,9 @@ def test_full_size_iteration_matches(wl):
     sd = binding.SlimDP(n, W, seed=workloads.EXPLORE_SEED)
     w = torch.from_numpy(w_h).to(dev)
     g = [torch.from_numpy(x).to(dev) for x in g_h]
+    sd.set_option("speculative_pack", 1)
+    S = sd.score(w, g, wl.c)                     # as bench.py's warm-up does: a first selection sets the capture bound
+    sd.select_core(S, [k], reuse_histogram=True)
     sd.explore_hint([k], it, [m], 0, W)
     S = sd.score(w, g, wl.c)
     core_idx, core_bits, core_off, epoch = sd.select_core(S, [k], reuse_histogram=True)

@@ -41,7 +41,8 @@ def host_tile_offsets(idx, tile_start):
     return np.searchsorted(idx.astype(np.int64), tile_start.astype(np.int64), side="left").astype(np.uint32)
 
 
-def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, check=True, hint=False, per_tile_tail=False):
+def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, check=True, hint=False, per_tile_tail=False,
+                  clobber_after_select=False):
     """One reselect iteration on the GPU and in the oracle; returns both results."""
     seg_off = [int(x) for x in wl.segment_offsets()]
     ks, ms = [int(x) for x in wl.k_seg()], [int(x) for x in wl.m_seg()]
@@ -59,6 +60,9 @@ def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, chec
     S = sd.score(w, g, wl.c)
     core_idx, core_bits, core_off, epoch = sd.select_core(S, ks, reuse_histogram=True)
     expl_idx, expl_off = sd.sample_explore(core_bits, ks, iteration, ms, 0, wl.W)
+    if clobber_after_select:        # probe: values that can then only come from what the scoring pass kept
+        for x in g:
+            x.zero_()
     core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)
     sd.merge(w, wl.lr, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
     core_out, expl_out = sd.pull(w, epoch, core_idx, core_off, expl_idx, expl_off)
@@ -229,6 +233,48 @@ def test_explorer_ties_at_the_threshold_take_the_lower_index(per_tile_tail):
         expl_idx, expl_off = sd.sample_explore(core_bits, [0], 0, [m], 0, 1)
         sd.synchronize()
         assert np.array_equal(u32(expl_idx[0]), want)
+    sd.close()
+
+
+@pytest.mark.parametrize("hint", [False, True])
+def test_speculative_pack_over_iterations(hint):
+    """With speculative packing on, the scoring pass keeps the update values of the likely core (from the second
+    iteration on, once a threshold is known) and the pack takes them from there; everything stays bit-exact.
+    Flat, segmented (tiles that are never captured), and a changing core size (threshold below the capture bound)."""
+    for wl in (workloads.TINY.scaled(200_003), workloads.GOOGLENET.scaled(300_001), workloads.STRESS.scaled(150_001, W=8)):
+        seg_off = [int(x) for x in wl.segment_offsets()]
+        sd = binding.SlimDP(wl.n, wl.W, seg_off=seg_off, seed=workloads.EXPLORE_SEED)
+        sd.set_option("speculative_pack", 1)
+        for t in range(3):
+            got, want = run_iteration(wl, iteration=t, sd=sd, hint=hint)
+            assert_iteration_matches(wl, got, want)
+        wl2 = workloads.TINY.scaled(wl.n, W=wl.W, core_pct=25) if wl.n_seg == 1 else None
+        if wl2 is not None:                 # a much larger core: its threshold lies below what was captured
+            got, want = run_iteration(wl2, iteration=3, sd=sd, hint=hint)
+            assert_iteration_matches(wl2, got, want)
+            got, want = run_iteration(wl2, iteration=4, sd=sd, hint=hint)
+            assert_iteration_matches(wl2, got, want)
+        sd.close()
+
+
+def test_speculative_pack_really_uses_the_captured_values():
+    """White-box probe: zero the update vectors after the selection.  Core values of captured tiles must still be
+    the original ones (they can only come from the capture); from the third pack on nothing is captured any more
+    (one capture serves one pack) and the same pack call reads the zeroed vectors."""
+    wl = workloads.TINY.scaled(200_000)            # whole tiles except the last one
+    sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
+    sd.set_option("speculative_pack", 1)
+    run_iteration(wl, iteration=0, sd=sd, check=False)
+    got, want = run_iteration(wl, iteration=1, sd=sd, clobber_after_select=True)
+    ts = got["tile_start"]
+    full = int(ts[-2])                              # parameters below this index lie in whole tiles
+    core = want["core_idx"]
+    inside = core < full
+    assert inside.sum() > 1000
+    for q in range(wl.W):
+        assert np.array_equal(f32bits(got["core_val"][q][inside]), f32bits(want["packs"][q][0][inside]))
+        assert not np.any(got["core_val"][q][~inside])       # the ragged last tile is gathered: zeros
+        assert not np.any(got["expl_val"][q])                # explorer values are gathered: zeros
     sd.close()
 
 
