@@ -569,7 +569,7 @@ int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_
     ctx->spec.captured = false;
     if (capture) {
         if (ctx->spec.next_written) { ctx->spec.cur ^= 1; ctx->spec.next_written = false; }
-        sa.lo = ctx->spec.lo[ctx->spec.cur]; sa.bits = ctx->spec.bits; sa.vals = ctx->spec.vals; sa.stride = ctx->keys_stride;
+        sa.lo = ctx->spec.lo[ctx->spec.cur]; sa.bits = ctx->spec.bits; sa.vals = ctx->spec.vals;
     }
     const uint32_t P = persistent_blocks(ctx, SCORE_MINB, 1);
     const dim3 grid(P), block(BLOCK);
@@ -866,7 +866,7 @@ int slimdp_pack(slimdp_ctx* ctx, uint32_t n_workers, const float* const* g, cons
         if (k) {
             hipLaunchKernelGGL(k_pack_core_spec, dim3((ctx->T + 3) / 4), dim3(BLOCK), 0, ctx->stream, make_tab<PtrTab>(g, n_workers),
                                n_workers, ctx->n, ctx->d_tile_start, ctx->d_tile_seg, ctx->T, core_idx, core_off, ctx->spec.bits,
-                               ctx->spec.vals, ctx->keys_stride, ctx->spec.fail, ctx->spec.vec_ok,
+                               ctx->spec.vals, ctx->spec.fail, ctx->spec.vec_ok,
                                make_tab<MutPtrTab>(core_val, n_workers));
             SLIMDP_LAUNCHED(ctx, "k_pack_core_spec");
         }

@@ -190,7 +190,7 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
     }
     const uint32_t base = start + off;
     uint32_t* ckeys = out.cand_keys + (size_t)base;
-    uint32_t run = 0;
+    uint32_t run = 0, sword = 0, cword = 0;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
         const uint32_t e0 = (uint32_t)it * 256u + lane * 4u;      // first of this lane's four parameters
@@ -209,13 +209,13 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
         vs |= __shfl_xor(vs, 1, 64);
         vs |= __shfl_xor(vs, 2, 64);
         vs |= __shfl_xor(vs, 4, 64);
-        if ((lane & 7u) == 0) swords[it * 8 + (lane >> 3)] = vs;
+        if ((lane & 7u) == (uint32_t)it) sword = vs;       // all eight lanes of a group hold the word: lane `it` of the group keeps it
         if (!PAIRS) {
             uint32_t vc = fc << (4u * (lane & 7u));
             vc |= __shfl_xor(vc, 1, 64);
             vc |= __shfl_xor(vc, 2, 64);
             vc |= __shfl_xor(vc, 4, 64);
-            if ((lane & 7u) == 0) cwords[it * 8 + (lane >> 3)] = vc;
+            if ((lane & 7u) == (uint32_t)it) cword = vc;
         }
         // place in the list: candidates of lower lanes in this round, all four components
         uint32_t below = 0, total = 0;
@@ -237,6 +237,11 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
             }
         }
         run += total;
+    }
+    // the 32 bitmap words of the sub-tile in one store: word 8 * it + j sits in lane 8 * j + it
+    if ((lane & 7u) < 4u) {
+        swords[(lane & 7u) * 8u + (lane >> 3)] = sword;
+        if (!PAIRS) cwords[(lane & 7u) * 8u + (lane >> 3)] = cword;
     }
     if (lane == 0) out.cnt_cand[(size_t)t * SUBS + sub] = run;
 }
@@ -270,15 +275,19 @@ struct PreArgs {
 // SPEC = 1 (speculative packing, WT != 0 only) keeps, for every parameter of a full aligned
 // tile whose significance reaches spec.lo[segment] - a little below the core threshold of
 // the previous selection -, the W update values while they are in registers: one bit in
-// spec.bits, the values compacted per sub-tile in index order at spec.vals[q * stride +
-// tile start + 1024 * sub-tile + rank].  If the coming selection's threshold is not below
-// spec.lo, every core parameter is among them and the pack need not read the updates again.
+// spec.bits, and one entry of W consecutive values in spec.vals.  The entries of a sub-tile
+// follow each other in index order from entry (tile start + 1024 * sub-tile); each round of
+// 256 parameters starts on a 128-byte line and its last line is filled up, so that every
+// line is written whole and at once (a line written in parts minutes apart leaves the cache
+// in between and costs a read-modify-write in memory).
+// If the coming selection's threshold is not below spec.lo, every core parameter is among
+// them and the pack need not read the updates again.
 struct SpecArgs {
     const uint32_t* lo;      // [n_seg] lowest captured significance (as bits)
     uint32_t* bits;          // [T * TILE_WORDS]
-    float* vals;             // [W][stride]
-    uint64_t stride;
+    float* vals;             // [entries][W]
 };
+__host__ __device__ constexpr uint32_t spec_align(uint32_t W) { return (W == 0u || W >= 32u) ? 1u : 32u / W; }   // entries per 128-byte line
 
 #ifndef SCORE_MINB
 #define SCORE_MINB 4
@@ -392,22 +401,39 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                         below += __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
                         total += (uint32_t)__popcll(bal);
                     }
+                    constexpr uint32_t A = spec_align(WT);
+                    const uint32_t padded = (total + A - 1u) & ~(A - 1u);
+                    float* sub_base = spec.vals + ((size_t)start + wid * SUB) * WT;     // uniform; the rank is the lane's part
                     if (f) {
-                        float* sub_base = spec.vals + (size_t)start + wid * SUB;     // uniform; the rank is the lane's part
                         uint32_t pos = spec_run + below;
 #pragma unroll
                         for (int cc = 0; cc < 4; ++cc) {
                             if ((f >> cc) & 1u) {
+                                float* d = sub_base + (size_t)pos * WT;
+                                if (WT >= 4) {
 #pragma unroll
-                                for (int k = 0; k < WT; ++k) {
-                                    const float val = cc == 0 ? x[k].x : cc == 1 ? x[k].y : cc == 2 ? x[k].z : x[k].w;
-                                    (sub_base + (size_t)k * spec.stride)[pos] = val;
+                                    for (int k = 0; k < WT; k += 4) {
+                                        float4 o;
+                                        o.x = cc == 0 ? x[k].x : cc == 1 ? x[k].y : cc == 2 ? x[k].z : x[k].w;
+                                        o.y = cc == 0 ? x[k + 1].x : cc == 1 ? x[k + 1].y : cc == 2 ? x[k + 1].z : x[k + 1].w;
+                                        o.z = cc == 0 ? x[k + 2].x : cc == 1 ? x[k + 2].y : cc == 2 ? x[k + 2].z : x[k + 2].w;
+                                        o.w = cc == 0 ? x[k + 3].x : cc == 1 ? x[k + 3].y : cc == 2 ? x[k + 3].z : x[k + 3].w;
+                                        reinterpret_cast<float4*>(d)[k / 4] = o;
+                                    }
+                                } else {
+#pragma unroll
+                                    for (int k = 0; k < WT; ++k) d[k] = cc == 0 ? x[k].x : cc == 1 ? x[k].y : cc == 2 ? x[k].z : x[k].w;
                                 }
                                 ++pos;
                             }
                         }
                     }
-                    spec_run += total;
+                    if (lane < padded - total) {          // fill the round's last line
+                        float* d = sub_base + (size_t)(spec_run + total + lane) * WT;
+#pragma unroll
+                        for (int k = 0; k < WT; ++k) d[k] = 0.0f;
+                    }
+                    spec_run += padded;
                 }
             }
         }
@@ -1527,7 +1553,7 @@ __global__ __launch_bounds__(BLOCK) void k_pack_core_spec(PtrTab g, uint32_t nw,
                                                           const uint32_t* __restrict__ core_idx,
                                                           const uint32_t* __restrict__ core_off,
                                                           const uint32_t* __restrict__ spec_bits,
-                                                          const float* __restrict__ spec_vals, uint64_t stride,
+                                                          const float* __restrict__ spec_vals,
                                                           const uint32_t* __restrict__ spec_fail, int vec_ok, MutPtrTab core_val)
 {
     __shared__ uint32_t wd[4][TILE_WORDS], pre[4][TILE_WORDS];
@@ -1538,19 +1564,35 @@ __global__ __launch_bounds__(BLOCK) void k_pack_core_spec(PtrTab g, uint32_t nw,
     if (j0 >= j1) return;
     const bool captured = vec_ok && len == TILE && (start & 3u) == 0 && spec_fail[tile_seg[t]] == 0;
     if (captured) {
+        // entry number of every captured parameter inside its sub-tile: lanes 4r..4r+3 hold the eight bitmap
+        // words of round r (16 rounds a tile, 4 a sub-tile); a round's entries start on a multiple of A
+        const uint32_t A = spec_align(nw);
         const uint2 w2 = *reinterpret_cast<const uint2*>(spec_bits + (size_t)t * TILE_WORDS + 2 * lane);
         const uint32_t pc = __popc(w2.x) + __popc(w2.y);
-        const uint32_t excl = wave_incl_scan(pc) - pc;
-        const uint32_t group0 = __shfl(excl, (int)(lane & ~15u), 64);       // ranks restart at every sub-tile
+        const uint32_t incl = wave_incl_scan(pc);
+        const uint32_t round0 = __shfl(incl - pc, (int)(lane & ~3u), 64);                     // captured before this round
+        const uint32_t round_total = __shfl(incl, (int)(lane | 3u), 64) - round0;
+        const uint32_t round_padded = (round_total + A - 1u) & ~(A - 1u);
+        const uint32_t pin = wave_incl_scan((lane & 3u) == 0 ? round_padded : 0u);            // padded rounds up to this one
+        const uint32_t sub0 = __shfl(pin - ((lane & 3u) == 0 ? round_padded : 0u), (int)(lane & ~15u), 64);
+        const uint32_t first = (__shfl(pin, (int)(lane & ~3u), 64) - round_padded) - sub0 + (incl - pc - round0);
         wd[wid][2 * lane] = w2.x; wd[wid][2 * lane + 1] = w2.y;
-        pre[wid][2 * lane] = excl - group0; pre[wid][2 * lane + 1] = excl - group0 + __popc(w2.x);
+        pre[wid][2 * lane] = first; pre[wid][2 * lane + 1] = first + __popc(w2.x);
         wave_sync();
         for (uint32_t j = j0 + lane; j < j1; j += 64) {
             const uint32_t e = core_idx[j] - start;
             if (e >= TILE) continue;                                        // not this tile's: the caller's lists are inconsistent
-            const uint32_t rank = pre[wid][e >> 5] + __popc(wd[wid][e >> 5] & mask_below(e & 31u));
-            const float* src = spec_vals + (size_t)start + (e & ~(SUB - 1u)) + rank;
-            for (uint32_t q = 0; q < nw; ++q) static_cast<float*>(core_val.p[q])[j] = src[(size_t)q * stride];
+            const uint32_t entry = pre[wid][e >> 5] + __popc(wd[wid][e >> 5] & mask_below(e & 31u));
+            const float* src = spec_vals + ((size_t)start + (e & ~(SUB - 1u)) + entry) * nw;
+            if ((nw & 3u) == 0) {
+                for (uint32_t q = 0; q < nw; q += 4) {
+                    const float4 v = *reinterpret_cast<const float4*>(src + q);
+                    static_cast<float*>(core_val.p[q])[j] = v.x; static_cast<float*>(core_val.p[q + 1])[j] = v.y;
+                    static_cast<float*>(core_val.p[q + 2])[j] = v.z; static_cast<float*>(core_val.p[q + 3])[j] = v.w;
+                }
+            } else {
+                for (uint32_t q = 0; q < nw; ++q) static_cast<float*>(core_val.p[q])[j] = src[q];
+            }
         }
     } else {
         for (uint32_t j = j0 + lane; j < j1; j += 64) {
