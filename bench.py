@@ -65,6 +65,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--n", type=int, default=0, help="override the parameter count (profiling runs)")
     ap.add_argument("--cpu-sample", type=int, default=8_000_000, help="oracle sample size; 0 skips the CPU leg")
+    ap.add_argument("--opt", action="append", default=[], help="library option name=value (tuning runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (known traffic) so that hardware byte counters "
                          "read under rocprofv3 --pmc can be scaled")
@@ -89,6 +90,9 @@ def main() -> int:
     n, W, k, m = wl.n, wl.W, wl.k, wl.m
     sd = binding.SlimDP(n, W, seed=workloads.EXPLORE_SEED)
     sd.set_option("speculative_pack", 1)   # the scoring pass keeps the likely core's update values for the pack
+    for kv in args.opt:
+        name, value = kv.split("=")
+        sd.set_option(name, int(value))
 
     w = torch.from_numpy(wl.weights()).to(dev)
     g = [torch.from_numpy(wl.gradient(0, q)).to(dev) for q in range(W)]
@@ -107,13 +111,15 @@ def main() -> int:
             if ev is not None:
                 ev[j].record()
         mark(0)
-        sd.explore_hint([k], t, [m], 0, W)      # host-only: the draw rides inside the scoring kernel
         sd.score(w, g, wl.c, out=S)
         mark(1)
         _, _, _, epoch = sd.select_core(S, [k], reuse_histogram=True, core_idx=core_idx, core_bits=core_bits,
                                         core_off=core_off)
         mark(2)
         sd.sample_explore(core_bits, [k], t, [m], 0, W, expl_idx=expl_idx, expl_off=expl_off)
+        # the next iteration's random draw (integer work only) starts now on the library's side stream and
+        # runs beside the memory-bound kernels that follow: every step launches exactly one draw
+        sd.explore_hint([k], t + 1, [m], 0, W)
         mark(3)
         sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch, core_val=core_val, expl_val=expl_val)
         mark(4)
@@ -127,6 +133,7 @@ def main() -> int:
         torch.cuda.synchronize()
         del a, b
 
+    sd.explore_hint([k], 0, [m], 0, W)
     for t in range(args.warmup):
         step(t)
     sd.synchronize()

@@ -85,6 +85,13 @@ struct slimdp_ctx {
     uint32_t maxW = 0, n_seg = 0, T = 0;
     uint64_t seed = 0;
     hipStream_t stream = nullptr;
+    // an announced explorer draw can run beside the caller's stream: pure integer work that fills the
+    // arithmetic units the memory-bound kernels leave idle
+    hipStream_t side = nullptr;
+    hipEvent_t ev_consumed = nullptr;      // main stream: the draw buffers of the last sample_explore have been read
+    hipEvent_t ev_drawn = nullptr;         // side stream: the announced draw is complete
+    bool side_pending = false;             // a side draw was launched and the main stream has not waited for it yet
+    bool consumed_recorded = false;
     int device = 0, cus = 256;
     std::vector<uint64_t> seg_off;
     Tiling tl;
@@ -99,6 +106,7 @@ struct slimdp_ctx {
     uint32_t *c_cnt_gt = nullptr, *c_cnt_cand = nullptr, *c_cnt_sel = nullptr, *c_cnt_tie = nullptr, *c_tie_pre = nullptr;
     // explorer selection (batch = worker)
     SegState* e_state = nullptr;
+    SegState* e_draw_state = nullptr;      // zone bounds of the announced draw (side stream)
     uint32_t *e_hist = nullptr, *e_sure_bits = nullptr, *e_cand_bits = nullptr, *e_cand_keys = nullptr;
     uint32_t *e_cnt_gt = nullptr, *e_nsure = nullptr, *e_list_count = nullptr, *e_chunk_sum = nullptr, *e_tie_list = nullptr;
     uint4* e_list = nullptr;
@@ -111,6 +119,8 @@ struct slimdp_ctx {
     const float* hist_score = nullptr;
     int64_t opt_force_fallback = 0;
     int64_t opt_per_tile_tail = 0;
+    int64_t opt_side_blocks = 2;           // blocks per compute unit of a side-stream draw
+    int64_t opt_hint_mode = 0;             // 0: the announced draw rides inside slimdp_score; 1: side stream
     // speculative packing: its own allocation, made when the option is switched on
     struct Spec {
         bool on = false;
@@ -168,6 +178,7 @@ void carve(slimdp_ctx* c, Carver& cv)
     c->c_cnt_tie = cv.take<uint32_t>(T);
     c->c_tie_pre = cv.take<uint32_t>(T + 1);
     c->e_state = cv.take<SegState>(B * S);
+    c->e_draw_state = cv.take<SegState>(B * S);
     c->e_hist = cv.take<uint32_t>(B * S * H_STRIDE);
     c->e_sure_bits = cv.take<uint32_t>(B * T * TILE_WORDS);
     c->e_cand_bits = cv.take<uint32_t>(B * T * TILE_WORDS);
@@ -224,15 +235,17 @@ int fill(slimdp_ctx* c, uint32_t* p, uint64_t count, uint32_t v)
     return SLIMDP_OK;
 }
 
-int init_states(slimdp_ctx* c, SegState* st, const std::vector<SegInit>& init, uint32_t nbatch, int core)
+int init_states(slimdp_ctx* c, SegState* st, const std::vector<SegInit>& init, uint32_t nbatch, int core,
+                hipStream_t stream = nullptr)
 {
+    if (!stream) stream = c->stream;
     for (uint32_t s0 = 0; s0 < c->n_seg; s0 += INIT_CHUNK) {
         SegInitChunk chunk;
         const uint32_t cnt = (c->n_seg - s0 < (uint32_t)INIT_CHUNK) ? c->n_seg - s0 : (uint32_t)INIT_CHUNK;
         memset(&chunk, 0, sizeof chunk);
         for (uint32_t j = 0; j < cnt; ++j) chunk.s[j] = init[s0 + j];
         const uint32_t threads = cnt * nbatch;
-        hipLaunchKernelGGL(k_init_state, dim3((threads + 255) / 256), dim3(256), 0, c->stream, st, chunk, s0, cnt,
+        hipLaunchKernelGGL(k_init_state, dim3((threads + 255) / 256), dim3(256), 0, stream, st, chunk, s0, cnt,
                            c->n_seg, nbatch, core);
         SLIMDP_LAUNCHED(c, "k_init_state");
     }
@@ -446,8 +459,14 @@ int slimdp_create(slimdp_ctx** out, uint64_t n, uint32_t max_workers, uint32_t n
     if (e == hipSuccess) e = hipMemcpy(c->d_tile_seg, c->tl.tile_seg.data(), c->T * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(c->d_seg_first_tile, c->tl.seg_first_tile.data(), (n_seg + 1) * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(c->d_flags, 0, 64 * 4);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);      // default priority
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_consumed, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_drawn, hipEventDisableTiming);
     if (e != hipSuccess) {
-        int rc = hip_fail(nullptr, e, "slimdp_create: table upload");
+        int rc = hip_fail(nullptr, e, "slimdp_create: table upload, side stream");
+        if (c->ev_consumed) (void)hipEventDestroy(c->ev_consumed);
+        if (c->ev_drawn) (void)hipEventDestroy(c->ev_drawn);
+        if (c->side) (void)hipStreamDestroy(c->side);
         (void)hipFree(c->ws);
         delete c;
         return rc;
@@ -459,7 +478,11 @@ int slimdp_create(slimdp_ctx** out, uint64_t n, uint32_t max_workers, uint32_t n
 int slimdp_destroy(slimdp_ctx* ctx)
 {
     if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    (void)hipStreamSynchronize(ctx->side);
     (void)hipStreamSynchronize(ctx->stream);
+    (void)hipEventDestroy(ctx->ev_consumed);
+    (void)hipEventDestroy(ctx->ev_drawn);
+    (void)hipStreamDestroy(ctx->side);
     hipError_t e = hipFree(ctx->ws);
     if (ctx->spec.mem) (void)hipFree(ctx->spec.mem);
     delete ctx;
@@ -478,6 +501,8 @@ int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value)
     if (!ctx || !name) return SLIMDP_ERR_INVALID_ARG;
     if (strcmp(name, "explore_force_fallback") == 0) { ctx->opt_force_fallback = value; return SLIMDP_OK; }
     if (strcmp(name, "explore_per_tile_tail") == 0) { ctx->opt_per_tile_tail = value; return SLIMDP_OK; }
+    if (strcmp(name, "side_blocks") == 0 && value >= 1 && value <= 8) { ctx->opt_side_blocks = value; return SLIMDP_OK; }
+    if (strcmp(name, "explore_hint_mode") == 0 && (value == 0 || value == 1)) { ctx->opt_hint_mode = value; return SLIMDP_OK; }
     if (strcmp(name, "pack_nbuf") == 0 && (value == 1 || value == 2)) { ctx->opt_pack_nbuf = value; return SLIMDP_OK; }
     if (strcmp(name, "speculative_pack") == 0) {
         ctx->spec.captured = false;
@@ -518,6 +543,7 @@ int slimdp_synchronize(slimdp_ctx* ctx)
 {
     if (!ctx) return SLIMDP_ERR_INVALID_ARG;
     SLIMDP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    SLIMDP_HIP(ctx, hipStreamSynchronize(ctx->side));
     uint32_t flags[2] = {0, 0};
     SLIMDP_HIP(ctx, hipMemcpy(flags, ctx->d_flags, sizeof flags, hipMemcpyDeviceToHost));
     if (flags[1]) {
@@ -546,13 +572,17 @@ int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_
     // an announced explorer draw rides along if every segment has a narrow candidate bound
     PreArgs pre{};
     bool presample = false, pairs = false;
-    ctx->pre.valid = false;
-    if (ctx->hint.valid && ctx->tl.quad_aligned) {
+    if (ctx->opt_hint_mode == 0) ctx->pre.valid = false;      // a draw made on the side stream stays valid
+    if (ctx->hint.valid && ctx->opt_hint_mode == 0 && ctx->tl.quad_aligned) {
         std::vector<SegInit> init;
         uint64_t M = 0;
         bool narrow = false;
         if (explorer_init(ctx, "slimdp_score(hint)", ctx->hint.k_seg.data(), ctx->hint.m_seg.data(), ctx->hint.n_workers, init,
                           &M, &narrow, &pairs) == SLIMDP_OK && narrow && M > 0) {
+            if (ctx->side_pending) {
+                SLIMDP_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_drawn, 0));
+                ctx->side_pending = false;
+            }
             rc = init_states(ctx, ctx->e_state, init, ctx->hint.n_workers, 0);
             if (rc) return rc;
             pre.nw = ctx->hint.n_workers; pre.worker0 = ctx->hint.worker0; pre.n_seg = ctx->n_seg;
@@ -695,6 +725,10 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
     const bool cached = ctx->pre.same(iteration, worker0, n_workers, k_seg, m_seg, S) && ctx->pre.pairs == short_list;
     ctx->pre.valid = false;
     ctx->hint.valid = false;
+    if (ctx->side_pending) {             // whether or not it is the draw this call wants: the buffers are its until it is done
+        SLIMDP_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_drawn, 0));
+        ctx->side_pending = false;
+    }
     rc = init_states(ctx, ctx->e_state, init, B, 0);
     if (rc) return rc;
     rc = fill(ctx, ctx->e_hist, (uint64_t)B * S * H_STRIDE, 0u);
@@ -792,9 +826,13 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
 #undef LAUNCH_DRAW
 #undef LAUNCH_FILTER
 #undef LAUNCH_T0
-    return finish_selection<EXPL_KPL, 4>(ctx, B, ctx->e_state, ctx->e_hist, ctx->e_sure_bits, ctx->e_cand_bits, ctx->e_cand_keys,
-                            ctx->e_cnt_gt, ctx->e_cnt_cand, ctx->e_cnt_sel, ctx->e_cnt_tie, ctx->e_tie_pre, ctx->keys_stride,
-                            false, off_tab, idx_tab, (uint32_t)M, nullptr, core_bits, short_list ? ctx->d_flags : nullptr);
+    rc = finish_selection<EXPL_KPL, 4>(ctx, B, ctx->e_state, ctx->e_hist, ctx->e_sure_bits, ctx->e_cand_bits, ctx->e_cand_keys,
+                          ctx->e_cnt_gt, ctx->e_cnt_cand, ctx->e_cnt_sel, ctx->e_cnt_tie, ctx->e_tie_pre, ctx->keys_stride,
+                          false, off_tab, idx_tab, (uint32_t)M, nullptr, core_bits, short_list ? ctx->d_flags : nullptr);
+    if (rc) return rc;
+    SLIMDP_HIP(ctx, hipEventRecord(ctx->ev_consumed, ctx->stream));      // the next announced draw may overwrite the buffers
+    ctx->consumed_recorded = true;
+    return SLIMDP_OK;
 }
 
 int slimdp_explore_hint(slimdp_ctx* ctx, const uint64_t* k_seg, uint32_t worker0, uint32_t n_workers,
@@ -813,7 +851,32 @@ int slimdp_explore_hint(slimdp_ctx* ctx, const uint64_t* k_seg, uint32_t worker0
     ctx->hint.iteration = iteration; ctx->hint.worker0 = worker0; ctx->hint.n_workers = n_workers;
     ctx->hint.k_seg.assign(k_seg, k_seg + ctx->n_seg);
     ctx->hint.m_seg.assign(m_seg, m_seg + ctx->n_seg);
-    ctx->hint.valid = true;
+    if (ctx->opt_hint_mode == 0) {           // slimdp_score will draw
+        ctx->hint.valid = true;
+        return SLIMDP_OK;
+    }
+    if (!narrow || M == 0) return SLIMDP_OK;  // nothing worth drawing ahead: slimdp_sample_explore draws itself
+    // the draw starts now on the side stream, once the previous draw's buffers have been read
+    if (ctx->consumed_recorded) SLIMDP_HIP(ctx, hipStreamWaitEvent(ctx->side, ctx->ev_consumed, 0));
+    rc = init_states(ctx, ctx->e_draw_state, init, n_workers, 0, ctx->side);
+    if (rc) return rc;
+    // few waves keep the arithmetic units busy; the wave slots stay with the kernels of the main stream
+    const uint32_t P = persistent_blocks(ctx, (uint32_t)ctx->opt_side_blocks, n_workers);
+    const PhiloxKey pk{(uint32_t)ctx->seed, (uint32_t)(ctx->seed >> 32), (uint32_t)iteration, (uint32_t)(iteration >> 32)};
+    const dim3 grid(P, n_workers), block(BLOCK);
+#define LAUNCH_SIDE_DRAW(FAST, PAIRS)                                                                                   \
+    hipLaunchKernelGGL((k_explore_keys<FAST, PAIRS>), grid, block, 0, ctx->side, ctx->d_tile_start, ctx->d_tile_seg,    \
+                       ctx->T, ctx->n_seg, ctx->e_draw_state, ctx->e_sure_bits, ctx->e_cand_bits, ctx->e_cand_keys,     \
+                       ctx->e_cnt_cand, ctx->keys_stride, worker0, pk, 0, ctx->d_flags)
+    if (ctx->tl.quad_aligned) { if (short_list) LAUNCH_SIDE_DRAW(1, 1); else LAUNCH_SIDE_DRAW(1, 0); }
+    else { if (short_list) LAUNCH_SIDE_DRAW(0, 1); else LAUNCH_SIDE_DRAW(0, 0); }
+#undef LAUNCH_SIDE_DRAW
+    SLIMDP_LAUNCHED(ctx, "k_explore_keys(side stream)");
+    SLIMDP_HIP(ctx, hipEventRecord(ctx->ev_drawn, ctx->side));
+    ctx->side_pending = true;
+    ctx->pre = ctx->hint;
+    ctx->pre.valid = true;
+    ctx->pre.pairs = short_list;
     return SLIMDP_OK;
 }
 

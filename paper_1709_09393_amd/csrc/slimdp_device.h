@@ -62,6 +62,17 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
     return v;
 }
 
+// OR over aligned groups of eight lanes, every lane of a group getting the result.  Three
+// data-parallel-primitive moves inside a row of 16 lanes (swap neighbours, swap pairs, mirror
+// each half row) instead of three trips through the LDS crossbar.
+__device__ __forceinline__ uint32_t or_reduce8(uint32_t v)
+{
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);      // quad_perm [1,0,3,2]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);      // quad_perm [2,3,0,1]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true);     // row_half_mirror
+    return v;
+}
+
 __device__ __forceinline__ uint32_t wave_sum(uint32_t v)
 {
 #pragma unroll

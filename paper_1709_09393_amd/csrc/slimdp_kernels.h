@@ -190,53 +190,54 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
     }
     const uint32_t base = start + off;
     uint32_t* ckeys = out.cand_keys + (size_t)base;
+    const uint32_t sure_excl = has_sure ? sure_m1 + 1u : 0u;         // sure_m1 < bound_m1: no overflow
     uint32_t run = 0, sword = 0, cword = 0;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
         const uint32_t e0 = (uint32_t)it * 256u + lane * 4u;      // first of this lane's four parameters
         uint32_t r[4];
         philox4x32_10((base + e0) >> 2, worker, pk.it_lo, pk.it_hi, pk.seed_lo, pk.seed_hi, r);
-        uint32_t fs = 0, fc = 0;
-#pragma unroll
-        for (int cc = 0; cc < 4; ++cc) {
-            if (e0 + cc < sub_len) {
-                if (has_sure && r[cc] <= sure_m1) fs |= 1u << cc;
-                else if (r[cc] <= bound_m1) fc |= 1u << cc;
-            }
+        // zone flags of the four parameters, without branches: sure (word below sure_excl), candidate (not sure, word
+        // up to the bound)
+        uint32_t fs = (r[0] < sure_excl ? 1u : 0u) | (r[1] < sure_excl ? 2u : 0u) | (r[2] < sure_excl ? 4u : 0u) |
+                      (r[3] < sure_excl ? 8u : 0u);
+        uint32_t fc = (r[0] <= bound_m1 ? 1u : 0u) | (r[1] <= bound_m1 ? 2u : 0u) | (r[2] <= bound_m1 ? 4u : 0u) |
+                      (r[3] <= bound_m1 ? 8u : 0u);
+        if (sub_len != SUB) {                                         // uniform: a ragged sub-tile
+            const uint32_t left = (e0 < sub_len) ? sub_len - e0 : 0u;
+            const uint32_t inside = (left >= 4u) ? 15u : ((1u << left) - 1u);
+            fs &= inside; fc &= inside;
         }
+        fc &= ~fs;
         // bitmap words: lanes 8j..8j+7 make word j of this round
-        uint32_t vs = fs << (4u * (lane & 7u));
-        vs |= __shfl_xor(vs, 1, 64);
-        vs |= __shfl_xor(vs, 2, 64);
-        vs |= __shfl_xor(vs, 4, 64);
+        const uint32_t vs = or_reduce8(fs << (4u * (lane & 7u)));
         if ((lane & 7u) == (uint32_t)it) sword = vs;       // all eight lanes of a group hold the word: lane `it` of the group keeps it
         if (!PAIRS) {
-            uint32_t vc = fc << (4u * (lane & 7u));
-            vc |= __shfl_xor(vc, 1, 64);
-            vc |= __shfl_xor(vc, 2, 64);
-            vc |= __shfl_xor(vc, 4, 64);
+            const uint32_t vc = or_reduce8(fc << (4u * (lane & 7u)));
             if ((lane & 7u) == (uint32_t)it) cword = vc;
         }
         // place in the list: candidates of lower lanes in this round, all four components
-        uint32_t below = 0, total = 0;
-#pragma unroll
-        for (int cc = 0; cc < 4; ++cc) {
-            const unsigned long long bal = __ballot((fc >> cc) & 1u);
-            below += __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
-            total += (uint32_t)__popcll(bal);
-        }
-        if (fc) {
-            uint32_t pos = run + below;
+        if (__ballot(fc != 0u) != 0ull) {                             // uniform; rare with a narrow candidate zone
+            uint32_t below = 0, total = 0;
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) {
-                if ((fc >> cc) & 1u) {
-                    if (!PAIRS) ckeys[pos] = bound_m1 - r[cc];
-                    else if (pos < SUB / 2) { ckeys[2u * pos] = bound_m1 - r[cc]; ckeys[2u * pos + 1u] = e0 + cc; }
-                    ++pos;
+                const unsigned long long bal = __ballot((fc >> cc) & 1u);
+                below += __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+                total += (uint32_t)__popcll(bal);
+            }
+            if (fc) {
+                uint32_t pos = run + below;
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    if ((fc >> cc) & 1u) {
+                        if (!PAIRS) ckeys[pos] = bound_m1 - r[cc];
+                        else if (pos < SUB / 2) { ckeys[2u * pos] = bound_m1 - r[cc]; ckeys[2u * pos + 1u] = e0 + cc; }
+                        ++pos;
+                    }
                 }
             }
+            run += total;
         }
-        run += total;
     }
     // the 32 bitmap words of the sub-tile in one store: word 8 * it + j sits in lane 8 * j + it
     if ((lane & 7u) < 4u) {
@@ -389,10 +390,7 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                 if (SPEC) {
                     const uint32_t f = (__float_as_uint(sc.x) >= spec_lo ? 1u : 0u) | (__float_as_uint(sc.y) >= spec_lo ? 2u : 0u) |
                                        (__float_as_uint(sc.z) >= spec_lo ? 4u : 0u) | (__float_as_uint(sc.w) >= spec_lo ? 8u : 0u);
-                    uint32_t v = f << (4u * (lane & 7u));      // lanes 8j..8j+7 make bitmap word j of this round
-                    v |= __shfl_xor(v, 1, 64);
-                    v |= __shfl_xor(v, 2, 64);
-                    v |= __shfl_xor(v, 4, 64);
+                    const uint32_t v = or_reduce8(f << (4u * (lane & 7u)));      // lanes 8j..8j+7 make bitmap word j of this round
                     if ((lane & 7u) == 0) spec.bits[(size_t)t * TILE_WORDS + wid * SUB_WORDS + r * 8 + (lane >> 3)] = v;
                     uint32_t below = 0, total = 0;
 #pragma unroll
@@ -641,10 +639,7 @@ __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ 
                     else if (d == b1) fc |= 1u << cc;
                 }
             }
-            uint32_t vg = fg << (4u * (lane & 7u)), vc = fc << (4u * (lane & 7u));
-            vg |= __shfl_xor(vg, 1, 64); vc |= __shfl_xor(vc, 1, 64);
-            vg |= __shfl_xor(vg, 2, 64); vc |= __shfl_xor(vc, 2, 64);
-            vg |= __shfl_xor(vg, 4, 64); vc |= __shfl_xor(vc, 4, 64);
+            const uint32_t vg = or_reduce8(fg << (4u * (lane & 7u))), vc = or_reduce8(fc << (4u * (lane & 7u)));
             if ((lane & 7u) == 0) { gwords[it * 8 + (lane >> 3)] = vg; cwords[it * 8 + (lane >> 3)] = vc; }
             ngt += __popc(fg);
             uint32_t below = 0, total = 0;
@@ -1579,19 +1574,44 @@ __global__ __launch_bounds__(BLOCK) void k_pack_core_spec(PtrTab g, uint32_t nw,
         wd[wid][2 * lane] = w2.x; wd[wid][2 * lane + 1] = w2.y;
         pre[wid][2 * lane] = first; pre[wid][2 * lane + 1] = first + __popc(w2.x);
         wave_sync();
-        for (uint32_t j = j0 + lane; j < j1; j += 64) {
-            const uint32_t e = core_idx[j] - start;
-            if (e >= TILE) continue;                                        // not this tile's: the caller's lists are inconsistent
-            const uint32_t entry = pre[wid][e >> 5] + __popc(wd[wid][e >> 5] & mask_below(e & 31u));
-            const float* src = spec_vals + ((size_t)start + (e & ~(SUB - 1u)) + entry) * nw;
+        // four list entries per lane and pass: all their index loads are requested first, then all their values
+        constexpr int U = 4;
+        for (uint32_t jb = j0; jb < j1; jb += 64 * U) {
+            uint32_t e[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t j = jb + u * 64 + lane;
+                e[u] = (j < j1) ? core_idx[j] - start : 0xFFFFFFFFu;       // beyond the tile: the caller's lists are inconsistent
+            }
             if ((nw & 3u) == 0) {
                 for (uint32_t q = 0; q < nw; q += 4) {
-                    const float4 v = *reinterpret_cast<const float4*>(src + q);
-                    static_cast<float*>(core_val.p[q])[j] = v.x; static_cast<float*>(core_val.p[q + 1])[j] = v.y;
-                    static_cast<float*>(core_val.p[q + 2])[j] = v.z; static_cast<float*>(core_val.p[q + 3])[j] = v.w;
+                    float4 v[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (e[u] < TILE) {
+                            const uint32_t entry = pre[wid][e[u] >> 5] + __popc(wd[wid][e[u] >> 5] & mask_below(e[u] & 31u));
+                            v[u] = *reinterpret_cast<const float4*>(spec_vals + ((size_t)start + (e[u] & ~(SUB - 1u)) + entry) * nw + q);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const uint32_t j = jb + u * 64 + lane;
+                        if (e[u] < TILE) {
+                            static_cast<float*>(core_val.p[q])[j] = v[u].x; static_cast<float*>(core_val.p[q + 1])[j] = v[u].y;
+                            static_cast<float*>(core_val.p[q + 2])[j] = v[u].z; static_cast<float*>(core_val.p[q + 3])[j] = v[u].w;
+                        }
+                    }
                 }
             } else {
-                for (uint32_t q = 0; q < nw; ++q) static_cast<float*>(core_val.p[q])[j] = src[q];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t j = jb + u * 64 + lane;
+                    if (e[u] >= TILE) continue;
+                    const uint32_t entry = pre[wid][e[u] >> 5] + __popc(wd[wid][e[u] >> 5] & mask_below(e[u] & 31u));
+                    const float* src = spec_vals + ((size_t)start + (e[u] & ~(SUB - 1u)) + entry) * nw;
+                    for (uint32_t q = 0; q < nw; ++q) static_cast<float*>(core_val.p[q])[j] = src[q];
+                }
             }
         }
     } else {

@@ -1,5 +1,5 @@
 """Full-size parity: the VGG-16-sized workload in the launch configuration bench.py times
-(flat model, n = 138,357,544, W = 8, hinted explorer draw inside the scoring kernel,
+(flat model, n = 138,357,544, W = 8, explorer draw announced ahead and made on the library's side stream,
 speculative packing with the capture bound of an earlier selection), and
 the tie-heavy stress workload of the same length (W = 16, values rounded through binary16).
 

@@ -42,7 +42,7 @@ def host_tile_offsets(idx, tile_start):
 
 
 def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, check=True, hint=False, per_tile_tail=False,
-                  clobber_after_select=False):
+                  clobber_after_select=False, hint_mode=0):
     """One reselect iteration on the GPU and in the oracle; returns both results."""
     seg_off = [int(x) for x in wl.segment_offsets()]
     ks, ms = [int(x) for x in wl.k_seg()], [int(x) for x in wl.m_seg()]
@@ -55,7 +55,8 @@ def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, chec
     sd.set_option("explore_per_tile_tail", int(per_tile_tail))      # 1: never the short-list explorer path
     w = to_dev(w_h)
     g = [to_dev(x) for x in g_h]
-    if hint:        # the explorer candidates are drawn inside the scoring kernel
+    sd.set_option("explore_hint_mode", hint_mode)
+    if hint:        # the explorer zones are drawn ahead: on the library's side stream (1) or inside the scoring kernel (0)
         sd.explore_hint(ks, iteration, ms, 0, wl.W)
     S = sd.score(w, g, wl.c)
     core_idx, core_bits, core_off, epoch = sd.select_core(S, ks, reuse_histogram=True)
@@ -183,29 +184,31 @@ def test_explore_per_tile_tail_with_narrow_zones(hint):
         assert_iteration_matches(wl, got, want)
 
 
+@pytest.mark.parametrize("hint_mode", [0, 1])
 @pytest.mark.parametrize("n,W", [(5, 1), (4097, 3), (200_003, 4), (150_001, 8)])
-def test_hinted_draw_inside_score_matches(n, W):
+def test_hinted_draw_matches(n, W, hint_mode):
     wl = workloads.TINY.scaled(n, W=W)
-    got, want = run_iteration(wl, iteration=3, hint=True)
+    got, want = run_iteration(wl, iteration=3, hint=True, hint_mode=hint_mode)
     assert_iteration_matches(wl, got, want)
 
 
-def test_hinted_draw_segmented_and_stress_and_rerun():
+@pytest.mark.parametrize("hint_mode", [0, 1])
+def test_hinted_draw_segmented_and_stress_and_rerun(hint_mode):
     wl = workloads.GOOGLENET.scaled(300_001)
-    got, want = run_iteration(wl, hint=True)
+    got, want = run_iteration(wl, hint=True, hint_mode=hint_mode)
     assert_iteration_matches(wl, got, want)
     wl = workloads.TINY.scaled(30_000, seg_off=(0, 1, 18, 4114, 4115, 12_307, 29_999, 30_000), n_seg=7)
-    got, want = run_iteration(wl, hint=True)
+    got, want = run_iteration(wl, hint=True, hint_mode=hint_mode)
     assert_iteration_matches(wl, got, want)
     wl = workloads.STRESS.scaled(100_003)
-    got, want = run_iteration(wl, hint=True)
+    got, want = run_iteration(wl, hint=True, hint_mode=hint_mode)
     assert_iteration_matches(wl, got, want)
     wl = workloads.TINY.scaled(100_003)                       # narrow bound too small: exact rerun
-    got, want = run_iteration(wl, hint=True, force_fallback=True)
+    got, want = run_iteration(wl, hint=True, force_fallback=True, hint_mode=hint_mode)
     assert_iteration_matches(wl, got, want)
     for core_pct, explore_pct in [(0, 2), (10, 0), (50, 100), (10, 60)]:
         wl = workloads.TINY.scaled(20_005, core_pct=core_pct, explore_pct=explore_pct)
-        got, want = run_iteration(wl, hint=True)
+        got, want = run_iteration(wl, hint=True, hint_mode=hint_mode)
         assert_iteration_matches(wl, got, want)
 
 
@@ -278,9 +281,11 @@ def test_speculative_pack_really_uses_the_captured_values():
     sd.close()
 
 
-def test_hint_that_does_not_match_the_request_is_ignored():
+@pytest.mark.parametrize("hint_mode", [0, 1])
+def test_hint_that_does_not_match_the_request_is_ignored(hint_mode):
     wl = workloads.TINY.scaled(50_001, W=2)
     sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
+    sd.set_option("explore_hint_mode", hint_mode)
     w = to_dev(wl.weights())
     g_h = wl.gradients(0)
     g = [to_dev(x) for x in g_h]
