@@ -103,6 +103,7 @@ struct slimdp_ctx {
     // core selection
     SegState* c_state = nullptr;
     uint32_t *c_hist = nullptr, *c_gt_bits = nullptr, *c_cand_bits = nullptr, *c_cand_keys = nullptr;
+    uint32_t* c_chunk_sum = nullptr;
     uint32_t *c_cnt_gt = nullptr, *c_cnt_cand = nullptr, *c_cnt_sel = nullptr, *c_cnt_tie = nullptr, *c_tie_pre = nullptr;
     // explorer selection (batch = worker)
     SegState* e_state = nullptr;
@@ -186,7 +187,8 @@ void carve(slimdp_ctx* c, Carver& cv)
     c->e_nsure = cv.take<uint32_t>(B * S);
     c->e_list_count = cv.take<uint32_t>(64);          // [0] candidates listed, [1] ties listed
     c->e_tie_list = cv.take<uint32_t>(TIE_CAP);
-    c->e_chunk_sum = cv.take<uint32_t>(B * c->n_chunks);
+    c->e_chunk_sum = cv.take<uint32_t>(2 * B * c->n_chunks);   // tie sums, then offset sums
+    c->c_chunk_sum = cv.take<uint32_t>(2 * c->n_chunks);
     c->e_list = cv.take<uint4>(c->list_cap);
     c->e_cand_keys = cv.take<uint32_t>(B * c->keys_stride);
     c->e_cnt_cand = cv.take<uint32_t>(B * T * SUBS);
@@ -268,7 +270,7 @@ int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* his
                      const uint32_t* cnt_cand, uint32_t* cnt_sel, uint32_t* cnt_tie, uint32_t* tie_pre,
                      uint64_t keys_stride, bool level1_done, const MutPtrTab& out_off, const MutPtrTab& out_idx,
                      uint32_t expected, uint32_t* pub_bits, const uint32_t* excl_bits, const uint32_t* gate,
-                     SpecTau sp = SpecTau{nullptr, nullptr, nullptr})
+                     uint32_t* chunk_sum, SpecTau sp = SpecTau{nullptr, nullptr, nullptr})
 {
     const uint32_t T = c->T, S = c->n_seg;
     const dim3 wave_grid((T + 3) / 4, (nbatch + BPW - 1) / BPW);     // a wave serves its tile for BPW batches
@@ -289,14 +291,17 @@ int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* his
     hipLaunchKernelGGL((k_count<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg, T, S,
                        nbatch, st, cand_keys, cnt_cand, cnt_gt, keys_stride, cnt_sel, cnt_tie, gate);
     SLIMDP_LAUNCHED(c, "k_count");
-    hipLaunchKernelGGL(k_scan, dim3(1, nbatch), dim3(1024), 0, c->stream, c->d_tile_seg, c->d_seg_first_tile, T, S, st,
-                       cnt_sel, cnt_tie, tie_pre, out_off, expected, c->d_flags, gate);
-    SLIMDP_LAUNCHED(c, "k_scan");
-    PtrTab off_ro;
-    for (int q = 0; q < MAXW; ++q) off_ro.p[q] = out_off.p[q];
+    const dim3 scan_grid(c->n_chunks, nbatch);
+    hipLaunchKernelGGL(k_tile_scan<0>, scan_grid, dim3(1024), 0, c->stream, c->d_tile_seg, c->d_seg_first_tile, T, S, st, cnt_sel,
+                       cnt_tie, tie_pre, chunk_sum, out_off, chunk_sum + (size_t)nbatch * c->n_chunks, gate);
+    SLIMDP_LAUNCHED(c, "k_tile_scan(ties)");
+    hipLaunchKernelGGL(k_tile_scan<1>, scan_grid, dim3(1024), 0, c->stream, c->d_tile_seg, c->d_seg_first_tile, T, S, st, cnt_sel,
+                       cnt_tie, tie_pre, chunk_sum, out_off, chunk_sum + (size_t)nbatch * c->n_chunks, gate);
+    SLIMDP_LAUNCHED(c, "k_tile_scan(offsets)");
     hipLaunchKernelGGL((k_emit<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg,
-                       c->d_seg_first_tile, T, S, nbatch, st, gt_bits, cand_bits, cand_keys, keys_stride, tie_pre, off_ro,
-                       out_idx, expected, pub_bits, excl_bits, (uint32_t)((c->n + 31) / 32), gate);
+                       c->d_seg_first_tile, T, S, nbatch, st, gt_bits, cand_bits, cand_keys, keys_stride, tie_pre, out_off,
+                       out_idx, expected, pub_bits, excl_bits, (uint32_t)((c->n + 31) / 32), gate, chunk_sum,
+                       chunk_sum + (size_t)nbatch * c->n_chunks, c->n_chunks, c->d_flags);
     SLIMDP_LAUNCHED(c, "k_emit");
     return SLIMDP_OK;
 }
@@ -689,7 +694,7 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
     uint32_t* pub = ctx->tl.word_aligned ? core_bits : nullptr;
     rc = finish_selection<CORE_KPL, 1>(ctx, 1, ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys,
                           ctx->c_cnt_gt, ctx->c_cnt_cand, ctx->c_cnt_sel, ctx->c_cnt_tie, ctx->c_tie_pre, ctx->keys_stride,
-                          true, off_tab, idx_tab, (uint32_t)K, pub, nullptr, nullptr, sp);
+                          true, off_tab, idx_tab, (uint32_t)K, pub, nullptr, nullptr, ctx->c_chunk_sum, sp);
     if (rc) return rc;
     if (!pub) {
         rc = fill(ctx, core_bits, (ctx->n + 31) / 32, 0u);
@@ -828,7 +833,8 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
 #undef LAUNCH_T0
     rc = finish_selection<EXPL_KPL, 4>(ctx, B, ctx->e_state, ctx->e_hist, ctx->e_sure_bits, ctx->e_cand_bits, ctx->e_cand_keys,
                           ctx->e_cnt_gt, ctx->e_cnt_cand, ctx->e_cnt_sel, ctx->e_cnt_tie, ctx->e_tie_pre, ctx->keys_stride,
-                          false, off_tab, idx_tab, (uint32_t)M, nullptr, core_bits, short_list ? ctx->d_flags : nullptr);
+                          false, off_tab, idx_tab, (uint32_t)M, nullptr, core_bits, short_list ? ctx->d_flags : nullptr,
+                          ctx->e_chunk_sum);
     if (rc) return rc;
     SLIMDP_HIP(ctx, hipEventRecord(ctx->ev_consumed, ctx->stream));      // the next announced draw may overwrite the buffers
     ctx->consumed_recorded = true;

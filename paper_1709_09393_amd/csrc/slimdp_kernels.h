@@ -250,7 +250,7 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
 // ---------------------------------------------------------------------------------------
 // K1: significance of every parameter + level-0 histogram of its bits (per segment).
 // Reads w and the W updates once, writes the score once: 4n(W+2) bytes.
-// Persistent blocks over contiguous tile ranges keep the 8192-bin histogram in LDS.
+// Persistent blocks over contiguous tile ranges keep the level-0 histogram in LDS.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ void flush_hist(uint32_t* lds, uint32_t nb, uint32_t* __restrict__ g)
 {
@@ -300,11 +300,13 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                                                  uint32_t* __restrict__ hist, int vec_ok, PreArgs pre, SpecArgs spec)
 {
     static_assert(!SPEC || WT != 0, "capture needs the update values in registers");
-    __shared__ uint32_t h[CORE_NB0];
+    // a significance is never negative: its sign bit is clear and the upper half of the level-0 bins stays empty
+    constexpr uint32_t NB = CORE_NB0 / 2;
+    __shared__ uint32_t h[NB];
     const int W = WT ? WT : Wrt;
     // the wave's number as a scalar: addresses below are then a scalar base plus a small per-lane offset
     const uint32_t lane = lane_id(), wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    for (uint32_t b = threadIdx.x; b < CORE_NB0; b += BLOCK) h[b] = 0;
+    for (uint32_t b = threadIdx.x; b < NB; b += BLOCK) h[b] = 0;
     __syncthreads();
     const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
     const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
@@ -316,7 +318,7 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
         const uint32_t seg = tile_seg[t];
         if (seg != cur_seg) {
             __syncthreads();
-            flush_hist(h, CORE_NB0, hist + (size_t)cur_seg * H_STRIDE + H_L0);
+            flush_hist(h, NB, hist + (size_t)cur_seg * H_STRIDE + H_L0);
             __syncthreads();
             cur_seg = seg;
         }
@@ -338,7 +340,7 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                 for (int k = 1; k < W; ++k) a = a + static_cast<const float*>(g.p[k])[e];
                 const float sc = significance(w[e], a, c);
                 S[e] = sc;
-                atomicAdd(&h[__float_as_uint(sc) >> CORE_SHIFT0], 1u);
+                atomicAdd(&h[(__float_as_uint(sc) >> CORE_SHIFT0) & (NB - 1u)], 1u);
             }
         }
         if (!vec && !PRE) continue;
@@ -383,10 +385,10 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                 sc.x = significance(wv.x, a.x, c); sc.y = significance(wv.y, a.y, c);
                 sc.z = significance(wv.z, a.z, c); sc.w = significance(wv.w, a.w, c);
                 reinterpret_cast<float4*>(S + e0)[lane] = sc;
-                atomicAdd(&h[__float_as_uint(sc.x) >> CORE_SHIFT0], 1u);
-                atomicAdd(&h[__float_as_uint(sc.y) >> CORE_SHIFT0], 1u);
-                atomicAdd(&h[__float_as_uint(sc.z) >> CORE_SHIFT0], 1u);
-                atomicAdd(&h[__float_as_uint(sc.w) >> CORE_SHIFT0], 1u);
+                atomicAdd(&h[(__float_as_uint(sc.x) >> CORE_SHIFT0) & (NB - 1u)], 1u);
+                atomicAdd(&h[(__float_as_uint(sc.y) >> CORE_SHIFT0) & (NB - 1u)], 1u);
+                atomicAdd(&h[(__float_as_uint(sc.z) >> CORE_SHIFT0) & (NB - 1u)], 1u);
+                atomicAdd(&h[(__float_as_uint(sc.w) >> CORE_SHIFT0) & (NB - 1u)], 1u);
                 if (SPEC) {
                     const uint32_t f = (__float_as_uint(sc.x) >= spec_lo ? 1u : 0u) | (__float_as_uint(sc.y) >= spec_lo ? 2u : 0u) |
                                        (__float_as_uint(sc.z) >= spec_lo ? 4u : 0u) | (__float_as_uint(sc.w) >= spec_lo ? 8u : 0u);
@@ -437,7 +439,7 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
         }
     }
     __syncthreads();
-    flush_hist(h, CORE_NB0, hist + (size_t)cur_seg * H_STRIDE + H_L0);
+    flush_hist(h, NB, hist + (size_t)cur_seg * H_STRIDE + H_L0);
 }
 
 // Level-0 histogram of a score array that did not come from k_score.
@@ -1281,64 +1283,63 @@ __global__ __launch_bounds__(BLOCK) void k_count(uint64_t n, const uint32_t* __r
 }
 
 // ---------------------------------------------------------------------------------------
-// Scan over tiles: global tie prefix, then how many ties each tile takes under its
-// segment's quota, then the output offset of every tile.  grid (1, nbatch), 1024 threads.
-// The tiles go through LDS in chunks of 8192: coalesced loads, each thread scans eight
-// consecutive values (padded rows, no bank conflicts), one block scan per chunk.
+// Scan over tiles in chunks of SCAN_CHUNK tiles, one block per chunk and batch; a value
+// of the whole array is its chunk-relative prefix plus the sums of the chunks before it
+// (chunk_base).  Two passes: PASS 0 over the tie counts (tie_pre), PASS 1 over what each
+// tile emits (certain ones plus the ties it takes under its segment's quota) -> out_off.
+// The emission turns the chunk-relative offsets into final ones.
+// grid (ceil(T / SCAN_CHUNK), nbatch), 1024 threads.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void k_scan(const uint32_t* __restrict__ tile_seg, const uint32_t* __restrict__ seg_first_tile,
-                                               uint32_t T, uint32_t n_seg, const SegState* __restrict__ states,
-                                               const uint32_t* __restrict__ cnt_sel, const uint32_t* __restrict__ cnt_tie,
-                                               uint32_t* __restrict__ tie_pre, MutPtrTab out_off, uint32_t expected,
-                                               uint32_t* __restrict__ flags, const uint32_t* __restrict__ gate)
+__device__ __forceinline__ uint32_t chunk_base(const uint32_t* __restrict__ sums, uint32_t chunk)
+{
+    uint32_t base = 0;
+    for (uint32_t c = 0; c < chunk; ++c) base += sums[c];
+    return base;
+}
+
+template <int PASS>
+__global__ __launch_bounds__(1024) void k_tile_scan(const uint32_t* __restrict__ tile_seg,
+                                                    const uint32_t* __restrict__ seg_first_tile, uint32_t T, uint32_t n_seg,
+                                                    const SegState* __restrict__ states, const uint32_t* __restrict__ cnt_sel,
+                                                    const uint32_t* __restrict__ cnt_tie, uint32_t* __restrict__ tie_pre,
+                                                    uint32_t* __restrict__ tie_sum, MutPtrTab out_off,
+                                                    uint32_t* __restrict__ off_sum, const uint32_t* __restrict__ gate)
 {
     __shared__ uint32_t vals[SCAN_CHUNK + SCAN_CHUNK / 8];
     __shared__ uint32_t wtot[16];
     if (gate && gate[0] == 0) return;
-    const uint32_t b = blockIdx.y;
+    const uint32_t b = blockIdx.y, c0 = blockIdx.x * SCAN_CHUNK, n_chunks = gridDim.x;
     const uint32_t* cs = cnt_sel + (size_t)b * T;
     const uint32_t* ct = cnt_tie + (size_t)b * T;
-    const SegState* st = states + (size_t)b * n_seg;
     uint32_t* tp = tie_pre + (size_t)b * (T + 1);
-    uint32_t* off = static_cast<uint32_t*>(out_off.p[b]);
-    // ---- ties ---------------------------------------------------------------------------
-    uint32_t carry = 0;
-    for (uint32_t c0 = 0; c0 < T; c0 += SCAN_CHUNK) {
-        for (uint32_t x = threadIdx.x; x < SCAN_CHUNK; x += 1024) vals[scan_phys(x)] = (c0 + x < T) ? ct[c0 + x] : 0u;
-        __syncthreads();
-        const uint32_t total = scan_chunk(vals, wtot);
-        for (uint32_t x = threadIdx.x; x < SCAN_CHUNK && c0 + x < T; x += 1024) tp[c0 + x] = carry + vals[scan_phys(x)];
-        carry += total;
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) tp[T] = carry;
-    __syncthreads();      // tp written by other threads of this block is read below
-    // ---- output offsets -------------------------------------------------------------------
-    carry = 0;
-    for (uint32_t c0 = 0; c0 < T; c0 += SCAN_CHUNK) {
-        for (uint32_t x = threadIdx.x; x < SCAN_CHUNK; x += 1024) {
-            const uint32_t t = c0 + x;
-            uint32_t v = 0;
-            if (t < T) {
+    const uint32_t* ts = tie_sum + (size_t)b * n_chunks;
+    for (uint32_t x = threadIdx.x; x < SCAN_CHUNK; x += 1024) {
+        const uint32_t t = c0 + x;
+        uint32_t v = 0;
+        if (t < T) {
+            const uint32_t c = ct[t];
+            if (PASS == 0) v = c;
+            else {
+                // ties before this tile inside its segment, against the segment's quota
+                const SegState* st = states + (size_t)b * n_seg;
                 const uint32_t seg = (n_seg == 1) ? 0u : tile_seg[t];
-                const uint32_t base = tp[t] - ((n_seg == 1) ? 0u : tp[seg_first_tile[seg]]);
+                uint32_t before = tp[t] + chunk_base(ts, blockIdx.x);
+                if (n_seg != 1) {
+                    const uint32_t f = seg_first_tile[seg];
+                    before -= tp[f] + chunk_base(ts, f / SCAN_CHUNK);
+                }
                 const uint32_t q = st[seg].quota;
-                const uint32_t room = (q > base) ? q - base : 0u;
-                const uint32_t c = ct[t];
+                const uint32_t room = (q > before) ? q - before : 0u;
                 v = cs[t] + (room < c ? room : c);
             }
-            vals[scan_phys(x)] = v;
         }
-        __syncthreads();
-        const uint32_t total = scan_chunk(vals, wtot);
-        for (uint32_t x = threadIdx.x; x < SCAN_CHUNK && c0 + x < T; x += 1024) off[c0 + x] = carry + vals[scan_phys(x)];
-        carry += total;
-        __syncthreads();
+        vals[scan_phys(x)] = v;
     }
-    if (threadIdx.x == 0) {
-        off[T] = carry;
-        if (carry != expected) atomicOr(&flags[1], 1u);
-    }
+    __syncthreads();
+    const uint32_t total = scan_chunk(vals, wtot);
+    uint32_t* dst = (PASS == 0) ? tp : static_cast<uint32_t*>(out_off.p[b]);
+    for (uint32_t x = threadIdx.x; x < SCAN_CHUNK && c0 + x < T; x += 1024) dst[c0 + x] = vals[scan_phys(x)];
+    if (threadIdx.x == 0) ((PASS == 0) ? tie_sum : off_sum)[(size_t)b * n_chunks + blockIdx.x] = total;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1353,10 +1354,12 @@ __global__ __launch_bounds__(BLOCK) void k_emit(uint64_t n, const uint32_t* __re
                                                 uint32_t nbatch, const SegState* __restrict__ states,
                                                 const uint32_t* __restrict__ gt_bits, const uint32_t* __restrict__ cand_bits,
                                                 const uint32_t* __restrict__ cand_keys, uint64_t keys_stride,
-                                                const uint32_t* __restrict__ tie_pre, PtrTab out_off, MutPtrTab out_idx,
+                                                const uint32_t* __restrict__ tie_pre, MutPtrTab out_off, MutPtrTab out_idx,
                                                 uint32_t expected, uint32_t* __restrict__ pub_bits,
                                                 const uint32_t* __restrict__ excl_bits, uint32_t n_words,
-                                                const uint32_t* __restrict__ gate)
+                                                const uint32_t* __restrict__ gate, const uint32_t* __restrict__ tie_sum,
+                                                const uint32_t* __restrict__ off_sum, uint32_t n_chunks,
+                                                uint32_t* __restrict__ flags)
 {
     __shared__ uint32_t kb[4][SUBS * 16 * KPL];
     const uint32_t wid = threadIdx.x >> 6;
@@ -1417,8 +1420,13 @@ __global__ __launch_bounds__(BLOCK) void k_emit(uint64_t n, const uint32_t* __re
         const uint32_t tcnt = __popc(tiemask[0]) + __popc(tiemask[1]);
         uint32_t taken[2] = {0u, 0u};
         if (__ballot(tcnt != 0)) {
-            const uint32_t tp_seg = (n_seg == 1) ? 0u : tp[seg_first_tile[seg]];
-            const uint32_t tbase = tp_t[bb] - tp_seg + wave_incl_scan(tcnt) - tcnt;
+            const uint32_t* ts = tie_sum + (size_t)b * n_chunks;
+            uint32_t tp_seg = 0;
+            if (n_seg != 1) {
+                const uint32_t f = seg_first_tile[seg];
+                tp_seg = tp[f] + chunk_base(ts, f / SCAN_CHUNK);
+            }
+            const uint32_t tbase = tp_t[bb] + chunk_base(ts, t / SCAN_CHUNK) - tp_seg + wave_incl_scan(tcnt) - tcnt;
             uint32_t take = (quota > tbase) ? quota - tbase : 0u;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
@@ -1429,7 +1437,16 @@ __global__ __launch_bounds__(BLOCK) void k_emit(uint64_t n, const uint32_t* __re
         const uint32_t fm0 = gw[0] | selmask[0] | taken[0], fm1 = gw[1] | selmask[1] | taken[1];
         const uint32_t ocnt = __popc(fm0) + __popc(fm1);
         uint32_t* out = static_cast<uint32_t*>(out_idx.p[b]);
-        uint32_t o = off_t[bb] + wave_incl_scan(ocnt) - ocnt;
+        // the tile's offset so far counts from its chunk: make it final, for this emission and for the caller
+        const uint32_t first = off_t[bb] + chunk_base(off_sum + (size_t)b * n_chunks, t / SCAN_CHUNK);
+        const uint32_t oincl = wave_incl_scan(ocnt);
+        uint32_t* off = static_cast<uint32_t*>(out_off.p[b]);
+        if (lane == 0) off[t] = first;
+        if (t == T - 1 && lane == 63) {
+            off[T] = first + oincl;
+            if (first + oincl != expected) atomicOr(&flags[1], 1u);
+        }
+        uint32_t o = first + oincl - ocnt;
         {
             uint32_t m = fm0;
             while (m) {
