@@ -736,10 +736,14 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
     }
     rc = init_states(ctx, ctx->e_state, init, B, 0);
     if (rc) return rc;
-    rc = fill(ctx, ctx->e_hist, (uint64_t)B * S * H_STRIDE, 0u);
-    if (rc) return rc;
-    rc = fill(ctx, ctx->d_flags, 1, 0u);
-    if (rc) return rc;
+    {   // histograms, rerun flag, list counters
+        FillJobs fj{};
+        fj.p[0] = ctx->e_hist; fj.count[0] = (uint64_t)B * S * H_STRIDE;
+        fj.p[1] = ctx->d_flags; fj.count[1] = 1;
+        fj.p[2] = ctx->e_list_count; fj.count[2] = 2;
+        hipLaunchKernelGGL(k_fill_multi, dim3(fill_grid(fj.count[0])), dim3(256), 0, ctx->stream, fj);
+        SLIMDP_LAUNCHED(ctx, "k_fill_multi");
+    }
     const uint32_t P = persistent_blocks(ctx, 8, B);
     const uint32_t n_words = (uint32_t)((ctx->n + 31) / 32);
     const PhiloxKey pk{(uint32_t)ctx->seed, (uint32_t)(ctx->seed >> 32), (uint32_t)iteration, (uint32_t)(iteration >> 32)};
@@ -781,8 +785,6 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
         // the few candidates go through one unordered list; any irregularity raises the flag that
         // switches these kernels off and the wide-bound per-tile rerun below on
         constexpr int SBPW = 8;
-        rc = fill(ctx, ctx->e_list_count, 2, 0u);
-        if (rc) return rc;
         if (!cached) LAUNCH_DRAW(1, 0);
         hipLaunchKernelGGL(k_sure_count<SBPW>, dim3((T + 3) / 4, (B + SBPW - 1) / SBPW), dim3(BLOCK), 0, ctx->stream, core_bits,
                            n_words, ctx->n, ctx->d_tile_start, ctx->d_tile_seg, T, S, B, ctx->e_sure_bits, ctx->e_cnt_sel);
@@ -807,9 +809,8 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
                            (uint32_t)ctx->list_cap, ctx->e_state, T, ctx->e_sure_bits, ctx->e_cnt_sel, ctx->e_tie_list,
                            ctx->e_list_count + 1, ctx->d_flags);
         SLIMDP_LAUNCHED(ctx, "k_short_mark");
-        hipLaunchKernelGGL(k_short_ties, dim3(1), dim3(1024), 0, ctx->stream, ctx->e_list, ctx->e_list_count,
-                           (uint32_t)ctx->list_cap, ctx->e_state, T, ctx->e_sure_bits, ctx->e_cnt_sel, ctx->e_tie_list,
-                           ctx->e_list_count + 1, ctx->d_flags);
+        hipLaunchKernelGGL(k_short_ties, dim3(1), dim3(1024), 0, ctx->stream, ctx->e_list, ctx->e_state, T, ctx->e_sure_bits,
+                           ctx->e_cnt_sel, ctx->e_tie_list, ctx->e_list_count + 1, ctx->d_flags);
         SLIMDP_LAUNCHED(ctx, "k_short_ties");
         hipLaunchKernelGGL(k_chunk_scan, dim3(ctx->n_chunks, B), dim3(1024), 0, ctx->stream, T, ctx->e_cnt_sel, off_tab,
                            ctx->e_chunk_sum, ctx->d_flags);

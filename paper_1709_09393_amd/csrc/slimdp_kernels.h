@@ -28,6 +28,16 @@ __global__ __launch_bounds__(256) void k_fill_u32(uint32_t* __restrict__ p, uint
 
 // Writes the selection state of segments [seg0, seg0+count) for every batch.
 // core != 0: fixed score-bit levels; else explorer levels derived from (bound_m1, shift0).
+// Several fills in one launch (a launch costs more than a small fill).
+struct FillJobs { uint32_t* p[4]; uint64_t count[4]; uint32_t v[4]; };
+__global__ __launch_bounds__(256) void k_fill_multi(FillJobs jobs)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < jobs.count[j]; i += (uint64_t)gridDim.x * 256)
+            jobs.p[j][i] = jobs.v[j];
+}
+
 __global__ __launch_bounds__(256) void k_init_state(SegState* __restrict__ st, SegInitChunk chunk, uint32_t seg0,
                                                     uint32_t count, uint32_t n_seg, uint32_t nbatch, int core)
 {
@@ -1027,29 +1037,24 @@ __global__ __launch_bounds__(256) void k_short_mark(const uint4* __restrict__ li
     }
 }
 
-// Ties that the quota covers only in part: the quota goes to the lowest positions.  The rank
-// of a tied entry is the number of tied entries of its segment below it, counted by the
-// whole block over the candidate list.  One block of 1024 threads; nothing to do as a rule.
-__global__ __launch_bounds__(1024) void k_short_ties(const uint4* __restrict__ list, const uint32_t* __restrict__ list_count,
-                                                     uint32_t list_cap, const SegState* __restrict__ states, uint32_t T,
-                                                     uint32_t* __restrict__ sure_bits, uint32_t* __restrict__ cnt_sel,
-                                                     const uint32_t* __restrict__ tie_list,
+// Ties that the quota covers only in part: the quota goes to the lowest positions.  Every
+// entry equal to its segment's tau is on the tie list, so the rank of a tied entry is the
+// number of tie-list entries of its segment below it.  One block; nothing to do as a rule.
+__global__ __launch_bounds__(1024) void k_short_ties(const uint4* __restrict__ list, const SegState* __restrict__ states,
+                                                     uint32_t T, uint32_t* __restrict__ sure_bits,
+                                                     uint32_t* __restrict__ cnt_sel, const uint32_t* __restrict__ tie_list,
                                                      const uint32_t* __restrict__ tie_count, const uint32_t* __restrict__ flags)
 {
-    __shared__ uint32_t wtot[16];
-    if (flags[0] != 0) return;                       // nobody raises the flag while this kernel runs
+    if (flags[0] != 0) return;
     const uint32_t nt = min(tie_count[0], TIE_CAP);
-    const uint32_t cnt = min(list_count[0], list_cap);
-    for (uint32_t q = 0; q < nt; ++q) {
+    for (uint32_t q = threadIdx.x; q < nt; q += 1024) {
         const uint4 e = list[tie_list[q]];
-        uint32_t below = 0;
-        for (uint32_t j = threadIdx.x; j < cnt; j += 1024) {
-            const uint4 o = list[j];
-            below += (o.z == e.z && o.x == e.x && o.y < e.y) ? 1u : 0u;
+        uint32_t rank = 0;
+        for (uint32_t p = 0; p < nt; ++p) {
+            const uint4 o = list[tie_list[p]];
+            rank += (o.z == e.z && o.y < e.y) ? 1u : 0u;
         }
-        uint32_t rank;
-        (void)block_excl_scan<16>(below, wtot, rank);
-        if (threadIdx.x == 0 && rank < states[e.z].quota) short_take(e, T, sure_bits, cnt_sel);
+        if (rank < states[e.z].quota) short_take(e, T, sure_bits, cnt_sel);
     }
 }
 
