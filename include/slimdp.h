@@ -88,9 +88,25 @@ const char* slimdp_last_error(const slimdp_ctx* ctx);
  * not match).  The only call that blocks the host. */
 int slimdp_synchronize(slimdp_ctx* ctx);
 
-/* Tuning / test switches.  Known names:
- *   "explore_force_fallback" (0/1): make the first candidate bound of slimdp_sample_explore
- *                                   too small, so that the exact wide-bound path runs. */
+/* Options.  Known names:
+ *   "speculative_pack" (0/1, default 0): slimdp_score additionally keeps the update values of
+ *       every parameter whose significance reaches the threshold of the previous
+ *       slimdp_select_core less a small margin (own device allocation of about 4*W*n bytes,
+ *       made by this call); if the following slimdp_select_core(..REUSE_HISTOGRAM) finds its
+ *       threshold at or above that bound, the next slimdp_pack takes the core values from
+ *       there instead of scanning the update vectors again.  Results are bit-identical either
+ *       way (the same slow drift of the core that the paper's key caching relies on, section
+ *       3.3).  CONTRACT while the option is on: the first slimdp_pack after such a selection
+ *       is given the very update arrays, unchanged, that slimdp_score read; one capture
+ *       serves one pack, later packs of the same core read the vectors they are given.
+ *   "explore_hint_mode" (0/1, default 0): where an announced explorer draw runs: 0 inside
+ *       the next slimdp_score, 1 at once on a side stream of the library (default priority),
+ *       beside whatever runs on the context's stream.
+ *   "side_blocks" (1..8): blocks per compute unit of a side-stream draw.
+ *   "pack_nbuf" (1/2): tiles in flight in the general pack kernel.
+ *   "explore_force_fallback" (0/1/2), "explore_per_tile_tail" (0/1): test switches: make
+ *       the explorer's first zones miss (1: too few candidates, 2: sure zone too large) so
+ *       that the exact rerun runs; never take the short-list tail. */
 int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value);
 
 /* ---------------------------------------------------------------------------------- */
@@ -146,15 +162,16 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
                           const uint64_t* m_seg, uint32_t* const* expl_idx,
                           uint32_t* const* expl_off);
 
-/* Optional announcement: the next slimdp_score on this context is to draw, while it
- * streams the model, the explorer candidates that the following
+/* Optional announcement of the explorer draw that a coming
  * slimdp_sample_explore(ctx, core_bits, k_seg, worker0, n_workers, iteration, m_seg, ...)
  * will need (the arguments must then be identical, else the draw is simply redone).  The
- * random words do not depend on the core, so their generation -- the only step of the path
- * bound by integer arithmetic rather than by memory -- can hide under the scoring pass, as
- * the paper notes for its worker side (section 3.5, "Time Efficiency").  Purely a
- * performance hint: results are bit-identical with or without it.  Host arrays as in
- * slimdp_sample_explore; k_seg is the core size the coming slimdp_select_core will use. */
+ * random words do not depend on the core or on any data, so their generation -- the only
+ * step of the path bound by integer arithmetic rather than by memory -- can hide under
+ * memory-bound work, as the paper notes for its worker side (section 3.5, "Time
+ * Efficiency"): by default the next slimdp_score on this context draws while it streams
+ * the model; with option "explore_hint_mode" = 1 the draw starts at once on a side stream.
+ * Purely a performance hint: results are bit-identical with or without it.  Host arrays as
+ * in slimdp_sample_explore; k_seg is the core size the coming slimdp_select_core will use. */
 int slimdp_explore_hint(slimdp_ctx* ctx, const uint64_t* k_seg, uint32_t worker0, uint32_t n_workers,
                         uint64_t iteration, const uint64_t* m_seg);
 
