@@ -62,6 +62,8 @@ def _declare(L: C.CDLL) -> None:
     L.oracle_explore_words.restype = None
     L.oracle_score.argtypes = [C.c_uint64, C.c_uint32, _f32p, C.POINTER(_f32p), C.c_float, _f32p]
     L.oracle_score.restype = None
+    L.oracle_dense_update_score.argtypes = [C.c_uint64, C.c_uint32, _f32p, C.POINTER(_f32p), C.c_float, C.c_float, _f32p]
+    L.oracle_dense_update_score.restype = None
     L.oracle_select_core.argtypes = [_f32p, C.c_uint32, C.c_uint32, C.c_uint32, _u32p]
     L.oracle_select_core.restype = C.c_int
     L.oracle_sample_explore.argtypes = [_u8p, C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint64,
@@ -125,6 +127,18 @@ def score(w: np.ndarray, g: Sequence[np.ndarray], c: float) -> np.ndarray:
     lib().oracle_score(w.size, len(gs), _p(w, C.c_float), _table(gs, C.c_float), C.c_float(c),
                        _p(S, C.c_float))
     return S
+
+
+def dense_update_score(w: np.ndarray, g: Sequence[np.ndarray], lr: float, c: float):
+    """Algorithm 1, the iteration before a reselection: all updates applied, significance of the new model.
+    Returns (w_new, S); the input is not modified."""
+    w_new = np.array(_as(w, np.float32), copy=True)
+    gs = [_as(x, np.float32) for x in g]
+    assert all(x.shape == w_new.shape for x in gs) and len(gs) >= 1
+    S = np.empty_like(w_new)
+    lib().oracle_dense_update_score(w_new.size, len(gs), _p(w_new, C.c_float), _table(gs, C.c_float), C.c_float(lr),
+                                    C.c_float(c), _p(S, C.c_float))
+    return w_new, S
 
 
 def _segments(n: int, seg_off: Optional[Sequence[int]]):

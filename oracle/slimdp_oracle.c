@@ -223,6 +223,34 @@ void oracle_merge(uint64_t n, float* w, float lr, uint32_t W,
 
 /* The same update in binary64 with no intermediate rounding to binary32:
  * the reference against which the binary32 tolerance is stated. */
+/* ------------------------------------------------------------------ */
+/* The last iteration before a reselection (algorithm 1: the branch    */
+/* (t+1) % q == 0; section 3.3 steps 3 and 6): every worker pushes its */
+/* whole update, the server applies all of them,                       */
+/*     w_new_i = w_i - lr * sum_k g_k[i],                              */
+/* and the new core is ranked with the NEW model and these updates,    */
+/*     S_i = |w_new_i| + c * |sum_k g_k[i]|        (equation (1)).     */
+/* The sum is the server's: from +0, one worker after the other, as in */
+/* oracle_merge with every index sent by every worker; one fmaf for    */
+/* the model, one for the significance.                                */
+/* ------------------------------------------------------------------ */
+void oracle_dense_update_score(uint64_t n, uint32_t W, float* w, const float* const* g,
+                               float lr, float c, float* S)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        float acc = 0.0f;
+        for (uint32_t k = 0; k < W; ++k)
+            acc = acc + g[k][i];
+        w[i] = fmaf(-lr, acc, w[i]);
+        float s = fmaf(c, fabsf(acc), fabsf(w[i]));
+        if (s != s) {
+            uint32_t qnan = 0x7FC00000u;
+            memcpy(&s, &qnan, 4);
+        }
+        S[i] = s;
+    }
+}
+
 void oracle_merge_f64(uint64_t n, const float* w_in, double* w_out, double lr, uint32_t W,
                       const uint32_t* core_idx, uint64_t k, const float* const* core_val,
                       const uint32_t* const* expl_idx, const float* const* expl_val,

@@ -1765,8 +1765,8 @@ __global__ __launch_bounds__(BLOCK) void k_pack_stream(PtrTab g, uint32_t nw, co
 // go right after the tile's offsets are known.
 // ---------------------------------------------------------------------------------------
 constexpr int MERGE_R = 4;                 // explorer entries per thread kept in registers
-constexpr uint32_t MERGE_HOT_CAP = 256;
-constexpr uint32_t MERGE_STAGE = 512;
+constexpr uint32_t MERGE_HOT_CAP = 128;
+constexpr uint32_t MERGE_STAGE = 256;
 
 __global__ __launch_bounds__(BLOCK) void k_merge(float* __restrict__ w, float lr, uint32_t nw,
                                                  const uint32_t* __restrict__ tile_start,

@@ -420,6 +420,64 @@ def test_merge_conservation_and_f64_tolerance():
 # ----------------------------------------------------------------------------------------
 # Pull and local merge
 # ----------------------------------------------------------------------------------------
+# ----------------------------------------------------------------------------------------
+# Dense update + significance of the new model (algorithm 1, the iteration before a reselection)
+# ----------------------------------------------------------------------------------------
+def test_dense_update_score_exact_rational_closed_form():
+    rng = np.random.default_rng(21)
+    n, W = 193, 3
+    w = rng.standard_normal(n).astype(np.float32)
+    g = [rng.standard_normal(n).astype(np.float32) * np.float32(1e-2) for _ in range(W)]
+    lr = np.float32(0.01)
+    c = np.float32(1.0 + 2.0 ** -12)
+    w_before = w.copy()
+    w_new, S = oracle.dense_update_score(w, g, float(lr), float(c))
+    assert np.array_equal(bits(w), bits(w_before))                           # the input is not modified
+    for i in range(n):
+        acc = np.float32(0.0)
+        for k in range(W):                    # from +0, worker order, each add correctly rounded
+            acc = round_to_f32(f32_exact(acc) + f32_exact(g[k][i]))
+        want_w = round_to_f32(f32_exact(w[i]) - f32_exact(lr) * f32_exact(acc))            # one rounding
+        assert bits(w_new[i:i + 1])[0] == bits(np.array([want_w]))[0], i
+        want_s = round_to_f32(abs(f32_exact(want_w)) + f32_exact(c) * abs(f32_exact(acc)))  # of the NEW model
+        assert bits(S[i:i + 1])[0] == bits(np.array([want_s]))[0], i
+    # the old model would have given other scores: the test can tell the two apart
+    assert not np.array_equal(bits(S), bits(oracle.score(w, g, float(c))))
+
+
+def test_dense_update_score_reduces_to_known_cases():
+    rng = np.random.default_rng(22)
+    n, W = 1000, 4
+    w = rng.standard_normal(n).astype(np.float32)
+    g = [rng.standard_normal(n).astype(np.float32) for _ in range(W)]
+    # lr = 0: the model keeps its bits and the significance is equation (1) on it
+    w0, S0 = oracle.dense_update_score(w, g, 0.0, 0.5)
+    assert np.array_equal(bits(w0), bits(w))
+    assert np.array_equal(bits(S0), bits(oracle.score(w, g, 0.5)))
+    # the model part is the merge with every index sent by every worker (the Plump-DP update)
+    core = np.arange(n, dtype=np.uint32)
+    none_i, none_v = [np.zeros(0, np.uint32)] * W, [np.zeros(0, np.float32)] * W
+    w1, S1 = oracle.dense_update_score(w, g, 0.125, 1.0)
+    assert np.array_equal(bits(w1), bits(oracle.merge(w, 0.125, core, g, none_i, none_v)))
+    # ... and the significance is equation (1) evaluated on that new model
+    assert np.array_equal(bits(S1), bits(oracle.score(w1, g, 1.0)))
+    # c = 0: magnitude of the new model alone
+    w2, S2 = oracle.dense_update_score(w, g, 0.125, 0.0)
+    assert np.array_equal(bits(S2), bits(np.abs(w2)))
+    # dyadic values: no rounding anywhere, plain NumPy in binary64 is exact
+    wd = (rng.integers(-1024, 1024, n) / 64.0).astype(np.float32)
+    gd = [(rng.integers(-256, 256, n) / 16.0).astype(np.float32) for _ in range(W)]
+    w3, S3 = oracle.dense_update_score(wd, gd, 0.25, 2.0)
+    gsum = np.sum(np.stack(gd).astype(np.float64), axis=0)
+    assert np.array_equal(w3.astype(np.float64), wd.astype(np.float64) - 0.25 * gsum)
+    assert np.array_equal(S3.astype(np.float64), np.abs(w3.astype(np.float64)) + 2.0 * np.abs(gsum))
+    # order of the sum and sign of zero: (+0 + -0) is +0, so a model value of -0 stays -0 only through the fma
+    wz = np.array([-0.0, 1.0], np.float32)
+    gz = [np.array([-0.0, 1e8], np.float32), np.array([-0.0, -1e8], np.float32), np.array([-0.0, 1.0], np.float32)]
+    w4, S4 = oracle.dense_update_score(wz, gz, 1.0, 1.0)
+    assert bits(w4)[0] == 0x80000000 and w4[1] == np.float32(0.0) and S4[1] == np.float32(1.0)
+
+
 def test_pull_reads_and_overwrites_only_the_communication_set():
     rng = np.random.default_rng(6)
     w = rng.standard_normal(100).astype(np.float32)
