@@ -124,6 +124,18 @@ int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value);
 int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_t W, float c,
                  float* score);
 
+/* The last iteration before a reselection (algorithm 1, the branch (t+1) % q == 0; section
+ * 3.3 steps 3 and 6): every worker has pushed its WHOLE update, the server applies all of
+ * them and ranks the new core with the new model and these updates, in one pass:
+ *     acc_i = ((+0 + g_0[i]) + g_1[i]) + ...           binary32, worker order (as slimdp_merge)
+ *     w_i  <- fma(-lr, acc_i, w_i)                     every i, in place
+ *     score_i = fma(c, |acc_i|, |w_i (new)|)           equation (1), quiet NaN as in slimdp_score
+ * Arguments as slimdp_score, w is read and written; lr finite; score must not alias w.
+ * Leaves the same histogram behind as slimdp_score for slimdp_select_core to reuse, and
+ * serves an announced explorer draw the same way. */
+int slimdp_dense_update_score(slimdp_ctx* ctx, float* w, const float* const* g, uint32_t W, float lr,
+                              float c, float* score);
+
 /* Core-Selection operator T_S (section 3.1 item 1; section 3.2 "rank ... select the top";
  * section 3.3 step 6): per segment s the k_seg[s] parameters that come first when ranked
  * by (score bit pattern as uint32, descending; index, ascending).  For scores >= +0 that

@@ -30,7 +30,7 @@ SELECT_REUSE_HISTOGRAM = 1
 EXPORTS = [
     "slimdp_create", "slimdp_destroy", "slimdp_workspace_bytes", "slimdp_num_tiles",
     "slimdp_tile_starts", "slimdp_last_error", "slimdp_synchronize", "slimdp_set_option",
-    "slimdp_score", "slimdp_select_core", "slimdp_sample_explore", "slimdp_explore_hint", "slimdp_tile_offsets",
+    "slimdp_score", "slimdp_dense_update_score", "slimdp_select_core", "slimdp_sample_explore", "slimdp_explore_hint", "slimdp_tile_offsets",
     "slimdp_pack", "slimdp_merge", "slimdp_pull", "slimdp_debug_philox",
 ]
 
@@ -74,6 +74,8 @@ def load() -> C.CDLL:
     L.slimdp_set_option.restype = C.c_int
     L.slimdp_score.argtypes = [_vp, _vp, _vpp, C.c_uint32, C.c_float, _vp]
     L.slimdp_score.restype = C.c_int
+    L.slimdp_dense_update_score.argtypes = [_vp, _vp, _vpp, C.c_uint32, C.c_float, C.c_float, _vp]
+    L.slimdp_dense_update_score.restype = C.c_int
     L.slimdp_select_core.argtypes = [_vp, _vp, _u64p, C.c_uint32, _vp, _vp, _vp, _u64p]
     L.slimdp_select_core.restype = C.c_int
     L.slimdp_sample_explore.argtypes = [_vp, _vp, _u64p, C.c_uint32, C.c_uint32, C.c_uint64, _u64p, _vpp, _vpp]
@@ -193,6 +195,15 @@ class SlimDP:
         if out is None:
             out = self._empty(self.n, torch.float32)
         self._check(self._L.slimdp_score(self._h, _ptr(w), _table(g), len(g), C.c_float(c), _ptr(out)))
+        return out
+
+    def dense_update_score(self, w, g: Sequence, lr: float, c: float, out=None):
+        """w <- w - lr * sum of all updates (in place), then the significance of the new model."""
+        torch = self._torch
+        if out is None:
+            out = self._empty(self.n, torch.float32)
+        self._check(self._L.slimdp_dense_update_score(self._h, _ptr(w), _table(g), len(g), C.c_float(lr), C.c_float(c),
+                                                      _ptr(out)))
         return out
 
     def select_core(self, score, k_seg, reuse_histogram: bool = False, core_idx=None, core_bits=None, core_off=None):

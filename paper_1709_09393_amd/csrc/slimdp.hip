@@ -561,7 +561,8 @@ int slimdp_synchronize(slimdp_ctx* ctx)
 }
 
 // ------------------------------------------------------------------------------------------
-int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_t W, float c, float* score)
+static int score_impl(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_t W, float c, float* score, float* w_new,
+                      float lr)
 {
     if (!ctx) return SLIMDP_ERR_INVALID_ARG;
     if (!w || !score) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_score: NULL array");
@@ -600,7 +601,8 @@ int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_
     }
     // speculative packing: keep the update values of the parameters at or above the previous threshold
     SpecArgs sa{};
-    const bool capture = ctx->spec.on && (W == 1 || W == 2 || W == 4 || W == 8 || W == 16);
+    // (not after a dense update: the pack that follows it belongs to the next iteration's updates)
+    const bool capture = ctx->spec.on && !w_new && (W == 1 || W == 2 || W == 4 || W == 8 || W == 16);
     ctx->spec.captured = false;
     if (capture) {
         if (ctx->spec.next_written) { ctx->spec.cur ^= 1; ctx->spec.next_written = false; }
@@ -610,7 +612,7 @@ int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_
     const dim3 grid(P), block(BLOCK);
 #define LAUNCH_SCORE_P(WT, PRE, SPEC)                                                                                 \
     hipLaunchKernelGGL((k_score<WT, PRE, SPEC>), grid, block, 0, ctx->stream, w, gt, (int)W, c, score,                \
-                       ctx->d_tile_start, ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok, pre, sa)
+                       ctx->d_tile_start, ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok, pre, sa, w_new, lr)
 #define LAUNCH_SCORE_S(WT, SPEC)                                                                                      \
     do {                                                                                                              \
         if (presample && pairs) LAUNCH_SCORE_P(WT, 2, SPEC);                                                          \
@@ -643,6 +645,20 @@ int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_
     ctx->hist_pending = true;
     ctx->hist_score = score;
     return SLIMDP_OK;
+}
+
+int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_t W, float c, float* score)
+{
+    return score_impl(ctx, w, g, W, c, score, nullptr, 0.0f);
+}
+
+int slimdp_dense_update_score(slimdp_ctx* ctx, float* w, const float* const* g, uint32_t W, float lr, float c, float* score)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    if (!std::isfinite(lr)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_dense_update_score: lr must be finite");
+    if (w && score && static_cast<const void*>(w) == static_cast<const void*>(score))
+        return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_dense_update_score: score aliases w");
+    return score_impl(ctx, w, g, W, c, score, w, lr);
 }
 
 int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_seg, uint32_t flags, uint32_t* core_idx,

@@ -260,6 +260,10 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
 // ---------------------------------------------------------------------------------------
 // K1: significance of every parameter + level-0 histogram of its bits (per segment).
 // Reads w and the W updates once, writes the score once: 4n(W+2) bytes.
+// With w_new != nullptr (the iteration before a reselection, algorithm 1 / section 3.3 steps
+// 3 and 6: every worker pushed its whole update) the model is first updated with all of them,
+// w_new = fma(-lr, (+0 + g_0) + g_1 + ..., w), written to w_new (which may be w itself), and
+// the significance is that of the new model: 4n(W+3) bytes.
 // Persistent blocks over contiguous tile ranges keep the level-0 histogram in LDS.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ void flush_hist(uint32_t* lds, uint32_t nb, uint32_t* __restrict__ g)
@@ -307,7 +311,8 @@ template <int WT, int PRE, int SPEC>
 __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __restrict__ w, PtrTab g, int Wrt, float c,
                                                  float* __restrict__ S, const uint32_t* __restrict__ tile_start,
                                                  const uint32_t* __restrict__ tile_seg, uint32_t T,
-                                                 uint32_t* __restrict__ hist, int vec_ok, PreArgs pre, SpecArgs spec)
+                                                 uint32_t* __restrict__ hist, int vec_ok, PreArgs pre, SpecArgs spec,
+                                                 float* __restrict__ w_new, float lr)
 {
     static_assert(!SPEC || WT != 0, "capture needs the update values in registers");
     // a significance is never negative: its sign bit is clear and the upper half of the level-0 bins stays empty
@@ -348,7 +353,9 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                 const size_t e = (size_t)start + l;
                 float a = static_cast<const float*>(g.p[0])[e];
                 for (int k = 1; k < W; ++k) a = a + static_cast<const float*>(g.p[k])[e];
-                const float sc = significance(w[e], a, c);
+                float we = w[e];
+                if (w_new) { we = __builtin_fmaf(-lr, a + 0.0f, we); w_new[e] = we; }      // dense update first
+                const float sc = significance(we, a, c);
                 S[e] = sc;
                 atomicAdd(&h[(__float_as_uint(sc) >> CORE_SHIFT0) & (NB - 1u)], 1u);
             }
@@ -390,6 +397,11 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                         const float4 y = reinterpret_cast<const float4*>(static_cast<const float*>(g.p[k]) + e0)[lane];
                         a.x = a.x + y.x; a.y = a.y + y.y; a.z = a.z + y.z; a.w = a.w + y.w;
                     }
+                }
+                if (w_new) {        // uniform: the server's dense update first (its sum starts from +0), then the new model's score
+                    wv.x = __builtin_fmaf(-lr, a.x + 0.0f, wv.x); wv.y = __builtin_fmaf(-lr, a.y + 0.0f, wv.y);
+                    wv.z = __builtin_fmaf(-lr, a.z + 0.0f, wv.z); wv.w = __builtin_fmaf(-lr, a.w + 0.0f, wv.w);
+                    reinterpret_cast<float4*>(w_new + e0)[lane] = wv;
                 }
                 float4 sc;
                 sc.x = significance(wv.x, a.x, c); sc.y = significance(wv.y, a.y, c);

@@ -448,6 +448,76 @@ def test_multi_iteration_loop_scaled():
     sd.close()
 
 
+@pytest.mark.parametrize("n,W,segmented", [(5, 1, False), (4097, 3, False), (200_003, 8, False), (300_001, 4, True)])
+@pytest.mark.parametrize("hint", [False, True])
+def test_dense_update_score_matches_oracle(n, W, segmented, hint):
+    """The iteration before a reselection: all updates applied, significance of the new model, then the selection."""
+    wl = workloads.GOOGLENET.scaled(n, W=W) if segmented else workloads.TINY.scaled(n, W=W)
+    seg_off = [int(x) for x in wl.segment_offsets()]
+    ks, ms = [int(x) for x in wl.k_seg()], [int(x) for x in wl.m_seg()]
+    sd = binding.SlimDP(wl.n, wl.W, seg_off=seg_off, seed=workloads.EXPLORE_SEED)
+    sd.set_option("speculative_pack", 1)            # must not capture here: the next pack packs other updates
+    w_h, g_h = wl.weights(), wl.gradients(4)
+    w, g = to_dev(w_h), [to_dev(x) for x in g_h]
+    if hint:
+        sd.explore_hint(ks, 5, ms, 0, wl.W)
+    S = sd.dense_update_score(w, g, wl.lr, wl.c)
+    core_idx, core_bits, core_off, epoch = sd.select_core(S, ks, reuse_histogram=True)
+    expl_idx, expl_off = sd.sample_explore(core_bits, ks, 5, ms, 0, wl.W)
+    g2_h = wl.gradients(5)                          # the next iteration's updates go through the new sets
+    g2 = [to_dev(x) for x in g2_h]
+    core_val, expl_val = sd.pack(g2, core_idx, core_off, expl_idx, expl_off, epoch)
+    sd.synchronize()
+    w_o, S_o = oracle.dense_update_score(w_h, g_h, wl.lr, wl.c)
+    assert np.array_equal(f32bits(w.cpu().numpy()), f32bits(w_o)), "updated model bits"
+    assert np.array_equal(f32bits(S.cpu().numpy()), f32bits(S_o)), "score bits"
+    so = None if not segmented else seg_off
+    core_o = oracle.select_core(S_o, ks, so)
+    assert np.array_equal(u32(core_idx), core_o)
+    for q in range(wl.W):
+        ei_o = oracle.sample_explore(wl.n, core_o, workloads.EXPLORE_SEED, 5, q, ms, so)
+        assert np.array_equal(u32(expl_idx[q]), ei_o), q
+        cv_o, ev_o = oracle.pack(g2_h[q], core_o, ei_o)
+        assert np.array_equal(f32bits(core_val[q].cpu().numpy()), f32bits(cv_o)), q
+        assert np.array_equal(f32bits(expl_val[q].cpu().numpy()), f32bits(ev_o)), q
+    sd.close()
+
+
+def test_paper_schedule_loop_scaled():
+    """Algorithm 1's schedule with q = 5 over 12 iterations: sparse push/merge through the cached core, except that
+    the iteration before each reselection pushes everything and the new core is ranked with the new model."""
+    wl = workloads.LOOP.scaled(40_009, W=4)
+    q_every = 5
+    sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
+    w_h = wl.weights()
+    w = to_dev(w_h)
+    k, m = wl.k, wl.m
+    # before the first reselection there is no core in the paper: the benchmark's start (selection at t = 0)
+    g_h = wl.gradients(0)
+    S = sd.score(w, [to_dev(x) for x in g_h], wl.c)
+    core_idx, core_bits, core_off, epoch = sd.select_core(S, [k], reuse_histogram=True)
+    core_o = oracle.select_core(oracle.score(w_h, g_h, wl.c), k)
+    for t in range(12):
+        g_h = wl.gradients(t)
+        g = [to_dev(x) for x in g_h]
+        if (t + 1) % q_every == 0:
+            S = sd.dense_update_score(w, g, wl.lr, wl.c)
+            core_idx, core_bits, core_off, epoch = sd.select_core(S, [k], reuse_histogram=True)
+            w_h, S_o = oracle.dense_update_score(w_h, g_h, wl.lr, wl.c)
+            core_o = oracle.select_core(S_o, k)
+            assert np.array_equal(u32(core_idx), core_o), t
+        else:
+            expl_idx, expl_off = sd.sample_explore(core_bits, [k], t, [m], 0, wl.W)
+            core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)
+            sd.merge(w, wl.lr, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
+            ei_o = [oracle.sample_explore(wl.n, core_o, workloads.EXPLORE_SEED, t, q, m) for q in range(wl.W)]
+            packs = [oracle.pack(g_h[q], core_o, ei_o[q]) for q in range(wl.W)]
+            w_h = oracle.merge(w_h, wl.lr, core_o, [p[0] for p in packs], ei_o, [p[1] for p in packs])
+    sd.synchronize()
+    assert np.array_equal(f32bits(w.cpu().numpy()), f32bits(w_h))
+    sd.close()
+
+
 def test_error_paths_launch_nothing():
     n = 10_000
     sd = binding.SlimDP(n, 2)
@@ -477,6 +547,12 @@ def test_error_paths_launch_nothing():
     assert e.value.code == binding.ERR_STALE_CORE
     with pytest.raises(binding.SlimDPError) as e:
         sd.score(S, [S], -1.0)
+    assert e.value.code == binding.ERR_INVALID_ARG
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.dense_update_score(S, [S], 0.1, 1.0, out=S)          # the score may not overwrite the model
+    assert e.value.code == binding.ERR_INVALID_ARG
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.dense_update_score(S, [S], float("nan"), 1.0)
     assert e.value.code == binding.ERR_INVALID_ARG
     sd.synchronize()
     # a bitmap with more core bits than k_seg claims: the device reports the shortfall
