@@ -177,6 +177,23 @@ def main() -> int:
         "stage_hbm_frac": {s: sb[s] / (stage_ms[s] * 1e-3) / 1e9 / HBM_PEAK_GBS for s in STAGES},
         "roofline": roofline,
     }
+    # beside the headline: the iteration before a reselection as algorithm 1 has it (every worker pushes its whole
+    # update; dense update, significance of the new model and selection: no pack, no sparse merge)
+    ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    reps = max(3, min(args.steps, 10))
+    sd.dense_update_score(w, g, wl.lr, wl.c, out=S)
+    sd.select_core(S, [k], reuse_histogram=True, core_idx=core_idx, core_bits=core_bits, core_off=core_off)
+    ev2[0].record()
+    for _ in range(reps):
+        sd.dense_update_score(w, g, wl.lr, wl.c, out=S)
+        sd.select_core(S, [k], reuse_histogram=True, core_idx=core_idx, core_bits=core_bits, core_off=core_off)
+    ev2[1].record()
+    torch.cuda.synchronize()
+    sd.synchronize()
+    dense_ms = ev2[0].elapsed_time(ev2[1]) / reps
+    out["paper_schedule_reselect"] = {"ms": dense_ms, "Gparam_per_s": n / (dense_ms * 1e-3) / 1e9,
+                                      "what": "slimdp_dense_update_score + slimdp_select_core",
+                                      "algorithmic_bytes": 4 * n * (W + 3) + 4 * n + 4 * k + n // 8}
     sd.close()
     del w, g, S
     if args.cpu_sample > 0:

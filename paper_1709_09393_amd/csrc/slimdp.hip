@@ -610,19 +610,20 @@ static int score_impl(slimdp_ctx* ctx, const float* w, const float* const* g, ui
     }
     const uint32_t P = persistent_blocks(ctx, SCORE_MINB, 1);
     const dim3 grid(P), block(BLOCK);
-#define LAUNCH_SCORE_P(WT, PRE, SPEC)                                                                                 \
-    hipLaunchKernelGGL((k_score<WT, PRE, SPEC>), grid, block, 0, ctx->stream, w, gt, (int)W, c, score,                \
+#define LAUNCH_SCORE_P(WT, PRE, SPEC, DENSE)                                                                          \
+    hipLaunchKernelGGL((k_score<WT, PRE, SPEC, DENSE>), grid, block, 0, ctx->stream, w, gt, (int)W, c, score,         \
                        ctx->d_tile_start, ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok, pre, sa, w_new, lr)
-#define LAUNCH_SCORE_S(WT, SPEC)                                                                                      \
+#define LAUNCH_SCORE_S(WT, SPEC, DENSE)                                                                               \
     do {                                                                                                              \
-        if (presample && pairs) LAUNCH_SCORE_P(WT, 2, SPEC);                                                          \
-        else if (presample) LAUNCH_SCORE_P(WT, 1, SPEC);                                                              \
-        else LAUNCH_SCORE_P(WT, 0, SPEC);                                                                             \
+        if (presample && pairs) LAUNCH_SCORE_P(WT, 2, SPEC, DENSE);                                                   \
+        else if (presample) LAUNCH_SCORE_P(WT, 1, SPEC, DENSE);                                                       \
+        else LAUNCH_SCORE_P(WT, 0, SPEC, DENSE);                                                                      \
     } while (0)
 #define LAUNCH_SCORE(WT)                                                                                              \
     do {                                                                                                              \
-        if (capture) LAUNCH_SCORE_S(WT, 1);                                                                           \
-        else LAUNCH_SCORE_S(WT, 0);                                                                                   \
+        if (w_new) LAUNCH_SCORE_S(WT, 0, 1);                                                                          \
+        else if (capture) LAUNCH_SCORE_S(WT, 1, 0);                                                                   \
+        else LAUNCH_SCORE_S(WT, 0, 0);                                                                                \
     } while (0)
     switch (W) {
         case 1: LAUNCH_SCORE(1); break;
@@ -630,7 +631,10 @@ static int score_impl(slimdp_ctx* ctx, const float* w, const float* const* g, ui
         case 4: LAUNCH_SCORE(4); break;
         case 8: LAUNCH_SCORE(8); break;
         case 16: LAUNCH_SCORE(16); break;
-        default: LAUNCH_SCORE_S(0, 0); break;
+        default:
+            if (w_new) LAUNCH_SCORE_S(0, 0, 1);
+            else LAUNCH_SCORE_S(0, 0, 0);
+            break;
     }
 #undef LAUNCH_SCORE_P
 #undef LAUNCH_SCORE_S

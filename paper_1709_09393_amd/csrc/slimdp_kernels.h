@@ -260,7 +260,7 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
 // ---------------------------------------------------------------------------------------
 // K1: significance of every parameter + level-0 histogram of its bits (per segment).
 // Reads w and the W updates once, writes the score once: 4n(W+2) bytes.
-// With w_new != nullptr (the iteration before a reselection, algorithm 1 / section 3.3 steps
+// With DENSE = 1 (the iteration before a reselection, algorithm 1 / section 3.3 steps
 // 3 and 6: every worker pushed its whole update) the model is first updated with all of them,
 // w_new = fma(-lr, (+0 + g_0) + g_1 + ..., w), written to w_new (which may be w itself), and
 // the significance is that of the new model: 4n(W+3) bytes.
@@ -307,7 +307,7 @@ __host__ __device__ constexpr uint32_t spec_align(uint32_t W) { return (W == 0u 
 #ifndef SCORE_MINB
 #define SCORE_MINB 4
 #endif
-template <int WT, int PRE, int SPEC>
+template <int WT, int PRE, int SPEC, int DENSE>
 __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __restrict__ w, PtrTab g, int Wrt, float c,
                                                  float* __restrict__ S, const uint32_t* __restrict__ tile_start,
                                                  const uint32_t* __restrict__ tile_seg, uint32_t T,
@@ -315,6 +315,7 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                                                  float* __restrict__ w_new, float lr)
 {
     static_assert(!SPEC || WT != 0, "capture needs the update values in registers");
+    static_assert(!(SPEC && DENSE), "a dense update is never followed by a pack of the same updates");
     // a significance is never negative: its sign bit is clear and the upper half of the level-0 bins stays empty
     constexpr uint32_t NB = CORE_NB0 / 2;
     __shared__ uint32_t h[NB];
@@ -354,7 +355,7 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                 float a = static_cast<const float*>(g.p[0])[e];
                 for (int k = 1; k < W; ++k) a = a + static_cast<const float*>(g.p[k])[e];
                 float we = w[e];
-                if (w_new) { we = __builtin_fmaf(-lr, a + 0.0f, we); w_new[e] = we; }      // dense update first
+                if (DENSE) { we = __builtin_fmaf(-lr, a + 0.0f, we); w_new[e] = we; }      // dense update first
                 const float sc = significance(we, a, c);
                 S[e] = sc;
                 atomicAdd(&h[(__float_as_uint(sc) >> CORE_SHIFT0) & (NB - 1u)], 1u);
@@ -398,7 +399,7 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                         a.x = a.x + y.x; a.y = a.y + y.y; a.z = a.z + y.z; a.w = a.w + y.w;
                     }
                 }
-                if (w_new) {        // uniform: the server's dense update first (its sum starts from +0), then the new model's score
+                if (DENSE) {        // the server's dense update first (its sum starts from +0), then the new model's score
                     wv.x = __builtin_fmaf(-lr, a.x + 0.0f, wv.x); wv.y = __builtin_fmaf(-lr, a.y + 0.0f, wv.y);
                     wv.z = __builtin_fmaf(-lr, a.z + 0.0f, wv.z); wv.w = __builtin_fmaf(-lr, a.w + 0.0f, wv.w);
                     reinterpret_cast<float4*>(w_new + e0)[lane] = wv;
