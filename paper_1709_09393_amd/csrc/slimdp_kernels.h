@@ -175,6 +175,13 @@ __device__ __forceinline__ void explore_subtile(uint32_t worker, uint32_t t, uin
     wave_sync();
 }
 
+// Which of a lane's four parameters e0 .. e0+3 lie inside a ragged sub-tile of sub_len parameters.
+__device__ __forceinline__ uint32_t inside_mask(uint32_t e0, uint32_t sub_len)
+{
+    const uint32_t left = (e0 < sub_len) ? sub_len - e0 : 0u;
+    return (left >= 4u) ? 15u : ((1u << left) - 1u);
+}
+
 // The same for a sub-tile that starts on a Philox block (start + 1024*sub divisible by 4):
 // no LDS at all.  Round `it` covers the 256 parameters [256*it, 256*it+256) of the sub-tile
 // in index order (lane L owns parameters 4L..4L+3 of the round), so a candidate's place in
@@ -201,33 +208,34 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
     const uint32_t base = start + off;
     uint32_t* ckeys = out.cand_keys + (size_t)base;
     const uint32_t sure_excl = has_sure ? sure_m1 + 1u : 0u;         // sure_m1 < bound_m1: no overflow
+    const uint32_t width_m1 = bound_m1 - sure_excl;                  // candidate words are sure_excl .. bound_m1
     uint32_t run = 0, sword = 0, cword = 0;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
         const uint32_t e0 = (uint32_t)it * 256u + lane * 4u;      // first of this lane's four parameters
         uint32_t r[4];
         philox4x32_10((base + e0) >> 2, worker, pk.it_lo, pk.it_hi, pk.seed_lo, pk.seed_hi, r);
-        // zone flags of the four parameters, without branches: sure (word below sure_excl), candidate (not sure, word
-        // up to the bound)
+        // sure flags of the four parameters, without branches (word below sure_excl)
         uint32_t fs = (r[0] < sure_excl ? 1u : 0u) | (r[1] < sure_excl ? 2u : 0u) | (r[2] < sure_excl ? 4u : 0u) |
                       (r[3] < sure_excl ? 8u : 0u);
-        uint32_t fc = (r[0] <= bound_m1 ? 1u : 0u) | (r[1] <= bound_m1 ? 2u : 0u) | (r[2] <= bound_m1 ? 4u : 0u) |
-                      (r[3] <= bound_m1 ? 8u : 0u);
-        if (sub_len != SUB) {                                         // uniform: a ragged sub-tile
-            const uint32_t left = (e0 < sub_len) ? sub_len - e0 : 0u;
-            const uint32_t inside = (left >= 4u) ? 15u : ((1u << left) - 1u);
-            fs &= inside; fc &= inside;
-        }
-        fc &= ~fs;
+        if (sub_len != SUB) fs &= inside_mask(e0, sub_len);           // uniform: a ragged sub-tile
         // bitmap words: lanes 8j..8j+7 make word j of this round
         const uint32_t vs = or_reduce8(fs << (4u * (lane & 7u)));
         if ((lane & 7u) == (uint32_t)it) sword = vs;       // all eight lanes of a group hold the word: lane `it` of the group keeps it
-        if (!PAIRS) {
-            const uint32_t vc = or_reduce8(fc << (4u * (lane & 7u)));
-            if ((lane & 7u) == (uint32_t)it) cword = vc;
-        }
-        // place in the list: candidates of lower lanes in this round, all four components
-        if (__ballot(fc != 0u) != 0ull) {                             // uniform; rare with a narrow candidate zone
+        // candidate zone sure_excl <= word <= bound: one test for the four (the smallest distance above sure_excl;
+        // words below it wrap to huge distances); the per-parameter work only when some lane of the wave has one,
+        // which is rare with a narrow zone
+        const uint32_t d0 = r[0] - sure_excl, d1 = r[1] - sure_excl, d2 = r[2] - sure_excl, d3 = r[3] - sure_excl;
+        const uint32_t dmin = min(min(d0, d1), min(d2, d3));
+        if (__ballot(dmin <= width_m1) != 0ull) {                     // uniform
+            uint32_t fc = (d0 <= width_m1 ? 1u : 0u) | (d1 <= width_m1 ? 2u : 0u) | (d2 <= width_m1 ? 4u : 0u) |
+                          (d3 <= width_m1 ? 8u : 0u);
+            if (sub_len != SUB) fc &= inside_mask(e0, sub_len);
+            if (!PAIRS) {
+                const uint32_t vc = or_reduce8(fc << (4u * (lane & 7u)));
+                if ((lane & 7u) == (uint32_t)it) cword = vc;
+            }
+            // place in the list: candidates of lower lanes in this round, all four components
             uint32_t below = 0, total = 0;
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) {
