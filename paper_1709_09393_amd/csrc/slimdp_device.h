@@ -62,6 +62,30 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
     return v;
 }
 
+// Buffer addressing: a 128-bit descriptor in scalar registers (base, byte range, no stride)
+// plus one 32-bit per-lane byte offset and a scalar offset.  Compared with flat 64-bit
+// per-lane addresses this keeps the address arithmetic out of the vector registers, and
+// accesses outside [0, bytes) are dropped by the hardware.  Callers pass 0 as the scalar
+// offset and fold the wave's part into the lane offset: with a scalar-register offset the
+// 16-byte forms were seen to store, now and then, a stale first dword on this target
+// (caught by the several-tiles-per-block scoring test).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_of(const void* base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ float4 buffer_load4(__amdgpu_buffer_rsrc_t r, uint32_t lane_bytes, uint32_t wave_bytes)
+{
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_bytes, (int)wave_bytes, 0);
+    return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+}
+__device__ __forceinline__ void buffer_store4(__amdgpu_buffer_rsrc_t r, uint32_t lane_bytes, uint32_t wave_bytes, float4 f)
+{
+    u32x4 v;
+    v.x = __float_as_uint(f.x); v.y = __float_as_uint(f.y); v.z = __float_as_uint(f.z); v.w = __float_as_uint(f.w);
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)lane_bytes, (int)wave_bytes, 0);
+}
+
 // OR over aligned groups of eight lanes, every lane of a group getting the result.  Three
 // data-parallel-primitive moves inside a row of 16 lanes (swap neighbours, swap pairs, mirror
 // each half row) instead of three trips through the LDS crossbar.

@@ -257,10 +257,16 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
             run += total;
         }
     }
-    // the 32 bitmap words of the sub-tile in one store: word 8 * it + j sits in lane 8 * j + it
-    if ((lane & 7u) < 4u) {
-        swords[(lane & 7u) * 8u + (lane >> 3)] = sword;
-        if (!PAIRS) cwords[(lane & 7u) * 8u + (lane >> 3)] = cword;
+    // the 32 bitmap words of the sub-tile in one store of one whole line by lanes 0..31 in address order (scattered
+    // words make the memory side read the line first): word 8 * it + j sits in lane 8 * j + it
+    {
+        const int src = (int)(8u * (lane & 7u) + ((lane >> 3) & 3u));
+        const uint32_t sw = __shfl(sword, src, 64);
+        if (lane < SUB_WORDS) swords[lane] = sw;
+        if (!PAIRS) {
+            const uint32_t cw = __shfl(cword, src, 64);
+            if (lane < SUB_WORDS) cwords[lane] = cw;
+        }
     }
     if (lane == 0) out.cnt_cand[(size_t)t * SUBS + sub] = run;
 }
@@ -330,6 +336,7 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
     const int W = WT ? WT : Wrt;
     // the wave's number as a scalar: addresses below are then a scalar base plus a small per-lane offset
     const uint32_t lane = lane_id(), wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lane16 = lane * 16u;      // byte offset of the lane's float4: a 32-bit offset beside a scalar base
     for (uint32_t b = threadIdx.x; b < NB; b += BLOCK) h[b] = 0;
     __syncthreads();
     const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
@@ -370,16 +377,26 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
             }
         }
         if (!vec && !PRE) continue;
+        // the tile through buffer descriptors (scalar base per array, one 32-bit lane offset for all of them)
+        const __amdgpu_buffer_rsrc_t rw = buffer_of(w + start, TILE * 4u);
+        const __amdgpu_buffer_rsrc_t rS = buffer_of(S + start, TILE * 4u);
+        const __amdgpu_buffer_rsrc_t rn = buffer_of(DENSE ? w_new + start : S + start, TILE * 4u);
+        __amdgpu_buffer_rsrc_t rg[WT ? WT : 1];
+        if (WT) {
+#pragma unroll
+            for (int k = 0; k < WT; ++k) rg[k] = buffer_of(static_cast<const float*>(g.p[k]) + start, TILE * 4u);
+        }
 #pragma unroll 1
         for (int r = 0; r < 4; ++r) {
             const size_t e0 = (size_t)start + (size_t)wid * SUB + (size_t)r * 256;      // uniform over the wave
+            const uint32_t lane_bytes = (wid * SUB + (uint32_t)r * 256u) * 4u + lane16;  // of the lane's float4 inside the tile
             float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
             float4 x[WT ? WT : 1];
             if (vec) {          // request this round's lines first ...
-                wv = reinterpret_cast<const float4*>(w + e0)[lane];
+                wv = buffer_load4(rw, lane_bytes, 0u);
                 if (WT) {
 #pragma unroll
-                    for (int k = 0; k < WT; ++k) x[k] = reinterpret_cast<const float4*>(static_cast<const float*>(g.p[k]) + e0)[lane];
+                    for (int k = 0; k < WT; ++k) x[k] = buffer_load4(rg[k], lane_bytes, 0u);
                 }
             }
             if (PRE) {          // ... do this round's share of the integer work while they fly ...
@@ -401,21 +418,21 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
 #pragma unroll
                     for (int k = 1; k < WT; ++k) { a.x = a.x + x[k].x; a.y = a.y + x[k].y; a.z = a.z + x[k].z; a.w = a.w + x[k].w; }
                 } else {
-                    a = reinterpret_cast<const float4*>(static_cast<const float*>(g.p[0]) + e0)[lane];
+                    a = *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(static_cast<const float*>(g.p[0]) + e0) + lane16);
                     for (int k = 1; k < W; ++k) {
-                        const float4 y = reinterpret_cast<const float4*>(static_cast<const float*>(g.p[k]) + e0)[lane];
+                        const float4 y = *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(static_cast<const float*>(g.p[k]) + e0) + lane16);
                         a.x = a.x + y.x; a.y = a.y + y.y; a.z = a.z + y.z; a.w = a.w + y.w;
                     }
                 }
                 if (DENSE) {        // the server's dense update first (its sum starts from +0), then the new model's score
                     wv.x = __builtin_fmaf(-lr, a.x + 0.0f, wv.x); wv.y = __builtin_fmaf(-lr, a.y + 0.0f, wv.y);
                     wv.z = __builtin_fmaf(-lr, a.z + 0.0f, wv.z); wv.w = __builtin_fmaf(-lr, a.w + 0.0f, wv.w);
-                    reinterpret_cast<float4*>(w_new + e0)[lane] = wv;
+                    buffer_store4(rn, lane_bytes, 0u, wv);
                 }
                 float4 sc;
                 sc.x = significance(wv.x, a.x, c); sc.y = significance(wv.y, a.y, c);
                 sc.z = significance(wv.z, a.z, c); sc.w = significance(wv.w, a.w, c);
-                reinterpret_cast<float4*>(S + e0)[lane] = sc;
+                buffer_store4(rS, lane_bytes, 0u, sc);
                 atomicAdd(&h[(__float_as_uint(sc.x) >> CORE_SHIFT0) & (NB - 1u)], 1u);
                 atomicAdd(&h[(__float_as_uint(sc.y) >> CORE_SHIFT0) & (NB - 1u)], 1u);
                 atomicAdd(&h[(__float_as_uint(sc.z) >> CORE_SHIFT0) & (NB - 1u)], 1u);

@@ -131,6 +131,34 @@ def test_flat_iteration_sizes(n):
     assert_iteration_matches(wl, got, want)
 
 
+@pytest.mark.parametrize("W", [4, 16])
+def test_score_with_several_tiles_per_persistent_block(W):
+    """More tiles than the scoring kernel has blocks, so that every wave walks through several tiles (the smaller
+    cases give each block one tile at most); with and without the announced draw and the capture."""
+    wl = workloads.TINY.scaled(6_000_003, W=W)
+    w_h, g_h = wl.weights(), wl.gradients(0)
+    S_o = oracle.score(w_h, g_h, wl.c)
+    sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
+    w, g = to_dev(w_h), [to_dev(x) for x in g_h]
+    assert sd.T > 1024
+    S = sd.score(w, g, wl.c)
+    sd.synchronize()
+    assert np.array_equal(f32bits(S.cpu().numpy()), f32bits(S_o)), "plain"
+    sd.set_option("speculative_pack", 1)
+    for t in range(2):
+        sd.explore_hint([wl.k], t, [wl.m], 0, wl.W)
+        sd.score(w, g, wl.c, out=S)
+        core_idx, core_bits, core_off, epoch = sd.select_core(S, [wl.k], reuse_histogram=True)
+        sd.synchronize()
+        assert np.array_equal(f32bits(S.cpu().numpy()), f32bits(S_o)), "hinted, capturing (%d)" % t
+    w2 = to_dev(w_h)
+    sd.dense_update_score(w2, g, wl.lr, wl.c, out=S)
+    sd.synchronize()
+    w_o, S2_o = oracle.dense_update_score(w_h, g_h, wl.lr, wl.c)
+    assert np.array_equal(f32bits(w2.cpu().numpy()), f32bits(w_o)) and np.array_equal(f32bits(S.cpu().numpy()), f32bits(S2_o))
+    sd.close()
+
+
 @pytest.mark.parametrize("W", [1, 2, 3, 8, 16])
 def test_worker_counts(W):
     wl = workloads.TINY.scaled(30_011, W=W)
