@@ -86,6 +86,11 @@ __device__ __forceinline__ void buffer_store4(__amdgpu_buffer_rsrc_t r, uint32_t
     __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)lane_bytes, (int)wave_bytes, 0);
 }
 
+__device__ __forceinline__ void buffer_store1(__amdgpu_buffer_rsrc_t r, uint32_t lane_bytes, uint32_t v)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)lane_bytes, 0, 0);
+}
+
 // OR over aligned groups of eight lanes, every lane of a group getting the result.  Three
 // data-parallel-primitive moves inside a row of 16 lanes (swap neighbours, swap pairs, mirror
 // each half row) instead of three trips through the LDS crossbar.

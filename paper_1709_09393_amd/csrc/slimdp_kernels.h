@@ -451,13 +451,13 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                     }
                     constexpr uint32_t A = spec_align(WT);
                     const uint32_t padded = (total + A - 1u) & ~(A - 1u);
-                    float* sub_base = spec.vals + ((size_t)start + wid * SUB) * WT;     // uniform; the rank is the lane's part
+                    // the sub-tile's entries through a descriptor: the entry number is the lane's part
+                    const __amdgpu_buffer_rsrc_t rv = buffer_of(spec.vals + ((size_t)start + wid * SUB) * WT, SUB * WT * 4u);
                     if (f) {
                         uint32_t pos = spec_run + below;
 #pragma unroll
                         for (int cc = 0; cc < 4; ++cc) {
                             if ((f >> cc) & 1u) {
-                                float* d = sub_base + (size_t)pos * WT;
                                 if (WT >= 4) {
 #pragma unroll
                                     for (int k = 0; k < WT; k += 4) {
@@ -466,20 +466,21 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                                         o.y = cc == 0 ? x[k + 1].x : cc == 1 ? x[k + 1].y : cc == 2 ? x[k + 1].z : x[k + 1].w;
                                         o.z = cc == 0 ? x[k + 2].x : cc == 1 ? x[k + 2].y : cc == 2 ? x[k + 2].z : x[k + 2].w;
                                         o.w = cc == 0 ? x[k + 3].x : cc == 1 ? x[k + 3].y : cc == 2 ? x[k + 3].z : x[k + 3].w;
-                                        reinterpret_cast<float4*>(d)[k / 4] = o;
+                                        buffer_store4(rv, (pos * WT + k) * 4u, 0u, o);
                                     }
                                 } else {
 #pragma unroll
-                                    for (int k = 0; k < WT; ++k) d[k] = cc == 0 ? x[k].x : cc == 1 ? x[k].y : cc == 2 ? x[k].z : x[k].w;
+                                    for (int k = 0; k < WT; ++k)
+                                        buffer_store1(rv, (pos * WT + k) * 4u,
+                                                      __float_as_uint(cc == 0 ? x[k].x : cc == 1 ? x[k].y : cc == 2 ? x[k].z : x[k].w));
                                 }
                                 ++pos;
                             }
                         }
                     }
                     if (lane < padded - total) {          // fill the round's last line
-                        float* d = sub_base + (size_t)(spec_run + total + lane) * WT;
 #pragma unroll
-                        for (int k = 0; k < WT; ++k) d[k] = 0.0f;
+                        for (int k = 0; k < WT; ++k) buffer_store1(rv, ((spec_run + total + lane) * WT + k) * 4u, 0u);
                     }
                     spec_run += padded;
                 }
