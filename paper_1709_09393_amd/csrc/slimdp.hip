@@ -128,7 +128,7 @@ struct slimdp_ctx {
         char* mem = nullptr;
         uint32_t* lo[2] = {nullptr, nullptr};   // capture bound per segment: [cur] read by the scoring pass, the other written by the selection
         uint32_t* fail = nullptr;               // per segment: the selection's threshold fell below the capture bound
-        uint32_t* bits = nullptr;
+        uint2* bits = nullptr;
         float* vals = nullptr;
         int cur = 0;
         bool next_written = false;              // a selection has refreshed lo[cur ^ 1] since the last capture
@@ -518,7 +518,7 @@ int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value)
                 ctx->spec.lo[0] = cv.take<uint32_t>(S);
                 ctx->spec.lo[1] = cv.take<uint32_t>(S);
                 ctx->spec.fail = cv.take<uint32_t>(S);
-                ctx->spec.bits = cv.take<uint32_t>((size_t)ctx->T * TILE_WORDS);
+                ctx->spec.bits = cv.take<uint2>((size_t)ctx->T * TILE_WORDS);
                 ctx->spec.vals = cv.take<float>((size_t)ctx->maxW * ctx->keys_stride);
             };
             carve_spec(sizing);
@@ -953,7 +953,16 @@ int slimdp_pack(slimdp_ctx* ctx, uint32_t n_workers, const float* const* g, cons
     for (uint32_t q = 0; spec && q < n_workers; ++q) spec = ctx->spec.g[q] == g[q];
     if (spec) {
         ctx->spec.captured = false;      // one capture serves one pack
-        if (k) {
+        if (k && ctx->n_seg == 1) {
+            // flat model: tile = index / 4096; all tiles but a ragged last one are full
+            const uint32_t T_full = (uint32_t)(ctx->n / TILE);
+            uint64_t blocks = (k + 1023) / 1024;
+            if (blocks > 4096) blocks = 4096;
+            hipLaunchKernelGGL(k_pack_core_flat, dim3((uint32_t)blocks), dim3(256), 0, ctx->stream, make_tab<PtrTab>(g, n_workers),
+                               n_workers, ctx->n, T_full, core_idx, (uint32_t)k, ctx->spec.bits, ctx->spec.vals, ctx->spec.fail,
+                               ctx->spec.vec_ok, make_tab<MutPtrTab>(core_val, n_workers));
+            SLIMDP_LAUNCHED(ctx, "k_pack_core_flat");
+        } else if (k) {
             hipLaunchKernelGGL(k_pack_core_spec, dim3((ctx->T + 3) / 4), dim3(BLOCK), 0, ctx->stream, make_tab<PtrTab>(g, n_workers),
                                n_workers, ctx->n, ctx->d_tile_start, ctx->d_tile_seg, ctx->T, core_idx, core_off, ctx->spec.bits,
                                ctx->spec.vals, ctx->spec.fail, ctx->spec.vec_ok,

@@ -304,7 +304,8 @@ struct PreArgs {
 // SPEC = 1 (speculative packing, WT != 0 only) keeps, for every parameter of a full aligned
 // tile whose significance reaches spec.lo[segment] - a little below the core threshold of
 // the previous selection -, the W update values while they are in registers: one bit in
-// spec.bits, and one entry of W consecutive values in spec.vals.  The entries of a sub-tile
+// spec.bits (beside each bitmap word: the entry number of its first parameter), and one
+// entry of W consecutive values in spec.vals.  The entries of a sub-tile
 // follow each other in index order from entry (tile start + 1024 * sub-tile); each round of
 // 256 parameters starts on a 128-byte line and its last line is filled up, so that every
 // line is written whole and at once (a line written in parts minutes apart leaves the cache
@@ -313,7 +314,7 @@ struct PreArgs {
 // them and the pack need not read the updates again.
 struct SpecArgs {
     const uint32_t* lo;      // [n_seg] lowest captured significance (as bits)
-    uint32_t* bits;          // [T * TILE_WORDS]
+    uint2* bits;             // [T * TILE_WORDS] x = the bits, y = number of the word's first entry inside its sub-tile
     float* vals;             // [entries][W]
 };
 __host__ __device__ constexpr uint32_t spec_align(uint32_t W) { return (W == 0u || W >= 32u) ? 1u : 32u / W; }   // entries per 128-byte line
@@ -441,7 +442,6 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                     const uint32_t f = (__float_as_uint(sc.x) >= spec_lo ? 1u : 0u) | (__float_as_uint(sc.y) >= spec_lo ? 2u : 0u) |
                                        (__float_as_uint(sc.z) >= spec_lo ? 4u : 0u) | (__float_as_uint(sc.w) >= spec_lo ? 8u : 0u);
                     const uint32_t v = or_reduce8(f << (4u * (lane & 7u)));      // lanes 8j..8j+7 make bitmap word j of this round
-                    if ((lane & 7u) == 0) spec.bits[(size_t)t * TILE_WORDS + wid * SUB_WORDS + r * 8 + (lane >> 3)] = v;
                     uint32_t below = 0, total = 0;
 #pragma unroll
                     for (int cc = 0; cc < 4; ++cc) {
@@ -449,6 +449,9 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                         below += __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
                         total += (uint32_t)__popcll(bal);
                     }
+                    // lane 8j holds word j of the round and the number of captured parameters before it
+                    if ((lane & 7u) == 0)
+                        spec.bits[(size_t)t * TILE_WORDS + wid * SUB_WORDS + r * 8 + (lane >> 3)] = make_uint2(v, spec_run + below);
                     constexpr uint32_t A = spec_align(WT);
                     const uint32_t padded = (total + A - 1u) & ~(A - 1u);
                     // the sub-tile's entries through a descriptor: the entry number is the lane's part
@@ -1608,7 +1611,7 @@ __global__ __launch_bounds__(BLOCK) void k_pack_core_spec(PtrTab g, uint32_t nw,
                                                           const uint32_t* __restrict__ tile_seg, uint32_t T,
                                                           const uint32_t* __restrict__ core_idx,
                                                           const uint32_t* __restrict__ core_off,
-                                                          const uint32_t* __restrict__ spec_bits,
+                                                          const uint2* __restrict__ spec_bits,
                                                           const float* __restrict__ spec_vals,
                                                           const uint32_t* __restrict__ spec_fail, int vec_ok, MutPtrTab core_val)
 {
@@ -1623,7 +1626,8 @@ __global__ __launch_bounds__(BLOCK) void k_pack_core_spec(PtrTab g, uint32_t nw,
         // entry number of every captured parameter inside its sub-tile: lanes 4r..4r+3 hold the eight bitmap
         // words of round r (16 rounds a tile, 4 a sub-tile); a round's entries start on a multiple of A
         const uint32_t A = spec_align(nw);
-        const uint2 w2 = *reinterpret_cast<const uint2*>(spec_bits + (size_t)t * TILE_WORDS + 2 * lane);
+        const uint4 w4 = *reinterpret_cast<const uint4*>(spec_bits + (size_t)t * TILE_WORDS + 2 * lane);
+        const uint2 w2 = make_uint2(w4.x, w4.z);
         const uint32_t pc = __popc(w2.x) + __popc(w2.y);
         const uint32_t incl = wave_incl_scan(pc);
         const uint32_t round0 = __shfl(incl - pc, (int)(lane & ~3u), 64);                     // captured before this round
@@ -1680,6 +1684,70 @@ __global__ __launch_bounds__(BLOCK) void k_pack_core_spec(PtrTab g, uint32_t nw,
             const uint32_t i = core_idx[j];
             if (i >= n) continue;
             for (uint32_t q = 0; q < nw; ++q) static_cast<float*>(core_val.p[q])[j] = static_cast<const float*>(g.p[q])[i];
+        }
+    }
+}
+
+// The same for a flat model, one thread per list entry: the tile and the bitmap word follow
+// from the index itself, the word's first entry number is stored beside the word.  Every wave
+// writes 64 consecutive list positions per worker (whole, aligned lines: a store that covers
+// a line only in part makes the memory side read it first).  grid: any, grid-stride.
+__global__ __launch_bounds__(256) void k_pack_core_flat(PtrTab g, uint32_t nw, uint64_t n, uint32_t T_full,
+                                                        const uint32_t* __restrict__ core_idx, uint32_t k,
+                                                        const uint2* __restrict__ spec_bits,
+                                                        const float* __restrict__ spec_vals,
+                                                        const uint32_t* __restrict__ spec_fail, int vec_ok, MutPtrTab core_val)
+{
+    constexpr int U = 4;
+    const bool ok = vec_ok && spec_fail[0] == 0;
+    const uint32_t stride = gridDim.x * 256u;
+    for (uint32_t jb = blockIdx.x * 256u + threadIdx.x; jb < k; jb += U * stride) {
+        uint32_t i[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) i[u] = (jb + u * stride < k) ? core_idx[jb + u * stride] : 0xFFFFFFFFu;
+        uint2 bp[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            bp[u] = make_uint2(0u, 0u);
+            if (i[u] < n && ok && (i[u] >> 12) < T_full) bp[u] = spec_bits[i[u] >> 5];      // tile * 128 + word in tile
+        }
+        if ((nw & 3u) == 0) {
+            for (uint32_t q = 0; q < nw; q += 4) {
+                float4 v[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (i[u] >= n) continue;
+                    if (ok && (i[u] >> 12) < T_full) {
+                        const uint32_t entry = bp[u].y + __popc(bp[u].x & mask_below(i[u] & 31u));
+                        v[u] = *reinterpret_cast<const float4*>(spec_vals + ((size_t)(i[u] & ~(SUB - 1u)) + entry) * nw + q);
+                    } else {
+                        v[u].x = static_cast<const float*>(g.p[q])[i[u]]; v[u].y = static_cast<const float*>(g.p[q + 1])[i[u]];
+                        v[u].z = static_cast<const float*>(g.p[q + 2])[i[u]]; v[u].w = static_cast<const float*>(g.p[q + 3])[i[u]];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t j = jb + u * stride;
+                    if (i[u] < n) {
+                        static_cast<float*>(core_val.p[q])[j] = v[u].x; static_cast<float*>(core_val.p[q + 1])[j] = v[u].y;
+                        static_cast<float*>(core_val.p[q + 2])[j] = v[u].z; static_cast<float*>(core_val.p[q + 3])[j] = v[u].w;
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t j = jb + u * stride;
+                if (i[u] >= n) continue;
+                if (ok && (i[u] >> 12) < T_full) {
+                    const uint32_t entry = bp[u].y + __popc(bp[u].x & mask_below(i[u] & 31u));
+                    const float* src = spec_vals + ((size_t)(i[u] & ~(SUB - 1u)) + entry) * nw;
+                    for (uint32_t q = 0; q < nw; ++q) static_cast<float*>(core_val.p[q])[j] = src[q];
+                } else {
+                    for (uint32_t q = 0; q < nw; ++q) static_cast<float*>(core_val.p[q])[j] = static_cast<const float*>(g.p[q])[i[u]];
+                }
+            }
         }
     }
 }
