@@ -64,7 +64,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--n", type=int, default=0, help="override the parameter count (profiling runs)")
-    ap.add_argument("--cpu-sample", type=int, default=8_000_000, help="oracle sample size; 0 skips the CPU leg")
+    ap.add_argument("--cpu-sample", type=int, default=16_000_000, help="oracle sample size; 0 skips the CPU leg")
+    ap.add_argument("--workload", default="vgg16_flat", help="another named configuration (not the headline): "
+                    "tiny, googlenet_seg57, tie_stress")
     ap.add_argument("--opt", action="append", default=[], help="library option name=value (tuning runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (known traffic) so that hardware byte counters "
@@ -86,9 +88,12 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    wl = workloads.VGG16 if not args.n else workloads.VGG16.scaled(args.n)
+    wl = workloads.BY_NAME[args.workload]
+    if args.n:
+        wl = wl.scaled(args.n)
     n, W, k, m = wl.n, wl.W, wl.k, wl.m
-    sd = binding.SlimDP(n, W, seed=workloads.EXPLORE_SEED)
+    ks, ms = [int(x) for x in wl.k_seg()], [int(x) for x in wl.m_seg()]
+    sd = binding.SlimDP(n, W, seg_off=[int(x) for x in wl.segment_offsets()], seed=workloads.EXPLORE_SEED)
     sd.set_option("speculative_pack", 1)   # the scoring pass keeps the likely core's update values for the pack
     for kv in args.opt:
         name, value = kv.split("=")
@@ -113,13 +118,13 @@ def main() -> int:
         mark(0)
         sd.score(w, g, wl.c, out=S)
         mark(1)
-        _, _, _, epoch = sd.select_core(S, [k], reuse_histogram=True, core_idx=core_idx, core_bits=core_bits,
+        _, _, _, epoch = sd.select_core(S, ks, reuse_histogram=True, core_idx=core_idx, core_bits=core_bits,
                                         core_off=core_off)
         mark(2)
-        sd.sample_explore(core_bits, [k], t, [m], 0, W, expl_idx=expl_idx, expl_off=expl_off)
+        sd.sample_explore(core_bits, ks, t, ms, 0, W, expl_idx=expl_idx, expl_off=expl_off)
         # the next iteration's random draw (integer work only) starts now on the library's side stream and
         # runs beside the memory-bound kernels that follow: every step launches exactly one draw
-        sd.explore_hint([k], t + 1, [m], 0, W)
+        sd.explore_hint(ks, t + 1, ms, 0, W)
         mark(3)
         sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch, core_val=core_val, expl_val=expl_val)
         mark(4)
@@ -133,7 +138,7 @@ def main() -> int:
         torch.cuda.synchronize()
         del a, b
 
-    sd.explore_hint([k], 0, [m], 0, W)
+    sd.explore_hint(ks, 0, ms, 0, W)
     for t in range(args.warmup):
         step(t)
     sd.synchronize()
@@ -160,7 +165,7 @@ def main() -> int:
     # factors being what the same counters read for a plain 1 GiB copy): 5.226 GB + 1.312 GB on the
     # default workload (the bytes above the algorithmic ones: capture for the pack, the draws' bitmaps,
     # spill reloads).  Measured under rocprofv3, not in this process; null for any other size.
-    traffic = 6.538e9 if (not args.n) else None
+    traffic = 6.538e9 if (not args.n and wl.name == "vgg16_flat") else None
     roofline = {"bound": "hbm", "kernel": "k_score", "achieved": score_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": score_gbs / HBM_PEAK_GBS, "traffic": traffic,
                 "algorithmic_bytes_per_launch": sb["score"], "avg_launch_ms": stage_ms["score"]}
@@ -183,11 +188,11 @@ def main() -> int:
     ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     reps = max(3, min(args.steps, 10))
     sd.dense_update_score(w, g, wl.lr, wl.c, out=S)
-    sd.select_core(S, [k], reuse_histogram=True, core_idx=core_idx, core_bits=core_bits, core_off=core_off)
+    sd.select_core(S, ks, reuse_histogram=True, core_idx=core_idx, core_bits=core_bits, core_off=core_off)
     ev2[0].record()
     for _ in range(reps):
         sd.dense_update_score(w, g, wl.lr, wl.c, out=S)
-        sd.select_core(S, [k], reuse_histogram=True, core_idx=core_idx, core_bits=core_bits, core_off=core_off)
+        sd.select_core(S, ks, reuse_histogram=True, core_idx=core_idx, core_bits=core_bits, core_off=core_off)
     ev2[1].record()
     torch.cuda.synchronize()
     sd.synchronize()
