@@ -1014,7 +1014,8 @@ int slimdp_merge(slimdp_ctx* ctx, float* w, float lr, uint64_t core_epoch, uint3
     if (rc) return rc;
     hipLaunchKernelGGL(k_merge, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, w, lr, n_workers, ctx->d_tile_start, core_idx,
                        core_off, make_tab<PtrTab>(core_val, n_workers), make_tab<PtrTab>(expl_idx, n_workers),
-                       make_tab<PtrTab>(expl_off, n_workers), make_tab<PtrTab>(expl_val, n_workers), (int)aligned16(w));
+                       make_tab<PtrTab>(expl_off, n_workers), make_tab<PtrTab>(expl_val, n_workers), (int)aligned16(w),
+                       ctx->n, ctx->n_seg);
     SLIMDP_LAUNCHED(ctx, "k_merge");
     return SLIMDP_OK;
 }

@@ -1712,26 +1712,35 @@ __global__ __launch_bounds__(256) void k_pack_core_flat(PtrTab g, uint32_t nw, u
             if (i[u] < n && ok && (i[u] >> 12) < T_full) bp[u] = spec_bits[i[u] >> 5];      // tile * 128 + word in tile
         }
         if ((nw & 3u) == 0) {
-            for (uint32_t q = 0; q < nw; q += 4) {
-                float4 v[U];
+            // eight workers (two 16-byte pieces of an entry) per turn, all loads of a turn requested before any store
+            for (uint32_t q = 0; q < nw; q += 8) {
+                float4 v[U][2];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (i[u] >= n) continue;
-                    if (ok && (i[u] >> 12) < T_full) {
-                        const uint32_t entry = bp[u].y + __popc(bp[u].x & mask_below(i[u] & 31u));
-                        v[u] = *reinterpret_cast<const float4*>(spec_vals + ((size_t)(i[u] & ~(SUB - 1u)) + entry) * nw + q);
-                    } else {
-                        v[u].x = static_cast<const float*>(g.p[q])[i[u]]; v[u].y = static_cast<const float*>(g.p[q + 1])[i[u]];
-                        v[u].z = static_cast<const float*>(g.p[q + 2])[i[u]]; v[u].w = static_cast<const float*>(g.p[q + 3])[i[u]];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        v[u][h] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        const uint32_t qq = q + 4u * h;
+                        if (i[u] >= n || qq >= nw) continue;
+                        if (ok && (i[u] >> 12) < T_full) {
+                            const uint32_t entry = bp[u].y + __popc(bp[u].x & mask_below(i[u] & 31u));
+                            v[u][h] = *reinterpret_cast<const float4*>(spec_vals + ((size_t)(i[u] & ~(SUB - 1u)) + entry) * nw + qq);
+                        } else {
+                            v[u][h].x = static_cast<const float*>(g.p[qq])[i[u]]; v[u][h].y = static_cast<const float*>(g.p[qq + 1])[i[u]];
+                            v[u][h].z = static_cast<const float*>(g.p[qq + 2])[i[u]]; v[u][h].w = static_cast<const float*>(g.p[qq + 3])[i[u]];
+                        }
                     }
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const uint32_t j = jb + u * stride;
-                    if (i[u] < n) {
-                        static_cast<float*>(core_val.p[q])[j] = v[u].x; static_cast<float*>(core_val.p[q + 1])[j] = v[u].y;
-                        static_cast<float*>(core_val.p[q + 2])[j] = v[u].z; static_cast<float*>(core_val.p[q + 3])[j] = v[u].w;
+                    if (i[u] >= n) continue;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const uint32_t qq = q + 4u * h;
+                        if (qq >= nw) continue;
+                        static_cast<float*>(core_val.p[qq])[j] = v[u][h].x; static_cast<float*>(core_val.p[qq + 1])[j] = v[u][h].y;
+                        static_cast<float*>(core_val.p[qq + 2])[j] = v[u][h].z; static_cast<float*>(core_val.p[qq + 3])[j] = v[u][h].w;
                     }
                 }
             }
@@ -1871,6 +1880,21 @@ __global__ __launch_bounds__(BLOCK) void k_pack_stream(PtrTab g, uint32_t nw, co
 // All loads of a tile (its w, its core slice, its explorer entries) are requested in one
 // go right after the tile's offsets are known.
 // ---------------------------------------------------------------------------------------
+// Sum of the W workers' values of core entry j, from +0 in worker order.  The loads of eight workers are requested
+// together (a loop with one load and one add per turn waits for memory W times in a row).
+__device__ __forceinline__ float core_sum(const PtrTab& core_val, uint32_t nw, uint32_t j)
+{
+    float a = 0.0f;
+    for (uint32_t q0 = 0; q0 < nw; q0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = (q0 + u < nw) ? static_cast<const float*>(core_val.p[q0 + u])[j] : 0.0f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) if (q0 + u < nw) a = a + v[u];
+    }
+    return a;
+}
+
 constexpr int MERGE_R = 4;                 // explorer entries per thread kept in registers
 constexpr uint32_t MERGE_HOT_CAP = 128;
 constexpr uint32_t MERGE_STAGE = 256;
@@ -1879,7 +1903,7 @@ __global__ __launch_bounds__(BLOCK) void k_merge(float* __restrict__ w, float lr
                                                  const uint32_t* __restrict__ tile_start,
                                                  const uint32_t* __restrict__ core_idx, const uint32_t* __restrict__ core_off,
                                                  PtrTab core_val, PtrTab expl_idx, PtrTab expl_off, PtrTab expl_val,
-                                                 int vec_ok)
+                                                 int vec_ok, uint64_t n, uint32_t n_seg)
 {
     __shared__ float acc[TILE];
     __shared__ uint32_t cnt[TILE / 4];     // one byte per position: bit 7 = core, low bits = explorer entries
@@ -1891,7 +1915,15 @@ __global__ __launch_bounds__(BLOCK) void k_merge(float* __restrict__ w, float lr
     __shared__ uint16_t spos[MERGE_STAGE];
     __shared__ float sval[MERGE_STAGE];
     const uint32_t t = blockIdx.x;
-    const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
+    // flat model: no table look-up before the tile's loads can be requested
+    uint32_t start, len;
+    if (n_seg == 1) {
+        start = t * TILE;
+        const uint64_t rest = n - (uint64_t)start;
+        len = rest < TILE ? (uint32_t)rest : TILE;
+    } else {
+        start = tile_start[t]; len = tile_start[t + 1] - start;
+    }
     const bool vec = vec_ok && len == TILE && (start & 3u) == 0;
     const uint32_t c0 = core_off[t], c1 = core_off[t + 1];
     float wv[EPT];
@@ -1942,8 +1974,7 @@ __global__ __launch_bounds__(BLOCK) void k_merge(float* __restrict__ w, float lr
     // core: every worker contributes, in worker order
     for (uint32_t j = c0 + threadIdx.x; j < c1; j += BLOCK) {
         const uint32_t pos = core_idx[j] - start;
-        float a = 0.0f;
-        for (uint32_t q = 0; q < nw; ++q) a = a + static_cast<const float*>(core_val.p[q])[j];
+        const float a = core_sum(core_val, nw, j);
         if (pos < len) { acc[pos] = a; atomicOr(&cnt[pos >> 2], 0x80u << (8u * (pos & 3u))); }
     }
     if (fast) {
@@ -1998,8 +2029,7 @@ __global__ __launch_bounds__(BLOCK) void k_merge(float* __restrict__ w, float lr
             __syncthreads();
             for (uint32_t j = c0 + threadIdx.x; j < c1; j += BLOCK) {
                 const uint32_t pos = core_idx[j] - start;
-                float a = 0.0f;
-                for (uint32_t q = 0; q < nw; ++q) a = a + static_cast<const float*>(core_val.p[q])[j];
+                const float a = core_sum(core_val, nw, j);
                 if (pos < len) acc[pos] = a;
             }
         }
