@@ -633,6 +633,81 @@ __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states
 // owns 4L..4L+3), the eight bitmap words of a round are OR-reductions over groups of
 // eight lanes, a candidate's place in the key list comes from wave ballots.
 // ---------------------------------------------------------------------------------------
+// The 1024 scores of sub-tile `wid` of a tile as keys: lane L holds parameters 4L..4L+3 of each round of 256.
+__device__ __forceinline__ void core_load_keys(const float* __restrict__ S, uint32_t start, uint32_t len, uint32_t wid,
+                                               uint32_t lane, int vec_ok, uint32_t key[4][4])
+{
+    const uint32_t off = wid * SUB;
+    const uint32_t sub_len = (len > off) ? ((len - off < SUB) ? len - off : SUB) : 0u;
+    const float* src = S + (size_t)start + off;
+    if (vec_ok && sub_len == SUB && (start & 3u) == 0) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const uint4 v = *reinterpret_cast<const uint4*>(src + it * 256 + lane * 4);
+            key[it][0] = v.x; key[it][1] = v.y; key[it][2] = v.z; key[it][3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < 4; ++it)
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                const uint32_t e = (uint32_t)it * 256u + lane * 4u + cc;
+                key[it][cc] = (e < sub_len) ? __float_as_uint(src[e]) : 0u;
+            }
+    }
+}
+
+// One sub-tile's keys against the level-0 threshold bin b1: bitmaps, candidate keys, counts, level-1 histogram (LDS).
+__device__ __forceinline__ void core_classify(const uint32_t key[4][4], uint32_t t, uint32_t start, uint32_t len, uint32_t wid,
+                                              uint32_t lane, uint32_t b1, uint32_t none, uint32_t* __restrict__ h,
+                                              uint32_t* __restrict__ gt_bits, uint32_t* __restrict__ cand_bits,
+                                              uint32_t* __restrict__ cand_keys, uint32_t* __restrict__ cnt_gt,
+                                              uint32_t* __restrict__ cnt_cand)
+{
+    const uint32_t off = wid * SUB;
+    const uint32_t sub_len = (len > off) ? ((len - off < SUB) ? len - off : SUB) : 0u;
+    uint32_t* gwords = gt_bits + (size_t)t * TILE_WORDS + wid * SUB_WORDS;
+    uint32_t* cwords = cand_bits + (size_t)t * TILE_WORDS + wid * SUB_WORDS;
+    uint32_t* ckeys = cand_keys + (size_t)start + off;
+    uint32_t run = 0, ngt = 0;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        uint32_t fg = 0, fc = 0;
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+            const uint32_t e = (uint32_t)it * 256u + lane * 4u + cc;
+            if (e < sub_len && !none) {
+                const uint32_t d = key[it][cc] >> CORE_SHIFT0;
+                if (d > b1) fg |= 1u << cc;
+                else if (d == b1) fc |= 1u << cc;
+            }
+        }
+        const uint32_t vg = or_reduce8(fg << (4u * (lane & 7u))), vc = or_reduce8(fc << (4u * (lane & 7u)));
+        if ((lane & 7u) == 0) { gwords[it * 8 + (lane >> 3)] = vg; cwords[it * 8 + (lane >> 3)] = vc; }
+        ngt += __popc(fg);
+        uint32_t below = 0, total = 0;
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+            const unsigned long long bal = __ballot((fc >> cc) & 1u);
+            below += __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+            total += (uint32_t)__popcll(bal);
+        }
+        if (fc) {
+            uint32_t pos = run + below;
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                if ((fc >> cc) & 1u) {
+                    ckeys[pos++] = key[it][cc];
+                    atomicAdd(&h[(key[it][cc] >> CORE_SHIFT1) & (CORE_NB1 - 1u)], 1u);
+                }
+            }
+        }
+        run += total;
+    }
+    ngt = wave_sum(ngt);
+    if (lane == 0) { cnt_cand[(size_t)t * SUBS + wid] = run; cnt_gt[(size_t)t * SUBS + wid] = ngt; }
+}
+
 __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ S, const uint32_t* __restrict__ tile_start,
                                                       const uint32_t* __restrict__ tile_seg, uint32_t T,
                                                       const SegState* __restrict__ states, uint32_t* __restrict__ hist,
@@ -648,75 +723,29 @@ __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ 
     const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
     if (t0 >= t1) return;
     uint32_t cur_seg = tile_seg[t0];
-    for (uint32_t t = t0; t < t1; ++t) {
-        const uint32_t seg = tile_seg[t];
-        if (seg != cur_seg) {
-            __syncthreads();
-            flush_hist(h, CORE_NB1, hist + (size_t)cur_seg * H_STRIDE + H_L1);
-            __syncthreads();
-            cur_seg = seg;
+    // two tiles a turn: the scores of both are requested before either is worked on
+    for (uint32_t t = t0; t < t1; t += 2) {
+        const bool two = t + 1 < t1;
+        const uint32_t startA = tile_start[t], lenA = tile_start[t + 1] - startA;
+        const uint32_t startB = two ? tile_start[t + 1] : 0u, lenB = two ? tile_start[t + 2] - startB : 0u;
+        uint32_t keyA[4][4], keyB[4][4];
+        core_load_keys(S, startA, lenA, wid, lane, vec_ok, keyA);
+        if (two) core_load_keys(S, startB, lenB, wid, lane, vec_ok, keyB);
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            if (half == 1 && !two) break;
+            const uint32_t tt = t + half;
+            const uint32_t seg = tile_seg[tt];
+            if (seg != cur_seg) {
+                __syncthreads();
+                flush_hist(h, CORE_NB1, hist + (size_t)cur_seg * H_STRIDE + H_L1);
+                __syncthreads();
+                cur_seg = seg;
+            }
+            const uint32_t b1 = states[seg].prefix, none = states[seg].none;
+            if (half == 0) core_classify(keyA, tt, startA, lenA, wid, lane, b1, none, h, gt_bits, cand_bits, cand_keys, cnt_gt, cnt_cand);
+            else core_classify(keyB, tt, startB, lenB, wid, lane, b1, none, h, gt_bits, cand_bits, cand_keys, cnt_gt, cnt_cand);
         }
-        const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
-        const uint32_t b1 = states[seg].prefix, none = states[seg].none;
-        const uint32_t off = wid * SUB;
-        const uint32_t sub_len = (len > off) ? ((len - off < SUB) ? len - off : SUB) : 0u;
-        const float* src = S + (size_t)start + off;
-        uint32_t* gwords = gt_bits + (size_t)t * TILE_WORDS + wid * SUB_WORDS;
-        uint32_t* cwords = cand_bits + (size_t)t * TILE_WORDS + wid * SUB_WORDS;
-        uint32_t* ckeys = cand_keys + (size_t)start + off;
-        uint32_t key[4][4];
-        if (vec_ok && sub_len == SUB && (start & 3u) == 0) {
-#pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const uint4 v = *reinterpret_cast<const uint4*>(src + it * 256 + lane * 4);
-                key[it][0] = v.x; key[it][1] = v.y; key[it][2] = v.z; key[it][3] = v.w;
-            }
-        } else {
-#pragma unroll
-            for (int it = 0; it < 4; ++it)
-#pragma unroll
-                for (int cc = 0; cc < 4; ++cc) {
-                    const uint32_t e = (uint32_t)it * 256u + lane * 4u + cc;
-                    key[it][cc] = (e < sub_len) ? __float_as_uint(src[e]) : 0u;
-                }
-        }
-        uint32_t run = 0, ngt = 0;
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            uint32_t fg = 0, fc = 0;
-#pragma unroll
-            for (int cc = 0; cc < 4; ++cc) {
-                const uint32_t e = (uint32_t)it * 256u + lane * 4u + cc;
-                if (e < sub_len && !none) {
-                    const uint32_t d = key[it][cc] >> CORE_SHIFT0;
-                    if (d > b1) fg |= 1u << cc;
-                    else if (d == b1) fc |= 1u << cc;
-                }
-            }
-            const uint32_t vg = or_reduce8(fg << (4u * (lane & 7u))), vc = or_reduce8(fc << (4u * (lane & 7u)));
-            if ((lane & 7u) == 0) { gwords[it * 8 + (lane >> 3)] = vg; cwords[it * 8 + (lane >> 3)] = vc; }
-            ngt += __popc(fg);
-            uint32_t below = 0, total = 0;
-#pragma unroll
-            for (int cc = 0; cc < 4; ++cc) {
-                const unsigned long long bal = __ballot((fc >> cc) & 1u);
-                below += __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
-                total += (uint32_t)__popcll(bal);
-            }
-            if (fc) {
-                uint32_t pos = run + below;
-#pragma unroll
-                for (int cc = 0; cc < 4; ++cc) {
-                    if ((fc >> cc) & 1u) {
-                        ckeys[pos++] = key[it][cc];
-                        atomicAdd(&h[(key[it][cc] >> CORE_SHIFT1) & (CORE_NB1 - 1u)], 1u);
-                    }
-                }
-            }
-            run += total;
-        }
-        ngt = wave_sum(ngt);
-        if (lane == 0) { cnt_cand[(size_t)t * SUBS + wid] = run; cnt_gt[(size_t)t * SUBS + wid] = ngt; }
     }
     __syncthreads();
     flush_hist(h, CORE_NB1, hist + (size_t)cur_seg * H_STRIDE + H_L1);
