@@ -88,10 +88,9 @@ struct slimdp_ctx {
     // an announced explorer draw can run beside the caller's stream: pure integer work that fills the
     // arithmetic units the memory-bound kernels leave idle
     hipStream_t side = nullptr;
-    hipEvent_t ev_consumed = nullptr;      // main stream: the draw buffers of the last sample_explore have been read
+    hipEvent_t ev_consumed = nullptr;      // main stream: everything enqueued before a side-stream draw (readers of its buffers)
     hipEvent_t ev_drawn = nullptr;         // side stream: the announced draw is complete
     bool side_pending = false;             // a side draw was launched and the main stream has not waited for it yet
-    bool consumed_recorded = false;
     int device = 0, cus = 256;
     std::vector<uint64_t> seg_off;
     Tiling tl;
@@ -857,8 +856,6 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
                           false, off_tab, idx_tab, (uint32_t)M, nullptr, core_bits, short_list ? ctx->d_flags : nullptr,
                           ctx->e_chunk_sum);
     if (rc) return rc;
-    SLIMDP_HIP(ctx, hipEventRecord(ctx->ev_consumed, ctx->stream));      // the next announced draw may overwrite the buffers
-    ctx->consumed_recorded = true;
     return SLIMDP_OK;
 }
 
@@ -884,7 +881,9 @@ int slimdp_explore_hint(slimdp_ctx* ctx, const uint64_t* k_seg, uint32_t worker0
     }
     if (!narrow || M == 0) return SLIMDP_OK;  // nothing worth drawing ahead: slimdp_sample_explore draws itself
     // the draw starts now on the side stream, once the previous draw's buffers have been read
-    if (ctx->consumed_recorded) SLIMDP_HIP(ctx, hipStreamWaitEvent(ctx->side, ctx->ev_consumed, 0));
+    // (the event is recorded here, not after every slimdp_sample_explore: an event on a stream costs a gap between kernels)
+    SLIMDP_HIP(ctx, hipEventRecord(ctx->ev_consumed, ctx->stream));
+    SLIMDP_HIP(ctx, hipStreamWaitEvent(ctx->side, ctx->ev_consumed, 0));
     rc = init_states(ctx, ctx->e_draw_state, init, n_workers, 0, ctx->side);
     if (rc) return rc;
     // few waves keep the arithmetic units busy; the wave slots stay with the kernels of the main stream

@@ -708,9 +708,6 @@ __device__ __forceinline__ void core_classify(const uint32_t key[4][4], uint32_t
     if (lane == 0) { cnt_cand[(size_t)t * SUBS + wid] = run; cnt_gt[(size_t)t * SUBS + wid] = ngt; }
 }
 
-#ifndef CORE_BUILD_TILES
-#define CORE_BUILD_TILES 2
-#endif
 __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ S, const uint32_t* __restrict__ tile_start,
                                                       const uint32_t* __restrict__ tile_seg, uint32_t T,
                                                       const SegState* __restrict__ states, uint32_t* __restrict__ hist,
@@ -726,23 +723,18 @@ __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ 
     const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
     if (t0 >= t1) return;
     uint32_t cur_seg = tile_seg[t0];
-    // several tiles a turn: the scores of all of them are requested before any is worked on
-    constexpr int NT = CORE_BUILD_TILES;
-    for (uint32_t t = t0; t < t1; t += NT) {
-        uint32_t start[NT], len[NT];
-        uint32_t key[NT][4][4];
+    // two tiles a turn: the scores of both are requested before either is worked on
+    for (uint32_t t = t0; t < t1; t += 2) {
+        const bool two = t + 1 < t1;
+        const uint32_t startA = tile_start[t], lenA = tile_start[t + 1] - startA;
+        const uint32_t startB = two ? tile_start[t + 1] : 0u, lenB = two ? tile_start[t + 2] - startB : 0u;
+        uint32_t keyA[4][4], keyB[4][4];
+        core_load_keys(S, startA, lenA, wid, lane, vec_ok, keyA);
+        if (two) core_load_keys(S, startB, lenB, wid, lane, vec_ok, keyB);
 #pragma unroll
-        for (int x = 0; x < NT; ++x) {
-            start[x] = 0; len[x] = 0;
-            if (t + x < t1) {
-                start[x] = tile_start[t + x]; len[x] = tile_start[t + x + 1] - start[x];
-                core_load_keys(S, start[x], len[x], wid, lane, vec_ok, key[x]);
-            }
-        }
-#pragma unroll
-        for (int x = 0; x < NT; ++x) {
-            if (t + x >= t1) break;
-            const uint32_t tt = t + x;
+        for (int half = 0; half < 2; ++half) {
+            if (half == 1 && !two) break;
+            const uint32_t tt = t + half;
             const uint32_t seg = tile_seg[tt];
             if (seg != cur_seg) {
                 __syncthreads();
@@ -751,7 +743,8 @@ __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ 
                 cur_seg = seg;
             }
             const uint32_t b1 = states[seg].prefix, none = states[seg].none;
-            core_classify(key[x], tt, start[x], len[x], wid, lane, b1, none, h, gt_bits, cand_bits, cand_keys, cnt_gt, cnt_cand);
+            if (half == 0) core_classify(keyA, tt, startA, lenA, wid, lane, b1, none, h, gt_bits, cand_bits, cand_keys, cnt_gt, cnt_cand);
+            else core_classify(keyB, tt, startB, lenB, wid, lane, b1, none, h, gt_bits, cand_bits, cand_keys, cnt_gt, cnt_cand);
         }
     }
     __syncthreads();
