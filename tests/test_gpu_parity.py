@@ -288,6 +288,35 @@ def test_speculative_pack_over_iterations(hint):
         sd.close()
 
 
+@pytest.mark.parametrize("W", [1, 2, 3, 16])
+def test_speculative_pack_worker_counts(W):
+    """Entry widths of 1, 2 and 16 values (W = 3 is never captured: the pack then gathers); several tiles per block."""
+    wl = workloads.TINY.scaled(4_500_007, W=W)
+    sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
+    sd.set_option("speculative_pack", 1)
+    k, m = wl.k, wl.m
+    w_h = wl.weights()
+    w = to_dev(w_h)
+    for t in range(2):
+        g_h = wl.gradients(t)
+        g = [to_dev(x) for x in g_h]
+        sd.explore_hint([k], t, [m], 0, W)
+        S = sd.score(w, g, wl.c)
+        core_idx, core_bits, core_off, epoch = sd.select_core(S, [k], reuse_histogram=True)
+        expl_idx, expl_off = sd.sample_explore(core_bits, [k], t, [m], 0, W)
+        core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)
+        sd.synchronize()
+        core_o = oracle.select_core(oracle.score(w_h, g_h, wl.c), k)
+        assert np.array_equal(u32(core_idx), core_o), t
+        for q in range(W):
+            ei_o = oracle.sample_explore(wl.n, core_o, workloads.EXPLORE_SEED, t, q, m)
+            assert np.array_equal(u32(expl_idx[q]), ei_o), (t, q)
+            cv_o, ev_o = oracle.pack(g_h[q], core_o, ei_o)
+            assert np.array_equal(f32bits(core_val[q].cpu().numpy()), f32bits(cv_o)), (t, q)
+            assert np.array_equal(f32bits(expl_val[q].cpu().numpy()), f32bits(ev_o)), (t, q)
+    sd.close()
+
+
 def test_speculative_pack_really_uses_the_captured_values():
     """White-box probe: zero the update vectors after the selection.  Core values of captured tiles must still be
     the original ones (they can only come from the capture); from the third pack on nothing is captured any more
