@@ -119,6 +119,7 @@ struct slimdp_ctx {
     const float* hist_score = nullptr;
     int64_t opt_force_fallback = 0;
     int64_t opt_per_tile_tail = 0;
+    int64_t opt_strided = 1;               // flat model: persistent blocks take every P-th tile
     int64_t opt_side_blocks = 2;           // blocks per compute unit of a side-stream draw
     int64_t opt_hint_mode = 0;             // 0: the announced draw rides inside slimdp_score; 1: side stream
     // speculative packing: its own allocation, made when the option is switched on
@@ -505,6 +506,7 @@ int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value)
     if (!ctx || !name) return SLIMDP_ERR_INVALID_ARG;
     if (strcmp(name, "explore_force_fallback") == 0) { ctx->opt_force_fallback = value; return SLIMDP_OK; }
     if (strcmp(name, "explore_per_tile_tail") == 0) { ctx->opt_per_tile_tail = value; return SLIMDP_OK; }
+    if (strcmp(name, "strided_tiles") == 0 && (value == 0 || value == 1)) { ctx->opt_strided = value; return SLIMDP_OK; }
     if (strcmp(name, "side_blocks") == 0 && value >= 1 && value <= 8) { ctx->opt_side_blocks = value; return SLIMDP_OK; }
     if (strcmp(name, "explore_hint_mode") == 0 && (value == 0 || value == 1)) { ctx->opt_hint_mode = value; return SLIMDP_OK; }
     if (strcmp(name, "pack_nbuf") == 0 && (value == 1 || value == 2)) { ctx->opt_pack_nbuf = value; return SLIMDP_OK; }
@@ -611,7 +613,8 @@ static int score_impl(slimdp_ctx* ctx, const float* w, const float* const* g, ui
     const dim3 grid(P), block(BLOCK);
 #define LAUNCH_SCORE_P(WT, PRE, SPEC, DENSE)                                                                          \
     hipLaunchKernelGGL((k_score<WT, PRE, SPEC, DENSE>), grid, block, 0, ctx->stream, w, gt, (int)W, c, score,         \
-                       ctx->d_tile_start, ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok, pre, sa, w_new, lr)
+                       ctx->d_tile_start, ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok, pre, sa, w_new, lr,                 \
+                       (int)(ctx->n_seg == 1 && ctx->opt_strided))
 #define LAUNCH_SCORE_S(WT, SPEC, DENSE)                                                                               \
     do {                                                                                                              \
         if (presample && pairs) LAUNCH_SCORE_P(WT, 2, SPEC, DENSE);                                                   \
@@ -702,7 +705,7 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
     SLIMDP_LAUNCHED(ctx, "k_threshold(0)");
     hipLaunchKernelGGL(k_core_build, dim3(P), dim3(BLOCK), 0, ctx->stream, score, ctx->d_tile_start, ctx->d_tile_seg, T,
                        ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys, ctx->c_cnt_gt,
-                       ctx->c_cnt_cand, (int)aligned16(score));
+                       ctx->c_cnt_cand, (int)aligned16(score), (int)(S == 1 && ctx->opt_strided));
     SLIMDP_LAUNCHED(ctx, "k_core_build");
     MutPtrTab off_tab = make_tab<MutPtrTab, uint32_t*>(&core_off, 1);
     MutPtrTab idx_tab = make_tab<MutPtrTab, uint32_t*>(&core_idx, 1);

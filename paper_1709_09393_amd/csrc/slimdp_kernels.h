@@ -327,7 +327,7 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                                                  float* __restrict__ S, const uint32_t* __restrict__ tile_start,
                                                  const uint32_t* __restrict__ tile_seg, uint32_t T,
                                                  uint32_t* __restrict__ hist, int vec_ok, PreArgs pre, SpecArgs spec,
-                                                 float* __restrict__ w_new, float lr)
+                                                 float* __restrict__ w_new, float lr, int strided)
 {
     static_assert(!SPEC || WT != 0, "capture needs the update values in registers");
     static_assert(!(SPEC && DENSE), "a dense update is never followed by a pack of the same updates");
@@ -340,13 +340,18 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
     const uint32_t lane16 = lane * 16u;      // byte offset of the lane's float4: a 32-bit offset beside a scalar base
     for (uint32_t b = threadIdx.x; b < NB; b += BLOCK) h[b] = 0;
     __syncthreads();
-    const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
-    const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
+    // A block's tiles: a contiguous range (few segment changes, each of which flushes the histogram), or - flat model,
+    // strided != 0 - every gridDim.x-th tile, so that at any moment the whole chip streams through one window of each
+    // array instead of a thousand separate places (fewer DRAM rows open at a time).
+    uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
+    uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
+    uint32_t tstep = 1;
+    if (strided) { t0 = blockIdx.x; t1 = T; tstep = gridDim.x; }
     if (t0 >= t1) return;
     uint32_t cur_seg = tile_seg[t0];
     // Every wave owns sub-tile `wid` of each tile and runs through the block's tiles on its
     // own; the block only meets at a segment change and at the end (histogram flush).
-    for (uint32_t t = t0; t < t1; ++t) {
+    for (uint32_t t = t0; t < t1; t += tstep) {
         const uint32_t seg = tile_seg[t];
         if (seg != cur_seg) {
             __syncthreads();
@@ -713,28 +718,32 @@ __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ 
                                                       const SegState* __restrict__ states, uint32_t* __restrict__ hist,
                                                       uint32_t* __restrict__ gt_bits, uint32_t* __restrict__ cand_bits,
                                                       uint32_t* __restrict__ cand_keys, uint32_t* __restrict__ cnt_gt,
-                                                      uint32_t* __restrict__ cnt_cand, int vec_ok)
+                                                      uint32_t* __restrict__ cnt_cand, int vec_ok, int strided)
 {
     __shared__ uint32_t h[CORE_NB1];
     const uint32_t lane = lane_id(), wid = threadIdx.x >> 6;
     for (uint32_t b = threadIdx.x; b < CORE_NB1; b += BLOCK) h[b] = 0;
     __syncthreads();
-    const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
-    const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
+    // a contiguous range of tiles, or (flat model) every gridDim.x-th tile: see k_score
+    uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
+    uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
+    uint32_t tstep = 1;
+    if (strided) { t0 = blockIdx.x; t1 = T; tstep = gridDim.x; }
     if (t0 >= t1) return;
     uint32_t cur_seg = tile_seg[t0];
     // two tiles a turn: the scores of both are requested before either is worked on
-    for (uint32_t t = t0; t < t1; t += 2) {
-        const bool two = t + 1 < t1;
+    for (uint32_t t = t0; t < t1; t += 2 * tstep) {
+        const uint32_t tB = t + tstep;
+        const bool two = tB < t1;
         const uint32_t startA = tile_start[t], lenA = tile_start[t + 1] - startA;
-        const uint32_t startB = two ? tile_start[t + 1] : 0u, lenB = two ? tile_start[t + 2] - startB : 0u;
+        const uint32_t startB = two ? tile_start[tB] : 0u, lenB = two ? tile_start[tB + 1] - startB : 0u;
         uint32_t keyA[4][4], keyB[4][4];
         core_load_keys(S, startA, lenA, wid, lane, vec_ok, keyA);
         if (two) core_load_keys(S, startB, lenB, wid, lane, vec_ok, keyB);
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             if (half == 1 && !two) break;
-            const uint32_t tt = t + half;
+            const uint32_t tt = half ? tB : t;
             const uint32_t seg = tile_seg[tt];
             if (seg != cur_seg) {
                 __syncthreads();
