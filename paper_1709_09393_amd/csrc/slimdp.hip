@@ -280,13 +280,13 @@ int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* his
         SLIMDP_LAUNCHED(c, "k_list_hist(1)");
     }
     hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 1, (uint32_t)H_L1, S, 0, c->d_flags,
-                       nullptr, gate ? 2 : 0, SpecTau{nullptr, nullptr, nullptr});
+                       nullptr, gate ? 1 : 0, SpecTau{nullptr, nullptr, nullptr});
     SLIMDP_LAUNCHED(c, "k_threshold(1)");
     hipLaunchKernelGGL((k_list_hist<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg,
                        T, S, nbatch, st, hist, (uint32_t)H_L2, 2, cand_keys, cnt_cand, keys_stride, gate);
     SLIMDP_LAUNCHED(c, "k_list_hist(2)");
     hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 2, (uint32_t)H_L2, S, 0, c->d_flags,
-                       nullptr, gate ? 2 : 0, sp);
+                       nullptr, gate ? 1 : 0, sp);
     SLIMDP_LAUNCHED(c, "k_threshold(2)");
     hipLaunchKernelGGL((k_count<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg, T, S,
                        nbatch, st, cand_keys, cnt_cand, cnt_gt, keys_stride, cnt_sel, cnt_tie, gate);
@@ -771,48 +771,28 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
     const PhiloxKey pk{(uint32_t)ctx->seed, (uint32_t)(ctx->seed >> 32), (uint32_t)iteration, (uint32_t)(iteration >> 32)};
     MutPtrTab off_tab = make_tab<MutPtrTab>(expl_off, B);
     MutPtrTab idx_tab = make_tab<MutPtrTab>(expl_idx, B);
-#define LAUNCH_DRAW(PAIRS, WIDE)                                                                                         \
+#define LAUNCH_DRAW(PAIRS)                                                                                               \
     do {                                                                                                                 \
         if (ctx->tl.quad_aligned)                                                                                        \
             hipLaunchKernelGGL((k_explore_keys<1, PAIRS>), dim3(P, B), dim3(BLOCK), 0, ctx->stream, ctx->d_tile_start,   \
                                ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_sure_bits, ctx->e_cand_bits,                  \
-                               ctx->e_cand_keys, ctx->e_cnt_cand, ctx->keys_stride, worker0, pk, WIDE, ctx->d_flags);    \
+                               ctx->e_cand_keys, ctx->e_cnt_cand, ctx->keys_stride, worker0, pk);                        \
         else                                                                                                             \
             hipLaunchKernelGGL((k_explore_keys<0, PAIRS>), dim3(P, B), dim3(BLOCK), 0, ctx->stream, ctx->d_tile_start,   \
                                ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_sure_bits, ctx->e_cand_bits,                  \
-                               ctx->e_cand_keys, ctx->e_cnt_cand, ctx->keys_stride, worker0, pk, WIDE, ctx->d_flags);    \
+                               ctx->e_cand_keys, ctx->e_cnt_cand, ctx->keys_stride, worker0, pk);                        \
         SLIMDP_LAUNCHED(ctx, "k_explore_keys");                                                                          \
-    } while (0)
-#define LAUNCH_FILTER(WIDE)                                                                                              \
-    do {                                                                                                                 \
-        hipLaunchKernelGGL(k_explore_filter, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->n,                 \
-                           ctx->d_tile_start, ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_sure_bits,        \
-                           ctx->e_cnt_gt, ctx->e_cand_bits, ctx->e_cand_keys, ctx->e_cnt_cand, ctx->keys_stride,         \
-                           n_words, WIDE, ctx->d_flags);                                                                 \
-        SLIMDP_LAUNCHED(ctx, "k_explore_filter");                                                                        \
-        if (!(WIDE)) {                                                                                                   \
-            hipLaunchKernelGGL(k_seg_sum, dim3(S, B), dim3(1024), 0, ctx->stream, ctx->e_cnt_gt, (uint32_t)SUBS,         \
-                               ctx->d_seg_first_tile, T, S, ctx->e_nsure, ctx->d_flags, 0);                              \
-            SLIMDP_LAUNCHED(ctx, "k_seg_sum");                                                                           \
-        }                                                                                                                \
-    } while (0)
-#define LAUNCH_T0(MODE, GATE)                                                                                            \
-    do {                                                                                                                 \
-        hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, ctx->stream, ctx->e_state, ctx->e_hist, 0,             \
-                           (uint32_t)((MODE) == 2 ? H_L0FB : H_L0), S, MODE, ctx->d_flags, ctx->e_nsure, GATE,           \
-                           SpecTau{nullptr, nullptr, nullptr});                                                          \
-        SLIMDP_LAUNCHED(ctx, "k_threshold(0)");                                                                          \
     } while (0)
     if (short_list) {
         // the few candidates go through one unordered list; any irregularity raises the flag that
-        // switches these kernels off and the wide-bound per-tile rerun below on
+        // switches these kernels off and the exact rerun below on
         constexpr int SBPW = 8;
-        if (!cached) LAUNCH_DRAW(1, 0);
+        if (!cached) LAUNCH_DRAW(1);
         hipLaunchKernelGGL(k_sure_count<SBPW>, dim3((T + 3) / 4, (B + SBPW - 1) / SBPW), dim3(BLOCK), 0, ctx->stream, core_bits,
                            n_words, ctx->n, ctx->d_tile_start, ctx->d_tile_seg, T, S, B, ctx->e_sure_bits, ctx->e_cnt_sel);
         SLIMDP_LAUNCHED(ctx, "k_sure_count");
         hipLaunchKernelGGL(k_seg_sum, dim3(S, B), dim3(1024), 0, ctx->stream, ctx->e_cnt_sel, 1u, ctx->d_seg_first_tile, T, S,
-                           ctx->e_nsure, ctx->d_flags, 0);
+                           ctx->e_nsure);
         SLIMDP_LAUNCHED(ctx, "k_seg_sum");
         hipLaunchKernelGGL(k_cand_gather, dim3((uint32_t)(((uint64_t)B * T + 1023) / 1024)), dim3(1024), 0, ctx->stream,
                            core_bits, ctx->n, ctx->d_tile_start, ctx->d_tile_seg, T, S, B, ctx->e_cand_keys, ctx->keys_stride,
@@ -843,22 +823,29 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
                            ctx->n_chunks, off_tab, idx_tab, (uint32_t)M, ctx->d_flags);
         SLIMDP_LAUNCHED(ctx, "k_emit_bits");
     } else {
-        if (!cached) LAUNCH_DRAW(0, 0);
-        LAUNCH_FILTER(0);
-        LAUNCH_T0(1, 0);
+        // zones that are not narrow: the per-tile tail that the core selection uses
+        if (!cached) LAUNCH_DRAW(0);
+        hipLaunchKernelGGL(k_explore_filter, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->n, ctx->d_tile_start,
+                           ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_sure_bits, ctx->e_cnt_gt, ctx->e_cand_bits,
+                           ctx->e_cand_keys, ctx->e_cnt_cand, ctx->keys_stride, n_words);
+        SLIMDP_LAUNCHED(ctx, "k_explore_filter");
+        hipLaunchKernelGGL(k_seg_sum, dim3(S, B), dim3(1024), 0, ctx->stream, ctx->e_cnt_gt, (uint32_t)SUBS, ctx->d_seg_first_tile,
+                           T, S, ctx->e_nsure);
+        SLIMDP_LAUNCHED(ctx, "k_seg_sum");
+        hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, ctx->stream, ctx->e_state, ctx->e_hist, 0, (uint32_t)H_L0, S, 1,
+                           ctx->d_flags, ctx->e_nsure, 0, SpecTau{nullptr, nullptr, nullptr});
+        SLIMDP_LAUNCHED(ctx, "k_threshold(0)");
+        rc = finish_selection<EXPL_KPL, 4>(ctx, B, ctx->e_state, ctx->e_hist, ctx->e_sure_bits, ctx->e_cand_bits,
+                              ctx->e_cand_keys, ctx->e_cnt_gt, ctx->e_cnt_cand, ctx->e_cnt_sel, ctx->e_cnt_tie, ctx->e_tie_pre,
+                              ctx->keys_stride, false, off_tab, idx_tab, (uint32_t)M, nullptr, core_bits, ctx->d_flags,
+                              ctx->e_chunk_sum);
+        if (rc) return rc;
     }
-    // every word a candidate, no sure zone: runs only if the flag went up
-    LAUNCH_DRAW(0, 1);
-    LAUNCH_FILTER(1);
-    LAUNCH_T0(2, 2);
 #undef LAUNCH_DRAW
-#undef LAUNCH_FILTER
-#undef LAUNCH_T0
-    rc = finish_selection<EXPL_KPL, 4>(ctx, B, ctx->e_state, ctx->e_hist, ctx->e_sure_bits, ctx->e_cand_bits, ctx->e_cand_keys,
-                          ctx->e_cnt_gt, ctx->e_cnt_cand, ctx->e_cnt_sel, ctx->e_cnt_tie, ctx->e_tie_pre, ctx->keys_stride,
-                          false, off_tab, idx_tab, (uint32_t)M, nullptr, core_bits, short_list ? ctx->d_flags : nullptr,
-                          ctx->e_chunk_sum);
-    if (rc) return rc;
+    // zones missed (flag up): the whole request again, exactly, from the definition; idle otherwise
+    hipLaunchKernelGGL(k_explore_exact, dim3(1, B), dim3(1024), 0, ctx->stream, core_bits, ctx->n, ctx->d_tile_start,
+                       ctx->d_seg_first_tile, T, S, ctx->e_state, worker0, pk, idx_tab, off_tab, (uint32_t)M, ctx->d_flags);
+    SLIMDP_LAUNCHED(ctx, "k_explore_exact");
     return SLIMDP_OK;
 }
 
@@ -896,7 +883,7 @@ int slimdp_explore_hint(slimdp_ctx* ctx, const uint64_t* k_seg, uint32_t worker0
 #define LAUNCH_SIDE_DRAW(FAST, PAIRS)                                                                                   \
     hipLaunchKernelGGL((k_explore_keys<FAST, PAIRS>), grid, block, 0, ctx->side, ctx->d_tile_start, ctx->d_tile_seg,    \
                        ctx->T, ctx->n_seg, ctx->e_draw_state, ctx->e_sure_bits, ctx->e_cand_bits, ctx->e_cand_keys,     \
-                       ctx->e_cnt_cand, ctx->keys_stride, worker0, pk, 0, ctx->d_flags)
+                       ctx->e_cnt_cand, ctx->keys_stride, worker0, pk)
     if (ctx->tl.quad_aligned) { if (short_list) LAUNCH_SIDE_DRAW(1, 1); else LAUNCH_SIDE_DRAW(1, 0); }
     else { if (short_list) LAUNCH_SIDE_DRAW(0, 1); else LAUNCH_SIDE_DRAW(0, 0); }
 #undef LAUNCH_SIDE_DRAW

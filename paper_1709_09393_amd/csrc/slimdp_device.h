@@ -15,9 +15,8 @@ constexpr int MAXW = SLIMDP_MAX_WORKERS;
 constexpr int BLOCK = 256;                        // threads per block in the tile kernels
 constexpr int EPT = TILE / BLOCK;                 // elements per thread per tile (16)
 
-// Histogram storage per (batch, segment): level 0, level 0 of the wide-bound rerun,
-// level 1, level 2.
-constexpr uint32_t H_L0 = 0, H_L0FB = 8192, H_L1 = 16384, H_L2 = 20480, H_STRIDE = 24576;
+// Histogram storage per (batch, segment): level 0, level 1, level 2.
+constexpr uint32_t H_L0 = 0, H_L1 = 8192, H_L2 = 12288, H_STRIDE = 16384;
 
 // Core ranking key = raw bits of the score: 13 + 12 + 7 bits.
 constexpr uint32_t CORE_SHIFT0 = 19, CORE_NB0 = 8192, CORE_SHIFT1 = 7, CORE_NB1 = 4096, CORE_NB2 = 128;

@@ -530,11 +530,10 @@ __global__ __launch_bounds__(BLOCK) void k_core_hist0(const float* __restrict__ 
 // ---------------------------------------------------------------------------------------
 // Threshold step of one radix level: walk the bins from the largest digit down until
 // `need` keys are covered.  grid (n_seg, nbatch), 256 threads.
-// mode 0: plain.  mode 1: explorer level 0 with the narrow bound; too few candidates raise
-// the rerun flag.  mode 2: explorer level 0 after the wide-bound rerun (only if flagged).
-// gate 1: only while the rerun flag is down; gate 2: only once it is up; 0: always.
-// The kernels of the per-tile tail take the flag word as `gate` (nullptr: always run) and
-// return at once while it is down: they then serve the rerun after the short-list path.
+// mode 0: plain.  mode 1: explorer level 0 with zones: a miss on either side raises the
+// rerun flag (flags[0]).  gate != 0: return at once if the flag is already up (the exact
+// rerun k_explore_exact follows and overwrites everything); the kernels of the per-tile tail
+// take the flag word as `gate` the same way (nullptr: always run).
 // ---------------------------------------------------------------------------------------
 // At the last level of a core selection with speculative packing on (st.next != nullptr):
 // fail[seg] tells whether the threshold fell below what the scoring pass captured (cur), and
@@ -553,29 +552,17 @@ __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states
     if (gate) {          // other blocks of this launch may raise the flag: one read per block
         if (threadIdx.x == 0) sh_bcast[0] = flags[0];
         __syncthreads();
-        if ((sh_bcast[0] != 0) != (gate == 2)) return;
+        if (sh_bcast[0] != 0) return;
     }
     const uint32_t seg = blockIdx.x, b = blockIdx.y;
     SegState* st = &states[(size_t)b * n_seg + seg];
     const uint32_t* hp = hist + ((size_t)b * n_seg + seg) * H_STRIDE + hist_off;
-    if (mode == 2) {
-        if (flags[0] == 0) return;
-        if (threadIdx.x == 0) {          // wide bound: every non-core parameter is a candidate
-            st->bound_m1 = 0xFFFFFFFFu;
-            st->shift[0] = 20; st->nbins[0] = 4096;
-            st->shift[1] = 8;  st->nbins[1] = 4096;
-            st->shift[2] = 0;  st->nbins[2] = 256;
-            st->need = st->need0; st->prefix = 0; st->none = (st->need0 == 0) ? 1u : 0u;
-            st->has_gt = 0;
-        }
-        __syncthreads();
-    }
     if (mode == 1 && st->has_gt) {
         // the certainly taken ones (word below the sure bound, outside the core) come off the demand
         const uint32_t ns = nsure[(size_t)b * n_seg + seg];
         const uint32_t n0 = st->need0;
         __syncthreads();
-        if (ns > n0) {                        // the sure zone alone is already too large: rerun with the wide bound
+        if (ns > n0) {                        // the sure zone alone is already too large: exact rerun
             if (threadIdx.x == 0) atomicOr(&flags[0], 1u);
             return;
         }
@@ -601,7 +588,7 @@ __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states
     const uint32_t excl = block_excl_scan<4>(sum, wtot, total);
     if (total < need) {
         if (threadIdx.x == 0) {
-            if (mode == 1) atomicOr(&flags[0], 1u);                    // rerun with the wide bound
+            if (mode == 1) atomicOr(&flags[0], 1u);                    // too few candidates: exact rerun
             else { atomicOr(&flags[1], 2u); st->none = 1; st->need = 0; st->tau = NONE; st->quota = 0; }
         }
         return;
@@ -761,19 +748,16 @@ __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ 
 }
 
 // Stand-alone draw over every (worker, tile); each wave owns one sub-tile of the block's
-// tiles.  grid (blocks, n_workers); wide != 0: the rerun with every word a candidate and no
-// sure zone, a no-op unless flagged.
+// tiles.  grid (blocks, n_workers).
 template <int FAST, int PAIRS>
 __global__ __launch_bounds__(BLOCK) void k_explore_keys(const uint32_t* __restrict__ tile_start,
                                                         const uint32_t* __restrict__ tile_seg, uint32_t T,
                                                         uint32_t n_seg, const SegState* __restrict__ states,
                                                         uint32_t* __restrict__ sure_bits, uint32_t* __restrict__ cand_bits,
                                                         uint32_t* __restrict__ cand_keys, uint32_t* __restrict__ cnt_cand,
-                                                        uint64_t keys_stride, uint32_t worker0, PhiloxKey pk, int wide,
-                                                        const uint32_t* __restrict__ flags)
+                                                        uint64_t keys_stride, uint32_t worker0, PhiloxKey pk)
 {
     __shared__ uint32_t wa[FAST ? 1 : 4][SUB_WORDS], wb[FAST ? 1 : 4][SUB_WORDS], wp[FAST ? 1 : 4][SUB_WORDS];
-    if (wide && flags[0] == 0) return;
     const uint32_t b = blockIdx.y, worker = worker0 + b, wid = threadIdx.x >> 6;
     const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
     const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
@@ -785,8 +769,8 @@ __global__ __launch_bounds__(BLOCK) void k_explore_keys(const uint32_t* __restri
     for (uint32_t t = t0; t < t1; ++t) {
         const uint32_t seg = (n_seg == 1) ? 0u : tile_seg[t];
         const SegState* st = &states[(size_t)b * n_seg + seg];
-        const uint32_t bound_m1 = wide ? 0xFFFFFFFFu : st->bound_m1;
-        const uint32_t sure_m1 = st->sure_m1, has_sure = wide ? 0u : st->has_gt;
+        const uint32_t bound_m1 = st->bound_m1;
+        const uint32_t sure_m1 = st->sure_m1, has_sure = st->has_gt;
         const uint32_t skip = st->need0 == 0;
         const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
         if (FAST)
@@ -853,8 +837,7 @@ __device__ __forceinline__ void bitmap_window(const uint32_t* __restrict__ bits,
 //   candidate zone: candidates inside the core are dropped (bitmap bit cleared, the sub-tile's
 //     key list closed up in place, its count lowered); the remaining keys feed the level-0
 //     histogram.
-// grid (blocks, n_workers), persistent so that the histogram stays in LDS.  wide != 0: after
-// the wide-bound rerun (no sure zone, 20-bit shift), a no-op unless flagged.
+// grid (blocks, n_workers), persistent so that the histogram stays in LDS.
 __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __restrict__ core_bits, uint64_t n,
                                                           const uint32_t* __restrict__ tile_start,
                                                           const uint32_t* __restrict__ tile_seg, uint32_t T,
@@ -863,11 +846,10 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
                                                           uint32_t* __restrict__ cnt_gt,
                                                           uint32_t* __restrict__ cand_bits, uint32_t* __restrict__ cand_keys,
                                                           uint32_t* __restrict__ cnt_cand, uint64_t keys_stride,
-                                                          uint32_t n_words, int wide, const uint32_t* __restrict__ flags)
+                                                          uint32_t n_words)
 {
     __shared__ uint32_t h[4096];
     __shared__ uint32_t kl[4][SUB];
-    if (wide && flags[0] == 0) return;
     const uint32_t b = blockIdx.y, lane = lane_id(), wid = threadIdx.x >> 6;
     for (uint32_t x = threadIdx.x; x < 4096; x += BLOCK) h[x] = 0;
     __syncthreads();
@@ -877,7 +859,7 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
     // one segment per block range: histogram in LDS; otherwise straight to global memory
     const uint32_t seg_first = (n_seg == 1) ? 0u : tile_seg[t0];
     const bool one_seg = (n_seg == 1) || seg_first == tile_seg[t1 - 1];
-    const uint32_t hist_off = wide ? H_L0FB : H_L0;
+    const uint32_t hist_off = H_L0;
     uint32_t* klw = kl[wid];
     for (uint32_t t = t0 + wid; t < t1; t += 4) {
         const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
@@ -889,7 +871,7 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
         const uint32_t cnt = cnt_cand[bt * SUBS + (lane >> 4)];
         uint32_t kw[2];
         bitmap_window(core_bits, n_words, tr.start + lane * 64u, kw);
-        const uint32_t need0 = st->need0, shift0 = wide ? 20u : st->shift[0], has_sure = wide ? 0u : st->has_gt;
+        const uint32_t need0 = st->need0, shift0 = st->shift[0], has_sure = st->has_gt;
         {
             uint32_t g = (has_sure && need0) ? __popc(s2.x & ~kw[0]) + __popc(s2.y & ~kw[1]) : 0u;
             g += __shfl_xor(g, 1, 64); g += __shfl_xor(g, 2, 64); g += __shfl_xor(g, 4, 64); g += __shfl_xor(g, 8, 64);
@@ -941,6 +923,115 @@ __global__ __launch_bounds__(BLOCK) void k_explore_filter(const uint32_t* __rest
 }
 
 // =======================================================================================
+// Explorer, exact rerun.  When the zones of a draw missed (flags[0] raised; once in about
+// 10^9 draws, or forced by a test switch) this kernel redoes the whole request from the
+// definition, slowly and with no assumption: per worker one block walks every segment,
+// finds the need-th smallest Philox word among the parameters outside the core by a
+// three-pass radix descent over ALL of them (11 + 11 + 10 bits, words recomputed in every
+// pass), then emits tile by tile in index order, ties at the threshold word going to the
+// lowest indices.  grid (1, n_workers), 1024 threads; returns at once while the flag is down.
+// =======================================================================================
+__device__ __forceinline__ uint32_t explore_word(uint32_t i, uint32_t worker, PhiloxKey pk)
+{
+    uint32_t r[4];
+    philox4x32_10(i >> 2, worker, pk.it_lo, pk.it_hi, pk.seed_lo, pk.seed_hi, r);
+    const uint32_t c = i & 3u;
+    return c == 0 ? r[0] : c == 1 ? r[1] : c == 2 ? r[2] : r[3];
+}
+
+__global__ __launch_bounds__(1024) void k_explore_exact(const uint32_t* __restrict__ core_bits, uint64_t n,
+                                                        const uint32_t* __restrict__ tile_start,
+                                                        const uint32_t* __restrict__ seg_first_tile, uint32_t T, uint32_t n_seg,
+                                                        const SegState* __restrict__ states, uint32_t worker0, PhiloxKey pk,
+                                                        MutPtrTab out_idx, MutPtrTab out_off, uint32_t expected,
+                                                        uint32_t* __restrict__ flags)
+{
+    constexpr uint32_t NBIN = 2048;
+    __shared__ uint32_t h[NBIN];
+    __shared__ uint32_t wtot[16];
+    __shared__ uint32_t sh[4];
+    if (flags[0] == 0) return;                       // nobody raises the flag while this kernel runs
+    const uint32_t b = blockIdx.y, worker = worker0 + b, tid = threadIdx.x;
+    uint32_t* out = static_cast<uint32_t*>(out_idx.p[b]);
+    uint32_t* off = static_cast<uint32_t*>(out_off.p[b]);
+    uint32_t run = 0;                                // indices emitted so far (uniform)
+    for (uint32_t seg = 0; seg < n_seg; ++seg) {
+        const uint32_t f0 = seg_first_tile[seg], f1 = seg_first_tile[seg + 1];
+        uint32_t need = states[(size_t)b * n_seg + seg].need0;
+        // ---- the need-th smallest word: descent over bits 31..21, 20..10, 9..0
+        uint32_t prefix = 0, short_of = 0;
+        const uint32_t shifts[3] = {21u, 10u, 0u}, nbits[3] = {11u, 11u, 10u};
+        for (int p = 0; p < 3 && need != 0 && !short_of; ++p) {
+            for (uint32_t x = tid; x < NBIN; x += 1024) h[x] = 0;
+            __syncthreads();
+            const uint32_t hi_shift = shifts[p] + nbits[p];        // bits above this pass's digit
+            for (uint32_t t = f0; t < f1; ++t) {
+                const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
+                for (uint32_t e = tid; e < len; e += 1024) {
+                    const uint32_t i = start + e;
+                    if ((core_bits[i >> 5] >> (i & 31u)) & 1u) continue;
+                    const uint32_t r = explore_word(i, worker, pk);
+                    if (hi_shift < 32u && (r >> hi_shift) != prefix) continue;
+                    atomicAdd(&h[(r >> shifts[p]) & ((1u << nbits[p]) - 1u)], 1u);
+                }
+            }
+            __syncthreads();
+            // the bin that holds the need-th smallest: two bins per thread, ascending
+            const uint32_t c0 = h[2 * tid], c1 = h[2 * tid + 1];
+            uint32_t total;
+            const uint32_t excl = block_excl_scan<16>(c0 + c1, wtot, total);
+            if (tid == 0) sh[2] = (total < need) ? 1u : 0u;
+            if (excl < need && need <= excl + c0) { sh[0] = 2 * tid; sh[1] = need - excl; }
+            else if (excl + c0 < need && need <= excl + c0 + c1) { sh[0] = 2 * tid + 1; sh[1] = need - excl - c0; }
+            __syncthreads();
+            if (sh[2]) { short_of = 1; if (tid == 0) atomicOr(&flags[1], 2u); }     // fewer eligible parameters than requested
+            else { prefix = (prefix << nbits[p]) | sh[0]; need = sh[1]; }
+            __syncthreads();
+        }
+        // words below tau are taken, of the words equal to tau the first `need` in index order
+        const uint32_t tau = short_of ? 0xFFFFFFFFu : prefix;
+        const uint32_t take_all = short_of;
+        const uint32_t want = states[(size_t)b * n_seg + seg].need0;
+        uint32_t ties_seen = 0;                      // uniform
+        // ---- ordered emission, tile by tile (four consecutive parameters per thread)
+        for (uint32_t t = f0; t < f1; ++t) {
+            const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
+            uint32_t sel = 0, tie = 0;
+            if (want != 0) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint32_t e = 4u * tid + c;
+                    if (e >= len) continue;
+                    const uint32_t i = start + e;
+                    if ((core_bits[i >> 5] >> (i & 31u)) & 1u) continue;
+                    const uint32_t r = explore_word(i, worker, pk);
+                    if (take_all || r < tau) sel |= 1u << c;
+                    else if (r == tau) tie |= 1u << c;
+                }
+            }
+            uint32_t tie_total;
+            const uint32_t tie_excl = block_excl_scan<16>(__popc(tie), wtot, tie_total);
+            uint32_t rank = ties_seen + tie_excl;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if ((tie >> c) & 1u) { if (rank < need) sel |= 1u << c; ++rank; }
+            ties_seen += tie_total;
+            uint32_t sel_total;
+            uint32_t o = run + block_excl_scan<16>(__popc(sel), wtot, sel_total);
+            if (tid == 0) off[t] = run;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if ((sel >> c) & 1u) { if (o < expected) out[o] = start + 4u * tid + c; ++o; }
+            run += sel_total;
+        }
+    }
+    if (tid == 0) {
+        off[T] = run;
+        if (run != expected) atomicOr(&flags[1], 1u);
+    }
+}
+
+// =======================================================================================
 // Explorer, short-list path (every segment's candidate zone is narrow, draw with PAIRS = 1).
 // The few candidates outside the core are collected into one unordered list; the radix
 // descent, the decision against tau and the tie ranks run over that list; the chosen
@@ -985,10 +1076,9 @@ __global__ __launch_bounds__(BLOCK) void k_sure_count(const uint32_t* __restrict
 // grid (n_seg, nbatch), 1024 threads.
 __global__ __launch_bounds__(1024) void k_seg_sum(const uint32_t* __restrict__ counts, uint32_t per,
                                                   const uint32_t* __restrict__ seg_first_tile, uint32_t T, uint32_t n_seg,
-                                                  uint32_t* __restrict__ nsure, const uint32_t* __restrict__ flags, int wide)
+                                                  uint32_t* __restrict__ nsure)
 {
     __shared__ uint32_t wtot[16];
-    if (wide && flags[0] == 0) return;
     const uint32_t seg = blockIdx.x, b = blockIdx.y;
     const size_t x0 = ((size_t)b * T + seg_first_tile[seg]) * per, x1 = ((size_t)b * T + seg_first_tile[seg + 1]) * per;
     uint32_t sum = 0;
@@ -1253,7 +1343,7 @@ __global__ __launch_bounds__(BLOCK) void k_list_hist(uint64_t n, const uint32_t*
                                                      const uint32_t* __restrict__ gate)
 {
     const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b0 = blockIdx.y * BPW, lane = lane_id();
-    if (t >= T || (gate && gate[0] == 0)) return;
+    if (t >= T || (gate && gate[0] != 0)) return;
     const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
     // one wave serves the tile for BPW batches: all their loads are requested before any is used
     uint32_t kv[BPW][KPL], cnt[BPW];
@@ -1316,7 +1406,7 @@ __global__ __launch_bounds__(BLOCK) void k_count(uint64_t n, const uint32_t* __r
                                                  const uint32_t* __restrict__ gate)
 {
     const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), b0 = blockIdx.y * BPW, lane = lane_id();
-    if (t >= T || (gate && gate[0] == 0)) return;
+    if (t >= T || (gate && gate[0] != 0)) return;
     const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
     uint32_t kv[BPW][KPL], cnt[BPW];
 #pragma unroll
@@ -1392,7 +1482,7 @@ __global__ __launch_bounds__(1024) void k_tile_scan(const uint32_t* __restrict__
 {
     __shared__ uint32_t vals[SCAN_CHUNK + SCAN_CHUNK / 8];
     __shared__ uint32_t wtot[16];
-    if (gate && gate[0] == 0) return;
+    if (gate && gate[0] != 0) return;
     const uint32_t b = blockIdx.y, c0 = blockIdx.x * SCAN_CHUNK, n_chunks = gridDim.x;
     const uint32_t* cs = cnt_sel + (size_t)b * T;
     const uint32_t* ct = cnt_tie + (size_t)b * T;
@@ -1449,7 +1539,7 @@ __global__ __launch_bounds__(BLOCK) void k_emit(uint64_t n, const uint32_t* __re
     __shared__ uint32_t kb[4][SUBS * 16 * KPL];
     const uint32_t wid = threadIdx.x >> 6;
     const uint32_t t = blockIdx.x * 4 + wid, b0 = blockIdx.y * BPW, lane = lane_id();
-    if (t >= T || (gate && gate[0] == 0)) return;
+    if (t >= T || (gate && gate[0] != 0)) return;
     const TileRef tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
     const uint32_t start = tr.start, len = tr.len, seg = tr.seg;
     // one wave serves the tile for BPW batches: all their loads are requested before any is used

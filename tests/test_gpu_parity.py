@@ -194,7 +194,7 @@ def test_tie_heavy_stress_recipe_scaled():
 @pytest.mark.parametrize("mode", [1, 2])          # 1: too few candidates; 2: the sure zone alone exceeds the demand
 @pytest.mark.parametrize("hint", [False, True])
 @pytest.mark.parametrize("per_tile_tail", [False, True])
-def test_explore_wide_bound_rerun_gives_the_same_sets(mode, hint, per_tile_tail):
+def test_explore_exact_rerun_gives_the_same_sets(mode, hint, per_tile_tail):
     wl = workloads.TINY.scaled(100_003)
     got, want = run_iteration(wl, force_fallback=mode, hint=hint, per_tile_tail=per_tile_tail)
     assert_iteration_matches(wl, got, want)
