@@ -611,10 +611,18 @@ static int score_impl(slimdp_ctx* ctx, const float* w, const float* const* g, ui
     }
     const uint32_t P = persistent_blocks(ctx, SCORE_MINB, 1);
     const dim3 grid(P), block(BLOCK);
+    // flat model, up to 8 workers: every P-th tile per block (measured: 8 workers 1.38 -> 1.34 ms; 16 workers slower)
+    const bool strided = ctx->n_seg == 1 && ctx->opt_strided && W <= 8;
+#define LAUNCH_SCORE_Q(WT, PRE, SPEC, DENSE, STRIDED)                                                                 \
+    hipLaunchKernelGGL((k_score<WT, PRE, SPEC, DENSE, STRIDED>), grid, block, 0, ctx->stream, w, gt, (int)W, c, score, \
+                       ctx->d_tile_start, ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok, pre, sa, w_new, lr)
 #define LAUNCH_SCORE_P(WT, PRE, SPEC, DENSE)                                                                          \
-    hipLaunchKernelGGL((k_score<WT, PRE, SPEC, DENSE>), grid, block, 0, ctx->stream, w, gt, (int)W, c, score,         \
-                       ctx->d_tile_start, ctx->d_tile_seg, ctx->T, ctx->c_hist, vec_ok, pre, sa, w_new, lr,                 \
-                       (int)(ctx->n_seg == 1 && ctx->opt_strided))
+    do {                                                                                                              \
+        if constexpr ((WT) >= 1 && (WT) <= 8) {                                                                       \
+            if (strided) LAUNCH_SCORE_Q(WT, PRE, SPEC, DENSE, 1);                                                     \
+            else LAUNCH_SCORE_Q(WT, PRE, SPEC, DENSE, 0);                                                             \
+        } else LAUNCH_SCORE_Q(WT, PRE, SPEC, DENSE, 0);                                                               \
+    } while (0)
 #define LAUNCH_SCORE_S(WT, SPEC, DENSE)                                                                               \
     do {                                                                                                              \
         if (presample && pairs) LAUNCH_SCORE_P(WT, 2, SPEC, DENSE);                                                   \
@@ -639,6 +647,7 @@ static int score_impl(slimdp_ctx* ctx, const float* w, const float* const* g, ui
             break;
     }
 #undef LAUNCH_SCORE_P
+#undef LAUNCH_SCORE_Q
 #undef LAUNCH_SCORE_S
 #undef LAUNCH_SCORE
     SLIMDP_LAUNCHED(ctx, "k_score");

@@ -322,12 +322,12 @@ __host__ __device__ constexpr uint32_t spec_align(uint32_t W) { return (W == 0u 
 #ifndef SCORE_MINB
 #define SCORE_MINB 4
 #endif
-template <int WT, int PRE, int SPEC, int DENSE>
+template <int WT, int PRE, int SPEC, int DENSE, int STRIDED>
 __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __restrict__ w, PtrTab g, int Wrt, float c,
                                                  float* __restrict__ S, const uint32_t* __restrict__ tile_start,
                                                  const uint32_t* __restrict__ tile_seg, uint32_t T,
                                                  uint32_t* __restrict__ hist, int vec_ok, PreArgs pre, SpecArgs spec,
-                                                 float* __restrict__ w_new, float lr, int strided)
+                                                 float* __restrict__ w_new, float lr)
 {
     static_assert(!SPEC || WT != 0, "capture needs the update values in registers");
     static_assert(!(SPEC && DENSE), "a dense update is never followed by a pack of the same updates");
@@ -341,12 +341,12 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
     for (uint32_t b = threadIdx.x; b < NB; b += BLOCK) h[b] = 0;
     __syncthreads();
     // A block's tiles: a contiguous range (few segment changes, each of which flushes the histogram), or - flat model,
-    // strided != 0 - every gridDim.x-th tile, so that at any moment the whole chip streams through one window of each
-    // array instead of a thousand separate places (fewer DRAM rows open at a time).
-    uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
-    uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
-    uint32_t tstep = 1;
-    if (strided) { t0 = blockIdx.x; t1 = T; tstep = gridDim.x; }
+    // STRIDED - every gridDim.x-th tile, so that at any moment the whole chip streams through one window of each
+    // array instead of a thousand separate places (fewer DRAM rows open at a time).  A compile-time choice: with the
+    // step in a register the 16-worker variant spills more and loses 0.3 ms.
+    const uint32_t t0 = STRIDED ? blockIdx.x : (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
+    const uint32_t t1 = STRIDED ? T : (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
+    const uint32_t tstep = STRIDED ? gridDim.x : 1u;
     if (t0 >= t1) return;
     uint32_t cur_seg = tile_seg[t0];
     // Every wave owns sub-tile `wid` of each tile and runs through the block's tiles on its
