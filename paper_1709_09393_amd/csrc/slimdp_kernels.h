@@ -195,14 +195,17 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
     const uint32_t lane = lane_id();
     const uint32_t off = sub * SUB;
     const uint32_t sub_len = (len > off) ? ((len - off < SUB) ? len - off : SUB) : 0u;
-    uint32_t* cwords = out.cand_bits + (size_t)t * TILE_WORDS + sub * SUB_WORDS;
-    uint32_t* swords = out.sure_bits + (size_t)t * TILE_WORDS + sub * SUB_WORDS;
+    // the sub-tile's bitmap words and count through descriptors (t and sub are the same for the whole wave): scalar bases,
+    // no per-lane 64-bit addresses that a caller's loop over workers would have to carry along
+    const __amdgpu_buffer_rsrc_t rc = buffer_of(out.cand_bits + (size_t)t * TILE_WORDS + sub * SUB_WORDS, SUB_WORDS * 4u);
+    const __amdgpu_buffer_rsrc_t rs = buffer_of(out.sure_bits + (size_t)t * TILE_WORDS + sub * SUB_WORDS, SUB_WORDS * 4u);
+    const __amdgpu_buffer_rsrc_t rn = buffer_of(out.cnt_cand + (size_t)t * SUBS + sub, 4u);
     if (sub_len == 0 || skip) {                                   // uniform over the wave
         if (lane < SUB_WORDS) {
-            if (!PAIRS) cwords[lane] = 0;
-            swords[lane] = 0;
+            if (!PAIRS) buffer_store1(rc, lane * 4u, 0u);
+            buffer_store1(rs, lane * 4u, 0u);
         }
-        if (lane == 0) out.cnt_cand[(size_t)t * SUBS + sub] = 0;
+        if (lane == 0) buffer_store1(rn, 0u, 0u);
         return;
     }
     const uint32_t base = start + off;
@@ -262,13 +265,13 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
     {
         const int src = (int)(8u * (lane & 7u) + ((lane >> 3) & 3u));
         const uint32_t sw = __shfl(sword, src, 64);
-        if (lane < SUB_WORDS) swords[lane] = sw;
+        if (lane < SUB_WORDS) buffer_store1(rs, lane * 4u, sw);
         if (!PAIRS) {
             const uint32_t cw = __shfl(cword, src, 64);
-            if (lane < SUB_WORDS) cwords[lane] = cw;
+            if (lane < SUB_WORDS) buffer_store1(rc, lane * 4u, cw);
         }
     }
-    if (lane == 0) out.cnt_cand[(size_t)t * SUBS + sub] = run;
+    if (lane == 0) buffer_store1(rn, 0u, run);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -758,7 +761,7 @@ __global__ __launch_bounds__(BLOCK) void k_explore_keys(const uint32_t* __restri
                                                         uint64_t keys_stride, uint32_t worker0, PhiloxKey pk)
 {
     __shared__ uint32_t wa[FAST ? 1 : 4][SUB_WORDS], wb[FAST ? 1 : 4][SUB_WORDS], wp[FAST ? 1 : 4][SUB_WORDS];
-    const uint32_t b = blockIdx.y, worker = worker0 + b, wid = threadIdx.x >> 6;
+    const uint32_t b = blockIdx.y, worker = worker0 + b, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
     const uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
     DrawOut out;
