@@ -162,10 +162,10 @@ def main() -> int:
     # dominant kernel: k_score (one launch per step: reads w and the W updates, writes the score)
     score_gbs = sb["score"] / (stage_ms["score"] * 1e-3) / 1e9
     # HBM bytes per k_score launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
-    # factors being what the same counters read for a plain 1 GiB copy): 5.612 GB + 1.345 GB on the
+    # factors being what the same counters read for a plain 1 GiB copy): 5.237 GB + 1.326 GB on the
     # default workload (the bytes above the algorithmic ones: capture for the pack, the draws' bitmaps,
     # spill reloads).  Measured under rocprofv3, not in this process; null for any other size.
-    traffic = 6.957e9 if (not args.n and wl.name == "vgg16_flat") else None
+    traffic = 6.562e9 if (not args.n and wl.name == "vgg16_flat") else None
     roofline = {"bound": "hbm", "kernel": "k_score", "achieved": score_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": score_gbs / HBM_PEAK_GBS, "traffic": traffic,
                 "algorithmic_bytes_per_launch": sb["score"], "avg_launch_ms": stage_ms["score"]}
