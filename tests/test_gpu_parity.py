@@ -178,6 +178,19 @@ def test_segmented_googlenet_recipe_scaled():
     assert_iteration_matches(wl, got, want)
 
 
+def test_segmented_googlenet_config_full_size_as_benched():
+    """The GoogLeNet-sized configuration at full size (6,998,552 parameters in 57 segments, W = 4) the way
+    bench.py drives it: speculative packing on, the draw announced ahead, two iterations on one context."""
+    wl = workloads.GOOGLENET
+    seg_off = [int(x) for x in wl.segment_offsets()]
+    sd = binding.SlimDP(wl.n, wl.W, seg_off=seg_off, seed=workloads.EXPLORE_SEED)
+    sd.set_option("speculative_pack", 1)
+    for t in range(2):
+        got, want = run_iteration(wl, iteration=t, sd=sd, hint=True)
+        assert_iteration_matches(wl, got, want)
+    sd.close()
+
+
 def test_segments_with_awkward_boundaries():
     n = 30_000
     wl = workloads.TINY.scaled(n, seg_off=(0, 1, 18, 4114, 4115, 12_307, 29_999, n), n_seg=7)
