@@ -116,4 +116,17 @@ def test_full_size_iteration_matches(wl):
     assert np.all(np.abs(w_g - w_o) <= 1e-6 * np.abs(w_o) + 1e-12), "merge tolerance"
     assert np.array_equal(w_g.view(np.uint32), w_o.view(np.uint32)), "merge bits"
     print("merge ok (%.1f s)" % (time.time() - t0), flush=True)
+
+    # the exact rerun of the explorer (zones forced to miss) at this size: one block per worker, about 0.4 s
+    if wl.name == "vgg16_flat":
+        sd.set_option("explore_force_fallback", 1)
+        expl_idx2, expl_off2 = sd.sample_explore(core_bits, [k], it, [m], 0, W)
+        sd.synchronize()
+        q = W - 1
+        words = oracle.explore_words(workloads.EXPLORE_SEED, it, q, 0, n)
+        want = exact_top(words, ~in_core, m, largest=False)
+        assert np.array_equal(u32(expl_idx2[q]), want), "exact rerun, explorer %d" % q
+        assert np.array_equal(u32(expl_off2[q]), np.searchsorted(want, ts.astype(np.int64)).astype(np.uint32))
+        assert np.array_equal(u32(expl_idx2[0]), ei_got[0]), "exact rerun, explorer 0"
+        print("exact rerun ok (%.1f s)" % (time.time() - t0), flush=True)
     sd.close()
