@@ -81,6 +81,10 @@ def _declare(L: C.CDLL) -> None:
     L.oracle_merge_f64.restype = None
     L.oracle_pull.argtypes = [_f32p, _u32p, C.c_uint64, _u32p, C.c_uint64, _f32p, _f32p, _f32p]
     L.oracle_pull.restype = None
+    L.oracle_splitmix64_mix.argtypes = [C.c_uint64]
+    L.oracle_splitmix64_mix.restype = C.c_uint64
+    L.oracle_core_signature.argtypes = [_u32p, C.c_uint64]
+    L.oracle_core_signature.restype = C.c_uint64
 
 
 def _as(a, dtype) -> np.ndarray:
@@ -127,6 +131,16 @@ def score(w: np.ndarray, g: Sequence[np.ndarray], c: float) -> np.ndarray:
     lib().oracle_score(w.size, len(gs), _p(w, C.c_float), _table(gs, C.c_float), C.c_float(c),
                        _p(S, C.c_float))
     return S
+
+
+def splitmix64_mix(x: int) -> int:
+    return int(lib().oracle_splitmix64_mix(C.c_uint64(x & 0xFFFFFFFFFFFFFFFF)))
+
+
+def core_signature(core_idx: np.ndarray) -> int:
+    """Signature of the cached core keys (section 3.5): sum over j of mix(core_idx[j] + 2^32 j) modulo 2^64."""
+    ci = _as(core_idx, np.uint32)
+    return int(lib().oracle_core_signature(_p(ci, C.c_uint32), ci.size))
 
 
 def dense_update_score(w: np.ndarray, g: Sequence[np.ndarray], lr: float, c: float):

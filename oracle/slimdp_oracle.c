@@ -269,6 +269,30 @@ void oracle_merge_f64(uint64_t n, const float* w_in, double* w_out, double lr, u
 /* model at the worker's communication set; if w_local is given,      */
 /* overwrite the local model at those indices and leave the rest.     */
 /* ------------------------------------------------------------------ */
+/* ------------------------------------------------------------------ */
+/* Signature of the cached keys (section 3.5: for the core only the    */
+/* values travel, "and the signature of the keys").  The paper does not */
+/* say which; the reading taken: the 64-bit sum, modulo 2^64, over the  */
+/* list positions j of mix(core_idx[j] + 2^32 * j), mix being the       */
+/* output function of SplitMix64 (Steele, Lea, Flood, OOPSLA 2014).     */
+/* Order-sensitive, and a plain sum so that any schedule gives it.      */
+/* ------------------------------------------------------------------ */
+uint64_t oracle_splitmix64_mix(uint64_t x)
+{
+    uint64_t z = x + 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+uint64_t oracle_core_signature(const uint32_t* core_idx, uint64_t k)
+{
+    uint64_t sig = 0;
+    for (uint64_t j = 0; j < k; ++j)
+        sig += oracle_splitmix64_mix((uint64_t)core_idx[j] + (j << 32));
+    return sig;
+}
+
 void oracle_pull(const float* w, const uint32_t* core_idx, uint64_t k,
                  const uint32_t* expl_idx, uint64_t m,
                  float* core_out, float* expl_out, float* w_local)

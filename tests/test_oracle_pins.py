@@ -478,6 +478,30 @@ def test_dense_update_score_reduces_to_known_cases():
     assert bits(w4)[0] == 0x80000000 and w4[1] == np.float32(0.0) and S4[1] == np.float32(1.0)
 
 
+def test_core_signature_mix_known_answers_and_definition():
+    gamma, mask = 0x9E3779B97F4A7C15, (1 << 64) - 1
+    for line in open(os.path.join(GOLDEN, "splitmix64_kat.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        tok = line.split()
+        state = int(tok[0], 0)
+        for want in tok[1:]:                     # the generator's n-th output is mix(seed + (n - 1) gamma)
+            assert oracle.splitmix64_mix(state) == int(want, 0)
+            state = (state + gamma) & mask
+    # the signature against the definition in Python integers; order matters, the empty list gives 0
+    rng = np.random.default_rng(5)
+    idx = np.sort(rng.choice(1 << 20, 1000, replace=False)).astype(np.uint32)
+    want = sum(oracle.splitmix64_mix(int(i) + (j << 32)) for j, i in enumerate(idx)) & mask
+    assert oracle.core_signature(idx) == want
+    assert oracle.core_signature(np.zeros(0, np.uint32)) == 0
+    swapped = idx.copy()
+    swapped[[3, 4]] = swapped[[4, 3]]
+    assert oracle.core_signature(swapped) != want
+    changed = idx.copy()
+    changed[500] += 1
+    assert oracle.core_signature(changed) != want
+
+
 def test_pull_reads_and_overwrites_only_the_communication_set():
     rng = np.random.default_rng(6)
     w = rng.standard_normal(100).astype(np.float32)
