@@ -232,6 +232,13 @@ int slimdp_pull(slimdp_ctx* ctx, const float* w, uint64_t core_epoch, uint32_t n
                 const uint64_t* m_w, float* const* core_out, float* const* expl_out,
                 float* const* w_local);
 
+/* Signature of the cached core keys (section 3.5, "Communication Efficiency": for the core only the values are
+ * sent, "and the signature of the keys"): the two sides of a link compare it instead of the key list.  The paper
+ * does not fix the function; here: sum over list positions j of mix(core_idx[j] + 2^32 * j) modulo 2^64, mix being
+ * the output function of SplitMix64 (Steele, Lea, Flood, OOPSLA 2014).
+ *   core_idx [dev, k], sig [dev, one uint64, 8-byte aligned] overwritten. */
+int slimdp_core_signature(slimdp_ctx* ctx, const uint32_t* core_idx, uint64_t k, uint64_t* sig);
+
 /* The raw random words slimdp_sample_explore attaches to the indices i0 .. i0+count-1 for
  * (worker, iteration) under the context's seed.  out [dev, count]. */
 int slimdp_debug_philox(slimdp_ctx* ctx, uint64_t iteration, uint32_t worker, uint32_t i0,

@@ -31,7 +31,7 @@ EXPORTS = [
     "slimdp_create", "slimdp_destroy", "slimdp_workspace_bytes", "slimdp_num_tiles",
     "slimdp_tile_starts", "slimdp_last_error", "slimdp_synchronize", "slimdp_set_option",
     "slimdp_score", "slimdp_dense_update_score", "slimdp_select_core", "slimdp_sample_explore", "slimdp_explore_hint", "slimdp_tile_offsets",
-    "slimdp_pack", "slimdp_merge", "slimdp_pull", "slimdp_debug_philox",
+    "slimdp_pack", "slimdp_merge", "slimdp_pull", "slimdp_core_signature", "slimdp_debug_philox",
 ]
 
 
@@ -76,6 +76,8 @@ def load() -> C.CDLL:
     L.slimdp_score.restype = C.c_int
     L.slimdp_dense_update_score.argtypes = [_vp, _vp, _vpp, C.c_uint32, C.c_float, C.c_float, _vp]
     L.slimdp_dense_update_score.restype = C.c_int
+    L.slimdp_core_signature.argtypes = [_vp, _vp, C.c_uint64, _vp]
+    L.slimdp_core_signature.restype = C.c_int
     L.slimdp_select_core.argtypes = [_vp, _vp, _u64p, C.c_uint32, _vp, _vp, _vp, _u64p]
     L.slimdp_select_core.restype = C.c_int
     L.slimdp_sample_explore.argtypes = [_vp, _vp, _u64p, C.c_uint32, C.c_uint32, C.c_uint64, _u64p, _vpp, _vpp]
@@ -283,6 +285,12 @@ class SlimDP:
                                         _table(expl_idx), _table(expl_off), mw, _table(core_out), _table(expl_out),
                                         _table(w_local)))
         return core_out, expl_out
+
+    def core_signature(self, core_idx):
+        """Signature of the cached core keys; returns a one-element int64 device tensor (read it after synchronize)."""
+        out = self._empty(1, self._torch.int64)
+        self._check(self._L.slimdp_core_signature(self._h, _ptr(core_idx), core_idx.numel(), _ptr(out)))
+        return out
 
     def debug_philox(self, iteration: int, worker: int, i0: int, count: int):
         out = self._empty(count, self._torch.int32)

@@ -1042,6 +1042,21 @@ int slimdp_pull(slimdp_ctx* ctx, const float* w, uint64_t core_epoch, uint32_t n
     return SLIMDP_OK;
 }
 
+int slimdp_core_signature(slimdp_ctx* ctx, const uint32_t* core_idx, uint64_t k, uint64_t* sig)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    if (!sig || (k && !core_idx)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_core_signature: NULL argument");
+    if (k > ctx->n) return fail(ctx, SLIMDP_ERR_OUT_OF_RANGE, "slimdp_core_signature: k exceeds n");
+    int rc = fill(ctx, reinterpret_cast<uint32_t*>(sig), 2, 0u);
+    if (rc) return rc;
+    if (k) {
+        hipLaunchKernelGGL(k_signature, dim3(fill_grid(k)), dim3(256), 0, ctx->stream, core_idx, k,
+                           reinterpret_cast<unsigned long long*>(sig));
+        SLIMDP_LAUNCHED(ctx, "k_signature");
+    }
+    return SLIMDP_OK;
+}
+
 int slimdp_debug_philox(slimdp_ctx* ctx, uint64_t iteration, uint32_t worker, uint32_t i0, uint64_t count, uint32_t* out)
 {
     if (!ctx) return SLIMDP_ERR_INVALID_ARG;

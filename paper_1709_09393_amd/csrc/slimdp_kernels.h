@@ -2214,6 +2214,33 @@ __global__ __launch_bounds__(BLOCK) void k_merge(float* __restrict__ w, float lr
     }
 }
 
+// Signature of the cached keys: sum over list positions j of mix(idx[j] + 2^32 j) modulo 2^64, mix = the output
+// function of SplitMix64.  A wrapping integer sum: any order of the partial sums gives the same bits.
+// *sig must be zero at launch.  grid: any, 256 threads.
+__device__ __forceinline__ uint64_t splitmix64_mix(uint64_t x)
+{
+    uint64_t z = x + 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+__global__ __launch_bounds__(256) void k_signature(const uint32_t* __restrict__ idx, uint64_t k, unsigned long long* __restrict__ sig)
+{
+    __shared__ unsigned long long part[4];
+    unsigned long long s = 0;
+    for (uint64_t j = (uint64_t)blockIdx.x * 256 + threadIdx.x; j < k; j += (uint64_t)gridDim.x * 256)
+        s += splitmix64_mix((uint64_t)idx[j] + (j << 32));
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
+    if ((threadIdx.x & 63u) == 0) part[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned long long t = part[0] + part[1] + part[2] + part[3];
+        if (t) atomicAdd(sig, t);
+    }
+}
+
 // Raw random words of the explorer for indices i0 .. i0+count-1.
 __global__ __launch_bounds__(256) void k_debug_philox(uint32_t seed_lo, uint32_t seed_hi, uint32_t it_lo, uint32_t it_hi,
                                                       uint32_t worker, uint32_t i0, uint64_t count, uint32_t* __restrict__ out)

@@ -588,6 +588,22 @@ def test_paper_schedule_loop_scaled():
     sd.close()
 
 
+def test_core_signature_matches_oracle():
+    wl = workloads.TINY.scaled(700_001)
+    sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
+    S = to_dev(oracle.score(wl.weights(), wl.gradients(0), wl.c))
+    core_idx, core_bits, core_off, epoch = sd.select_core(S, [wl.k])
+    sig = sd.core_signature(core_idx)
+    empty = sd.core_signature(core_idx[:0])
+    one = sd.core_signature(core_idx[:1])
+    sd.synchronize()
+    core = u32(core_idx)
+    assert int(sig.cpu().numpy().view(np.uint64)[0]) == oracle.core_signature(core)
+    assert int(empty.cpu().numpy().view(np.uint64)[0]) == 0
+    assert int(one.cpu().numpy().view(np.uint64)[0]) == oracle.core_signature(core[:1])
+    sd.close()
+
+
 def test_error_paths_launch_nothing():
     n = 10_000
     sd = binding.SlimDP(n, 2)
