@@ -1687,7 +1687,16 @@ __global__ __launch_bounds__(BLOCK) void k_gather(PtrTab src, int shared_src, ui
                                                   PtrTab expl_idx, PtrTab expl_off, MutPtrTab core_val, MutPtrTab expl_val,
                                                   MutPtrTab scatter_dst)
 {
+    __shared__ uint32_t elo[MAXW], ecn[MAXW];
     const uint32_t t = blockIdx.x;
+    // the tile's slices of all explorer lists are requested first, in one go (one list after the other would wait
+    // for memory three times per worker)
+    if (threadIdx.x < nw) {
+        const uint32_t* eo = static_cast<const uint32_t*>(expl_off.p[threadIdx.x]);
+        const uint32_t lo = eo[t];
+        elo[threadIdx.x] = lo;
+        ecn[threadIdx.x] = eo[t + 1] - lo;
+    }
     const uint32_t c0 = core_off[t], c1 = core_off[t + 1];
     for (uint32_t j = c0 + threadIdx.x; j < c1; j += BLOCK) {
         const uint32_t i = core_idx[j];
@@ -1699,36 +1708,45 @@ __global__ __launch_bounds__(BLOCK) void k_gather(PtrTab src, int shared_src, ui
                 if (scatter_dst.p[q]) static_cast<float*>(scatter_dst.p[q])[i] = v;
             }
         } else {
-            for (uint32_t q = 0; q < nw; ++q)
-                static_cast<float*>(core_val.p[q])[j] = static_cast<const float*>(src.p[q])[i];
+            for (uint32_t q0 = 0; q0 < nw; q0 += 8) {          // eight workers' loads together
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = (q0 + u < nw) ? static_cast<const float*>(src.p[q0 + u])[i] : 0.0f;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) if (q0 + u < nw) static_cast<float*>(core_val.p[q0 + u])[j] = v[u];
+            }
         }
     }
-    for (uint32_t q = 0; q < nw; ++q) {
-        const uint32_t* eo = static_cast<const uint32_t*>(expl_off.p[q]);
-        const uint32_t* ei = static_cast<const uint32_t*>(expl_idx.p[q]);
-        const float* s = static_cast<const float*>(src.p[shared_src ? 0 : q]);
-        float* ev = static_cast<float*>(expl_val.p[q]);
-        float* sd = static_cast<float*>(scatter_dst.p[q]);
-        const uint32_t e0 = eo[t], e1 = eo[t + 1];
-        for (uint32_t j = e0 + threadIdx.x; j < e1; j += BLOCK) {
-            const uint32_t i = ei[j];
-            if (i >= n) continue;
-            const float v = s[i];
-            ev[j] = v;
-            if (sd) sd[i] = v;
+    __syncthreads();
+    uint32_t E = 0;
+    for (uint32_t q = 0; q < nw; ++q) E += ecn[q];
+    for (uint32_t x0 = 0; x0 < E; x0 += 2 * BLOCK) {            // two entries per thread in flight
+        uint32_t qq[2], jj[2], ii[2];
+        float vv[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint32_t x = x0 + u * BLOCK + threadIdx.x;
+            qq[u] = 0; jj[u] = 0; ii[u] = 0xFFFFFFFFu;
+            if (x < E) {
+                uint32_t q = 0, run = 0;
+                while (q + 1 < nw && run + ecn[q] <= x) { run += ecn[q]; ++q; }
+                qq[u] = q; jj[u] = elo[q] + (x - run);
+                ii[u] = static_cast<const uint32_t*>(expl_idx.p[q])[jj[u]];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            vv[u] = (ii[u] < n) ? static_cast<const float*>(src.p[shared_src ? 0 : qq[u]])[ii[u]] : 0.0f;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (ii[u] >= n) continue;
+            static_cast<float*>(expl_val.p[qq[u]])[jj[u]] = vv[u];
+            float* sd = static_cast<float*>(scatter_dst.p[qq[u]]);
+            if (sd) sd[ii[u]] = vv[u];
         }
     }
 }
 
-// ---------------------------------------------------------------------------------------
-// K5 (pack): extraction by streaming, the way the paper puts it ("scanning the whole set").
-// One block per tile.  Each worker's tile of updates is read with full-width coalesced
-// loads into LDS (the next worker's tile is already in flight in registers), and the
-// tile's slice of the core list and of the worker's explorer list is then picked out of
-// LDS and written out contiguously.  (Storing the core values straight from registers at
-// their prefix-sum positions was tried and is slower: many narrow partial-line stores.)
-// NBUF = 2: one barrier per worker; NBUF = 1: two barriers, half the LDS, more blocks per CU.
-// ---------------------------------------------------------------------------------------
 // ---------------------------------------------------------------------------------------
 // Pack after a scoring pass that captured the update values of every parameter at or above
 // spec_lo (k_score<.., SPEC = 1>): the core values of a captured tile come from the compact
