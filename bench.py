@@ -200,6 +200,30 @@ def main() -> int:
     out["paper_schedule_reselect"] = {"ms": dense_ms, "Gparam_per_s": n / (dense_ms * 1e-3) / 1e9,
                                       "what": "slimdp_dense_update_score + slimdp_select_core",
                                       "algorithmic_bytes": 4 * n * (W + 3) + 4 * n + 4 * k + n // 8}
+    # and the steady iteration between two reselections (cached core keys, fresh updates: explorers, pack by scanning
+    # the updates, merge); there is no scoring pass to carry the next draw, so it is announced to the side stream and
+    # runs beside the pack and the merge
+    sd.set_option("explore_hint_mode", 1)
+    _, _, _, epoch2 = sd.select_core(S, ks, core_idx=core_idx, core_bits=core_bits, core_off=core_off)
+    sd.explore_hint(ks, 10_000, ms, 0, W)
+    sd.sample_explore(core_bits, ks, 10_000, ms, 0, W, expl_idx=expl_idx, expl_off=expl_off)
+    sd.explore_hint(ks, 10_001, ms, 0, W)
+    ev3 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev3[0].record()
+    for r in range(reps):
+        sd.sample_explore(core_bits, ks, 10_001 + r, ms, 0, W, expl_idx=expl_idx, expl_off=expl_off)
+        sd.explore_hint(ks, 10_002 + r, ms, 0, W)
+        sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch2, core_val=core_val, expl_val=expl_val)
+        sd.merge(w, wl.lr, epoch2, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
+    ev3[1].record()
+    torch.cuda.synchronize()
+    sd.synchronize()
+    steady_ms = ev3[0].elapsed_time(ev3[1]) / reps
+    steady_bytes = sb["sample_explore"] + sb["pack"] + sb["merge"]
+    out["steady_iteration"] = {"ms": steady_ms, "Gparam_per_s": n / (steady_ms * 1e-3) / 1e9,
+                               "what": "slimdp_sample_explore + slimdp_pack + slimdp_merge, core keys cached",
+                               "algorithmic_bytes": steady_bytes,
+                               "hbm_frac": steady_bytes / (steady_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
     sd.close()
     del w, g, S
     if args.cpu_sample > 0:

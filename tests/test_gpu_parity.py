@@ -487,10 +487,15 @@ def test_same_call_twice_gives_identical_bits_and_workers_differ():
     assert not np.array_equal(a["expl_idx"][0], c["expl_idx"][0])
 
 
-def test_multi_iteration_loop_scaled():
-    # 20 iterations, core every 5, explorer every iteration, model carried along
-    wl = workloads.LOOP.scaled(40_009, W=4)
+@pytest.mark.parametrize("announce", [False, True])
+def test_multi_iteration_loop_scaled(announce):
+    # 20 iterations, core every 5, explorer every iteration, model carried along.  announce: every draw is announced
+    # one iteration ahead; the scoring pass of a reselecting iteration carries it, otherwise the side stream
+    wl = workloads.LOOP.scaled(40_009 if not announce else 300_007, W=4)
     sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
+    if announce:
+        sd.set_option("speculative_pack", 1)
+        sd.explore_hint([wl.k], 0, [wl.m], 0, wl.W)
     w_h = wl.weights()
     w = to_dev(w_h)
     k, m = wl.k, wl.m
@@ -504,6 +509,9 @@ def test_multi_iteration_loop_scaled():
             core_o = oracle.select_core(oracle.score(w_h, g_h, wl.c), k)
             assert np.array_equal(u32(core_idx), core_o), t
         expl_idx, expl_off = sd.sample_explore(core_bits, [k], t, [m], 0, wl.W)
+        if announce:
+            sd.set_option("explore_hint_mode", 0 if (t + 1) % wl.reselect_every == 0 else 1)
+            sd.explore_hint([k], t + 1, [m], 0, wl.W)
         core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)
         sd.merge(w, wl.lr, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
         ei_o = [oracle.sample_explore(wl.n, core_o, workloads.EXPLORE_SEED, t, q, m) for q in range(wl.W)]
