@@ -612,6 +612,34 @@ def test_core_signature_matches_oracle():
     sd.close()
 
 
+def test_randomized_configurations():
+    """Seeded sweep over sizes, worker counts, fractions, segmentations and the library's options (announced draws in
+    both modes, speculative packing, the general explorer tail, forced exact reruns), a few iterations per context."""
+    import random
+    rnd = random.Random(20260101)
+    for case in range(16):
+        n = rnd.choice([rnd.randint(1, 5000), rnd.randint(5000, 300_000), rnd.randint(300_000, 900_000)])
+        W = rnd.choice([1, 2, 3, 4, 5, 8, 16])
+        kw = dict(W=W, core_pct=rnd.choice([0, 1, 5, 10, 30, 100]), explore_pct=rnd.choice([0, 1, 2, 10, 50, 100]))
+        nseg = rnd.choice([1, 1, 1, rnd.randint(2, 40)])
+        if nseg > 1 and n > 2 * nseg:
+            cuts = sorted(rnd.sample(range(1, n), nseg - 1))
+            kw.update(seg_off=tuple([0] + cuts + [n]), n_seg=nseg)
+        wl = (workloads.TINY if rnd.random() < 0.7 else workloads.STRESS).scaled(n, **kw)
+        sd = binding.SlimDP(wl.n, wl.W, seg_off=[int(x) for x in wl.segment_offsets()], seed=workloads.EXPLORE_SEED)
+        if rnd.random() < 0.6:
+            sd.set_option("speculative_pack", 1)
+        for t in range(rnd.choice([1, 2, 3])):
+            opts = dict(hint=rnd.random() < 0.6, hint_mode=rnd.choice([0, 1]), per_tile_tail=rnd.random() < 0.2,
+                        force_fallback=rnd.choice([0, 0, 0, 1, 2]))
+            got, want = run_iteration(wl, iteration=t, sd=sd, **opts)
+            try:
+                assert_iteration_matches(wl, got, want)
+            except AssertionError as e:
+                raise AssertionError("case %d (%s, iteration %d, %r): %s" % (case, wl, t, opts, e))
+        sd.close()
+
+
 def test_error_paths_launch_nothing():
     n = 10_000
     sd = binding.SlimDP(n, 2)
