@@ -15,8 +15,12 @@
  *    or prints.
  *  - Calls are asynchronous on the HIP stream given to slimdp_create and never
  *    synchronise the host; every output size is known from the arguments.  Conditions
- *    only the device can detect (see slimdp_synchronize) are reported there.
- *  - The library allocates device memory only in slimdp_create.
+ *    only the device can detect (see slimdp_synchronize) are reported there.  The one
+ *    piece of work that may run elsewhere is an announced explorer draw on the library's
+ *    own side stream (option "explore_hint_mode" = 1); the calls that need its result
+ *    make the caller's stream wait for it.
+ *  - The library allocates device memory in slimdp_create, and once more when the option
+ *    "speculative_pack" is first switched on.
  *  - Same inputs give the same output bits, whatever the launch geometry.
  *  - Indices are 0-based uint32 (the paper counts from 1); n < 2^32.
  *
