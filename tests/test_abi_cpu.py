@@ -93,3 +93,19 @@ def test_workload_recipes():
     st = workloads.STRESS.scaled(10000)
     wv = st.weights()
     assert np.array_equal(wv, wv.astype(np.float16).astype(np.float32))
+
+
+def test_bench_refuses_more_than_one_gpu_and_models_the_stages():
+    """bench.py runs on one GPU only and says so; its stream model of the headline workload is the 13.864 GB of the
+    benchmark definition (no GPU needed for either)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    proc = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert proc.returncode != 0 and "ONE GPU" in proc.stderr and proc.stdout.strip() == ""
+    sys.path.insert(0, root)
+    import bench
+    wl = workloads.VGG16
+    sb = bench.stage_bytes(wl.n, wl.W, wl.k, wl.m)
+    assert abs(sum(sb.values()) - 13.864e9) < 1e6
+    assert sb["score"] == 4 * wl.n * (wl.W + 2)
