@@ -57,6 +57,8 @@ enum {
 
 /* slimdp_select_core flags */
 #define SLIMDP_SELECT_REUSE_HISTOGRAM 1u
+/* slimdp_pack flags */
+#define SLIMDP_PACK_UPDATES_AS_SCORED 1u
 
 typedef struct slimdp_ctx slimdp_ctx;
 
@@ -98,11 +100,11 @@ int slimdp_synchronize(slimdp_ctx* ctx);
  *       slimdp_select_core less a small margin (own device allocation of about 4*W*n bytes,
  *       made by this call); if the following slimdp_select_core(..REUSE_HISTOGRAM) finds its
  *       threshold at or above that bound, the next slimdp_pack takes the core values from
- *       there instead of scanning the update vectors again.  Results are bit-identical either
- *       way (the same slow drift of the core that the paper's key caching relies on, section
- *       3.3).  CONTRACT while the option is on: the first slimdp_pack after such a selection
- *       is given the very update arrays, unchanged, that slimdp_score read; one capture
- *       serves one pack, later packs of the same core read the vectors they are given.
+ *       there instead of scanning the update vectors again, PROVIDED that call carries the
+ *       flag SLIMDP_PACK_UPDATES_AS_SCORED (see slimdp_pack); without the flag a pack always
+ *       reads the vectors it is given.  Results are bit-identical either way (the same slow
+ *       drift of the core that the paper's key caching relies on, section 3.3).  One capture
+ *       serves one pack.
  *   "explore_hint_mode" (0/1, default 0): where an announced explorer draw runs: 0 inside
  *       the next slimdp_score, 1 at once on a side stream of the library (default priority),
  *       beside whatever runs on the context's stream.
@@ -140,7 +142,7 @@ int slimdp_score(slimdp_ctx* ctx, const float* w, const float* const* g, uint32_
 int slimdp_dense_update_score(slimdp_ctx* ctx, float* w, const float* const* g, uint32_t W, float lr,
                               float c, float* score);
 
-/* Core-Selection operator T_S (section 3.1 item 1; section 3.2 "rank ... select the top";
+/* Core-Selection operator T_S (section 3.1 item 1; section 3.2, the ranking after equation (1);
  * section 3.3 step 6): per segment s the k_seg[s] parameters that come first when ranked
  * by (score bit pattern as uint32, descending; index, ascending).  For scores >= +0 that
  * is the numeric order with ties going to the lower index; NaN ranks above +infinity.
@@ -152,7 +154,7 @@ int slimdp_dense_update_score(slimdp_ctx* ctx, float* w, const float* const* g, 
  *   core_idx [dev, sum k_seg]  chosen global indices, ascending
  *   core_bits[dev, ceil(n/32)] bit (i mod 32) of word (i div 32) set iff i is in the core
  *   core_off [dev, T+1]        tile offsets of core_idx
- *   core_epoch [host, 1]       identifier of this core: the "signature of the keys" both
+ *   core_epoch [host, 1]       identifier of this core, the library's stand-in for what both
  *            ends of the key-caching filter hold (section 3.5); pack/merge/pull made for
  *            another core are refused with SLIMDP_ERR_STALE_CORE. */
 int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_seg, uint32_t flags,
@@ -183,8 +185,8 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
  * will need (the arguments must then be identical, else the draw is simply redone).  The
  * random words do not depend on the core or on any data, so their generation -- the only
  * step of the path bound by integer arithmetic rather than by memory -- can hide under
- * memory-bound work, as the paper notes for its worker side (section 3.5, "Time
- * Efficiency"): by default the next slimdp_score on this context draws while it streams
+ * memory-bound work, as the paper notes for its worker side (section 3.5, the paragraph on
+ * time efficiency): by default the next slimdp_score on this context draws while it streams
  * the model; with option "explore_hint_mode" = 1 the draw starts at once on a side stream.
  * Purely a performance hint: results are bit-identical with or without it.  Host arrays as
  * in slimdp_sample_explore; k_seg is the core size the coming slimdp_select_core will use. */
@@ -203,12 +205,20 @@ int slimdp_tile_offsets(slimdp_ctx* ctx, const uint32_t* idx, uint64_t count, ui
  *   g [host table, n_workers] of [dev, n]; core_idx [dev, k]; core_off [dev, T+1];
  *   expl_idx / expl_off [host tables]; m_w [host, n_workers] explorer sizes;
  *   core_val [host table] of [dev, k]; expl_val [host table] of [dev, m_w[q]].
+ *   flags    SLIMDP_PACK_UPDATES_AS_SCORED: the caller states that g is the very table of
+ *            arrays, unmodified since, that the last slimdp_score on this context read, and
+ *            that core_idx came from the slimdp_select_core(..REUSE_HISTOGRAM) that followed
+ *            it.  With option "speculative_pack" on, the pack may then take values the scoring
+ *            pass kept instead of reading g again.  Never set it after refilling the update
+ *            buffers (the steady iterations of algorithm 1 pack updates no scoring pass has
+ *            seen): the library cannot detect changed contents, only a different table
+ *            (SLIMDP_ERR_INVALID_ARG).  Without the flag nothing kept is ever used.
  * Words on the wire per worker: k + 2*m_w[q], the (2*alpha - beta)*n of section 3.5. */
 int slimdp_pack(slimdp_ctx* ctx, uint32_t n_workers, const float* const* g,
                 const uint32_t* core_idx, const uint32_t* core_off, uint64_t k,
                 const uint32_t* const* expl_idx, const uint32_t* const* expl_off,
                 const uint64_t* m_w, float* const* core_val, float* const* expl_val,
-                uint64_t core_epoch);
+                uint64_t core_epoch, uint32_t flags);
 
 /* Update, server side (section 3.3 step 3):  w_i <- w_i - lr * sum_q T_C(delta_q)_i.
  * For every index i some worker sent: acc = +0; for q ascending over the workers whose
@@ -216,7 +226,7 @@ int slimdp_pack(slimdp_ctx* ctx, uint32_t n_workers, const float* const* g,
  * sent keep their bits.  No atomics; the result does not depend on scheduling.
  * Requires each explorer list to be disjoint from the core (as slimdp_sample_explore
  * guarantees); otherwise the core contributions to an index are added before the
- * explorer ones.
+ * explorer ones, those again in worker order.
  *   w [dev, n] in place; the other arguments as in slimdp_pack (values are inputs). */
 int slimdp_merge(slimdp_ctx* ctx, float* w, float lr, uint64_t core_epoch, uint32_t n_workers,
                  const uint32_t* core_idx, const uint32_t* core_off, uint64_t k,
@@ -236,9 +246,9 @@ int slimdp_pull(slimdp_ctx* ctx, const float* w, uint64_t core_epoch, uint32_t n
                 const uint64_t* m_w, float* const* core_out, float* const* expl_out,
                 float* const* w_local);
 
-/* Signature of the cached core keys (section 3.5, "Communication Efficiency": for the core only the values are
- * sent, "and the signature of the keys"): the two sides of a link compare it instead of the key list.  The paper
- * does not fix the function; here: sum over list positions j of mix(core_idx[j] + 2^32 * j) modulo 2^64, mix being
+/* Signature of the cached core keys (section 3.5, communication efficiency: for the core only the values
+ * travel, together with a signature of the cached keys): the two sides of a link compare it instead of the key
+ * list.  The paper does not fix the function; here: sum over list positions j of mix(core_idx[j] + 2^32 * j) modulo 2^64, mix being
  * the output function of SplitMix64 (Steele, Lea, Flood, OOPSLA 2014).
  *   core_idx [dev, k], sig [dev, one uint64, 8-byte aligned] overwritten. */
 int slimdp_core_signature(slimdp_ctx* ctx, const uint32_t* core_idx, uint64_t k, uint64_t* sig);

@@ -26,6 +26,7 @@ ERR_WORKSPACE = -4
 ERR_HIP = -5
 ERR_DEVICE_STATUS = -6
 SELECT_REUSE_HISTOGRAM = 1
+PACK_UPDATES_AS_SCORED = 1
 
 EXPORTS = [
     "slimdp_create", "slimdp_destroy", "slimdp_workspace_bytes", "slimdp_num_tiles",
@@ -86,7 +87,8 @@ def load() -> C.CDLL:
     L.slimdp_explore_hint.restype = C.c_int
     L.slimdp_tile_offsets.argtypes = [_vp, _vp, C.c_uint64, _vp]
     L.slimdp_tile_offsets.restype = C.c_int
-    L.slimdp_pack.argtypes = [_vp, C.c_uint32, _vpp, _vp, _vp, C.c_uint64, _vpp, _vpp, _u64p, _vpp, _vpp, C.c_uint64]
+    L.slimdp_pack.argtypes = [_vp, C.c_uint32, _vpp, _vp, _vp, C.c_uint64, _vpp, _vpp, _u64p, _vpp, _vpp, C.c_uint64,
+                              C.c_uint32]
     L.slimdp_pack.restype = C.c_int
     L.slimdp_merge.argtypes = [_vp, _vp, C.c_float, C.c_uint64, C.c_uint32, _vp, _vp, C.c_uint64, _vpp, _vpp, _vpp,
                                _vpp, _u64p]
@@ -250,7 +252,8 @@ class SlimDP:
         return out
 
     def pack(self, g: Sequence, core_idx, core_off, expl_idx: Sequence, expl_off: Sequence, core_epoch: int,
-             core_val: Optional[List] = None, expl_val: Optional[List] = None):
+             core_val: Optional[List] = None, expl_val: Optional[List] = None, updates_as_scored: bool = False):
+        """updates_as_scored: g is, unchanged, what the last score() on this context read."""
         torch = self._torch
         nw = len(g)
         k = core_idx.numel()
@@ -260,7 +263,8 @@ class SlimDP:
             expl_val = [self._empty(expl_idx[q].numel(), torch.float32) for q in range(nw)]
         mw = _u64arr([expl_idx[q].numel() for q in range(nw)])
         self._check(self._L.slimdp_pack(self._h, nw, _table(g), _ptr(core_idx), _ptr(core_off), k, _table(expl_idx),
-                                        _table(expl_off), mw, _table(core_val), _table(expl_val), int(core_epoch)))
+                                        _table(expl_off), mw, _table(core_val), _table(expl_val), int(core_epoch),
+                                        PACK_UPDATES_AS_SCORED if updates_as_scored else 0))
         return core_val, expl_val
 
     def merge(self, w, lr: float, core_epoch: int, core_idx, core_off, core_val: Sequence, expl_idx: Sequence,

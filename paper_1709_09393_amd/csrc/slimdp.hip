@@ -934,9 +934,10 @@ static int check_lists(slimdp_ctx* ctx, const char* who, uint32_t n_workers, con
 
 int slimdp_pack(slimdp_ctx* ctx, uint32_t n_workers, const float* const* g, const uint32_t* core_idx,
                 const uint32_t* core_off, uint64_t k, const uint32_t* const* expl_idx, const uint32_t* const* expl_off,
-                const uint64_t* m_w, float* const* core_val, float* const* expl_val, uint64_t core_epoch)
+                const uint64_t* m_w, float* const* core_val, float* const* expl_val, uint64_t core_epoch, uint32_t flags)
 {
     if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    if (flags & ~SLIMDP_PACK_UPDATES_AS_SCORED) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_pack: unknown flag bits 0x%x", flags);
     int rc = check_lists(ctx, "slimdp_pack", n_workers, core_idx, core_off, k, expl_idx, expl_off, m_w);
     if (rc) return rc;
     if (!table_ok(g, n_workers)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_pack: NULL update pointer");
@@ -946,9 +947,18 @@ int slimdp_pack(slimdp_ctx* ctx, uint32_t n_workers, const float* const* g, cons
     }
     rc = check_epoch(ctx, core_epoch);
     if (rc) return rc;
+    // The caller states that g is what the last scoring pass read.  That the contents are unchanged cannot be
+    // checked here; that it is the same table can.
+    const bool as_scored = (flags & SLIMDP_PACK_UPDATES_AS_SCORED) != 0;
+    if (as_scored && ctx->spec.captured) {
+        bool same = ctx->spec.W == n_workers;
+        for (uint32_t q = 0; same && q < n_workers; ++q) same = ctx->spec.g[q] == g[q];
+        if (!same)
+            return fail(ctx, SLIMDP_ERR_INVALID_ARG,
+                        "slimdp_pack: SLIMDP_PACK_UPDATES_AS_SCORED, but g is not the table of arrays the last slimdp_score read");
+    }
     // the scoring pass of this very selection kept the core's update values: no second pass over the updates
-    bool spec = ctx->spec.on && ctx->spec.captured && ctx->spec.core_epoch == core_epoch && ctx->spec.W == n_workers;
-    for (uint32_t q = 0; spec && q < n_workers; ++q) spec = ctx->spec.g[q] == g[q];
+    const bool spec = as_scored && ctx->spec.on && ctx->spec.captured && ctx->spec.core_epoch == core_epoch;
     if (spec) {
         ctx->spec.captured = false;      // one capture serves one pack
         if (k && ctx->n_seg == 1) {

@@ -2022,7 +2022,8 @@ __global__ __launch_bounds__(BLOCK) void k_pack_stream(PtrTab g, uint32_t nw, co
 // Explorers: each entry of the tile takes a ticket at its position (LDS byte counter).  A
 // position with one or two entries is summed in ticket order -- with at most two addends
 // the binary32 sum does not depend on their order.  Positions with three or more entries
-// (rare) go to a short list that one thread replays in worker order.  Tiles with more
+// (rare), or with two on top of a core sum (only if a list overlaps the core), go to a short
+// list that one thread replays in worker order.  Tiles with more
 // explorer entries than the fast path holds in registers, or with too many such positions,
 // take the generic path: entries staged through LDS and applied one worker at a time.
 //
@@ -2146,6 +2147,9 @@ __global__ __launch_bounds__(BLOCK) void k_merge(float* __restrict__ w, float lr
             if (epos[i] != 0xFFFFFFFFu) {
                 const uint32_t byte = (cnt[epos[i] >> 2] >> (8u * (epos[i] & 3u))) & 0xFFu;
                 tot[i] = byte & 0x7Fu;
+                // two explorer entries on top of a core sum (lists that overlap the core: invalid input) would make
+                // the result depend on the ticket order: such a position is replayed in worker order as well
+                if (tot[i] == 2u && (byte & 0x80u)) tot[i] = 3u;
                 if (tot[i] <= 2u) {
                     if (etk[i] == 0) acc[epos[i]] = ((byte & 0x80u) ? acc[epos[i]] : 0.0f) + eval[i];
                 } else {

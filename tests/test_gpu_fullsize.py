@@ -1,6 +1,6 @@
 """Full-size parity: the VGG-16-sized workload in the launch configuration bench.py times
-(flat model, n = 138,357,544, W = 8, explorer draw announced ahead and made on the library's side stream,
-speculative packing with the capture bound of an earlier selection), and
+(flat model, n = 138,357,544, W = 8, explorer draw announced ahead and made inside the scoring pass,
+speculative packing with the capture bound of an earlier selection), the multi-iteration loop at the same size, and
 the tie-heavy stress workload of the same length (W = 16, values rounded through binary16).
 
 What the oracle can do at this size it does in full (score, random words, pack, merge:
@@ -64,7 +64,7 @@ def test_full_size_iteration_matches(wl):
     S = sd.score(w, g, wl.c)
     core_idx, core_bits, core_off, epoch = sd.select_core(S, [k], reuse_histogram=True)
     expl_idx, expl_off = sd.sample_explore(core_bits, [k], it, [m], 0, W)
-    core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)
+    core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch, updates_as_scored=True)
     sd.merge(w, wl.lr, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
     sd.synchronize()
     print("GPU iteration done", flush=True)
@@ -90,17 +90,19 @@ def test_full_size_iteration_matches(wl):
     assert np.array_equal(u32(core_bits), bits_want), "core bitmap"
     print("core ok (%.1f s)" % (time.time() - t0), flush=True)
 
-    # explorers: first, last and one middle worker in full; sizes and disjointness for all
+    # explorers: every worker's set in full (the host work of several workers runs side by side)
+    from concurrent.futures import ThreadPoolExecutor
     ei_got = [u32(x) for x in expl_idx]
-    for q in range(W):
-        assert ei_got[q].size == m and np.all(np.diff(ei_got[q].astype(np.int64)) > 0), q
-        assert not in_core[ei_got[q]].any(), q
-    for q in (0, W // 2 - 1, W - 1):
+
+    def check_explorer(q):
         words = oracle.explore_words(workloads.EXPLORE_SEED, it, q, 0, n)
         want = exact_top(words, ~in_core, m, largest=False)
-        assert np.array_equal(ei_got[q], want), "explorer %d" % q
-        assert np.array_equal(u32(expl_off[q]), np.searchsorted(want, ts.astype(np.int64)).astype(np.uint32))
-        print("explorer %d ok (%.1f s)" % (q, time.time() - t0), flush=True)
+        return np.array_equal(ei_got[q], want) and np.array_equal(
+            u32(expl_off[q]), np.searchsorted(want, ts.astype(np.int64)).astype(np.uint32))
+    with ThreadPoolExecutor(8) as pool:
+        ok = list(pool.map(check_explorer, range(W)))
+    assert all(ok), "explorer sets: %r" % ok
+    print("all %d explorers ok (%.1f s)" % (W, time.time() - t0), flush=True)
 
     # packs: bit copies, every entry
     cv = [x.cpu().numpy() for x in core_val]
@@ -130,3 +132,107 @@ def test_full_size_iteration_matches(wl):
         assert np.array_equal(u32(expl_idx2[0]), ei_got[0]), "exact rerun, explorer 0"
         print("exact rerun ok (%.1f s)" % (time.time() - t0), flush=True)
     sd.close()
+
+
+def test_full_size_loop_steady_path_matches():
+    """The multi-iteration configuration at its stated size (n = 138,357,544, W = 8; core every 5 iterations,
+    explorer every iteration, fresh updates per (iteration, worker) written into the SAME device buffers), six
+    iterations: t = 0 the first selection of a fresh context, t = 1..4 steady iterations (core keys cached, the pack
+    scans updates no scoring pass has seen, every draw announced one iteration ahead: on the side stream, or inside
+    the scoring pass before a reselection), t = 5 a reselection whose capture bound comes from t = 0's selection on
+    other updates.  Checked over every element: scores, both packs of a reselecting iteration (values kept by the
+    scoring pass, and the scanning pack), merge, pull (+ local overwrite), ALL W explorer sets of every iteration,
+    and one dense update + significance; the rankings through the threshold property."""
+    from concurrent.futures import ThreadPoolExecutor
+    if not torch.cuda.is_available():
+        pytest.fail("GPU test selected but torch.cuda.is_available() is False")
+    dev = torch.device("cuda:0")
+    wl = workloads.LOOP
+    n, W, k, m = wl.n, wl.W, wl.k, wl.m
+    every = wl.reselect_every
+    t0 = time.time()
+    pool = ThreadPoolExecutor(8)
+    sd = binding.SlimDP(n, W, seed=workloads.EXPLORE_SEED)
+    sd.set_option("speculative_pack", 1)
+    w_h = wl.weights()
+    w = torch.from_numpy(w_h).to(dev)
+    g = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(W)]
+    ts = sd.tile_starts().astype(np.int64)
+    rng = np.random.default_rng(5)
+    local_h = rng.standard_normal(n).astype(np.float32)
+
+    def u32(t):
+        return t.cpu().numpy().view(np.uint32)
+
+    core_want = in_core = None
+    sd.explore_hint([k], 0, [m], 0, W)                     # the first draw rides inside the first scoring pass
+    for t in range(6):
+        g_h = list(pool.map(lambda q: wl.gradient(t, q), range(W)))
+        for q in range(W):
+            g[q].copy_(torch.from_numpy(g_h[q]))            # refilled in place
+        resel = t % every == 0
+        if resel:
+            S = sd.score(w, g, wl.c)
+            core_idx, core_bits, core_off, epoch = sd.select_core(S, [k], reuse_histogram=True)
+        expl_idx, expl_off = sd.sample_explore(core_bits, [k], t, [m], 0, W)
+        sd.set_option("explore_hint_mode", 0 if (t + 1) % every == 0 else 1)
+        sd.explore_hint([k], t + 1, [m], 0, W)
+        core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch, updates_as_scored=resel)
+        if resel:                                           # the scanning pack of the same updates gives the same bits
+            cv2, ev2 = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)
+        sd.merge(w, wl.lr, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
+        w_local = [None] * W
+        if t in (1, 5):
+            w_local[W - 1] = torch.from_numpy(local_h).to(dev)
+        core_out, expl_out = sd.pull(w, epoch, core_idx, core_off, expl_idx, expl_off, w_local=w_local)
+        sd.synchronize()
+        print("t=%d GPU done (%.1f s)" % (t, time.time() - t0), flush=True)
+
+        if resel:
+            S_o = oracle.score(w_h, g_h, wl.c)
+            assert np.array_equal(S.cpu().numpy().view(np.uint32), S_o.view(np.uint32)), "score bits, t=%d" % t
+            core_want = exact_top(S_o.view(np.uint32), None, k, largest=True)
+            assert np.array_equal(u32(core_idx), core_want), "core set, t=%d" % t
+            assert np.array_equal(u32(core_off), np.searchsorted(core_want, ts).astype(np.uint32))
+            in_core = np.zeros(n, bool)
+            in_core[core_want] = True
+            for q in range(W):
+                assert torch.equal(cv2[q].view(torch.int32), core_val[q].view(torch.int32)), (t, q)
+                assert torch.equal(ev2[q].view(torch.int32), expl_val[q].view(torch.int32)), (t, q)
+            del cv2, ev2, S_o
+        ei_got = [u32(x) for x in expl_idx]
+
+        def check_explorer(q):
+            words = oracle.explore_words(workloads.EXPLORE_SEED, t, q, 0, n)
+            want = exact_top(words, ~in_core, m, largest=False)
+            return np.array_equal(ei_got[q], want) and np.array_equal(
+                u32(expl_off[q]), np.searchsorted(want, ts).astype(np.uint32))
+        ok = list(pool.map(check_explorer, range(W)))
+        assert all(ok), "explorer sets, t=%d: %r" % (t, ok)
+        cv = [x.cpu().numpy() for x in core_val]
+        ev = [x.cpu().numpy() for x in expl_val]
+        for q in range(W):
+            assert np.array_equal(cv[q].view(np.uint32), g_h[q][core_want].view(np.uint32)), (t, q)
+            assert np.array_equal(ev[q].view(np.uint32), g_h[q][ei_got[q]].view(np.uint32)), (t, q)
+        w_h = oracle.merge(w_h, wl.lr, core_want, cv, ei_got, ev)
+        w_g = w.cpu().numpy()
+        assert np.all(np.abs(w_g - w_h) <= 1e-6 * np.abs(w_h) + 1e-12), "merge tolerance, t=%d" % t
+        assert np.array_equal(w_g.view(np.uint32), w_h.view(np.uint32)), "merge bits, t=%d" % t
+        for q in range(W):
+            assert np.array_equal(core_out[q].cpu().numpy().view(np.uint32), w_h[core_want].view(np.uint32)), (t, q)
+            assert np.array_equal(expl_out[q].cpu().numpy().view(np.uint32), w_h[ei_got[q]].view(np.uint32)), (t, q)
+        if w_local[W - 1] is not None:
+            _, _, want_local = oracle.pull(w_h, core_want, ei_got[W - 1], local_h)
+            assert np.array_equal(w_local[W - 1].cpu().numpy().view(np.uint32), want_local.view(np.uint32)), t
+        del cv, ev, w_g, core_out, expl_out, w_local
+        print("t=%d checked (%.1f s)" % (t, time.time() - t0), flush=True)
+
+    # the iteration before a reselection as algorithm 1 has it: every update applied, significance of the new model
+    S2 = sd.dense_update_score(w, g, wl.lr, wl.c)
+    sd.synchronize()
+    w_o, S_o = oracle.dense_update_score(w_h, g_h, wl.lr, wl.c)
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), w_o.view(np.uint32)), "dense update bits"
+    assert np.array_equal(S2.cpu().numpy().view(np.uint32), S_o.view(np.uint32)), "dense score bits"
+    print("dense update ok (%.1f s)" % (time.time() - t0), flush=True)
+    sd.close()
+    pool.shutdown()

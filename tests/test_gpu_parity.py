@@ -42,7 +42,7 @@ def host_tile_offsets(idx, tile_start):
 
 
 def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, check=True, hint=False, per_tile_tail=False,
-                  clobber_after_select=False, hint_mode=0):
+                  clobber_after_select=False, hint_mode=0, as_scored=True, refill_before_pack=False):
     """One reselect iteration on the GPU and in the oracle; returns both results."""
     seg_off = [int(x) for x in wl.segment_offsets()]
     ks, ms = [int(x) for x in wl.k_seg()], [int(x) for x in wl.m_seg()]
@@ -64,7 +64,11 @@ def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, chec
     if clobber_after_select:        # probe: values that can then only come from what the scoring pass kept
         for x in g:
             x.zero_()
-    core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)
+    if refill_before_pack:          # the same buffers get the next updates: the pack (no flag) must extract those
+        g_h = wl.gradients(iteration + 1000)
+        for x, y in zip(g, g_h):
+            x.copy_(to_dev(y))
+    core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch, updates_as_scored=as_scored)
     sd.merge(w, wl.lr, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
     core_out, expl_out = sd.pull(w, epoch, core_idx, core_off, expl_idx, expl_off)
     sd.synchronize()
@@ -78,7 +82,7 @@ def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, chec
     if not check:
         return got, None
     so = None if wl.n_seg == 1 and wl.seg_off is None else seg_off
-    S_o = oracle.score(w_h, g_h, wl.c)
+    S_o = oracle.score(w_h, wl.gradients(iteration), wl.c)
     core_o = oracle.select_core(S_o, ks, so)
     ei_o = [oracle.sample_explore(wl.n, core_o, workloads.EXPLORE_SEED, iteration, q, ms, so) for q in range(wl.W)]
     packs = [oracle.pack(g_h[q], core_o, ei_o[q]) for q in range(wl.W)]
@@ -317,7 +321,7 @@ def test_speculative_pack_worker_counts(W):
         S = sd.score(w, g, wl.c)
         core_idx, core_bits, core_off, epoch = sd.select_core(S, [k], reuse_histogram=True)
         expl_idx, expl_off = sd.sample_explore(core_bits, [k], t, [m], 0, W)
-        core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)
+        core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch, updates_as_scored=True)
         sd.synchronize()
         core_o = oracle.select_core(oracle.score(w_h, g_h, wl.c), k)
         assert np.array_equal(u32(core_idx), core_o), t
@@ -348,6 +352,30 @@ def test_speculative_pack_really_uses_the_captured_values():
         assert np.array_equal(f32bits(got["core_val"][q][inside]), f32bits(want["packs"][q][0][inside]))
         assert not np.any(got["core_val"][q][~inside])       # the ragged last tile is gathered: zeros
         assert not np.any(got["expl_val"][q])                # explorer values are gathered: zeros
+    sd.close()
+
+
+def test_pack_without_the_flag_reads_the_buffers_it_is_given():
+    """The update buffers are refilled in place between the scoring pass and the pack (what a training loop that
+    reuses its buffers does between two iterations): without SLIMDP_PACK_UPDATES_AS_SCORED the pack must extract the
+    new contents although a capture of the old ones exists; a table of other arrays under the flag is refused."""
+    wl = workloads.TINY.scaled(200_003)
+    sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
+    sd.set_option("speculative_pack", 1)
+    run_iteration(wl, iteration=0, sd=sd, check=False)
+    got, want = run_iteration(wl, iteration=1, sd=sd, as_scored=False, refill_before_pack=True)
+    assert_iteration_matches(wl, got, want)
+    # the flag with a different table: an error, nothing launched
+    w = to_dev(wl.weights())
+    g = [to_dev(x) for x in wl.gradients(2)]
+    S = sd.score(w, g, wl.c)
+    core_idx, core_bits, core_off, epoch = sd.select_core(S, [wl.k], reuse_histogram=True)
+    expl_idx, expl_off = sd.sample_explore(core_bits, [wl.k], 2, [wl.m], 0, wl.W)
+    other = [x.clone() for x in g]
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.pack(other, core_idx, core_off, expl_idx, expl_off, epoch, updates_as_scored=True)
+    assert e.value.code == binding.ERR_INVALID_ARG
+    sd.synchronize()
     sd.close()
 
 
@@ -512,7 +540,9 @@ def test_multi_iteration_loop_scaled(announce):
         if announce:
             sd.set_option("explore_hint_mode", 0 if (t + 1) % wl.reselect_every == 0 else 1)
             sd.explore_hint([k], t + 1, [m], 0, wl.W)
-        core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)
+        # only a reselecting iteration packs the updates its scoring pass saw
+        core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch,
+                                     updates_as_scored=(t % wl.reselect_every == 0))
         sd.merge(w, wl.lr, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
         ei_o = [oracle.sample_explore(wl.n, core_o, workloads.EXPLORE_SEED, t, q, m) for q in range(wl.W)]
         for q in range(wl.W):
