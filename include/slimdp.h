@@ -161,6 +161,20 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
                        uint32_t* core_idx, uint32_t* core_bits, uint32_t* core_off,
                        uint64_t* core_epoch);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): the same selection as slimdp_select_core for a flat model (one segment) without a context.
+ * Calls no hipMalloc / hipFree: the workspace is a fixed array of 5 MiB inside the library's device image (every GPU
+ * the library runs on holds its own copy until the process ends), which serves n <= SLIMDP_STATIC_MAX_N
+ * parameters; a larger n is refused with SLIMDP_ERR_OUT_OF_RANGE.  Runs on the current device, asynchronously on
+ * hip_stream (NULL = the default stream).  All calls on one GPU share that GPU's array: calls that overlap in time
+ * on one GPU (different streams or threads) race; serialise them.  Nothing else is shared with contexts.
+ *   score [dev, n]; k <= n; core_idx [dev, k] ascending; core_bits [dev, ceil(n/32)];
+ *   core_off [dev, slimdp_num_tiles(n, 1, {0, n}) + 1].  Errors: message via slimdp_last_error(NULL).
+ * Conditions only the device could detect are not reported (there is no context to ask). */
+#define SLIMDP_STATIC_MAX_N (1u << 20)
+int slimdp_select_core_static(const float* score, uint64_t n, uint64_t k, uint32_t* core_idx, uint32_t* core_bits,
+                              uint32_t* core_off, void* hip_stream);
+
 /* Exploration operator T_R^k (section 3.1 item 2; section 3.3 step 2) for the workers
  * worker0 .. worker0+n_workers-1: each draws, per segment s, m_seg[s] parameters uniformly
  * without replacement from those outside the core, afresh for every (worker, iteration).

@@ -33,6 +33,7 @@ EXPORTS = [
     "slimdp_tile_starts", "slimdp_last_error", "slimdp_synchronize", "slimdp_set_option",
     "slimdp_score", "slimdp_dense_update_score", "slimdp_select_core", "slimdp_sample_explore", "slimdp_explore_hint", "slimdp_tile_offsets",
     "slimdp_pack", "slimdp_merge", "slimdp_pull", "slimdp_core_signature", "slimdp_debug_philox",
+    "slimdp_select_core_static",
 ]
 
 
@@ -98,6 +99,8 @@ def load() -> C.CDLL:
     L.slimdp_pull.restype = C.c_int
     L.slimdp_debug_philox.argtypes = [_vp, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64, _vp]
     L.slimdp_debug_philox.restype = C.c_int
+    L.slimdp_select_core_static.argtypes = [_vp, C.c_uint64, C.c_uint64, _vp, _vp, _vp, _vp]
+    L.slimdp_select_core_static.restype = C.c_int
     _lib = L
     return L
 
@@ -137,6 +140,19 @@ def _table(ts: Optional[Sequence]) -> "C.Array":
     for j, t in enumerate(ts):
         arr[j] = _ptr(t)
     return arr
+
+
+STATIC_MAX_N = 1 << 20
+
+
+def select_core_static(score, k: int, core_idx, core_bits, core_off, stream=None) -> None:
+    """slimdp_select_core_static: flat selection without a context; every array is the caller's (nothing is allocated)."""
+    import torch
+    st = stream if stream is not None else torch.cuda.current_stream()
+    rc = load().slimdp_select_core_static(_ptr(score), score.numel(), int(k), _ptr(core_idx), _ptr(core_bits),
+                                          _ptr(core_off), C.c_void_p(st.cuda_stream))
+    if rc != OK:
+        raise SlimDPError(rc, load().slimdp_last_error(None).decode())
 
 
 class SlimDP:

@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -161,9 +162,10 @@ struct slimdp_ctx {
 
 namespace {
 
-void carve(slimdp_ctx* c, Carver& cv)
+// Tables and the buffers of the core selection (all that a selection without explorers needs).
+void carve_core(slimdp_ctx* c, Carver& cv)
 {
-    const size_t T = c->T, S = c->n_seg, B = c->maxW;
+    const size_t T = c->T, S = c->n_seg;
     c->d_tile_start = cv.take<uint32_t>(T + 1);
     c->d_tile_seg = cv.take<uint32_t>(T);
     c->d_seg_first_tile = cv.take<uint32_t>(S + 1);
@@ -178,6 +180,13 @@ void carve(slimdp_ctx* c, Carver& cv)
     c->c_cnt_sel = cv.take<uint32_t>(T);
     c->c_cnt_tie = cv.take<uint32_t>(T);
     c->c_tie_pre = cv.take<uint32_t>(T + 1);
+    c->c_chunk_sum = cv.take<uint32_t>(2 * c->n_chunks);
+}
+
+void carve(slimdp_ctx* c, Carver& cv)
+{
+    const size_t T = c->T, S = c->n_seg, B = c->maxW;
+    carve_core(c, cv);
     c->e_state = cv.take<SegState>(B * S);
     c->e_draw_state = cv.take<SegState>(B * S);
     c->e_hist = cv.take<uint32_t>(B * S * H_STRIDE);
@@ -188,7 +197,6 @@ void carve(slimdp_ctx* c, Carver& cv)
     c->e_list_count = cv.take<uint32_t>(64);          // [0] candidates listed, [1] ties listed
     c->e_tie_list = cv.take<uint32_t>(TIE_CAP);
     c->e_chunk_sum = cv.take<uint32_t>(2 * B * c->n_chunks);   // tie sums, then offset sums
-    c->c_chunk_sum = cv.take<uint32_t>(2 * c->n_chunks);
     c->e_list = cv.take<uint4>(c->list_cap);
     c->e_cand_keys = cv.take<uint32_t>(B * c->keys_stride);
     c->e_cnt_cand = cv.take<uint32_t>(B * T * SUBS);
@@ -676,10 +684,10 @@ int slimdp_dense_update_score(slimdp_ctx* ctx, float* w, const float* const* g, 
     return score_impl(ctx, w, g, W, c, score, w, lr);
 }
 
-int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_seg, uint32_t flags, uint32_t* core_idx,
-                       uint32_t* core_bits, uint32_t* core_off, uint64_t* core_epoch)
+// The selection itself, for a context whose device pointers may also lie in the static scratch array.
+static int select_core_impl(slimdp_ctx* ctx, const float* score, const uint64_t* k_seg, uint32_t flags, uint32_t* core_idx,
+                            uint32_t* core_bits, uint32_t* core_off, uint64_t* core_epoch)
 {
-    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
     if (!score || !k_seg || !core_bits || !core_off || !core_epoch)
         return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_select_core: NULL argument");
     uint64_t K = 0;
@@ -739,6 +747,84 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
     if (spec_sel) { ctx->spec.core_epoch = ctx->epoch; ctx->spec.next_written = true; }
     else ctx->spec.core_epoch = 0;
     return SLIMDP_OK;
+}
+
+int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_seg, uint32_t flags, uint32_t* core_idx,
+                       uint32_t* core_bits, uint32_t* core_off, uint64_t* core_epoch)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    return select_core_impl(ctx, score, k_seg, flags, core_idx, core_bits, core_off, core_epoch);
+}
+
+// ------------------------------------------------------------------------------------------
+// Core selection for callers that cannot allocate: no context, no hipMalloc.  The workspace is
+// a file-scope array in device memory (one copy per GPU, held until the process ends); the
+// host uses its per-device address obtained from the runtime, never the symbol itself.
+// ------------------------------------------------------------------------------------------
+#define SLIMDP_STATIC_SCRATCH_BYTES (5u << 20)
+static __device__ __align__(256) unsigned char scratch[SLIMDP_STATIC_SCRATCH_BYTES];
+
+namespace {
+struct StaticDev { void* ptr = nullptr; int cus = 0; };
+constexpr int STATIC_MAX_DEVICES = 64;
+StaticDev g_static[STATIC_MAX_DEVICES];
+std::mutex g_static_mu;
+}  // namespace
+
+int slimdp_select_core_static(const float* score, uint64_t n, uint64_t k, uint32_t* core_idx, uint32_t* core_bits,
+                              uint32_t* core_off, void* hip_stream)
+{
+    if (!score || !core_bits || !core_off || (k && !core_idx))
+        return fail(nullptr, SLIMDP_ERR_INVALID_ARG, "slimdp_select_core_static: NULL argument");
+    if (n == 0 || n > SLIMDP_STATIC_MAX_N)
+        return fail(nullptr, SLIMDP_ERR_OUT_OF_RANGE, "slimdp_select_core_static: n=%llu outside [1, %u] (the static workspace "
+                    "serves at most SLIMDP_STATIC_MAX_N parameters; larger models need a context)",
+                    (unsigned long long)n, (unsigned)SLIMDP_STATIC_MAX_N);
+    if (k > n) return fail(nullptr, SLIMDP_ERR_OUT_OF_RANGE, "slimdp_select_core_static: k exceeds n");
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return hip_fail(nullptr, e, "hipGetDevice");
+    if (device < 0 || device >= STATIC_MAX_DEVICES)
+        return fail(nullptr, SLIMDP_ERR_INVALID_ARG, "slimdp_select_core_static: device %d not supported", device);
+    StaticDev sdv;
+    {
+        std::lock_guard<std::mutex> lock(g_static_mu);
+        if (!g_static[device].ptr) {          // once per device, with that device current: this GPU's copy of the array
+            void* p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p) return hip_fail(nullptr, e, "hipGetSymbolAddress(scratch)");
+            int cus = 0;
+            e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
+            if (e != hipSuccess) return hip_fail(nullptr, e, "hipDeviceGetAttribute");
+            g_static[device].cus = cus > 0 ? cus : 256;
+            g_static[device].ptr = p;
+        }
+        sdv = g_static[device];
+    }
+    // a context on the stack whose device pointers lie inside this GPU's array (host members only, nothing allocated on the device)
+    slimdp_ctx tmp;
+    const uint64_t so[2] = {0, n};
+    tmp.n = n; tmp.maxW = 1; tmp.n_seg = 1; tmp.seed = 0;
+    tmp.stream = static_cast<hipStream_t>(hip_stream);
+    tmp.device = device; tmp.cus = sdv.cus;
+    tmp.seg_off.assign(so, so + 2);
+    tmp.T = (uint32_t)count_tiles(n, 1, so);
+    tmp.keys_stride = align_up(n, TILE) + TILE;
+    tmp.n_chunks = (tmp.T + SCAN_CHUNK - 1) / SCAN_CHUNK;
+    Carver cv(static_cast<char*>(sdv.ptr));
+    carve_core(&tmp, cv);
+    if (cv.pos > SLIMDP_STATIC_SCRATCH_BYTES)
+        return fail(nullptr, SLIMDP_ERR_WORKSPACE, "slimdp_select_core_static: %zu bytes of workspace needed, %u available",
+                    cv.pos, (unsigned)SLIMDP_STATIC_SCRATCH_BYTES);
+    // the array keeps the previous call's contents: tables for this n, flags cleared (the histogram is cleared by the selection)
+    hipLaunchKernelGGL(k_flat_tables, dim3((tmp.T + 1 + 255) / 256), dim3(256), 0, tmp.stream, tmp.d_tile_start, tmp.d_tile_seg,
+                       tmp.d_seg_first_tile, tmp.d_flags, tmp.T, (uint32_t)n);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(nullptr, e, "k_flat_tables");
+    uint64_t epoch = 0;
+    const int rc = select_core_impl(&tmp, score, &k, 0u, core_idx, core_bits, core_off, &epoch);
+    if (rc) g_create_error = tmp.err;
+    return rc;
 }
 
 int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint64_t* k_seg, uint32_t worker0,

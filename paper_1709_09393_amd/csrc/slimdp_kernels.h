@@ -26,6 +26,18 @@ __global__ __launch_bounds__(256) void k_fill_u32(uint32_t* __restrict__ p, uint
         p[i] = v;
 }
 
+// Tile tables of a flat model of n parameters, and the 64 flag words cleared (for a workspace that keeps the
+// contents of an earlier, differently sized call).  grid ceil((T+1)/256).
+__global__ __launch_bounds__(256) void k_flat_tables(uint32_t* __restrict__ tile_start, uint32_t* __restrict__ tile_seg,
+                                                     uint32_t* __restrict__ seg_first_tile, uint32_t* __restrict__ flags,
+                                                     uint32_t T, uint32_t n)
+{
+    const uint32_t t = blockIdx.x * 256 + threadIdx.x;
+    if (t < T) { tile_start[t] = t * TILE; tile_seg[t] = 0; }
+    if (t == T) { tile_start[T] = n; seg_first_tile[0] = 0; seg_first_tile[1] = T; }
+    if (t < 64) flags[t] = 0;
+}
+
 // Writes the selection state of segments [seg0, seg0+count) for every batch.
 // core != 0: fixed score-bit levels; else explorer levels derived from (bound_m1, shift0).
 // Several fills in one launch (a launch costs more than a small fill).
