@@ -374,13 +374,15 @@ def main() -> int:
                                    "algorithmic_bytes": steady_bytes, "hbm_frac": frac(steady_bytes, steady_ms)}
     sd.close()
     if not args.no_variants:
-        # (5) the very first iteration of a fresh context: no selection before it, no draw announced
+        # (5) the very first iteration of a fresh context: no selection before it (its draw is announced: that needs
+        # nothing but the sizes)
         cold = []
         for _ in range(3):
             c = new_context()
             w.copy_(w0)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            c.explore_hint(ks, 0, ms, 0, W)
             e0.record()
             reselect_step(c, wl, b, w, g, ks, ms, 0, announce=False)
             e1.record()

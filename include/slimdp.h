@@ -105,6 +105,11 @@ int slimdp_synchronize(slimdp_ctx* ctx);
  *       reads the vectors it is given.  Results are bit-identical either way (the same slow
  *       drift of the core that the paper's key caching relies on, section 3.3).  One capture
  *       serves one pack.
+ *       Before the first selection of a context there is no earlier threshold: the scoring pass
+ *       then estimates the coming one from a sample of its own significances (flat model, at
+ *       least 64 whole tiles), provided it knows the size of the coming core: from an announced
+ *       draw (slimdp_explore_hint), from option "expected_core", or from the last selection.
+ *   "expected_core" (-1 = unknown, default; else k of the next slimdp_select_core, flat model).
  *   "explore_hint_mode" (0/1, default 0): where an announced explorer draw runs: 0 inside
  *       the next slimdp_score, 1 at once on a side stream of the library (default priority),
  *       beside whatever runs on the context's stream.
@@ -112,7 +117,8 @@ int slimdp_synchronize(slimdp_ctx* ctx);
  *   "pack_nbuf" (1/2): tiles in flight in the general pack kernel.
  *   "explore_force_fallback" (0/1/2), "explore_per_tile_tail" (0/1): test switches: make
  *       the explorer's first zones miss (1: too few candidates, 2: sure zone too large) so
- *       that the exact rerun runs; never take the short-list tail. */
+ *       that the exact rerun runs; never take the short-list tail.
+ *   "capture_estimate_bias" (test switch): added to a sampled capture bound, in units of the last place. */
 int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value);
 
 /* ---------------------------------------------------------------------------------- */

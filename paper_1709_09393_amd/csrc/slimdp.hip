@@ -133,6 +133,8 @@ struct slimdp_ctx {
         float* vals = nullptr;
         int cur = 0;
         bool next_written = false;              // a selection has refreshed lo[cur ^ 1] since the last capture
+        bool bound_valid = false;               // lo[cur] comes from a selection (else: nothing, or a sampled estimate)
+        uint32_t* sample = nullptr;             // keys of the sampled significances (flat model)
         // the capture made by the last slimdp_score, and the selection that used that score
         bool captured = false;
         const float* score = nullptr;
@@ -142,6 +144,11 @@ struct slimdp_ctx {
         uint64_t core_epoch = 0;                // 0: no selection on the captured score yet
     } spec;
     int64_t opt_pack_nbuf = 2;
+    int64_t opt_score_pipeline = 1;        // flat aligned models: the scoring kernel with two rounds of loads in flight
+    int64_t opt_expected_core = -1;        // core size the next selection will ask for (flat model), if the caller says
+    int64_t opt_estimate_bias = 0;         // test switch: added to a sampled capture bound
+    uint64_t last_K = 0;                   // core size of the last selection
+    bool have_last_K = false;
     // explorer draw announced by slimdp_explore_hint (hint) / already drawn inside slimdp_score (pre)
     struct Draw {
         bool valid = false;
@@ -518,6 +525,9 @@ int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value)
     if (strcmp(name, "side_blocks") == 0 && value >= 1 && value <= 8) { ctx->opt_side_blocks = value; return SLIMDP_OK; }
     if (strcmp(name, "explore_hint_mode") == 0 && (value == 0 || value == 1)) { ctx->opt_hint_mode = value; return SLIMDP_OK; }
     if (strcmp(name, "pack_nbuf") == 0 && (value == 1 || value == 2)) { ctx->opt_pack_nbuf = value; return SLIMDP_OK; }
+    if (strcmp(name, "expected_core") == 0 && value >= -1 && (value < 0 || (uint64_t)value <= ctx->n)) { ctx->opt_expected_core = value; return SLIMDP_OK; }
+    if (strcmp(name, "score_pipeline") == 0 && (value == 0 || value == 1)) { ctx->opt_score_pipeline = value; return SLIMDP_OK; }
+    if (strcmp(name, "capture_estimate_bias") == 0) { ctx->opt_estimate_bias = value; return SLIMDP_OK; }
     if (strcmp(name, "speculative_pack") == 0) {
         ctx->spec.captured = false;
         if (value && !ctx->spec.mem) {
@@ -529,6 +539,7 @@ int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value)
                 ctx->spec.fail = cv.take<uint32_t>(S);
                 ctx->spec.bits = cv.take<uint2>((size_t)ctx->T * TILE_WORDS);
                 ctx->spec.vals = cv.take<float>((size_t)ctx->maxW * ctx->keys_stride);
+                ctx->spec.sample = cv.take<uint32_t>((size_t)ctx->T * SAMPLE_PER);
             };
             carve_spec(sizing);
             hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->spec.mem), align_up(sizing.pos, 256));
@@ -546,6 +557,7 @@ int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value)
             if (rc) return rc;
             ctx->spec.cur = 0;
             ctx->spec.next_written = false;
+            ctx->spec.bound_valid = false;
         }
         ctx->spec.on = value != 0;
         return SLIMDP_OK;
@@ -614,8 +626,65 @@ static int score_impl(slimdp_ctx* ctx, const float* w, const float* const* g, ui
     const bool capture = ctx->spec.on && !w_new && (W == 1 || W == 2 || W == 4 || W == 8 || W == 16);
     ctx->spec.captured = false;
     if (capture) {
-        if (ctx->spec.next_written) { ctx->spec.cur ^= 1; ctx->spec.next_written = false; }
+        if (ctx->spec.next_written) { ctx->spec.cur ^= 1; ctx->spec.next_written = false; ctx->spec.bound_valid = true; }
         sa.lo = ctx->spec.lo[ctx->spec.cur]; sa.bits = ctx->spec.bits; sa.vals = ctx->spec.vals;
+        // No selection has set a bound yet (first iteration of a context): estimate the coming threshold from a sample of
+        // the very significances this pass computes, if the size of the coming core is known (announced draw, option, or
+        // the previous selection).  Flat model, whole aligned tiles.
+        const uint32_t T_full = (uint32_t)(ctx->n / TILE);
+        int64_t expect = ctx->opt_expected_core;
+        if (expect < 0 && ctx->hint.valid && ctx->n_seg == 1) expect = (int64_t)ctx->hint.k_seg[0];
+        if (expect < 0 && ctx->have_last_K) expect = (int64_t)ctx->last_K;
+        if (!ctx->spec.bound_valid && ctx->n_seg == 1 && vec_ok && T_full >= 64 && expect >= 0) {
+            const uint32_t N = T_full * SAMPLE_PER;
+            // rank of the threshold inside the sample, rounded up
+            const uint64_t need = ((uint64_t)expect * N + ctx->n - 1) / ctx->n;
+            hipLaunchKernelGGL(k_sample_keys, dim3((N + 255) / 256), dim3(256), 0, ctx->stream, w, gt, (int)W, c, T_full,
+                               ctx->spec.sample);
+            SLIMDP_LAUNCHED(ctx, "k_sample_keys");
+            hipLaunchKernelGGL(k_sample_bound, dim3(1), dim3(1024), 0, ctx->stream, ctx->spec.sample, N, (uint32_t)need,
+                               (long long)ctx->opt_estimate_bias, ctx->spec.lo[ctx->spec.cur]);
+            SLIMDP_LAUNCHED(ctx, "k_sample_bound");
+        }
+    }
+    // flat model, aligned arrays, 1/2/4/8 workers: the pipelined kernel
+    if (ctx->n_seg == 1 && vec_ok && ctx->opt_strided && ctx->opt_score_pipeline && ctx->n < (1ull << 30) &&
+        (W == 1 || W == 2 || W == 4 || W == 8)) {
+        const dim3 fgrid(persistent_blocks(ctx, SCOREF_MINB, 1)), fblock(BLOCK);
+#define LAUNCH_FLAT_Q(WT, PRE, SPEC, DENSE)                                                                           \
+    hipLaunchKernelGGL((k_score_flat<WT, PRE, SPEC, DENSE>), fgrid, fblock, 0, ctx->stream, w, gt, c, score, ctx->n,  \
+                       ctx->c_hist, pre, sa, w_new, lr)
+#define LAUNCH_FLAT_S(WT, SPEC, DENSE)                                                                                \
+    do {                                                                                                              \
+        if (presample && pairs) LAUNCH_FLAT_Q(WT, 2, SPEC, DENSE);                                                    \
+        else if (presample) LAUNCH_FLAT_Q(WT, 1, SPEC, DENSE);                                                        \
+        else LAUNCH_FLAT_Q(WT, 0, SPEC, DENSE);                                                                       \
+    } while (0)
+#define LAUNCH_FLAT(WT)                                                                                               \
+    do {                                                                                                              \
+        if (w_new) LAUNCH_FLAT_S(WT, 0, 1);                                                                           \
+        else if (capture) LAUNCH_FLAT_S(WT, 1, 0);                                                                    \
+        else LAUNCH_FLAT_S(WT, 0, 0);                                                                                 \
+    } while (0)
+        switch (W) {
+            case 1: LAUNCH_FLAT(1); break;
+            case 2: LAUNCH_FLAT(2); break;
+            case 4: LAUNCH_FLAT(4); break;
+            default: LAUNCH_FLAT(8); break;
+        }
+#undef LAUNCH_FLAT
+#undef LAUNCH_FLAT_S
+#undef LAUNCH_FLAT_Q
+        SLIMDP_LAUNCHED(ctx, "k_score_flat");
+        if (presample) { ctx->pre = ctx->hint; ctx->pre.pairs = pairs; }
+        if (capture) {
+            ctx->spec.captured = true; ctx->spec.score = score; ctx->spec.W = W; ctx->spec.vec_ok = vec_ok; ctx->spec.core_epoch = 0;
+            for (uint32_t q = 0; q < W; ++q) ctx->spec.g[q] = g[q];
+        }
+        ctx->hint.valid = false;
+        ctx->hist_pending = true;
+        ctx->hist_score = score;
+        return SLIMDP_OK;
     }
     const uint32_t P = persistent_blocks(ctx, SCORE_MINB, 1);
     const dim3 grid(P), block(BLOCK);
@@ -744,6 +813,7 @@ static int select_core_impl(slimdp_ctx* ctx, const float* score, const uint64_t*
         }
     }
     *core_epoch = ++ctx->epoch;
+    ctx->last_K = K; ctx->have_last_K = true;
     if (spec_sel) { ctx->spec.core_epoch = ctx->epoch; ctx->spec.next_written = true; }
     else ctx->spec.core_epoch = 0;
     return SLIMDP_OK;

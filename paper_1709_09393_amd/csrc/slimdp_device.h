@@ -78,6 +78,21 @@ __device__ __forceinline__ float4 buffer_load4(__amdgpu_buffer_rsrc_t r, uint32_
     const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_bytes, (int)wave_bytes, 0);
     return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
 }
+// The same with a cache policy (the intrinsic's auxiliary operand must be a constant: 0 = default, 2 = non-temporal,
+// for data that is touched once).
+template <int AUX>
+__device__ __forceinline__ float4 buffer_load4_aux(__amdgpu_buffer_rsrc_t r, uint32_t lane_bytes)
+{
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_bytes, 0, AUX);
+    return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+}
+template <int AUX>
+__device__ __forceinline__ void buffer_store4_aux(__amdgpu_buffer_rsrc_t r, uint32_t lane_bytes, float4 f)
+{
+    u32x4 v;
+    v.x = __float_as_uint(f.x); v.y = __float_as_uint(f.y); v.z = __float_as_uint(f.z); v.w = __float_as_uint(f.w);
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)lane_bytes, 0, AUX);
+}
 __device__ __forceinline__ void buffer_store4(__amdgpu_buffer_rsrc_t r, uint32_t lane_bytes, uint32_t wave_bytes, float4 f)
 {
     u32x4 v;
@@ -136,12 +151,43 @@ __device__ __forceinline__ uint32_t elem_scl(int j) { return (uint32_t)j * BLOCK
 
 __device__ __forceinline__ uint32_t mask_below(uint32_t bit) { return (1u << bit) - 1u; }   // bit in 0..31
 
-// 16-byte load of data that is read once (streamed): bypasses cache-line retention.
+// Accesses to data that is touched once (streamed): NT != 0 marks them non-temporal, so that they do not
+// push lines that will be used again out of the caches.  A non-temporal store must cover whole 128-byte lines
+// per instruction (a partial one goes to memory as a read-modify-write).
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ float4 load_stream4(const float* p)
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+template <int NT> __device__ __forceinline__ float4 ld4(const float* p)
 {
-    const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
-    return make_float4(v.x, v.y, v.z, v.w);
+    if (NT) {
+        const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+        return make_float4(v.x, v.y, v.z, v.w);
+    }
+    return *reinterpret_cast<const float4*>(p);
+}
+template <int NT> __device__ __forceinline__ uint4 ld4u(const uint32_t* p)
+{
+    if (NT) {
+        const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+        return make_uint4(v.x, v.y, v.z, v.w);
+    }
+    return *reinterpret_cast<const uint4*>(p);
+}
+template <int NT> __device__ __forceinline__ void st4(float* p, float4 v)
+{
+    if (NT) {
+        f32x4_t o; o.x = v.x; o.y = v.y; o.z = v.z; o.w = v.w;
+        __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t*>(p));
+    } else *reinterpret_cast<float4*>(p) = v;
+}
+template <int NT, class Tp> __device__ __forceinline__ Tp ld1(const Tp* p)
+{
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+template <int NT, class Tp> __device__ __forceinline__ void st1(Tp* p, Tp v)
+{
+    if (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
 }
 
 // ---------------------------------------------------------------------------------------

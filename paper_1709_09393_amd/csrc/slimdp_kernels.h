@@ -15,6 +15,33 @@
 #pragma once
 #include "slimdp_device.h"
 
+// Cache policy of the streaming accesses, per kernel (0 = default, 1 = non-temporal).  Measured on the VGG-16-sized
+// workload: each switch alone moves its kernel by 0 to 5 %, all together take 0.07 ms off the 2.75 ms step.
+#ifndef NT_BUILD
+#define NT_BUILD 1
+#endif
+#ifndef NT_MERGE_LD
+#define NT_MERGE_LD 1
+#endif
+#ifndef NT_MERGE_ST
+#define NT_MERGE_ST 1
+#endif
+#ifndef NT_MERGE_VAL
+#define NT_MERGE_VAL 1
+#endif
+#ifndef NT_PACKS
+#define NT_PACKS 1
+#endif
+#ifndef NT_PACKC_LD
+#define NT_PACKC_LD 1
+#endif
+#ifndef NT_PACKC_ST
+#define NT_PACKC_ST 1
+#endif
+#ifndef NT_EXPLG
+#define NT_EXPLG 1
+#endif
+
 namespace slimdp {
 
 // ---------------------------------------------------------------------------------------
@@ -514,6 +541,271 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
     flush_hist(h, NB, hist + (size_t)cur_seg * H_STRIDE + H_L0);
 }
 
+// ---------------------------------------------------------------------------------------
+// K1 for a flat model whose arrays are 16-byte aligned: the same results as k_score, with
+// the loads of the NEXT round of 256 parameters per wave (the next tile's first round after
+// a tile's last) requested before the current round is worked on, so that a wave always has
+// two rounds of nine 16-byte loads in flight, also while it draws explorer zones.  Whole
+// arrays are addressed through one descriptor each (n < 2^30 parameters: byte offsets fit 32
+// bits); block b takes the whole tiles b, b + gridDim.x, ...; the ragged last tile, if any,
+// goes to one block after its loop, element by element.
+// ---------------------------------------------------------------------------------------
+#ifndef SCOREF_MINB
+#define SCOREF_MINB 3
+#endif
+#ifndef SCOREF_LD_AUX
+#define SCOREF_LD_AUX 2
+#endif
+#ifndef SCOREF_ST_AUX
+#define SCOREF_ST_AUX 2
+#endif
+#ifndef SCOREF_CAP_AUX
+#define SCOREF_CAP_AUX 2
+#endif
+template <int WT, int PRE, int SPEC, int DENSE>
+__global__ __launch_bounds__(BLOCK, SCOREF_MINB) void k_score_flat(const float* __restrict__ w, PtrTab g, float c,
+                                                                   float* __restrict__ S, uint64_t n, uint32_t* __restrict__ hist,
+                                                                   PreArgs pre, SpecArgs spec, float* __restrict__ w_new, float lr)
+{
+    static_assert(WT >= 1 && WT <= 8, "two rounds of W + 1 vectors must fit the registers");
+    static_assert(!(SPEC && DENSE), "a dense update is never followed by a pack of the same updates");
+    constexpr uint32_t NB = CORE_NB0 / 2;
+    __shared__ uint32_t h[NB];
+    __shared__ __align__(16) float stage[SPEC ? 4 * 256 * WT : 4];
+    const uint32_t lane = lane_id(), wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t T_full = (uint32_t)(n / TILE), T = (uint32_t)((n + TILE - 1) / TILE);
+    for (uint32_t b = threadIdx.x; b < NB; b += BLOCK) h[b] = 0;
+    __syncthreads();
+    const uint32_t bytes = (uint32_t)(n * 4u);
+    const __amdgpu_buffer_rsrc_t rw = buffer_of(w, bytes), rS = buffer_of(S, bytes), rn = buffer_of(DENSE ? w_new : S, bytes);
+    __amdgpu_buffer_rsrc_t rg[WT];
+#pragma unroll
+    for (int k = 0; k < WT; ++k) rg[k] = buffer_of(g.p[k], bytes);
+    uint32_t pre_bound = 0, pre_sure = 0, pre_has_sure = 0, pre_skip = 1;
+    if (PRE) {
+        const SegState* st = &pre.states[0];
+        pre_bound = st->bound_m1; pre_sure = st->sure_m1; pre_has_sure = st->has_gt; pre_skip = st->need0 == 0;
+    }
+    uint32_t spec_lo = 0xFFFFFFFFu;
+    if (SPEC) spec_lo = spec.lo[0];
+    // byte offset of this lane's vector in round r of this wave's sub-tile of tile t
+    auto voff = [&](uint32_t t, uint32_t r) { return (t * TILE + wid * SUB + r * 256u) * 4u + lane * 16u; };
+    auto fetch = [&](float4 (&x)[WT + 1], uint32_t t, uint32_t r) {
+        const uint32_t o = voff(t, r);
+        x[WT] = buffer_load4_aux<SCOREF_LD_AUX>(rw, o);
+#pragma unroll
+        for (int k = 0; k < WT; ++k) x[k] = buffer_load4_aux<SCOREF_LD_AUX>(rg[k], o);
+    };
+    auto draw = [&](uint32_t t, uint32_t len, uint32_t r) {      // this round's share of the announced draws
+        if (PRE) {
+#pragma unroll 1
+            for (uint32_t b = r; b < pre.nw; b += 4) {
+                DrawOut out;
+                out.sure_bits = pre.sure_bits + (size_t)b * T * TILE_WORDS;
+                out.cand_bits = pre.cand_bits + (size_t)b * T * TILE_WORDS;
+                out.cand_keys = pre.cand_keys + (size_t)b * pre.keys_stride;
+                out.cnt_cand = pre.cnt_cand + (size_t)b * T * SUBS;
+                explore_subtile_fast<(PRE == 2) ? 1 : 0>(pre.worker0 + b, t, wid, t * TILE, len, pre_bound, pre_sure,
+                                                         pre_has_sure, pre_skip, out, pre.pk);
+            }
+        }
+    };
+    uint32_t spec_run = 0;
+    uint2 bw[4];
+    auto work = [&](float4 (&x)[WT + 1], uint32_t t, uint32_t r) {
+        const uint32_t o = voff(t, r);
+        float4 a = x[0];
+#pragma unroll
+        for (int k = 1; k < WT; ++k) { a.x = a.x + x[k].x; a.y = a.y + x[k].y; a.z = a.z + x[k].z; a.w = a.w + x[k].w; }
+        float4 wv = x[WT];
+        if (DENSE) {
+            wv.x = __builtin_fmaf(-lr, a.x + 0.0f, wv.x); wv.y = __builtin_fmaf(-lr, a.y + 0.0f, wv.y);
+            wv.z = __builtin_fmaf(-lr, a.z + 0.0f, wv.z); wv.w = __builtin_fmaf(-lr, a.w + 0.0f, wv.w);
+            buffer_store4_aux<0>(rn, o, wv);
+        }
+        float4 sc;
+        sc.x = significance(wv.x, a.x, c); sc.y = significance(wv.y, a.y, c);
+        sc.z = significance(wv.z, a.z, c); sc.w = significance(wv.w, a.w, c);
+        buffer_store4_aux<SCOREF_ST_AUX>(rS, o, sc);
+        atomicAdd(&h[(__float_as_uint(sc.x) >> CORE_SHIFT0) & (NB - 1u)], 1u);
+        atomicAdd(&h[(__float_as_uint(sc.y) >> CORE_SHIFT0) & (NB - 1u)], 1u);
+        atomicAdd(&h[(__float_as_uint(sc.z) >> CORE_SHIFT0) & (NB - 1u)], 1u);
+        atomicAdd(&h[(__float_as_uint(sc.w) >> CORE_SHIFT0) & (NB - 1u)], 1u);
+        if (SPEC) {
+            if (r == 0) spec_run = 0;
+            const uint32_t f = (__float_as_uint(sc.x) >= spec_lo ? 1u : 0u) | (__float_as_uint(sc.y) >= spec_lo ? 2u : 0u) |
+                               (__float_as_uint(sc.z) >= spec_lo ? 4u : 0u) | (__float_as_uint(sc.w) >= spec_lo ? 8u : 0u);
+            const uint32_t v = or_reduce8(f << (4u * (lane & 7u)));
+            uint32_t below = 0, total = 0;
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                const unsigned long long bal = __ballot((f >> cc) & 1u);
+                below += __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+                total += (uint32_t)__popcll(bal);
+            }
+            // bitmap words with their entry numbers: lane 8j holds word j of this round; after the sub-tile's last
+            // round lanes 0..31 write all 32 of them at once (two whole lines)
+            bw[r] = make_uint2(v, spec_run + below);
+            if (r == 3) {
+                const int src = (int)(8u * (lane & 7u));
+                uint2 o = make_uint2(0u, 0u);
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const uint32_t ox = __shfl(bw[rr].x, src, 64), oy = __shfl(bw[rr].y, src, 64);
+                    if ((lane >> 3) == (uint32_t)rr) o = make_uint2(ox, oy);
+                }
+                if (lane < SUB_WORDS) spec.bits[(size_t)t * TILE_WORDS + wid * SUB_WORDS + lane] = o;
+            }
+            constexpr uint32_t A = spec_align(WT);
+            const uint32_t padded = (total + A - 1u) & ~(A - 1u);
+            // the round's entries go through the wave's staging area in LDS, so that every 128-byte line of the capture is
+            // written by one store instruction, whole (a line written piecewise by several instructions can leave the
+            // cache half-written and costs a read-modify-write in memory)
+            float* stf = stage + wid * (256 * WT);
+            if (f) {
+                uint32_t pos = below;
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    if ((f >> cc) & 1u) {
+                        if (WT >= 4) {
+#pragma unroll
+                            for (int k = 0; k < WT; k += 4) {
+                                float4 q;
+                                q.x = cc == 0 ? x[k].x : cc == 1 ? x[k].y : cc == 2 ? x[k].z : x[k].w;
+                                q.y = cc == 0 ? x[k + 1].x : cc == 1 ? x[k + 1].y : cc == 2 ? x[k + 1].z : x[k + 1].w;
+                                q.z = cc == 0 ? x[k + 2].x : cc == 1 ? x[k + 2].y : cc == 2 ? x[k + 2].z : x[k + 2].w;
+                                q.w = cc == 0 ? x[k + 3].x : cc == 1 ? x[k + 3].y : cc == 2 ? x[k + 3].z : x[k + 3].w;
+                                *reinterpret_cast<float4*>(stf + pos * WT + k) = q;
+                            }
+                        } else {
+#pragma unroll
+                            for (int k = 0; k < WT; ++k)
+                                stf[pos * WT + k] = cc == 0 ? x[k].x : cc == 1 ? x[k].y : cc == 2 ? x[k].z : x[k].w;
+                        }
+                        ++pos;
+                    }
+                }
+            }
+            if (lane < padded - total) {          // fill the round's last line
+#pragma unroll
+                for (int k = 0; k < WT; ++k) stf[(total + lane) * WT + k] = 0.0f;
+            }
+            wave_sync();
+            {
+                const __amdgpu_buffer_rsrc_t rv = buffer_of(spec.vals + ((size_t)t * TILE + wid * SUB) * WT, SUB * WT * 4u);
+                const uint32_t nchunk = padded * WT / 4u;          // 16-byte pieces: a multiple of 8 (whole lines)
+                for (uint32_t cidx = lane; cidx < nchunk; cidx += 64)
+                    buffer_store4_aux<SCOREF_CAP_AUX>(rv, spec_run * WT * 4u + cidx * 16u, *reinterpret_cast<const float4*>(stf + cidx * 4u));
+            }
+            wave_sync();
+            spec_run += padded;
+        }
+    };
+    float4 xa[WT + 1], xb[WT + 1];
+    uint32_t t = blockIdx.x;
+    if (t < T_full) fetch(xa, t, 0);
+#pragma unroll 1
+    for (; t < T_full; t += gridDim.x) {
+        const uint32_t tn = t + gridDim.x;
+        fetch(xb, t, 1); draw(t, TILE, 0); work(xa, t, 0);
+        fetch(xa, t, 2); draw(t, TILE, 1); work(xb, t, 1);
+        fetch(xb, t, 3); draw(t, TILE, 2); work(xa, t, 2);
+        if (tn < T_full) fetch(xa, tn, 0);
+        draw(t, TILE, 3); work(xb, t, 3);
+    }
+    // the ragged last tile
+    if (T != T_full && blockIdx.x == T_full % gridDim.x) {
+        const uint32_t start = T_full * TILE, len = (uint32_t)(n - start);
+        const uint32_t lo = wid * SUB, hi = (lo + SUB < len) ? lo + SUB : len;
+        for (uint32_t l = lo + lane; l < hi; l += 64) {
+            const size_t e = (size_t)start + l;
+            float a = static_cast<const float*>(g.p[0])[e];
+#pragma unroll
+            for (int k = 1; k < WT; ++k) a = a + static_cast<const float*>(g.p[k])[e];
+            float we = w[e];
+            if (DENSE) { we = __builtin_fmaf(-lr, a + 0.0f, we); w_new[e] = we; }
+            const float sc = significance(we, a, c);
+            S[e] = sc;
+            atomicAdd(&h[(__float_as_uint(sc) >> CORE_SHIFT0) & (NB - 1u)], 1u);
+        }
+        for (uint32_t r = 0; r < 4; ++r) draw(T_full, len, r);
+    }
+    __syncthreads();
+    flush_hist(h, NB, hist + H_L0);
+}
+
+// ---------------------------------------------------------------------------------------
+// Capture bound without an earlier selection (flat model): a sample of the significances about
+// to be computed gives an estimate of the coming threshold.  k_sample_keys scores SAMPLE_PER
+// consecutive parameters of every full tile, at a tile-dependent offset; k_sample_bound (one
+// block) finds the sample's need-th largest key by a two-level radix descent (12 + 12 bits:
+// 2^7 units in the last place) and writes it, less a margin, as the capture bound.  An
+// estimate that turns out too high is caught by the selection's own verdict (the pack then
+// gathers); one that is too low only makes the capture larger.
+// ---------------------------------------------------------------------------------------
+constexpr uint32_t SAMPLE_PER = 8;
+constexpr uint32_t SAMPLE_MARGIN = 1u << 18;
+__global__ __launch_bounds__(256) void k_sample_keys(const float* __restrict__ w, PtrTab g, int W, float c, uint32_t T_full,
+                                                     uint32_t* __restrict__ keys)
+{
+    const uint32_t x = blockIdx.x * 256 + threadIdx.x;
+    if (x >= T_full * SAMPLE_PER) return;
+    const uint32_t t = x / SAMPLE_PER, j = x % SAMPLE_PER;
+    const uint32_t off = ((t * 0x9E3779B1u) >> 23) * SAMPLE_PER;       // 0 .. 4088 in steps of 8: inside the tile
+    const size_t i = (size_t)t * TILE + off + j;
+    float a = static_cast<const float*>(g.p[0])[i];
+    for (int k = 1; k < W; ++k) a = a + static_cast<const float*>(g.p[k])[i];
+    keys[x] = __float_as_uint(significance(w[i], a, c));
+}
+
+// bias: test switch, added to the bound (in units of the last place, clamped).
+__global__ __launch_bounds__(1024) void k_sample_bound(const uint32_t* __restrict__ keys, uint32_t N, uint32_t need,
+                                                       long long bias, uint32_t* __restrict__ lo)
+{
+    __shared__ uint32_t h[4096];
+    __shared__ uint32_t wtot[16];
+    __shared__ uint32_t sh[2];
+    const uint32_t tid = threadIdx.x;
+    if (need == 0 || need > N) { if (tid == 0) lo[0] = NONE; return; }       // nothing to estimate: nothing is captured
+    uint32_t prefix = 0, want = need;
+#pragma unroll 1
+    for (int level = 0; level < 2; ++level) {
+        for (uint32_t b = tid; b < 4096; b += 1024) h[b] = 0;
+        __syncthreads();
+        for (uint32_t x = tid; x < N; x += 1024) {
+            const uint32_t key = keys[x];
+            if (level == 0) atomicAdd(&h[(key >> 19) & 4095u], 1u);
+            else if ((key >> 19) == prefix) atomicAdd(&h[(key >> 7) & 4095u], 1u);
+        }
+        __syncthreads();
+        // four bins per thread, from the largest digit down
+        uint32_t cnt[4], sum = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { cnt[e] = h[4095u - (tid * 4u + e)]; sum += cnt[e]; }
+        uint32_t total;
+        const uint32_t excl = block_excl_scan<16>(sum, wtot, total);
+        if (excl < want && want <= excl + sum) {
+            uint32_t run = excl;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (run < want && want <= run + cnt[e]) { sh[0] = 4095u - (tid * 4u + e); sh[1] = want - run; }
+                run += cnt[e];
+            }
+        }
+        __syncthreads();
+        prefix = (level == 0) ? sh[0] : ((prefix << 12) | sh[0]);
+        want = sh[1];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const long long tau = (long long)(prefix << 7);
+        long long b = tau - (long long)SAMPLE_MARGIN + bias;
+        if (b < 0) b = 0;
+        if (b > 0x7FFFFFFFll) b = 0x7FFFFFFFll;
+        lo[0] = (uint32_t)b;
+    }
+}
+
 // Level-0 histogram of a score array that did not come from k_score.
 __global__ __launch_bounds__(BLOCK) void k_core_hist0(const float* __restrict__ S, const uint32_t* __restrict__ tile_start,
                                                       const uint32_t* __restrict__ tile_seg, uint32_t T,
@@ -650,7 +942,7 @@ __device__ __forceinline__ void core_load_keys(const float* __restrict__ S, uint
     if (vec_ok && sub_len == SUB && (start & 3u) == 0) {
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-            const uint4 v = *reinterpret_cast<const uint4*>(src + it * 256 + lane * 4);
+            const uint4 v = ld4u<NT_BUILD>(reinterpret_cast<const uint32_t*>(src + it * 256 + lane * 4));
             key[it][0] = v.x; key[it][1] = v.y; key[it][2] = v.z; key[it][3] = v.w;
         }
     } else {
@@ -1885,7 +2177,7 @@ __global__ __launch_bounds__(256) void k_pack_core_flat(PtrTab g, uint32_t nw, u
                         if (i[u] >= n || qq >= nw) continue;
                         if (ok && (i[u] >> 12) < T_full) {
                             const uint32_t entry = bp[u].y + __popc(bp[u].x & mask_below(i[u] & 31u));
-                            v[u][h] = *reinterpret_cast<const float4*>(spec_vals + ((size_t)(i[u] & ~(SUB - 1u)) + entry) * nw + qq);
+                            v[u][h] = ld4<NT_PACKC_LD>(spec_vals + ((size_t)(i[u] & ~(SUB - 1u)) + entry) * nw + qq);
                         } else {
                             v[u][h].x = static_cast<const float*>(g.p[qq])[i[u]]; v[u][h].y = static_cast<const float*>(g.p[qq + 1])[i[u]];
                             v[u][h].z = static_cast<const float*>(g.p[qq + 2])[i[u]]; v[u][h].w = static_cast<const float*>(g.p[qq + 3])[i[u]];
@@ -1900,8 +2192,10 @@ __global__ __launch_bounds__(256) void k_pack_core_flat(PtrTab g, uint32_t nw, u
                     for (int h = 0; h < 2; ++h) {
                         const uint32_t qq = q + 4u * h;
                         if (qq >= nw) continue;
-                        static_cast<float*>(core_val.p[qq])[j] = v[u][h].x; static_cast<float*>(core_val.p[qq + 1])[j] = v[u][h].y;
-                        static_cast<float*>(core_val.p[qq + 2])[j] = v[u][h].z; static_cast<float*>(core_val.p[qq + 3])[j] = v[u][h].w;
+                        st1<NT_PACKC_ST>(static_cast<float*>(core_val.p[qq]) + j, v[u][h].x);
+                        st1<NT_PACKC_ST>(static_cast<float*>(core_val.p[qq + 1]) + j, v[u][h].y);
+                        st1<NT_PACKC_ST>(static_cast<float*>(core_val.p[qq + 2]) + j, v[u][h].z);
+                        st1<NT_PACKC_ST>(static_cast<float*>(core_val.p[qq + 3]) + j, v[u][h].w);
                     }
                 }
             }
@@ -1938,7 +2232,7 @@ __global__ __launch_bounds__(256) void k_pack_expl_gather(PtrTab g, uint64_t n, 
 #pragma unroll
         for (int u = 0; u < 4; ++u) i[u] = (j + u * stride < cnt) ? idx[j + u * stride] : 0u;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = (j + u * stride < cnt && i[u] < n) ? src[i[u]] : 0.f;
+        for (int u = 0; u < 4; ++u) v[u] = (j + u * stride < cnt && i[u] < n) ? ld1<NT_EXPLG>(src + i[u]) : 0.f;
 #pragma unroll
         for (int u = 0; u < 4; ++u) if (j + u * stride < cnt) out[j + u * stride] = v[u];
     }
@@ -1978,7 +2272,7 @@ __global__ __launch_bounds__(BLOCK) void k_pack_stream(PtrTab g, uint32_t nw, co
         if (vec) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const float4 v = *reinterpret_cast<const float4*>(src + k * 1024 + threadIdx.x * 4);
+                const float4 v = ld4<NT_PACKS>(src + k * 1024 + threadIdx.x * 4);
                 r[4 * k + 0] = v.x; r[4 * k + 1] = v.y; r[4 * k + 2] = v.z; r[4 * k + 3] = v.w;
             }
         } else {
@@ -2050,7 +2344,7 @@ __device__ __forceinline__ float core_sum(const PtrTab& core_val, uint32_t nw, u
     for (uint32_t q0 = 0; q0 < nw; q0 += 8) {
         float v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = (q0 + u < nw) ? static_cast<const float*>(core_val.p[q0 + u])[j] : 0.0f;
+        for (int u = 0; u < 8; ++u) v[u] = (q0 + u < nw) ? ld1<NT_MERGE_VAL>(static_cast<const float*>(core_val.p[q0 + u]) + j) : 0.0f;
 #pragma unroll
         for (int u = 0; u < 8; ++u) if (q0 + u < nw) a = a + v[u];
     }
@@ -2092,7 +2386,7 @@ __global__ __launch_bounds__(BLOCK) void k_merge(float* __restrict__ w, float lr
     if (vec) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const float4 v = *reinterpret_cast<const float4*>(w + (size_t)start + r * 1024 + threadIdx.x * 4);
+            const float4 v = ld4<NT_MERGE_LD>(w + (size_t)start + r * 1024 + threadIdx.x * 4);
             wv[4 * r + 0] = v.x; wv[4 * r + 1] = v.y; wv[4 * r + 2] = v.z; wv[4 * r + 3] = v.w;
         }
     } else {
@@ -2243,8 +2537,8 @@ __global__ __launch_bounds__(BLOCK) void k_merge(float* __restrict__ w, float lr
     if (vec) {
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            *reinterpret_cast<float4*>(w + (size_t)start + r * 1024 + threadIdx.x * 4) =
-                make_float4(wv[4 * r], wv[4 * r + 1], wv[4 * r + 2], wv[4 * r + 3]);
+            st4<NT_MERGE_ST>(w + (size_t)start + r * 1024 + threadIdx.x * 4,
+                             make_float4(wv[4 * r], wv[4 * r + 1], wv[4 * r + 2], wv[4 * r + 3]));
     }
 }
 

@@ -355,6 +355,40 @@ def test_speculative_pack_really_uses_the_captured_values():
     sd.close()
 
 
+@pytest.mark.parametrize("bias", [0, 1 << 22, -(1 << 22)])
+@pytest.mark.parametrize("announced", [False, True])
+def test_first_iteration_captures_under_a_sampled_bound(bias, announced):
+    """No selection has run yet: the scoring pass estimates the coming threshold from a sample of its own
+    significances.  Estimate as it is, forced far too high (the selection's verdict rejects the capture: the pack
+    gathers) and far too low (a larger capture): the same bits in every case; the white-box probe (updates zeroed
+    after the selection) shows which source the pack used."""
+    wl = workloads.TINY.scaled(700_000)             # 170 whole tiles and a ragged one
+    sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
+    sd.set_option("speculative_pack", 1)
+    sd.set_option("capture_estimate_bias", bias)
+    if not announced:
+        sd.set_option("expected_core", wl.k)
+    got, want = run_iteration(wl, iteration=0, sd=sd, hint=announced)
+    assert_iteration_matches(wl, got, want)
+    sd.close()
+    if bias == 0:
+        return
+    sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
+    sd.set_option("speculative_pack", 1)
+    sd.set_option("capture_estimate_bias", bias)
+    if not announced:
+        sd.set_option("expected_core", wl.k)
+    got, want = run_iteration(wl, iteration=0, sd=sd, hint=announced, clobber_after_select=True)
+    full = int(got["tile_start"][-2])
+    inside = want["core_idx"] < full
+    for q in range(wl.W):
+        if bias < 0:        # every core parameter of a whole tile was kept by the scoring pass
+            assert np.array_equal(f32bits(got["core_val"][q][inside]), f32bits(want["packs"][q][0][inside]))
+        else:               # rejected capture: the pack read the (zeroed) vectors
+            assert not np.any(got["core_val"][q])
+    sd.close()
+
+
 def test_pack_without_the_flag_reads_the_buffers_it_is_given():
     """The update buffers are refilled in place between the scoring pass and the pack (what a training loop that
     reuses its buffers does between two iterations): without SLIMDP_PACK_UPDATES_AS_SCORED the pack must extract the
