@@ -27,12 +27,17 @@ _CFLAGS = ["-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fas
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (a checker being built is not the product using it)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", *_CFLAGS, "-o", tmp, _SRC, "-lm"])
-        os.replace(tmp, _LIB)
-    return _LIB
+    """Compile the oracle with gcc (a checker being built is not the product using it).
+    SLIMDP_ORACLE_SRC / SLIMDP_ORACLE_LIB (both set): build and load another source file instead -- used only by
+    the test that plants mistakes in copies of the oracle and expects the pins to fail."""
+    src, lib_path = _SRC, _LIB
+    if os.environ.get("SLIMDP_ORACLE_SRC") and os.environ.get("SLIMDP_ORACLE_LIB"):
+        src, lib_path = os.environ["SLIMDP_ORACLE_SRC"], os.environ["SLIMDP_ORACLE_LIB"]
+    if force or not os.path.exists(lib_path) or os.path.getmtime(lib_path) < os.path.getmtime(src):
+        tmp = lib_path + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", *_CFLAGS, "-o", tmp, src, "-lm"])
+        os.replace(tmp, lib_path)
+    return lib_path
 
 
 _lib = None
@@ -85,6 +90,14 @@ def _declare(L: C.CDLL) -> None:
     L.oracle_splitmix64_mix.restype = C.c_uint64
     L.oracle_core_signature.argtypes = [_u32p, C.c_uint64]
     L.oracle_core_signature.restype = C.c_uint64
+    L.oracle_local_step.argtypes = [C.c_uint64, _f32p, _f32p, _f32p, C.c_float, C.c_int]
+    L.oracle_local_step.restype = None
+    L.oracle_quant_word.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64]
+    L.oracle_quant_word.restype = C.c_uint32
+    L.oracle_quantize.argtypes = [_f32p, C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32, _u8p, _f32p]
+    L.oracle_quantize.restype = None
+    L.oracle_dequantize.argtypes = [_u8p, _f32p, C.c_uint64, _f32p]
+    L.oracle_dequantize.restype = None
 
 
 def _as(a, dtype) -> np.ndarray:
@@ -275,3 +288,56 @@ def pull(w: np.ndarray, core_idx: np.ndarray, expl_idx: np.ndarray,
                       _p(co, C.c_float), _p(eo, C.c_float),
                       _p(wl, C.c_float) if wl is not None else None)
     return co, eo, wl
+
+
+# --------------------------------------------------------------------------------------
+# Worker side: local training stand-in (section 3.3 step 1)
+# --------------------------------------------------------------------------------------
+def local_step(w_local: np.ndarray, delta: Optional[np.ndarray], grad: np.ndarray, eta: float):
+    """One mini-batch step on a local model and the accumulation of its update; delta None starts a new
+    accumulation.  Returns (w_local_new, delta_new); the inputs are not modified."""
+    w = np.array(_as(w_local, np.float32), copy=True)
+    g = _as(grad, np.float32)
+    first = delta is None
+    # a new accumulation must not read the old one: it gets a buffer of NaNs
+    d = np.full_like(w, np.nan) if first else np.array(_as(delta, np.float32), copy=True)
+    assert g.shape == w.shape == d.shape
+    lib().oracle_local_step(w.size, _p(w, C.c_float), _p(d, C.c_float), _p(g, C.c_float), C.c_float(eta), int(first))
+    return w, d
+
+
+# --------------------------------------------------------------------------------------
+# Quantised wire values (section 2.2 end; section 4.2: 8 bits, buckets of 512)
+# --------------------------------------------------------------------------------------
+QUANT_BUCKET = 512
+
+
+def quant_word(seed: int, iteration: int, worker: int, kind: int, j: int) -> int:
+    return int(lib().oracle_quant_word(seed, iteration, worker, kind, j))
+
+
+def quantize(v: np.ndarray, seed: int, iteration: int, worker: int, kind: int):
+    """Returns (codes uint8 [count], scales float32 [ceil(count / 512)])."""
+    v = _as(v, np.float32)
+    code = np.empty(v.size, np.uint8)
+    scale = np.empty((v.size + QUANT_BUCKET - 1) // QUANT_BUCKET, np.float32)
+    lib().oracle_quantize(_p(v, C.c_float), v.size, seed, iteration, worker, kind, _p(code, C.c_uint8),
+                          _p(scale, C.c_float))
+    return code, scale
+
+
+def dequantize(code: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    code = _as(code, np.uint8)
+    scale = _as(scale, np.float32)
+    out = np.empty(code.size, np.float32)
+    lib().oracle_dequantize(_p(code, C.c_uint8), _p(scale, C.c_float), code.size, _p(out, C.c_float))
+    return out
+
+
+def wire_bytes(k: int, m: int, quantized: bool) -> int:
+    """Bytes one worker sends per push (section 3.5): core values only (keys cached), explorer <key, value> pairs;
+    quantised values take one byte each plus one binary32 scale per bucket of 512."""
+    if not quantized:
+        return 4 * (k + 2 * m)
+    nb = lambda c: (c + QUANT_BUCKET - 1) // QUANT_BUCKET
+    return k + 4 * nb(k) + m + 4 * nb(m) + 4 * m

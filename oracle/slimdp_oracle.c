@@ -11,8 +11,10 @@
  *
  * Every function is pinned by tests that do not go through this file:
  * published Philox known-answer vectors, closed forms, brute-force stable
- * argsort on tiny inputs, the dense (Plump-DP) special case, conservation
- * and hand-built collision cases.  No function here is "parity unpinned".
+ * argsort on tiny inputs, the dense (Plump-DP) special case, conservation,
+ * hand-built collision cases, exact rationals and (for the quantiser) grid
+ * points, the random draw fed through a known answer, and unbiasedness.
+ * No function here is "parity unpinned".
  *
  * Conventions: indices are 0-based uint32 (the paper counts from 1), values
  * are IEEE binary32, all arithmetic is round-to-nearest-even with no
@@ -221,8 +223,6 @@ void oracle_merge(uint64_t n, float* w, float lr, uint32_t W,
         if (scratch_hit[i]) w[i] = fmaf(-lr, scratch_acc[i], w[i]);
 }
 
-/* The same update in binary64 with no intermediate rounding to binary32:
- * the reference against which the binary32 tolerance is stated. */
 /* ------------------------------------------------------------------ */
 /* The last iteration before a reselection (algorithm 1: the branch    */
 /* (t+1) % q == 0; section 3.3 steps 3 and 6): every worker pushes its */
@@ -251,6 +251,8 @@ void oracle_dense_update_score(uint64_t n, uint32_t W, float* w, const float* co
     }
 }
 
+/* The update of oracle_merge in binary64 with no intermediate rounding to
+ * binary32: the reference against which the binary32 tolerance is stated. */
 void oracle_merge_f64(uint64_t n, const float* w_in, double* w_out, double lr, uint32_t W,
                       const uint32_t* core_idx, uint64_t k, const float* const* core_val,
                       const uint32_t* const* expl_idx, const float* const* expl_val,
@@ -265,14 +267,9 @@ void oracle_merge_f64(uint64_t n, const float* w_in, double* w_out, double lr, u
 }
 
 /* ------------------------------------------------------------------ */
-/* Pull and local Merge (section 3.3 steps 4 and 5): read the global  */
-/* model at the worker's communication set; if w_local is given,      */
-/* overwrite the local model at those indices and leave the rest.     */
-/* ------------------------------------------------------------------ */
-/* ------------------------------------------------------------------ */
 /* Signature of the cached keys (section 3.5: for the core only the    */
-/* values travel, "and the signature of the keys").  The paper does not */
-/* say which; the reading taken: the 64-bit sum, modulo 2^64, over the  */
+/* values travel, with a signature of the cached keys).  The paper does  */
+/* not say which; the reading taken: the 64-bit sum, modulo 2^64, over the  */
 /* list positions j of mix(core_idx[j] + 2^32 * j), mix being the       */
 /* output function of SplitMix64 (Steele, Lea, Flood, OOPSLA 2014).     */
 /* Order-sensitive, and a plain sum so that any schedule gives it.      */
@@ -293,6 +290,11 @@ uint64_t oracle_core_signature(const uint32_t* core_idx, uint64_t k)
     return sig;
 }
 
+/* ------------------------------------------------------------------ */
+/* Pull and local Merge (section 3.3 steps 4 and 5): read the global  */
+/* model at the worker's communication set; if w_local is given,      */
+/* overwrite the local model at those indices and leave the rest.     */
+/* ------------------------------------------------------------------ */
 void oracle_pull(const float* w, const uint32_t* core_idx, uint64_t k,
                  const uint32_t* expl_idx, uint64_t m,
                  float* core_out, float* expl_out, float* w_local)
@@ -304,5 +306,88 @@ void oracle_pull(const float* w, const uint32_t* core_idx, uint64_t k,
     for (uint64_t j = 0; j < m; ++j) {
         expl_out[j] = w[expl_idx[j]];
         if (w_local) w_local[expl_idx[j]] = expl_out[j];
+    }
+}
+
+
+/* ------------------------------------------------------------------ */
+/* LocalTrain (section 3.3 step 1; algorithm 1, first line of the      */
+/* worker loop): one mini-batch step of worker k on its LOCAL model,   */
+/*     w_k <- w_k - eta * grad,                                        */
+/* and the accumulation of the update over the p mini-batches between  */
+/* two communications, delta_k = grad_1 + grad_2 + ... in binary32 in  */
+/* mini-batch order (first != 0 starts a new accumulation).  The       */
+/* gradient itself is an input: there is no network here to           */
+/* differentiate.  One fmaf for the model.                             */
+/* ------------------------------------------------------------------ */
+void oracle_local_step(uint64_t n, float* w_local, float* delta, const float* grad, float eta, int first)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        w_local[i] = fmaf(-eta, grad[i], w_local[i]);
+        delta[i] = first ? grad[i] : delta[i] + grad[i];
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* Quantisation of the packed values (section 2.2, last sentences:     */
+/* the method composes with gradient quantisation; section 4.2: the    */
+/* comparison uses random quantisation, 8 bits, buckets of 512).       */
+/* Random quantisation after Alistarh et al. (QSGD): per bucket a      */
+/* scale, per value a sign and a level l in 0..127 on the grid         */
+/* scale * l / 127, rounded up with probability equal to the fraction  */
+/* so that the expectation is the value.  Readings (the paper fixes    */
+/* none): the scale is the bucket's largest magnitude (exact, order-   */
+/* free); 8 bits = sign + 7 level bits; arithmetic in binary32:        */
+/*   y = (|v| / scale) * 127, l = floor(y), up = u < y - l,            */
+/*   u = (random word >> 8) * 2^-24.                                   */
+/* The random word of element j of list `kind` (0 core values, 1       */
+/* explorer values) of a worker: word (j mod 4) of Philox4x32-10 with  */
+/* counter (j div 4, worker, iteration low, iteration high) and key    */
+/* (seed low ^ 0x51534744, seed high ^ kind): another key than the     */
+/* explorer's.  A bucket of zeros has scale 0 and levels 0.  Values    */
+/* must be finite.                                                     */
+/* ------------------------------------------------------------------ */
+#define ORACLE_QUANT_BUCKET 512u
+#define ORACLE_QUANT_LEVELS 127.0f
+
+uint32_t oracle_quant_word(uint64_t seed, uint64_t iteration, uint32_t worker, uint32_t kind, uint64_t j)
+{
+    uint32_t ctr[4] = { (uint32_t)(j >> 2), worker, (uint32_t)iteration, (uint32_t)(iteration >> 32) };
+    uint32_t key[2] = { (uint32_t)seed ^ 0x51534744u, (uint32_t)(seed >> 32) ^ kind };
+    uint32_t out[4];
+    oracle_philox4x32_10(ctr, key, out);
+    return out[j & 3u];
+}
+
+void oracle_quantize(const float* v, uint64_t count, uint64_t seed, uint64_t iteration, uint32_t worker,
+                     uint32_t kind, uint8_t* code, float* scale)
+{
+    for (uint64_t b0 = 0; b0 < count; b0 += ORACLE_QUANT_BUCKET) {
+        uint64_t b1 = b0 + ORACLE_QUANT_BUCKET < count ? b0 + ORACLE_QUANT_BUCKET : count;
+        float s = 0.0f;
+        for (uint64_t j = b0; j < b1; ++j)
+            if (fabsf(v[j]) > s) s = fabsf(v[j]);
+        scale[b0 / ORACLE_QUANT_BUCKET] = s;
+        for (uint64_t j = b0; j < b1; ++j) {
+            uint32_t level = 0;
+            if (s > 0.0f) {
+                float y = (fabsf(v[j]) / s) * ORACLE_QUANT_LEVELS;
+                float l = floorf(y);
+                float frac = y - l;
+                float u = (float)(oracle_quant_word(seed, iteration, worker, kind, j) >> 8) * 0x1p-24f;
+                level = (uint32_t)l + (u < frac ? 1u : 0u);
+            }
+            code[j] = (uint8_t)((signbit(v[j]) ? 0x80u : 0u) | level);
+        }
+    }
+}
+
+/* value = sign * (scale * level / 127), two binary32 roundings: the product, then the quotient */
+void oracle_dequantize(const uint8_t* code, const float* scale, uint64_t count, float* out)
+{
+    for (uint64_t j = 0; j < count; ++j) {
+        float s = scale[j / ORACLE_QUANT_BUCKET];
+        float mag = (s * (float)(code[j] & 0x7Fu)) / ORACLE_QUANT_LEVELS;
+        out[j] = (code[j] & 0x80u) ? -mag : mag;
     }
 }

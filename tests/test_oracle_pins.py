@@ -515,3 +515,144 @@ def test_pull_reads_and_overwrites_only_the_communication_set():
     want[expl] = w[expl]
     assert np.array_equal(bits(new_local), bits(want))
     assert oracle.pull(w, core, expl)[2] is None
+
+
+# ----------------------------------------------------------------------------------------
+# Worker side: local step and accumulation (section 3.3 step 1)
+# ----------------------------------------------------------------------------------------
+def test_local_step_exact_rational_and_accumulation_order():
+    rng = np.random.default_rng(11)
+    n = 257
+    w = rng.standard_normal(n).astype(np.float32)
+    eta = np.float32(0.3)
+    g = [(rng.standard_normal(n) * 10.0 ** rng.integers(-3, 4, n)).astype(np.float32) for _ in range(3)]
+    w1, d1 = oracle.local_step(w, None, g[0], eta)
+    # one rounding for the model: the exact rational w - eta * g, rounded once
+    for i in range(n):
+        assert w1[i] == round_to_f32(f32_exact(w[i]) - f32_exact(eta) * f32_exact(g[0][i])), i
+    assert np.array_equal(bits(d1), bits(g[0]))                 # a new accumulation starts with the first update itself
+    w2, d2 = oracle.local_step(w1, d1, g[1], eta)
+    w3, d3 = oracle.local_step(w2, d2, g[2], eta)
+    # accumulated in binary32 in mini-batch order: (g1 + g2) + g3, each sum rounded
+    for i in range(n):
+        s12 = round_to_f32(f32_exact(g[0][i]) + f32_exact(g[1][i]))
+        assert d2[i] == s12 and d3[i] == round_to_f32(f32_exact(s12) + f32_exact(g[2][i])), i
+    # an order-sensitive triple: (1e8 + -1e8) + 1 = 1, not 1e8 + (-1e8 + 1) = 0
+    a = [np.array([1e8], np.float32), np.array([-1e8], np.float32), np.array([1.0], np.float32)]
+    _, d = oracle.local_step(np.zeros(1, np.float32), None, a[0], 0.0)
+    _, d = oracle.local_step(np.zeros(1, np.float32), d, a[1], 0.0)
+    _, d = oracle.local_step(np.zeros(1, np.float32), d, a[2], 0.0)
+    assert d[0] == np.float32(1.0)
+    # inputs are not modified; dyadic closed form: p equal steps of 2^-3 with eta = 2^-1
+    w0 = np.full(5, 1.0, np.float32)
+    gg = np.full(5, 0.125, np.float32)
+    ww, dd = w0, None
+    for _ in range(4):
+        ww, dd = oracle.local_step(ww, dd, gg, 0.5)
+    assert np.all(ww == np.float32(1.0 - 4 * 0.0625)) and np.all(dd == np.float32(0.5)) and np.all(w0 == 1.0)
+    # the sign: a positive gradient lowers the parameter
+    wn, _ = oracle.local_step(np.zeros(1, np.float32), None, np.ones(1, np.float32), 0.25)
+    assert wn[0] == np.float32(-0.25)
+
+
+# ----------------------------------------------------------------------------------------
+# Quantised wire values (section 2.2 end; section 4.2: 8 bits, buckets of 512)
+# ----------------------------------------------------------------------------------------
+def test_quant_word_counter_layout_through_a_known_answer():
+    # counter (j div 4, worker, iteration low, iteration high), key (seed low ^ 0x51534744, seed high ^ kind),
+    # word j mod 4: the third Philox known answer fed through that layout
+    ctr, key, out = _kat()[2]
+    for kind in (0, 1):
+        seed = (key[0] ^ 0x51534744) | ((key[1] ^ kind) << 32)
+        iteration = ctr[2] | (ctr[3] << 32)
+        for c in range(4):
+            assert oracle.quant_word(seed, iteration, ctr[1], kind, 4 * ctr[0] + c) == out[c]
+    # kind, worker and iteration each change the stream
+    base = [oracle.quant_word(7, 3, 2, 0, j) for j in range(64)]
+    assert base != [oracle.quant_word(7, 3, 2, 1, j) for j in range(64)]
+    assert base != [oracle.quant_word(7, 3, 1, 0, j) for j in range(64)]
+    assert base != [oracle.quant_word(7, 4, 2, 0, j) for j in range(64)]
+
+
+def test_quantize_grid_points_are_exact_and_signs_and_buckets():
+    # scale 127 * 2^e: the grid scale * l / 127 is l * 2^e, exactly representable, so the fraction is 0, the code is
+    # the level whatever the random word says, and dequantisation returns the value itself
+    levels = np.arange(128, dtype=np.float32)
+    v = np.concatenate([levels * 0.25, -levels * 0.25])                  # one bucket of 256 values, scale 31.75
+    code, scale = oracle.quantize(v, 5, 0, 0, 0)
+    assert scale.size == 1 and scale[0] == np.float32(31.75)
+    assert np.array_equal(code[:128], np.arange(128, dtype=np.uint8))
+    assert np.array_equal(code[129:], np.arange(129, 256, dtype=np.uint8))   # sign bit + level
+    assert code[128] == 0x80                                               # -0.0 keeps its sign bit
+    out = oracle.dequantize(code, scale)
+    assert np.array_equal(bits(out), bits(v))
+    # buckets of 512: element 512 belongs to the second bucket and is scaled by ITS maximum; a ragged last bucket;
+    # a bucket of zeros
+    v = np.zeros(512 * 3 + 5, np.float32)
+    v[0], v[511], v[512], v[1023] = 127.0, 1.0, 254.0, -2.0
+    v[1536:] = [0.5, 0.25, 0.0, -0.5, 0.125]
+    code, scale = oracle.quantize(v, 1, 2, 3, 1)
+    assert np.array_equal(scale, np.array([127.0, 254.0, 0.0, 0.5], np.float32))
+    assert code[0] == 127 and code[511] == 1 and code[512] == 127 and code[1023] == 0x80 | 1
+    assert not code[1024:1536].any()
+    assert code[1536] == 127 and code[1539] == 0x80 | 127 and code[1538] == 0
+    assert np.array_equal(oracle.dequantize(code, scale)[[0, 511, 512, 1023]], np.array([127.0, 1.0, 254.0, -2.0], np.float32))
+
+
+def test_quantize_rounds_up_exactly_when_the_word_says_so():
+    """Between two grid points the code is the lower level plus (u < fraction), with u the top 24 bits of the
+    element's random word as a fraction of 2^24; checked in exact rationals with words from the pinned Philox."""
+    rng = np.random.default_rng(3)
+    n = 700
+    v = rng.standard_normal(n).astype(np.float32)
+    seed, it, worker, kind = 12345, 9, 4, 1
+    code, scale = oracle.quantize(v, seed, it, worker, kind)
+    ups = 0
+    for j in range(n):
+        s = np.float32(np.max(np.abs(v[(j // 512) * 512:(j // 512 + 1) * 512])))
+        assert scale[j // 512] == s
+        r = round_to_f32(abs(f32_exact(v[j])) / f32_exact(s))              # binary32 quotient
+        y = round_to_f32(f32_exact(r) * 127)                               # binary32 product
+        lvl = int(np.floor(float(y)))
+        frac = f32_exact(y) - lvl                                          # exact in binary32
+        block = oracle.philox4x32_10([j >> 2, worker, it, 0], [seed ^ 0x51534744, kind])
+        u = Fraction(int(block[j & 3]) >> 8, 1 << 24)
+        up = 1 if u < frac else 0
+        ups += up
+        assert int(code[j]) == (0x80 if v[j] < 0 else 0) | (lvl + up), j
+    assert 0.3 * n < ups < 0.7 * n                                          # both branches are taken
+    # dequantisation: two roundings, product then quotient
+    out = oracle.dequantize(code, scale)
+    for j in range(n):
+        lvl = int(code[j]) & 0x7F
+        mag = round_to_f32(f32_exact(round_to_f32(f32_exact(scale[j // 512]) * lvl)) / 127)
+        assert out[j] == (-mag if code[j] & 0x80 else mag), j
+
+
+def test_quantize_is_unbiased_and_bounded():
+    """Expectation over the random words equals the value (the property that makes the scheme usable for gradients),
+    and a dequantised value never leaves the two grid points around it."""
+    rng = np.random.default_rng(8)
+    n = 512
+    v = (rng.standard_normal(n) * 1e-4).astype(np.float32)
+    acc = np.zeros(n, np.float64)
+    reps = 400
+    step = float(np.max(np.abs(v))) / 127.0
+    for it in range(reps):
+        code, scale = oracle.quantize(v, 77, it, 0, 0)
+        out = oracle.dequantize(code, scale).astype(np.float64)
+        assert np.all(np.abs(out - v) <= step * (1 + 1e-6))
+        acc += out
+    mean = acc / reps
+    # the error of one draw is at most one step with variance <= step^2 / 4: 6 standard errors
+    assert np.all(np.abs(mean - v) <= 6 * 0.5 * step / np.sqrt(reps) + 1e-12)
+
+
+def test_wire_bytes_against_section_3_5():
+    n, alpha, beta = 1_000_000, 0.2, 0.1
+    k, m = int(beta * n), int((alpha - beta) * n)
+    assert oracle.wire_bytes(k, m, False) == round(4 * (2 * alpha - beta) * n)     # (2 alpha - beta) n words
+    q = oracle.wire_bytes(k, m, True)
+    nb = lambda c: -(-c // 512)
+    assert q == k + m + 4 * m + 4 * (nb(k) + nb(m))
+    assert q < 0.6 * oracle.wire_bytes(k, m, False)            # values shrink fourfold, the explorer's keys do not
