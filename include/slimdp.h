@@ -266,6 +266,38 @@ int slimdp_pull(slimdp_ctx* ctx, const float* w, uint64_t core_epoch, uint32_t n
                 const uint64_t* m_w, float* const* core_out, float* const* expl_out,
                 float* const* w_local);
 
+/* LocalTrain, worker side (section 3.3 step 1; first line of the worker loop of algorithm 1): one mini-batch step
+ * of every worker on its LOCAL model, and the accumulation of the update that the next push extracts from:
+ *     w_local[q][i] <- fma(-eta, grad[q][i], w_local[q][i])
+ *     delta[q][i]   <- grad[q][i]                      with SLIMDP_LOCAL_FIRST (first mini-batch after a communication)
+ *     delta[q][i]   <- delta[q][i] + grad[q][i]        otherwise: the sum over the p mini-batches in binary32, in order
+ * The gradient is an input (the library trains no network).  delta[q] is what slimdp_pack takes as g[q]; after the
+ * push, slimdp_pull overwrites w_local[q] at the communication set (steps 4 and 5) and leaves the rest to diverge
+ * from the global model, which is what the explorer is for (section 3.1).
+ *   w_local, grad, delta [host tables, n_workers] of [dev, n], pairwise distinct per worker; eta finite. */
+#define SLIMDP_LOCAL_FIRST 1u
+int slimdp_local_step(slimdp_ctx* ctx, uint32_t n_workers, float* const* w_local, const float* const* grad,
+                      float* const* delta, float eta, uint32_t flags);
+
+/* Quantised wire values: the method composes with gradient quantisation (section 2.2, last sentences); the
+ * comparison of section 4.2 uses random quantisation with 8 bits and buckets of 512, after Alistarh et al. (QSGD).
+ * Applied to the packed values of workers worker0 .. worker0+n_workers-1 (kind 0: core_val, kind 1: expl_val):
+ * per bucket of 512 consecutive list entries one binary32 scale = the bucket's largest magnitude; per value one
+ * byte = sign bit | level, the level in 0..127 on the grid scale * level / 127, rounded up with probability equal
+ * to the fraction (unbiased): y = (|v| / scale) * 127, level = floor(y) + (u < y - floor(y)), all in binary32,
+ * u = (word >> 8) * 2^-24, word = word (j mod 4) of Philox4x32-10 with counter (j div 4, worker, iteration low,
+ * iteration high) and key (seed low ^ 0x51534744, seed high ^ kind) for list entry j.  Values must be finite.
+ * Bytes on the wire per worker: k + 4 ceil(k/512) for the core, 5 m + 4 ceil(m/512) for the explorer (its keys
+ * stay 32-bit), against the 4 (k + 2m) of section 3.5.
+ *   val [host table] of [dev, count[q]]; count [host, n_workers] <= n;
+ *   code [host table] of [dev, count[q]] bytes; scale [host table] of [dev, ceil(count[q] / 512)]. */
+int slimdp_quantize(slimdp_ctx* ctx, uint32_t n_workers, uint32_t worker0, const float* const* val, const uint64_t* count,
+                    uint32_t kind, uint64_t iteration, uint8_t* const* code, float* const* scale);
+/* The receiver's side: val[q][j] = sign * ((scale * level) / 127), two binary32 roundings.  The result feeds
+ * slimdp_merge like unquantised packs. */
+int slimdp_dequantize(slimdp_ctx* ctx, uint32_t n_workers, const uint8_t* const* code, const float* const* scale,
+                      const uint64_t* count, float* const* val);
+
 /* Signature of the cached core keys (section 3.5, communication efficiency: for the core only the values
  * travel, together with a signature of the cached keys): the two sides of a link compare it instead of the key
  * list.  The paper does not fix the function; here: sum over list positions j of mix(core_idx[j] + 2^32 * j) modulo 2^64, mix being

@@ -27,13 +27,15 @@ ERR_HIP = -5
 ERR_DEVICE_STATUS = -6
 SELECT_REUSE_HISTOGRAM = 1
 PACK_UPDATES_AS_SCORED = 1
+LOCAL_FIRST = 1
+QUANT_BUCKET = 512
 
 EXPORTS = [
     "slimdp_create", "slimdp_destroy", "slimdp_workspace_bytes", "slimdp_num_tiles",
     "slimdp_tile_starts", "slimdp_last_error", "slimdp_synchronize", "slimdp_set_option",
     "slimdp_score", "slimdp_dense_update_score", "slimdp_select_core", "slimdp_sample_explore", "slimdp_explore_hint", "slimdp_tile_offsets",
     "slimdp_pack", "slimdp_merge", "slimdp_pull", "slimdp_core_signature", "slimdp_debug_philox",
-    "slimdp_select_core_static",
+    "slimdp_select_core_static", "slimdp_local_step", "slimdp_quantize", "slimdp_dequantize",
 ]
 
 
@@ -101,6 +103,12 @@ def load() -> C.CDLL:
     L.slimdp_debug_philox.restype = C.c_int
     L.slimdp_select_core_static.argtypes = [_vp, C.c_uint64, C.c_uint64, _vp, _vp, _vp, _vp]
     L.slimdp_select_core_static.restype = C.c_int
+    L.slimdp_local_step.argtypes = [_vp, C.c_uint32, _vpp, _vpp, _vpp, C.c_float, C.c_uint32]
+    L.slimdp_local_step.restype = C.c_int
+    L.slimdp_quantize.argtypes = [_vp, C.c_uint32, C.c_uint32, _vpp, _u64p, C.c_uint32, C.c_uint64, _vpp, _vpp]
+    L.slimdp_quantize.restype = C.c_int
+    L.slimdp_dequantize.argtypes = [_vp, C.c_uint32, _vpp, _vpp, _u64p, _vpp]
+    L.slimdp_dequantize.restype = C.c_int
     _lib = L
     return L
 
@@ -316,3 +324,38 @@ class SlimDP:
         out = self._empty(count, self._torch.int32)
         self._check(self._L.slimdp_debug_philox(self._h, int(iteration), int(worker), int(i0), int(count), _ptr(out)))
         return out
+
+    # -- worker side and wire codec ------------------------------------------------------
+    def local_step(self, w_local: Sequence, grad: Sequence, delta: Sequence, eta: float, first: bool) -> None:
+        """One mini-batch step on every local model; delta accumulates the update (first: starts a new sum)."""
+        self._check(self._L.slimdp_local_step(self._h, len(w_local), _table(w_local), _table(grad), _table(delta),
+                                              C.c_float(eta), LOCAL_FIRST if first else 0))
+
+    def quantize(self, val: Sequence, kind: int, iteration: int, worker0: int = 0, code=None, scale=None):
+        torch = self._torch
+        nw = len(val)
+        if code is None:
+            code = [self._empty(v.numel(), torch.uint8) for v in val]
+        if scale is None:
+            scale = [self._empty((v.numel() + QUANT_BUCKET - 1) // QUANT_BUCKET, torch.float32) for v in val]
+        cnt = _u64arr([v.numel() for v in val])
+        self._check(self._L.slimdp_quantize(self._h, nw, int(worker0), _table(val), cnt, int(kind), int(iteration),
+                                            _table(code), _table(scale)))
+        return code, scale
+
+    def dequantize(self, code: Sequence, scale: Sequence, out=None):
+        torch = self._torch
+        nw = len(code)
+        if out is None:
+            out = [self._empty(c.numel(), torch.float32) for c in code]
+        cnt = _u64arr([c.numel() for c in code])
+        self._check(self._L.slimdp_dequantize(self._h, nw, _table(code), _table(scale), cnt, _table(out)))
+        return out
+
+
+def wire_bytes(k: int, m: int, quantized: bool) -> int:
+    """Bytes one worker pushes (core values + explorer <key, value> pairs), plain or with 8-bit values."""
+    if not quantized:
+        return 4 * (k + 2 * m)
+    nb = lambda c: (c + QUANT_BUCKET - 1) // QUANT_BUCKET
+    return k + 4 * nb(k) + 5 * m + 4 * nb(m)

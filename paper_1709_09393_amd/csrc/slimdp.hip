@@ -1208,6 +1208,96 @@ int slimdp_pull(slimdp_ctx* ctx, const float* w, uint64_t core_epoch, uint32_t n
     return SLIMDP_OK;
 }
 
+int slimdp_local_step(slimdp_ctx* ctx, uint32_t n_workers, float* const* w_local, const float* const* grad,
+                      float* const* delta, float eta, uint32_t flags)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    if (flags & ~SLIMDP_LOCAL_FIRST) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_local_step: unknown flag bits 0x%x", flags);
+    if (n_workers == 0 || n_workers > ctx->maxW)
+        return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_local_step: n_workers=%u outside [1, %u]", n_workers, ctx->maxW);
+    if (!table_ok(w_local, n_workers) || !table_ok(grad, n_workers) || !table_ok(delta, n_workers))
+        return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_local_step: NULL array");
+    if (!std::isfinite(eta)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_local_step: eta must be finite");
+    int vec_ok = 1;
+    for (uint32_t q = 0; q < n_workers; ++q) {
+        vec_ok = vec_ok && aligned16(w_local[q]) && aligned16(grad[q]) && aligned16(delta[q]);
+        if (static_cast<const void*>(w_local[q]) == static_cast<const void*>(delta[q]) ||
+            static_cast<const void*>(grad[q]) == static_cast<const void*>(delta[q]) ||
+            static_cast<const void*>(grad[q]) == static_cast<const void*>(w_local[q]))
+            return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_local_step: arrays of worker %u alias", q);
+    }
+    uint64_t blocks = (ctx->n / 4 + 511) / 512;
+    const uint64_t cap = (uint64_t)ctx->cus * 16 / n_workers + 1;
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(k_local_step, dim3((uint32_t)blocks, n_workers), dim3(256), 0, ctx->stream, make_tab<MutPtrTab>(w_local, n_workers),
+                       make_tab<PtrTab>(grad, n_workers), make_tab<MutPtrTab>(delta, n_workers), ctx->n, eta,
+                       (int)((flags & SLIMDP_LOCAL_FIRST) != 0), vec_ok);
+    SLIMDP_LAUNCHED(ctx, "k_local_step");
+    return SLIMDP_OK;
+}
+
+static int quant_args(slimdp_ctx* ctx, const char* who, uint32_t n_workers, const void* const* a, const void* const* b,
+                      const void* const* c, const uint64_t* count, Count64Tab* ct, uint64_t* cmax)
+{
+    if (n_workers == 0 || n_workers > ctx->maxW)
+        return fail(ctx, SLIMDP_ERR_INVALID_ARG, "%s: n_workers=%u outside [1, %u]", who, n_workers, ctx->maxW);
+    if (!count || !a || !b || !c) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "%s: NULL argument", who);
+    *cmax = 0;
+    for (uint32_t q = 0; q < n_workers; ++q) {
+        if (count[q] > ctx->n) return fail(ctx, SLIMDP_ERR_OUT_OF_RANGE, "%s: count[%u] exceeds n", who, q);
+        if (count[q] && (!a[q] || !b[q] || !c[q])) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "%s: NULL array of worker %u", who, q);
+        ct->c[q] = count[q];
+        if (count[q] > *cmax) *cmax = count[q];
+    }
+    return SLIMDP_OK;
+}
+
+int slimdp_quantize(slimdp_ctx* ctx, uint32_t n_workers, uint32_t worker0, const float* const* val, const uint64_t* count,
+                    uint32_t kind, uint64_t iteration, uint8_t* const* code, float* const* scale)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    if (kind > 1) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_quantize: kind must be 0 (core values) or 1 (explorer values)");
+    Count64Tab ct{};
+    uint64_t cmax = 0;
+    int rc = quant_args(ctx, "slimdp_quantize", n_workers, reinterpret_cast<const void* const*>(val),
+                        reinterpret_cast<const void* const*>(code), reinterpret_cast<const void* const*>(scale), count, &ct, &cmax);
+    if (rc) return rc;
+    if (cmax == 0) return SLIMDP_OK;
+    int vec_ok = 1;
+    for (uint32_t q = 0; q < n_workers; ++q)
+        vec_ok = vec_ok && aligned16(val[q]) && (reinterpret_cast<uintptr_t>(code[q]) & 3u) == 0;
+    const uint64_t buckets = (cmax + QB - 1) / QB;
+    const PhiloxKey pk{(uint32_t)ctx->seed, (uint32_t)(ctx->seed >> 32), (uint32_t)iteration, (uint32_t)(iteration >> 32)};
+    hipLaunchKernelGGL(k_quantize, dim3((uint32_t)((buckets + 3) / 4), n_workers), dim3(BLOCK), 0, ctx->stream,
+                       make_tab<PtrTab>(val, n_workers), ct, kind, worker0, pk, make_tab<MutPtrTab>(code, n_workers),
+                       make_tab<MutPtrTab>(scale, n_workers), vec_ok);
+    SLIMDP_LAUNCHED(ctx, "k_quantize");
+    return SLIMDP_OK;
+}
+
+int slimdp_dequantize(slimdp_ctx* ctx, uint32_t n_workers, const uint8_t* const* code, const float* const* scale,
+                      const uint64_t* count, float* const* val)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    Count64Tab ct{};
+    uint64_t cmax = 0;
+    int rc = quant_args(ctx, "slimdp_dequantize", n_workers, reinterpret_cast<const void* const*>(code),
+                        reinterpret_cast<const void* const*>(scale), reinterpret_cast<const void* const*>(val), count, &ct, &cmax);
+    if (rc) return rc;
+    if (cmax == 0) return SLIMDP_OK;
+    int vec_ok = 1;
+    for (uint32_t q = 0; q < n_workers; ++q)
+        vec_ok = vec_ok && aligned16(val[q]) && (reinterpret_cast<uintptr_t>(code[q]) & 3u) == 0;
+    uint64_t blocks = (cmax / 4 + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(k_dequantize, dim3((uint32_t)blocks, n_workers), dim3(256), 0, ctx->stream, make_tab<PtrTab>(code, n_workers),
+                       make_tab<PtrTab>(scale, n_workers), ct, make_tab<MutPtrTab>(val, n_workers), vec_ok);
+    SLIMDP_LAUNCHED(ctx, "k_dequantize");
+    return SLIMDP_OK;
+}
+
 int slimdp_core_signature(slimdp_ctx* ctx, const uint32_t* core_idx, uint64_t k, uint64_t* sig)
 {
     if (!ctx) return SLIMDP_ERR_INVALID_ARG;

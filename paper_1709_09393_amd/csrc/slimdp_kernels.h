@@ -2542,6 +2542,153 @@ __global__ __launch_bounds__(BLOCK) void k_merge(float* __restrict__ w, float lr
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Worker side, LocalTrain (section 3.3 step 1): one mini-batch step on every worker's LOCAL
+// model, w_q <- fma(-eta, grad_q, w_q), and the accumulation of the update that the next
+// push sends, delta_q = grad_1 + grad_2 + ... in binary32 in mini-batch order (first: a new
+// accumulation starts with this gradient; delta is then not read).  20 bytes per parameter
+// and worker (16 when first).  grid (blocks, n_workers).
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_local_step(MutPtrTab w_local, PtrTab grad, MutPtrTab delta, uint64_t n, float eta,
+                                                    int first, int vec_ok)
+{
+    const uint32_t q = blockIdx.y;
+    float* w = static_cast<float*>(w_local.p[q]);
+    const float* g = static_cast<const float*>(grad.p[q]);
+    float* d = static_cast<float*>(delta.p[q]);
+    const uint64_t stride = (uint64_t)gridDim.x * 256;
+    const uint64_t n4 = vec_ok ? n / 4 : 0;
+    for (uint64_t x = (uint64_t)blockIdx.x * 256 + threadIdx.x; x < n4; x += 2 * stride) {       // two vectors per turn in flight
+        const uint64_t x2 = x + stride;
+        const bool two = x2 < n4;
+        const float4 ga = ld4<1>(g + 4 * x), wa = ld4<1>(w + 4 * x);
+        const float4 gb = two ? ld4<1>(g + 4 * x2) : make_float4(0.f, 0.f, 0.f, 0.f);
+        const float4 wb = two ? ld4<1>(w + 4 * x2) : make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 da = ga, db = gb;
+        if (!first) {
+            const float4 oa = ld4<1>(d + 4 * x);
+            da = make_float4(oa.x + ga.x, oa.y + ga.y, oa.z + ga.z, oa.w + ga.w);
+            if (two) {
+                const float4 ob = ld4<1>(d + 4 * x2);
+                db = make_float4(ob.x + gb.x, ob.y + gb.y, ob.z + gb.z, ob.w + gb.w);
+            }
+        }
+        st4<1>(w + 4 * x, make_float4(__builtin_fmaf(-eta, ga.x, wa.x), __builtin_fmaf(-eta, ga.y, wa.y),
+                                      __builtin_fmaf(-eta, ga.z, wa.z), __builtin_fmaf(-eta, ga.w, wa.w)));
+        st4<1>(d + 4 * x, da);
+        if (two) {
+            st4<1>(w + 4 * x2, make_float4(__builtin_fmaf(-eta, gb.x, wb.x), __builtin_fmaf(-eta, gb.y, wb.y),
+                                           __builtin_fmaf(-eta, gb.z, wb.z), __builtin_fmaf(-eta, gb.w, wb.w)));
+            st4<1>(d + 4 * x2, db);
+        }
+    }
+    for (uint64_t i = 4 * n4 + (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {      // tail, or unaligned arrays
+        const float gi = g[i];
+        w[i] = __builtin_fmaf(-eta, gi, w[i]);
+        d[i] = first ? gi : d[i] + gi;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Quantised wire values (section 2.2, last sentences; section 4.2: random quantisation, 8 bits,
+// buckets of 512).  Per bucket of QB consecutive list entries: scale = largest magnitude;
+// per value: code = sign bit | level, level = floor(y) + (u < y - floor(y)), y = (|v| / scale) * 127
+// in binary32, u = (random word >> 8) * 2^-24; the word of entry j: word (j mod 4) of
+// Philox4x32-10 with counter (j div 4, worker, iteration low, high) and key
+// (seed low ^ 0x51534744, seed high ^ kind).  One wave per bucket: lane L holds entries
+// 4L..4L+3 and 256+4L..256+4L+3 (two Philox calls), the maximum is a wave reduction (exact,
+// whatever the order), the 512 codes leave as two stores of whole lines.
+// grid (ceil(buckets / 4), n_workers).
+// ---------------------------------------------------------------------------------------
+constexpr uint32_t QB = 512;
+struct Count64Tab { uint64_t c[MAXW]; };
+__device__ __forceinline__ uint32_t quant_code(float v, float s, uint32_t word)
+{
+    uint32_t level = 0;
+    if (s > 0.0f) {
+        const float y = (__builtin_fabsf(v) / s) * 127.0f;
+        const float l = __builtin_floorf(y);
+        const float u = (float)(word >> 8) * 0x1p-24f;
+        level = (uint32_t)l + ((u < y - l) ? 1u : 0u);
+    }
+    return ((__float_as_uint(v) >> 24) & 0x80u) | level;
+}
+
+__global__ __launch_bounds__(BLOCK) void k_quantize(PtrTab val, Count64Tab count, uint32_t kind, uint32_t worker0,
+                                                    PhiloxKey pk, MutPtrTab code, MutPtrTab scale, int vec_ok)
+{
+    const uint32_t q = blockIdx.y, lane = lane_id();
+    const uint64_t cnt = count.c[q];
+    const uint64_t b = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const uint64_t j0 = b * QB;
+    if (j0 >= cnt) return;
+    const float* v = static_cast<const float*>(val.p[q]);
+    uint8_t* out = static_cast<uint8_t*>(code.p[q]);
+    const uint32_t len = (cnt - j0 < QB) ? (uint32_t)(cnt - j0) : QB;
+    float x[2][4];
+    if (vec_ok && len == QB) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const float4 t = ld4<1>(v + j0 + h * 256 + lane * 4);
+            x[h][0] = t.x; x[h][1] = t.y; x[h][2] = t.z; x[h][3] = t.w;
+        }
+    } else {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t e = h * 256 + lane * 4 + c;
+                x[h][c] = (e < len) ? v[j0 + e] : 0.0f;
+            }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) s = __builtin_fmaxf(s, __builtin_fabsf(x[h][c]));
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) s = __builtin_fmaxf(s, __shfl_xor(s, d, 64));
+    if (lane == 0) static_cast<float*>(scale.p[q])[b] = s;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint32_t r[4];
+        philox4x32_10((uint32_t)((j0 + h * 256 + lane * 4) >> 2), worker0 + q, pk.it_lo, pk.it_hi, pk.seed_lo ^ 0x51534744u,
+                      pk.seed_hi ^ kind, r);
+        uint32_t packed = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) packed |= quant_code(x[h][c], s, r[c]) << (8 * c);
+        const uint32_t e = h * 256 + lane * 4;
+        if (vec_ok && len == QB) *reinterpret_cast<uint32_t*>(out + j0 + e) = packed;
+        else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (e + c < len) out[j0 + e + c] = (uint8_t)(packed >> (8 * c));
+        }
+    }
+}
+
+// value = sign * ((scale * level) / 127): two binary32 roundings.  Four codes per thread.  grid (blocks, n_workers).
+__global__ __launch_bounds__(256) void k_dequantize(PtrTab code, PtrTab scale, Count64Tab count, MutPtrTab val, int vec_ok)
+{
+    const uint32_t q = blockIdx.y;
+    const uint64_t cnt = count.c[q];
+    const uint8_t* in = static_cast<const uint8_t*>(code.p[q]);
+    const float* sc = static_cast<const float*>(scale.p[q]);
+    float* out = static_cast<float*>(val.p[q]);
+    const uint64_t stride = (uint64_t)gridDim.x * 256;
+    const uint64_t n4 = vec_ok ? cnt / 4 : 0;
+    auto one = [](uint32_t c, float s) {
+        const float mag = (s * (float)(c & 0x7Fu)) / 127.0f;
+        return (c & 0x80u) ? -mag : mag;
+    };
+    for (uint64_t x = (uint64_t)blockIdx.x * 256 + threadIdx.x; x < n4; x += stride) {
+        const uint32_t p = *reinterpret_cast<const uint32_t*>(in + 4 * x);
+        const float s = sc[(4 * x) / QB];
+        st4<1>(out + 4 * x, make_float4(one(p & 0xFFu, s), one((p >> 8) & 0xFFu, s), one((p >> 16) & 0xFFu, s), one(p >> 24, s)));
+    }
+    for (uint64_t j = 4 * n4 + (uint64_t)blockIdx.x * 256 + threadIdx.x; j < cnt; j += stride) out[j] = one(in[j], sc[j / QB]);
+}
+
 // Signature of the cached keys: sum over list positions j of mix(idx[j] + 2^32 j) modulo 2^64, mix = the output
 // function of SplitMix64.  A wrapping integer sum: any order of the partial sums gives the same bits.
 // *sig must be zero at launch.  grid: any, 256 threads.

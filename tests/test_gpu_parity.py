@@ -749,3 +749,156 @@ def test_error_paths_launch_nothing():
     assert e.value.code == binding.ERR_DEVICE_STATUS
     sd.synchronize()                                            # status is cleared once reported
     sd.close()
+
+
+# ----------------------------------------------------------------------------------------
+# Worker side: local steps, accumulated updates, pull with local overwrite (section 3.3 steps 1, 4, 5)
+# ----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,W,shift", [(1, 1, 0), (4099, 3, 0), (300_001, 4, 0), (70_000, 2, 1)])
+def test_local_step_matches_oracle(n, W, shift):
+    """p = 3 mini-batch steps; shift = 1 starts every array one element into its allocation (no 16-byte alignment)."""
+    rng = np.random.default_rng(n)
+    sd = binding.SlimDP(n, W)
+    eta = 0.05
+    w_h = [rng.standard_normal(n).astype(np.float32) for _ in range(W)]
+    d_h = [None] * W
+
+    def dev_arr(a):
+        buf = torch.full((n + shift,), float("nan"), dtype=torch.float32, device=dev())
+        buf[shift:] = torch.from_numpy(a)
+        return buf[shift:]
+    w = [dev_arr(x) for x in w_h]
+    d = [dev_arr(np.full(n, np.nan, np.float32)) for _ in range(W)]      # a first step must not read it
+    for j in range(3):
+        g_h = [(rng.standard_normal(n) * 10.0 ** rng.integers(-4, 3, n)).astype(np.float32) for _ in range(W)]
+        g = [dev_arr(x) for x in g_h]
+        sd.local_step(w, g, d, eta, first=(j == 0))
+        sd.synchronize()
+        for q in range(W):
+            w_h[q], d_h[q] = oracle.local_step(w_h[q], d_h[q], g_h[q], eta)
+            assert np.array_equal(f32bits(w[q].cpu().numpy()), f32bits(w_h[q])), (j, q)
+            assert np.array_equal(f32bits(d[q].cpu().numpy()), f32bits(d_h[q])), (j, q)
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.local_step(w, w, d, eta, first=True)                           # gradient aliases the model
+    assert e.value.code == binding.ERR_INVALID_ARG
+    sd.close()
+
+
+def test_worker_loop_closure_local_models_diverge_and_are_pulled_back():
+    """W local models carried through the loop of algorithm 1's worker side: p = 2 local mini-batch steps accumulate
+    delta_k, the communication set of delta_k is pushed and merged, the worker pulls the global values at its
+    communication set and overwrites its local model there.  Global model, every local model and every set match the
+    oracle at every iteration; and, as section 3.1 argues, parameters outside a worker's communication set drift away
+    from the global model while those inside are equal to it right after the pull."""
+    wl = workloads.LOOP.scaled(60_001, W=4)
+    n, W, k, m = wl.n, wl.W, wl.k, wl.m
+    p_steps, every, eta = 2, 3, 0.05
+    sd = binding.SlimDP(n, W, seed=workloads.EXPLORE_SEED)
+    w_h = wl.weights()
+    w = to_dev(w_h)
+    wk_h = [w_h.copy() for _ in range(W)]                   # first line of the worker loop: every worker pulls the whole model
+    wk = [to_dev(x) for x in wk_h]
+    delta = [torch.empty(n, dtype=torch.float32, device=dev()) for _ in range(W)]
+    core_o = None
+    for t in range(7):
+        d_h = [None] * W
+        for j in range(p_steps):
+            g_h = wl.gradients(t * p_steps + j)
+            sd.local_step(wk, [to_dev(x) for x in g_h], delta, eta, first=(j == 0))
+            for q in range(W):
+                wk_h[q], d_h[q] = oracle.local_step(wk_h[q], d_h[q], g_h[q], eta)
+        if t % every == 0:
+            S = sd.score(w, delta, wl.c)
+            core_idx, core_bits, core_off, epoch = sd.select_core(S, [k], reuse_histogram=True)
+            core_o = oracle.select_core(oracle.score(w_h, d_h, wl.c), k)
+            assert np.array_equal(u32(core_idx), core_o), t
+        expl_idx, expl_off = sd.sample_explore(core_bits, [k], t, [m], 0, W)
+        core_val, expl_val = sd.pack(delta, core_idx, core_off, expl_idx, expl_off, epoch)
+        sd.merge(w, wl.lr, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
+        sd.pull(w, epoch, core_idx, core_off, expl_idx, expl_off, w_local=wk)
+        sd.synchronize()
+        ei_o = [oracle.sample_explore(n, core_o, workloads.EXPLORE_SEED, t, q, m) for q in range(W)]
+        packs = [oracle.pack(d_h[q], core_o, ei_o[q]) for q in range(W)]
+        w_h = oracle.merge(w_h, wl.lr, core_o, [x[0] for x in packs], ei_o, [x[1] for x in packs])
+        assert np.array_equal(f32bits(w.cpu().numpy()), f32bits(w_h)), t
+        for q in range(W):
+            assert np.array_equal(u32(expl_idx[q]), ei_o[q]), (t, q)
+            _, _, wk_h[q] = oracle.pull(w_h, core_o, ei_o[q], wk_h[q])
+            got = wk[q].cpu().numpy()
+            assert np.array_equal(f32bits(got), f32bits(wk_h[q])), (t, q)
+            inside = np.zeros(n, bool)
+            inside[core_o] = True
+            inside[ei_o[q]] = True
+            assert np.array_equal(f32bits(got[inside]), f32bits(w_h[inside]))          # pulled: equal to the global model
+            if t >= 2:      # never-communicated parameters have drifted: almost all of them differ from the global model
+                outside = ~inside
+                assert np.mean(got[outside] != w_h[outside]) > 0.95, (t, q)
+    sd.close()
+
+
+# ----------------------------------------------------------------------------------------
+# Quantised wire values (sections 2.2 and 4.2: 8 bits, buckets of 512)
+# ----------------------------------------------------------------------------------------
+def test_quantized_packs_match_oracle_and_merge():
+    wl = workloads.TINY.scaled(300_007)
+    n, W, k, m = wl.n, wl.W, wl.k, wl.m
+    it = 6
+    sd = binding.SlimDP(n, W, seed=0x1234_5678_9ABC_DEF0)
+    w_h, g_h = wl.weights(), wl.gradients(it)
+    w, g = to_dev(w_h), [to_dev(x) for x in g_h]
+    S = sd.score(w, g, wl.c)
+    core_idx, core_bits, core_off, epoch = sd.select_core(S, [k], reuse_histogram=True)
+    expl_idx, expl_off = sd.sample_explore(core_bits, [k], it, [m], 0, W)
+    core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)
+    c_code, c_scale = sd.quantize(core_val, 0, it)
+    e_code, e_scale = sd.quantize(expl_val, 1, it)
+    cv_q = sd.dequantize(c_code, c_scale)
+    ev_q = sd.dequantize(e_code, e_scale)
+    sd.merge(w, wl.lr, epoch, core_idx, core_off, cv_q, expl_idx, expl_off, ev_q)
+    sd.synchronize()
+    core_o, ei_o = u32(core_idx), [u32(x) for x in expl_idx]
+    cv_o, ev_o = [], []
+    for q in range(W):
+        cv_h, ev_h = oracle.pack(g_h[q], core_o, ei_o[q])
+        for kind, vals, code, scale, deq, keep in ((0, cv_h, c_code, c_scale, cv_q, cv_o), (1, ev_h, e_code, e_scale, ev_q, ev_o)):
+            code_o, scale_o = oracle.quantize(vals, 0x1234_5678_9ABC_DEF0, it, q, kind)
+            assert np.array_equal(code[q].cpu().numpy(), code_o), (q, kind)
+            assert np.array_equal(f32bits(scale[q].cpu().numpy()), f32bits(scale_o)), (q, kind)
+            deq_o = oracle.dequantize(code_o, scale_o)
+            assert np.array_equal(f32bits(deq[q].cpu().numpy()), f32bits(deq_o)), (q, kind)
+            keep.append(deq_o)
+    w_o = oracle.merge(w_h, wl.lr, core_o, cv_o, ei_o, ev_o)
+    w_g = w.cpu().numpy()
+    assert np.all(np.abs(w_g - w_o) <= 1e-6 * np.abs(w_o) + 1e-12)
+    assert np.array_equal(f32bits(w_g), f32bits(w_o))
+    # the quantised update stays within one grid step of the exact one, and the bytes shrink as section 3.5 counts them
+    exact = oracle.merge(w_h, wl.lr, core_o, [oracle.pack(g_h[q], core_o, ei_o[q])[0] for q in range(W)], ei_o,
+                         [oracle.pack(g_h[q], core_o, ei_o[q])[1] for q in range(W)])
+    step = max(float(np.max(np.abs(x))) for x in g_h) / 127.0
+    assert np.max(np.abs(w_o - exact)) <= wl.lr * W * step * 1.01
+    assert binding.wire_bytes(k, m, True) == oracle.wire_bytes(k, m, True) < binding.wire_bytes(k, m, False) == 4 * (k + 2 * m)
+    sd.close()
+
+
+@pytest.mark.parametrize("count", [1, 3, 511, 512, 513, 1024, 5001])
+def test_quantize_ragged_counts_zero_buckets_and_unaligned_arrays(count):
+    rng = np.random.default_rng(count)
+    sd = binding.SlimDP(10_000, 3, seed=5)
+    vals_h = [rng.standard_normal(count).astype(np.float32) * np.float32(10.0 ** rng.integers(-6, 3)) for _ in range(3)]
+    vals_h[1][: min(count, 512)] = 0.0                                  # a bucket of zeros (incl. a negative zero)
+    vals_h[1][0] = -0.0
+    buf = [torch.empty(count + 1, dtype=torch.float32, device=dev()) for _ in range(3)]
+    vals = []
+    for q in range(3):
+        view = buf[q][1:] if q == 2 else buf[q][:count]                  # worker 2: not 16-byte aligned
+        view.copy_(torch.from_numpy(vals_h[q]))
+        vals.append(view)
+    code, scale = sd.quantize(vals, 1, 2 ** 35 + 3, worker0=0)
+    out = sd.dequantize(code, scale)
+    sd.synchronize()
+    for q in range(3):
+        code_o, scale_o = oracle.quantize(vals_h[q], 5, 2 ** 35 + 3, q, 1)
+        assert np.array_equal(code[q].cpu().numpy(), code_o), q
+        assert np.array_equal(f32bits(scale[q].cpu().numpy()), f32bits(scale_o)), q
+        assert np.array_equal(f32bits(out[q].cpu().numpy()), f32bits(oracle.dequantize(code_o, scale_o))), q
+    sd.close()
