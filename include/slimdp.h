@@ -167,6 +167,15 @@ int slimdp_select_core(slimdp_ctx* ctx, const float* score, const uint64_t* k_se
                        uint32_t* core_idx, uint32_t* core_bits, uint32_t* core_off,
                        uint64_t* core_epoch);
 
+/* Resuming from a checkpoint.  The state of the path between two iterations is the global model, the cached core
+ * keys, the iteration number and the seed (the explorers are functions of seed, iteration, worker and the core).  A
+ * new context (same n, segments and seed) adopts the saved keys with this call and continues as if it had selected
+ * them: it rebuilds the bitmap and the tile offsets from the list and issues a core epoch of its own.
+ *   core_idx [dev, sum k_seg] ascending, k_seg[s] of them inside segment s (as slimdp_select_core wrote them; not
+ *   re-checked); core_bits [dev, ceil(n/32)], core_off [dev, T+1], core_epoch [host, 1]: outputs. */
+int slimdp_import_core(slimdp_ctx* ctx, const uint32_t* core_idx, const uint64_t* k_seg, uint32_t* core_bits,
+                       uint32_t* core_off, uint64_t* core_epoch);
+
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc): the same selection as slimdp_select_core for a flat model (one segment) without a context.
  * Calls no hipMalloc / hipFree: the workspace is a fixed array of 5 MiB inside the library's device image (every GPU

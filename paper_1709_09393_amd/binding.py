@@ -35,7 +35,7 @@ EXPORTS = [
     "slimdp_tile_starts", "slimdp_last_error", "slimdp_synchronize", "slimdp_set_option",
     "slimdp_score", "slimdp_dense_update_score", "slimdp_select_core", "slimdp_sample_explore", "slimdp_explore_hint", "slimdp_tile_offsets",
     "slimdp_pack", "slimdp_merge", "slimdp_pull", "slimdp_core_signature", "slimdp_debug_philox",
-    "slimdp_select_core_static", "slimdp_local_step", "slimdp_quantize", "slimdp_dequantize",
+    "slimdp_select_core_static", "slimdp_import_core", "slimdp_local_step", "slimdp_quantize", "slimdp_dequantize",
 ]
 
 
@@ -103,6 +103,8 @@ def load() -> C.CDLL:
     L.slimdp_debug_philox.restype = C.c_int
     L.slimdp_select_core_static.argtypes = [_vp, C.c_uint64, C.c_uint64, _vp, _vp, _vp, _vp]
     L.slimdp_select_core_static.restype = C.c_int
+    L.slimdp_import_core.argtypes = [_vp, _vp, _u64p, _vp, _vp, _u64p]
+    L.slimdp_import_core.restype = C.c_int
     L.slimdp_local_step.argtypes = [_vp, C.c_uint32, _vpp, _vpp, _vpp, C.c_float, C.c_uint32]
     L.slimdp_local_step.restype = C.c_int
     L.slimdp_quantize.argtypes = [_vp, C.c_uint32, C.c_uint32, _vpp, _u64p, C.c_uint32, C.c_uint64, _vpp, _vpp]
@@ -324,6 +326,19 @@ class SlimDP:
         out = self._empty(count, self._torch.int32)
         self._check(self._L.slimdp_debug_philox(self._h, int(iteration), int(worker), int(i0), int(count), _ptr(out)))
         return out
+
+    def import_core(self, core_idx, k_seg, core_bits=None, core_off=None):
+        """Adopts core keys saved from another context (resume); returns (core_bits, core_off, epoch)."""
+        torch = self._torch
+        ks = [int(k_seg)] if np.isscalar(k_seg) else [int(x) for x in k_seg]
+        if core_bits is None:
+            core_bits = self._empty((self.n + 31) // 32, torch.int32)
+        if core_off is None:
+            core_off = self._empty(self.T + 1, torch.int32)
+        epoch = C.c_uint64(0)
+        self._check(self._L.slimdp_import_core(self._h, _ptr(core_idx), _u64arr(ks), _ptr(core_bits), _ptr(core_off),
+                                               C.byref(epoch)))
+        return core_bits, core_off, int(epoch.value)
 
     # -- worker side and wire codec ------------------------------------------------------
     def local_step(self, w_local: Sequence, grad: Sequence, delta: Sequence, eta: float, first: bool) -> None:

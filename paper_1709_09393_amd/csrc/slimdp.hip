@@ -897,6 +897,34 @@ int slimdp_select_core_static(const float* score, uint64_t n, uint64_t k, uint32
     return rc;
 }
 
+int slimdp_import_core(slimdp_ctx* ctx, const uint32_t* core_idx, const uint64_t* k_seg, uint32_t* core_bits,
+                       uint32_t* core_off, uint64_t* core_epoch)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    if (!k_seg || !core_bits || !core_off || !core_epoch) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_import_core: NULL argument");
+    uint64_t K = 0;
+    for (uint32_t s = 0; s < ctx->n_seg; ++s) {
+        if (k_seg[s] > ctx->seg_off[s + 1] - ctx->seg_off[s])
+            return fail(ctx, SLIMDP_ERR_OUT_OF_RANGE, "slimdp_import_core: k_seg[%u] exceeds the segment size", s);
+        K += k_seg[s];
+    }
+    if (K && !core_idx) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_import_core: core_idx is NULL");
+    int rc = fill(ctx, core_bits, (ctx->n + 31) / 32, 0u);
+    if (rc) return rc;
+    if (K) {
+        hipLaunchKernelGGL(k_bits_from_idx, dim3(fill_grid(K)), dim3(256), 0, ctx->stream, core_idx, K, ctx->n, core_bits);
+        SLIMDP_LAUNCHED(ctx, "k_bits_from_idx");
+    }
+    hipLaunchKernelGGL(k_tile_offsets, dim3((ctx->T + 1 + 255) / 256), dim3(256), 0, ctx->stream, core_idx, K, ctx->d_tile_start,
+                       ctx->T, ctx->n, core_off);
+    SLIMDP_LAUNCHED(ctx, "k_tile_offsets");
+    ctx->hist_pending = false;
+    ctx->spec.core_epoch = 0;
+    *core_epoch = ++ctx->epoch;
+    ctx->last_K = K; ctx->have_last_K = true;
+    return SLIMDP_OK;
+}
+
 int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint64_t* k_seg, uint32_t worker0,
                           uint32_t n_workers, uint64_t iteration, const uint64_t* m_seg, uint32_t* const* expl_idx,
                           uint32_t* const* expl_off)

@@ -902,3 +902,56 @@ def test_quantize_ragged_counts_zero_buckets_and_unaligned_arrays(count):
         assert np.array_equal(f32bits(scale[q].cpu().numpy()), f32bits(scale_o)), q
         assert np.array_equal(f32bits(out[q].cpu().numpy()), f32bits(oracle.dequantize(code_o, scale_o))), q
     sd.close()
+
+
+@pytest.mark.parametrize("segmented", [False, True])
+def test_checkpoint_resume_gives_the_same_run(segmented):
+    """20 iterations in one go against 12 iterations, a checkpoint (global model, core keys, iteration; the seed is
+    configuration), a NEW context that adopts the keys, and the remaining 8: the same explorer sets at every
+    iteration and the same final model bits.  The counter-based generator makes the explorers functions of
+    (seed, iteration, worker, core) alone, so nothing else needs saving."""
+    wl = (workloads.GOOGLENET.scaled(200_001, W=3) if segmented else workloads.LOOP.scaled(40_009, W=4))
+    seg_off = [int(x) for x in wl.segment_offsets()]
+    ks, ms = [int(x) for x in wl.k_seg()], [int(x) for x in wl.m_seg()]
+    T_all, every, stop = 20, 5, 12
+
+    def run(t_from, t_to, w, sd, core):
+        sets = {}
+        for t in range(t_from, t_to):
+            g = [to_dev(x) for x in wl.gradients(t)]
+            if t % every == 0:
+                S = sd.score(w, g, wl.c)
+                core = sd.select_core(S, ks, reuse_histogram=True)
+            core_idx, core_bits, core_off, epoch = core
+            expl_idx, expl_off = sd.sample_explore(core_bits, ks, t, ms, 0, wl.W)
+            core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)
+            sd.merge(w, wl.lr, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
+            sd.synchronize()
+            sets[t] = [u32(x) for x in expl_idx]
+        return core, sets
+
+    sd = binding.SlimDP(wl.n, wl.W, seg_off=seg_off, seed=workloads.EXPLORE_SEED)
+    w_a = to_dev(wl.weights())
+    _, sets_a = run(0, T_all, w_a, sd, None)
+    sd.close()
+
+    sd = binding.SlimDP(wl.n, wl.W, seg_off=seg_off, seed=workloads.EXPLORE_SEED)
+    w_b = to_dev(wl.weights())
+    core, sets_b = run(0, stop, w_b, sd, None)
+    saved_w, saved_core = w_b.cpu().numpy().copy(), u32(core[0]).copy()          # the checkpoint
+    sd.close()
+    del w_b, core
+    sd = binding.SlimDP(wl.n, wl.W, seg_off=seg_off, seed=workloads.EXPLORE_SEED)
+    w_b = to_dev(saved_w)
+    core_idx = to_dev(saved_core)
+    core_bits, core_off, epoch = sd.import_core(core_idx, ks)
+    sd.synchronize()
+    assert np.array_equal(u32(core_bits), oracle.core_bits(wl.n, saved_core))
+    assert np.array_equal(u32(core_off), host_tile_offsets(saved_core, sd.tile_starts()))
+    _, sets_c = run(stop, T_all, w_b, sd, (core_idx, core_bits, core_off, epoch))
+    sets_b.update(sets_c)
+    for t in range(T_all):
+        for q in range(wl.W):
+            assert np.array_equal(sets_a[t][q], sets_b[t][q]), (t, q)
+    assert np.array_equal(f32bits(w_a.cpu().numpy()), f32bits(w_b.cpu().numpy()))
+    sd.close()
