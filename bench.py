@@ -372,6 +372,38 @@ def main() -> int:
         out["steady_iteration"] = {"ms": steady_ms, "Gparam_per_s": n / (steady_ms * 1e-3) / 1e9,
                                    "what": "slimdp_sample_explore + slimdp_pack + slimdp_merge, core keys cached",
                                    "algorithmic_bytes": steady_bytes, "hbm_frac": frac(steady_bytes, steady_ms)}
+        # (4b) the rest of the loop around the path: pull with local overwrite (section 3.3 steps 4, 5), one local
+        # mini-batch step of all W workers with update accumulation (step 1), and the 8-bit wire codec (section 4.2)
+        sd.set_option("explore_hint_mode", 0)
+        w_local = [w0.clone() for _ in range(W)]
+        delta = [torch.empty_like(w0) for _ in range(W)]
+        sd.local_step(w_local, g, delta, 0.01, first=True)
+        ls_ms = timed(lambda r: sd.local_step(w_local, g, delta, 0.01, first=False), reps)
+        pull_ms = timed(lambda r: sd.pull(w, epoch2, b.core_idx, b.core_off, b.expl_idx, b.expl_off, w_local=w_local,
+                                          core_out=b.core_val, expl_out=b.expl_val), reps)
+        del w_local, delta
+        codes = sd.quantize(b.core_val, 0, 0)
+        codes_e = sd.quantize(b.expl_val, 1, 0)
+
+        def quant(_r):
+            sd.quantize(b.core_val, 0, _r, code=codes[0], scale=codes[1])
+            sd.quantize(b.expl_val, 1, _r, code=codes_e[0], scale=codes_e[1])
+
+        def dequant(_r):
+            sd.dequantize(codes[0], codes[1], out=b.core_val)
+            sd.dequantize(codes_e[0], codes_e[1], out=b.expl_val)
+        q_ms = timed(quant, reps)
+        dq_ms = timed(dequant, reps)
+        nvals = W * (k + m)
+        out["worker_side"] = {
+            "local_step": {"ms": ls_ms, "algorithmic_bytes": 20 * n * W, "hbm_frac": frac(20 * n * W, ls_ms)},
+            "pull_with_local_overwrite": {"ms": pull_ms},
+            "quantize": {"ms": q_ms, "algorithmic_bytes": 5 * nvals, "hbm_frac": frac(5 * nvals, q_ms)},
+            "dequantize": {"ms": dq_ms, "algorithmic_bytes": 5 * nvals, "hbm_frac": frac(5 * nvals, dq_ms)},
+            "wire_bytes_per_worker": {"plain": binding.wire_bytes(k, m, False), "quantized": binding.wire_bytes(k, m, True),
+                                      "dense": 4 * n},
+        }
+        del codes, codes_e
     sd.close()
     if not args.no_variants:
         # (5) the very first iteration of a fresh context: no selection before it (its draw is announced: that needs

@@ -118,6 +118,10 @@ int slimdp_synchronize(slimdp_ctx* ctx);
  *   "explore_force_fallback" (0/1/2), "explore_per_tile_tail" (0/1): test switches: make
  *       the explorer's first zones miss (1: too few candidates, 2: sure zone too large) so
  *       that the exact rerun runs; never take the short-list tail.
+ *   "core_predict" (0/1/2, default 1): flat models with 16-byte aligned arrays: slimdp_score also sorts every whole tile
+ *       against the threshold bin of the previous selection, so that slimdp_select_core(..REUSE_HISTOGRAM) need not read
+ *       the scores again when its histogram confirms that bin (otherwise it does, as without the option).  0 switches
+ *       that off; 2 is a test switch that makes the prediction always wrong.
  *   "capture_estimate_bias" (test switch): added to a sampled capture bound, in units of the last place. */
 int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value);
 

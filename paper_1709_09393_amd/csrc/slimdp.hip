@@ -104,6 +104,8 @@ struct slimdp_ctx {
     SegState* c_state = nullptr;
     uint32_t *c_hist = nullptr, *c_gt_bits = nullptr, *c_cand_bits = nullptr, *c_cand_keys = nullptr;
     uint32_t* c_chunk_sum = nullptr;
+    uint32_t *c_pred = nullptr, *c_skip = nullptr, *c_used = nullptr;   // predicted level-0 threshold bin per segment; "the scoring pass classified against the right bin"
+    bool cls_by_score = false;                       // the last scoring pass classified whole tiles against c_pred
     uint32_t *c_cnt_gt = nullptr, *c_cnt_cand = nullptr, *c_cnt_sel = nullptr, *c_cnt_tie = nullptr, *c_tie_pre = nullptr;
     // explorer selection (batch = worker)
     SegState* e_state = nullptr;
@@ -144,6 +146,8 @@ struct slimdp_ctx {
         uint64_t core_epoch = 0;                // 0: no selection on the captured score yet
     } spec;
     int64_t opt_pack_nbuf = 2;
+    int64_t opt_build_blocks = 4;
+    int64_t opt_core_predict = 1;          // the flat scoring kernel sorts whole tiles against the predicted threshold bin (0: never; 2: test, a wrong bin)          // blocks per compute unit of the core candidate pass
     int64_t opt_score_pipeline = 1;        // flat aligned models: the scoring kernel with two rounds of loads in flight
     int64_t opt_expected_core = -1;        // core size the next selection will ask for (flat model), if the caller says
     int64_t opt_estimate_bias = 0;         // test switch: added to a sampled capture bound
@@ -188,6 +192,9 @@ void carve_core(slimdp_ctx* c, Carver& cv)
     c->c_cnt_tie = cv.take<uint32_t>(T);
     c->c_tie_pre = cv.take<uint32_t>(T + 1);
     c->c_chunk_sum = cv.take<uint32_t>(2 * c->n_chunks);
+    c->c_pred = cv.take<uint32_t>(S);
+    c->c_skip = cv.take<uint32_t>(S);
+    c->c_used = cv.take<uint32_t>(S);
 }
 
 void carve(slimdp_ctx* c, Carver& cv)
@@ -285,7 +292,8 @@ int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* his
                      const uint32_t* cnt_cand, uint32_t* cnt_sel, uint32_t* cnt_tie, uint32_t* tie_pre,
                      uint64_t keys_stride, bool level1_done, const MutPtrTab& out_off, const MutPtrTab& out_idx,
                      uint32_t expected, uint32_t* pub_bits, const uint32_t* excl_bits, const uint32_t* gate,
-                     uint32_t* chunk_sum, SpecTau sp = SpecTau{nullptr, nullptr, nullptr})
+                     uint32_t* chunk_sum, SpecTau sp = SpecTau{nullptr, nullptr, nullptr},
+                     CorePred cp = CorePred{nullptr, nullptr, nullptr, 0})
 {
     const uint32_t T = c->T, S = c->n_seg;
     const dim3 wave_grid((T + 3) / 4, (nbatch + BPW - 1) / BPW);     // a wave serves its tile for BPW batches
@@ -295,13 +303,13 @@ int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* his
         SLIMDP_LAUNCHED(c, "k_list_hist(1)");
     }
     hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 1, (uint32_t)H_L1, S, 0, c->d_flags,
-                       nullptr, gate ? 1 : 0, SpecTau{nullptr, nullptr, nullptr});
+                       nullptr, gate ? 1 : 0, SpecTau{nullptr, nullptr, nullptr}, CorePred{nullptr, nullptr, nullptr, 0});
     SLIMDP_LAUNCHED(c, "k_threshold(1)");
     hipLaunchKernelGGL((k_list_hist<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg,
                        T, S, nbatch, st, hist, (uint32_t)H_L2, 2, cand_keys, cnt_cand, keys_stride, gate);
     SLIMDP_LAUNCHED(c, "k_list_hist(2)");
     hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 2, (uint32_t)H_L2, S, 0, c->d_flags,
-                       nullptr, gate ? 1 : 0, sp);
+                       nullptr, gate ? 1 : 0, sp, cp);
     SLIMDP_LAUNCHED(c, "k_threshold(2)");
     hipLaunchKernelGGL((k_count<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg, T, S,
                        nbatch, st, cand_keys, cnt_cand, cnt_gt, keys_stride, cnt_sel, cnt_tie, gate);
@@ -479,6 +487,8 @@ int slimdp_create(slimdp_ctx** out, uint64_t n, uint32_t max_workers, uint32_t n
     if (e == hipSuccess) e = hipMemcpy(c->d_tile_seg, c->tl.tile_seg.data(), c->T * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(c->d_seg_first_tile, c->tl.seg_first_tile.data(), (n_seg + 1) * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(c->d_flags, 0, 64 * 4);
+    if (e == hipSuccess) e = hipMemset(c->c_pred, 0xFF, (size_t)n_seg * 4);      // no prediction yet
+    if (e == hipSuccess) e = hipMemset(c->c_skip, 0, (size_t)n_seg * 4);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);      // default priority
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_consumed, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_drawn, hipEventDisableTiming);
@@ -524,6 +534,8 @@ int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value)
     if (strcmp(name, "strided_tiles") == 0 && (value == 0 || value == 1)) { ctx->opt_strided = value; return SLIMDP_OK; }
     if (strcmp(name, "side_blocks") == 0 && value >= 1 && value <= 8) { ctx->opt_side_blocks = value; return SLIMDP_OK; }
     if (strcmp(name, "explore_hint_mode") == 0 && (value == 0 || value == 1)) { ctx->opt_hint_mode = value; return SLIMDP_OK; }
+    if (strcmp(name, "core_predict") == 0 && value >= 0 && value <= 2) { ctx->opt_core_predict = value; return SLIMDP_OK; }
+    if (strcmp(name, "build_blocks") == 0 && value >= 1 && value <= 64) { ctx->opt_build_blocks = value; return SLIMDP_OK; }
     if (strcmp(name, "pack_nbuf") == 0 && (value == 1 || value == 2)) { ctx->opt_pack_nbuf = value; return SLIMDP_OK; }
     if (strcmp(name, "expected_core") == 0 && value >= -1 && (value < 0 || (uint64_t)value <= ctx->n)) { ctx->opt_expected_core = value; return SLIMDP_OK; }
     if (strcmp(name, "score_pipeline") == 0 && (value == 0 || value == 1)) { ctx->opt_score_pipeline = value; return SLIMDP_OK; }
@@ -591,6 +603,7 @@ static int score_impl(slimdp_ctx* ctx, const float* w, const float* const* g, ui
     if (!table_ok(g, W)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_score: NULL update pointer");
     if (!(c >= 0.0f) || std::isinf(c)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_score: c must be finite and >= 0");
     ctx->hist_pending = false;
+    ctx->cls_by_score = false;
     int rc = fill(ctx, ctx->c_hist, (uint64_t)ctx->n_seg * H_STRIDE, 0u);
     if (rc) return rc;
     PtrTab gt = make_tab<PtrTab>(g, W);
@@ -643,7 +656,7 @@ static int score_impl(slimdp_ctx* ctx, const float* w, const float* const* g, ui
                                ctx->spec.sample);
             SLIMDP_LAUNCHED(ctx, "k_sample_keys");
             hipLaunchKernelGGL(k_sample_bound, dim3(1), dim3(1024), 0, ctx->stream, ctx->spec.sample, N, (uint32_t)need,
-                               (long long)ctx->opt_estimate_bias, ctx->spec.lo[ctx->spec.cur]);
+                               (long long)ctx->opt_estimate_bias, ctx->spec.lo[ctx->spec.cur], ctx->c_pred);
             SLIMDP_LAUNCHED(ctx, "k_sample_bound");
         }
     }
@@ -651,9 +664,10 @@ static int score_impl(slimdp_ctx* ctx, const float* w, const float* const* g, ui
     if (ctx->n_seg == 1 && vec_ok && ctx->opt_strided && ctx->opt_score_pipeline && ctx->n < (1ull << 30) &&
         (W == 1 || W == 2 || W == 4 || W == 8)) {
         const dim3 fgrid(persistent_blocks(ctx, SCOREF_MINB, 1)), fblock(BLOCK);
+        const ClsArgs cls{ctx->c_pred, ctx->c_used, (int)ctx->opt_core_predict, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys, ctx->c_cnt_gt, ctx->c_cnt_cand};
 #define LAUNCH_FLAT_Q(WT, PRE, SPEC, DENSE)                                                                           \
     hipLaunchKernelGGL((k_score_flat<WT, PRE, SPEC, DENSE>), fgrid, fblock, 0, ctx->stream, w, gt, c, score, ctx->n,  \
-                       ctx->c_hist, pre, sa, w_new, lr)
+                       ctx->c_hist, pre, sa, cls, w_new, lr)
 #define LAUNCH_FLAT_S(WT, SPEC, DENSE)                                                                                \
     do {                                                                                                              \
         if (presample && pairs) LAUNCH_FLAT_Q(WT, 2, SPEC, DENSE);                                                    \
@@ -676,6 +690,7 @@ static int score_impl(slimdp_ctx* ctx, const float* w, const float* const* g, ui
 #undef LAUNCH_FLAT_S
 #undef LAUNCH_FLAT_Q
         SLIMDP_LAUNCHED(ctx, "k_score_flat");
+        ctx->cls_by_score = true;
         if (presample) { ctx->pre = ctx->hint; ctx->pre.pairs = pairs; }
         if (capture) {
             ctx->spec.captured = true; ctx->spec.score = score; ctx->spec.W = W; ctx->spec.vec_ok = vec_ok; ctx->spec.core_epoch = 0;
@@ -778,7 +793,7 @@ static int select_core_impl(slimdp_ctx* ctx, const float* score, const uint64_t*
     const uint32_t T = ctx->T, S = ctx->n_seg;
     int rc = init_states(ctx, ctx->c_state, init, 1, 1);
     if (rc) return rc;
-    const uint32_t P = persistent_blocks(ctx, 4, 1);
+    const uint32_t P = persistent_blocks(ctx, (uint32_t)ctx->opt_build_blocks, 1);
     if (!reuse) {
         rc = fill(ctx, ctx->c_hist, (uint64_t)S * H_STRIDE, 0u);
         if (rc) return rc;
@@ -786,11 +801,15 @@ static int select_core_impl(slimdp_ctx* ctx, const float* score, const uint64_t*
                            ctx->c_hist);
         SLIMDP_LAUNCHED(ctx, "k_core_hist0");
     }
+    // did the scoring pass that made this histogram already sort the whole tiles against a predicted bin?
+    const bool classified = reuse && ctx->cls_by_score;
+    ctx->cls_by_score = false;
+    const CorePred cp{ctx->c_pred, ctx->c_skip, ctx->c_used, classified ? 1 : 0};
     hipLaunchKernelGGL(k_threshold, dim3(S, 1), dim3(256), 0, ctx->stream, ctx->c_state, ctx->c_hist, 0, (uint32_t)H_L0, S, 0,
-                       ctx->d_flags, nullptr, 0, SpecTau{nullptr, nullptr, nullptr});
+                       ctx->d_flags, nullptr, 0, SpecTau{nullptr, nullptr, nullptr}, cp);
     SLIMDP_LAUNCHED(ctx, "k_threshold(0)");
     hipLaunchKernelGGL(k_core_build, dim3(P), dim3(BLOCK), 0, ctx->stream, score, ctx->d_tile_start, ctx->d_tile_seg, T,
-                       ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys, ctx->c_cnt_gt,
+                       ctx->c_state, ctx->c_skip, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys, ctx->c_cnt_gt,
                        ctx->c_cnt_cand, (int)aligned16(score), (int)(S == 1 && ctx->opt_strided));
     SLIMDP_LAUNCHED(ctx, "k_core_build");
     MutPtrTab off_tab = make_tab<MutPtrTab, uint32_t*>(&core_off, 1);
@@ -802,7 +821,8 @@ static int select_core_impl(slimdp_ctx* ctx, const float* score, const uint64_t*
     uint32_t* pub = ctx->tl.word_aligned ? core_bits : nullptr;
     rc = finish_selection<CORE_KPL, 1>(ctx, 1, ctx->c_state, ctx->c_hist, ctx->c_gt_bits, ctx->c_cand_bits, ctx->c_cand_keys,
                           ctx->c_cnt_gt, ctx->c_cnt_cand, ctx->c_cnt_sel, ctx->c_cnt_tie, ctx->c_tie_pre, ctx->keys_stride,
-                          true, off_tab, idx_tab, (uint32_t)K, pub, nullptr, nullptr, ctx->c_chunk_sum, sp);
+                          true, off_tab, idx_tab, (uint32_t)K, pub, nullptr, nullptr, ctx->c_chunk_sum, sp,
+                          CorePred{ctx->c_pred, nullptr, nullptr, 0});
     if (rc) return rc;
     if (!pub) {
         rc = fill(ctx, core_bits, (ctx->n + 31) / 32, 0u);
@@ -997,7 +1017,7 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
                                (uint32_t)ctx->list_cap, ctx->e_state, ctx->e_hist, hoff[level], level, ctx->d_flags);
             SLIMDP_LAUNCHED(ctx, "k_short_hist");
             hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, ctx->stream, ctx->e_state, ctx->e_hist, level, hoff[level],
-                               S, level == 0 ? 1 : 0, ctx->d_flags, ctx->e_nsure, 1, SpecTau{nullptr, nullptr, nullptr});
+                               S, level == 0 ? 1 : 0, ctx->d_flags, ctx->e_nsure, 1, SpecTau{nullptr, nullptr, nullptr}, CorePred{nullptr, nullptr, nullptr, 0});
             SLIMDP_LAUNCHED(ctx, "k_threshold");
         }
         hipLaunchKernelGGL(k_short_mark, dim3(512), dim3(256), 0, ctx->stream, ctx->e_list, ctx->e_list_count,
@@ -1026,7 +1046,7 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
                            T, S, ctx->e_nsure);
         SLIMDP_LAUNCHED(ctx, "k_seg_sum");
         hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, ctx->stream, ctx->e_state, ctx->e_hist, 0, (uint32_t)H_L0, S, 1,
-                           ctx->d_flags, ctx->e_nsure, 0, SpecTau{nullptr, nullptr, nullptr});
+                           ctx->d_flags, ctx->e_nsure, 0, SpecTau{nullptr, nullptr, nullptr}, CorePred{nullptr, nullptr, nullptr, 0});
         SLIMDP_LAUNCHED(ctx, "k_threshold(0)");
         rc = finish_selection<EXPL_KPL, 4>(ctx, B, ctx->e_state, ctx->e_hist, ctx->e_sure_bits, ctx->e_cand_bits,
                               ctx->e_cand_keys, ctx->e_cnt_gt, ctx->e_cnt_cand, ctx->e_cnt_sel, ctx->e_cnt_tie, ctx->e_tie_pre,

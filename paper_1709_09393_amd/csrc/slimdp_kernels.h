@@ -551,7 +551,7 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
 // goes to one block after its loop, element by element.
 // ---------------------------------------------------------------------------------------
 #ifndef SCOREF_MINB
-#define SCOREF_MINB 3
+#define SCOREF_MINB 2
 #endif
 #ifndef SCOREF_LD_AUX
 #define SCOREF_LD_AUX 2
@@ -562,19 +562,30 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
 #ifndef SCOREF_CAP_AUX
 #define SCOREF_CAP_AUX 2
 #endif
+// cls.pred[0] != NONE: every whole tile is also sorted against that predicted level-0 threshold bin, exactly as
+// k_core_build would do it once the bin is known (certain bitmap, candidate bitmap, candidate keys compacted per
+// sub-tile, counts): if the histogram then confirms the bin, the selection need not read the scores again.
+struct ClsArgs {
+    const uint32_t* pred;
+    uint32_t* used;          // [0]: the bin this launch classified against (NONE: it did not)
+    int mode;                // 1: pred[0]; test switches: 0 never classify, 2 take the bin above the prediction (always wrong)
+    uint32_t *gt_bits, *cand_bits, *cand_keys, *cnt_gt, *cnt_cand;
+};
 template <int WT, int PRE, int SPEC, int DENSE>
 __global__ __launch_bounds__(BLOCK, SCOREF_MINB) void k_score_flat(const float* __restrict__ w, PtrTab g, float c,
                                                                    float* __restrict__ S, uint64_t n, uint32_t* __restrict__ hist,
-                                                                   PreArgs pre, SpecArgs spec, float* __restrict__ w_new, float lr)
+                                                                   PreArgs pre, SpecArgs spec, ClsArgs cls, float* __restrict__ w_new, float lr)
 {
     static_assert(WT >= 1 && WT <= 8, "two rounds of W + 1 vectors must fit the registers");
     static_assert(!(SPEC && DENSE), "a dense update is never followed by a pack of the same updates");
     constexpr uint32_t NB = CORE_NB0 / 2;
     __shared__ uint32_t h[NB];
     __shared__ __align__(16) float stage[SPEC ? 4 * 256 * WT : 4];
+    __shared__ uint32_t h1[CORE_NB1];                // level-1 digits of the candidates of the predicted bin
     const uint32_t lane = lane_id(), wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t T_full = (uint32_t)(n / TILE), T = (uint32_t)((n + TILE - 1) / TILE);
     for (uint32_t b = threadIdx.x; b < NB; b += BLOCK) h[b] = 0;
+    for (uint32_t b = threadIdx.x; b < CORE_NB1; b += BLOCK) h1[b] = 0;
     __syncthreads();
     const uint32_t bytes = (uint32_t)(n * 4u);
     const __amdgpu_buffer_rsrc_t rw = buffer_of(w, bytes), rS = buffer_of(S, bytes), rn = buffer_of(DENSE ? w_new : S, bytes);
@@ -588,6 +599,10 @@ __global__ __launch_bounds__(BLOCK, SCOREF_MINB) void k_score_flat(const float* 
     }
     uint32_t spec_lo = 0xFFFFFFFFu;
     if (SPEC) spec_lo = spec.lo[0];
+    uint32_t b1 = cls.mode ? cls.pred[0] : NONE;     // predicted threshold bin, NONE: no prediction
+    if (cls.mode == 2 && b1 != NONE) b1 += 1u;
+    if (blockIdx.x == 0 && threadIdx.x == 0) cls.used[0] = b1;
+    uint32_t crun = 0, ngt = 0, gw[4], cw[4];
     // byte offset of this lane's vector in round r of this wave's sub-tile of tile t
     auto voff = [&](uint32_t t, uint32_t r) { return (t * TILE + wid * SUB + r * 256u) * 4u + lane * 16u; };
     auto fetch = [&](float4 (&x)[WT + 1], uint32_t t, uint32_t r) {
@@ -631,6 +646,47 @@ __global__ __launch_bounds__(BLOCK, SCOREF_MINB) void k_score_flat(const float* 
         atomicAdd(&h[(__float_as_uint(sc.y) >> CORE_SHIFT0) & (NB - 1u)], 1u);
         atomicAdd(&h[(__float_as_uint(sc.z) >> CORE_SHIFT0) & (NB - 1u)], 1u);
         atomicAdd(&h[(__float_as_uint(sc.w) >> CORE_SHIFT0) & (NB - 1u)], 1u);
+        if (b1 != NONE) {                            // uniform
+            if (r == 0) { crun = 0; ngt = 0; }
+            const uint32_t d0 = __float_as_uint(sc.x) >> CORE_SHIFT0, d1 = __float_as_uint(sc.y) >> CORE_SHIFT0,
+                           d2 = __float_as_uint(sc.z) >> CORE_SHIFT0, d3 = __float_as_uint(sc.w) >> CORE_SHIFT0;
+            const uint32_t fg = (d0 > b1 ? 1u : 0u) | (d1 > b1 ? 2u : 0u) | (d2 > b1 ? 4u : 0u) | (d3 > b1 ? 8u : 0u);
+            const uint32_t fc = (d0 == b1 ? 1u : 0u) | (d1 == b1 ? 2u : 0u) | (d2 == b1 ? 4u : 0u) | (d3 == b1 ? 8u : 0u);
+            gw[r] = or_reduce8(fg << (4u * (lane & 7u)));
+            cw[r] = or_reduce8(fc << (4u * (lane & 7u)));
+            ngt += __popc(fg);
+            if (__ballot(fc != 0u) != 0ull) {
+                uint32_t below = 0, total = 0;
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    const unsigned long long bal = __ballot((fc >> cc) & 1u);
+                    below += __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+                    total += (uint32_t)__popcll(bal);
+                }
+                if (fc) {
+                    const __amdgpu_buffer_rsrc_t rk = buffer_of(cls.cand_keys + (size_t)t * TILE + wid * SUB, SUB * 4u);
+                    uint32_t pos = crun + below;
+                    if (fc & 1u) { buffer_store1(rk, 4u * pos++, __float_as_uint(sc.x)); atomicAdd(&h1[(__float_as_uint(sc.x) >> CORE_SHIFT1) & (CORE_NB1 - 1u)], 1u); }
+                    if (fc & 2u) { buffer_store1(rk, 4u * pos++, __float_as_uint(sc.y)); atomicAdd(&h1[(__float_as_uint(sc.y) >> CORE_SHIFT1) & (CORE_NB1 - 1u)], 1u); }
+                    if (fc & 4u) { buffer_store1(rk, 4u * pos++, __float_as_uint(sc.z)); atomicAdd(&h1[(__float_as_uint(sc.z) >> CORE_SHIFT1) & (CORE_NB1 - 1u)], 1u); }
+                    if (fc & 8u) { buffer_store1(rk, 4u * pos, __float_as_uint(sc.w)); atomicAdd(&h1[(__float_as_uint(sc.w) >> CORE_SHIFT1) & (CORE_NB1 - 1u)], 1u); }
+                }
+                crun += total;
+            }
+            if (r == 3) {          // the sub-tile's 32 + 32 bitmap words as whole lines, its two counts
+                const int src = (int)(8u * (lane & 7u));
+                uint32_t og = 0, oc = 0;
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const uint32_t xg = __shfl(gw[rr], src, 64), xc = __shfl(cw[rr], src, 64);
+                    if ((lane >> 3) == (uint32_t)rr) { og = xg; oc = xc; }
+                }
+                const size_t wbase = (size_t)t * TILE_WORDS + wid * SUB_WORDS;
+                if (lane < SUB_WORDS) { cls.gt_bits[wbase + lane] = og; cls.cand_bits[wbase + lane] = oc; }
+                const uint32_t ng = wave_sum(ngt);
+                if (lane == 0) { cls.cnt_cand[(size_t)t * SUBS + wid] = crun; cls.cnt_gt[(size_t)t * SUBS + wid] = ng; }
+            }
+        }
         if (SPEC) {
             if (r == 0) spec_run = 0;
             const uint32_t f = (__float_as_uint(sc.x) >= spec_lo ? 1u : 0u) | (__float_as_uint(sc.y) >= spec_lo ? 2u : 0u) |
@@ -732,6 +788,7 @@ __global__ __launch_bounds__(BLOCK, SCOREF_MINB) void k_score_flat(const float* 
     }
     __syncthreads();
     flush_hist(h, NB, hist + H_L0);
+    if (b1 != NONE) flush_hist(h1, CORE_NB1, hist + H_L1);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -760,13 +817,13 @@ __global__ __launch_bounds__(256) void k_sample_keys(const float* __restrict__ w
 
 // bias: test switch, added to the bound (in units of the last place, clamped).
 __global__ __launch_bounds__(1024) void k_sample_bound(const uint32_t* __restrict__ keys, uint32_t N, uint32_t need,
-                                                       long long bias, uint32_t* __restrict__ lo)
+                                                       long long bias, uint32_t* __restrict__ lo, uint32_t* __restrict__ pred)
 {
     __shared__ uint32_t h[4096];
     __shared__ uint32_t wtot[16];
     __shared__ uint32_t sh[2];
     const uint32_t tid = threadIdx.x;
-    if (need == 0 || need > N) { if (tid == 0) lo[0] = NONE; return; }       // nothing to estimate: nothing is captured
+    if (need == 0 || need > N) { if (tid == 0) { lo[0] = NONE; pred[0] = NONE; } return; }   // nothing to estimate, nothing captured
     uint32_t prefix = 0, want = need;
 #pragma unroll 1
     for (int level = 0; level < 2; ++level) {
@@ -803,6 +860,7 @@ __global__ __launch_bounds__(1024) void k_sample_bound(const uint32_t* __restric
         if (b < 0) b = 0;
         if (b > 0x7FFFFFFFll) b = 0x7FFFFFFFll;
         lo[0] = (uint32_t)b;
+        pred[0] = prefix >> 12;          // the level-0 bin of the estimated threshold
     }
 }
 
@@ -847,12 +905,18 @@ __global__ __launch_bounds__(BLOCK) void k_core_hist0(const float* __restrict__ 
 // next[seg] becomes the capture bound of the next scoring pass: the new threshold less
 // 2^17 units in the last place (0.8 % to 1.6 %).
 struct SpecTau { const uint32_t* cur; uint32_t* next; uint32_t* fail; };
+// Core selection whose scoring pass already sorted every whole tile against a PREDICTED level-0 threshold bin
+// (used[seg]: what the scoring pass took, normally pred[seg], the bin of the previous threshold): level 0 tells per
+// segment whether the prediction held
+// (skip[seg] = 1: the candidate pass has nothing left to do for whole tiles), the last level records the bin
+// of the new threshold as the next prediction.  check = 0: the scoring pass did not classify.
+struct CorePred { uint32_t* pred; uint32_t* skip; const uint32_t* used; int check; };
 constexpr uint32_t SPEC_MARGIN = 1u << 17;
 
-__global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states, const uint32_t* __restrict__ hist,
+__global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states, uint32_t* __restrict__ hist,
                                                    int level, uint32_t hist_off, uint32_t n_seg, int mode,
                                                    uint32_t* __restrict__ flags, const uint32_t* __restrict__ nsure, int gate,
-                                                   SpecTau sp)
+                                                   SpecTau sp, CorePred cp)
 {
     __shared__ uint32_t wtot[4];
     __shared__ uint32_t sh_bcast[2];
@@ -884,6 +948,8 @@ __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states
         if (threadIdx.x == 0) {
             st->none = 1; st->need = 0; st->tau = NONE; st->quota = 0;
             if (level == 2 && sp.next) { sp.fail[seg] = 0; sp.next[seg] = NONE; }      // nothing selected, nothing to capture
+            if (cp.skip && level == 0) cp.skip[seg] = 0;
+            if (cp.pred && level == 2) cp.pred[seg] = NONE;
         }
         return;
     }
@@ -897,6 +963,7 @@ __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states
         if (threadIdx.x == 0) {
             if (mode == 1) atomicOr(&flags[0], 1u);                    // too few candidates: exact rerun
             else { atomicOr(&flags[1], 2u); st->none = 1; st->need = 0; st->tau = NONE; st->quota = 0; }
+            if (cp.skip && level == 0) cp.skip[seg] = 0;
         }
         return;
     }
@@ -909,6 +976,12 @@ __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states
                 const uint32_t np = (level == 0) ? bin : ((prefix << bits) | bin);
                 st->prefix = np;
                 st->need = need - run;
+                if (cp.skip && level == 0) {
+                    const uint32_t ok = (cp.check && cp.used[seg] == np) ? 1u : 0u;
+                    cp.skip[seg] = ok;
+                    sh_bcast[1] = ok;
+                }
+                if (cp.pred && level == 2) cp.pred[seg] = np >> CORE_SHIFT0;
                 if (level == 2) {
                     st->tau = np; st->quota = need - run; st->tie_all = (need - run == cnt) ? 1u : 0u;
                     if (sp.next) {
@@ -919,6 +992,14 @@ __global__ __launch_bounds__(256) void k_threshold(SegState* __restrict__ states
                 break;
             }
             run += cnt;
+        }
+    }
+    if (cp.skip && level == 0 && cp.check) {
+        // the scoring pass has already added the level-1 digits of ITS candidates: if they belong to another bin they go
+        __syncthreads();
+        if (sh_bcast[1] == 0) {
+            uint32_t* h1 = hist + ((size_t)b * n_seg + seg) * H_STRIDE + H_L1;
+            for (uint32_t x = threadIdx.x; x < CORE_NB1; x += 256) h1[x] = 0;
         }
     }
 }
@@ -994,12 +1075,11 @@ __device__ __forceinline__ void core_classify(const uint32_t key[4][4], uint32_t
         if (fc) {
             uint32_t pos = run + below;
 #pragma unroll
-            for (int cc = 0; cc < 4; ++cc) {
+            for (int cc = 0; cc < 4; ++cc)
                 if ((fc >> cc) & 1u) {
                     ckeys[pos++] = key[it][cc];
                     atomicAdd(&h[(key[it][cc] >> CORE_SHIFT1) & (CORE_NB1 - 1u)], 1u);
                 }
-            }
         }
         run += total;
     }
@@ -1007,36 +1087,47 @@ __device__ __forceinline__ void core_classify(const uint32_t key[4][4], uint32_t
     if (lane == 0) { cnt_cand[(size_t)t * SUBS + wid] = run; cnt_gt[(size_t)t * SUBS + wid] = ngt; }
 }
 
+// skip [n_seg] (may be nullptr): 1 = the scoring pass has already classified every whole, 4-aligned tile of the
+// segment against the right bin; only ragged or unaligned tiles are left.
 __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ S, const uint32_t* __restrict__ tile_start,
                                                       const uint32_t* __restrict__ tile_seg, uint32_t T,
-                                                      const SegState* __restrict__ states, uint32_t* __restrict__ hist,
+                                                      const SegState* __restrict__ states, const uint32_t* __restrict__ skip,
+                                                      uint32_t* __restrict__ hist,
                                                       uint32_t* __restrict__ gt_bits, uint32_t* __restrict__ cand_bits,
                                                       uint32_t* __restrict__ cand_keys, uint32_t* __restrict__ cnt_gt,
                                                       uint32_t* __restrict__ cnt_cand, int vec_ok, int strided)
 {
     __shared__ uint32_t h[CORE_NB1];
     const uint32_t lane = lane_id(), wid = threadIdx.x >> 6;
-    for (uint32_t b = threadIdx.x; b < CORE_NB1; b += BLOCK) h[b] = 0;
-    __syncthreads();
     // a contiguous range of tiles, or (flat model) every gridDim.x-th tile: see k_score
     uint32_t t0 = (uint32_t)((uint64_t)T * blockIdx.x / gridDim.x);
     uint32_t t1 = (uint32_t)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
     uint32_t tstep = 1;
     if (strided) { t0 = blockIdx.x; t1 = T; tstep = gridDim.x; }
     if (t0 >= t1) return;
+    auto done = [&](uint32_t t) {       // already classified by the scoring pass?
+        if (!skip || !skip[tile_seg[t]]) return false;
+        const uint32_t start = tile_start[t];
+        return tile_start[t + 1] - start == TILE && (start & 3u) == 0;
+    };
+    // flat model, prediction held: only a ragged last tile can be left, and most blocks do not own it
+    if (strided && skip && skip[0] && (T - 1) % gridDim.x != blockIdx.x) return;
+    for (uint32_t b = threadIdx.x; b < CORE_NB1; b += BLOCK) h[b] = 0;
+    __syncthreads();
     uint32_t cur_seg = tile_seg[t0];
     // two tiles a turn: the scores of both are requested before either is worked on
     for (uint32_t t = t0; t < t1; t += 2 * tstep) {
         const uint32_t tB = t + tstep;
-        const bool two = tB < t1;
+        const bool one = !done(t), two = tB < t1 && !done(tB);
+        if (!one && !two) continue;
         const uint32_t startA = tile_start[t], lenA = tile_start[t + 1] - startA;
         const uint32_t startB = two ? tile_start[tB] : 0u, lenB = two ? tile_start[tB + 1] - startB : 0u;
         uint32_t keyA[4][4], keyB[4][4];
-        core_load_keys(S, startA, lenA, wid, lane, vec_ok, keyA);
+        if (one) core_load_keys(S, startA, lenA, wid, lane, vec_ok, keyA);
         if (two) core_load_keys(S, startB, lenB, wid, lane, vec_ok, keyB);
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-            if (half == 1 && !two) break;
+            if (half == 0 ? !one : !two) continue;
             const uint32_t tt = half ? tB : t;
             const uint32_t seg = tile_seg[tt];
             if (seg != cur_seg) {

@@ -389,6 +389,33 @@ def test_first_iteration_captures_under_a_sampled_bound(bias, announced):
     sd.close()
 
 
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_selection_with_the_scoring_pass_classifying_against_a_predicted_bin(mode):
+    """Flat models: the scoring pass sorts whole tiles against the previous selection's threshold bin and the selection
+    skips its own pass over the scores when the histogram confirms the bin.  mode 1 as shipped (iterations 1.. predict
+    from the iteration before; a much larger core in between moves the bin, so the prediction fails there), 0 never,
+    2 always a wrong bin: the same sets in every case.  Also through the dense update + score call."""
+    wl = workloads.TINY.scaled(500_003)                 # 122 whole tiles and a ragged one
+    sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
+    sd.set_option("core_predict", mode)
+    sd.set_option("speculative_pack", 1)
+    for t, pct in enumerate([10, 10, 30, 30, 1, 10]):
+        wl2 = workloads.TINY.scaled(wl.n, core_pct=pct)
+        got, want = run_iteration(wl2, iteration=t, sd=sd, hint=(t % 2 == 0))
+        assert_iteration_matches(wl2, got, want)
+    w_h, g_h = wl.weights(), wl.gradients(9)
+    w, g = to_dev(w_h), [to_dev(x) for x in g_h]
+    for rep in range(2):                                # the second call predicts from the first one's selection
+        w_h, S_o = oracle.dense_update_score(w_h, g_h, wl.lr, wl.c)
+        S = sd.dense_update_score(w, g, wl.lr, wl.c)
+        core_idx, core_bits, core_off, epoch = sd.select_core(S, [wl.k], reuse_histogram=True)
+        sd.synchronize()
+        core_o = oracle.select_core(S_o, wl.k)
+        assert np.array_equal(u32(core_idx), core_o), rep
+        assert np.array_equal(u32(core_bits), oracle.core_bits(wl.n, core_o)), rep
+    sd.close()
+
+
 def test_pack_without_the_flag_reads_the_buffers_it_is_given():
     """The update buffers are refilled in place between the scoring pass and the pack (what a training loop that
     reuses its buffers does between two iterations): without SLIMDP_PACK_UPDATES_AS_SCORED the pack must extract the
