@@ -19,8 +19,9 @@
  *    piece of work that may run elsewhere is an announced explorer draw on the library's
  *    own side stream (option "explore_hint_mode" = 1); the calls that need its result
  *    make the caller's stream wait for it.
- *  - The library allocates device memory in slimdp_create, and once more when the option
- *    "speculative_pack" is first switched on.
+ *  - The library allocates device memory in slimdp_create, once more when the option
+ *    "speculative_pack" is first switched on (slimdp_capture_bytes), and once more on the first
+ *    explorer request whose zones are wide (see slimdp_capture_bytes); never otherwise.
  *  - Same inputs give the same output bits, whatever the launch geometry.
  *  - Indices are 0-based uint32 (the paper counts from 1); n < 2^32.
  *
@@ -79,6 +80,10 @@ int slimdp_destroy(slimdp_ctx* ctx);
 /* Device bytes slimdp_create allocates; 0 if the arguments are invalid.  Pure host function. */
 uint64_t slimdp_workspace_bytes(uint64_t n, uint32_t max_workers, uint32_t n_seg,
                                 const uint64_t* seg_off);
+/* Device bytes that switching option "speculative_pack" on allocates on top; 0 if the arguments are invalid.
+ * Explorer requests with wide zones (m at least a quarter of what lies outside the core) allocate once more,
+ * 4 * max_workers * (n rounded up to tiles + one tile) bytes, on their first occurrence.  Pure host function. */
+uint64_t slimdp_capture_bytes(uint64_t n, uint32_t max_workers, uint32_t n_seg, const uint64_t* seg_off);
 /* Number of tiles T; 0 if the arguments are invalid.  Pure host function. */
 uint64_t slimdp_num_tiles(uint64_t n, uint32_t n_seg, const uint64_t* seg_off);
 /* tile_start [host, T+1]: start index of every tile, tile_start[T] = n. */
@@ -97,8 +102,8 @@ int slimdp_synchronize(slimdp_ctx* ctx);
 /* Options.  Known names:
  *   "speculative_pack" (0/1, default 0): slimdp_score additionally keeps the update values of
  *       every parameter whose significance reaches the threshold of the previous
- *       slimdp_select_core less a small margin (own device allocation of about 4*W*n bytes,
- *       made by this call); if the following slimdp_select_core(..REUSE_HISTOGRAM) finds its
+ *       slimdp_select_core less a small margin, up to a quarter of every 1024 parameters (own device
+ *       allocation of about W*n bytes, made by this call: slimdp_capture_bytes); if the following slimdp_select_core(..REUSE_HISTOGRAM) finds its
  *       threshold at or above that bound, the next slimdp_pack takes the core values from
  *       there instead of scanning the update vectors again, PROVIDED that call carries the
  *       flag SLIMDP_PACK_UPDATES_AS_SCORED (see slimdp_pack); without the flag a pack always

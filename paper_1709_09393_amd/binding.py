@@ -31,7 +31,7 @@ LOCAL_FIRST = 1
 QUANT_BUCKET = 512
 
 EXPORTS = [
-    "slimdp_create", "slimdp_destroy", "slimdp_workspace_bytes", "slimdp_num_tiles",
+    "slimdp_create", "slimdp_destroy", "slimdp_workspace_bytes", "slimdp_capture_bytes", "slimdp_num_tiles",
     "slimdp_tile_starts", "slimdp_last_error", "slimdp_synchronize", "slimdp_set_option",
     "slimdp_score", "slimdp_dense_update_score", "slimdp_select_core", "slimdp_sample_explore", "slimdp_explore_hint", "slimdp_tile_offsets",
     "slimdp_pack", "slimdp_merge", "slimdp_pull", "slimdp_core_signature", "slimdp_debug_philox",
@@ -66,6 +66,8 @@ def load() -> C.CDLL:
     L.slimdp_destroy.restype = C.c_int
     L.slimdp_workspace_bytes.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, _u64p]
     L.slimdp_workspace_bytes.restype = C.c_uint64
+    L.slimdp_capture_bytes.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, _u64p]
+    L.slimdp_capture_bytes.restype = C.c_uint64
     L.slimdp_num_tiles.argtypes = [C.c_uint64, C.c_uint32, _u64p]
     L.slimdp_num_tiles.restype = C.c_uint64
     L.slimdp_tile_starts.argtypes = [_vp, C.POINTER(C.c_uint32)]
@@ -134,6 +136,11 @@ def num_tiles(n: int, seg_off=None) -> int:
 def workspace_bytes(n: int, max_workers: int, seg_off=None) -> int:
     so = [0, n] if seg_off is None else [int(x) for x in seg_off]
     return int(load().slimdp_workspace_bytes(n, max_workers, len(so) - 1, _u64arr(so)))
+
+
+def capture_bytes(n: int, max_workers: int, seg_off=None) -> int:
+    so = [0, n] if seg_off is None else [int(x) for x in seg_off]
+    return int(load().slimdp_capture_bytes(n, max_workers, len(so) - 1, _u64arr(so)))
 
 
 def _ptr(t) -> Optional[int]:

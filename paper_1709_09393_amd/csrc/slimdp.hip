@@ -110,7 +110,11 @@ struct slimdp_ctx {
     // explorer selection (batch = worker)
     SegState* e_state = nullptr;
     SegState* e_draw_state = nullptr;      // zone bounds of the announced draw (side stream)
-    uint32_t *e_hist = nullptr, *e_sure_bits = nullptr, *e_cand_bits = nullptr, *e_cand_keys = nullptr;
+    uint32_t *e_hist = nullptr, *e_sure_bits = nullptr, *e_cand_bits = nullptr;
+    uint32_t* e_pair_keys = nullptr;       // narrow zones: per sub-tile a slot of (key, offset) pairs
+    uint64_t pair_stride = 0;              // words per worker of the pair slots
+    uint32_t* e_cand_keys = nullptr;       // wide zones: candidate keys compacted per sub-tile over the whole index range;
+                                           // its own allocation, made by the first request that needs it
     uint32_t *e_cnt_gt = nullptr, *e_nsure = nullptr, *e_list_count = nullptr, *e_chunk_sum = nullptr, *e_tie_list = nullptr;
     uint4* e_list = nullptr;
     uint64_t list_cap = 0;
@@ -212,7 +216,7 @@ void carve(slimdp_ctx* c, Carver& cv)
     c->e_tie_list = cv.take<uint32_t>(TIE_CAP);
     c->e_chunk_sum = cv.take<uint32_t>(2 * B * c->n_chunks);   // tie sums, then offset sums
     c->e_list = cv.take<uint4>(c->list_cap);
-    c->e_cand_keys = cv.take<uint32_t>(B * c->keys_stride);
+    c->e_pair_keys = cv.take<uint32_t>(B * c->pair_stride);
     c->e_cnt_cand = cv.take<uint32_t>(B * T * SUBS);
     c->e_cnt_sel = cv.take<uint32_t>(B * T);
     c->e_cnt_tie = cv.take<uint32_t>(B * T);
@@ -355,6 +359,20 @@ int check_epoch(slimdp_ctx* c, uint64_t core_epoch)
     return SLIMDP_OK;
 }
 
+// Explorer requests whose zones are not narrow compact their candidate keys over the whole index range: that buffer
+// (4 bytes per parameter and worker) is allocated by the first such request and kept.
+int ensure_wide_keys(slimdp_ctx* c)
+{
+    if (c->e_cand_keys) return SLIMDP_OK;
+    const size_t bytes = (size_t)c->maxW * c->keys_stride * sizeof(uint32_t);
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->e_cand_keys), bytes);
+    if (e != hipSuccess) {
+        c->e_cand_keys = nullptr;
+        return fail(c, SLIMDP_ERR_WORKSPACE, "explorer with wide zones: hipMalloc(%zu bytes): %s", bytes, hipGetErrorString(e));
+    }
+    return SLIMDP_OK;
+}
+
 // Per-segment start of the explorer's radix descent.  The m-th smallest Philox word of the
 // avail = n_s - k_s parameters outside the core lies, with overwhelming probability, between
 // the words that m - 6 sqrt(m) - 32 and m + 6 sqrt(m) + 32 of them are expected to stay below:
@@ -433,11 +451,24 @@ uint64_t slimdp_workspace_bytes(uint64_t n, uint32_t max_workers, uint32_t n_seg
     tmp.n = n; tmp.maxW = max_workers; tmp.n_seg = n_seg;
     tmp.T = (uint32_t)count_tiles(n, n_seg, seg_off);
     tmp.keys_stride = align_up(n, TILE) + TILE;
+    tmp.pair_stride = (uint64_t)tmp.T * SUBS * PAIR_SLOT;
     tmp.n_chunks = (tmp.T + SCAN_CHUNK - 1) / SCAN_CHUNK;
     tmp.list_cap = (uint64_t)tmp.maxW * (64ull * tmp.T + 8192ull);
     if (tmp.list_cap > 0x40000000ull) tmp.list_cap = 0x40000000ull;
     Carver cv(nullptr);
     carve(&tmp, cv);
+    return align_up(cv.pos, 256);
+}
+
+uint64_t slimdp_capture_bytes(uint64_t n, uint32_t max_workers, uint32_t n_seg, const uint64_t* seg_off)
+{
+    if (!valid_shape(n, n_seg, seg_off) || max_workers == 0 || max_workers > SLIMDP_MAX_WORKERS) return 0;
+    const uint64_t T = count_tiles(n, n_seg, seg_off);
+    Carver cv(nullptr);
+    cv.take<uint32_t>(n_seg); cv.take<uint32_t>(n_seg); cv.take<uint32_t>(n_seg);
+    cv.take<uint2>((size_t)T * TILE_WORDS);
+    cv.take<float>((size_t)max_workers * T * SUBS * SPEC_CAP);
+    cv.take<uint32_t>((size_t)T * SAMPLE_PER);
     return align_up(cv.pos, 256);
 }
 
@@ -462,6 +493,7 @@ int slimdp_create(slimdp_ctx** out, uint64_t n, uint32_t max_workers, uint32_t n
     c->tl = make_tiling(n, n_seg, seg_off);
     c->T = (uint32_t)c->tl.tile_seg.size();
     c->keys_stride = align_up(n, TILE) + TILE;
+    c->pair_stride = (uint64_t)c->T * SUBS * PAIR_SLOT;
     c->n_chunks = (c->T + SCAN_CHUNK - 1) / SCAN_CHUNK;
     c->list_cap = (uint64_t)c->maxW * (64ull * c->T + 8192ull);
     if (c->list_cap > 0x40000000ull) c->list_cap = 0x40000000ull;
@@ -515,6 +547,7 @@ int slimdp_destroy(slimdp_ctx* ctx)
     (void)hipStreamDestroy(ctx->side);
     hipError_t e = hipFree(ctx->ws);
     if (ctx->spec.mem) (void)hipFree(ctx->spec.mem);
+    if (ctx->e_cand_keys) (void)hipFree(ctx->e_cand_keys);
     delete ctx;
     return e == hipSuccess ? SLIMDP_OK : SLIMDP_ERR_HIP;
 }
@@ -550,7 +583,7 @@ int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value)
                 ctx->spec.lo[1] = cv.take<uint32_t>(S);
                 ctx->spec.fail = cv.take<uint32_t>(S);
                 ctx->spec.bits = cv.take<uint2>((size_t)ctx->T * TILE_WORDS);
-                ctx->spec.vals = cv.take<float>((size_t)ctx->maxW * ctx->keys_stride);
+                ctx->spec.vals = cv.take<float>((size_t)ctx->maxW * ctx->T * SUBS * SPEC_CAP);
                 ctx->spec.sample = cv.take<uint32_t>((size_t)ctx->T * SAMPLE_PER);
             };
             carve_spec(sizing);
@@ -627,7 +660,9 @@ static int score_impl(slimdp_ctx* ctx, const float* w, const float* const* g, ui
             if (rc) return rc;
             pre.nw = ctx->hint.n_workers; pre.worker0 = ctx->hint.worker0; pre.n_seg = ctx->n_seg;
             pre.states = ctx->e_state; pre.sure_bits = ctx->e_sure_bits; pre.cand_bits = ctx->e_cand_bits;
-            pre.cand_keys = ctx->e_cand_keys; pre.cnt_cand = ctx->e_cnt_cand; pre.keys_stride = ctx->keys_stride;
+            if (!pairs) { rc = ensure_wide_keys(ctx); if (rc) return rc; }
+            pre.cand_keys = pairs ? ctx->e_pair_keys : ctx->e_cand_keys; pre.cnt_cand = ctx->e_cnt_cand;
+            pre.keys_stride = pairs ? ctx->pair_stride : ctx->keys_stride;
             pre.pk = PhiloxKey{(uint32_t)ctx->seed, (uint32_t)(ctx->seed >> 32), (uint32_t)ctx->hint.iteration,
                                (uint32_t)(ctx->hint.iteration >> 32)};
             presample = true;
@@ -989,11 +1024,13 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
         if (ctx->tl.quad_aligned)                                                                                        \
             hipLaunchKernelGGL((k_explore_keys<1, PAIRS>), dim3(P, B), dim3(BLOCK), 0, ctx->stream, ctx->d_tile_start,   \
                                ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_sure_bits, ctx->e_cand_bits,                  \
-                               ctx->e_cand_keys, ctx->e_cnt_cand, ctx->keys_stride, worker0, pk);                        \
+                               (PAIRS) ? ctx->e_pair_keys : ctx->e_cand_keys, ctx->e_cnt_cand,                           \
+                               (PAIRS) ? ctx->pair_stride : ctx->keys_stride, worker0, pk);                              \
         else                                                                                                             \
             hipLaunchKernelGGL((k_explore_keys<0, PAIRS>), dim3(P, B), dim3(BLOCK), 0, ctx->stream, ctx->d_tile_start,   \
                                ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_sure_bits, ctx->e_cand_bits,                  \
-                               ctx->e_cand_keys, ctx->e_cnt_cand, ctx->keys_stride, worker0, pk);                        \
+                               (PAIRS) ? ctx->e_pair_keys : ctx->e_cand_keys, ctx->e_cnt_cand,                           \
+                               (PAIRS) ? ctx->pair_stride : ctx->keys_stride, worker0, pk);                              \
         SLIMDP_LAUNCHED(ctx, "k_explore_keys");                                                                          \
     } while (0)
     if (short_list) {
@@ -1008,7 +1045,7 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
                            ctx->e_nsure);
         SLIMDP_LAUNCHED(ctx, "k_seg_sum");
         hipLaunchKernelGGL(k_cand_gather, dim3((uint32_t)(((uint64_t)B * T + 1023) / 1024)), dim3(1024), 0, ctx->stream,
-                           core_bits, ctx->n, ctx->d_tile_start, ctx->d_tile_seg, T, S, B, ctx->e_cand_keys, ctx->keys_stride,
+                           core_bits, ctx->n, ctx->d_tile_start, ctx->d_tile_seg, T, S, B, ctx->e_pair_keys, ctx->pair_stride,
                            ctx->e_cnt_cand, ctx->e_list, ctx->e_list_count, (uint32_t)ctx->list_cap, ctx->d_flags);
         SLIMDP_LAUNCHED(ctx, "k_cand_gather");
         const uint32_t hoff[3] = {H_L0, H_L1, H_L2};
@@ -1037,6 +1074,8 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
         SLIMDP_LAUNCHED(ctx, "k_emit_bits");
     } else {
         // zones that are not narrow: the per-tile tail that the core selection uses
+        rc = ensure_wide_keys(ctx);
+        if (rc) return rc;
         if (!cached) LAUNCH_DRAW(0);
         hipLaunchKernelGGL(k_explore_filter, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->n, ctx->d_tile_start,
                            ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_sure_bits, ctx->e_cnt_gt, ctx->e_cand_bits,
@@ -1083,6 +1122,7 @@ int slimdp_explore_hint(slimdp_ctx* ctx, const uint64_t* k_seg, uint32_t worker0
         return SLIMDP_OK;
     }
     if (!narrow || M == 0) return SLIMDP_OK;  // nothing worth drawing ahead: slimdp_sample_explore draws itself
+    if (!short_list) { rc = ensure_wide_keys(ctx); if (rc) return rc; }
     // the draw starts now on the side stream, once the previous draw's buffers have been read
     // (the event is recorded here, not after every slimdp_sample_explore: an event on a stream costs a gap between kernels)
     SLIMDP_HIP(ctx, hipEventRecord(ctx->ev_consumed, ctx->stream));
@@ -1095,8 +1135,9 @@ int slimdp_explore_hint(slimdp_ctx* ctx, const uint64_t* k_seg, uint32_t worker0
     const dim3 grid(P, n_workers), block(BLOCK);
 #define LAUNCH_SIDE_DRAW(FAST, PAIRS)                                                                                   \
     hipLaunchKernelGGL((k_explore_keys<FAST, PAIRS>), grid, block, 0, ctx->side, ctx->d_tile_start, ctx->d_tile_seg,    \
-                       ctx->T, ctx->n_seg, ctx->e_draw_state, ctx->e_sure_bits, ctx->e_cand_bits, ctx->e_cand_keys,     \
-                       ctx->e_cnt_cand, ctx->keys_stride, worker0, pk)
+                       ctx->T, ctx->n_seg, ctx->e_draw_state, ctx->e_sure_bits, ctx->e_cand_bits,                       \
+                       (PAIRS) ? ctx->e_pair_keys : ctx->e_cand_keys, ctx->e_cnt_cand,                                  \
+                       (PAIRS) ? ctx->pair_stride : ctx->keys_stride, worker0, pk)
     if (ctx->tl.quad_aligned) { if (short_list) LAUNCH_SIDE_DRAW(1, 1); else LAUNCH_SIDE_DRAW(1, 0); }
     else { if (short_list) LAUNCH_SIDE_DRAW(0, 1); else LAUNCH_SIDE_DRAW(0, 0); }
 #undef LAUNCH_SIDE_DRAW

@@ -117,11 +117,14 @@ __global__ __launch_bounds__(256) void k_init_state(SegState* __restrict__ st, S
 // The draw does not look at the core; a later pass applies it, so the same routine serves
 // inside the scoring kernel (core not known yet) and stand-alone.
 // PAIRS = 1 (every segment's candidate zone is narrow): no candidate bitmap; the sub-tile's
-// list holds (key, offset inside the sub-tile) pairs, at most SUB/2 of them: the count still
+// slot holds (key, offset inside the sub-tile) pairs, at most PAIR_CAP of them: the count still
 // reports any beyond, which the gathering pass turns into the exact rerun.
 // wa, wb, wp: 32 words of LDS each, private to the calling wave (generic variant only).
 // ---------------------------------------------------------------------------------------
 struct PhiloxKey { uint32_t seed_lo, seed_hi, it_lo, it_hi; };
+// PAIRS = 1: a sub-tile's (key, offset) pairs live in a slot of PAIR_SLOT words at
+// cand_keys[(tile * SUBS + sub-tile) * PAIR_SLOT]: PAIR_CAP pairs, about a hundred times the expected number.
+constexpr uint32_t PAIR_CAP = 16, PAIR_SLOT = 2 * PAIR_CAP;
 struct DrawOut {                 // per batch (worker) base pointers
     uint32_t* sure_bits;         // [T * TILE_WORDS]
     uint32_t* cand_bits;         // [T * TILE_WORDS]
@@ -203,9 +206,9 @@ __device__ __forceinline__ void explore_subtile(uint32_t worker, uint32_t t, uin
                     const uint32_t e = (gi << 2) + cc - base;
                     const uint32_t rank = wp[e >> 5] + __popc(wb[e >> 5] & mask_below(e & 31));
                     if (!PAIRS) out.cand_keys[(size_t)base + rank] = key[it][cc];
-                    else if (rank < SUB / 2) {
-                        out.cand_keys[(size_t)base + 2u * rank] = key[it][cc];
-                        out.cand_keys[(size_t)base + 2u * rank + 1u] = e;
+                    else if (rank < PAIR_CAP) {
+                        out.cand_keys[((size_t)t * SUBS + sub) * PAIR_SLOT + 2u * rank] = key[it][cc];
+                        out.cand_keys[((size_t)t * SUBS + sub) * PAIR_SLOT + 2u * rank + 1u] = e;
                     }
                 }
             }
@@ -248,7 +251,7 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
         return;
     }
     const uint32_t base = start + off;
-    uint32_t* ckeys = out.cand_keys + (size_t)base;
+    uint32_t* ckeys = PAIRS ? out.cand_keys + ((size_t)t * SUBS + sub) * PAIR_SLOT : out.cand_keys + (size_t)base;
     const uint32_t sure_excl = has_sure ? sure_m1 + 1u : 0u;         // sure_m1 < bound_m1: no overflow
     const uint32_t width_m1 = bound_m1 - sure_excl;                  // candidate words are sure_excl .. bound_m1
     uint32_t run = 0, sword = 0, cword = 0;
@@ -291,7 +294,7 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
                 for (int cc = 0; cc < 4; ++cc) {
                     if ((fc >> cc) & 1u) {
                         if (!PAIRS) ckeys[pos] = bound_m1 - r[cc];
-                        else if (pos < SUB / 2) { ckeys[2u * pos] = bound_m1 - r[cc]; ckeys[2u * pos + 1u] = e0 + cc; }
+                        else if (pos < PAIR_CAP) { ckeys[2u * pos] = bound_m1 - r[cc]; ckeys[2u * pos + 1u] = e0 + cc; }
                         ++pos;
                     }
                 }
@@ -359,6 +362,10 @@ struct SpecArgs {
     uint2* bits;             // [T * TILE_WORDS] x = the bits, y = number of the word's first entry inside its sub-tile
     float* vals;             // [entries][W]
 };
+// A sub-tile's entries live at spec.vals[(tile * SUBS + sub-tile) * SPEC_CAP * W]; entries beyond SPEC_CAP (a quarter
+// of the sub-tile: two and a half times a 10 % core) are not kept (the descriptor's range drops their stores) and
+// the pack reads those parameters from the update vectors.
+constexpr uint32_t SPEC_CAP = SUB / 4;
 __host__ __device__ constexpr uint32_t spec_align(uint32_t W) { return (W == 0u || W >= 32u) ? 1u : 32u / W; }   // entries per 128-byte line
 
 #ifndef SCORE_MINB
@@ -502,7 +509,7 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                     constexpr uint32_t A = spec_align(WT);
                     const uint32_t padded = (total + A - 1u) & ~(A - 1u);
                     // the sub-tile's entries through a descriptor: the entry number is the lane's part
-                    const __amdgpu_buffer_rsrc_t rv = buffer_of(spec.vals + ((size_t)start + wid * SUB) * WT, SUB * WT * 4u);
+                    const __amdgpu_buffer_rsrc_t rv = buffer_of(spec.vals + ((size_t)t * SUBS + wid) * SPEC_CAP * WT, SPEC_CAP * WT * 4u);
                     if (f) {
                         uint32_t pos = spec_run + below;
 #pragma unroll
@@ -748,7 +755,7 @@ __global__ __launch_bounds__(BLOCK, SCOREF_MINB) void k_score_flat(const float* 
             }
             wave_sync();
             {
-                const __amdgpu_buffer_rsrc_t rv = buffer_of(spec.vals + ((size_t)t * TILE + wid * SUB) * WT, SUB * WT * 4u);
+                const __amdgpu_buffer_rsrc_t rv = buffer_of(spec.vals + ((size_t)t * SUBS + wid) * SPEC_CAP * WT, SPEC_CAP * WT * 4u);
                 const uint32_t nchunk = padded * WT / 4u;          // 16-byte pieces: a multiple of 8 (whole lines)
                 for (uint32_t cidx = lane; cidx < nchunk; cidx += 64)
                     buffer_store4_aux<SCOREF_CAP_AUX>(rv, spec_run * WT * 4u + cidx * 16u, *reinterpret_cast<const float4*>(stf + cidx * 4u));
@@ -800,7 +807,7 @@ __global__ __launch_bounds__(BLOCK, SCOREF_MINB) void k_score_flat(const float* 
 // estimate that turns out too high is caught by the selection's own verdict (the pack then
 // gathers); one that is too low only makes the capture larger.
 // ---------------------------------------------------------------------------------------
-constexpr uint32_t SAMPLE_PER = 8;
+constexpr uint32_t SAMPLE_PER = 2;
 constexpr uint32_t SAMPLE_MARGIN = 1u << 18;
 __global__ __launch_bounds__(256) void k_sample_keys(const float* __restrict__ w, PtrTab g, int W, float c, uint32_t T_full,
                                                      uint32_t* __restrict__ keys)
@@ -808,7 +815,7 @@ __global__ __launch_bounds__(256) void k_sample_keys(const float* __restrict__ w
     const uint32_t x = blockIdx.x * 256 + threadIdx.x;
     if (x >= T_full * SAMPLE_PER) return;
     const uint32_t t = x / SAMPLE_PER, j = x % SAMPLE_PER;
-    const uint32_t off = ((t * 0x9E3779B1u) >> 23) * SAMPLE_PER;       // 0 .. 4088 in steps of 8: inside the tile
+    const uint32_t off = ((t * 0x9E3779B1u) >> 21) * SAMPLE_PER;       // 0 .. 4094 in steps of 2: inside the tile
     const size_t i = (size_t)t * TILE + off + j;
     float a = static_cast<const float*>(g.p[0])[i];
     for (int k = 1; k < W; ++k) a = a + static_cast<const float*>(g.p[k])[i];
@@ -1110,8 +1117,11 @@ __global__ __launch_bounds__(BLOCK) void k_core_build(const float* __restrict__ 
         const uint32_t start = tile_start[t];
         return tile_start[t + 1] - start == TILE && (start & 3u) == 0;
     };
-    // flat model, prediction held: only a ragged last tile can be left, and most blocks do not own it
-    if (strided && skip && skip[0] && (T - 1) % gridDim.x != blockIdx.x) return;
+    // flat model, prediction held: only a ragged last tile can be left; one block looks at it
+    if (strided && skip && skip[0]) {
+        if (blockIdx.x != 0) return;
+        t0 = T - 1;
+    }
     for (uint32_t b = threadIdx.x; b < CORE_NB1; b += BLOCK) h[b] = 0;
     __syncthreads();
     uint32_t cur_seg = tile_seg[t0];
@@ -1487,8 +1497,8 @@ __global__ __launch_bounds__(1024) void k_seg_sum(const uint32_t* __restrict__ c
 }
 
 // Candidates outside the core -> list.  One thread per (batch, tile); a block reserves its
-// share of the list with one atomic.  A sub-tile with more pairs than its slots hold, or a
-// full list, raises the rerun flag.  grid ceil(nbatch * T / 1024), 1024 threads.
+// share of the list with one atomic.  A sub-tile with more pairs than its slot holds, or a
+// full list, raises the rerun flag.  keys_stride: words per batch of the pair slots.  grid ceil(nbatch * T / 1024), 1024 threads.
 __global__ __launch_bounds__(1024) void k_cand_gather(const uint32_t* __restrict__ core_bits, uint64_t n,
                                                       const uint32_t* __restrict__ tile_start,
                                                       const uint32_t* __restrict__ tile_seg, uint32_t T, uint32_t n_seg,
@@ -1511,18 +1521,18 @@ __global__ __launch_bounds__(1024) void k_cand_gather(const uint32_t* __restrict
     bool over = false;
 #pragma unroll
     for (int sub = 0; sub < SUBS; ++sub)
-        if (cs[sub] > SUB / 2) { over = true; cs[sub] = 0; }
+        if (cs[sub] > PAIR_CAP) { over = true; cs[sub] = 0; }
     if (over) atomicOr(&flags[0], FLAG_RERUN);
     uint32_t mine = 0;
     TileRef tr{0u, 0u, 0u};
     const uint32_t* keys = cand_keys;
     if (cs[0] | cs[1] | cs[2] | cs[3]) {
         tr = tile_ref(t, n_seg, n, tile_start, tile_seg);
-        keys = cand_keys + (size_t)b * keys_stride + tr.start;
+        keys = cand_keys + (size_t)b * keys_stride + (size_t)t * SUBS * PAIR_SLOT;
 #pragma unroll 1
         for (int sub = 0; sub < SUBS; ++sub)
             for (uint32_t j = 0; j < cs[sub]; ++j) {
-                const uint32_t i = tr.start + sub * SUB + keys[sub * SUB + 2 * j + 1];
+                const uint32_t i = tr.start + sub * SUB + keys[sub * PAIR_SLOT + 2 * j + 1];
                 mine += ((core_bits[i >> 5] >> (i & 31u)) & 1u) ^ 1u;
             }
     }
@@ -1541,7 +1551,7 @@ __global__ __launch_bounds__(1024) void k_cand_gather(const uint32_t* __restrict
 #pragma unroll 1
     for (int sub = 0; sub < SUBS; ++sub)
         for (uint32_t j = 0; j < cs[sub]; ++j) {
-            const uint32_t key = keys[sub * SUB + 2 * j], e = keys[sub * SUB + 2 * j + 1];
+            const uint32_t key = keys[sub * PAIR_SLOT + 2 * j], e = keys[sub * PAIR_SLOT + 2 * j + 1];
             const uint32_t i = tr.start + sub * SUB + e;
             if ((core_bits[i >> 5] >> (i & 31u)) & 1u) continue;
             list[o++] = make_uint4(key, t * TILE + sub * SUB + e, b * n_seg + tr.seg, b);
@@ -2200,7 +2210,13 @@ __global__ __launch_bounds__(BLOCK) void k_pack_core_spec(PtrTab g, uint32_t nw,
                         v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
                         if (e[u] < TILE) {
                             const uint32_t entry = pre[wid][e[u] >> 5] + __popc(wd[wid][e[u] >> 5] & mask_below(e[u] & 31u));
-                            v[u] = *reinterpret_cast<const float4*>(spec_vals + ((size_t)start + (e[u] & ~(SUB - 1u)) + entry) * nw + q);
+                            if (entry < SPEC_CAP)
+                                v[u] = *reinterpret_cast<const float4*>(spec_vals + (((size_t)t * SUBS + (e[u] >> 10)) * SPEC_CAP + entry) * nw + q);
+                            else {
+                                const size_t i = (size_t)start + e[u];
+                                v[u].x = static_cast<const float*>(g.p[q])[i]; v[u].y = static_cast<const float*>(g.p[q + 1])[i];
+                                v[u].z = static_cast<const float*>(g.p[q + 2])[i]; v[u].w = static_cast<const float*>(g.p[q + 3])[i];
+                            }
                         }
                     }
 #pragma unroll
@@ -2218,8 +2234,9 @@ __global__ __launch_bounds__(BLOCK) void k_pack_core_spec(PtrTab g, uint32_t nw,
                     const uint32_t j = jb + u * 64 + lane;
                     if (e[u] >= TILE) continue;
                     const uint32_t entry = pre[wid][e[u] >> 5] + __popc(wd[wid][e[u] >> 5] & mask_below(e[u] & 31u));
-                    const float* src = spec_vals + ((size_t)start + (e[u] & ~(SUB - 1u)) + entry) * nw;
-                    for (uint32_t q = 0; q < nw; ++q) static_cast<float*>(core_val.p[q])[j] = src[q];
+                    const float* src = spec_vals + (((size_t)t * SUBS + (e[u] >> 10)) * SPEC_CAP + entry) * nw;
+                    for (uint32_t q = 0; q < nw; ++q)
+                        static_cast<float*>(core_val.p[q])[j] = (entry < SPEC_CAP) ? src[q] : static_cast<const float*>(g.p[q])[(size_t)start + e[u]];
                 }
             }
         }
@@ -2266,9 +2283,9 @@ __global__ __launch_bounds__(256) void k_pack_core_flat(PtrTab g, uint32_t nw, u
                         v[u][h] = make_float4(0.f, 0.f, 0.f, 0.f);
                         const uint32_t qq = q + 4u * h;
                         if (i[u] >= n || qq >= nw) continue;
-                        if (ok && (i[u] >> 12) < T_full) {
-                            const uint32_t entry = bp[u].y + __popc(bp[u].x & mask_below(i[u] & 31u));
-                            v[u][h] = ld4<NT_PACKC_LD>(spec_vals + ((size_t)(i[u] & ~(SUB - 1u)) + entry) * nw + qq);
+                        const uint32_t entry = bp[u].y + __popc(bp[u].x & mask_below(i[u] & 31u));
+                        if (ok && (i[u] >> 12) < T_full && entry < SPEC_CAP) {
+                            v[u][h] = ld4<NT_PACKC_LD>(spec_vals + ((size_t)(i[u] >> 10) * SPEC_CAP + entry) * nw + qq);
                         } else {
                             v[u][h].x = static_cast<const float*>(g.p[qq])[i[u]]; v[u][h].y = static_cast<const float*>(g.p[qq + 1])[i[u]];
                             v[u][h].z = static_cast<const float*>(g.p[qq + 2])[i[u]]; v[u][h].w = static_cast<const float*>(g.p[qq + 3])[i[u]];
@@ -2295,9 +2312,9 @@ __global__ __launch_bounds__(256) void k_pack_core_flat(PtrTab g, uint32_t nw, u
             for (int u = 0; u < U; ++u) {
                 const uint32_t j = jb + u * stride;
                 if (i[u] >= n) continue;
-                if (ok && (i[u] >> 12) < T_full) {
-                    const uint32_t entry = bp[u].y + __popc(bp[u].x & mask_below(i[u] & 31u));
-                    const float* src = spec_vals + ((size_t)(i[u] & ~(SUB - 1u)) + entry) * nw;
+                const uint32_t entry = bp[u].y + __popc(bp[u].x & mask_below(i[u] & 31u));
+                if (ok && (i[u] >> 12) < T_full && entry < SPEC_CAP) {
+                    const float* src = spec_vals + ((size_t)(i[u] >> 10) * SPEC_CAP + entry) * nw;
                     for (uint32_t q = 0; q < nw; ++q) static_cast<float*>(core_val.p[q])[j] = src[q];
                 } else {
                     for (uint32_t q = 0; q < nw; ++q) static_cast<float*>(core_val.p[q])[j] = static_cast<const float*>(g.p[q])[i[u]];

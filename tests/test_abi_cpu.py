@@ -54,7 +54,9 @@ def test_num_tiles_and_workspace_are_pure_host_functions():
     assert binding.workspace_bytes(10, 33) == 0
     small = binding.workspace_bytes(1_000_000, 4)
     big = binding.workspace_bytes(138_357_544, 8)
-    assert 0 < small < big < 16 * 2 ** 30
+    assert 0 < small < big < 2 * 2 ** 30           # 1.2 GiB at the VGG-16 size: bitmaps, counts, pair slots, lists
+    assert 0 < binding.capture_bytes(138_357_544, 8) < 1.3 * 2 ** 30
+    assert binding.capture_bytes(10, 0) == 0
 
 
 def test_create_rejects_bad_arguments_before_touching_the_gpu():

@@ -289,7 +289,8 @@ def test_speculative_pack_over_iterations(hint):
     """With speculative packing on, the scoring pass keeps the update values of the likely core (from the second
     iteration on, once a threshold is known) and the pack takes them from there; everything stays bit-exact.
     Flat, segmented (tiles that are never captured), and a changing core size (threshold below the capture bound)."""
-    for wl in (workloads.TINY.scaled(200_003), workloads.GOOGLENET.scaled(300_001), workloads.STRESS.scaled(150_001, W=8)):
+    for wl in (workloads.TINY.scaled(200_003), workloads.GOOGLENET.scaled(300_001), workloads.STRESS.scaled(150_001, W=8),
+               workloads.GOOGLENET.scaled(300_001, core_pct=40)):       # more captured per sub-tile than is kept
         seg_off = [int(x) for x in wl.segment_offsets()]
         sd = binding.SlimDP(wl.n, wl.W, seg_off=seg_off, seed=workloads.EXPLORE_SEED)
         sd.set_option("speculative_pack", 1)
@@ -355,13 +356,14 @@ def test_speculative_pack_really_uses_the_captured_values():
     sd.close()
 
 
-@pytest.mark.parametrize("bias", [0, 1 << 22, -(1 << 22)])
+@pytest.mark.parametrize("bias", [0, 1 << 22, -(1 << 20), -(1 << 22)])
 @pytest.mark.parametrize("announced", [False, True])
 def test_first_iteration_captures_under_a_sampled_bound(bias, announced):
     """No selection has run yet: the scoring pass estimates the coming threshold from a sample of its own
     significances.  Estimate as it is, forced far too high (the selection's verdict rejects the capture: the pack
-    gathers) and far too low (a larger capture): the same bits in every case; the white-box probe (updates zeroed
-    after the selection) shows which source the pack used."""
+    gathers), too low (a larger capture) and far too low (more parameters qualify than a sub-tile keeps: the pack
+    gathers the rest): the same bits in every case; the white-box probe (updates zeroed after the selection) shows
+    which source the pack used."""
     wl = workloads.TINY.scaled(700_000)             # 170 whole tiles and a ragged one
     sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
     sd.set_option("speculative_pack", 1)
@@ -371,7 +373,7 @@ def test_first_iteration_captures_under_a_sampled_bound(bias, announced):
     got, want = run_iteration(wl, iteration=0, sd=sd, hint=announced)
     assert_iteration_matches(wl, got, want)
     sd.close()
-    if bias == 0:
+    if bias == 0 or bias == -(1 << 22):
         return
     sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
     sd.set_option("speculative_pack", 1)
