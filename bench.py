@@ -105,6 +105,8 @@ class Buffers:
         self.core_off = torch.empty(sd.T + 1, dtype=i32, device=dev)
         self.expl_idx = [torch.empty(m, dtype=i32, device=dev) for _ in range(W)]
         self.expl_off = [torch.empty(sd.T + 1, dtype=i32, device=dev) for _ in range(W)]
+        self.expl_idx2 = [torch.empty(m, dtype=i32, device=dev) for _ in range(W)]      # a request one iteration ahead
+        self.expl_off2 = [torch.empty(sd.T + 1, dtype=i32, device=dev) for _ in range(W)]
         self.core_val = [torch.empty(k, dtype=f32, device=dev) for _ in range(W)]
         self.expl_val = [torch.empty(m, dtype=f32, device=dev) for _ in range(W)]
 
@@ -151,22 +153,31 @@ def device_updates(torch, wl, workloads, t, dev):
 def run_loop(torch, sd, wl, b, w, g_all, ks, ms):
     """The multi-iteration loop: core every reselect_every iterations from the current model and that iteration's
     updates, explorer every iteration, every draw announced one iteration ahead (inside the scoring pass of a
-    reselecting iteration, otherwise on the library's side stream beside pack and merge)."""
+    reselecting iteration, otherwise on the library's side stream).  While the core stays, the explorer request of
+    the next iteration is issued before this iteration's pack (two sets of list arrays) and runs beside pack and merge."""
     epoch = None
     W = wl.W
+    lists = [(b.expl_idx, b.expl_off), (b.expl_idx2, b.expl_off2)]
+    ahead = False
     for t in range(wl.iterations):
         g = g_all[t]
         resel = t % wl.reselect_every == 0
+        ei, eo = lists[t & 1]
         if resel:
             sd.score(w, g, wl.c, out=b.S)
             _, _, _, epoch = sd.select_core(b.S, ks, reuse_histogram=True, core_idx=b.core_idx, core_bits=b.core_bits,
                                             core_off=b.core_off)
-        sd.sample_explore(b.core_bits, ks, t, ms, 0, W, expl_idx=b.expl_idx, expl_off=b.expl_off)
-        sd.set_option("explore_hint_mode", 0 if (t + 1) % wl.reselect_every == 0 else 1)
+        if not ahead:
+            sd.sample_explore(b.core_bits, ks, t, ms, 0, W, expl_idx=ei, expl_off=eo)
+        next_resel = (t + 1) % wl.reselect_every == 0
+        sd.set_option("explore_hint_mode", 0 if next_resel else 1)
         sd.explore_hint(ks, t + 1, ms, 0, W)
-        sd.pack(g, b.core_idx, b.core_off, b.expl_idx, b.expl_off, epoch, core_val=b.core_val, expl_val=b.expl_val,
+        ahead = not next_resel and t + 1 < wl.iterations
+        if ahead:
+            sd.sample_explore(b.core_bits, ks, t + 1, ms, 0, W, expl_idx=lists[(t + 1) & 1][0], expl_off=lists[(t + 1) & 1][1])
+        sd.pack(g, b.core_idx, b.core_off, ei, eo, epoch, core_val=b.core_val, expl_val=b.expl_val,
                 updates_as_scored=resel)
-        sd.merge(w, wl.lr, epoch, b.core_idx, b.core_off, b.core_val, b.expl_idx, b.expl_off, b.expl_val)
+        sd.merge(w, wl.lr, epoch, b.core_idx, b.core_off, b.core_val, ei, eo, b.expl_val)
 
 
 def main() -> int:
@@ -213,6 +224,7 @@ def main() -> int:
         c = binding.SlimDP(n, W, seg_off=seg_off, seed=workloads.EXPLORE_SEED)
         if capture:
             c.set_option("speculative_pack", 1)   # the scoring pass keeps the likely core's update values for the pack
+            c.set_option("explore_async", 1)      # explorer requests on the library's side stream, beside the pack
         for kv in args.opt:
             name, value = kv.split("=")
             c.set_option(name, int(value))
@@ -317,8 +329,8 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "n": n, "W": W, "k": k, "m": m, "core_pct": wl.core_pct,
                    "explore_pct": wl.explore_pct, "c": wl.c, "lr": wl.lr, "tile": binding.TILE,
-                   "state": "steady: option speculative_pack on, every draw announced one step ahead, the same update "
-                            "vectors every step"},
+                   "state": "steady: options speculative_pack and explore_async on, every draw announced one step ahead, "
+                            "the same update vectors every step"},
         "hbm_frac_whole_step": frac(total_bytes, ms_per_step),
         "algorithmic_bytes_per_step": total_bytes,
         "stage_ms": stage_ms,
@@ -354,19 +366,20 @@ def main() -> int:
                                           "what": "slimdp_dense_update_score + slimdp_select_core",
                                           "algorithmic_bytes": 4 * n * (W + 3) + 4 * n + 4 * k + n // 8}
         # (4) the steady iteration between two reselections (cached core keys, updates no scoring pass has seen:
-        # explorers, pack by scanning the updates, merge); the next draw is announced to the side stream and runs
-        # beside the pack and the merge
+        # explorers, pack by scanning the updates, merge); the next iteration's draw and explorer request run on the side
+        # stream beside this iteration's pack and merge
         sd.set_option("explore_hint_mode", 1)
         _, _, _, epoch2 = sd.select_core(b.S, ks, core_idx=b.core_idx, core_bits=b.core_bits, core_off=b.core_off)
+        lists = [(b.expl_idx, b.expl_off), (b.expl_idx2, b.expl_off2)]
         sd.explore_hint(ks, 10_000, ms, 0, W)
-        sd.sample_explore(b.core_bits, ks, 10_000, ms, 0, W, expl_idx=b.expl_idx, expl_off=b.expl_off)
-        sd.explore_hint(ks, 10_001, ms, 0, W)
+        sd.sample_explore(b.core_bits, ks, 10_000, ms, 0, W, expl_idx=lists[0][0], expl_off=lists[0][1])
 
         def steady(r):
-            sd.sample_explore(b.core_bits, ks, 10_001 + r, ms, 0, W, expl_idx=b.expl_idx, expl_off=b.expl_off)
-            sd.explore_hint(ks, 10_002 + r, ms, 0, W)
-            sd.pack(g, b.core_idx, b.core_off, b.expl_idx, b.expl_off, epoch2, core_val=b.core_val, expl_val=b.expl_val)
-            sd.merge(w, wl.lr, epoch2, b.core_idx, b.core_off, b.core_val, b.expl_idx, b.expl_off, b.expl_val)
+            ei, eo = lists[r & 1]
+            sd.explore_hint(ks, 10_001 + r, ms, 0, W)                       # next draw and next request: the side stream
+            sd.sample_explore(b.core_bits, ks, 10_001 + r, ms, 0, W, expl_idx=lists[(r + 1) & 1][0], expl_off=lists[(r + 1) & 1][1])
+            sd.pack(g, b.core_idx, b.core_off, ei, eo, epoch2, core_val=b.core_val, expl_val=b.expl_val)
+            sd.merge(w, wl.lr, epoch2, b.core_idx, b.core_off, b.core_val, ei, eo, b.expl_val)
         steady_ms = timed(steady, reps)
         steady_bytes = sb["sample_explore"] + sb["pack"] + sb["merge"]
         out["steady_iteration"] = {"ms": steady_ms, "Gparam_per_s": n / (steady_ms * 1e-3) / 1e9,

@@ -15,10 +15,10 @@
  *    or prints.
  *  - Calls are asynchronous on the HIP stream given to slimdp_create and never
  *    synchronise the host; every output size is known from the arguments.  Conditions
- *    only the device can detect (see slimdp_synchronize) are reported there.  The one
- *    piece of work that may run elsewhere is an announced explorer draw on the library's
- *    own side stream (option "explore_hint_mode" = 1); the calls that need its result
- *    make the caller's stream wait for it.
+ *    only the device can detect (see slimdp_synchronize) are reported there.  The only
+ *    work that may run elsewhere: an announced explorer draw (option "explore_hint_mode" = 1)
+ *    and explorer requests (option "explore_async" = 1) on the library's own side stream; the
+ *    calls that need their results make the caller's stream wait for them.
  *  - The library allocates device memory in slimdp_create, once more when the option
  *    "speculative_pack" is first switched on (slimdp_capture_bytes), and once more on the first
  *    explorer request whose zones are wide (see slimdp_capture_bytes); never otherwise.
@@ -118,6 +118,16 @@ int slimdp_synchronize(slimdp_ctx* ctx);
  *   "explore_hint_mode" (0/1, default 0): where an announced explorer draw runs: 0 inside
  *       the next slimdp_score, 1 at once on a side stream of the library (default priority),
  *       beside whatever runs on the context's stream.
+ *   "explore_async" (0/1, default 0): slimdp_sample_explore runs on the library's side stream, beside whatever is
+ *       enqueued on the context's stream AFTER the call (its many small kernels are bound by latency, not by memory).
+ *       It starts once everything enqueued before the call is done.  slimdp_pack, slimdp_merge and slimdp_pull wait
+ *       for the requests that write the lists they are given (and do not wait for requests into other arrays);
+ *       slimdp_select_core, slimdp_import_core, a synchronous slimdp_sample_explore, a slimdp_score that carries an
+ *       announced draw, and slimdp_synchronize wait for all of them.  Other work on the context's stream must not
+ *       touch the lists before one of those calls.  A pack that takes kept values
+ *       (SLIMDP_PACK_UPDATES_AS_SCORED) extracts the core values meanwhile.  With cached core keys the request for
+ *       iteration t+1 can be issued before the pack of iteration t (other output arrays) and then runs beside pack
+ *       and merge.
  *   "side_blocks" (1..8): blocks per compute unit of a side-stream draw.
  *   "pack_nbuf" (1/2): tiles in flight in the general pack kernel.
  *   "explore_force_fallback" (0/1/2), "explore_per_tile_tail" (0/1): test switches: make

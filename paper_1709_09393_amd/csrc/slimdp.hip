@@ -92,6 +92,19 @@ struct slimdp_ctx {
     hipEvent_t ev_consumed = nullptr;      // main stream: everything enqueued before a side-stream draw (readers of its buffers)
     hipEvent_t ev_drawn = nullptr;         // side stream: the announced draw is complete
     bool side_pending = false;             // a side draw was launched and the main stream has not waited for it yet
+    // asynchronous slimdp_sample_explore requests (option "explore_async") that the main stream has not waited for yet:
+    // their completion events on the side stream and the address ranges they write
+    static constexpr int N_PENDING = 4;
+    struct PendingExplore {
+        hipEvent_t ev = nullptr;
+        bool live = false;
+        uint64_t seq = 0;
+        uint32_t nw = 0;
+        uintptr_t idx[MAXW] = {}, off[MAXW] = {};
+        uint64_t idx_bytes = 0, off_bytes = 0;
+    } pend[N_PENDING];
+    uint64_t pend_seq = 0;
+    int64_t opt_explore_async = 0;
     int device = 0, cus = 256;
     std::vector<uint64_t> seg_off;
     Tiling tl;
@@ -151,6 +164,7 @@ struct slimdp_ctx {
     } spec;
     int64_t opt_pack_nbuf = 2;
     int64_t opt_build_blocks = 4;
+    int64_t opt_pack_core_blocks = 0;      // blocks per compute unit of the pack from the capture (0: one per 1024 list entries)
     int64_t opt_core_predict = 1;          // the flat scoring kernel sorts whole tiles against the predicted threshold bin (0: never; 2: test, a wrong bin)          // blocks per compute unit of the core candidate pass
     int64_t opt_score_pipeline = 1;        // flat aligned models: the scoring kernel with two rounds of loads in flight
     int64_t opt_expected_core = -1;        // core size the next selection will ask for (flat model), if the caller says
@@ -297,35 +311,36 @@ int finish_selection(slimdp_ctx* c, uint32_t nbatch, SegState* st, uint32_t* his
                      uint64_t keys_stride, bool level1_done, const MutPtrTab& out_off, const MutPtrTab& out_idx,
                      uint32_t expected, uint32_t* pub_bits, const uint32_t* excl_bits, const uint32_t* gate,
                      uint32_t* chunk_sum, SpecTau sp = SpecTau{nullptr, nullptr, nullptr},
-                     CorePred cp = CorePred{nullptr, nullptr, nullptr, 0})
+                     CorePred cp = CorePred{nullptr, nullptr, nullptr, 0}, hipStream_t stream = nullptr)
 {
+    if (!stream) stream = c->stream;
     const uint32_t T = c->T, S = c->n_seg;
     const dim3 wave_grid((T + 3) / 4, (nbatch + BPW - 1) / BPW);     // a wave serves its tile for BPW batches
     if (!level1_done) {
-        hipLaunchKernelGGL((k_list_hist<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start,
+        hipLaunchKernelGGL((k_list_hist<KPL, BPW>), wave_grid, dim3(BLOCK), 0, stream, c->n, c->d_tile_start,
                            c->d_tile_seg, T, S, nbatch, st, hist, (uint32_t)H_L1, 1, cand_keys, cnt_cand, keys_stride, gate);
         SLIMDP_LAUNCHED(c, "k_list_hist(1)");
     }
-    hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 1, (uint32_t)H_L1, S, 0, c->d_flags,
+    hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, stream, st, hist, 1, (uint32_t)H_L1, S, 0, c->d_flags,
                        nullptr, gate ? 1 : 0, SpecTau{nullptr, nullptr, nullptr}, CorePred{nullptr, nullptr, nullptr, 0});
     SLIMDP_LAUNCHED(c, "k_threshold(1)");
-    hipLaunchKernelGGL((k_list_hist<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg,
+    hipLaunchKernelGGL((k_list_hist<KPL, BPW>), wave_grid, dim3(BLOCK), 0, stream, c->n, c->d_tile_start, c->d_tile_seg,
                        T, S, nbatch, st, hist, (uint32_t)H_L2, 2, cand_keys, cnt_cand, keys_stride, gate);
     SLIMDP_LAUNCHED(c, "k_list_hist(2)");
-    hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, c->stream, st, hist, 2, (uint32_t)H_L2, S, 0, c->d_flags,
+    hipLaunchKernelGGL(k_threshold, dim3(S, nbatch), dim3(256), 0, stream, st, hist, 2, (uint32_t)H_L2, S, 0, c->d_flags,
                        nullptr, gate ? 1 : 0, sp, cp);
     SLIMDP_LAUNCHED(c, "k_threshold(2)");
-    hipLaunchKernelGGL((k_count<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg, T, S,
+    hipLaunchKernelGGL((k_count<KPL, BPW>), wave_grid, dim3(BLOCK), 0, stream, c->n, c->d_tile_start, c->d_tile_seg, T, S,
                        nbatch, st, cand_keys, cnt_cand, cnt_gt, keys_stride, cnt_sel, cnt_tie, gate);
     SLIMDP_LAUNCHED(c, "k_count");
     const dim3 scan_grid(c->n_chunks, nbatch);
-    hipLaunchKernelGGL(k_tile_scan<0>, scan_grid, dim3(1024), 0, c->stream, c->d_tile_seg, c->d_seg_first_tile, T, S, st, cnt_sel,
+    hipLaunchKernelGGL(k_tile_scan<0>, scan_grid, dim3(1024), 0, stream, c->d_tile_seg, c->d_seg_first_tile, T, S, st, cnt_sel,
                        cnt_tie, tie_pre, chunk_sum, out_off, chunk_sum + (size_t)nbatch * c->n_chunks, gate);
     SLIMDP_LAUNCHED(c, "k_tile_scan(ties)");
-    hipLaunchKernelGGL(k_tile_scan<1>, scan_grid, dim3(1024), 0, c->stream, c->d_tile_seg, c->d_seg_first_tile, T, S, st, cnt_sel,
+    hipLaunchKernelGGL(k_tile_scan<1>, scan_grid, dim3(1024), 0, stream, c->d_tile_seg, c->d_seg_first_tile, T, S, st, cnt_sel,
                        cnt_tie, tie_pre, chunk_sum, out_off, chunk_sum + (size_t)nbatch * c->n_chunks, gate);
     SLIMDP_LAUNCHED(c, "k_tile_scan(offsets)");
-    hipLaunchKernelGGL((k_emit<KPL, BPW>), wave_grid, dim3(BLOCK), 0, c->stream, c->n, c->d_tile_start, c->d_tile_seg,
+    hipLaunchKernelGGL((k_emit<KPL, BPW>), wave_grid, dim3(BLOCK), 0, stream, c->n, c->d_tile_start, c->d_tile_seg,
                        c->d_seg_first_tile, T, S, nbatch, st, gt_bits, cand_bits, cand_keys, keys_stride, tie_pre, out_off,
                        out_idx, expected, pub_bits, excl_bits, (uint32_t)((c->n + 31) / 32), gate, chunk_sum,
                        chunk_sum + (size_t)nbatch * c->n_chunks, c->n_chunks, c->d_flags);
@@ -349,6 +364,53 @@ template <class Tab, class P> Tab make_tab(P const* tab, uint32_t nw)
     if (tab)
         for (uint32_t q = 0; q < nw; ++q) t.p[q] = (decltype(t.p[0]))tab[q];
     return t;
+}
+
+// The context's stream waits for whatever the side stream still has in flight (an announced draw, asynchronous
+// explorer requests) before it touches what that work reads or writes.
+int wait_for_side(slimdp_ctx* c)
+{
+    int last = -1;
+    for (int j = 0; j < slimdp_ctx::N_PENDING; ++j)
+        if (c->pend[j].live && (last < 0 || c->pend[j].seq > c->pend[last].seq)) last = j;
+    if (last >= 0) {                     // the side stream runs in order: the newest request's event covers all
+        SLIMDP_HIP(c, hipStreamWaitEvent(c->stream, c->pend[last].ev, 0));
+        for (int j = 0; j < slimdp_ctx::N_PENDING; ++j) c->pend[j].live = false;
+        c->side_pending = false;         // a draw that preceded it on the same stream is done as well
+    }
+    if (c->side_pending) {
+        SLIMDP_HIP(c, hipStreamWaitEvent(c->stream, c->ev_drawn, 0));
+        c->side_pending = false;
+    }
+    return SLIMDP_OK;
+}
+
+// A call that reads explorer lists waits for the asynchronous requests that write any of them (address ranges
+// compared, so views into the same allocation count), and with them for every older request; requests whose
+// arrays it does not touch keep running beside it.
+int wait_for_lists(slimdp_ctx* c, uint32_t nw, const uint32_t* const* expl_idx, const uint32_t* const* expl_off,
+                   const uint64_t* m_w)
+{
+    int hit = -1;
+    for (int j = 0; j < slimdp_ctx::N_PENDING; ++j) {
+        const slimdp_ctx::PendingExplore& p = c->pend[j];
+        if (!p.live) continue;
+        bool touches = false;
+        for (uint32_t a = 0; a < nw && !touches; ++a)
+            for (uint32_t b = 0; b < p.nw && !touches; ++b) {
+                const uintptr_t i0 = reinterpret_cast<uintptr_t>(expl_idx ? expl_idx[a] : nullptr);
+                const uintptr_t o0 = reinterpret_cast<uintptr_t>(expl_off ? expl_off[a] : nullptr);
+                if (i0 && i0 < p.idx[b] + p.idx_bytes && p.idx[b] < i0 + (m_w ? m_w[a] : 0) * 4 + 4) touches = true;
+                if (o0 && o0 < p.off[b] + p.off_bytes && p.off[b] < o0 + p.off_bytes) touches = true;
+            }
+        if (touches && (hit < 0 || p.seq > c->pend[hit].seq)) hit = j;
+    }
+    if (hit < 0) return SLIMDP_OK;
+    SLIMDP_HIP(c, hipStreamWaitEvent(c->stream, c->pend[hit].ev, 0));
+    const uint64_t upto = c->pend[hit].seq;
+    for (int j = 0; j < slimdp_ctx::N_PENDING; ++j)
+        if (c->pend[j].live && c->pend[j].seq <= upto) c->pend[j].live = false;
+    return SLIMDP_OK;
 }
 
 int check_epoch(slimdp_ctx* c, uint64_t core_epoch)
@@ -524,10 +586,14 @@ int slimdp_create(slimdp_ctx** out, uint64_t n, uint32_t max_workers, uint32_t n
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);      // default priority
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_consumed, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_drawn, hipEventDisableTiming);
+    for (int j = 0; j < slimdp_ctx::N_PENDING && e == hipSuccess; ++j)
+        e = hipEventCreateWithFlags(&c->pend[j].ev, hipEventDisableTiming);
     if (e != hipSuccess) {
         int rc = hip_fail(nullptr, e, "slimdp_create: table upload, side stream");
         if (c->ev_consumed) (void)hipEventDestroy(c->ev_consumed);
         if (c->ev_drawn) (void)hipEventDestroy(c->ev_drawn);
+        for (int j = 0; j < slimdp_ctx::N_PENDING; ++j)
+            if (c->pend[j].ev) (void)hipEventDestroy(c->pend[j].ev);
         if (c->side) (void)hipStreamDestroy(c->side);
         (void)hipFree(c->ws);
         delete c;
@@ -544,6 +610,7 @@ int slimdp_destroy(slimdp_ctx* ctx)
     (void)hipStreamSynchronize(ctx->stream);
     (void)hipEventDestroy(ctx->ev_consumed);
     (void)hipEventDestroy(ctx->ev_drawn);
+    for (int j = 0; j < slimdp_ctx::N_PENDING; ++j) (void)hipEventDestroy(ctx->pend[j].ev);
     (void)hipStreamDestroy(ctx->side);
     hipError_t e = hipFree(ctx->ws);
     if (ctx->spec.mem) (void)hipFree(ctx->spec.mem);
@@ -566,8 +633,10 @@ int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value)
     if (strcmp(name, "explore_per_tile_tail") == 0) { ctx->opt_per_tile_tail = value; return SLIMDP_OK; }
     if (strcmp(name, "strided_tiles") == 0 && (value == 0 || value == 1)) { ctx->opt_strided = value; return SLIMDP_OK; }
     if (strcmp(name, "side_blocks") == 0 && value >= 1 && value <= 8) { ctx->opt_side_blocks = value; return SLIMDP_OK; }
+    if (strcmp(name, "explore_async") == 0 && (value == 0 || value == 1)) { ctx->opt_explore_async = value; return SLIMDP_OK; }
     if (strcmp(name, "explore_hint_mode") == 0 && (value == 0 || value == 1)) { ctx->opt_hint_mode = value; return SLIMDP_OK; }
     if (strcmp(name, "core_predict") == 0 && value >= 0 && value <= 2) { ctx->opt_core_predict = value; return SLIMDP_OK; }
+    if (strcmp(name, "pack_core_blocks") == 0 && value >= 0 && value <= 64) { ctx->opt_pack_core_blocks = value; return SLIMDP_OK; }
     if (strcmp(name, "build_blocks") == 0 && value >= 1 && value <= 64) { ctx->opt_build_blocks = value; return SLIMDP_OK; }
     if (strcmp(name, "pack_nbuf") == 0 && (value == 1 || value == 2)) { ctx->opt_pack_nbuf = value; return SLIMDP_OK; }
     if (strcmp(name, "expected_core") == 0 && value >= -1 && (value < 0 || (uint64_t)value <= ctx->n)) { ctx->opt_expected_core = value; return SLIMDP_OK; }
@@ -615,6 +684,8 @@ int slimdp_synchronize(slimdp_ctx* ctx)
     if (!ctx) return SLIMDP_ERR_INVALID_ARG;
     SLIMDP_HIP(ctx, hipStreamSynchronize(ctx->stream));
     SLIMDP_HIP(ctx, hipStreamSynchronize(ctx->side));
+    for (int j = 0; j < slimdp_ctx::N_PENDING; ++j) ctx->pend[j].live = false;
+    ctx->side_pending = false;
     uint32_t flags[2] = {0, 0};
     SLIMDP_HIP(ctx, hipMemcpy(flags, ctx->d_flags, sizeof flags, hipMemcpyDeviceToHost));
     if (flags[1]) {
@@ -652,10 +723,8 @@ static int score_impl(slimdp_ctx* ctx, const float* w, const float* const* g, ui
         bool narrow = false;
         if (explorer_init(ctx, "slimdp_score(hint)", ctx->hint.k_seg.data(), ctx->hint.m_seg.data(), ctx->hint.n_workers, init,
                           &M, &narrow, &pairs) == SLIMDP_OK && narrow && M > 0) {
-            if (ctx->side_pending) {
-                SLIMDP_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_drawn, 0));
-                ctx->side_pending = false;
-            }
+            rc = wait_for_side(ctx);         // the draw's buffers may still be read by work on the side stream
+            if (rc) return rc;
             rc = init_states(ctx, ctx->e_state, init, ctx->hint.n_workers, 0);
             if (rc) return rc;
             pre.nw = ctx->hint.n_workers; pre.worker0 = ctx->hint.worker0; pre.n_seg = ctx->n_seg;
@@ -826,7 +895,9 @@ static int select_core_impl(slimdp_ctx* ctx, const float* score, const uint64_t*
                     "slimdp_select_core: no histogram pending for this score buffer (call slimdp_score first)");
     ctx->hist_pending = false;
     const uint32_t T = ctx->T, S = ctx->n_seg;
-    int rc = init_states(ctx, ctx->c_state, init, 1, 1);
+    int rc = wait_for_side(ctx);             // an explorer request on the side stream may still read the bitmap this call rewrites
+    if (rc) return rc;
+    rc = init_states(ctx, ctx->c_state, init, 1, 1);
     if (rc) return rc;
     const uint32_t P = persistent_blocks(ctx, (uint32_t)ctx->opt_build_blocks, 1);
     if (!reuse) {
@@ -964,7 +1035,9 @@ int slimdp_import_core(slimdp_ctx* ctx, const uint32_t* core_idx, const uint64_t
         K += k_seg[s];
     }
     if (K && !core_idx) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_import_core: core_idx is NULL");
-    int rc = fill(ctx, core_bits, (ctx->n + 31) / 32, 0u);
+    int rc = wait_for_side(ctx);
+    if (rc) return rc;
+    rc = fill(ctx, core_bits, (ctx->n + 31) / 32, 0u);
     if (rc) return rc;
     if (K) {
         hipLaunchKernelGGL(k_bits_from_idx, dim3(fill_grid(K)), dim3(256), 0, ctx->stream, core_idx, K, ctx->n, core_bits);
@@ -1000,18 +1073,27 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
     const bool cached = ctx->pre.same(iteration, worker0, n_workers, k_seg, m_seg, S) && ctx->pre.pairs == short_list;
     ctx->pre.valid = false;
     ctx->hint.valid = false;
-    if (ctx->side_pending) {             // whether or not it is the draw this call wants: the buffers are its until it is done
-        SLIMDP_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_drawn, 0));
-        ctx->side_pending = false;
+    // Option "explore_async": the whole request runs on the library's side stream, beside whatever the caller enqueues
+    // on the context's stream after this call; the calls that take the lists make the context's stream wait for them.
+    const bool async = ctx->opt_explore_async != 0;
+    hipStream_t st = async ? ctx->side : ctx->stream;
+    if (async) {
+        // everything enqueued so far comes first: the selection that wrote core_bits, readers of the output arrays
+        SLIMDP_HIP(ctx, hipEventRecord(ctx->ev_consumed, ctx->stream));
+        SLIMDP_HIP(ctx, hipStreamWaitEvent(ctx->side, ctx->ev_consumed, 0));
+        ctx->side_pending = false;       // a draw on the side stream precedes this request in stream order
+    } else {
+        rc = wait_for_side(ctx);         // an announced draw, or an earlier asynchronous request: their buffers are theirs until done
+        if (rc) return rc;
     }
-    rc = init_states(ctx, ctx->e_state, init, B, 0);
+    rc = init_states(ctx, ctx->e_state, init, B, 0, st);
     if (rc) return rc;
     {   // histograms, rerun flag, list counters
         FillJobs fj{};
         fj.p[0] = ctx->e_hist; fj.count[0] = (uint64_t)B * S * H_STRIDE;
         fj.p[1] = ctx->d_flags; fj.count[1] = 1;
         fj.p[2] = ctx->e_list_count; fj.count[2] = 2;
-        hipLaunchKernelGGL(k_fill_multi, dim3(fill_grid(fj.count[0])), dim3(256), 0, ctx->stream, fj);
+        hipLaunchKernelGGL(k_fill_multi, dim3(fill_grid(fj.count[0])), dim3(256), 0, st, fj);
         SLIMDP_LAUNCHED(ctx, "k_fill_multi");
     }
     const uint32_t P = persistent_blocks(ctx, 8, B);
@@ -1022,12 +1104,12 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
 #define LAUNCH_DRAW(PAIRS)                                                                                               \
     do {                                                                                                                 \
         if (ctx->tl.quad_aligned)                                                                                        \
-            hipLaunchKernelGGL((k_explore_keys<1, PAIRS>), dim3(P, B), dim3(BLOCK), 0, ctx->stream, ctx->d_tile_start,   \
+            hipLaunchKernelGGL((k_explore_keys<1, PAIRS>), dim3(P, B), dim3(BLOCK), 0, st, ctx->d_tile_start,   \
                                ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_sure_bits, ctx->e_cand_bits,                  \
                                (PAIRS) ? ctx->e_pair_keys : ctx->e_cand_keys, ctx->e_cnt_cand,                           \
                                (PAIRS) ? ctx->pair_stride : ctx->keys_stride, worker0, pk);                              \
         else                                                                                                             \
-            hipLaunchKernelGGL((k_explore_keys<0, PAIRS>), dim3(P, B), dim3(BLOCK), 0, ctx->stream, ctx->d_tile_start,   \
+            hipLaunchKernelGGL((k_explore_keys<0, PAIRS>), dim3(P, B), dim3(BLOCK), 0, st, ctx->d_tile_start,   \
                                ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_sure_bits, ctx->e_cand_bits,                  \
                                (PAIRS) ? ctx->e_pair_keys : ctx->e_cand_keys, ctx->e_cnt_cand,                           \
                                (PAIRS) ? ctx->pair_stride : ctx->keys_stride, worker0, pk);                              \
@@ -1038,37 +1120,37 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
         // switches these kernels off and the exact rerun below on
         constexpr int SBPW = 8;
         if (!cached) LAUNCH_DRAW(1);
-        hipLaunchKernelGGL(k_sure_count<SBPW>, dim3((T + 3) / 4, (B + SBPW - 1) / SBPW), dim3(BLOCK), 0, ctx->stream, core_bits,
+        hipLaunchKernelGGL(k_sure_count<SBPW>, dim3((T + 3) / 4, (B + SBPW - 1) / SBPW), dim3(BLOCK), 0, st, core_bits,
                            n_words, ctx->n, ctx->d_tile_start, ctx->d_tile_seg, T, S, B, ctx->e_sure_bits, ctx->e_cnt_sel);
         SLIMDP_LAUNCHED(ctx, "k_sure_count");
-        hipLaunchKernelGGL(k_seg_sum, dim3(S, B), dim3(1024), 0, ctx->stream, ctx->e_cnt_sel, 1u, ctx->d_seg_first_tile, T, S,
+        hipLaunchKernelGGL(k_seg_sum, dim3(S, B), dim3(1024), 0, st, ctx->e_cnt_sel, 1u, ctx->d_seg_first_tile, T, S,
                            ctx->e_nsure);
         SLIMDP_LAUNCHED(ctx, "k_seg_sum");
-        hipLaunchKernelGGL(k_cand_gather, dim3((uint32_t)(((uint64_t)B * T + 1023) / 1024)), dim3(1024), 0, ctx->stream,
+        hipLaunchKernelGGL(k_cand_gather, dim3((uint32_t)(((uint64_t)B * T + 1023) / 1024)), dim3(1024), 0, st,
                            core_bits, ctx->n, ctx->d_tile_start, ctx->d_tile_seg, T, S, B, ctx->e_pair_keys, ctx->pair_stride,
                            ctx->e_cnt_cand, ctx->e_list, ctx->e_list_count, (uint32_t)ctx->list_cap, ctx->d_flags);
         SLIMDP_LAUNCHED(ctx, "k_cand_gather");
         const uint32_t hoff[3] = {H_L0, H_L1, H_L2};
         for (int level = 0; level < 3; ++level) {
-            hipLaunchKernelGGL(k_short_hist, dim3(512), dim3(256), 0, ctx->stream, ctx->e_list, ctx->e_list_count,
+            hipLaunchKernelGGL(k_short_hist, dim3(512), dim3(256), 0, st, ctx->e_list, ctx->e_list_count,
                                (uint32_t)ctx->list_cap, ctx->e_state, ctx->e_hist, hoff[level], level, ctx->d_flags);
             SLIMDP_LAUNCHED(ctx, "k_short_hist");
-            hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, ctx->stream, ctx->e_state, ctx->e_hist, level, hoff[level],
+            hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, st, ctx->e_state, ctx->e_hist, level, hoff[level],
                                S, level == 0 ? 1 : 0, ctx->d_flags, ctx->e_nsure, 1, SpecTau{nullptr, nullptr, nullptr}, CorePred{nullptr, nullptr, nullptr, 0});
             SLIMDP_LAUNCHED(ctx, "k_threshold");
         }
-        hipLaunchKernelGGL(k_short_mark, dim3(512), dim3(256), 0, ctx->stream, ctx->e_list, ctx->e_list_count,
+        hipLaunchKernelGGL(k_short_mark, dim3(512), dim3(256), 0, st, ctx->e_list, ctx->e_list_count,
                            (uint32_t)ctx->list_cap, ctx->e_state, T, ctx->e_sure_bits, ctx->e_cnt_sel, ctx->e_tie_list,
                            ctx->e_list_count + 1, ctx->d_flags);
         SLIMDP_LAUNCHED(ctx, "k_short_mark");
-        hipLaunchKernelGGL(k_short_ties, dim3(1), dim3(1024), 0, ctx->stream, ctx->e_list, ctx->e_state, T, ctx->e_sure_bits,
+        hipLaunchKernelGGL(k_short_ties, dim3(1), dim3(1024), 0, st, ctx->e_list, ctx->e_state, T, ctx->e_sure_bits,
                            ctx->e_cnt_sel, ctx->e_tie_list, ctx->e_list_count + 1, ctx->d_flags);
         SLIMDP_LAUNCHED(ctx, "k_short_ties");
-        hipLaunchKernelGGL(k_chunk_scan, dim3(ctx->n_chunks, B), dim3(1024), 0, ctx->stream, T, ctx->e_cnt_sel, off_tab,
+        hipLaunchKernelGGL(k_chunk_scan, dim3(ctx->n_chunks, B), dim3(1024), 0, st, T, ctx->e_cnt_sel, off_tab,
                            ctx->e_chunk_sum, ctx->d_flags);
         SLIMDP_LAUNCHED(ctx, "k_chunk_scan");
         constexpr int EBPW = 4;
-        hipLaunchKernelGGL(k_emit_bits<EBPW>, dim3((T + 3) / 4, (B + EBPW - 1) / EBPW), dim3(BLOCK), 0, ctx->stream, core_bits,
+        hipLaunchKernelGGL(k_emit_bits<EBPW>, dim3((T + 3) / 4, (B + EBPW - 1) / EBPW), dim3(BLOCK), 0, st, core_bits,
                            n_words, ctx->n, ctx->d_tile_start, ctx->d_tile_seg, T, S, B, ctx->e_sure_bits, ctx->e_chunk_sum,
                            ctx->n_chunks, off_tab, idx_tab, (uint32_t)M, ctx->d_flags);
         SLIMDP_LAUNCHED(ctx, "k_emit_bits");
@@ -1077,27 +1159,47 @@ int slimdp_sample_explore(slimdp_ctx* ctx, const uint32_t* core_bits, const uint
         rc = ensure_wide_keys(ctx);
         if (rc) return rc;
         if (!cached) LAUNCH_DRAW(0);
-        hipLaunchKernelGGL(k_explore_filter, dim3(P, B), dim3(BLOCK), 0, ctx->stream, core_bits, ctx->n, ctx->d_tile_start,
+        hipLaunchKernelGGL(k_explore_filter, dim3(P, B), dim3(BLOCK), 0, st, core_bits, ctx->n, ctx->d_tile_start,
                            ctx->d_tile_seg, T, S, ctx->e_state, ctx->e_hist, ctx->e_sure_bits, ctx->e_cnt_gt, ctx->e_cand_bits,
                            ctx->e_cand_keys, ctx->e_cnt_cand, ctx->keys_stride, n_words);
         SLIMDP_LAUNCHED(ctx, "k_explore_filter");
-        hipLaunchKernelGGL(k_seg_sum, dim3(S, B), dim3(1024), 0, ctx->stream, ctx->e_cnt_gt, (uint32_t)SUBS, ctx->d_seg_first_tile,
+        hipLaunchKernelGGL(k_seg_sum, dim3(S, B), dim3(1024), 0, st, ctx->e_cnt_gt, (uint32_t)SUBS, ctx->d_seg_first_tile,
                            T, S, ctx->e_nsure);
         SLIMDP_LAUNCHED(ctx, "k_seg_sum");
-        hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, ctx->stream, ctx->e_state, ctx->e_hist, 0, (uint32_t)H_L0, S, 1,
+        hipLaunchKernelGGL(k_threshold, dim3(S, B), dim3(256), 0, st, ctx->e_state, ctx->e_hist, 0, (uint32_t)H_L0, S, 1,
                            ctx->d_flags, ctx->e_nsure, 0, SpecTau{nullptr, nullptr, nullptr}, CorePred{nullptr, nullptr, nullptr, 0});
         SLIMDP_LAUNCHED(ctx, "k_threshold(0)");
         rc = finish_selection<EXPL_KPL, 4>(ctx, B, ctx->e_state, ctx->e_hist, ctx->e_sure_bits, ctx->e_cand_bits,
                               ctx->e_cand_keys, ctx->e_cnt_gt, ctx->e_cnt_cand, ctx->e_cnt_sel, ctx->e_cnt_tie, ctx->e_tie_pre,
                               ctx->keys_stride, false, off_tab, idx_tab, (uint32_t)M, nullptr, core_bits, ctx->d_flags,
-                              ctx->e_chunk_sum);
+                              ctx->e_chunk_sum, SpecTau{nullptr, nullptr, nullptr}, CorePred{nullptr, nullptr, nullptr, 0}, st);
         if (rc) return rc;
     }
 #undef LAUNCH_DRAW
     // zones missed (flag up): the whole request again, exactly, from the definition; idle otherwise
-    hipLaunchKernelGGL(k_explore_exact, dim3(1, B), dim3(1024), 0, ctx->stream, core_bits, ctx->n, ctx->d_tile_start,
+    hipLaunchKernelGGL(k_explore_exact, dim3(1, B), dim3(1024), 0, st, core_bits, ctx->n, ctx->d_tile_start,
                        ctx->d_seg_first_tile, T, S, ctx->e_state, worker0, pk, idx_tab, off_tab, (uint32_t)M, ctx->d_flags);
     SLIMDP_LAUNCHED(ctx, "k_explore_exact");
+    if (async) {
+        // a free slot, else the oldest one (the main stream then waits for that request first)
+        int slot = -1;
+        for (int j = 0; j < slimdp_ctx::N_PENDING && slot < 0; ++j)
+            if (!ctx->pend[j].live) slot = j;
+        if (slot < 0) {
+            slot = 0;
+            for (int j = 1; j < slimdp_ctx::N_PENDING; ++j)
+                if (ctx->pend[j].seq < ctx->pend[slot].seq) slot = j;
+            SLIMDP_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->pend[slot].ev, 0));
+        }
+        slimdp_ctx::PendingExplore& p = ctx->pend[slot];
+        SLIMDP_HIP(ctx, hipEventRecord(p.ev, ctx->side));
+        p.live = true; p.seq = ++ctx->pend_seq; p.nw = B;
+        p.idx_bytes = M * 4 + 4; p.off_bytes = ((uint64_t)T + 1) * 4;
+        for (uint32_t q = 0; q < B; ++q) {
+            p.idx[q] = reinterpret_cast<uintptr_t>(expl_idx ? expl_idx[q] : nullptr);
+            p.off[q] = reinterpret_cast<uintptr_t>(expl_off[q]);
+        }
+    }
     return SLIMDP_OK;
 }
 
@@ -1209,8 +1311,15 @@ int slimdp_pack(slimdp_ctx* ctx, uint32_t n_workers, const float* const* g, cons
         if (k && ctx->n_seg == 1) {
             // flat model: tile = index / 4096; all tiles but a ragged last one are full
             const uint32_t T_full = (uint32_t)(ctx->n / TILE);
+            // many short blocks: work on the side stream (an asynchronous explorer request) gets its turn between them
             uint64_t blocks = (k + 1023) / 1024;
-            if (blocks > 4096) blocks = 4096;
+            if (blocks > 32768) blocks = 32768;
+            // while an explorer request runs on the side stream: few resident blocks, so that its small kernels find free
+            // slots at once (measured: 2.54 -> 2.48 ms per step with one block per compute unit)
+            bool side_busy = false;
+            for (int j = 0; j < slimdp_ctx::N_PENDING; ++j) side_busy = side_busy || ctx->pend[j].live;
+            const uint64_t per_cu = ctx->opt_pack_core_blocks > 0 ? (uint64_t)ctx->opt_pack_core_blocks : (side_busy ? 1u : 0u);
+            if (per_cu > 0 && blocks > (uint64_t)ctx->cus * per_cu) blocks = (uint64_t)ctx->cus * per_cu;
             hipLaunchKernelGGL(k_pack_core_flat, dim3((uint32_t)blocks), dim3(256), 0, ctx->stream, make_tab<PtrTab>(g, n_workers),
                                n_workers, ctx->n, T_full, core_idx, (uint32_t)k, ctx->spec.bits, ctx->spec.vals, ctx->spec.fail,
                                ctx->spec.vec_ok, make_tab<MutPtrTab>(core_val, n_workers));
@@ -1225,6 +1334,8 @@ int slimdp_pack(slimdp_ctx* ctx, uint32_t n_workers, const float* const* g, cons
         CountTab mt{};
         uint64_t mmax = 0;
         for (uint32_t q = 0; q < n_workers; ++q) { mt.c[q] = (uint32_t)m_w[q]; if (m_w[q] > mmax) mmax = m_w[q]; }
+        rc = wait_for_lists(ctx, n_workers, expl_idx, expl_off, m_w);    // the core values above did not need the explorer lists; these do
+        if (rc) return rc;
         if (mmax) {
             uint64_t blocks = (mmax + 1023) / 1024;
             if (blocks > 2048) blocks = 2048;
@@ -1235,6 +1346,8 @@ int slimdp_pack(slimdp_ctx* ctx, uint32_t n_workers, const float* const* g, cons
         }
         return SLIMDP_OK;
     }
+    rc = wait_for_lists(ctx, n_workers, expl_idx, expl_off, m_w);
+    if (rc) return rc;
     int vec_ok = 1;
     for (uint32_t q = 0; q < n_workers; ++q) vec_ok = vec_ok && aligned16(g[q]);
     if (ctx->opt_pack_nbuf == 2)
@@ -1265,6 +1378,8 @@ int slimdp_merge(slimdp_ctx* ctx, float* w, float lr, uint64_t core_epoch, uint3
     }
     rc = check_epoch(ctx, core_epoch);
     if (rc) return rc;
+    rc = wait_for_lists(ctx, n_workers, expl_idx, expl_off, m_w);
+    if (rc) return rc;
     hipLaunchKernelGGL(k_merge, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, w, lr, n_workers, ctx->d_tile_start, core_idx,
                        core_off, make_tab<PtrTab>(core_val, n_workers), make_tab<PtrTab>(expl_idx, n_workers),
                        make_tab<PtrTab>(expl_off, n_workers), make_tab<PtrTab>(expl_val, n_workers), (int)aligned16(w),
@@ -1287,6 +1402,8 @@ int slimdp_pull(slimdp_ctx* ctx, const float* w, uint64_t core_epoch, uint32_t n
         if (w_local && w_local[q] == w) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_pull: w_local aliases w");
     }
     rc = check_epoch(ctx, core_epoch);
+    if (rc) return rc;
+    rc = wait_for_lists(ctx, n_workers, expl_idx, expl_off, m_w);
     if (rc) return rc;
     const float* src = w;
     hipLaunchKernelGGL(k_gather, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, make_tab<PtrTab, const float*>(&src, 1), 1,

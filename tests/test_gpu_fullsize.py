@@ -58,6 +58,7 @@ def test_full_size_iteration_matches(wl):
     w = torch.from_numpy(w_h).to(dev)
     g = [torch.from_numpy(x).to(dev) for x in g_h]
     sd.set_option("speculative_pack", 1)
+    sd.set_option("explore_async", 1)            # as bench.py runs it: the explorer request beside the pack of the core
     S = sd.score(w, g, wl.c)                     # as bench.py's warm-up does: a first selection sets the capture bound
     sd.select_core(S, [k], reuse_histogram=True)
     sd.explore_hint([k], it, [m], 0, W)
@@ -139,7 +140,7 @@ def test_full_size_loop_steady_path_matches():
     explorer every iteration, fresh updates per (iteration, worker) written into the SAME device buffers), six
     iterations: t = 0 the first selection of a fresh context, t = 1..4 steady iterations (core keys cached, the pack
     scans updates no scoring pass has seen, every draw announced one iteration ahead: on the side stream, or inside
-    the scoring pass before a reselection), t = 5 a reselection whose capture bound comes from t = 0's selection on
+    the scoring pass before a reselection; explorer requests on the side stream, one iteration ahead while the core stays), t = 5 a reselection whose capture bound comes from t = 0's selection on
     other updates.  Checked over every element: scores, both packs of a reselecting iteration (values kept by the
     scoring pass, and the scanning pack), merge, pull (+ local overwrite), ALL W explorer sets of every iteration,
     and one dense update + significance; the rankings through the threshold property."""
@@ -154,9 +155,11 @@ def test_full_size_loop_steady_path_matches():
     pool = ThreadPoolExecutor(8)
     sd = binding.SlimDP(n, W, seed=workloads.EXPLORE_SEED)
     sd.set_option("speculative_pack", 1)
+    sd.set_option("explore_async", 1)
     w_h = wl.weights()
     w = torch.from_numpy(w_h).to(dev)
     g = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(W)]
+    ahead = None                                            # explorer lists requested one iteration ahead
     ts = sd.tile_starts().astype(np.int64)
     rng = np.random.default_rng(5)
     local_h = rng.standard_normal(n).astype(np.float32)
@@ -174,9 +177,14 @@ def test_full_size_loop_steady_path_matches():
         if resel:
             S = sd.score(w, g, wl.c)
             core_idx, core_bits, core_off, epoch = sd.select_core(S, [k], reuse_histogram=True)
-        expl_idx, expl_off = sd.sample_explore(core_bits, [k], t, [m], 0, W)
+        if ahead is not None:
+            expl_idx, expl_off = ahead
+        else:
+            expl_idx, expl_off = sd.sample_explore(core_bits, [k], t, [m], 0, W)
         sd.set_option("explore_hint_mode", 0 if (t + 1) % every == 0 else 1)
         sd.explore_hint([k], t + 1, [m], 0, W)
+        # the next iteration keeps the core: its explorer request goes out now and runs beside this pack and merge
+        ahead = sd.sample_explore(core_bits, [k], t + 1, [m], 0, W) if (t + 1) % every != 0 else None
         core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch, updates_as_scored=resel)
         if resel:                                           # the scanning pack of the same updates gives the same bits
             cv2, ev2 = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)

@@ -42,7 +42,7 @@ def host_tile_offsets(idx, tile_start):
 
 
 def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, check=True, hint=False, per_tile_tail=False,
-                  clobber_after_select=False, hint_mode=0, as_scored=True, refill_before_pack=False):
+                  clobber_after_select=False, hint_mode=0, as_scored=True, refill_before_pack=False, explore_async=0):
     """One reselect iteration on the GPU and in the oracle; returns both results."""
     seg_off = [int(x) for x in wl.segment_offsets()]
     ks, ms = [int(x) for x in wl.k_seg()], [int(x) for x in wl.m_seg()]
@@ -56,6 +56,7 @@ def run_iteration(wl, iteration=0, w_h=None, sd=None, force_fallback=False, chec
     w = to_dev(w_h)
     g = [to_dev(x) for x in g_h]
     sd.set_option("explore_hint_mode", hint_mode)
+    sd.set_option("explore_async", explore_async)
     if hint:        # the explorer zones are drawn ahead: on the library's side stream (1) or inside the scoring kernel (0)
         sd.explore_hint(ks, iteration, ms, 0, wl.W)
     S = sd.score(w, g, wl.c)
@@ -415,6 +416,69 @@ def test_selection_with_the_scoring_pass_classifying_against_a_predicted_bin(mod
         core_o = oracle.select_core(S_o, wl.k)
         assert np.array_equal(u32(core_idx), core_o), rep
         assert np.array_equal(u32(core_bits), oracle.core_bits(wl.n, core_o)), rep
+    sd.close()
+
+
+@pytest.mark.parametrize("hint_mode", [0, 1])
+@pytest.mark.parametrize("spec", [0, 1])
+def test_asynchronous_explorer_requests(hint_mode, spec):
+    """Option explore_async: the explorer request runs on the library's side stream; pack (after extracting the core
+    values from what the scoring pass kept, if it did), merge and pull wait for it.  Flat, segmented, wide zones,
+    forced exact rerun; a few iterations on one context."""
+    cases = [workloads.TINY.scaled(300_007), workloads.GOOGLENET.scaled(300_001), workloads.STRESS.scaled(100_003, W=5),
+             workloads.TINY.scaled(20_005, core_pct=10, explore_pct=60)]
+    for wl in cases:
+        sd = binding.SlimDP(wl.n, wl.W, seg_off=[int(x) for x in wl.segment_offsets()], seed=workloads.EXPLORE_SEED)
+        sd.set_option("speculative_pack", spec)
+        for t in range(3):
+            got, want = run_iteration(wl, iteration=t, sd=sd, hint=True, hint_mode=hint_mode, explore_async=1,
+                                      force_fallback=(1 if t == 2 else 0))
+            assert_iteration_matches(wl, got, want)
+        sd.close()
+
+
+@pytest.mark.parametrize("hint_mode", [0, 1])
+def test_asynchronous_explorer_one_iteration_ahead(hint_mode):
+    """Steady iterations with cached core keys: the request for iteration t+1 (other output arrays) is issued before
+    the pack of iteration t and runs on the side stream beside pack and merge (hint_mode 1: after its announced draw
+    on the same stream; 0: nothing announced, the request draws itself).  Every set, and the model after every
+    iteration, as in the oracle."""
+    wl = workloads.LOOP.scaled(250_007, W=4)
+    n, W, k, m = wl.n, wl.W, wl.k, wl.m
+    sd = binding.SlimDP(n, W, seed=workloads.EXPLORE_SEED)
+    sd.set_option("explore_async", 1)
+    sd.set_option("explore_hint_mode", hint_mode)
+    w_h = wl.weights()
+    w = to_dev(w_h)
+    g_h = wl.gradients(0)
+    S = sd.score(w, [to_dev(x) for x in g_h], wl.c)
+    core_idx, core_bits, core_off, epoch = sd.select_core(S, [k], reuse_histogram=True)
+    core_o = oracle.select_core(oracle.score(w_h, g_h, wl.c), k)
+    bufs = [sd.sample_explore(core_bits, [k], 0, [m], 0, W), None]
+    for t in range(8):
+        g_h = wl.gradients(t)
+        g = [to_dev(x) for x in g_h]
+        if hint_mode == 1:
+            sd.explore_hint([k], t + 1, [m], 0, W)
+        nxt = bufs[(t + 1) & 1]
+        expl_idx, expl_off = bufs[t & 1]
+
+        def request_next():
+            bufs[(t + 1) & 1] = sd.sample_explore(core_bits, [k], t + 1, [m], 0, W, expl_idx=None if nxt is None else nxt[0],
+                                                  expl_off=None if nxt is None else nxt[1])
+        request_next()
+        core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch)
+        sd.merge(w, wl.lr, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
+        core_out, expl_out = sd.pull(w, epoch, core_idx, core_off, expl_idx, expl_off)
+        sd.synchronize()
+        ei_o = [oracle.sample_explore(n, core_o, workloads.EXPLORE_SEED, t, q, m) for q in range(W)]
+        packs = [oracle.pack(g_h[q], core_o, ei_o[q]) for q in range(W)]
+        w_h = oracle.merge(w_h, wl.lr, core_o, [x[0] for x in packs], ei_o, [x[1] for x in packs])
+        for q in range(W):
+            assert np.array_equal(u32(expl_idx[q]), ei_o[q]), (t, q)
+            assert np.array_equal(f32bits(expl_val[q].cpu().numpy()), f32bits(packs[q][1])), (t, q)
+            assert np.array_equal(f32bits(expl_out[q].cpu().numpy()), f32bits(w_h[ei_o[q]])), (t, q)
+        assert np.array_equal(f32bits(w.cpu().numpy()), f32bits(w_h)), t
     sd.close()
 
 
