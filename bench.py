@@ -69,15 +69,29 @@ def cpu_baseline(sample_n: int, all_cores: bool) -> dict:
     k, m = wl.k, wl.m
     oracle.lib()
 
+    def note(what, t0):      # progress of a long CPU leg, from the work itself
+        if sample_n >= 50_000_000:
+            print("cpu_baseline: %s done at %.1f s" % (what, time.perf_counter() - t0), file=sys.stderr, flush=True)
+
     def one(pool):
         mp = (lambda f, xs: list(pool.map(f, xs))) if pool else (lambda f, xs: [f(x) for x in xs])
         t0 = time.perf_counter()
         S = oracle.score(w, g, wl.c)
+        note("score", t0)
         core = oracle.select_core(S, k)
-        ei = mp(lambda q: oracle.sample_explore(wl.n, core, workloads.EXPLORE_SEED, 0, q, m), range(wl.W))
+        note("core selection", t0)
+
+        def explore(q):
+            r = oracle.sample_explore(wl.n, core, workloads.EXPLORE_SEED, 0, q, m)
+            note("explorer of worker %d" % q, t0)
+            return r
+        ei = mp(explore, range(wl.W))
         packs = mp(lambda q: oracle.pack(g[q], core, ei[q]), range(wl.W))
+        note("packs", t0)
         oracle.merge(w, wl.lr, core, [p[0] for p in packs], ei, [p[1] for p in packs])
-        return time.perf_counter() - t0
+        dt = time.perf_counter() - t0
+        note("merge", t0)
+        return dt
 
     dt = one(None)
     out = {"value": wl.n / dt / 1e9, "unit": "Gparam/s", "cores": 1, "kind": "oracle",

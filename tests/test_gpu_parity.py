@@ -600,6 +600,61 @@ def test_merge_hand_built_collisions_and_tile_offsets():
     sd.close()
 
 
+def test_merge_explorer_lists_that_overlap_the_core_follow_the_stated_order():
+    # Invalid input (an explorer never holds a core index), but the interface states what happens: the core
+    # contributions to such an index are added first, in worker order, then the explorer ones in worker order.
+    # The addends are chosen so that any other order gives other bits.
+    n = 3 * 4096 + 77
+    W = 3
+    sd = binding.SlimDP(n, W)
+    rng = np.random.default_rng(5)
+    w_h = rng.standard_normal(n).astype(np.float32)
+    S = to_dev(np.abs(w_h))
+    k = 40
+    core_idx, core_bits, core_off, epoch = sd.select_core(S, [k])
+    core_h = u32(core_idx)
+    cv = [rng.standard_normal(k).astype(np.float32) for _ in range(W)]
+    one, two, three = int(core_h[3]), int(core_h[17]), int(core_h[31])       # core indices also sent as explorers
+    w_h[[one, two, three]] = [0.75, -1.25, 2.5]      # short values: the expected fma below is exact in binary64
+    big = np.float32(2.0 ** 26)
+    for j in (3, 31):
+        cv[0][j], cv[1][j], cv[2][j] = big, np.float32(1.0), -big            # (big + 1) - big = 0 in binary32
+    cv[0][17], cv[1][17], cv[2][17] = big, np.float32(1.0), np.float32(1.0)  # stays big (spacing 8 above 2^26)
+    rest = np.setdiff1d(np.arange(n, dtype=np.uint32), core_h)
+    ei = [np.sort(np.concatenate([rest[[5, 900]], [one, two, three]])).astype(np.uint32),
+          np.sort(np.concatenate([rest[[5, 7000]], [three]])).astype(np.uint32),
+          np.sort(np.concatenate([rest[[5, 12000]], [two, three]])).astype(np.uint32)]
+    ev = [rng.standard_normal(x.size).astype(np.float32) for x in ei]
+    sent = {one: [(0, 0.5)], two: [(0, 5.0), (2, -3.0)], three: [(0, big), (1, 5.0), (2, -big)]}
+    accs = {}
+    for idx, lst in sent.items():
+        for q, v in lst:
+            ev[q][np.searchsorted(ei[q], idx)] = np.float32(v)
+    lr = np.float32(0.5)
+    want = oracle.merge(w_h, float(lr), core_h, cv, [np.setdiff1d(x, core_h) for x in ei],
+                        [v[~np.isin(x, core_h)] for x, v in zip(ei, ev)])    # everything outside the three indices
+    for idx, lst in sent.items():
+        j = int(np.searchsorted(core_h, idx))
+        acc = np.float32(0.0)
+        for q in range(W):
+            acc = np.float32(acc + cv[q][j])
+        for q, v in lst:
+            acc = np.float32(acc + np.float32(v))
+        accs[idx] = float(acc)
+        want[idx] = np.float32(np.float64(w_h[idx]) - np.float64(lr) * np.float64(acc))   # exact product, one rounding
+    # core first: 0 + 0.5; (big + 5 -> big + 8) - 3 -> big + 8 (the other order gives big); ((0 + big) + 5 -> big + 8) - big
+    assert accs == {one: 0.5, two: float(big) + 8.0, three: 8.0}
+    d_ei = [to_dev(x) for x in ei]
+    d_eo = [sd.tile_offsets(x) for x in d_ei]
+    d_cv, d_ev = [to_dev(x) for x in cv], [to_dev(x) for x in ev]
+    for _ in range(3):
+        w = to_dev(w_h)
+        sd.merge(w, float(lr), epoch, core_idx, core_off, d_cv, d_ei, d_eo, d_ev)
+        sd.synchronize()
+        assert np.array_equal(f32bits(w.cpu().numpy()), f32bits(want))
+    sd.close()
+
+
 def test_pull_overwrites_local_models_only_at_the_communication_set():
     wl = workloads.TINY.scaled(25_003, W=2)
     seg_off = [0, wl.n]
