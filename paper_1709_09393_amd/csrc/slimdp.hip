@@ -435,6 +435,21 @@ int ensure_wide_keys(slimdp_ctx* c)
     return SLIMDP_OK;
 }
 
+// Probability that one sub-tile holds more than PAIR_CAP candidates of one draw when lambda are expected (the draw
+// marks each of its up to 1024 words independently: Poisson tail, summed directly so that tiny values keep their digits).
+double pair_overflow_prob(double lambda)
+{
+    if (lambda <= 0.0) return 0.0;
+    const int j0 = (int)PAIR_CAP + 1;
+    double term = std::exp(-lambda + j0 * std::log(lambda) - std::lgamma((double)j0 + 1.0)), sum = 0.0;
+    for (int j = j0; j < j0 + 4096; ++j) {
+        sum += term;
+        term *= lambda / (double)(j + 1);
+        if (term < 1e-18 * sum && (double)j > lambda) break;
+    }
+    return sum < 1.0 ? sum : 1.0;
+}
+
 // Per-segment start of the explorer's radix descent.  The m-th smallest Philox word of the
 // avail = n_s - k_s parameters outside the core lies, with overwhelming probability, between
 // the words that m - 6 sqrt(m) - 32 and m + 6 sqrt(m) + 32 of them are expected to stay below:
@@ -442,13 +457,16 @@ int ensure_wide_keys(slimdp_ctx* c)
 // become candidates.  The exact rerun with every word a candidate catches a miss on either
 // side.  Returns an error code for impossible requests; *narrow is set when every segment
 // got a narrow candidate zone; *short_list when the zones are so narrow that the candidates
-// of n_workers draws fit the unordered list of the short-list path with room to spare.
+// of n_workers draws fit the unordered list of the short-list path with room to spare and no
+// sub-tile is likely to see more of them than its pair slot holds (small segments have
+// relatively wide zones: twelve standard deviations of a small m are a large share of it).
 int explorer_init(slimdp_ctx* ctx, const char* who, const uint64_t* k_seg, const uint64_t* m_seg, uint32_t n_workers,
                   std::vector<SegInit>& init, uint64_t* M_out, bool* narrow, bool* short_list)
 {
     uint64_t M = 0;
     bool all_narrow = true, all_short = true;
     double expect = 0.0;           // candidates of one draw
+    double overflows = 0.0;        // expected number of sub-tiles of the request with more candidates than a pair slot holds
     init.resize(ctx->n_seg);
     for (uint32_t s = 0; s < ctx->n_seg; ++s) {
         const uint64_t ns = ctx->seg_off[s + 1] - ctx->seg_off[s];
@@ -467,6 +485,7 @@ int explorer_init(slimdp_ctx* ctx, const char* who, const uint64_t* k_seg, const
             uint64_t width = 1ull << 32;                     // number of distinct candidate words
             if (hi >= 0.25) all_short = false;
             expect += (hi - (lo > 0.0 ? lo : 0.0)) * avail;
+            overflows += pair_overflow_prob((hi - (lo > 0.0 ? lo : 0.0)) * (double)SUB) * ((double)ns / SUB + 2.0) * n_workers;
             if (hi >= 0.95) {
                 in.bound_m1 = 0xFFFFFFFFu;
                 all_narrow = false;
@@ -491,8 +510,9 @@ int explorer_init(slimdp_ctx* ctx, const char* who, const uint64_t* k_seg, const
     }
     *M_out = M;
     *narrow = all_narrow;
+    // an overflowing slot costs the exact rerun (about a thousand times the per-tile tail): taken only if that is unlikely
     *short_list = all_narrow && all_short && !ctx->opt_per_tile_tail && (uint64_t)ctx->T * TILE <= 0xFFFFFFFFull &&
-                  1.25 * expect * (double)n_workers + 4096.0 <= (double)ctx->list_cap;
+                  1.25 * expect * (double)n_workers + 4096.0 <= (double)ctx->list_cap && overflows <= 1e-5;
     return SLIMDP_OK;
 }
 
