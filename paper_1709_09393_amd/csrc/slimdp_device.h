@@ -201,14 +201,47 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     for (int r = 0; r < 10; ++r) {
         const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
         const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        // three-input exclusive or in one instruction (truth table 0x96)
+        const uint32_t n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(p1 >> 32), c1, k0, 0x96);
+        const uint32_t n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(p0 >> 32), c3, k1, 0x96);
         c1 = (uint32_t)p1;
         c3 = (uint32_t)p0;
         c0 = n0;
         c2 = n2;
         k0 += 0x9E3779B9u;
         k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// The same with the ten round keys handed over (key + round * Weyl constant): a kernel that draws many words under
+// one key computes them once and, made opaque to the compiler, keeps them in vector registers; left to itself the
+// compiler holds them in scalar registers, runs out of those and reloads each with a lane read before every use.
+struct PhiloxRoundKeys { uint32_t k0[10], k1[10]; };
+__device__ __forceinline__ PhiloxRoundKeys philox_round_keys(uint32_t k0, uint32_t k1)
+{
+    PhiloxRoundKeys rk;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        rk.k0[r] = k0 + (uint32_t)r * 0x9E3779B9u;
+        rk.k1[r] = k1 + (uint32_t)r * 0xBB67AE85u;
+        asm volatile("" : "+v"(rk.k0[r]), "+v"(rk.k1[r]));
+    }
+    return rk;
+}
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, const PhiloxRoundKeys& rk,
+                                              uint32_t out[4])
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(p1 >> 32), c1, rk.k0[r], 0x96);
+        const uint32_t n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(p0 >> 32), c3, rk.k1[r], 0x96);
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
     }
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }

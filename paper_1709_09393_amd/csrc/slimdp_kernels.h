@@ -229,10 +229,19 @@ __device__ __forceinline__ uint32_t inside_mask(uint32_t e0, uint32_t sub_len)
 // in index order (lane L owns parameters 4L..4L+3 of the round), so a candidate's place in
 // the key list is the number of candidates in earlier rounds plus a wave ballot count, and
 // the eight bitmap words of the round are OR-reductions over groups of eight lanes.
-template <int PAIRS>
+// KEYS: PhiloxKey, or PhiloxRoundKeys of a caller that draws under one key many times (pk then only names the iteration).
+__device__ __forceinline__ void philox_words(uint32_t c0, uint32_t worker, const PhiloxKey& pk, const PhiloxKey&, uint32_t r[4])
+{
+    philox4x32_10(c0, worker, pk.it_lo, pk.it_hi, pk.seed_lo, pk.seed_hi, r);
+}
+__device__ __forceinline__ void philox_words(uint32_t c0, uint32_t worker, const PhiloxKey& pk, const PhiloxRoundKeys& rk, uint32_t r[4])
+{
+    philox4x32_10(c0, worker, pk.it_lo, pk.it_hi, rk, r);
+}
+template <int PAIRS, class KEYS = PhiloxKey>
 __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t, uint32_t sub, uint32_t start, uint32_t len,
                                                      uint32_t bound_m1, uint32_t sure_m1, uint32_t has_sure, uint32_t skip,
-                                                     DrawOut out, PhiloxKey pk)
+                                                     DrawOut out, PhiloxKey pk, const KEYS& keys)
 {
     const uint32_t lane = lane_id();
     const uint32_t off = sub * SUB;
@@ -259,7 +268,7 @@ __device__ __forceinline__ void explore_subtile_fast(uint32_t worker, uint32_t t
     for (int it = 0; it < 4; ++it) {
         const uint32_t e0 = (uint32_t)it * 256u + lane * 4u;      // first of this lane's four parameters
         uint32_t r[4];
-        philox4x32_10((base + e0) >> 2, worker, pk.it_lo, pk.it_hi, pk.seed_lo, pk.seed_hi, r);
+        philox_words((base + e0) >> 2, worker, pk, keys, r);
         // sure flags of the four parameters, without branches (word below sure_excl)
         uint32_t fs = (r[0] < sure_excl ? 1u : 0u) | (r[1] < sure_excl ? 2u : 0u) | (r[2] < sure_excl ? 4u : 0u) |
                       (r[3] < sure_excl ? 8u : 0u);
@@ -463,7 +472,7 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
                     out.cand_keys = pre.cand_keys + (size_t)b * pre.keys_stride;
                     out.cnt_cand = pre.cnt_cand + (size_t)b * T * SUBS;
                     explore_subtile_fast<(PRE == 2) ? 1 : 0>(pre.worker0 + b, t, wid, start, len, pre_bound, pre_sure,
-                                                             pre_has_sure, pre_skip, out, pre.pk);
+                                                             pre_has_sure, pre_skip, out, pre.pk, pre.pk);
                 }
             }
             if (vec) {          // ... then score them
@@ -618,6 +627,8 @@ __global__ __launch_bounds__(BLOCK, SCOREF_MINB) void k_score_flat(const float* 
 #pragma unroll
         for (int k = 0; k < WT; ++k) x[k] = buffer_load4_aux<SCOREF_LD_AUX>(rg[k], o);
     };
+    PhiloxRoundKeys rkeys;
+    if (PRE) rkeys = philox_round_keys(pre.pk.seed_lo, pre.pk.seed_hi);
     auto draw = [&](uint32_t t, uint32_t len, uint32_t r) {      // this round's share of the announced draws
         if (PRE) {
 #pragma unroll 1
@@ -628,7 +639,7 @@ __global__ __launch_bounds__(BLOCK, SCOREF_MINB) void k_score_flat(const float* 
                 out.cand_keys = pre.cand_keys + (size_t)b * pre.keys_stride;
                 out.cnt_cand = pre.cnt_cand + (size_t)b * T * SUBS;
                 explore_subtile_fast<(PRE == 2) ? 1 : 0>(pre.worker0 + b, t, wid, t * TILE, len, pre_bound, pre_sure,
-                                                         pre_has_sure, pre_skip, out, pre.pk);
+                                                         pre_has_sure, pre_skip, out, pre.pk, rkeys);
             }
         }
     };
@@ -1182,7 +1193,7 @@ __global__ __launch_bounds__(BLOCK) void k_explore_keys(const uint32_t* __restri
         const uint32_t skip = st->need0 == 0;
         const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
         if (FAST)
-            explore_subtile_fast<PAIRS>(worker, t, wid, start, len, bound_m1, sure_m1, has_sure, skip, out, pk);
+            explore_subtile_fast<PAIRS>(worker, t, wid, start, len, bound_m1, sure_m1, has_sure, skip, out, pk, pk);
         else
             explore_subtile<PAIRS>(worker, t, wid, start, len, bound_m1, sure_m1, has_sure, skip, wa[FAST ? 0 : wid],
                             wb[FAST ? 0 : wid], wp[FAST ? 0 : wid], out, pk);

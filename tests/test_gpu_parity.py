@@ -357,6 +357,50 @@ def test_speculative_pack_really_uses_the_captured_values():
     sd.close()
 
 
+def test_pack_from_the_capture_with_lists_of_any_origin():
+    """A pack that states its updates are the scored ones takes the core values from what the scoring pass kept and
+    the explorer values by index: lists from another draw than the announced one, of another length, hand-made
+    lists, and a fuller explorer (10 % of the rest) all get the right values."""
+    wl = workloads.TINY.scaled(300_001, W=4)
+    ks, ms = [wl.k], [wl.m]
+    sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
+    sd.set_option("speculative_pack", 1)
+    w_h = wl.weights()
+    w = to_dev(w_h)
+    rng = np.random.default_rng(11)
+    for t, (it_hint, it_req, m_req) in enumerate([(0, 0, wl.m), (5, 6, wl.m), (7, 7, wl.m // 3), (8, 8, None)]):
+        g_h = wl.gradients(t)
+        g = [to_dev(x) for x in g_h]
+        sd.explore_hint(ks, it_hint, ms, 0, wl.W)
+        S = sd.score(w, g, wl.c)
+        core_idx, core_bits, core_off, epoch = sd.select_core(S, ks, reuse_histogram=True)
+        core_o = oracle.select_core(oracle.score(w_h, g_h, wl.c), ks[0])
+        if m_req is None:       # hand-made lists: random non-core indices, another length per worker
+            rest = np.setdiff1d(np.arange(wl.n, dtype=np.uint32), core_o)
+            ei_h = [np.sort(rng.choice(rest, size=1000 + 777 * q, replace=False)).astype(np.uint32) for q in range(wl.W)]
+            expl_idx = [to_dev(x) for x in ei_h]
+            expl_off = [sd.tile_offsets(x) for x in expl_idx]
+        else:
+            expl_idx, expl_off = sd.sample_explore(core_bits, ks, it_req, [m_req], 0, wl.W)
+            ei_h = [oracle.sample_explore(wl.n, core_o, workloads.EXPLORE_SEED, it_req, q, m_req) for q in range(wl.W)]
+        core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch, updates_as_scored=True)
+        sd.synchronize()
+        for q in range(wl.W):
+            assert np.array_equal(u32(expl_idx[q]), ei_h[q]), (t, q)
+            cv_o, ev_o = oracle.pack(g_h[q], core_o, ei_h[q])
+            assert np.array_equal(f32bits(core_val[q].cpu().numpy()), f32bits(cv_o)), (t, q)
+            assert np.array_equal(f32bits(expl_val[q].cpu().numpy()), f32bits(ev_o)), (t, q)
+    sd.close()
+    # a fuller explorer
+    wl = workloads.TINY.scaled(150_000, W=8, explore_pct=10)
+    sd = binding.SlimDP(wl.n, wl.W, seed=workloads.EXPLORE_SEED)
+    sd.set_option("speculative_pack", 1)
+    for t in range(2):
+        got, want = run_iteration(wl, iteration=t, sd=sd, hint=True)
+        assert_iteration_matches(wl, got, want)
+    sd.close()
+
+
 @pytest.mark.parametrize("bias", [0, 1 << 22, -(1 << 20), -(1 << 22)])
 @pytest.mark.parametrize("announced", [False, True])
 def test_first_iteration_captures_under_a_sampled_bound(bias, announced):
