@@ -406,6 +406,11 @@ def main() -> int:
         delta = [torch.empty_like(w0) for _ in range(W)]
         sd.local_step(w_local, g, delta, 0.01, first=True)
         ls_ms = timed(lambda r: sd.local_step(w_local, g, delta, 0.01, first=False), reps)
+        # the last local step before a push with the extraction in the same pass, against the two calls it replaces
+        lsp_ms = timed(lambda r: sd.local_step_pack(w_local, g, delta, 0.01, False, b.core_idx, b.core_off, b.expl_idx,
+                                                    b.expl_off, epoch2, core_val=b.core_val, expl_val=b.expl_val), reps)
+        pk_ms = timed(lambda r: sd.pack(delta, b.core_idx, b.core_off, b.expl_idx, b.expl_off, epoch2, core_val=b.core_val,
+                                        expl_val=b.expl_val), reps)
         pull_ms = timed(lambda r: sd.pull(w, epoch2, b.core_idx, b.core_off, b.expl_idx, b.expl_off, w_local=w_local,
                                           core_out=b.core_val, expl_out=b.expl_val), reps)
         del w_local, delta
@@ -424,6 +429,9 @@ def main() -> int:
         nvals = W * (k + m)
         out["worker_side"] = {
             "local_step": {"ms": ls_ms, "algorithmic_bytes": 20 * n * W, "hbm_frac": frac(20 * n * W, ls_ms)},
+            "local_step_and_pack_in_one_pass": {"ms": lsp_ms, "two_calls_ms": ls_ms + pk_ms,
+                                                "algorithmic_bytes": 20 * n * W + sb["pack"] - 4 * n * W,
+                                                "hbm_frac": frac(20 * n * W + sb["pack"] - 4 * n * W, lsp_ms)},
             "pull_with_local_overwrite": {"ms": pull_ms},
             "quantize": {"ms": q_ms, "algorithmic_bytes": 5 * nvals, "hbm_frac": frac(5 * nvals, q_ms)},
             "dequantize": {"ms": dq_ms, "algorithmic_bytes": 5 * nvals, "hbm_frac": frac(5 * nvals, dq_ms)},

@@ -137,7 +137,10 @@ int slimdp_synchronize(slimdp_ctx* ctx);
  *       against the threshold bin of the previous selection, so that slimdp_select_core(..REUSE_HISTOGRAM) need not read
  *       the scores again when its histogram confirms that bin (otherwise it does, as without the option).  0 switches
  *       that off; 2 is a test switch that makes the prediction always wrong.
- *   "capture_estimate_bias" (test switch): added to a sampled capture bound, in units of the last place. */
+ *   "capture_estimate_bias" (test switch): added to a sampled capture bound, in units of the last place.
+ *   "score_pipeline" (0/1), "strided_tiles" (0/1), "build_blocks" (1..64), "pack_core_blocks" (0..64): which scoring
+ *       kernel serves a flat model and launch shapes; results do not depend on them.
+ * An unknown name or a value outside the stated range is SLIMDP_ERR_INVALID_ARG. */
 int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value);
 
 /* ---------------------------------------------------------------------------------- */
@@ -306,6 +309,20 @@ int slimdp_pull(slimdp_ctx* ctx, const float* w, uint64_t core_epoch, uint32_t n
 #define SLIMDP_LOCAL_FIRST 1u
 int slimdp_local_step(slimdp_ctx* ctx, uint32_t n_workers, float* const* w_local, const float* const* grad,
                       float* const* delta, float eta, uint32_t flags);
+
+/* LocalTrain and Push in one pass (section 3.3 steps 1 and 3): the last mini-batch step before a communication
+ * together with the extraction of what the push sends.  Same results, bit for bit, as
+ *     slimdp_local_step(ctx, n_workers, w_local, grad, delta, eta, flags) followed by
+ *     slimdp_pack(ctx, n_workers, delta, core_idx, ..., core_val, expl_val, core_epoch, 0),
+ * but the accumulated updates are not read a second time: the extraction's own scan of the update vectors (the full
+ * scan that section 3.5 counts per extraction) rides on the pass that writes them.  Arguments as in those two
+ * calls; the explorer lists of the coming push must exist (they depend on seed, iteration, worker and the core only:
+ * slimdp_sample_explore can run before the local steps). */
+int slimdp_local_step_pack(slimdp_ctx* ctx, uint32_t n_workers, float* const* w_local, const float* const* grad,
+                           float* const* delta, float eta, uint32_t flags, const uint32_t* core_idx,
+                           const uint32_t* core_off, uint64_t k, const uint32_t* const* expl_idx,
+                           const uint32_t* const* expl_off, const uint64_t* m_w, float* const* core_val,
+                           float* const* expl_val, uint64_t core_epoch);
 
 /* Quantised wire values: the method composes with gradient quantisation (section 2.2, last sentences); the
  * comparison of section 4.2 uses random quantisation with 8 bits and buckets of 512, after Alistarh et al. (QSGD).

@@ -1463,6 +1463,49 @@ int slimdp_local_step(slimdp_ctx* ctx, uint32_t n_workers, float* const* w_local
     return SLIMDP_OK;
 }
 
+int slimdp_local_step_pack(slimdp_ctx* ctx, uint32_t n_workers, float* const* w_local, const float* const* grad,
+                           float* const* delta, float eta, uint32_t flags, const uint32_t* core_idx, const uint32_t* core_off,
+                           uint64_t k, const uint32_t* const* expl_idx, const uint32_t* const* expl_off, const uint64_t* m_w,
+                           float* const* core_val, float* const* expl_val, uint64_t core_epoch)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    if (flags & ~SLIMDP_LOCAL_FIRST) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_local_step_pack: unknown flag bits 0x%x", flags);
+    int rc = check_lists(ctx, "slimdp_local_step_pack", n_workers, core_idx, core_off, k, expl_idx, expl_off, m_w);
+    if (rc) return rc;
+    if (!table_ok(w_local, n_workers) || !table_ok(grad, n_workers) || !table_ok(delta, n_workers))
+        return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_local_step_pack: NULL array");
+    if (!std::isfinite(eta)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_local_step_pack: eta must be finite");
+    int vec_ok = 1;
+    for (uint32_t q = 0; q < n_workers; ++q) {
+        vec_ok = vec_ok && aligned16(w_local[q]) && aligned16(grad[q]) && aligned16(delta[q]);
+        if (static_cast<const void*>(w_local[q]) == static_cast<const void*>(delta[q]) ||
+            static_cast<const void*>(grad[q]) == static_cast<const void*>(delta[q]) ||
+            static_cast<const void*>(grad[q]) == static_cast<const void*>(w_local[q]))
+            return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_local_step_pack: arrays of worker %u alias", q);
+        if (k && (!core_val || !core_val[q])) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_local_step_pack: NULL core_val entry");
+        if (m_w[q] && (!expl_val || !expl_val[q])) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_local_step_pack: NULL expl_val entry");
+    }
+    rc = check_epoch(ctx, core_epoch);
+    if (rc) return rc;
+    rc = wait_for_lists(ctx, n_workers, expl_idx, expl_off, m_w);
+    if (rc) return rc;
+    const int first = (flags & SLIMDP_LOCAL_FIRST) != 0;
+    if (ctx->opt_pack_nbuf == 2)
+        hipLaunchKernelGGL(k_local_step_pack<2>, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, make_tab<MutPtrTab>(w_local, n_workers),
+                           make_tab<PtrTab>(grad, n_workers), make_tab<MutPtrTab>(delta, n_workers), eta, first, n_workers,
+                           ctx->d_tile_start, core_idx, core_off, make_tab<PtrTab>(expl_idx, n_workers),
+                           make_tab<PtrTab>(expl_off, n_workers), make_tab<MutPtrTab>(core_val, n_workers),
+                           make_tab<MutPtrTab>(expl_val, n_workers), vec_ok);
+    else
+        hipLaunchKernelGGL(k_local_step_pack<1>, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, make_tab<MutPtrTab>(w_local, n_workers),
+                           make_tab<PtrTab>(grad, n_workers), make_tab<MutPtrTab>(delta, n_workers), eta, first, n_workers,
+                           ctx->d_tile_start, core_idx, core_off, make_tab<PtrTab>(expl_idx, n_workers),
+                           make_tab<PtrTab>(expl_off, n_workers), make_tab<MutPtrTab>(core_val, n_workers),
+                           make_tab<MutPtrTab>(expl_val, n_workers), vec_ok);
+    SLIMDP_LAUNCHED(ctx, "k_local_step_pack");
+    return SLIMDP_OK;
+}
+
 static int quant_args(slimdp_ctx* ctx, const char* who, uint32_t n_workers, const void* const* a, const void* const* b,
                       const void* const* c, const uint64_t* count, Count64Tab* ct, uint64_t* cmax)
 {

@@ -2709,6 +2709,118 @@ __global__ __launch_bounds__(256) void k_local_step(MutPtrTab w_local, PtrTab gr
 }
 
 // ---------------------------------------------------------------------------------------
+// LocalTrain and Push in one pass (section 3.3 steps 1 and 3): the last mini-batch step before a
+// communication already streams the accumulated update of every worker; picking the values at
+// the communication set while a tile of the new update sits in LDS saves the extraction its own
+// scan of the update vectors (the full scan that section 3.5 counts per extraction).  Same
+// results as k_local_step followed by k_pack_stream on delta.  One block per tile, workers in
+// turn, the next worker's three tiles in flight while the current one is picked from.
+// ---------------------------------------------------------------------------------------
+template <int NBUF>
+__global__ __launch_bounds__(BLOCK) void k_local_step_pack(MutPtrTab w_local, PtrTab grad, MutPtrTab delta, float eta, int first,
+                                                           uint32_t nw, const uint32_t* __restrict__ tile_start,
+                                                           const uint32_t* __restrict__ core_idx,
+                                                           const uint32_t* __restrict__ core_off, PtrTab expl_idx, PtrTab expl_off,
+                                                           MutPtrTab core_val, MutPtrTab expl_val, int vec_ok)
+{
+    __shared__ float buf[NBUF][TILE];
+    __shared__ uint16_t cpos[TILE];          // the tile's core positions: the same for every worker
+    __shared__ uint32_t elo[MAXW], ehi[MAXW];
+    const uint32_t t = blockIdx.x;
+    const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
+    const bool vec = vec_ok && len == TILE && (start & 3u) == 0;
+    const uint32_t c0 = core_off[t], c1 = core_off[t + 1];
+    const uint32_t ccnt = (c1 - c0 < TILE) ? c1 - c0 : TILE;
+    if (threadIdx.x < nw) {
+        const uint32_t* eo = static_cast<const uint32_t*>(expl_off.p[threadIdx.x]);
+        elo[threadIdx.x] = eo[t];
+        ehi[threadIdx.x] = eo[t + 1];
+    }
+    for (uint32_t x = threadIdx.x; x < ccnt; x += BLOCK) {
+        const uint32_t pos = core_idx[c0 + x] - start;
+        cpos[x] = (pos < len) ? (uint16_t)pos : (uint16_t)0xFFFF;
+    }
+    __syncthreads();
+    float rg[EPT], rw[EPT], rd[EPT];
+    uint32_t epos = 0xFFFFFFFFu;
+    auto fetch = [&](uint32_t q) {
+        const float* g = static_cast<const float*>(grad.p[q]) + start;
+        const float* w = static_cast<const float*>(w_local.p[q]) + start;
+        const float* d = static_cast<const float*>(delta.p[q]) + start;
+        if (vec) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t o = k * 1024 + threadIdx.x * 4;
+                const float4 a = ld4<1>(g + o), b = ld4<1>(w + o);
+                rg[4 * k + 0] = a.x; rg[4 * k + 1] = a.y; rg[4 * k + 2] = a.z; rg[4 * k + 3] = a.w;
+                rw[4 * k + 0] = b.x; rw[4 * k + 1] = b.y; rw[4 * k + 2] = b.z; rw[4 * k + 3] = b.w;
+                if (!first) {
+                    const float4 c = ld4<1>(d + o);
+                    rd[4 * k + 0] = c.x; rd[4 * k + 1] = c.y; rd[4 * k + 2] = c.z; rd[4 * k + 3] = c.w;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < EPT; ++j) {
+                const uint32_t e = elem_scl(j);
+                rg[j] = (e < len) ? g[e] : 0.0f;
+                rw[j] = (e < len) ? w[e] : 0.0f;
+                rd[j] = (e < len && !first) ? d[e] : 0.0f;
+            }
+        }
+        const uint32_t j = elo[q] + threadIdx.x;
+        epos = (j < ehi[q]) ? static_cast<const uint32_t*>(expl_idx.p[q])[j] - start : 0xFFFFFFFFu;
+    };
+    fetch(0);
+    for (uint32_t q = 0; q < nw; ++q) {
+        float* b = buf[NBUF == 2 ? (q & 1u) : 0];
+        float* w = static_cast<float*>(w_local.p[q]) + start;
+        float* d = static_cast<float*>(delta.p[q]) + start;
+        if (NBUF == 1 && q) __syncthreads();     // the previous worker's readers are done with the buffer
+        // the step and the accumulation; the new update goes to memory and to LDS
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            rw[j] = __builtin_fmaf(-eta, rg[j], rw[j]);
+            rd[j] = first ? rg[j] : rd[j] + rg[j];
+        }
+        if (vec) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t o = k * 1024 + threadIdx.x * 4;
+                st4<1>(w + o, make_float4(rw[4 * k], rw[4 * k + 1], rw[4 * k + 2], rw[4 * k + 3]));
+                st4<1>(d + o, make_float4(rd[4 * k], rd[4 * k + 1], rd[4 * k + 2], rd[4 * k + 3]));
+                *reinterpret_cast<float4*>(b + o) = make_float4(rd[4 * k], rd[4 * k + 1], rd[4 * k + 2], rd[4 * k + 3]);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < EPT; ++j) {
+                const uint32_t e = elem_scl(j);
+                if (e < len) { w[e] = rw[j]; d[e] = rd[j]; }
+                b[e] = rd[j];
+            }
+        }
+        const uint32_t my_epos = epos;
+        __syncthreads();     // with two buffers this also orders a buffer's readers (two workers ago) before its writers
+        if (q + 1 < nw) fetch(q + 1);
+        float* cv = static_cast<float*>(core_val.p[q]);
+        for (uint32_t x = threadIdx.x; x < ccnt; x += BLOCK) {
+            const uint32_t pos = cpos[x];
+            if (pos != 0xFFFFu) cv[c0 + x] = b[pos];
+        }
+        float* ev = static_cast<float*>(expl_val.p[q]);
+        const uint32_t e0 = elo[q], e1 = ehi[q];
+        if (my_epos < len) ev[e0 + threadIdx.x] = b[my_epos];
+        if (e1 - e0 > BLOCK) {               // dense explorers: the rest of the slice, loaded here
+            const uint32_t* ei = static_cast<const uint32_t*>(expl_idx.p[q]);
+            for (uint32_t j = e0 + BLOCK + threadIdx.x; j < e1; j += BLOCK) {
+                const uint32_t pos = ei[j] - start;
+                if (pos < len) ev[j] = b[pos];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Quantised wire values (section 2.2, last sentences; section 4.2: random quantisation, 8 bits,
 // buckets of 512).  Per bucket of QB consecutive list entries: scale = largest magnitude;
 // per value: code = sign bit | level, level = floor(y) + (u < y - floor(y)), y = (|v| / scale) * 127

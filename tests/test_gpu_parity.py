@@ -976,6 +976,65 @@ def test_local_step_matches_oracle(n, W, shift):
     sd.close()
 
 
+@pytest.mark.parametrize("n,W,segmented,shift,nbuf", [(5, 1, False, 0, 2), (4097, 3, False, 0, 1), (200_003, 8, False, 0, 2),
+                                                        (300_001, 4, True, 0, 2), (70_000, 2, False, 1, 2)])
+def test_local_step_and_pack_in_one_pass(n, W, segmented, shift, nbuf):
+    """The last mini-batch step before a push together with the extraction: the same local models, accumulated updates
+    and packs as the oracle's local step followed by its pack, for a first step (p = 1) and for an accumulating one;
+    flat and segmented, ragged tiles, arrays without 16-byte alignment, an explorer request still running on the side
+    stream when the call is made."""
+    wl = (workloads.GOOGLENET if segmented else workloads.TINY).scaled(n, W=W)
+    seg_off = [int(x) for x in wl.segment_offsets()]
+    ks, ms = [int(x) for x in wl.k_seg()], [int(x) for x in wl.m_seg()]
+    so = None if wl.n_seg == 1 and wl.seg_off is None else seg_off
+    rng = np.random.default_rng(n + W)
+    sd = binding.SlimDP(n, W, seg_off=seg_off, seed=workloads.EXPLORE_SEED)
+    sd.set_option("pack_nbuf", nbuf)
+    sd.set_option("explore_async", 1)
+    eta = 0.05
+
+    def dev_arr(a):
+        buf = torch.full((n + shift,), float("nan"), dtype=torch.float32, device=dev())
+        buf[shift:] = torch.from_numpy(a)
+        return buf[shift:]
+    S_h = np.abs(wl.weights())
+    core_idx, core_bits, core_off, epoch = sd.select_core(to_dev(S_h), ks)
+    core_o = oracle.select_core(S_h, ks, so)
+    w_h = [rng.standard_normal(n).astype(np.float32) for _ in range(W)]
+    w = [dev_arr(x) for x in w_h]
+    d = [dev_arr(np.full(n, np.nan, np.float32)) for _ in range(W)]
+    d_h = [None] * W
+    for t, steps in enumerate([1, 3]):                       # p = 1: the only step is the first one; p = 3: two plain steps before
+        expl_idx, expl_off = sd.sample_explore(core_bits, ks, t, ms, 0, W)        # asynchronous: the call below waits for it
+        ei_o = [oracle.sample_explore(n, core_o, workloads.EXPLORE_SEED, t, q, ms, so) for q in range(W)]
+        d_h = [None] * W
+        for j in range(steps):
+            g_h = [(rng.standard_normal(n) * 10.0 ** rng.integers(-4, 3, n)).astype(np.float32) for _ in range(W)]
+            g = [dev_arr(x) for x in g_h]
+            if j + 1 < steps:
+                sd.local_step(w, g, d, eta, first=(j == 0))
+            else:
+                core_val, expl_val = sd.local_step_pack(w, g, d, eta, j == 0, core_idx, core_off, expl_idx, expl_off, epoch)
+            for q in range(W):
+                w_h[q], d_h[q] = oracle.local_step(w_h[q], d_h[q], g_h[q], eta)
+        sd.synchronize()
+        for q in range(W):
+            assert np.array_equal(u32(expl_idx[q]), ei_o[q]), (t, q)
+            assert np.array_equal(f32bits(w[q].cpu().numpy()), f32bits(w_h[q])), (t, q)
+            assert np.array_equal(f32bits(d[q].cpu().numpy()), f32bits(d_h[q])), (t, q)
+            cv_o, ev_o = oracle.pack(d_h[q], core_o, ei_o[q])
+            assert np.array_equal(f32bits(core_val[q].cpu().numpy()), f32bits(cv_o)), (t, q)
+            assert np.array_equal(f32bits(expl_val[q].cpu().numpy()), f32bits(ev_o)), (t, q)
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.local_step_pack(w, g, d, eta, True, core_idx, core_off, expl_idx, expl_off, epoch + 1)
+    assert e.value.code == binding.ERR_STALE_CORE
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.local_step_pack(w, w, d, eta, True, core_idx, core_off, expl_idx, expl_off, epoch)
+    assert e.value.code == binding.ERR_INVALID_ARG
+    sd.synchronize()
+    sd.close()
+
+
 def test_worker_loop_closure_local_models_diverge_and_are_pulled_back():
     """W local models carried through the loop of algorithm 1's worker side: p = 2 local mini-batch steps accumulate
     delta_k, the communication set of delta_k is pushed and merged, the worker pulls the global values at its
