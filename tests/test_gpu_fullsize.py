@@ -244,3 +244,62 @@ def test_full_size_loop_steady_path_matches():
     print("dense update ok (%.1f s)" % (time.time() - t0), flush=True)
     sd.close()
     pool.shutdown()
+
+
+def test_full_size_worker_side_local_steps_and_fused_pack():
+    """The worker side at the VGG-16 size (two of the eight workers, to keep the host's part short): a first local
+    step, then the last step before the push with the extraction in the same pass, then the pull with local overwrite.
+    Local models, accumulated updates and packs are compared with the oracle over every element; the index sets are the
+    library's own (their parity is the business of the tests above)."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU test selected but torch.cuda.is_available() is False")
+    dev = torch.device("cuda:0")
+    wl = workloads.VGG16
+    n, W, k, m = wl.n, 2, wl.k, wl.m
+    eta = 0.05
+    t0 = time.time()
+    w_h = wl.weights()
+    sd = binding.SlimDP(n, W, seed=workloads.EXPLORE_SEED)
+    sd.set_option("explore_async", 1)
+    w = torch.from_numpy(w_h).to(dev)
+    core_idx, core_bits, core_off, epoch = sd.select_core(w.abs(), [k])
+    expl_idx, expl_off = sd.sample_explore(core_bits, [k], 0, [m], 0, W)        # runs beside the local steps
+    wk_h = [w_h.copy() for _ in range(W)]
+    wk = [torch.from_numpy(x).to(dev) for x in wk_h]
+    delta = [torch.full((n,), float("nan"), dtype=torch.float32, device=dev) for _ in range(W)]
+    d_h = [None] * W
+    for j in range(2):
+        g_h = [wl.gradient(j, q) for q in range(W)]
+        g = [torch.from_numpy(x).to(dev) for x in g_h]
+        if j == 0:
+            sd.local_step(wk, g, delta, eta, first=True)
+        else:
+            core_val, expl_val = sd.local_step_pack(wk, g, delta, eta, False, core_idx, core_off, expl_idx, expl_off, epoch)
+        for q in range(W):
+            wk_h[q], d_h[q] = oracle.local_step(wk_h[q], d_h[q], g_h[q], eta)
+        del g
+    sd.synchronize()
+    print("local steps done at %.1f s" % (time.time() - t0), flush=True)
+    ci = core_idx.cpu().numpy().view(np.uint32)
+    for q in range(W):
+        ei = expl_idx[q].cpu().numpy().view(np.uint32)
+        assert ei.size == m and np.all(ei[1:] > ei[:-1])
+        assert np.array_equal(wk[q].cpu().numpy().view(np.uint32), wk_h[q].view(np.uint32)), "local model %d" % q
+        assert np.array_equal(delta[q].cpu().numpy().view(np.uint32), d_h[q].view(np.uint32)), "accumulated update %d" % q
+        cv_o, ev_o = oracle.pack(d_h[q], ci, ei)
+        assert np.array_equal(core_val[q].cpu().numpy().view(np.uint32), cv_o.view(np.uint32)), "core_val %d" % q
+        assert np.array_equal(expl_val[q].cpu().numpy().view(np.uint32), ev_o.view(np.uint32)), "expl_val %d" % q
+    # push, then pull with local overwrite: inside the communication set the local model equals the global one
+    sd.merge(w, wl.lr, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
+    sd.pull(w, epoch, core_idx, core_off, expl_idx, expl_off, w_local=wk)
+    sd.synchronize()
+    w_o = oracle.merge(w_h, wl.lr, ci, [oracle.pack(d_h[q], ci, expl_idx[q].cpu().numpy().view(np.uint32))[0] for q in range(W)],
+                       [expl_idx[q].cpu().numpy().view(np.uint32) for q in range(W)],
+                       [oracle.pack(d_h[q], ci, expl_idx[q].cpu().numpy().view(np.uint32))[1] for q in range(W)])
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), w_o.view(np.uint32)), "merged model"
+    for q in range(W):
+        ei = expl_idx[q].cpu().numpy().view(np.uint32)
+        _, _, want = oracle.pull(w_o, ci, ei, wk_h[q])
+        assert np.array_equal(wk[q].cpu().numpy().view(np.uint32), want.view(np.uint32)), "pulled local model %d" % q
+    print("worker side checked at %.1f s" % (time.time() - t0), flush=True)
+    sd.close()
