@@ -21,7 +21,7 @@
  *    calls that need their results make the caller's stream wait for them.
  *  - The library allocates device memory in slimdp_create, once more when the option
  *    "speculative_pack" is first switched on (slimdp_capture_bytes), and once more on the first
- *    explorer request whose zones are wide (see slimdp_capture_bytes); never otherwise.
+ *    explorer request that needs the large key buffer (see slimdp_capture_bytes); never otherwise.
  *  - Same inputs give the same output bits, whatever the launch geometry.
  *  - Indices are 0-based uint32 (the paper counts from 1); n < 2^32.
  *
@@ -81,8 +81,10 @@ int slimdp_destroy(slimdp_ctx* ctx);
 uint64_t slimdp_workspace_bytes(uint64_t n, uint32_t max_workers, uint32_t n_seg,
                                 const uint64_t* seg_off);
 /* Device bytes that switching option "speculative_pack" on allocates on top; 0 if the arguments are invalid.
- * Explorer requests with wide zones (m at least a quarter of what lies outside the core) allocate once more,
- * 4 * max_workers * (n rounded up to tiles + one tile) bytes, on their first occurrence.  Pure host function. */
+ * Explorer requests whose candidates do not fit the small per-sub-tile slots (m_seg at least a quarter of what lies
+ * outside the core, or segments so small that the candidate zone, about 12 sqrt(m_seg) + 64 words wide, covers more
+ * than a few parameters in a thousand) allocate once more, 4 * max_workers * (n rounded up to tiles + one tile)
+ * bytes, on their first occurrence.  Pure host function. */
 uint64_t slimdp_capture_bytes(uint64_t n, uint32_t max_workers, uint32_t n_seg, const uint64_t* seg_off);
 /* Number of tiles T; 0 if the arguments are invalid.  Pure host function. */
 uint64_t slimdp_num_tiles(uint64_t n, uint32_t n_seg, const uint64_t* seg_off);
