@@ -111,3 +111,41 @@ def test_bench_refuses_more_than_one_gpu_and_models_the_stages():
     sb = bench.stage_bytes(wl.n, wl.W, wl.k, wl.m)
     assert abs(sum(sb.values()) - 13.864e9) < 1e6
     assert sb["score"] == 4 * wl.n * (wl.W + 2)
+
+
+def test_product_path_and_oracle_do_not_know_each_other():
+    """The library's package never imports, names or loads the oracle, and the oracle nothing of the package
+    (the seeded input module is shared by the tests, not by the two sides); only tests, the smoke check and the
+    bench's CPU leg may touch oracle/."""
+    import subprocess
+    import sys
+    pkg = os.path.join(ROOT, "paper_1709_09393_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".h", ".hip", ".c", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(import|from)\s+oracle\b", text, flags=re.M), os.path.join(dirpath, f)
+                assert "slimdp_oracle" not in text and "oracle/" not in text, os.path.join(dirpath, f)
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c", ".h")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_1709_09393_amd" not in text and "slimdp.h" not in text and "libslimdp" not in text, f
+    # importing the package and loading the library pulls in no oracle module
+    code = ("import sys; from paper_1709_09393_amd import binding, workloads; binding.load(); "
+            "assert not [m for m in sys.modules if m == 'oracle' or m.startswith('oracle.')]")
+    subprocess.run([sys.executable, "-c", code], cwd=ROOT, check=True)
+    # bench.py imports the oracle only inside its CPU leg
+    bench_src = open(os.path.join(ROOT, "bench.py")).read()
+    top_level = [l for l in bench_src.splitlines() if re.match(r"(import|from)\s+oracle\b", l)]
+    assert not top_level
+
+
+def test_missing_library_fails_loudly(tmp_path, monkeypatch):
+    """No silent fallback: without the built library the binding raises and names the build step."""
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libslimdp.so"))
+    with pytest.raises(FileNotFoundError) as e:
+        binding.load()
+    assert "build" in str(e.value)
+    with pytest.raises(FileNotFoundError):
+        binding.num_tiles(10)
