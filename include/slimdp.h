@@ -23,7 +23,8 @@
  *    "speculative_pack" is first switched on (slimdp_capture_bytes), and once more on the first
  *    explorer request that needs the large key buffer (see slimdp_capture_bytes); never otherwise.
  *  - Same inputs give the same output bits, whatever the launch geometry.
- *  - Indices are 0-based uint32 (the paper counts from 1); n < 2^32.
+ *  - Indices are 0-based uint32 (the paper counts from 1); n <= SLIMDP_MAX_N = 2^31 (indices and loop counters are
+ *    32-bit and no loop steps by 2^31 or more, so none can wrap).
  *
  * Tiles.  The index range is cut into tiles of at most SLIMDP_TILE consecutive
  * parameters that never cross a segment boundary (flat model: tile t is
@@ -45,6 +46,7 @@ extern "C" {
 #define SLIMDP_TILE 4096u
 #define SLIMDP_MAX_WORKERS 32u
 #define SLIMDP_MAX_SEGMENTS 65536u
+#define SLIMDP_MAX_N (1ull << 31)
 
 enum {
     SLIMDP_OK = 0,

@@ -30,7 +30,7 @@ struct Tiling {
 
 bool valid_shape(uint64_t n, uint32_t n_seg, const uint64_t* seg_off)
 {
-    if (n == 0 || n >= (1ull << 32) || n_seg == 0 || n_seg > SLIMDP_MAX_SEGMENTS || !seg_off) return false;
+    if (n == 0 || n > SLIMDP_MAX_N || n_seg == 0 || n_seg > SLIMDP_MAX_SEGMENTS || !seg_off) return false;
     if (seg_off[0] != 0 || seg_off[n_seg] != n) return false;
     for (uint32_t s = 0; s < n_seg; ++s)
         if (seg_off[s + 1] <= seg_off[s]) return false;
@@ -51,7 +51,7 @@ Tiling make_tiling(uint64_t n, uint32_t n_seg, const uint64_t* seg_off)
         }
     }
     tl.seg_first_tile[n_seg] = (uint32_t)tl.tile_seg.size();
-    tl.tile_start.push_back((uint32_t)n);   // n < 2^32
+    tl.tile_start.push_back((uint32_t)n);   // n <= 2^31
     return tl;
 }
 
@@ -561,7 +561,7 @@ int slimdp_create(slimdp_ctx** out, uint64_t n, uint32_t max_workers, uint32_t n
 {
     if (!out) return fail(nullptr, SLIMDP_ERR_INVALID_ARG, "slimdp_create: out is NULL");
     *out = nullptr;
-    if (n == 0 || n >= (1ull << 32)) return fail(nullptr, SLIMDP_ERR_INVALID_ARG, "slimdp_create: n must be in [1, 2^32)");
+    if (n == 0 || n > SLIMDP_MAX_N) return fail(nullptr, SLIMDP_ERR_INVALID_ARG, "slimdp_create: n must be in [1, 2^31]");
     if (max_workers == 0 || max_workers > SLIMDP_MAX_WORKERS)
         return fail(nullptr, SLIMDP_ERR_INVALID_ARG, "slimdp_create: max_workers must be in [1, %u]", SLIMDP_MAX_WORKERS);
     if (!valid_shape(n, n_seg, seg_off))

@@ -49,6 +49,8 @@ def test_num_tiles_and_workspace_are_pure_host_functions():
     assert binding.num_tiles(10, [0, 5, 5, 10]) == 0        # empty segment
     assert binding.num_tiles(10, [0, 7, 5, 10]) == 0        # not increasing
     assert binding.num_tiles(10, [1, 10]) == 0
+    assert binding.num_tiles(2 ** 31) == 2 ** 31 // 4096      # the largest model
+    assert binding.num_tiles(2 ** 31 + 1) == 0
     assert binding.num_tiles(2 ** 32) == 0
     assert binding.workspace_bytes(10, 0) == 0
     assert binding.workspace_bytes(10, 33) == 0

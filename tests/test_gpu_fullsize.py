@@ -303,3 +303,75 @@ def test_full_size_worker_side_local_steps_and_fused_pack():
         assert np.array_equal(wk[q].cpu().numpy().view(np.uint32), want.view(np.uint32)), "pulled local model %d" % q
     print("worker side checked at %.1f s" % (time.time() - t0), flush=True)
     sd.close()
+
+
+@pytest.mark.parametrize("n", [2 ** 30 - 4089, 2 ** 30 + 12293, 2 ** 31], ids=["below_2_30", "above_2_30", "largest_2_31"])
+def test_sizes_around_the_32_bit_byte_offset_limit(n, capsys):
+    """A flat model just below 2^30 parameters (the largest the pipelined scoring kernel takes: its byte offsets reach
+    2^32 - 16 KB), just above (the general kernels with 64-bit addresses; more than 2^18 tiles), and the largest model
+    the interface takes (2^31 parameters: 8.6 GB per vector), one worker: score,
+    core, explorer, pack and merge against the oracle as in the full-size test above.  Inputs: uniform values with only
+    2^24 levels, so every threshold falls into a group of about a hundred equal keys (ties to the lower index)."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU test selected but torch.cuda.is_available() is False")
+    dev = torch.device("cuda:0")
+    W, it = 1, 5
+    k, m = n // 10, (n - n // 10) // 50
+    t0 = time.time()
+
+    def say(what):
+        with capsys.disabled():
+            print("  [n=%d] %s (%.1f s)" % (n, what, time.time() - t0), flush=True)
+    rng = np.random.default_rng(n)
+    w_h = rng.random(n, dtype=np.float32)
+    w_h -= np.float32(0.5)
+    g_h = rng.random(n, dtype=np.float32)
+    g_h -= np.float32(0.5)
+    g_h *= np.float32(0.01)
+    say("inputs drawn")
+    sd = binding.SlimDP(n, W, seed=workloads.EXPLORE_SEED)
+    sd.set_option("speculative_pack", 1)
+    w = torch.from_numpy(w_h).to(dev)
+    g = [torch.from_numpy(g_h).to(dev)]
+    sd.explore_hint([k], it, [m], 0, W)
+    S = sd.score(w, g, 1.0)
+    core_idx, core_bits, core_off, epoch = sd.select_core(S, [k], reuse_histogram=True)
+    expl_idx, expl_off = sd.sample_explore(core_bits, [k], it, [m], 0, W)
+    core_val, expl_val = sd.pack(g, core_idx, core_off, expl_idx, expl_off, epoch, updates_as_scored=True)
+    sd.merge(w, 0.01, epoch, core_idx, core_off, core_val, expl_idx, expl_off, expl_val)
+    sd.synchronize()
+    say("GPU iteration done")
+
+    def u32(t):
+        return t.cpu().numpy().view(np.uint32)
+    S_o = oracle.score(w_h, [g_h], 1.0)
+    assert np.array_equal(u32(S), S_o.view(np.uint32)), "score bits"
+    del S
+    say("score ok")
+    core_want = exact_top(S_o.view(np.uint32), None, k, largest=True)
+    del S_o
+    assert np.array_equal(u32(core_idx), core_want), "core set"
+    ts = sd.tile_starts()
+    assert np.array_equal(u32(core_off), np.searchsorted(core_want, ts.astype(np.int64)).astype(np.uint32))
+    in_core = np.zeros(n, bool)
+    in_core[core_want] = True
+    bits_want = np.packbits(np.concatenate([in_core, np.zeros((-n) % 32, bool)]).reshape(-1, 32), axis=1,
+                            bitorder="little").view(np.uint32).reshape(-1)
+    assert np.array_equal(u32(core_bits), bits_want), "core bitmap"
+    del bits_want
+    say("core ok")
+    words = oracle.explore_words(workloads.EXPLORE_SEED, it, 0, 0, n)
+    np.logical_not(in_core, out=in_core)
+    want = exact_top(words, in_core, m, largest=False)
+    del words, in_core
+    ei = u32(expl_idx[0])
+    assert np.array_equal(ei, want), "explorer set"
+    assert np.array_equal(u32(expl_off[0]), np.searchsorted(want, ts.astype(np.int64)).astype(np.uint32))
+    say("explorer ok")
+    cv, ev = core_val[0].cpu().numpy(), expl_val[0].cpu().numpy()
+    assert np.array_equal(cv.view(np.uint32), g_h[core_want].view(np.uint32)), "core_val"
+    assert np.array_equal(ev.view(np.uint32), g_h[ei].view(np.uint32)), "expl_val"
+    w_o = oracle.merge(w_h, 0.01, core_want, [cv], [ei], [ev])
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), w_o.view(np.uint32)), "merge bits"
+    say("packs and merge ok")
+    sd.close()
