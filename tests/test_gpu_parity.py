@@ -164,7 +164,7 @@ def test_score_with_several_tiles_per_persistent_block(W):
     sd.close()
 
 
-@pytest.mark.parametrize("W", [1, 2, 3, 8, 16])
+@pytest.mark.parametrize("W", [1, 2, 3, 8, 16, 32])          # 32: the most the interface takes
 def test_worker_counts(W):
     wl = workloads.TINY.scaled(30_011, W=W)
     got, want = run_iteration(wl)
@@ -201,6 +201,18 @@ def test_segments_with_awkward_boundaries():
     wl = workloads.TINY.scaled(n, seg_off=(0, 1, 18, 4114, 4115, 12_307, 29_999, n), n_seg=7)
     got, want = run_iteration(wl)
     assert_iteration_matches(wl, got, want)
+
+
+def test_many_small_segments():
+    """1,500 segments of 1 to 200 parameters (most tiles hold a few dozen parameters, many segments get k = 0 or m = 0):
+    per-segment rankings, the explorer's per-tile tail (such zones are not narrow) and every list's tile offsets."""
+    rng = np.random.default_rng(3)
+    sizes = rng.integers(1, 201, 1500)
+    seg_off = tuple(int(x) for x in np.concatenate([[0], np.cumsum(sizes)]))
+    wl = workloads.TINY.scaled(seg_off[-1], W=2, seg_off=seg_off, n_seg=len(sizes), core_pct=10, explore_pct=20)
+    for hint in (False, True):
+        got, want = run_iteration(wl, hint=hint)
+        assert_iteration_matches(wl, got, want)
 
 
 def test_tie_heavy_stress_recipe_scaled():
