@@ -163,6 +163,7 @@ struct slimdp_ctx {
         uint64_t core_epoch = 0;                // 0: no selection on the captured score yet
     } spec;
     int64_t opt_pack_nbuf = 2;
+    int64_t opt_pack_kernel = 1;           // general pack: 1 = loading and storing waves apart, 0 = one set of waves
     int64_t opt_build_blocks = 4;
     int64_t opt_pack_core_blocks = 0;      // blocks per compute unit of the pack from the capture (0: one per 1024 list entries)
     int64_t opt_core_predict = 1;          // the flat scoring kernel sorts whole tiles against the predicted threshold bin (0: never; 2: test, a wrong bin)          // blocks per compute unit of the core candidate pass
@@ -659,6 +660,7 @@ int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value)
     if (strcmp(name, "pack_core_blocks") == 0 && value >= 0 && value <= 64) { ctx->opt_pack_core_blocks = value; return SLIMDP_OK; }
     if (strcmp(name, "build_blocks") == 0 && value >= 1 && value <= 64) { ctx->opt_build_blocks = value; return SLIMDP_OK; }
     if (strcmp(name, "pack_nbuf") == 0 && (value == 1 || value == 2)) { ctx->opt_pack_nbuf = value; return SLIMDP_OK; }
+    if (strcmp(name, "pack_kernel") == 0 && (value == 0 || value == 1)) { ctx->opt_pack_kernel = value; return SLIMDP_OK; }
     if (strcmp(name, "expected_core") == 0 && value >= -1 && (value < 0 || (uint64_t)value <= ctx->n)) { ctx->opt_expected_core = value; return SLIMDP_OK; }
     if (strcmp(name, "score_pipeline") == 0 && (value == 0 || value == 1)) { ctx->opt_score_pipeline = value; return SLIMDP_OK; }
     if (strcmp(name, "capture_estimate_bias") == 0) { ctx->opt_estimate_bias = value; return SLIMDP_OK; }
@@ -1370,6 +1372,14 @@ int slimdp_pack(slimdp_ctx* ctx, uint32_t n_workers, const float* const* g, cons
     if (rc) return rc;
     int vec_ok = 1;
     for (uint32_t q = 0; q < n_workers; ++q) vec_ok = vec_ok && aligned16(g[q]);
+    if (ctx->opt_pack_kernel == 1) {
+        hipLaunchKernelGGL(k_pack_stream_ws, dim3(8 * ((ctx->T + 7) / 8)), dim3(2 * BLOCK), 0, ctx->stream,
+                           make_tab<PtrTab>(g, n_workers), n_workers, ctx->T, ctx->d_tile_start, core_idx, core_off,
+                           make_tab<PtrTab>(expl_idx, n_workers), make_tab<PtrTab>(expl_off, n_workers),
+                           make_tab<MutPtrTab>(core_val, n_workers), make_tab<MutPtrTab>(expl_val, n_workers), vec_ok);
+        SLIMDP_LAUNCHED(ctx, "k_pack_stream_ws");
+        return SLIMDP_OK;
+    }
     if (ctx->opt_pack_nbuf == 2)
         hipLaunchKernelGGL(k_pack_stream<2>, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, make_tab<PtrTab>(g, n_workers),
                            n_workers, ctx->d_tile_start, core_idx, core_off, make_tab<PtrTab>(expl_idx, n_workers),

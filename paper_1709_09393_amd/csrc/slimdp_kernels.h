@@ -2401,8 +2401,11 @@ __global__ __launch_bounds__(BLOCK) void k_pack_stream(PtrTab g, uint32_t nw, co
                 r[j] = (e < len) ? src[e] : 0.0f;
             }
         }
+        // the index itself: anything computed from it here would make the wave wait for this load, and with it for the
+        // tile requested just before, on the spot
         const uint32_t j = elo[q] + threadIdx.x;
-        epos = (j < ehi[q]) ? static_cast<const uint32_t*>(expl_idx.p[q])[j] - start : 0xFFFFFFFFu;
+        epos = 0xFFFFFFFFu;
+        if (j < ehi[q]) epos = static_cast<const uint32_t*>(expl_idx.p[q])[j];
     };
     fetch(0);
     for (uint32_t q = 0; q < nw; ++q) {
@@ -2416,7 +2419,7 @@ __global__ __launch_bounds__(BLOCK) void k_pack_stream(PtrTab g, uint32_t nw, co
 #pragma unroll
             for (int j = 0; j < EPT; ++j) b[elem_scl(j)] = r[j];
         }
-        const uint32_t my_epos = epos;
+        const uint32_t my_epos = epos - start;      // no entry: wraps to a position beyond any tile (start + len < 2^32)
         __syncthreads();     // with two buffers this also orders a buffer's readers (two workers ago) before its writers
         if (q + 1 < nw) fetch(q + 1);
         float* cv = static_cast<float*>(core_val.p[q]);
@@ -2432,6 +2435,104 @@ __global__ __launch_bounds__(BLOCK) void k_pack_stream(PtrTab g, uint32_t nw, co
             for (uint32_t j = e0 + BLOCK + threadIdx.x; j < e1; j += BLOCK) {
                 const uint32_t pos = ei[j] - start;
                 if (pos < len) ev[j] = b[pos];
+            }
+        }
+    }
+}
+
+// The same pack with the two halves of the work in different waves (512 threads: waves 0..3 load, waves 4..7 store).
+// A wave's vector-memory operations retire in issue order, so a wave that stores a worker's slices and then needs the
+// next worker's tile waits for its own stores to be acknowledged by the cache, every step; here the loading waves never
+// store and the storing waves never load from memory: the tile of updates, the core positions and the explorer
+// positions all reach them through LDS.  Consecutive tiles go to the same die (blocks are dealt to the eight dies in
+// turn), so that the partial lines at the two ends of a tile's output slices meet their other halves in one L2.
+// grid: 8 * ceil(T / 8) blocks.
+__global__ __launch_bounds__(2 * BLOCK) void k_pack_stream_ws(PtrTab g, uint32_t nw, uint32_t T,
+                                                               const uint32_t* __restrict__ tile_start,
+                                                               const uint32_t* __restrict__ core_idx,
+                                                               const uint32_t* __restrict__ core_off, PtrTab expl_idx,
+                                                               PtrTab expl_off, MutPtrTab core_val, MutPtrTab expl_val, int vec_ok)
+{
+    __shared__ float buf[2][TILE];
+    __shared__ uint16_t cpos[TILE];          // the tile's core positions: the same for every worker
+    __shared__ uint32_t epos[2][BLOCK];      // the first BLOCK explorer positions of the worker whose tile is in buf[.]
+    __shared__ uint32_t elo[MAXW], ehi[MAXW];
+    const uint32_t chunk = gridDim.x >> 3;
+    const uint32_t t = (blockIdx.x & 7u) * chunk + (blockIdx.x >> 3);
+    if (t >= T) return;                      // uniform over the block
+    const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
+    const bool vec = vec_ok && len == TILE && (start & 3u) == 0;
+    const uint32_t c0 = core_off[t], c1 = core_off[t + 1];
+    const uint32_t ccnt = (c1 - c0 < TILE) ? c1 - c0 : TILE;
+    const bool loader = threadIdx.x < BLOCK;
+    const uint32_t tid = threadIdx.x & (BLOCK - 1u);
+    if (threadIdx.x < nw) {
+        const uint32_t* eo = static_cast<const uint32_t*>(expl_off.p[threadIdx.x]);
+        elo[threadIdx.x] = eo[t];
+        ehi[threadIdx.x] = eo[t + 1];
+    }
+    for (uint32_t x = threadIdx.x; x < ccnt; x += 2 * BLOCK) {
+        const uint32_t pos = core_idx[c0 + x] - start;
+        cpos[x] = (pos < len) ? (uint16_t)pos : (uint16_t)0xFFFF;
+    }
+    __syncthreads();
+    float r[EPT];
+    uint32_t ep = 0xFFFFFFFFu;
+    auto fetch = [&](uint32_t q) {
+        const float* src = static_cast<const float*>(g.p[q]) + start;
+        if (vec) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float4 v = ld4<NT_PACKS>(src + k * 1024 + tid * 4);
+                r[4 * k + 0] = v.x; r[4 * k + 1] = v.y; r[4 * k + 2] = v.z; r[4 * k + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < EPT; ++j) {
+                const uint32_t e = (uint32_t)j * BLOCK + tid;
+                r[j] = (e < len) ? src[e] : 0.0f;
+            }
+        }
+        // the index itself: anything computed from it here would make the wave wait for this load, and with it for the
+        // tile requested just before, on the spot
+        const uint32_t j = elo[q] + tid;
+        ep = 0xFFFFFFFFu;
+        if (j < ehi[q]) ep = static_cast<const uint32_t*>(expl_idx.p[q])[j];
+    };
+    if (loader) fetch(0);
+    for (uint32_t q = 0; q < nw; ++q) {
+        float* b = buf[q & 1u];
+        if (loader) {
+            if (vec) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    *reinterpret_cast<float4*>(b + k * 1024 + tid * 4) = make_float4(r[4 * k], r[4 * k + 1], r[4 * k + 2], r[4 * k + 3]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < EPT; ++j) b[(uint32_t)j * BLOCK + tid] = r[j];
+            }
+            epos[q & 1u][tid] = ep - start;       // no entry: wraps to a position beyond any tile (start + len < 2^32)
+            if (q + 1 < nw) fetch(q + 1);
+        }
+        // the tile of worker q is in LDS; the storing waves are done with the buffer it replaced (worker q - 2): they
+        // passed the previous barrier only after issuing its last LDS reads, and LDS operations of a wave finish in order
+        __syncthreads();
+        if (!loader) {
+            float* cv = static_cast<float*>(core_val.p[q]);
+            for (uint32_t x = tid; x < ccnt; x += BLOCK) {
+                const uint32_t pos = cpos[x];
+                if (pos != 0xFFFFu) cv[c0 + x] = b[pos];
+            }
+            float* ev = static_cast<float*>(expl_val.p[q]);
+            const uint32_t e0 = elo[q], e1 = ehi[q];
+            const uint32_t my = epos[q & 1u][tid];
+            if (my < len) ev[e0 + tid] = b[my];
+            if (e1 - e0 > BLOCK) {               // dense explorers: the rest of the slice, positions loaded here
+                const uint32_t* ei = static_cast<const uint32_t*>(expl_idx.p[q]);
+                for (uint32_t j = e0 + BLOCK + tid; j < e1; j += BLOCK) {
+                    const uint32_t pos = ei[j] - start;
+                    if (pos < len) ev[j] = b[pos];
+                }
             }
         }
     }
@@ -2768,8 +2869,11 @@ __global__ __launch_bounds__(BLOCK) void k_local_step_pack(MutPtrTab w_local, Pt
                 rd[j] = (e < len && !first) ? d[e] : 0.0f;
             }
         }
+        // the index itself: anything computed from it here would make the wave wait for this load, and with it for the
+        // tile requested just before, on the spot
         const uint32_t j = elo[q] + threadIdx.x;
-        epos = (j < ehi[q]) ? static_cast<const uint32_t*>(expl_idx.p[q])[j] - start : 0xFFFFFFFFu;
+        epos = 0xFFFFFFFFu;
+        if (j < ehi[q]) epos = static_cast<const uint32_t*>(expl_idx.p[q])[j];
     };
     fetch(0);
     for (uint32_t q = 0; q < nw; ++q) {
@@ -2799,7 +2903,7 @@ __global__ __launch_bounds__(BLOCK) void k_local_step_pack(MutPtrTab w_local, Pt
                 b[e] = rd[j];
             }
         }
-        const uint32_t my_epos = epos;
+        const uint32_t my_epos = epos - start;      // no entry: wraps to a position beyond any tile (start + len < 2^32)
         __syncthreads();     // with two buffers this also orders a buffer's readers (two workers ago) before its writers
         if (q + 1 < nw) fetch(q + 1);
         float* cv = static_cast<float*>(core_val.p[q]);

@@ -203,6 +203,23 @@ def test_segments_with_awkward_boundaries():
     assert_iteration_matches(wl, got, want)
 
 
+@pytest.mark.parametrize("pack_kernel,nbuf", [(1, 2), (0, 1), (0, 2)])
+def test_general_pack_kernels(pack_kernel, nbuf):
+    """The pack that scans the update vectors, in its forms (loading and storing waves apart; one set of waves with
+    one or two tiles in LDS): flat with a ragged last tile and three workers, segmented, and an explorer so full that
+    a tile holds more of its entries than a block has threads."""
+    cases = [workloads.TINY.scaled(200_003, W=3), workloads.GOOGLENET.scaled(300_001),
+             workloads.TINY.scaled(50_000, W=2, core_pct=5, explore_pct=40), workloads.TINY.scaled(5, W=1)]
+    for wl in cases:
+        seg_off = [int(x) for x in wl.segment_offsets()]
+        sd = binding.SlimDP(wl.n, wl.W, seg_off=seg_off, seed=workloads.EXPLORE_SEED)
+        sd.set_option("pack_kernel", pack_kernel)
+        sd.set_option("pack_nbuf", nbuf)
+        got, want = run_iteration(wl, sd=sd, as_scored=False)
+        assert_iteration_matches(wl, got, want)
+        sd.close()
+
+
 def test_many_small_segments():
     """1,500 segments of 1 to 200 parameters (most tiles hold a few dozen parameters, many segments get k = 0 or m = 0):
     per-segment rankings, the explorer's per-tile tail (such zones are not narrow) and every list's tile offsets."""
