@@ -413,6 +413,10 @@ def main() -> int:
                                         expl_val=b.expl_val), reps)
         pull_ms = timed(lambda r: sd.pull(w, epoch2, b.core_idx, b.core_off, b.expl_idx, b.expl_off, w_local=w_local,
                                           core_out=b.core_val, expl_out=b.expl_val), reps)
+        # pull, local merge and the first local step of the next round in one pass, against the two calls it replaces
+        pls_ms = timed(lambda r: sd.pull_local_step(w, epoch2, b.core_idx, b.core_off, b.expl_idx, b.expl_off, w_local, g,
+                                                    delta, 0.01, first=True), reps)
+        ls1_ms = timed(lambda r: sd.local_step(w_local, g, delta, 0.01, first=True), reps)
         del w_local, delta
         codes = sd.quantize(b.core_val, 0, 0)
         codes_e = sd.quantize(b.expl_val, 1, 0)
@@ -433,6 +437,9 @@ def main() -> int:
                                                 "algorithmic_bytes": 20 * n * W + sb["pack"] - 4 * n * W,
                                                 "hbm_frac": frac(20 * n * W + sb["pack"] - 4 * n * W, lsp_ms)},
             "pull_with_local_overwrite": {"ms": pull_ms},
+            "pull_and_first_local_step_in_one_pass": {"ms": pls_ms, "two_calls_ms": pull_ms + ls1_ms,
+                                                      "algorithmic_bytes": 16 * n * W + 4 * n,
+                                                      "hbm_frac": frac(16 * n * W + 4 * n, pls_ms)},
             "quantize": {"ms": q_ms, "algorithmic_bytes": 5 * nvals, "hbm_frac": frac(5 * nvals, q_ms)},
             "dequantize": {"ms": dq_ms, "algorithmic_bytes": 5 * nvals, "hbm_frac": frac(5 * nvals, dq_ms)},
             "wire_bytes_per_worker": {"plain": binding.wire_bytes(k, m, False), "quantized": binding.wire_bytes(k, m, True),

@@ -329,6 +329,20 @@ int slimdp_local_step_pack(slimdp_ctx* ctx, uint32_t n_workers, float* const* w_
                            const uint32_t* const* expl_off, const uint64_t* m_w, float* const* core_val,
                            float* const* expl_val, uint64_t core_epoch);
 
+/* Pull, local Merge and the first LocalTrain step of the next round in one pass (section 3.3 steps 4 and 5, then step 1):
+ * every worker's local model is overwritten with the global one at its communication set, then stepped.  Same
+ * results, bit for bit, as
+ *     slimdp_pull(ctx, w, core_epoch, n_workers, core_idx, ..., w_local)      (its value outputs aside) followed by
+ *     slimdp_local_step(ctx, n_workers, w_local, grad, delta, eta, flags),
+ * but the local models are streamed once instead of being patched by scattered writes and then streamed.
+ *   w [dev, n] the global model after the merge; lists as in slimdp_pull; w_local, grad, delta, eta, flags as in
+ *   slimdp_local_step (SLIMDP_LOCAL_FIRST is the usual case: a new accumulation starts after a communication). */
+int slimdp_pull_local_step(slimdp_ctx* ctx, const float* w, uint64_t core_epoch, uint32_t n_workers,
+                           const uint32_t* core_idx, const uint32_t* core_off, uint64_t k,
+                           const uint32_t* const* expl_idx, const uint32_t* const* expl_off, const uint64_t* m_w,
+                           float* const* w_local, const float* const* grad, float* const* delta, float eta,
+                           uint32_t flags);
+
 /* Quantised wire values: the method composes with gradient quantisation (section 2.2, last sentences); the
  * comparison of section 4.2 uses random quantisation with 8 bits and buckets of 512, after Alistarh et al. (QSGD).
  * Applied to the packed values of workers worker0 .. worker0+n_workers-1 (kind 0: core_val, kind 1: expl_val):

@@ -35,7 +35,7 @@ EXPORTS = [
     "slimdp_tile_starts", "slimdp_last_error", "slimdp_synchronize", "slimdp_set_option",
     "slimdp_score", "slimdp_dense_update_score", "slimdp_select_core", "slimdp_sample_explore", "slimdp_explore_hint", "slimdp_tile_offsets",
     "slimdp_pack", "slimdp_merge", "slimdp_pull", "slimdp_core_signature", "slimdp_debug_philox",
-    "slimdp_select_core_static", "slimdp_import_core", "slimdp_local_step", "slimdp_local_step_pack", "slimdp_quantize",
+    "slimdp_select_core_static", "slimdp_import_core", "slimdp_local_step", "slimdp_local_step_pack", "slimdp_pull_local_step", "slimdp_quantize",
     "slimdp_dequantize",
 ]
 
@@ -113,6 +113,9 @@ def load() -> C.CDLL:
     L.slimdp_local_step_pack.argtypes = [_vp, C.c_uint32, _vpp, _vpp, _vpp, C.c_float, C.c_uint32, _vp, _vp, C.c_uint64, _vpp,
                                          _vpp, _u64p, _vpp, _vpp, C.c_uint64]
     L.slimdp_local_step_pack.restype = C.c_int
+    L.slimdp_pull_local_step.argtypes = [_vp, _vp, C.c_uint64, C.c_uint32, _vp, _vp, C.c_uint64, _vpp, _vpp, _u64p, _vpp, _vpp,
+                                         _vpp, C.c_float, C.c_uint32]
+    L.slimdp_pull_local_step.restype = C.c_int
     L.slimdp_quantize.argtypes = [_vp, C.c_uint32, C.c_uint32, _vpp, _u64p, C.c_uint32, C.c_uint64, _vpp, _vpp]
     L.slimdp_quantize.restype = C.c_int
     L.slimdp_dequantize.argtypes = [_vp, C.c_uint32, _vpp, _vpp, _u64p, _vpp]
@@ -374,6 +377,15 @@ class SlimDP:
                                                    _table(expl_idx), _table(expl_off), mw, _table(core_val),
                                                    _table(expl_val), int(core_epoch)))
         return core_val, expl_val
+
+    def pull_local_step(self, w, core_epoch: int, core_idx, core_off, expl_idx: Sequence, expl_off: Sequence,
+                        w_local: Sequence, grad: Sequence, delta: Sequence, eta: float, first: bool = True) -> None:
+        """pull(..., w_local=w_local) (its value outputs aside) and local_step() in one pass over the local models."""
+        nw = len(w_local)
+        mw = _u64arr([expl_idx[q].numel() for q in range(nw)])
+        self._check(self._L.slimdp_pull_local_step(self._h, _ptr(w), int(core_epoch), nw, _ptr(core_idx), _ptr(core_off),
+                                                   core_idx.numel(), _table(expl_idx), _table(expl_off), mw, _table(w_local),
+                                                   _table(grad), _table(delta), C.c_float(eta), LOCAL_FIRST if first else 0))
 
     def quantize(self, val: Sequence, kind: int, iteration: int, worker0: int = 0, code=None, scale=None):
         torch = self._torch

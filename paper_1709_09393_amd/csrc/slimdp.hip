@@ -1516,6 +1516,38 @@ int slimdp_local_step_pack(slimdp_ctx* ctx, uint32_t n_workers, float* const* w_
     return SLIMDP_OK;
 }
 
+int slimdp_pull_local_step(slimdp_ctx* ctx, const float* w, uint64_t core_epoch, uint32_t n_workers, const uint32_t* core_idx,
+                           const uint32_t* core_off, uint64_t k, const uint32_t* const* expl_idx,
+                           const uint32_t* const* expl_off, const uint64_t* m_w, float* const* w_local,
+                           const float* const* grad, float* const* delta, float eta, uint32_t flags)
+{
+    if (!ctx) return SLIMDP_ERR_INVALID_ARG;
+    if (!w) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_pull_local_step: w is NULL");
+    if (flags & ~SLIMDP_LOCAL_FIRST) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_pull_local_step: unknown flag bits 0x%x", flags);
+    int rc = check_lists(ctx, "slimdp_pull_local_step", n_workers, core_idx, core_off, k, expl_idx, expl_off, m_w);
+    if (rc) return rc;
+    if (!table_ok(w_local, n_workers) || !table_ok(grad, n_workers) || !table_ok(delta, n_workers))
+        return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_pull_local_step: NULL array");
+    if (!std::isfinite(eta)) return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_pull_local_step: eta must be finite");
+    int vec_ok = aligned16(w);
+    for (uint32_t q = 0; q < n_workers; ++q) {
+        vec_ok = vec_ok && aligned16(w_local[q]) && aligned16(grad[q]) && aligned16(delta[q]);
+        const void *a = w_local[q], *b = grad[q], *c = delta[q];
+        if (a == b || a == c || b == c || a == static_cast<const void*>(w) || c == static_cast<const void*>(w))
+            return fail(ctx, SLIMDP_ERR_INVALID_ARG, "slimdp_pull_local_step: arrays of worker %u alias", q);
+    }
+    rc = check_epoch(ctx, core_epoch);
+    if (rc) return rc;
+    rc = wait_for_lists(ctx, n_workers, expl_idx, expl_off, m_w);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_pull_local_step, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, w, make_tab<MutPtrTab>(w_local, n_workers),
+                       make_tab<PtrTab>(grad, n_workers), make_tab<MutPtrTab>(delta, n_workers), eta,
+                       (int)((flags & SLIMDP_LOCAL_FIRST) != 0), n_workers, ctx->d_tile_start, core_idx, core_off,
+                       make_tab<PtrTab>(expl_idx, n_workers), make_tab<PtrTab>(expl_off, n_workers), vec_ok);
+    SLIMDP_LAUNCHED(ctx, "k_pull_local_step");
+    return SLIMDP_OK;
+}
+
 static int quant_args(slimdp_ctx* ctx, const char* who, uint32_t n_workers, const void* const* a, const void* const* b,
                       const void* const* c, const uint64_t* count, Count64Tab* ct, uint64_t* cmax)
 {

@@ -2925,6 +2925,138 @@ __global__ __launch_bounds__(BLOCK) void k_local_step_pack(MutPtrTab w_local, Pt
 }
 
 // ---------------------------------------------------------------------------------------
+// Pull, local Merge and LocalTrain in one pass (section 3.3 steps 4, 5 and 1 of the next round): the local model
+// is overwritten with the global one at the worker's communication set, then stepped.  The first local step after a
+// communication streams every local model anyway; applying the pulled values there saves the pull its own pass,
+// whose scattered 4-byte writes touch nearly every line of every local model.  Same results as k_gather with a
+// scatter destination followed by k_local_step.  One block per tile: the tile of the global model stays in
+// registers for all workers, the communication set of a worker is a bitmap in LDS (core positions once per tile,
+// explorer positions per worker, marked one worker ahead), the next worker's three tiles travel meanwhile.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_pull_local_step(const float* __restrict__ w, MutPtrTab w_local, PtrTab grad, MutPtrTab delta,
+                                                           float eta, int first, uint32_t nw,
+                                                           const uint32_t* __restrict__ tile_start,
+                                                           const uint32_t* __restrict__ core_idx,
+                                                           const uint32_t* __restrict__ core_off, PtrTab expl_idx, PtrTab expl_off,
+                                                           int vec_ok)
+{
+    __shared__ uint32_t cm[TILE_WORDS];          // core positions of the tile
+    __shared__ uint32_t em[2][TILE_WORDS];       // explorer positions of a worker
+    __shared__ uint32_t elo[MAXW], ehi[MAXW];
+    const uint32_t t = blockIdx.x;
+    const uint32_t start = tile_start[t], len = tile_start[t + 1] - start;
+    const bool vec = vec_ok && len == TILE && (start & 3u) == 0;
+    const uint32_t c0 = core_off[t], c1 = core_off[t + 1];
+    if (threadIdx.x < nw) {
+        const uint32_t* eo = static_cast<const uint32_t*>(expl_off.p[threadIdx.x]);
+        elo[threadIdx.x] = eo[t];
+        ehi[threadIdx.x] = eo[t + 1];
+    }
+    if (threadIdx.x < TILE_WORDS) { cm[threadIdx.x] = 0; em[0][threadIdx.x] = 0; }
+    // this thread's elements of the global model: the same positions as its elements of every local model
+    float wv[EPT];
+    if (vec) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float4 v = ld4<1>(w + (size_t)start + k * 1024 + threadIdx.x * 4);
+            wv[4 * k + 0] = v.x; wv[4 * k + 1] = v.y; wv[4 * k + 2] = v.z; wv[4 * k + 3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            const uint32_t e = elem_scl(j);
+            wv[j] = (e < len) ? w[(size_t)start + e] : 0.0f;
+        }
+    }
+    __syncthreads();
+    for (uint32_t j = c0 + threadIdx.x; j < c1; j += BLOCK) {
+        const uint32_t pos = core_idx[j] - start;
+        if (pos < len) atomicOr(&cm[pos >> 5], 1u << (pos & 31u));
+    }
+    // explorer positions of worker q into em[q & 1] (zeroed before): the first BLOCK entries from the index each
+    // thread already holds (requested a turn ago with the tiles), the rest, if any, read here
+    uint32_t epre = 0xFFFFFFFFu;
+    auto mark = [&](uint32_t q, uint32_t held, uint32_t from) {
+        const uint32_t p0 = held - start;        // no entry: wraps beyond any tile
+        if (p0 < len) atomicOr(&em[q & 1u][p0 >> 5], 1u << (p0 & 31u));
+        const uint32_t* ei = static_cast<const uint32_t*>(expl_idx.p[q]);
+        for (uint32_t j = elo[q] + from + threadIdx.x; j < ehi[q]; j += BLOCK) {
+            const uint32_t pos = ei[j] - start;
+            if (pos < len) atomicOr(&em[q & 1u][pos >> 5], 1u << (pos & 31u));
+        }
+    };
+    float rg[EPT], rl[EPT], rd[EPT];
+    auto fetch = [&](uint32_t q) {
+        const float* g = static_cast<const float*>(grad.p[q]) + start;
+        const float* l = static_cast<const float*>(w_local.p[q]) + start;
+        const float* d = static_cast<const float*>(delta.p[q]) + start;
+        if (vec) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t o = k * 1024 + threadIdx.x * 4;
+                const float4 a = ld4<1>(g + o), b = ld4<1>(l + o);
+                rg[4 * k + 0] = a.x; rg[4 * k + 1] = a.y; rg[4 * k + 2] = a.z; rg[4 * k + 3] = a.w;
+                rl[4 * k + 0] = b.x; rl[4 * k + 1] = b.y; rl[4 * k + 2] = b.z; rl[4 * k + 3] = b.w;
+                if (!first) {
+                    const float4 c = ld4<1>(d + o);
+                    rd[4 * k + 0] = c.x; rd[4 * k + 1] = c.y; rd[4 * k + 2] = c.z; rd[4 * k + 3] = c.w;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < EPT; ++j) {
+                const uint32_t e = elem_scl(j);
+                rg[j] = (e < len) ? g[e] : 0.0f;
+                rl[j] = (e < len) ? l[e] : 0.0f;
+                rd[j] = (e < len && !first) ? d[e] : 0.0f;
+            }
+        }
+        // this thread's explorer index of the worker after: held, not used, until that worker's marks are made
+        epre = 0xFFFFFFFFu;
+        if (q + 1 < nw) {
+            const uint32_t j = elo[q + 1] + threadIdx.x;
+            if (j < ehi[q + 1]) epre = static_cast<const uint32_t*>(expl_idx.p[q + 1])[j];
+        }
+    };
+    mark(0, 0xFFFFFFFFu, 0u);
+    fetch(0);
+    for (uint32_t q = 0; q < nw; ++q) {
+        // the marks of worker q (made a turn ago) are complete; the other bitmap is free (its reader finished a turn ago)
+        __syncthreads();
+        if (threadIdx.x < TILE_WORDS) em[(q + 1u) & 1u][threadIdx.x] = 0;
+        float nl[EPT], nd[EPT];
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            const uint32_t e = vec ? elem_vec(j) : elem_scl(j);
+            const uint32_t bit = ((cm[e >> 5] | em[q & 1u][e >> 5]) >> (e & 31u)) & 1u;
+            const float base = bit ? wv[j] : rl[j];                  // steps 4, 5: the pulled value replaces the local one
+            nl[j] = __builtin_fmaf(-eta, rg[j], base);               // step 1 of the next round
+            nd[j] = first ? rg[j] : rd[j] + rg[j];
+        }
+        float* l = static_cast<float*>(w_local.p[q]) + start;
+        float* d = static_cast<float*>(delta.p[q]) + start;
+        __syncthreads();                         // the other bitmap is zero everywhere before the next worker's marks go in
+        // the next worker's marks and tiles, requested before this worker's stores: the wait for them need not cover the
+        // stores' acknowledgements
+        if (q + 1 < nw) { mark(q + 1, epre, BLOCK); fetch(q + 1); }
+        if (vec) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t o = k * 1024 + threadIdx.x * 4;
+                st4<1>(l + o, make_float4(nl[4 * k], nl[4 * k + 1], nl[4 * k + 2], nl[4 * k + 3]));
+                st4<1>(d + o, make_float4(nd[4 * k], nd[4 * k + 1], nd[4 * k + 2], nd[4 * k + 3]));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < EPT; ++j) {
+                const uint32_t e = elem_scl(j);
+                if (e < len) { l[e] = nl[j]; d[e] = nd[j]; }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Quantised wire values (section 2.2, last sentences; section 4.2: random quantisation, 8 bits,
 // buckets of 512).  Per bucket of QB consecutive list entries: scale = largest magnitude;
 // per value: code = sign bit | level, level = floor(y) + (u < y - floor(y)), y = (|v| / scale) * 127

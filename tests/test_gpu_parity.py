@@ -1064,6 +1064,58 @@ def test_local_step_and_pack_in_one_pass(n, W, segmented, shift, nbuf):
     sd.close()
 
 
+@pytest.mark.parametrize("n,W,segmented,shift,explore_pct", [(5, 1, False, 0, 2), (4097, 3, False, 0, 2), (200_003, 8, False, 0, 2),
+                                                               (300_001, 4, True, 0, 2), (70_000, 2, False, 1, 2),
+                                                               (50_000, 2, False, 0, 40)])
+def test_pull_and_local_step_in_one_pass(n, W, segmented, shift, explore_pct):
+    """Pull, local merge and the first local step of the next round together: the same local models and accumulated
+    updates as the oracle's pull (with local overwrite) followed by its local step, starting a new accumulation and
+    continuing one; flat and segmented, ragged tiles, arrays without 16-byte alignment, an explorer so full that a tile
+    holds more of its entries than a block has threads, an explorer request still running on the side stream."""
+    wl = (workloads.GOOGLENET if segmented else workloads.TINY).scaled(n, W=W, explore_pct=explore_pct)
+    seg_off = [int(x) for x in wl.segment_offsets()]
+    ks, ms = [int(x) for x in wl.k_seg()], [int(x) for x in wl.m_seg()]
+    so = None if wl.n_seg == 1 and wl.seg_off is None else seg_off
+    rng = np.random.default_rng(n + 7 * W)
+    sd = binding.SlimDP(n, W, seg_off=seg_off, seed=workloads.EXPLORE_SEED)
+    sd.set_option("explore_async", 1)
+    eta = 0.05
+
+    def dev_arr(a):
+        buf = torch.full((n + shift,), float("nan"), dtype=torch.float32, device=dev())
+        buf[shift:] = torch.from_numpy(a)
+        return buf[shift:]
+    w_h = wl.weights()
+    w = dev_arr(w_h)
+    core_idx, core_bits, core_off, epoch = sd.select_core(to_dev(np.abs(w_h)), ks)
+    core_o = oracle.select_core(np.abs(w_h), ks, so)
+    wk_h = [rng.standard_normal(n).astype(np.float32) for _ in range(W)]
+    wk = [dev_arr(x) for x in wk_h]
+    d = [dev_arr(np.full(n, np.nan, np.float32)) for _ in range(W)]
+    d_h = [None] * W
+    for t, first in enumerate([True, False]):
+        expl_idx, expl_off = sd.sample_explore(core_bits, ks, t, ms, 0, W)        # asynchronous: the call below waits for it
+        g_h = [(rng.standard_normal(n) * 10.0 ** rng.integers(-4, 3, n)).astype(np.float32) for _ in range(W)]
+        g = [dev_arr(x) for x in g_h]
+        sd.pull_local_step(w, epoch, core_idx, core_off, expl_idx, expl_off, wk, g, d, eta, first=first)
+        sd.synchronize()
+        for q in range(W):
+            ei_o = oracle.sample_explore(n, core_o, workloads.EXPLORE_SEED, t, q, ms, so)
+            assert np.array_equal(u32(expl_idx[q]), ei_o), (t, q)
+            _, _, pulled = oracle.pull(w_h, core_o, ei_o, wk_h[q])
+            wk_h[q], d_h[q] = oracle.local_step(pulled, None if first else d_h[q], g_h[q], eta)
+            assert np.array_equal(f32bits(wk[q].cpu().numpy()), f32bits(wk_h[q])), (t, q)
+            assert np.array_equal(f32bits(d[q].cpu().numpy()), f32bits(d_h[q])), (t, q)
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.pull_local_step(w, epoch + 1, core_idx, core_off, expl_idx, expl_off, wk, g, d, eta)
+    assert e.value.code == binding.ERR_STALE_CORE
+    with pytest.raises(binding.SlimDPError) as e:
+        sd.pull_local_step(w, epoch, core_idx, core_off, expl_idx, expl_off, wk, wk, d, eta)
+    assert e.value.code == binding.ERR_INVALID_ARG
+    sd.synchronize()
+    sd.close()
+
+
 def test_worker_loop_closure_local_models_diverge_and_are_pulled_back():
     """W local models carried through the loop of algorithm 1's worker side: p = 2 local mini-batch steps accumulate
     delta_k, the communication set of delta_k is pushed and merged, the worker pulls the global values at its
