@@ -133,6 +133,8 @@ int slimdp_synchronize(slimdp_ctx* ctx);
  *       iteration t+1 can be issued before the pack of iteration t (other output arrays) and then runs beside pack
  *       and merge.
  *   "side_blocks" (1..8): blocks per compute unit of a side-stream draw.
+ *   "pull_kernel" (0/1, default 1): how slimdp_pull patches local models (1: a pass that streams them; 0: scattered
+ *       writes); results do not depend on it.
  *   "pack_kernel" (0/1, default 1), "pack_nbuf" (1/2): which form of the general pack kernel runs (1: loading and
  *       storing waves apart; 0: one set of waves, with pack_nbuf tiles in LDS); results do not depend on them.
  *   "explore_force_fallback" (0/1/2), "explore_per_tile_tail" (0/1): test switches: make

@@ -164,6 +164,7 @@ struct slimdp_ctx {
     } spec;
     int64_t opt_pack_nbuf = 2;
     int64_t opt_pack_kernel = 1;           // general pack: 1 = loading and storing waves apart, 0 = one set of waves
+    int64_t opt_pull_kernel = 1;           // local overwrite of a pull: 1 = a pass that streams the local models, 0 = scattered writes
     int64_t opt_build_blocks = 4;
     int64_t opt_pack_core_blocks = 0;      // blocks per compute unit of the pack from the capture (0: one per 1024 list entries)
     int64_t opt_core_predict = 1;          // the flat scoring kernel sorts whole tiles against the predicted threshold bin (0: never; 2: test, a wrong bin)          // blocks per compute unit of the core candidate pass
@@ -661,6 +662,7 @@ int slimdp_set_option(slimdp_ctx* ctx, const char* name, int64_t value)
     if (strcmp(name, "build_blocks") == 0 && value >= 1 && value <= 64) { ctx->opt_build_blocks = value; return SLIMDP_OK; }
     if (strcmp(name, "pack_nbuf") == 0 && (value == 1 || value == 2)) { ctx->opt_pack_nbuf = value; return SLIMDP_OK; }
     if (strcmp(name, "pack_kernel") == 0 && (value == 0 || value == 1)) { ctx->opt_pack_kernel = value; return SLIMDP_OK; }
+    if (strcmp(name, "pull_kernel") == 0 && (value == 0 || value == 1)) { ctx->opt_pull_kernel = value; return SLIMDP_OK; }
     if (strcmp(name, "expected_core") == 0 && value >= -1 && (value < 0 || (uint64_t)value <= ctx->n)) { ctx->opt_expected_core = value; return SLIMDP_OK; }
     if (strcmp(name, "score_pipeline") == 0 && (value == 0 || value == 1)) { ctx->opt_score_pipeline = value; return SLIMDP_OK; }
     if (strcmp(name, "capture_estimate_bias") == 0) { ctx->opt_estimate_bias = value; return SLIMDP_OK; }
@@ -1436,11 +1438,24 @@ int slimdp_pull(slimdp_ctx* ctx, const float* w, uint64_t core_epoch, uint32_t n
     rc = wait_for_lists(ctx, n_workers, expl_idx, expl_off, m_w);
     if (rc) return rc;
     const float* src = w;
+    bool any_local = false;
+    for (uint32_t q = 0; w_local && q < n_workers; ++q) any_local = any_local || w_local[q] != nullptr;
+    // the values at the communication sets; the local models are patched by a pass of their own that streams them (a
+    // scattered 4-byte write per value would touch nearly every line of every local model, at a fraction of the rate)
     hipLaunchKernelGGL(k_gather, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, make_tab<PtrTab, const float*>(&src, 1), 1,
                        n_workers, ctx->n, core_idx, core_off, make_tab<PtrTab>(expl_idx, n_workers),
                        make_tab<PtrTab>(expl_off, n_workers), make_tab<MutPtrTab>(core_out, n_workers),
-                       make_tab<MutPtrTab>(expl_out, n_workers), make_tab<MutPtrTab>(w_local, w_local ? n_workers : 0));
+                       make_tab<MutPtrTab>(expl_out, n_workers),
+                       make_tab<MutPtrTab>(w_local, (w_local && ctx->opt_pull_kernel == 0) ? n_workers : 0));
     SLIMDP_LAUNCHED(ctx, "k_gather(pull)");
+    if (any_local && ctx->opt_pull_kernel == 1) {
+        int vec_ok = aligned16(w);
+        for (uint32_t q = 0; q < n_workers; ++q) vec_ok = vec_ok && (!w_local[q] || aligned16(w_local[q]));
+        hipLaunchKernelGGL(k_pull_local_step<0>, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, w,
+                           make_tab<MutPtrTab>(w_local, n_workers), PtrTab{}, MutPtrTab{}, 0.0f, 1, n_workers, ctx->d_tile_start,
+                           core_idx, core_off, make_tab<PtrTab>(expl_idx, n_workers), make_tab<PtrTab>(expl_off, n_workers), vec_ok);
+        SLIMDP_LAUNCHED(ctx, "k_pull_local_step<0>");
+    }
     return SLIMDP_OK;
 }
 
@@ -1540,7 +1555,7 @@ int slimdp_pull_local_step(slimdp_ctx* ctx, const float* w, uint64_t core_epoch,
     if (rc) return rc;
     rc = wait_for_lists(ctx, n_workers, expl_idx, expl_off, m_w);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_pull_local_step, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, w, make_tab<MutPtrTab>(w_local, n_workers),
+    hipLaunchKernelGGL(k_pull_local_step<1>, dim3(ctx->T), dim3(BLOCK), 0, ctx->stream, w, make_tab<MutPtrTab>(w_local, n_workers),
                        make_tab<PtrTab>(grad, n_workers), make_tab<MutPtrTab>(delta, n_workers), eta,
                        (int)((flags & SLIMDP_LOCAL_FIRST) != 0), n_workers, ctx->d_tile_start, core_idx, core_off,
                        make_tab<PtrTab>(expl_idx, n_workers), make_tab<PtrTab>(expl_off, n_workers), vec_ok);

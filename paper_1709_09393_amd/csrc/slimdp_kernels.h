@@ -2929,10 +2929,12 @@ __global__ __launch_bounds__(BLOCK) void k_local_step_pack(MutPtrTab w_local, Pt
 // is overwritten with the global one at the worker's communication set, then stepped.  The first local step after a
 // communication streams every local model anyway; applying the pulled values there saves the pull its own pass,
 // whose scattered 4-byte writes touch nearly every line of every local model.  Same results as k_gather with a
-// scatter destination followed by k_local_step.  One block per tile: the tile of the global model stays in
+// scatter destination followed by k_local_step.  STEP = 0: the overwrite alone (the write half of a pull with local
+// models: workers without one are skipped).  One block per tile: the tile of the global model stays in
 // registers for all workers, the communication set of a worker is a bitmap in LDS (core positions once per tile,
 // explorer positions per worker, marked one worker ahead), the next worker's three tiles travel meanwhile.
 // ---------------------------------------------------------------------------------------
+template <int STEP>
 __global__ __launch_bounds__(BLOCK) void k_pull_local_step(const float* __restrict__ w, MutPtrTab w_local, PtrTab grad, MutPtrTab delta,
                                                            float eta, int first, uint32_t nw,
                                                            const uint32_t* __restrict__ tile_start,
@@ -2987,17 +2989,22 @@ __global__ __launch_bounds__(BLOCK) void k_pull_local_step(const float* __restri
     };
     float rg[EPT], rl[EPT], rd[EPT];
     auto fetch = [&](uint32_t q) {
-        const float* g = static_cast<const float*>(grad.p[q]) + start;
+        const float* g = STEP ? static_cast<const float*>(grad.p[q]) + start : nullptr;
         const float* l = static_cast<const float*>(w_local.p[q]) + start;
-        const float* d = static_cast<const float*>(delta.p[q]) + start;
-        if (vec) {
+        const float* d = STEP ? static_cast<const float*>(delta.p[q]) + start : nullptr;
+        if (!STEP && !w_local.p[q]) {
+            // a worker without a local model to patch (uniform over the block)
+        } else if (vec) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const uint32_t o = k * 1024 + threadIdx.x * 4;
-                const float4 a = ld4<1>(g + o), b = ld4<1>(l + o);
-                rg[4 * k + 0] = a.x; rg[4 * k + 1] = a.y; rg[4 * k + 2] = a.z; rg[4 * k + 3] = a.w;
+                const float4 b = ld4<1>(l + o);
                 rl[4 * k + 0] = b.x; rl[4 * k + 1] = b.y; rl[4 * k + 2] = b.z; rl[4 * k + 3] = b.w;
-                if (!first) {
+                if (STEP) {
+                    const float4 a = ld4<1>(g + o);
+                    rg[4 * k + 0] = a.x; rg[4 * k + 1] = a.y; rg[4 * k + 2] = a.z; rg[4 * k + 3] = a.w;
+                }
+                if (STEP && !first) {
                     const float4 c = ld4<1>(d + o);
                     rd[4 * k + 0] = c.x; rd[4 * k + 1] = c.y; rd[4 * k + 2] = c.z; rd[4 * k + 3] = c.w;
                 }
@@ -3006,9 +3013,9 @@ __global__ __launch_bounds__(BLOCK) void k_pull_local_step(const float* __restri
 #pragma unroll
             for (int j = 0; j < EPT; ++j) {
                 const uint32_t e = elem_scl(j);
-                rg[j] = (e < len) ? g[e] : 0.0f;
+                rg[j] = (STEP && e < len) ? g[e] : 0.0f;
                 rl[j] = (e < len) ? l[e] : 0.0f;
-                rd[j] = (e < len && !first) ? d[e] : 0.0f;
+                rd[j] = (STEP && e < len && !first) ? d[e] : 0.0f;
             }
         }
         // this thread's explorer index of the worker after: held, not used, until that worker's marks are made
@@ -3030,27 +3037,29 @@ __global__ __launch_bounds__(BLOCK) void k_pull_local_step(const float* __restri
             const uint32_t e = vec ? elem_vec(j) : elem_scl(j);
             const uint32_t bit = ((cm[e >> 5] | em[q & 1u][e >> 5]) >> (e & 31u)) & 1u;
             const float base = bit ? wv[j] : rl[j];                  // steps 4, 5: the pulled value replaces the local one
-            nl[j] = __builtin_fmaf(-eta, rg[j], base);               // step 1 of the next round
+            nl[j] = STEP ? __builtin_fmaf(-eta, rg[j], base) : base; // step 1 of the next round
             nd[j] = first ? rg[j] : rd[j] + rg[j];
         }
+        const bool patch = STEP || w_local.p[q] != nullptr;          // uniform over the block
         float* l = static_cast<float*>(w_local.p[q]) + start;
-        float* d = static_cast<float*>(delta.p[q]) + start;
+        float* d = STEP ? static_cast<float*>(delta.p[q]) + start : nullptr;
         __syncthreads();                         // the other bitmap is zero everywhere before the next worker's marks go in
         // the next worker's marks and tiles, requested before this worker's stores: the wait for them need not cover the
         // stores' acknowledgements
         if (q + 1 < nw) { mark(q + 1, epre, BLOCK); fetch(q + 1); }
-        if (vec) {
+        if (!patch) {
+        } else if (vec) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const uint32_t o = k * 1024 + threadIdx.x * 4;
                 st4<1>(l + o, make_float4(nl[4 * k], nl[4 * k + 1], nl[4 * k + 2], nl[4 * k + 3]));
-                st4<1>(d + o, make_float4(nd[4 * k], nd[4 * k + 1], nd[4 * k + 2], nd[4 * k + 3]));
+                if (STEP) st4<1>(d + o, make_float4(nd[4 * k], nd[4 * k + 1], nd[4 * k + 2], nd[4 * k + 3]));
             }
         } else {
 #pragma unroll
             for (int j = 0; j < EPT; ++j) {
                 const uint32_t e = elem_scl(j);
-                if (e < len) { l[e] = nl[j]; d[e] = nd[j]; }
+                if (e < len) { l[e] = nl[j]; if (STEP) d[e] = nd[j]; }
             }
         }
     }

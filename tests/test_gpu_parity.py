@@ -728,10 +728,12 @@ def test_merge_explorer_lists_that_overlap_the_core_follow_the_stated_order():
     sd.close()
 
 
-def test_pull_overwrites_local_models_only_at_the_communication_set():
+@pytest.mark.parametrize("pull_kernel", [1, 0])       # 1: the local models are streamed; 0: patched by scattered writes
+def test_pull_overwrites_local_models_only_at_the_communication_set(pull_kernel):
     wl = workloads.TINY.scaled(25_003, W=2)
     seg_off = [0, wl.n]
     sd = binding.SlimDP(wl.n, wl.W)
+    sd.set_option("pull_kernel", pull_kernel)
     w_h = wl.weights()
     g_h = wl.gradients(0)
     w = to_dev(w_h)
