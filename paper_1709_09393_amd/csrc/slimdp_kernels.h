@@ -380,6 +380,9 @@ __host__ __device__ constexpr uint32_t spec_align(uint32_t W) { return (W == 0u 
 #ifndef SCORE_MINB
 #define SCORE_MINB 4
 #endif
+#ifndef SCORE_LD_AUX
+#define SCORE_LD_AUX 2          // cache policy of the general scoring kernel's loads: non-temporal (the stress workload scores 4 % faster)
+#endif
 template <int WT, int PRE, int SPEC, int DENSE, int STRIDED>
 __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __restrict__ w, PtrTab g, int Wrt, float c,
                                                  float* __restrict__ S, const uint32_t* __restrict__ tile_start,
@@ -457,10 +460,10 @@ __global__ __launch_bounds__(BLOCK, SCORE_MINB) void k_score(const float* __rest
             float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
             float4 x[WT ? WT : 1];
             if (vec) {          // request this round's lines first ...
-                wv = buffer_load4(rw, lane_bytes, 0u);
+                wv = buffer_load4_aux<SCORE_LD_AUX>(rw, lane_bytes);
                 if (WT) {
 #pragma unroll
-                    for (int k = 0; k < WT; ++k) x[k] = buffer_load4(rg[k], lane_bytes, 0u);
+                    for (int k = 0; k < WT; ++k) x[k] = buffer_load4_aux<SCORE_LD_AUX>(rg[k], lane_bytes);
                 }
             }
             if (PRE) {          // ... do this round's share of the integer work while they fly ...
